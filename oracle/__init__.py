@@ -1,0 +1,292 @@
+"""CPU oracle (fp64, plain definitions).  TEST INFRASTRUCTURE ONLY.
+
+Only tests/, the smoke check and the benchmark's cpu_baseline leg may import
+this package; the product path never does.  It shares no code with the HIP
+library: the C file ``sensei_oracle.c`` is compiled on its own with gcc.
+
+Contents
+  * thin ctypes wrappers over ``sensei_oracle.c`` (primitives, plain-definition
+    GCN / GAT layers, row-sampled layers),
+  * ``gcn_composition`` / ``gat_composition``: every re-association of a layer,
+    each following its sequence of primitives literally in fp64 (used for the
+    "all re-associations agree" invariant; Matrix representation section:
+    adjacent operands may be re-associated freely),
+  * ``dense``: brute force with dense matrices, independent of the CSR code,
+  * ``select_rules``: the embedding-size conditions of the code-generation
+    section (which compositions are candidates for in<out / in>out).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sensei_oracle.c")
+_LIBS = {False: os.path.join(_HERE, "liboracle.so"), True: os.path.join(_HERE, "liboracle_omp.so")}
+_loaded = {}
+
+
+def build(force: bool = False) -> None:
+    for omp, path in _LIBS.items():
+        if force or not os.path.exists(path) or os.path.getmtime(path) < os.path.getmtime(_SRC):
+            cmd = ["gcc", "-O2", "-shared", "-fPIC", _SRC, "-o", path, "-lm"]
+            if omp:
+                cmd[1:1] = ["-fopenmp", "-DORC_OMP"]
+            subprocess.check_call(cmd)
+
+
+def _lib(omp: bool = False):
+    if omp not in _loaded:
+        if not os.path.exists(_LIBS[omp]):
+            build()
+        lib = ctypes.CDLL(_LIBS[omp])
+        lib.orc_threads.restype = ctypes.c_int
+        _loaded[omp] = lib
+    return _loaded[omp]
+
+
+def threads(omp: bool = False) -> int:
+    return int(_lib(omp).orc_threads())
+
+
+def _p(a):
+    return None if a is None else ctypes.c_void_p(a.ctypes.data)
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _f64(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def _f32(a):
+    a = np.asarray(a)
+    assert a.dtype == np.float32, "oracle layers take the fp32 input bits"
+    return np.ascontiguousarray(a)
+
+
+I32, I64, DBL = ctypes.c_int32, ctypes.c_int64, ctypes.c_double
+
+
+# ------------------------------------------------------------------ primitives
+
+def degrees(n_rows, n_cols, row_ptr, col_idx):
+    row_ptr, col_idx = _i32(row_ptr), _i32(col_idx)
+    dr = np.empty(n_rows, dtype=np.int32)
+    dc = np.empty(n_cols, dtype=np.int32)
+    _lib().orc_degrees(I32(n_rows), I32(n_cols), _p(row_ptr), _p(col_idx), _p(dr), _p(dc))
+    return dr, dc
+
+
+def inv_sqrt_deg(deg):
+    deg = _i32(deg)
+    out = np.empty(deg.size, dtype=np.float64)
+    _lib().orc_inv_sqrt_deg(_p(deg), I64(deg.size), _p(out))
+    return out
+
+
+def spmm(row_ptr, col_idx, val, B):
+    row_ptr, col_idx, B = _i32(row_ptr), _i32(col_idx), _f64(B)
+    val = None if val is None else _f64(val)
+    n_rows, F = row_ptr.size - 1, B.shape[1]
+    C = np.empty((n_rows, F), dtype=np.float64)
+    _lib().orc_spmm(I32(n_rows), _p(row_ptr), _p(col_idx), _p(val), _p(B), I64(F), I32(F), _p(C), I64(F))
+    return C
+
+
+def sddmm_mul(row_ptr, col_idx, a, b, c):
+    row_ptr, col_idx, b, c = _i32(row_ptr), _i32(col_idx), _f64(b), _f64(c)
+    a = None if a is None else _f64(a)
+    d = np.empty(col_idx.size, dtype=np.float64)
+    _lib().orc_sddmm_mul(I32(row_ptr.size - 1), _p(row_ptr), _p(col_idx), _p(a), _p(b), _p(c), _p(d))
+    return d
+
+
+def gat_scores(row_ptr, col_idx, s_l, s_r, slope=0.2):
+    row_ptr, col_idx, s_l, s_r = _i32(row_ptr), _i32(col_idx), _f64(s_l), _f64(s_r)
+    e = np.empty(col_idx.size, dtype=np.float64)
+    _lib().orc_gat_scores(I32(row_ptr.size - 1), _p(row_ptr), _p(col_idx), _p(s_l), _p(s_r), DBL(slope), _p(e))
+    return e
+
+
+def edge_softmax(row_ptr, e):
+    row_ptr, e = _i32(row_ptr), _f64(e)
+    alpha = np.zeros(e.size, dtype=np.float64)
+    _lib().orc_edge_softmax(I32(row_ptr.size - 1), _p(row_ptr), _p(e), _p(alpha))
+    return alpha
+
+
+def row_broadcast(s, X):
+    s, X = _f64(s), _f64(X)
+    Y = np.empty_like(X)
+    _lib().orc_row_broadcast(I64(X.shape[0]), I32(X.shape[1]), _p(s), _p(X), I64(X.shape[1]), _p(Y), I64(X.shape[1]))
+    return Y
+
+
+def gemm(A, W):
+    A, W = _f64(A), _f64(W)
+    assert A.shape[1] == W.shape[0]
+    Y = np.empty((A.shape[0], W.shape[1]), dtype=np.float64)
+    _lib().orc_gemm(I64(A.shape[0]), I32(A.shape[1]), I32(W.shape[1]), _p(A), I64(A.shape[1]), _p(W), I64(W.shape[1]),
+                    _p(Y), I64(W.shape[1]))
+    return Y
+
+
+def gemv(A, v):
+    A, v = _f64(A), _f64(v)
+    y = np.empty(A.shape[0], dtype=np.float64)
+    _lib().orc_gemv(I64(A.shape[0]), I32(A.shape[1]), _p(A), I64(A.shape[1]), _p(v), _p(y))
+    return y
+
+
+def activation(Y, act):
+    Y = _f64(Y).copy()
+    _lib().orc_activation(I64(Y.size), ctypes.c_int(act), _p(Y))
+    return Y
+
+
+# ------------------------------------------------------- plain-definition layers
+
+def gcn_layer(n_rows, n_cols, row_ptr, col_idx, X, W, act=0, rows=None, omp=False):
+    """Eq. 3 / Eq. 4 as one plain definition; ``rows`` selects output rows."""
+    row_ptr, col_idx, X, W = _i32(row_ptr), _i32(col_idx), _f32(X), _f32(W)
+    F_in, F_out = W.shape
+    assert X.shape == (n_cols, F_in)
+    lib = _lib(omp)
+    if rows is None:
+        Y = np.empty((n_rows, F_out), dtype=np.float64)
+        rc = lib.orc_gcn_layer(I32(n_rows), I32(n_cols), _p(row_ptr), _p(col_idx), _p(X), I64(F_in), I32(F_in),
+                               _p(W), I64(F_out), I32(F_out), ctypes.c_int(act), _p(Y))
+    else:
+        rows = _i32(rows)
+        Y = np.empty((rows.size, F_out), dtype=np.float64)
+        rc = lib.orc_gcn_layer_rows(I32(n_rows), I32(n_cols), _p(row_ptr), _p(col_idx), _p(X), I64(F_in), I32(F_in),
+                                    _p(W), I64(F_out), I32(F_out), ctypes.c_int(act), _p(rows), I32(rows.size), _p(Y))
+    if rc != 0:
+        raise RuntimeError(f"oracle gcn_layer failed ({rc})")
+    return Y
+
+
+def gat_layer(n_rows, n_cols, row_ptr, col_idx, X, W, a_l, a_r, slope=0.2, act=0, rows=None, omp=False):
+    """Eq. 5 / Eq. 6 as one plain definition; ``rows`` selects output rows."""
+    row_ptr, col_idx, X, W, a_l, a_r = _i32(row_ptr), _i32(col_idx), _f32(X), _f32(W), _f32(a_l), _f32(a_r)
+    F_in, F_out = W.shape
+    assert X.shape == (n_cols, F_in) and a_l.size == F_out and a_r.size == F_out
+    lib = _lib(omp)
+    if rows is None:
+        Y = np.empty((n_rows, F_out), dtype=np.float64)
+        rc = lib.orc_gat_layer(I32(n_rows), I32(n_cols), _p(row_ptr), _p(col_idx), _p(X), I64(F_in), I32(F_in),
+                               _p(W), I64(F_out), I32(F_out), _p(a_l), _p(a_r), DBL(slope), ctypes.c_int(act), _p(Y))
+    else:
+        rows = _i32(rows)
+        Y = np.empty((rows.size, F_out), dtype=np.float64)
+        rc = lib.orc_gat_layer_rows(I32(n_rows), I32(n_cols), _p(row_ptr), _p(col_idx), _p(X), I64(F_in), I32(F_in),
+                                    _p(W), I64(F_out), I32(F_out), _p(a_l), _p(a_r), DBL(slope), ctypes.c_int(act),
+                                    _p(rows), I32(rows.size), _p(Y))
+    if rc != 0:
+        raise RuntimeError(f"oracle gat_layer failed ({rc})")
+    return Y
+
+
+# ------------------------------------------------------------- re-associations
+
+GCN_COMPOSITIONS = ("DYN_AGG", "DYN_UPD", "DYNF_AGG", "DYNF_UPD", "PRE_AGG", "PRE_UPD")
+GAT_COMPOSITIONS = ("REUSE", "RECOMP", "RECOMP_FOLD", "REUSE_FOLD")
+
+
+def gcn_composition(comp_id, n_rows, n_cols, row_ptr, col_idx, X, W, act=0):
+    """One GCN layer following composition ``comp_id`` step by step in fp64.
+
+    0 DYN_AGG   row-broadcast(c,X) -> pattern SpMM -> row-broadcast(r) -> GEMM    (Eq. 3, update last)
+    1 DYN_UPD   GEMM -> row-broadcast(c) -> pattern SpMM -> row-broadcast(r)      (Eq. 3, update first)
+    2 DYNF_AGG  SpMM with both scalings applied inside the sum -> GEMM
+    3 DYNF_UPD  GEMM -> SpMM with both scalings applied inside the sum
+    4 PRE_AGG   N~ by SDDMM (Eq. 4) -> weighted SpMM -> GEMM
+    5 PRE_UPD   N~ by SDDMM (Eq. 4) -> GEMM -> weighted SpMM
+    """
+    dr, dc = degrees(n_rows, n_cols, row_ptr, col_idx)
+    r, c = inv_sqrt_deg(dr), inv_sqrt_deg(dc)
+    X64, W64 = _f64(X), _f64(W)
+    if comp_id == 0:
+        out = gemm(row_broadcast(r, spmm(row_ptr, col_idx, None, row_broadcast(c, X64))), W64)
+    elif comp_id == 1:
+        out = row_broadcast(r, spmm(row_ptr, col_idx, None, row_broadcast(c, gemm(X64, W64))))
+    elif comp_id == 2:
+        out = gemm(_spmm_scaled(row_ptr, col_idx, r, c, X64), W64)
+    elif comp_id == 3:
+        out = _spmm_scaled(row_ptr, col_idx, r, c, gemm(X64, W64))
+    elif comp_id == 4:
+        nt = sddmm_mul(row_ptr, col_idx, None, r, c)
+        out = gemm(spmm(row_ptr, col_idx, nt, X64), W64)
+    elif comp_id == 5:
+        nt = sddmm_mul(row_ptr, col_idx, None, r, c)
+        out = spmm(row_ptr, col_idx, nt, gemm(X64, W64))
+    else:
+        raise ValueError("bad GCN composition id")
+    return activation(out, act)
+
+
+def _spmm_scaled(row_ptr, col_idx, r, c, B):
+    """U[i,:] = r_i * sum_j c_j B[j,:] (pure-Python loop over rows; small inputs only)."""
+    n_rows = len(row_ptr) - 1
+    U = np.zeros((n_rows, B.shape[1]), dtype=np.float64)
+    for i in range(n_rows):
+        acc = np.zeros(B.shape[1], dtype=np.float64)
+        for k in range(row_ptr[i], row_ptr[i + 1]):
+            acc += c[col_idx[k]] * B[col_idx[k]]
+        U[i] = r[i] * acc
+    return U
+
+
+def gat_composition(comp_id, n_rows, n_cols, row_ptr, col_idx, X, W, a_l, a_r, slope=0.2, act=0):
+    """One GAT layer following composition ``comp_id`` step by step in fp64.
+
+    0 REUSE        Theta=XW; s=Theta.a; scores; softmax; alpha.Theta                  (Eq. 5-6)
+    1 RECOMP       Theta=XW; s=Theta.a; scores; softmax; (alpha.X).W                  (Eq. 7)
+    2 RECOMP_FOLD  s=X.(W.a); scores; softmax; (alpha.X).W
+    3 REUSE_FOLD   s=X.(W.a); scores; softmax; alpha.(XW)
+    """
+    X64, W64, al, ar = _f64(X), _f64(W), _f64(a_l), _f64(a_r)
+    theta = None
+    if comp_id in (0, 1):
+        theta = gemm(X64, W64)
+        s_l, s_r = gemv(theta, al), gemv(theta, ar)
+    elif comp_id in (2, 3):
+        s_l, s_r = gemv(X64, gemv(W64, al)), gemv(X64, gemv(W64, ar))
+    else:
+        raise ValueError("bad GAT composition id")
+    alpha = edge_softmax(row_ptr, gat_scores(row_ptr, col_idx, s_l[:n_rows], s_r, slope))
+    if comp_id == 0:
+        out = spmm(row_ptr, col_idx, alpha, theta)
+    elif comp_id == 3:
+        out = spmm(row_ptr, col_idx, alpha, gemm(X64, W64))
+    else:
+        out = gemm(spmm(row_ptr, col_idx, alpha, X64), W64)
+    return activation(out, act)
+
+
+# -------------------------------------------------------------- selector rules
+
+def select_rules(kind, f_in, f_out):
+    """Composition ids left after the embedding-size conditions (code generation section;
+    GAT: recomputation is a candidate only when the input size is smaller than the output)."""
+    if kind == "gcn":
+        agg, upd = (0, 2, 4), (1, 3, 5)
+        if f_in < f_out:
+            return agg
+        if f_in > f_out:
+            return upd
+        return tuple(sorted(agg + upd))
+    if kind == "gat":
+        return (0, 1, 2, 3) if f_in < f_out else (0,)
+    raise ValueError(kind)
+
+
+def density(n_rows, n_cols, nnz):
+    """Graph feature used by the cost models: non-zeros over matrix area."""
+    return nnz / (float(n_rows) * float(n_cols))
