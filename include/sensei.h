@@ -1,0 +1,193 @@
+/*
+ * sensei.h - C ABI of the MI355X (gfx950) library that runs one GCN or GAT
+ * layer as a chosen composition of sparse and dense primitives, after the
+ * input-sensitive re-association method of SENSEi (arXiv 2306.15155).
+ *
+ * Conventions for every entry point
+ *   - Pointers named in a struct or argument as "device" are device (HBM)
+ *     addresses owned by the caller; the library never allocates, frees or
+ *     keeps them past the call.  Everything else is host memory.
+ *   - Dense matrices are row-major fp32 with an explicit leading dimension
+ *     (ld >= cols, in elements).  Indices are int32.  A sparse matrix is CSR:
+ *     rows are destination nodes, columns are source (in-neighbour) nodes,
+ *     row_ptr[0] == 0, columns strictly ascending within a row, all in
+ *     [0, n_cols).  Well-formed CSR is a precondition; it is not validated on
+ *     the device.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *     Calls enqueue work and return; only sensei_select in timed mode and
+ *     sensei_calibrate synchronise.
+ *   - `workspace` is device memory of at least the size the matching
+ *     *_workspace query returns, aligned to 256 bytes; its contents are
+ *     scratch.  Outputs must not alias inputs or the workspace.
+ *   - Return value: a sensei_status.  No exception or abort crosses the ABI.
+ *     Arguments are checked on the host before anything is launched; a failed
+ *     check launches nothing.
+ */
+#ifndef SENSEI_H
+#define SENSEI_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SENSEI_OK = 0,
+    SENSEI_INVALID_ARGUMENT = 1,   /* null pointer, negative size, ld < cols, shape mismatch, aliasing */
+    SENSEI_INVALID_COMPOSITION = 2,
+    SENSEI_WORKSPACE_TOO_SMALL = 3,
+    SENSEI_HIP_ERROR = 4,          /* a HIP runtime call or a launch failed */
+    SENSEI_UNSUPPORTED = 5
+} sensei_status;
+
+typedef struct sensei_ctx sensei_ctx; /* opaque: device id and cost-model calibration only */
+
+typedef struct {
+    int32_t n_rows, n_cols;
+    int64_t nnz;
+    const int32_t *row_ptr; /* device, n_rows + 1 */
+    const int32_t *col_idx; /* device, nnz */
+    const float *val;       /* device, nnz, or NULL: unweighted, only the positions are used
+                               (matrix attribute table: sparse weighted / unweighted) */
+} sensei_csr;
+
+typedef struct {
+    const float *ptr; /* device */
+    int64_t rows, cols, ld;
+} sensei_mat;
+
+enum { SENSEI_ACT_NONE = 0, SENSEI_ACT_RELU = 1 };
+enum { SENSEI_KIND_GCN = 0, SENSEI_KIND_GAT = 1 };
+
+/* GCN compositions (case study GCN).  AGG = aggregate then update (GEMM last), UPD = update then
+ * aggregate (GEMM first).  DYN = normalisation by two row broadcasts around a value-less SpMM
+ * (Eq. 3); DYNF = the same scalings applied inside the SpMM; PRE = weighted SpMM over the
+ * precomputed N~ (Eq. 4; the caller passes N~ as A->val, see sensei_gcn_precompute). */
+enum {
+    SENSEI_GCN_DYN_AGG = 0, SENSEI_GCN_DYN_UPD = 1, SENSEI_GCN_DYNF_AGG = 2,
+    SENSEI_GCN_DYNF_UPD = 3, SENSEI_GCN_PRE_AGG = 4, SENSEI_GCN_PRE_UPD = 5
+};
+/* GAT compositions (case study GAT).  REUSE aggregates the updated embeddings Theta (Eq. 6);
+ * RECOMP aggregates the input embeddings and applies W afterwards (Eq. 7).  *_FOLD obtain the
+ * two score vectors as X.(W.a) instead of (X.W).a. */
+enum { SENSEI_GAT_REUSE = 0, SENSEI_GAT_RECOMP = 1, SENSEI_GAT_RECOMP_FOLD = 2, SENSEI_GAT_REUSE_FOLD = 3 };
+
+/* SpMM flavours (sensei_spmm `mode`) */
+enum {
+    SENSEI_SPMM_PATTERN = 0, /* C[i,:] = sum_j B[j,:]                 value-less SpMM                */
+    SENSEI_SPMM_WEIGHTED = 1,/* C[i,:] = sum_j val[i,j] B[j,:]        Eq. 1 with (+,x)               */
+    SENSEI_SPMM_SCALED = 2   /* C[i,:] = r[i] sum_j c[j] B[j,:]       Eq. 3's scalings inside the sum */
+};
+
+/* ------------------------------------------------------------------ context */
+
+/* Creates a context bound to HIP device `device` (host pointer out). */
+int sensei_create(sensei_ctx **out, int device);
+int sensei_destroy(sensei_ctx *ctx);
+
+/* Measures the few device rates the additive cost model uses (streaming and gather bandwidth,
+ * GEMM rate, launch latency) with small kernels on `stream`; synchronises.  Optional: without it
+ * sensei_select uses built-in MI355X defaults.  `workspace` >= 64 MiB. */
+int sensei_calibrate(sensei_ctx *ctx, void *workspace, size_t ws_bytes, void *stream);
+
+int sensei_num_compositions(int kind);
+const char *sensei_composition_name(int kind, int comp_id);
+const char *sensei_status_string(int status);
+
+/* ------------------------------------------------- primitives (steps of a layer) */
+
+/* Degrees of the stored pattern, which holds the self edges (case study GCN: D~ is the degree
+ * of the nodes of A~).  deg_row[i] = entries of row i; deg_col[j] = entries of column j.
+ * Outputs: device int32, n_rows and n_cols entries.  Exact integer work. */
+int sensei_degrees(sensei_ctx *ctx, const sensei_csr *A, int32_t *deg_row, int32_t *deg_col, void *stream);
+
+/* out[i] = 1 / sqrt(max(deg[i], 1)) in fp32 with correctly rounded sqrt and divide: the vector
+ * form of D~^(-1/2) (Eq. 3).  deg, out: device, n entries. */
+int sensei_norm_vectors(sensei_ctx *ctx, const int32_t *deg, int64_t n, float *out, void *stream);
+
+/* Upper bound, in bytes, on the workspace any sparse primitive below needs for this matrix at
+ * feature width `f` (host pointers). */
+int sensei_sparse_workspace(const sensei_csr *A, int f, size_t *bytes);
+
+/* N~ = D_r^(-1/2) . A~ . D_c^(-1/2) as an SDDMM whose two dense operands are the diagonal
+ * matrices taken as vectors (Eq. 4; first candidate->primitive rule): val_out[e] = r[i] * c[j]
+ * for the e-th stored entry (i,j).  r: n_rows, c: n_cols, val_out: nnz, all device. */
+int sensei_gcn_precompute(sensei_ctx *ctx, const sensei_csr *A, const float *r, const float *c, float *val_out,
+                          void *workspace, size_t ws_bytes, void *stream);
+
+/* Row broadcast (Eq. 3): Y[i,:] = s[i] * X[i,:], s device with X.rows entries.  Y may equal X.ptr. */
+int sensei_row_broadcast(sensei_ctx *ctx, const float *s, sensei_mat X, float *Y, int64_t ldy, void *stream);
+
+/* g-SpMM with (+,x) (Eq. 1) in the three flavours above, followed by the activation.  B has
+ * A->n_cols rows; C is n_rows x B.cols with leading dimension ldc.  r / c are used by
+ * SENSEI_SPMM_SCALED only (NULL otherwise); A->val by SENSEI_SPMM_WEIGHTED only. */
+int sensei_spmm(sensei_ctx *ctx, const sensei_csr *A, int mode, const float *r, const float *c, sensei_mat B,
+                float *C, int64_t ldc, int activation, void *workspace, size_t ws_bytes, void *stream);
+
+/* Dense update Y = act(A . W) on the fp32 matrix cores (background: dense primitives).
+ * A: n x k, W: k x m, Y: n x m with leading dimension ldy. */
+int sensei_gemm(sensei_ctx *ctx, sensei_mat A, sensei_mat W, float *Y, int64_t ldy, int activation, void *stream);
+
+/* Two matrix-vector products in one pass over A: y1 = A.v1, y2 = A.v2 (v*: A.cols entries,
+ * y*: A.rows entries, device).  Used for the attention projections s_l, s_r of Eq. 5. */
+int sensei_gemv2(sensei_ctx *ctx, sensei_mat A, const float *v1, const float *v2, float *y1, float *y2, void *stream);
+
+/* Attention logits on the pattern (g-SDDMM, Eq. 2, with k = 1 and + as the inner operator):
+ * e[(i,j)] = LeakyReLU_slope(s_l[i] + s_r[j]); s_l: n_rows, s_r: n_cols, e_out: nnz (device). */
+int sensei_sddmm_score(sensei_ctx *ctx, const sensei_csr *A, const float *s_l, const float *s_r, float neg_slope,
+                       float *e_out, void *workspace, size_t ws_bytes, void *stream);
+
+/* Softmax over the stored entries of each row: alpha = exp(e - m_i) / sum_row exp(e - m_i),
+ * m_i the row maximum.  e, alpha_out: nnz (device); alpha_out may equal e. */
+int sensei_edge_softmax(sensei_ctx *ctx, const sensei_csr *A, const float *e, float *alpha_out,
+                        void *workspace, size_t ws_bytes, void *stream);
+
+/* ----------------------------------------------------------------------- layers */
+
+int sensei_gcn_workspace(const sensei_csr *A, int f_in, int f_out, int comp_id, size_t *bytes);
+
+/* One GCN layer, Y = act( D_r^(-1/2) A~ D_c^(-1/2) X W ) (Eq. 3 / Eq. 4), evaluated in the
+ * order composition `comp_id` prescribes.  A holds the self edges already.  r: n_rows and
+ * c: n_cols are the D~^(-1/2) vectors (sensei_norm_vectors of the row / column degrees); for
+ * PRE_* compositions A->val must hold N~ and r, c may be NULL; for the others A->val is ignored.
+ * X: n_cols x f_in, W: f_in x f_out, Y: n_rows x f_out. */
+int sensei_gcn_layer(sensei_ctx *ctx, const sensei_csr *A, const float *r, const float *c, sensei_mat X, sensei_mat W,
+                     float *Y, int64_t ldy, int activation, int comp_id, void *workspace, size_t ws_bytes, void *stream);
+
+int sensei_gat_workspace(const sensei_csr *A, int f_in, int f_out, int comp_id, size_t *bytes);
+
+/* One single-head GAT layer (Eq. 5-7): Theta = X.W; s_l = Theta.a_l, s_r = Theta.a_r;
+ * e_ij = LeakyReLU(s_l[i] + s_r[j]) on the pattern; alpha = row softmax; Y = act(alpha.Theta),
+ * in the order composition `comp_id` prescribes.  Destination node i is source node i
+ * (n_rows <= n_cols).  a_l, a_r: f_out entries (device). */
+int sensei_gat_layer(sensei_ctx *ctx, const sensei_csr *A, sensei_mat X, sensei_mat W, const float *a_l,
+                     const float *a_r, float neg_slope, float *Y, int64_t ldy, int activation, int comp_id,
+                     void *workspace, size_t ws_bytes, void *stream);
+
+/* --------------------------------------------------------------------- selector */
+
+enum { SENSEI_SELECT_MODEL = 0, SENSEI_SELECT_TIMED = 1 };
+
+/* Bytes sensei_select needs in timed mode (it runs every candidate once on scratch operands). */
+int sensei_select_workspace(int kind, const sensei_csr *A, int f_in, int f_out, size_t *bytes);
+
+/* Chooses a composition for (graph, f_in, f_out) (online stage; code generation of promoted
+ * candidates).  First the embedding-size conditions drop the candidates annotated for the other
+ * scenario; then
+ *   mode MODEL: cost(id) = sum of the predicted times of its primitives from the graph features
+ *               (rows, columns, non-zeros, density) and the sizes; smallest cost wins, ties to
+ *               the lowest id.  Host arithmetic only, nothing is launched, workspace unused.
+ *   mode TIMED: every remaining candidate is run once after one warm-up on scratch operands in
+ *               `workspace` and the fastest is kept (the "run all once, keep the best" strategy);
+ *               synchronises `stream`.
+ * comp_id_out: host int.  est_ms (host, nullable): sensei_num_compositions(kind) floats,
+ * predicted or measured ms per id, negative for ids the conditions dropped. */
+int sensei_select(sensei_ctx *ctx, int kind, const sensei_csr *A, int f_in, int f_out, int mode, int *comp_id_out,
+                  float *est_ms, void *workspace, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SENSEI_H */

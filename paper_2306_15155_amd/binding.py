@@ -1,0 +1,274 @@
+"""ctypes binding of libsensei_hip.so: argument marshalling only.
+
+Every function mirrors the C entry point of the same name in ``include/sensei.h``.
+Tensors are PyTorch ROCm tensors used as device buffers (``data_ptr()``); the
+stream is PyTorch's current HIP stream.  There is no fallback: if the library
+has not been built the import of :func:`lib` raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsensei_hip.so")
+
+ACT_NONE, ACT_RELU = 0, 1
+KIND_GCN, KIND_GAT = 0, 1
+SPMM_PATTERN, SPMM_WEIGHTED, SPMM_SCALED = 0, 1, 2
+SELECT_MODEL, SELECT_TIMED = 0, 1
+GCN_NAMES = ("DYN_AGG", "DYN_UPD", "DYNF_AGG", "DYNF_UPD", "PRE_AGG", "PRE_UPD")
+GAT_NAMES = ("REUSE", "RECOMP", "RECOMP_FOLD", "REUSE_FOLD")
+
+EXPORTS = (
+    "sensei_create", "sensei_destroy", "sensei_calibrate", "sensei_num_compositions", "sensei_composition_name",
+    "sensei_status_string", "sensei_degrees", "sensei_norm_vectors", "sensei_sparse_workspace", "sensei_gcn_precompute",
+    "sensei_row_broadcast", "sensei_spmm", "sensei_gemm", "sensei_gemv2", "sensei_sddmm_score", "sensei_edge_softmax",
+    "sensei_gcn_workspace", "sensei_gcn_layer", "sensei_gat_workspace", "sensei_gat_layer", "sensei_select_workspace",
+    "sensei_select",
+)
+
+
+class SenseiError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+class CsrStruct(ctypes.Structure):
+    _fields_ = [("n_rows", ctypes.c_int32), ("n_cols", ctypes.c_int32), ("nnz", ctypes.c_int64),
+                ("row_ptr", ctypes.c_void_p), ("col_idx", ctypes.c_void_p), ("val", ctypes.c_void_p)]
+
+
+class MatStruct(ctypes.Structure):
+    _fields_ = [("ptr", ctypes.c_void_p), ("rows", ctypes.c_int64), ("cols", ctypes.c_int64), ("ld", ctypes.c_int64)]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2306_15155_amd.build` "
+                              "(there is no CPU fallback)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64, sz, f32 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_size_t, ctypes.c_float
+        P = ctypes.POINTER
+        L.sensei_create.argtypes = [P(vp), i32]
+        L.sensei_destroy.argtypes = [vp]
+        L.sensei_calibrate.argtypes = [vp, vp, sz, vp]
+        L.sensei_num_compositions.argtypes = [i32]
+        L.sensei_composition_name.argtypes = [i32, i32]
+        L.sensei_composition_name.restype = ctypes.c_char_p
+        L.sensei_status_string.argtypes = [i32]
+        L.sensei_status_string.restype = ctypes.c_char_p
+        L.sensei_degrees.argtypes = [vp, P(CsrStruct), vp, vp, vp]
+        L.sensei_norm_vectors.argtypes = [vp, vp, i64, vp, vp]
+        L.sensei_sparse_workspace.argtypes = [P(CsrStruct), i32, P(sz)]
+        L.sensei_gcn_precompute.argtypes = [vp, P(CsrStruct), vp, vp, vp, vp, sz, vp]
+        L.sensei_row_broadcast.argtypes = [vp, vp, MatStruct, vp, i64, vp]
+        L.sensei_spmm.argtypes = [vp, P(CsrStruct), i32, vp, vp, MatStruct, vp, i64, i32, vp, sz, vp]
+        L.sensei_gemm.argtypes = [vp, MatStruct, MatStruct, vp, i64, i32, vp]
+        L.sensei_gemv2.argtypes = [vp, MatStruct, vp, vp, vp, vp, vp]
+        L.sensei_sddmm_score.argtypes = [vp, P(CsrStruct), vp, vp, f32, vp, vp, sz, vp]
+        L.sensei_edge_softmax.argtypes = [vp, P(CsrStruct), vp, vp, vp, sz, vp]
+        L.sensei_gcn_workspace.argtypes = [P(CsrStruct), i32, i32, i32, P(sz)]
+        L.sensei_gcn_layer.argtypes = [vp, P(CsrStruct), vp, vp, MatStruct, MatStruct, vp, i64, i32, i32, vp, sz, vp]
+        L.sensei_gat_workspace.argtypes = [P(CsrStruct), i32, i32, i32, P(sz)]
+        L.sensei_gat_layer.argtypes = [vp, P(CsrStruct), MatStruct, MatStruct, vp, vp, f32, vp, i64, i32, i32, vp, sz, vp]
+        L.sensei_select_workspace.argtypes = [i32, P(CsrStruct), i32, i32, P(sz)]
+        L.sensei_select.argtypes = [vp, i32, P(CsrStruct), i32, i32, i32, P(ctypes.c_int), P(f32), vp, sz, vp]
+        for name in EXPORTS:
+            if name not in ("sensei_composition_name", "sensei_status_string"):
+                getattr(L, name).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().sensei_status_string(status).decode()
+
+
+def composition_name(kind: int, comp_id: int) -> str:
+    return lib().sensei_composition_name(kind, comp_id).decode()
+
+
+def num_compositions(kind: int) -> int:
+    return lib().sensei_num_compositions(kind)
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise SenseiError(status, where)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def csr_struct(n_rows, n_cols, row_ptr, col_idx, val=None) -> CsrStruct:
+    assert row_ptr.dtype == torch.int32 and col_idx.dtype == torch.int32
+    assert val is None or val.dtype == torch.float32
+    return CsrStruct(n_rows, n_cols, int(col_idx.numel()), row_ptr.data_ptr(), col_idx.data_ptr() if col_idx.numel() else None,
+                     None if val is None else val.data_ptr())
+
+
+def mat_struct(t: torch.Tensor) -> MatStruct:
+    assert t.dtype == torch.float32 and t.dim() == 2 and (t.stride(1) == 1 or t.size(1) <= 1)
+    return MatStruct(t.data_ptr(), t.size(0), t.size(1), t.stride(0) if t.size(0) > 1 else max(t.stride(0), t.size(1)))
+
+
+class Workspace:
+    """A grow-only device byte buffer (PyTorch owns the memory)."""
+
+    def __init__(self, device="cuda:0"):
+        self.device = torch.device(device)
+        self.buf = torch.empty(0, dtype=torch.uint8, device=self.device)
+
+    def ensure(self, nbytes: int):
+        if self.buf.numel() < nbytes:
+            self.buf = torch.empty(int(nbytes) + 256, dtype=torch.uint8, device=self.device)
+        return self
+
+    @property
+    def ptr(self):
+        p = self.buf.data_ptr()
+        return ctypes.c_void_p((p + 255) // 256 * 256)
+
+    @property
+    def nbytes(self):
+        p = self.buf.data_ptr()
+        return max(0, self.buf.numel() - ((p + 255) // 256 * 256 - p))
+
+
+class Context:
+    def __init__(self, device: int = 0):
+        self._h = ctypes.c_void_p()
+        _check(lib().sensei_create(ctypes.byref(self._h), device), "sensei_create")
+        self.device = torch.device(f"cuda:{device}")
+        self.ws = Workspace(self.device)
+
+    def close(self):
+        if self._h:
+            lib().sensei_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- primitives
+    def degrees(self, A: CsrStruct):
+        dr = torch.empty(A.n_rows, dtype=torch.int32, device=self.device)
+        dc = torch.empty(A.n_cols, dtype=torch.int32, device=self.device)
+        _check(lib().sensei_degrees(self._h, ctypes.byref(A), _ptr(dr), _ptr(dc), _stream()), "sensei_degrees")
+        return dr, dc
+
+    def norm_vectors(self, deg: torch.Tensor):
+        out = torch.empty(deg.numel(), dtype=torch.float32, device=self.device)
+        _check(lib().sensei_norm_vectors(self._h, _ptr(deg), deg.numel(), _ptr(out), _stream()), "sensei_norm_vectors")
+        return out
+
+    def sparse_workspace(self, A: CsrStruct, f: int) -> int:
+        n = ctypes.c_size_t()
+        _check(lib().sensei_sparse_workspace(ctypes.byref(A), f, ctypes.byref(n)), "sensei_sparse_workspace")
+        return n.value
+
+    def gcn_precompute(self, A: CsrStruct, r, c):
+        val = torch.empty(max(A.nnz, 1), dtype=torch.float32, device=self.device)[:A.nnz]
+        self.ws.ensure(self.sparse_workspace(A, 1))
+        _check(lib().sensei_gcn_precompute(self._h, ctypes.byref(A), _ptr(r), _ptr(c), _ptr(val), self.ws.ptr, self.ws.nbytes,
+                                           _stream()), "sensei_gcn_precompute")
+        return val
+
+    def row_broadcast(self, s, X, out=None):
+        Y = torch.empty_like(X) if out is None else out
+        _check(lib().sensei_row_broadcast(self._h, _ptr(s), mat_struct(X), _ptr(Y), mat_struct(Y).ld, _stream()), "sensei_row_broadcast")
+        return Y
+
+    def spmm(self, A: CsrStruct, mode, B, r=None, c=None, activation=ACT_NONE, out=None):
+        C = torch.empty((A.n_rows, B.size(1)), dtype=torch.float32, device=self.device) if out is None else out
+        self.ws.ensure(self.sparse_workspace(A, B.size(1)))
+        _check(lib().sensei_spmm(self._h, ctypes.byref(A), mode, _ptr(r), _ptr(c), mat_struct(B), _ptr(C), mat_struct(C).ld,
+                                 activation, self.ws.ptr, self.ws.nbytes, _stream()), "sensei_spmm")
+        return C
+
+    def gemm(self, A, W, activation=ACT_NONE, out=None):
+        Y = torch.empty((A.size(0), W.size(1)), dtype=torch.float32, device=self.device) if out is None else out
+        _check(lib().sensei_gemm(self._h, mat_struct(A), mat_struct(W), _ptr(Y), mat_struct(Y).ld, activation, _stream()), "sensei_gemm")
+        return Y
+
+    def gemv2(self, A, v1, v2):
+        y1 = torch.empty(A.size(0), dtype=torch.float32, device=self.device)
+        y2 = torch.empty(A.size(0), dtype=torch.float32, device=self.device)
+        _check(lib().sensei_gemv2(self._h, mat_struct(A), _ptr(v1), _ptr(v2), _ptr(y1), _ptr(y2), _stream()), "sensei_gemv2")
+        return y1, y2
+
+    def sddmm_score(self, A: CsrStruct, s_l, s_r, neg_slope=0.2):
+        e = torch.empty(max(A.nnz, 1), dtype=torch.float32, device=self.device)[:A.nnz]
+        self.ws.ensure(self.sparse_workspace(A, 1))
+        _check(lib().sensei_sddmm_score(self._h, ctypes.byref(A), _ptr(s_l), _ptr(s_r), neg_slope, _ptr(e), self.ws.ptr,
+                                        self.ws.nbytes, _stream()), "sensei_sddmm_score")
+        return e
+
+    def edge_softmax(self, A: CsrStruct, e, out=None):
+        alpha = torch.empty_like(e) if out is None else out
+        self.ws.ensure(self.sparse_workspace(A, 1))
+        _check(lib().sensei_edge_softmax(self._h, ctypes.byref(A), _ptr(e), _ptr(alpha), self.ws.ptr, self.ws.nbytes, _stream()),
+               "sensei_edge_softmax")
+        return alpha
+
+    # ---- layers
+    def gcn_workspace(self, A: CsrStruct, f_in, f_out, comp_id) -> int:
+        n = ctypes.c_size_t()
+        _check(lib().sensei_gcn_workspace(ctypes.byref(A), f_in, f_out, comp_id, ctypes.byref(n)), "sensei_gcn_workspace")
+        return n.value
+
+    def gcn_layer(self, A: CsrStruct, r, c, X, W, comp_id, activation=ACT_NONE, out=None):
+        Y = torch.empty((A.n_rows, W.size(1)), dtype=torch.float32, device=self.device) if out is None else out
+        self.ws.ensure(self.gcn_workspace(A, X.size(1), W.size(1), comp_id))
+        _check(lib().sensei_gcn_layer(self._h, ctypes.byref(A), _ptr(r), _ptr(c), mat_struct(X), mat_struct(W), _ptr(Y),
+                                      mat_struct(Y).ld, activation, comp_id, self.ws.ptr, self.ws.nbytes, _stream()), "sensei_gcn_layer")
+        return Y
+
+    def gat_workspace(self, A: CsrStruct, f_in, f_out, comp_id) -> int:
+        n = ctypes.c_size_t()
+        _check(lib().sensei_gat_workspace(ctypes.byref(A), f_in, f_out, comp_id, ctypes.byref(n)), "sensei_gat_workspace")
+        return n.value
+
+    def gat_layer(self, A: CsrStruct, X, W, a_l, a_r, comp_id, neg_slope=0.2, activation=ACT_NONE, out=None):
+        Y = torch.empty((A.n_rows, W.size(1)), dtype=torch.float32, device=self.device) if out is None else out
+        self.ws.ensure(self.gat_workspace(A, X.size(1), W.size(1), comp_id))
+        _check(lib().sensei_gat_layer(self._h, ctypes.byref(A), mat_struct(X), mat_struct(W), _ptr(a_l), _ptr(a_r), neg_slope,
+                                      _ptr(Y), mat_struct(Y).ld, activation, comp_id, self.ws.ptr, self.ws.nbytes, _stream()),
+               "sensei_gat_layer")
+        return Y
+
+    # ---- selector
+    def select(self, kind, A: CsrStruct, f_in, f_out, mode=SELECT_MODEL):
+        n = num_compositions(kind)
+        est = (ctypes.c_float * n)()
+        cid = ctypes.c_int(-1)
+        ws_ptr, ws_bytes = None, 0
+        if mode == SELECT_TIMED:
+            need = ctypes.c_size_t()
+            _check(lib().sensei_select_workspace(kind, ctypes.byref(A), f_in, f_out, ctypes.byref(need)), "sensei_select_workspace")
+            self.ws.ensure(need.value)
+            ws_ptr, ws_bytes = self.ws.ptr, self.ws.nbytes
+        _check(lib().sensei_select(self._h, kind, ctypes.byref(A), f_in, f_out, mode, ctypes.byref(cid), est, ws_ptr, ws_bytes,
+                                   _stream()), "sensei_select")
+        return cid.value, [float(x) for x in est]
+
+    def calibrate(self):
+        self.ws.ensure(64 << 20)
+        _check(lib().sensei_calibrate(self._h, self.ws.ptr, self.ws.nbytes, _stream()), "sensei_calibrate")

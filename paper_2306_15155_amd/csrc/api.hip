@@ -1,0 +1,641 @@
+// C ABI of libsensei_hip: argument checks, workspace layout, the composition
+// executors for the GCN and GAT layer, and the composition selector.
+#include <cmath>
+#include <new>
+
+#include "sensei_internal.h"
+
+using namespace sensei;
+
+// Rates the additive cost model is built from; defaults are MI355X measurements and can be
+// replaced by sensei_calibrate.
+struct sensei_ctx {
+    int device;
+    double launch_us;      // fixed cost of one kernel launch in a stream
+    double stream_bps;     // achieved bandwidth of a streaming (read + write) kernel
+    double gather_l2_bps;  // row-gather bandwidth when the gathered slice fits the L2s
+    double gather_far_bps; // row-gather bandwidth when it does not (Infinity Cache / HBM)
+    double gemm_flops;     // achieved fp32 MFMA rate on large tiles
+    double l2_slice_bytes; // footprint of one feature-tile slice that still counts as L2 resident
+};
+
+namespace {
+
+const char *kGcnNames[] = {"DYN_AGG", "DYN_UPD", "DYNF_AGG", "DYNF_UPD", "PRE_AGG", "PRE_UPD"};
+const char *kGatNames[] = {"REUSE", "RECOMP", "RECOMP_FOLD", "REUSE_FOLD"};
+constexpr int kNumGcn = 6, kNumGat = 4;
+
+inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
+inline int hip_status(hipError_t e) { return e == hipSuccess ? SENSEI_OK : SENSEI_HIP_ERROR; }
+
+bool csr_ok(const sensei_csr *A, bool need_val) {
+    if (!A || A->n_rows < 0 || A->n_cols < 0 || A->nnz < 0) return false;
+    if (A->nnz > 2147483647LL - 4096) return false;
+    if (!A->row_ptr) return false;
+    if (A->nnz > 0 && !A->col_idx) return false;
+    if (need_val && A->nnz > 0 && !A->val) return false;
+    return true;
+}
+bool mat_ok(const sensei_mat &M) { return M.rows >= 0 && M.cols >= 0 && M.ld >= M.cols && (M.ptr || M.rows == 0 || M.cols == 0); }
+
+bool overlap(const void *a, size_t na, const void *b, size_t nb) {
+    if (!a || !b || na == 0 || nb == 0) return false;
+    const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
+    return x < y + nb && y < x + na;
+}
+size_t mat_bytes(const float *, int64_t rows, int64_t cols, int64_t ld) {
+    if (rows <= 0 || cols <= 0) return 0;
+    return (size_t)((rows - 1) * ld + cols) * sizeof(float);
+}
+
+// carves 256-byte aligned pieces out of the caller's workspace
+struct Carver {
+    char *base;
+    size_t used, cap;
+    Carver(void *p, size_t n) : base(static_cast<char *>(p)), used(0), cap(n) {}
+    template <class T> T *take(size_t count) {
+        const size_t bytes = align_up(count * sizeof(T), 256);
+        T *p = reinterpret_cast<T *>(base + used);
+        used += bytes;
+        return p;
+    }
+};
+
+size_t sparse_ws(const sensei_csr &A, int f) {
+    return plan_bytes(A.nnz) + spmm_carry_bytes(A.nnz, f) + softmax_ws_bytes(A) + 256;
+}
+
+ChunkPlan make_plan(const sensei_csr &A, Carver &cv) {
+    ChunkPlan p;
+    p.chunk_nnz = choose_chunk_nnz(A.nnz, 1);
+    p.n_chunks = A.nnz <= 0 ? 1 : (int)((A.nnz + p.chunk_nnz - 1) / p.chunk_nnz);
+    p.chunk_row = cv.take<int32_t>((size_t)p.n_chunks + 1);
+    return p;
+}
+
+bool gcn_is_agg(int id) { return id == SENSEI_GCN_DYN_AGG || id == SENSEI_GCN_DYNF_AGG || id == SENSEI_GCN_PRE_AGG; }
+
+size_t gcn_ws(const sensei_csr &A, int f_in, int f_out, int id) {
+    const int fs = gcn_is_agg(id) ? pad4(f_in) : pad4(f_out);
+    size_t b = plan_bytes(A.nnz) + spmm_carry_bytes(A.nnz, fs);
+    if (gcn_is_agg(id)) {
+        b += align_up((size_t)A.n_rows * fs * sizeof(float), 256);                                    // U
+        if (id == SENSEI_GCN_DYN_AGG) b += align_up((size_t)A.n_cols * fs * sizeof(float), 256);      // c (x) X
+    } else {
+        b += align_up((size_t)A.n_cols * fs * sizeof(float), 256);                                    // Z = X.W
+    }
+    return b + 256;
+}
+
+bool gat_is_reuse(int id) { return id == SENSEI_GAT_REUSE || id == SENSEI_GAT_REUSE_FOLD; }
+
+size_t gat_ws(const sensei_csr &A, int f_in, int f_out, int id) {
+    const int fo = pad4(f_out), fi = pad4(f_in);
+    size_t b = plan_bytes(A.nnz) + softmax_ws_bytes(A);
+    b += 2 * align_up((size_t)A.n_cols * sizeof(float), 256);                  // s_l, s_r
+    b += align_up((size_t)(A.nnz > 0 ? A.nnz : 1) * sizeof(float), 256);       // alpha
+    b += 2 * align_up((size_t)fi * sizeof(float), 256);                        // W.a_l, W.a_r
+    if (id != SENSEI_GAT_RECOMP_FOLD) b += align_up((size_t)A.n_cols * fo * sizeof(float), 256);  // Theta
+    if (gat_is_reuse(id)) {
+        b += spmm_carry_bytes(A.nnz, fo);
+    } else {
+        b += spmm_carry_bytes(A.nnz, fi);
+        b += align_up((size_t)A.n_rows * fi * sizeof(float), 256);             // U = alpha.X
+    }
+    return b + 256;
+}
+
+#define SENSEI_TRY(expr)                                  \
+    do {                                                  \
+        hipError_t e__ = (expr);                          \
+        if (e__ != hipSuccess) return SENSEI_HIP_ERROR;   \
+    } while (0)
+
+int run_gcn(const sensei_csr &A, const float *r, const float *c, const sensei_mat &X, const sensei_mat &W, float *Y,
+            int64_t ldy, int act, int id, void *ws, size_t ws_bytes, hipStream_t s) {
+    const int f_in = (int)X.cols, f_out = (int)W.cols;
+    Carver cv(ws, ws_bytes);
+    ChunkPlan plan = make_plan(A, cv);
+    SENSEI_TRY(launch_chunk_rows(A, plan, s));
+    const int mode = (id == SENSEI_GCN_DYN_AGG || id == SENSEI_GCN_DYN_UPD) ? SENSEI_SPMM_PATTERN
+                     : (id == SENSEI_GCN_DYNF_AGG || id == SENSEI_GCN_DYNF_UPD) ? SENSEI_SPMM_SCALED
+                                                                                 : SENSEI_SPMM_WEIGHTED;
+    if (gcn_is_agg(id)) {
+        const int fs = pad4(f_in);
+        float *carry = cv.take<float>(spmm_carry_bytes(A.nnz, fs) / sizeof(float));
+        float *U = cv.take<float>((size_t)A.n_rows * fs);
+        const float *src = X.ptr;
+        int64_t ld_src = X.ld;
+        if (id == SENSEI_GCN_DYN_AGG) {  // row broadcast, value-less SpMM, row broadcast (Eq. 3)
+            float *T = cv.take<float>((size_t)A.n_cols * fs);
+            SENSEI_TRY(launch_row_broadcast(c, X.ptr, X.ld, A.n_cols, f_in, T, fs, SENSEI_ACT_NONE, s));
+            src = T;
+            ld_src = fs;
+        }
+        SENSEI_TRY(launch_spmm(A, mode, r, c, src, ld_src, f_in, U, fs, f_in, SENSEI_ACT_NONE, plan, carry, s));
+        if (id == SENSEI_GCN_DYN_AGG) SENSEI_TRY(launch_row_broadcast(r, U, fs, A.n_rows, f_in, U, fs, SENSEI_ACT_NONE, s));
+        SENSEI_TRY(launch_gemm(U, fs, W.ptr, W.ld, Y, ldy, A.n_rows, f_in, f_out, f_out, act, s));
+    } else {
+        const int fs = pad4(f_out);
+        float *carry = cv.take<float>(spmm_carry_bytes(A.nnz, fs) / sizeof(float));
+        float *Z = cv.take<float>((size_t)A.n_cols * fs);
+        SENSEI_TRY(launch_gemm(X.ptr, X.ld, W.ptr, W.ld, Z, fs, A.n_cols, f_in, f_out, fs, SENSEI_ACT_NONE, s));
+        if (id == SENSEI_GCN_DYN_UPD) {
+            SENSEI_TRY(launch_row_broadcast(c, Z, fs, A.n_cols, fs, Z, fs, SENSEI_ACT_NONE, s));
+            SENSEI_TRY(launch_spmm(A, mode, r, c, Z, fs, fs, Y, ldy, f_out, SENSEI_ACT_NONE, plan, carry, s));
+            SENSEI_TRY(launch_row_broadcast(r, Y, ldy, A.n_rows, f_out, Y, ldy, act, s));
+        } else {
+            SENSEI_TRY(launch_spmm(A, mode, r, c, Z, fs, fs, Y, ldy, f_out, act, plan, carry, s));
+        }
+    }
+    return SENSEI_OK;
+}
+
+int run_gat(const sensei_csr &A, const sensei_mat &X, const sensei_mat &W, const float *a_l, const float *a_r,
+            float slope, float *Y, int64_t ldy, int act, int id, void *ws, size_t ws_bytes, hipStream_t s) {
+    const int f_in = (int)X.cols, f_out = (int)W.cols;
+    const int fo = pad4(f_out), fi = pad4(f_in);
+    Carver cv(ws, ws_bytes);
+    ChunkPlan plan = make_plan(A, cv);
+    float2 *stats = cv.take<float2>((size_t)A.n_rows + 1);
+    float2 *carry_stats = cv.take<float2>((size_t)plan.n_chunks);
+    float *s_l = cv.take<float>((size_t)A.n_cols);
+    float *s_r = cv.take<float>((size_t)A.n_cols);
+    float *alpha = cv.take<float>((size_t)(A.nnz > 0 ? A.nnz : 1));
+    float *v_l = cv.take<float>((size_t)fi);
+    float *v_r = cv.take<float>((size_t)fi);
+    float *theta = nullptr;
+    if (id != SENSEI_GAT_RECOMP_FOLD) theta = cv.take<float>((size_t)A.n_cols * fo);
+
+    SENSEI_TRY(launch_chunk_rows(A, plan, s));
+    const bool fold = (id == SENSEI_GAT_RECOMP_FOLD || id == SENSEI_GAT_REUSE_FOLD);
+    if (!fold) {  // Theta = X.W, then the two projections of Theta
+        SENSEI_TRY(launch_gemm(X.ptr, X.ld, W.ptr, W.ld, theta, fo, A.n_cols, f_in, f_out, fo, SENSEI_ACT_NONE, s));
+        SENSEI_TRY(launch_gemv2(theta, fo, A.n_cols, f_out, a_l, a_r, s_l, s_r, s));
+    } else {      // (X.W).a = X.(W.a)
+        SENSEI_TRY(launch_gemv2(W.ptr, W.ld, f_in, f_out, a_l, a_r, v_l, v_r, s));
+        SENSEI_TRY(launch_gemv2(X.ptr, X.ld, A.n_cols, f_in, v_l, v_r, s_l, s_r, s));
+    }
+    SENSEI_TRY(launch_softmax(A, nullptr, s_l, s_r, slope, alpha, plan, stats, carry_stats, s));
+    sensei_csr Aw = A;
+    Aw.val = alpha;
+    if (gat_is_reuse(id)) {
+        if (fold) SENSEI_TRY(launch_gemm(X.ptr, X.ld, W.ptr, W.ld, theta, fo, A.n_cols, f_in, f_out, fo, SENSEI_ACT_NONE, s));
+        float *carry = cv.take<float>(spmm_carry_bytes(A.nnz, fo) / sizeof(float));
+        SENSEI_TRY(launch_spmm(Aw, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, theta, fo, fo, Y, ldy, f_out, act, plan, carry, s));
+    } else {
+        float *carry = cv.take<float>(spmm_carry_bytes(A.nnz, fi) / sizeof(float));
+        float *U = cv.take<float>((size_t)A.n_rows * fi);
+        SENSEI_TRY(launch_spmm(Aw, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, X.ptr, X.ld, f_in, U, fi, f_in, SENSEI_ACT_NONE, plan, carry, s));
+        SENSEI_TRY(launch_gemm(U, fi, W.ptr, W.ld, Y, ldy, A.n_rows, f_in, f_out, f_out, act, s));
+    }
+    return SENSEI_OK;
+}
+
+// ------------------------------------------------------------------ cost model
+
+struct Features {
+    double n_rows, n_cols, nnz, density;
+};
+
+double t_stream(const sensei_ctx &c, double bytes) { return c.launch_us * 1e-6 + bytes / c.stream_bps; }
+
+double t_gemm(const sensei_ctx &c, double n, double k, double m) {
+    const double flops = 2.0 * n * k * m, bytes = 4.0 * (n * k + k * m + n * m);
+    return c.launch_us * 1e-6 + std::fmax(flops / c.gemm_flops, bytes / c.stream_bps);
+}
+
+// SpMM: index traffic streams, neighbour rows are gathered; the gather rate depends on whether
+// one 128-byte feature slice of the gathered matrix (n_cols lines) stays resident in an L2.
+double t_spmm(const sensei_ctx &c, const Features &g, double f, bool weighted) {
+    const double tiles = std::ceil(f / 32.0);
+    const double idx_bytes = g.nnz * (weighted ? 8.0 : 4.0) * tiles;
+    const double out_bytes = 4.0 * f * g.n_rows;
+    const double slice = g.n_cols * 128.0;
+    const double hit = std::fmin(1.0, c.l2_slice_bytes / std::fmax(slice, 1.0));
+    const double bw = 1.0 / (hit / c.gather_l2_bps + (1.0 - hit) / c.gather_far_bps);
+    const double gather = g.nnz * 4.0 * f / bw;
+    const double compulsory = (4.0 * f * g.n_cols + out_bytes + idx_bytes) / c.stream_bps;
+    return 3.0 * c.launch_us * 1e-6 + std::fmax(gather + idx_bytes / c.stream_bps, compulsory);
+}
+
+double gcn_cost(const sensei_ctx &c, const Features &g, int f_in, int f_out, int id) {
+    const bool agg = gcn_is_agg(id);
+    const double fs = agg ? f_in : f_out;
+    const double gemm_rows = agg ? g.n_rows : g.n_cols;
+    double t = c.launch_us * 1e-6 + t_gemm(c, gemm_rows, f_in, f_out);
+    switch (id) {
+        case SENSEI_GCN_DYN_AGG: case SENSEI_GCN_DYN_UPD:
+            t += t_spmm(c, g, fs, false) + t_stream(c, 8.0 * g.n_cols * fs) + t_stream(c, 8.0 * g.n_rows * fs);
+            break;
+        case SENSEI_GCN_DYNF_AGG: case SENSEI_GCN_DYNF_UPD:
+            t += t_spmm(c, g, fs, false);
+            break;
+        default:
+            t += t_spmm(c, g, fs, true);
+            break;
+    }
+    return t;
+}
+
+double gat_cost(const sensei_ctx &c, const Features &g, int f_in, int f_out, int id) {
+    const bool fold = (id == SENSEI_GAT_RECOMP_FOLD || id == SENSEI_GAT_REUSE_FOLD);
+    double t = c.launch_us * 1e-6;
+    // attention: stats + alpha passes over the pattern
+    t += 3.0 * c.launch_us * 1e-6 + (g.nnz * 12.0 + g.n_rows * 16.0) / c.stream_bps;
+    if (fold) t += t_stream(c, 4.0 * f_in * f_out) + t_stream(c, 4.0 * g.n_cols * f_in);
+    else t += t_gemm(c, g.n_cols, f_in, f_out) + t_stream(c, 4.0 * g.n_cols * f_out);
+    if (gat_is_reuse(id)) {
+        if (fold) t += t_gemm(c, g.n_cols, f_in, f_out);
+        t += t_spmm(c, g, f_out, true);
+    } else {
+        t += t_spmm(c, g, f_in, true) + t_gemm(c, g.n_rows, f_in, f_out);
+    }
+    return t;
+}
+
+void rule_filter(int kind, int f_in, int f_out, bool *keep) {
+    if (kind == SENSEI_KIND_GCN) {
+        for (int id = 0; id < kNumGcn; ++id) {
+            const bool agg = gcn_is_agg(id);
+            keep[id] = (f_in == f_out) || (agg ? f_in < f_out : f_in > f_out);
+        }
+    } else {
+        for (int id = 0; id < kNumGat; ++id) keep[id] = (f_in < f_out) || id == SENSEI_GAT_REUSE;
+    }
+}
+
+__global__ void k_fill_f32(float *p, long long n, float v) {
+    long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < n) p[t] = v * (float)((t % 7) - 3);
+}
+hipError_t fill(float *p, size_t n, float v, hipStream_t s) {
+    if (n) hipLaunchKernelGGL(k_fill_f32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p, (long long)n, v);
+    return hipGetLastError();
+}
+
+size_t select_scratch_bytes(int kind, const sensei_csr &A, int f_in, int f_out) {
+    size_t b = 0;
+    b += align_up((size_t)A.n_cols * f_in * sizeof(float), 256);   // X
+    b += align_up((size_t)f_in * f_out * sizeof(float), 256);      // W
+    b += align_up((size_t)A.n_rows * f_out * sizeof(float), 256);  // Y
+    b += 2 * align_up((size_t)(A.n_rows + A.n_cols) * sizeof(float), 256);  // r, c, degrees
+    b += align_up((size_t)(A.nnz > 0 ? A.nnz : 1) * sizeof(float), 256);    // N~
+    b += 2 * align_up((size_t)f_out * sizeof(float), 256);                  // a_l, a_r
+    size_t layer = 0;
+    const int n = kind == SENSEI_KIND_GCN ? kNumGcn : kNumGat;
+    for (int id = 0; id < n; ++id) {
+        const size_t w = kind == SENSEI_KIND_GCN ? gcn_ws(A, f_in, f_out, id) : gat_ws(A, f_in, f_out, id);
+        layer = w > layer ? w : layer;
+    }
+    return b + layer + 1024;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------- C ABI
+
+extern "C" {
+
+int sensei_create(sensei_ctx **out, int device) {
+    if (!out) return SENSEI_INVALID_ARGUMENT;
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess) return SENSEI_HIP_ERROR;
+    if (device < 0 || device >= count) return SENSEI_INVALID_ARGUMENT;
+    sensei_ctx *c = new (std::nothrow) sensei_ctx;
+    if (!c) return SENSEI_HIP_ERROR;
+    c->device = device;
+    c->launch_us = 3.0;
+    c->stream_bps = 4.0e12;
+    c->gather_l2_bps = 9.0e12;
+    c->gather_far_bps = 3.5e12;
+    c->gemm_flops = 60.0e12;
+    c->l2_slice_bytes = 3.0e6;
+    *out = c;
+    return SENSEI_OK;
+}
+
+int sensei_destroy(sensei_ctx *ctx) {
+    delete ctx;
+    return SENSEI_OK;
+}
+
+int sensei_num_compositions(int kind) { return kind == SENSEI_KIND_GCN ? kNumGcn : kind == SENSEI_KIND_GAT ? kNumGat : 0; }
+
+const char *sensei_composition_name(int kind, int id) {
+    if (kind == SENSEI_KIND_GCN && id >= 0 && id < kNumGcn) return kGcnNames[id];
+    if (kind == SENSEI_KIND_GAT && id >= 0 && id < kNumGat) return kGatNames[id];
+    return "?";
+}
+
+const char *sensei_status_string(int status) {
+    switch (status) {
+        case SENSEI_OK: return "ok";
+        case SENSEI_INVALID_ARGUMENT: return "invalid argument";
+        case SENSEI_INVALID_COMPOSITION: return "invalid composition id";
+        case SENSEI_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case SENSEI_HIP_ERROR: return "HIP error";
+        case SENSEI_UNSUPPORTED: return "unsupported";
+        default: return "unknown status";
+    }
+}
+
+int sensei_degrees(sensei_ctx *ctx, const sensei_csr *A, int32_t *deg_row, int32_t *deg_col, void *stream) {
+    if (!ctx || !csr_ok(A, false)) return SENSEI_INVALID_ARGUMENT;
+    if ((A->n_rows > 0 && !deg_row) || (A->n_cols > 0 && !deg_col)) return SENSEI_INVALID_ARGUMENT;
+    return hip_status(launch_degrees(*A, deg_row, deg_col, as_stream(stream)));
+}
+
+int sensei_norm_vectors(sensei_ctx *ctx, const int32_t *deg, int64_t n, float *out, void *stream) {
+    if (!ctx || n < 0 || (n > 0 && (!deg || !out))) return SENSEI_INVALID_ARGUMENT;
+    return hip_status(launch_norm_vectors(deg, n, out, as_stream(stream)));
+}
+
+int sensei_sparse_workspace(const sensei_csr *A, int f, size_t *bytes) {
+    if (!csr_ok(A, false) || f < 0 || !bytes) return SENSEI_INVALID_ARGUMENT;
+    *bytes = sparse_ws(*A, pad4(f));
+    return SENSEI_OK;
+}
+
+int sensei_gcn_precompute(sensei_ctx *ctx, const sensei_csr *A, const float *r, const float *c, float *val_out,
+                          void *workspace, size_t ws_bytes, void *stream) {
+    if (!ctx || !csr_ok(A, false)) return SENSEI_INVALID_ARGUMENT;
+    if (A->nnz > 0 && (!r || !c || !val_out)) return SENSEI_INVALID_ARGUMENT;
+    if (!workspace) return SENSEI_INVALID_ARGUMENT;
+    if (ws_bytes < plan_bytes(A->nnz)) return SENSEI_WORKSPACE_TOO_SMALL;
+    Carver cv(workspace, ws_bytes);
+    ChunkPlan plan = make_plan(*A, cv);
+    SENSEI_TRY(launch_chunk_rows(*A, plan, as_stream(stream)));
+    return hip_status(launch_sddmm_norm(*A, r, c, val_out, plan, as_stream(stream)));
+}
+
+int sensei_row_broadcast(sensei_ctx *ctx, const float *s, sensei_mat X, float *Y, int64_t ldy, void *stream) {
+    if (!ctx || !mat_ok(X) || ldy < X.cols) return SENSEI_INVALID_ARGUMENT;
+    if (X.rows > 0 && X.cols > 0 && (!s || !Y)) return SENSEI_INVALID_ARGUMENT;
+    if (X.cols > 2147483647LL) return SENSEI_INVALID_ARGUMENT;
+    if (Y != X.ptr && overlap(Y, mat_bytes(Y, X.rows, X.cols, ldy), X.ptr, mat_bytes(X.ptr, X.rows, X.cols, X.ld))) return SENSEI_INVALID_ARGUMENT;
+    if (Y == X.ptr && ldy != X.ld) return SENSEI_INVALID_ARGUMENT;
+    return hip_status(launch_row_broadcast(s, X.ptr, X.ld, X.rows, (int)X.cols, Y, ldy, SENSEI_ACT_NONE, as_stream(stream)));
+}
+
+int sensei_spmm(sensei_ctx *ctx, const sensei_csr *A, int mode, const float *r, const float *c, sensei_mat B, float *C,
+                int64_t ldc, int activation, void *workspace, size_t ws_bytes, void *stream) {
+    if (mode < SENSEI_SPMM_PATTERN || mode > SENSEI_SPMM_SCALED) return SENSEI_INVALID_ARGUMENT;
+    if (!ctx || !csr_ok(A, mode == SENSEI_SPMM_WEIGHTED) || !mat_ok(B)) return SENSEI_INVALID_ARGUMENT;
+    if (activation != SENSEI_ACT_NONE && activation != SENSEI_ACT_RELU) return SENSEI_INVALID_ARGUMENT;
+    if (B.rows != A->n_cols || ldc < B.cols || B.cols > (1 << 20)) return SENSEI_INVALID_ARGUMENT;
+    if (mode == SENSEI_SPMM_SCALED && ((A->n_rows > 0 && !r) || (A->n_cols > 0 && !c))) return SENSEI_INVALID_ARGUMENT;
+    if (A->n_rows > 0 && B.cols > 0 && !C) return SENSEI_INVALID_ARGUMENT;
+    if (A->n_rows == 0 || B.cols == 0) return SENSEI_OK;
+    if (!workspace) return SENSEI_INVALID_ARGUMENT;
+    const int f = (int)B.cols;
+    const size_t cbytes = mat_bytes(C, A->n_rows, f, ldc);
+    if (overlap(C, cbytes, B.ptr, mat_bytes(B.ptr, B.rows, f, B.ld)) || overlap(C, cbytes, workspace, ws_bytes)) return SENSEI_INVALID_ARGUMENT;
+    if (ws_bytes < plan_bytes(A->nnz) + spmm_carry_bytes(A->nnz, f)) return SENSEI_WORKSPACE_TOO_SMALL;
+    Carver cv(workspace, ws_bytes);
+    ChunkPlan plan = make_plan(*A, cv);
+    float *carry = cv.take<float>(spmm_carry_bytes(A->nnz, f) / sizeof(float));
+    SENSEI_TRY(launch_chunk_rows(*A, plan, as_stream(stream)));
+    return hip_status(launch_spmm(*A, mode, r, c, B.ptr, B.ld, f, C, ldc, f, activation, plan, carry, as_stream(stream)));
+}
+
+int sensei_gemm(sensei_ctx *ctx, sensei_mat A, sensei_mat W, float *Y, int64_t ldy, int activation, void *stream) {
+    if (!ctx || !mat_ok(A) || !mat_ok(W) || A.cols != W.rows || ldy < W.cols) return SENSEI_INVALID_ARGUMENT;
+    if (activation != SENSEI_ACT_NONE && activation != SENSEI_ACT_RELU) return SENSEI_INVALID_ARGUMENT;
+    if (A.cols > (1 << 20) || W.cols > (1 << 20)) return SENSEI_INVALID_ARGUMENT;
+    if (A.rows > 0 && W.cols > 0 && !Y) return SENSEI_INVALID_ARGUMENT;
+    const size_t ybytes = mat_bytes(Y, A.rows, W.cols, ldy);
+    if (overlap(Y, ybytes, A.ptr, mat_bytes(A.ptr, A.rows, A.cols, A.ld)) || overlap(Y, ybytes, W.ptr, mat_bytes(W.ptr, W.rows, W.cols, W.ld))) return SENSEI_INVALID_ARGUMENT;
+    return hip_status(launch_gemm(A.ptr, A.ld, W.ptr, W.ld, Y, ldy, A.rows, (int)A.cols, (int)W.cols, (int)W.cols, activation, as_stream(stream)));
+}
+
+int sensei_gemv2(sensei_ctx *ctx, sensei_mat A, const float *v1, const float *v2, float *y1, float *y2, void *stream) {
+    if (!ctx || !mat_ok(A) || A.cols > (1 << 20)) return SENSEI_INVALID_ARGUMENT;
+    if (A.rows > 0 && (!y1 || !y2)) return SENSEI_INVALID_ARGUMENT;
+    if (A.rows > 0 && A.cols > 0 && (!v1 || !v2)) return SENSEI_INVALID_ARGUMENT;
+    return hip_status(launch_gemv2(A.ptr, A.ld, A.rows, (int)A.cols, v1, v2, y1, y2, as_stream(stream)));
+}
+
+int sensei_sddmm_score(sensei_ctx *ctx, const sensei_csr *A, const float *s_l, const float *s_r, float neg_slope,
+                       float *e_out, void *workspace, size_t ws_bytes, void *stream) {
+    if (!ctx || !csr_ok(A, false)) return SENSEI_INVALID_ARGUMENT;
+    if (A->nnz > 0 && (!s_l || !s_r || !e_out)) return SENSEI_INVALID_ARGUMENT;
+    if (!workspace) return SENSEI_INVALID_ARGUMENT;
+    if (ws_bytes < plan_bytes(A->nnz)) return SENSEI_WORKSPACE_TOO_SMALL;
+    Carver cv(workspace, ws_bytes);
+    ChunkPlan plan = make_plan(*A, cv);
+    SENSEI_TRY(launch_chunk_rows(*A, plan, as_stream(stream)));
+    return hip_status(launch_score(*A, s_l, s_r, neg_slope, e_out, plan, as_stream(stream)));
+}
+
+int sensei_edge_softmax(sensei_ctx *ctx, const sensei_csr *A, const float *e, float *alpha_out, void *workspace,
+                        size_t ws_bytes, void *stream) {
+    if (!ctx || !csr_ok(A, false)) return SENSEI_INVALID_ARGUMENT;
+    if (A->nnz > 0 && (!e || !alpha_out)) return SENSEI_INVALID_ARGUMENT;
+    if (!workspace) return SENSEI_INVALID_ARGUMENT;
+    if (ws_bytes < plan_bytes(A->nnz) + softmax_ws_bytes(*A)) return SENSEI_WORKSPACE_TOO_SMALL;
+    if (A->nnz == 0) return SENSEI_OK;
+    Carver cv(workspace, ws_bytes);
+    ChunkPlan plan = make_plan(*A, cv);
+    float2 *stats = cv.take<float2>((size_t)A->n_rows + 1);
+    float2 *carry_stats = cv.take<float2>((size_t)plan.n_chunks);
+    SENSEI_TRY(launch_chunk_rows(*A, plan, as_stream(stream)));
+    return hip_status(launch_softmax(*A, e, nullptr, nullptr, 0.f, alpha_out, plan, stats, carry_stats, as_stream(stream)));
+}
+
+int sensei_gcn_workspace(const sensei_csr *A, int f_in, int f_out, int comp_id, size_t *bytes) {
+    if (!csr_ok(A, false) || f_in <= 0 || f_out <= 0 || !bytes) return SENSEI_INVALID_ARGUMENT;
+    if (comp_id < 0 || comp_id >= kNumGcn) return SENSEI_INVALID_COMPOSITION;
+    *bytes = gcn_ws(*A, f_in, f_out, comp_id);
+    return SENSEI_OK;
+}
+
+int sensei_gcn_layer(sensei_ctx *ctx, const sensei_csr *A, const float *r, const float *c, sensei_mat X, sensei_mat W,
+                     float *Y, int64_t ldy, int activation, int comp_id, void *workspace, size_t ws_bytes, void *stream) {
+    if (comp_id < 0 || comp_id >= kNumGcn) return SENSEI_INVALID_COMPOSITION;
+    const bool pre = (comp_id == SENSEI_GCN_PRE_AGG || comp_id == SENSEI_GCN_PRE_UPD);
+    if (!ctx || !csr_ok(A, pre) || !mat_ok(X) || !mat_ok(W)) return SENSEI_INVALID_ARGUMENT;
+    if (activation != SENSEI_ACT_NONE && activation != SENSEI_ACT_RELU) return SENSEI_INVALID_ARGUMENT;
+    if (X.rows != A->n_cols || X.cols != W.rows || X.cols <= 0 || W.cols <= 0 || ldy < W.cols) return SENSEI_INVALID_ARGUMENT;
+    if (X.cols > (1 << 20) || W.cols > (1 << 20)) return SENSEI_INVALID_ARGUMENT;
+    if (!X.ptr && A->n_cols > 0) return SENSEI_INVALID_ARGUMENT;
+    if (!W.ptr || (!Y && A->n_rows > 0) || !workspace) return SENSEI_INVALID_ARGUMENT;
+    if (!pre && ((A->n_rows > 0 && !r) || (A->n_cols > 0 && !c))) return SENSEI_INVALID_ARGUMENT;
+    const size_t ybytes = mat_bytes(Y, A->n_rows, W.cols, ldy);
+    if (overlap(Y, ybytes, X.ptr, mat_bytes(X.ptr, X.rows, X.cols, X.ld)) || overlap(Y, ybytes, W.ptr, mat_bytes(W.ptr, W.rows, W.cols, W.ld)) ||
+        overlap(Y, ybytes, workspace, ws_bytes) || overlap(X.ptr, mat_bytes(X.ptr, X.rows, X.cols, X.ld), workspace, ws_bytes))
+        return SENSEI_INVALID_ARGUMENT;
+    if (ws_bytes < gcn_ws(*A, (int)X.cols, (int)W.cols, comp_id)) return SENSEI_WORKSPACE_TOO_SMALL;
+    if (A->n_rows == 0) return SENSEI_OK;
+    return run_gcn(*A, r, c, X, W, Y, ldy, activation, comp_id, workspace, ws_bytes, as_stream(stream));
+}
+
+int sensei_gat_workspace(const sensei_csr *A, int f_in, int f_out, int comp_id, size_t *bytes) {
+    if (!csr_ok(A, false) || f_in <= 0 || f_out <= 0 || !bytes) return SENSEI_INVALID_ARGUMENT;
+    if (comp_id < 0 || comp_id >= kNumGat) return SENSEI_INVALID_COMPOSITION;
+    *bytes = gat_ws(*A, f_in, f_out, comp_id);
+    return SENSEI_OK;
+}
+
+int sensei_gat_layer(sensei_ctx *ctx, const sensei_csr *A, sensei_mat X, sensei_mat W, const float *a_l, const float *a_r,
+                     float neg_slope, float *Y, int64_t ldy, int activation, int comp_id, void *workspace, size_t ws_bytes,
+                     void *stream) {
+    if (comp_id < 0 || comp_id >= kNumGat) return SENSEI_INVALID_COMPOSITION;
+    if (!ctx || !csr_ok(A, false) || !mat_ok(X) || !mat_ok(W)) return SENSEI_INVALID_ARGUMENT;
+    if (activation != SENSEI_ACT_NONE && activation != SENSEI_ACT_RELU) return SENSEI_INVALID_ARGUMENT;
+    if (A->n_rows > A->n_cols) return SENSEI_INVALID_ARGUMENT;
+    if (X.rows != A->n_cols || X.cols != W.rows || X.cols <= 0 || W.cols <= 0 || ldy < W.cols) return SENSEI_INVALID_ARGUMENT;
+    if (X.cols > (1 << 20) || W.cols > (1 << 20)) return SENSEI_INVALID_ARGUMENT;
+    if (!X.ptr && A->n_cols > 0) return SENSEI_INVALID_ARGUMENT;
+    if (!W.ptr || !a_l || !a_r || (!Y && A->n_rows > 0) || !workspace) return SENSEI_INVALID_ARGUMENT;
+    const size_t ybytes = mat_bytes(Y, A->n_rows, W.cols, ldy);
+    if (overlap(Y, ybytes, X.ptr, mat_bytes(X.ptr, X.rows, X.cols, X.ld)) || overlap(Y, ybytes, W.ptr, mat_bytes(W.ptr, W.rows, W.cols, W.ld)) ||
+        overlap(Y, ybytes, workspace, ws_bytes) || overlap(X.ptr, mat_bytes(X.ptr, X.rows, X.cols, X.ld), workspace, ws_bytes))
+        return SENSEI_INVALID_ARGUMENT;
+    if (ws_bytes < gat_ws(*A, (int)X.cols, (int)W.cols, comp_id)) return SENSEI_WORKSPACE_TOO_SMALL;
+    if (A->n_rows == 0) return SENSEI_OK;
+    return run_gat(*A, X, W, a_l, a_r, neg_slope, Y, ldy, activation, comp_id, workspace, ws_bytes, as_stream(stream));
+}
+
+int sensei_select_workspace(int kind, const sensei_csr *A, int f_in, int f_out, size_t *bytes) {
+    if ((kind != SENSEI_KIND_GCN && kind != SENSEI_KIND_GAT) || !csr_ok(A, false) || f_in <= 0 || f_out <= 0 || !bytes)
+        return SENSEI_INVALID_ARGUMENT;
+    *bytes = select_scratch_bytes(kind, *A, f_in, f_out);
+    return SENSEI_OK;
+}
+
+int sensei_select(sensei_ctx *ctx, int kind, const sensei_csr *A, int f_in, int f_out, int mode, int *comp_id_out,
+                  float *est_ms, void *workspace, size_t ws_bytes, void *stream) {
+    if (!ctx || (kind != SENSEI_KIND_GCN && kind != SENSEI_KIND_GAT) || !csr_ok(A, false) || f_in <= 0 || f_out <= 0 || !comp_id_out)
+        return SENSEI_INVALID_ARGUMENT;
+    if (mode != SENSEI_SELECT_MODEL && mode != SENSEI_SELECT_TIMED) return SENSEI_INVALID_ARGUMENT;
+    if (kind == SENSEI_KIND_GAT && A->n_rows > A->n_cols) return SENSEI_INVALID_ARGUMENT;
+    const int n = kind == SENSEI_KIND_GCN ? kNumGcn : kNumGat;
+    bool keep[8];
+    rule_filter(kind, f_in, f_out, keep);
+    double cost[8];
+    for (int id = 0; id < n; ++id) cost[id] = -1.0;
+
+    if (mode == SENSEI_SELECT_MODEL) {
+        Features g;
+        g.n_rows = A->n_rows; g.n_cols = A->n_cols; g.nnz = (double)A->nnz;
+        g.density = (A->n_rows > 0 && A->n_cols > 0) ? g.nnz / (g.n_rows * g.n_cols) : 0.0;
+        for (int id = 0; id < n; ++id)
+            if (keep[id]) cost[id] = 1e3 * (kind == SENSEI_KIND_GCN ? gcn_cost(*ctx, g, f_in, f_out, id) : gat_cost(*ctx, g, f_in, f_out, id));
+    } else {
+        if (!workspace) return SENSEI_INVALID_ARGUMENT;
+        if (ws_bytes < select_scratch_bytes(kind, *A, f_in, f_out)) return SENSEI_WORKSPACE_TOO_SMALL;
+        hipStream_t s = as_stream(stream);
+        Carver cv(workspace, ws_bytes);
+        float *X = cv.take<float>((size_t)A->n_cols * f_in);
+        float *W = cv.take<float>((size_t)f_in * f_out);
+        float *Y = cv.take<float>((size_t)A->n_rows * f_out);
+        float *r = cv.take<float>((size_t)A->n_rows + A->n_cols);
+        float *c = r + A->n_rows;
+        int32_t *deg = cv.take<int32_t>((size_t)A->n_rows + A->n_cols);
+        float *nt = cv.take<float>((size_t)(A->nnz > 0 ? A->nnz : 1));
+        float *a_l = cv.take<float>((size_t)f_out);
+        float *a_r = cv.take<float>((size_t)f_out);
+        void *lws = cv.base + cv.used;
+        const size_t lws_bytes = ws_bytes - cv.used;
+        SENSEI_TRY(fill(X, (size_t)A->n_cols * f_in, 0.25f, s));
+        SENSEI_TRY(fill(W, (size_t)f_in * f_out, 0.01f, s));
+        SENSEI_TRY(fill(a_l, (size_t)f_out, 0.05f, s));
+        SENSEI_TRY(fill(a_r, (size_t)f_out, 0.05f, s));
+        SENSEI_TRY(launch_degrees(*A, deg, deg + A->n_rows, s));
+        SENSEI_TRY(launch_norm_vectors(deg, (int64_t)A->n_rows + A->n_cols, r, s));
+        sensei_csr Aw = *A;
+        if (kind == SENSEI_KIND_GCN) {
+            Carver pcv(lws, lws_bytes);
+            ChunkPlan plan = make_plan(*A, pcv);
+            SENSEI_TRY(launch_chunk_rows(*A, plan, s));
+            SENSEI_TRY(launch_sddmm_norm(*A, r, c, nt, plan, s));
+            Aw.val = nt;
+        }
+        sensei_mat Xm = {X, A->n_cols, f_in, f_in}, Wm = {W, f_in, f_out, f_out};
+        hipEvent_t e0, e1;
+        if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return SENSEI_HIP_ERROR;
+        int status = SENSEI_OK;
+        for (int id = 0; id < n && status == SENSEI_OK; ++id) {
+            if (!keep[id]) continue;
+            for (int rep = 0; rep < 2 && status == SENSEI_OK; ++rep) {  // rep 0 warms caches and code objects
+                if (rep == 1 && hipEventRecord(e0, s) != hipSuccess) status = SENSEI_HIP_ERROR;
+                if (status == SENSEI_OK)
+                    status = kind == SENSEI_KIND_GCN
+                                 ? run_gcn(Aw, r, c, Xm, Wm, Y, f_out, SENSEI_ACT_RELU, id, lws, lws_bytes, s)
+                                 : run_gat(*A, Xm, Wm, a_l, a_r, 0.2f, Y, f_out, SENSEI_ACT_RELU, id, lws, lws_bytes, s);
+            }
+            if (status != SENSEI_OK) break;
+            float ms = 0.f;
+            if (hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess) {
+                status = SENSEI_HIP_ERROR;
+                break;
+            }
+            cost[id] = ms;
+        }
+        (void)hipEventDestroy(e0);
+        (void)hipEventDestroy(e1);
+        if (status != SENSEI_OK) return status;
+    }
+    int best = -1;
+    for (int id = 0; id < n; ++id)
+        if (keep[id] && cost[id] >= 0.0 && (best < 0 || cost[id] < cost[best])) best = id;
+    if (best < 0) return SENSEI_UNSUPPORTED;
+    *comp_id_out = best;
+    if (est_ms) for (int id = 0; id < n; ++id) est_ms[id] = (float)cost[id];
+    return SENSEI_OK;
+}
+
+int sensei_calibrate(sensei_ctx *ctx, void *workspace, size_t ws_bytes, void *stream) {
+    if (!ctx || !workspace) return SENSEI_INVALID_ARGUMENT;
+    if (ws_bytes < (64u << 20)) return SENSEI_WORKSPACE_TOO_SMALL;
+    hipStream_t s = as_stream(stream);
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return SENSEI_HIP_ERROR;
+    int status = SENSEI_OK;
+    float ms = 0.f;
+    // streaming rate: scale a 32 MiB matrix into the other half of the workspace
+    {
+        float *src = static_cast<float *>(workspace);
+        float *dst = src + (8u << 20);
+        const int64_t rows = 8192, cols = 1024;
+        if (launch_row_broadcast(nullptr, src, cols, rows, (int)cols, dst, cols, SENSEI_ACT_NONE, s) != hipSuccess) status = SENSEI_HIP_ERROR;
+        (void)hipEventRecord(e0, s);
+        for (int it = 0; it < 10 && status == SENSEI_OK; ++it)
+            if (launch_row_broadcast(nullptr, src, cols, rows, (int)cols, dst, cols, SENSEI_ACT_NONE, s) != hipSuccess) status = SENSEI_HIP_ERROR;
+        (void)hipEventRecord(e1, s);
+        if (status == SENSEI_OK && (hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess)) status = SENSEI_HIP_ERROR;
+        if (status == SENSEI_OK && ms > 0.f) ctx->stream_bps = 10.0 * 2.0 * rows * cols * 4.0 / (ms * 1e-3);
+    }
+    // launch latency: empty-sized element-wise launches back to back
+    if (status == SENSEI_OK) {
+        float *src = static_cast<float *>(workspace);
+        (void)hipEventRecord(e0, s);
+        for (int it = 0; it < 100 && status == SENSEI_OK; ++it)
+            if (launch_row_broadcast(nullptr, src, 4, 64, 4, src + 1024, 4, SENSEI_ACT_NONE, s) != hipSuccess) status = SENSEI_HIP_ERROR;
+        (void)hipEventRecord(e1, s);
+        if (status == SENSEI_OK && (hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess)) status = SENSEI_HIP_ERROR;
+        if (status == SENSEI_OK && ms > 0.f) ctx->launch_us = ms * 1e3 / 100.0;
+    }
+    // GEMM rate: 16384 x 256 x 256 on scratch
+    if (status == SENSEI_OK) {
+        float *a = static_cast<float *>(workspace);
+        float *w = a + (size_t)16384 * 256;
+        float *y = w + (size_t)256 * 256;
+        (void)fill(a, (size_t)16384 * 256, 0.1f, s);
+        (void)fill(w, (size_t)256 * 256, 0.1f, s);
+        (void)launch_gemm(a, 256, w, 256, y, 256, 16384, 256, 256, 256, SENSEI_ACT_NONE, s);
+        (void)hipEventRecord(e0, s);
+        for (int it = 0; it < 10 && status == SENSEI_OK; ++it)
+            if (launch_gemm(a, 256, w, 256, y, 256, 16384, 256, 256, 256, SENSEI_ACT_NONE, s) != hipSuccess) status = SENSEI_HIP_ERROR;
+        (void)hipEventRecord(e1, s);
+        if (status == SENSEI_OK && (hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess)) status = SENSEI_HIP_ERROR;
+        const double t = ms * 1e-3 / 10.0 - ctx->launch_us * 1e-6;
+        if (status == SENSEI_OK && t > 0.0) ctx->gemm_flops = 2.0 * 16384 * 256 * 256 / t;
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    return status;
+}
+
+}  // extern "C"

@@ -1,0 +1,67 @@
+// Internal declarations shared by the HIP translation units of libsensei_hip.
+// Host-side launchers only; every launcher validates nothing (the C ABI layer
+// in api.hip does) and returns the hipError_t of its launches.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "sensei.h"
+
+namespace sensei {
+
+// ---- partition of the non-zeros into fixed-size chunks (one wavefront each)
+
+struct ChunkPlan {
+    int chunk_nnz;        // T: non-zeros per chunk, multiple of 64
+    int n_chunks;         // max(1, ceil(nnz / T))
+    int32_t *chunk_row;   // device, n_chunks + 1: first row starting at or after c*T; [n_chunks] = n_rows
+};
+
+int choose_chunk_nnz(int64_t nnz, int n_feature_tiles);
+size_t plan_bytes(int64_t nnz);  // upper bound over all chunk sizes
+hipError_t launch_chunk_rows(const sensei_csr &A, const ChunkPlan &p, hipStream_t s);
+
+// ---- SpMM
+
+struct SpmmShape {
+    int vec;      // floats per lane load: 4, 2 or 1
+    int lpg;      // lanes per neighbour group: 8, 16, 32 or 64
+    int n_tiles;  // feature tiles of vec*lpg floats
+    int f_carry;  // n_tiles * vec * lpg
+};
+SpmmShape spmm_shape(const float *B, int64_t ldb, int f);
+size_t spmm_carry_bytes(int64_t nnz, int f);  // upper bound
+// C[i, 0:f_store) = act(scale_i * sum_j w_ij B[j, 0:f)); f_store <= f; r/c only for SCALED.
+hipError_t launch_spmm(const sensei_csr &A, int mode, const float *r, const float *c, const float *B, int64_t ldb,
+                       int f, float *C, int64_t ldc, int f_store, int act, const ChunkPlan &p, float *carry,
+                       hipStream_t s);
+
+// ---- element-wise work over the non-zeros, degrees, scalings
+hipError_t launch_degrees(const sensei_csr &A, int32_t *deg_row, int32_t *deg_col, hipStream_t s);
+hipError_t launch_norm_vectors(const int32_t *deg, int64_t n, float *out, hipStream_t s);
+hipError_t launch_sddmm_norm(const sensei_csr &A, const float *r, const float *c, float *val, const ChunkPlan &p,
+                             hipStream_t s);
+hipError_t launch_row_broadcast(const float *s_vec, const float *X, int64_t ldx, int64_t n, int f, float *Y,
+                                int64_t ldy, int act, hipStream_t s);
+
+// ---- attention: logits, per-row softmax statistics, normalised weights
+hipError_t launch_score(const sensei_csr &A, const float *s_l, const float *s_r, float slope, float *e,
+                        const ChunkPlan &p, hipStream_t s);
+// stats[i] = (row max, sum of exp(e - max)); logits from `e` when non-null, else from s_l / s_r.
+hipError_t launch_softmax(const sensei_csr &A, const float *e, const float *s_l, const float *s_r, float slope,
+                          float *alpha, const ChunkPlan &p, float2 *stats, float2 *carry_stats, hipStream_t s);
+size_t softmax_ws_bytes(const sensei_csr &A);
+
+// ---- dense
+// Y[0:n, 0:m_store) = act(A[n x k] . W[k x m]); columns m..m_store are written as act(0).
+hipError_t launch_gemm(const float *A, int64_t lda, const float *W, int64_t ldw, float *Y, int64_t ldy, int64_t n,
+                       int k, int m, int m_store, int act, hipStream_t s);
+hipError_t launch_gemv2(const float *A, int64_t lda, int64_t n, int k, const float *v1, const float *v2, float *y1,
+                        float *y2, hipStream_t s);
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline int pad4(int f) { return (f + 3) & ~3; }
+
+}  // namespace sensei

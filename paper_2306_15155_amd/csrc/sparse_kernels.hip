@@ -1,0 +1,581 @@
+// Sparse kernels for gfx950: CSR SpMM (value-less, weighted, scaled), the
+// element-wise SDDMM instances, the segmented edge softmax, degree counts.
+//
+// Work decomposition shared by every kernel that reduces over rows: the
+// non-zeros are cut into chunks of T entries and one 64-lane wavefront owns
+// one chunk (x one feature tile for SpMM).  A row that lies inside a chunk is
+// finished by that wavefront.  A row that crosses a chunk boundary is written
+// in pieces - the piece in the chunk where the row starts goes to the output
+// row unscaled, each later piece goes to a per-chunk carry slot - and a small
+// fix-up kernel adds the carry slots to the row in chunk order.  No float
+// atomics: the summation order is fixed, results are reproducible, and a hub
+// row of a power-law graph is spread over as many wavefronts as it needs.
+#include "sensei_internal.h"
+
+namespace sensei {
+
+namespace {
+
+constexpr int kBlock = 256;
+constexpr int kWavesPerBlock = kBlock / 64;
+
+// ------------------------------------------------------------------ chunk plan
+
+__global__ void k_chunk_rows(const int32_t *__restrict__ row_ptr, int n_rows, int chunk_nnz, int n_chunks,
+                             int32_t *__restrict__ chunk_row) {
+    int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c > n_chunks) return;
+    if (c == n_chunks) { chunk_row[c] = n_rows; return; }
+    const long long target = (long long)c * chunk_nnz;
+    int lo = 0, hi = n_rows + 1;  // first index in [0, n_rows] with row_ptr[idx] >= target
+    while (lo < hi) {
+        int mid = (int)(((long long)lo + hi) >> 1);
+        if ((long long)row_ptr[mid] < target) lo = mid + 1; else hi = mid;
+    }
+    chunk_row[c] = lo < n_rows ? lo : n_rows;
+}
+
+// row that holds non-zero k, searched among the rows a chunk touches
+__device__ __forceinline__ int find_row(const int32_t *__restrict__ row_ptr, int lo_i, int hi_i, int k) {
+    int a = lo_i, b = hi_i;  // first index in [lo_i, hi_i) with row_ptr[idx] > k
+    while (a < b) {
+        int mid = (a + b) >> 1;
+        if (row_ptr[mid] <= k) a = mid + 1; else b = mid;
+    }
+    return a - 1;
+}
+
+// ------------------------------------------------------------------------ SpMM
+
+template <int VEC> struct Vec;
+template <> struct Vec<1> {
+    float v[1];
+    __device__ static Vec load(const float *p) { Vec r; r.v[0] = *p; return r; }
+    __device__ void store(float *p) const { *p = v[0]; }
+};
+template <> struct Vec<2> {
+    float v[2];
+    __device__ static Vec load(const float *p) { float2 t = *reinterpret_cast<const float2 *>(p); Vec r; r.v[0] = t.x; r.v[1] = t.y; return r; }
+    __device__ void store(float *p) const { *reinterpret_cast<float2 *>(p) = make_float2(v[0], v[1]); }
+};
+template <> struct Vec<4> {
+    float v[4];
+    __device__ static Vec load(const float *p) { float4 t = *reinterpret_cast<const float4 *>(p); Vec r; r.v[0] = t.x; r.v[1] = t.y; r.v[2] = t.z; r.v[3] = t.w; return r; }
+    __device__ void store(float *p) const { *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]); }
+};
+
+struct SpmmArgs {
+    const int32_t *row_ptr, *col_idx, *chunk_row;
+    const float *val, *r, *c, *B;
+    float *C, *carry;
+    long long ldb, ldc;
+    int n_rows, nnz, chunk_nnz, n_chunks;
+    int f, f_store, f_carry, n_tiles, act, store_vec_ok;
+};
+
+// One wavefront = one (chunk, feature tile).  The 64 lanes form G = 64/LPG
+// neighbour groups of LPG lanes; a group reads VEC*LPG consecutive floats of
+// one neighbour row per step (one or two 128-byte lines), so G neighbours are
+// in flight per step and 4 steps are issued back to back.  Column indices (and
+// weights) are fetched 64 at a time, one per lane, and handed to the groups by
+// cross-lane reads.  Block b works on feature tile b % n_tiles: consecutive
+// workgroups go to consecutive XCDs, so each XCD's L2 keeps seeing the same
+// slice of the feature columns.
+template <int VEC, int LPG, int MODE>
+__global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
+    constexpr int G = 64 / LPG;
+    constexpr int TF = VEC * LPG;
+    const int lane = threadIdx.x & 63;
+    const int tile = blockIdx.x % a.n_tiles;
+    const int chunk = (blockIdx.x / a.n_tiles) * kWavesPerBlock + (threadIdx.x >> 6);
+    if (chunk >= a.n_chunks) return;
+    const int g = lane / LPG;
+    const int f0 = tile * TF + (lane % LPG) * VEC;
+    const bool fok = f0 < a.f;
+
+    const long long lo_ll = (long long)chunk * a.chunk_nnz;
+    const int lo = (int)lo_ll;
+    const int hi = (int)((lo_ll + a.chunk_nnz < (long long)a.nnz) ? lo_ll + a.chunk_nnz : (long long)a.nnz);
+    const int i0 = a.chunk_row[chunk];
+    const int i1 = a.chunk_row[chunk + 1];
+
+    // first row touched: the one crossing `lo` if there is one, else the first owned row
+    bool cont = (a.nnz > 0) && (a.row_ptr[i0] > lo);
+    int i = cont ? i0 - 1 : i0;
+    int re = (i < a.n_rows) ? a.row_ptr[i + 1] : 0x7fffffff;
+
+    Vec<VEC> acc;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc.v[e] = 0.f;
+
+    auto finish_row = [&](bool complete) {
+#pragma unroll
+        for (int off = LPG; off < 64; off <<= 1) {
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc.v[e] += __shfl_xor(acc.v[e], off, 64);
+        }
+        if (g == 0 && fok) {
+            if (cont) {
+                acc.store(a.carry + (size_t)chunk * a.f_carry + f0);
+            } else {
+                if (complete) {
+                    float sc = 1.f;
+                    if (MODE == SENSEI_SPMM_SCALED) sc = a.r[i];
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) {
+                        float y = acc.v[e] * sc;
+                        if (a.act == SENSEI_ACT_RELU) y = y > 0.f ? y : 0.f;
+                        acc.v[e] = y;
+                    }
+                }
+                float *dst = a.C + (size_t)i * a.ldc + f0;
+                if (a.store_vec_ok && f0 + VEC <= a.f_store) {
+                    acc.store(dst);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) if (f0 + e < a.f_store) dst[e] = acc.v[e];
+                }
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc.v[e] = 0.f;
+    };
+
+    int pos = lo;
+    for (int base = lo; base < hi; base += 64) {
+        const int k = base + lane;
+        int col = 0;
+        float w = 0.f;
+        if (k < hi) {
+            col = a.col_idx[k];
+            if (MODE == SENSEI_SPMM_WEIGHTED) w = a.val[k];
+            if (MODE == SENSEI_SPMM_SCALED) w = a.c[col];
+        }
+        const int bhi = (base + 64 < hi) ? base + 64 : hi;
+        while (pos < bhi) {
+            while (re <= pos) {  // rows ending here (or empty): close them and move on
+                finish_row(true);
+                cont = false;
+                ++i;
+                re = a.row_ptr[i + 1];
+            }
+            const int seg_hi = re < bhi ? re : bhi;
+            const int u0 = pos - base, u1 = seg_hi - base;
+            const int n_it = (u1 - u0 + G - 1) / G;
+            int it = 0;
+            for (; it + 4 <= n_it; it += 4) {
+                Vec<VEC> b[4];
+                float ww[4];
+                bool ok[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int u = u0 + (it + q) * G + g;
+                    ok[q] = (u < u1) && fok;
+                    const int src = (u < u1) ? u : u0;
+                    const int j = __shfl(col, src, 64);
+                    ww[q] = (MODE == SENSEI_SPMM_PATTERN) ? 1.f : __shfl(w, src, 64);
+                    if (ok[q]) b[q] = Vec<VEC>::load(a.B + (size_t)j * a.ldb + f0);
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    if (ok[q]) {
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e) {
+                            if (MODE == SENSEI_SPMM_PATTERN) acc.v[e] += b[q].v[e];
+                            else acc.v[e] = fmaf(ww[q], b[q].v[e], acc.v[e]);
+                        }
+                    }
+                }
+            }
+            for (; it < n_it; ++it) {
+                const int u = u0 + it * G + g;
+                const bool ok = (u < u1) && fok;
+                const int src = (u < u1) ? u : u0;
+                const int j = __shfl(col, src, 64);
+                const float ww = (MODE == SENSEI_SPMM_PATTERN) ? 1.f : __shfl(w, src, 64);
+                if (ok) {
+                    Vec<VEC> b = Vec<VEC>::load(a.B + (size_t)j * a.ldb + f0);
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) {
+                        if (MODE == SENSEI_SPMM_PATTERN) acc.v[e] += b.v[e];
+                        else acc.v[e] = fmaf(ww, b.v[e], acc.v[e]);
+                    }
+                }
+            }
+            pos = seg_hi;
+        }
+    }
+    // close what is left: the current row if it ends in this chunk, then owned empty rows
+    while (i < i1) {
+        if (re <= hi) {
+            finish_row(true);
+            cont = false;
+            ++i;
+            re = (i < a.n_rows) ? a.row_ptr[i + 1] : 0x7fffffff;
+        } else {
+            finish_row(false);
+            break;
+        }
+    }
+}
+
+// Adds the carry slots of a row that spans several chunks to its output row, in chunk order,
+// then applies the row scale and the activation.  One wavefront per chunk; only the chunk that
+// holds the first continuation of a row does the work for that row.
+template <int MODE>
+__global__ __launch_bounds__(kBlock) void k_spmm_fixup(SpmmArgs a) {
+    const int c = 1 + blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+    if (c >= a.n_chunks) return;
+    const int lane = threadIdx.x & 63;
+    const long long lo = (long long)c * a.chunk_nnz;
+    const int i0 = a.chunk_row[c];
+    if ((long long)a.row_ptr[i0] <= lo) return;  // a row starts exactly at the boundary
+    const int i = i0 - 1;
+    const long long rs = a.row_ptr[i];
+    if (rs < lo - a.chunk_nnz) return;  // the row began before the previous chunk: not its first continuation
+    const int re = a.row_ptr[i + 1];
+    const int c_last = (re - 1) / a.chunk_nnz;
+    float sc = 1.f;
+    if (MODE == SENSEI_SPMM_SCALED) sc = a.r[i];
+    for (int f = lane; f < a.f_store; f += 64) {
+        float acc = a.C[(size_t)i * a.ldc + f];
+        for (int cc = c; cc <= c_last; ++cc) acc += a.carry[(size_t)cc * a.f_carry + f];
+        acc *= sc;
+        if (a.act == SENSEI_ACT_RELU) acc = acc > 0.f ? acc : 0.f;
+        a.C[(size_t)i * a.ldc + f] = acc;
+    }
+}
+
+template <int VEC, int LPG>
+hipError_t spmm_dispatch_mode(const SpmmArgs &a, int mode, dim3 grid, hipStream_t s) {
+    switch (mode) {
+        case SENSEI_SPMM_PATTERN: hipLaunchKernelGGL((k_spmm<VEC, LPG, SENSEI_SPMM_PATTERN>), grid, dim3(kBlock), 0, s, a); break;
+        case SENSEI_SPMM_WEIGHTED: hipLaunchKernelGGL((k_spmm<VEC, LPG, SENSEI_SPMM_WEIGHTED>), grid, dim3(kBlock), 0, s, a); break;
+        default: hipLaunchKernelGGL((k_spmm<VEC, LPG, SENSEI_SPMM_SCALED>), grid, dim3(kBlock), 0, s, a); break;
+    }
+    return hipGetLastError();
+}
+
+template <int VEC>
+hipError_t spmm_dispatch_lpg(const SpmmArgs &a, int mode, int lpg, dim3 grid, hipStream_t s) {
+    switch (lpg) {
+        case 8: return spmm_dispatch_mode<VEC, 8>(a, mode, grid, s);
+        case 16: return spmm_dispatch_mode<VEC, 16>(a, mode, grid, s);
+        case 32: return spmm_dispatch_mode<VEC, 32>(a, mode, grid, s);
+        default: return spmm_dispatch_mode<VEC, 64>(a, mode, grid, s);
+    }
+}
+
+// ------------------------------------------------------- element-wise / degrees
+
+__global__ void k_fill_i32(int32_t *p, long long n, int32_t v) {
+    long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < n) p[t] = v;
+}
+
+__global__ void k_deg_row(const int32_t *__restrict__ row_ptr, int n_rows, int32_t *__restrict__ deg_row) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n_rows) deg_row[i] = row_ptr[i + 1] - row_ptr[i];
+}
+
+__global__ void k_deg_col(const int32_t *__restrict__ col_idx, long long nnz, int32_t *__restrict__ deg_col) {
+    long long k = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k < nnz) atomicAdd(&deg_col[col_idx[k]], 1);  // integer atomics: the result is exact in any order
+}
+
+__global__ void k_norm_vec(const int32_t *__restrict__ deg, long long n, float *__restrict__ out) {
+    long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < n) {
+        int d = deg[t];
+        d = d < 1 ? 1 : d;
+        out[t] = __fdiv_rn(1.0f, __fsqrt_rn((float)d));
+    }
+}
+
+struct NnzArgs {
+    const int32_t *row_ptr, *col_idx, *chunk_row;
+    int n_rows, nnz, chunk_nnz, n_chunks;
+};
+
+__device__ __forceinline__ int row_of_nnz(const NnzArgs &a, int k) {
+    const int c = k / a.chunk_nnz;
+    const int i0 = a.chunk_row[c];
+    return find_row(a.row_ptr, i0 > 0 ? i0 - 1 : 0, a.chunk_row[c + 1], k);
+}
+
+__global__ void k_sddmm_norm(NnzArgs a, const float *__restrict__ r, const float *__restrict__ c, float *__restrict__ val) {
+    long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= a.nnz) return;
+    const int k = (int)t;
+    val[k] = r[row_of_nnz(a, k)] * c[a.col_idx[k]];
+}
+
+__device__ __forceinline__ float leaky(float t, float slope) { return t > 0.f ? t : slope * t; }
+
+__global__ void k_score(NnzArgs a, const float *__restrict__ s_l, const float *__restrict__ s_r, float slope, float *__restrict__ e) {
+    long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= a.nnz) return;
+    const int k = (int)t;
+    e[k] = leaky(s_l[row_of_nnz(a, k)] + s_r[a.col_idx[k]], slope);
+}
+
+template <int VEC>
+__global__ void k_row_broadcast(const float *__restrict__ s, const float *X, long long ldx, long long n, int f, float *Y,
+                                long long ldy, int act) {  // Y may be X (in place)
+    const int fv = f / VEC;
+    long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= n * fv) return;
+    const long long i = t / fv;
+    const int q = (int)(t % fv) * VEC;
+    const float sc = s ? s[i] : 1.f;
+    Vec<VEC> x = Vec<VEC>::load(X + i * ldx + q);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+        float y = x.v[e] * sc;
+        if (act == SENSEI_ACT_RELU) y = y > 0.f ? y : 0.f;
+        x.v[e] = y;
+    }
+    x.store(Y + i * ldy + q);
+}
+
+// ------------------------------------------------------------- edge softmax
+
+// (m, z) pairs: z = sum of exp(e - m).  Merge keeps m the larger maximum.
+__device__ __forceinline__ void mz_add(float &m, float &z, float e) {
+    if (e > m) { z = z * expf(m - e) + 1.f; m = e; }
+    else z += expf(e - m);
+}
+__device__ __forceinline__ void mz_merge(float &m, float &z, float m2, float z2) {
+    const float mm = m > m2 ? m : m2;
+    if (mm == -INFINITY) { m = mm; z = 0.f; return; }
+    z = z * expf(m - mm) + z2 * expf(m2 - mm);
+    m = mm;
+}
+
+struct SoftmaxArgs {
+    NnzArgs n;
+    const float *e, *s_l, *s_r;
+    float slope;
+    float2 *stats, *carry;
+    float *alpha;
+};
+
+// Row statistics with the same chunk ownership as SpMM: lanes stride over the non-zeros of the
+// current row piece, then a wavefront reduction closes the piece.
+template <bool FROM_E>
+__global__ __launch_bounds__(kBlock) void k_softmax_stats(SoftmaxArgs a) {
+    const int chunk = blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+    if (chunk >= a.n.n_chunks) return;
+    const int lane = threadIdx.x & 63;
+    const long long lo_ll = (long long)chunk * a.n.chunk_nnz;
+    const int lo = (int)lo_ll;
+    const int hi = (int)((lo_ll + a.n.chunk_nnz < (long long)a.n.nnz) ? lo_ll + a.n.chunk_nnz : (long long)a.n.nnz);
+    const int i0 = a.n.chunk_row[chunk], i1 = a.n.chunk_row[chunk + 1];
+    bool cont = (a.n.nnz > 0) && (a.n.row_ptr[i0] > lo);
+    int i = cont ? i0 - 1 : i0;
+    int re = (i < a.n.n_rows) ? a.n.row_ptr[i + 1] : 0x7fffffff;
+    float m = -INFINITY, z = 0.f;
+
+    auto finish_row = [&]() {
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const float m2 = __shfl_xor(m, off, 64), z2 = __shfl_xor(z, off, 64);
+            mz_merge(m, z, m2, z2);
+        }
+        if (lane == 0) {
+            if (cont) a.carry[chunk] = make_float2(m, z);
+            else a.stats[i] = make_float2(m, z);
+        }
+        m = -INFINITY; z = 0.f;
+    };
+
+    int pos = lo;
+    while (pos < hi) {
+        while (re <= pos) { finish_row(); cont = false; ++i; re = a.n.row_ptr[i + 1]; }
+        const int seg_hi = re < hi ? re : hi;
+        float sl = 0.f;
+        if (!FROM_E) sl = a.s_l[i];
+        for (int k = pos + lane; k < seg_hi; k += 64) {
+            const float e = FROM_E ? a.e[k] : leaky(sl + a.s_r[a.n.col_idx[k]], a.slope);
+            mz_add(m, z, e);
+        }
+        pos = seg_hi;
+    }
+    while (i < i1) {
+        finish_row();
+        if (re <= hi) { cont = false; ++i; re = (i < a.n.n_rows) ? a.n.row_ptr[i + 1] : 0x7fffffff; }
+        else break;
+    }
+}
+
+// merges the carried (m, z) pieces of rows that span several chunks, in chunk order
+__global__ void k_softmax_fixup(SoftmaxArgs a) {
+    const int c = 1 + blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= a.n.n_chunks) return;
+    const long long lo = (long long)c * a.n.chunk_nnz;
+    const int i0 = a.n.chunk_row[c];
+    if ((long long)a.n.row_ptr[i0] <= lo) return;
+    const int i = i0 - 1;
+    if ((long long)a.n.row_ptr[i] < lo - a.n.chunk_nnz) return;
+    const int c_last = (a.n.row_ptr[i + 1] - 1) / a.n.chunk_nnz;
+    float2 st = a.stats[i];
+    for (int cc = c; cc <= c_last; ++cc) {
+        const float2 p = a.carry[cc];
+        mz_merge(st.x, st.y, p.x, p.y);
+    }
+    a.stats[i] = st;
+}
+
+template <bool FROM_E>
+__global__ void k_softmax_alpha(SoftmaxArgs a) {
+    long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= a.n.nnz) return;
+    const int k = (int)t;
+    const int i = row_of_nnz(a.n, k);
+    const float e = FROM_E ? a.e[k] : leaky(a.s_l[i] + a.s_r[a.n.col_idx[k]], a.slope);
+    const float2 st = a.stats[i];
+    a.alpha[k] = __fdiv_rn(expf(e - st.x), st.y);
+}
+
+inline unsigned blocks_for(long long n, int per_block) { return (unsigned)((n + per_block - 1) / per_block); }
+
+NnzArgs nnz_args(const sensei_csr &A, const ChunkPlan &p) {
+    NnzArgs n;
+    n.row_ptr = A.row_ptr; n.col_idx = A.col_idx; n.chunk_row = p.chunk_row;
+    n.n_rows = A.n_rows; n.nnz = (int)A.nnz; n.chunk_nnz = p.chunk_nnz; n.n_chunks = p.n_chunks;
+    return n;
+}
+
+}  // namespace
+
+// ----------------------------------------------------------------- host side
+
+int choose_chunk_nnz(int64_t nnz, int) {
+    if (nnz >= (1LL << 24)) return 2048;
+    if (nnz >= (1LL << 21)) return 1024;
+    if (nnz >= (1LL << 18)) return 512;
+    return 256;
+}
+
+static int n_chunks_for(int64_t nnz, int t) { return nnz <= 0 ? 1 : (int)((nnz + t - 1) / t); }
+
+size_t plan_bytes(int64_t nnz) {
+    return align_up(((size_t)n_chunks_for(nnz, choose_chunk_nnz(nnz, 1)) + 1) * sizeof(int32_t), 256);
+}
+
+hipError_t launch_chunk_rows(const sensei_csr &A, const ChunkPlan &p, hipStream_t s) {
+    hipLaunchKernelGGL(k_chunk_rows, dim3(blocks_for(p.n_chunks + 1, kBlock)), dim3(kBlock), 0, s, A.row_ptr, A.n_rows,
+                       p.chunk_nnz, p.n_chunks, p.chunk_row);
+    return hipGetLastError();
+}
+
+SpmmShape spmm_shape(const float *B, int64_t ldb, int f) {
+    SpmmShape sh;
+    const uintptr_t addr = reinterpret_cast<uintptr_t>(B);
+    if (f % 4 == 0 && ldb % 4 == 0 && addr % 16 == 0) sh.vec = 4;
+    else if (f % 2 == 0 && ldb % 2 == 0 && addr % 8 == 0) sh.vec = 2;
+    else sh.vec = 1;
+    const int fv = (f + sh.vec - 1) / sh.vec;  // vector columns
+    // A neighbour group reads one 128-byte line per neighbour (32 floats); narrower rows use
+    // the smallest power-of-two group that covers them, very wide rows use wider groups so
+    // the number of feature tiles stays moderate.
+    int lpg = 32 / sh.vec;
+    while (lpg > 8 && lpg / 2 >= fv) lpg >>= 1;
+    while (lpg < 64 && (fv + lpg - 1) / lpg > 32) lpg <<= 1;
+    sh.lpg = lpg;
+    sh.n_tiles = (fv + lpg - 1) / lpg;
+    sh.f_carry = sh.n_tiles * lpg * sh.vec;
+    return sh;
+}
+
+size_t spmm_carry_bytes(int64_t nnz, int f) {
+    const int t = choose_chunk_nnz(nnz, 1);
+    // tiles are at most 256 floats wide, so the padded width stays below f + 256
+    const size_t f_carry = align_up((size_t)(f > 0 ? f : 1), 32) + 256;
+    return align_up((size_t)n_chunks_for(nnz, t) * f_carry * sizeof(float), 256);
+}
+
+hipError_t launch_spmm(const sensei_csr &A, int mode, const float *r, const float *c, const float *B, int64_t ldb,
+                       int f, float *C, int64_t ldc, int f_store, int act, const ChunkPlan &p, float *carry,
+                       hipStream_t s) {
+    const SpmmShape sh = spmm_shape(B, ldb, f);
+    SpmmArgs a;
+    a.row_ptr = A.row_ptr; a.col_idx = A.col_idx; a.chunk_row = p.chunk_row;
+    a.val = A.val; a.r = r; a.c = c; a.B = B; a.C = C; a.carry = carry;
+    a.ldb = ldb; a.ldc = ldc;
+    a.n_rows = A.n_rows; a.nnz = (int)A.nnz; a.chunk_nnz = p.chunk_nnz; a.n_chunks = p.n_chunks;
+    a.f = f; a.f_store = f_store; a.f_carry = sh.f_carry; a.n_tiles = sh.n_tiles; a.act = act;
+    a.store_vec_ok = (ldc % sh.vec == 0) && (reinterpret_cast<uintptr_t>(C) % (4 * sh.vec) == 0);
+    const unsigned groups = blocks_for(p.n_chunks, kWavesPerBlock);
+    dim3 grid(groups * (unsigned)sh.n_tiles);
+    hipError_t err;
+    switch (sh.vec) {
+        case 4: err = spmm_dispatch_lpg<4>(a, mode, sh.lpg, grid, s); break;
+        case 2: err = spmm_dispatch_lpg<2>(a, mode, sh.lpg, grid, s); break;
+        default: err = spmm_dispatch_lpg<1>(a, mode, sh.lpg, grid, s); break;
+    }
+    if (err != hipSuccess) return err;
+    if (p.n_chunks > 1) {
+        dim3 fg(blocks_for(p.n_chunks - 1, kWavesPerBlock));
+        if (mode == SENSEI_SPMM_SCALED) hipLaunchKernelGGL((k_spmm_fixup<SENSEI_SPMM_SCALED>), fg, dim3(kBlock), 0, s, a);
+        else hipLaunchKernelGGL((k_spmm_fixup<SENSEI_SPMM_PATTERN>), fg, dim3(kBlock), 0, s, a);
+        err = hipGetLastError();
+    }
+    return err;
+}
+
+hipError_t launch_degrees(const sensei_csr &A, int32_t *deg_row, int32_t *deg_col, hipStream_t s) {
+    if (A.n_rows > 0) hipLaunchKernelGGL(k_deg_row, dim3(blocks_for(A.n_rows, kBlock)), dim3(kBlock), 0, s, A.row_ptr, A.n_rows, deg_row);
+    if (A.n_cols > 0) hipLaunchKernelGGL(k_fill_i32, dim3(blocks_for(A.n_cols, kBlock)), dim3(kBlock), 0, s, deg_col, (long long)A.n_cols, 0);
+    if (A.nnz > 0) hipLaunchKernelGGL(k_deg_col, dim3(blocks_for(A.nnz, kBlock)), dim3(kBlock), 0, s, A.col_idx, (long long)A.nnz, deg_col);
+    return hipGetLastError();
+}
+
+hipError_t launch_norm_vectors(const int32_t *deg, int64_t n, float *out, hipStream_t s) {
+    if (n > 0) hipLaunchKernelGGL(k_norm_vec, dim3(blocks_for(n, kBlock)), dim3(kBlock), 0, s, deg, (long long)n, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_sddmm_norm(const sensei_csr &A, const float *r, const float *c, float *val, const ChunkPlan &p, hipStream_t s) {
+    if (A.nnz > 0) hipLaunchKernelGGL(k_sddmm_norm, dim3(blocks_for(A.nnz, kBlock)), dim3(kBlock), 0, s, nnz_args(A, p), r, c, val);
+    return hipGetLastError();
+}
+
+hipError_t launch_score(const sensei_csr &A, const float *s_l, const float *s_r, float slope, float *e, const ChunkPlan &p, hipStream_t s) {
+    if (A.nnz > 0) hipLaunchKernelGGL(k_score, dim3(blocks_for(A.nnz, kBlock)), dim3(kBlock), 0, s, nnz_args(A, p), s_l, s_r, slope, e);
+    return hipGetLastError();
+}
+
+hipError_t launch_row_broadcast(const float *s_vec, const float *X, int64_t ldx, int64_t n, int f, float *Y, int64_t ldy, int act, hipStream_t s) {
+    if (n <= 0 || f <= 0) return hipSuccess;
+    const bool a16 = reinterpret_cast<uintptr_t>(X) % 16 == 0 && reinterpret_cast<uintptr_t>(Y) % 16 == 0;
+    if (f % 4 == 0 && ldx % 4 == 0 && ldy % 4 == 0 && a16)
+        hipLaunchKernelGGL((k_row_broadcast<4>), dim3(blocks_for(n * (f / 4), kBlock)), dim3(kBlock), 0, s, s_vec, X, (long long)ldx, (long long)n, f, Y, (long long)ldy, act);
+    else
+        hipLaunchKernelGGL((k_row_broadcast<1>), dim3(blocks_for(n * f, kBlock)), dim3(kBlock), 0, s, s_vec, X, (long long)ldx, (long long)n, f, Y, (long long)ldy, act);
+    return hipGetLastError();
+}
+
+size_t softmax_ws_bytes(const sensei_csr &A) {
+    const int t = choose_chunk_nnz(A.nnz, 1);
+    return align_up((size_t)(A.n_rows + 1) * sizeof(float2), 256) + align_up((size_t)n_chunks_for(A.nnz, t) * sizeof(float2), 256);
+}
+
+hipError_t launch_softmax(const sensei_csr &A, const float *e, const float *s_l, const float *s_r, float slope, float *alpha,
+                          const ChunkPlan &p, float2 *stats, float2 *carry_stats, hipStream_t s) {
+    SoftmaxArgs a;
+    a.n = nnz_args(A, p);
+    a.e = e; a.s_l = s_l; a.s_r = s_r; a.slope = slope; a.stats = stats; a.carry = carry_stats; a.alpha = alpha;
+    dim3 g1(blocks_for(p.n_chunks, kWavesPerBlock));
+    if (e) hipLaunchKernelGGL((k_softmax_stats<true>), g1, dim3(kBlock), 0, s, a);
+    else hipLaunchKernelGGL((k_softmax_stats<false>), g1, dim3(kBlock), 0, s, a);
+    if (p.n_chunks > 1) hipLaunchKernelGGL(k_softmax_fixup, dim3(blocks_for(p.n_chunks - 1, kBlock)), dim3(kBlock), 0, s, a);
+    if (A.nnz > 0) {
+        dim3 g3(blocks_for(A.nnz, kBlock));
+        if (e) hipLaunchKernelGGL((k_softmax_alpha<true>), g3, dim3(kBlock), 0, s, a);
+        else hipLaunchKernelGGL((k_softmax_alpha<false>), g3, dim3(kBlock), 0, s, a);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace sensei
