@@ -27,7 +27,7 @@ EXPORTS = (
     "sensei_status_string", "sensei_degrees", "sensei_norm_vectors", "sensei_sparse_workspace", "sensei_gcn_precompute",
     "sensei_row_broadcast", "sensei_spmm", "sensei_gemm", "sensei_gemv2", "sensei_sddmm_score", "sensei_edge_softmax",
     "sensei_gcn_workspace", "sensei_gcn_layer", "sensei_gat_workspace", "sensei_gat_layer", "sensei_select_workspace",
-    "sensei_select",
+    "sensei_select", "sensei_profile_enable", "sensei_profile_read",
 )
 
 
@@ -82,6 +82,8 @@ def lib():
         L.sensei_gat_layer.argtypes = [vp, P(CsrStruct), MatStruct, MatStruct, vp, vp, f32, vp, i64, i32, i32, vp, sz, vp]
         L.sensei_select_workspace.argtypes = [i32, P(CsrStruct), i32, i32, P(sz)]
         L.sensei_select.argtypes = [vp, i32, P(CsrStruct), i32, i32, i32, P(ctypes.c_int), P(f32), vp, sz, vp]
+        L.sensei_profile_enable.argtypes = [vp, i32]
+        L.sensei_profile_read.argtypes = [vp, P(f32), i32, P(ctypes.c_int)]
         for name in EXPORTS:
             if name not in ("sensei_composition_name", "sensei_status_string"):
                 getattr(L, name).restype = ctypes.c_int
@@ -268,6 +270,17 @@ class Context:
         _check(lib().sensei_select(self._h, kind, ctypes.byref(A), f_in, f_out, mode, ctypes.byref(cid), est, ws_ptr, ws_bytes,
                                    _stream()), "sensei_select")
         return cid.value, [float(x) for x in est]
+
+    def profile_enable(self, enable: bool):
+        _check(lib().sensei_profile_enable(self._h, int(enable)), "sensei_profile_enable")
+
+    def profile_read(self):
+        """Elapsed ms of every SpMM kernel launch recorded since profile_enable(True), in launch order."""
+        n = ctypes.c_int(0)
+        _check(lib().sensei_profile_read(self._h, None, 0, ctypes.byref(n)), "sensei_profile_read")
+        buf = (ctypes.c_float * max(n.value, 1))()
+        _check(lib().sensei_profile_read(self._h, buf, n.value, ctypes.byref(n)), "sensei_profile_read")
+        return [float(buf[i]) for i in range(n.value)]
 
     def calibrate(self):
         self.ws.ensure(64 << 20)

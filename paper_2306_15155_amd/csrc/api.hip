@@ -17,6 +17,7 @@ struct sensei_ctx {
     double gather_far_bps; // row-gather bandwidth when it does not (Infinity Cache / HBM)
     double gemm_flops;     // achieved fp32 MFMA rate on large tiles
     double l2_slice_bytes; // footprint of one feature-tile slice that still counts as L2 resident
+    KernelTimer timer;     // optional per-launch timing of the SpMM kernel
 };
 
 namespace {
@@ -112,7 +113,7 @@ size_t gat_ws(const sensei_csr &A, int f_in, int f_out, int id) {
     } while (0)
 
 int run_gcn(const sensei_csr &A, const float *r, const float *c, const sensei_mat &X, const sensei_mat &W, float *Y,
-            int64_t ldy, int act, int id, void *ws, size_t ws_bytes, hipStream_t s) {
+            int64_t ldy, int act, int id, void *ws, size_t ws_bytes, hipStream_t s, KernelTimer *kt) {
     const int f_in = (int)X.cols, f_out = (int)W.cols;
     Carver cv(ws, ws_bytes);
     ChunkPlan plan = make_plan(A, cv);
@@ -132,7 +133,7 @@ int run_gcn(const sensei_csr &A, const float *r, const float *c, const sensei_ma
             src = T;
             ld_src = fs;
         }
-        SENSEI_TRY(launch_spmm(A, mode, r, c, src, ld_src, f_in, U, fs, f_in, SENSEI_ACT_NONE, plan, carry, s));
+        SENSEI_TRY(launch_spmm(A, mode, r, c, src, ld_src, f_in, U, fs, f_in, SENSEI_ACT_NONE, plan, carry, s, kt));
         if (id == SENSEI_GCN_DYN_AGG) SENSEI_TRY(launch_row_broadcast(r, U, fs, A.n_rows, f_in, U, fs, SENSEI_ACT_NONE, s));
         SENSEI_TRY(launch_gemm(U, fs, W.ptr, W.ld, Y, ldy, A.n_rows, f_in, f_out, f_out, act, s));
     } else {
@@ -142,17 +143,17 @@ int run_gcn(const sensei_csr &A, const float *r, const float *c, const sensei_ma
         SENSEI_TRY(launch_gemm(X.ptr, X.ld, W.ptr, W.ld, Z, fs, A.n_cols, f_in, f_out, fs, SENSEI_ACT_NONE, s));
         if (id == SENSEI_GCN_DYN_UPD) {
             SENSEI_TRY(launch_row_broadcast(c, Z, fs, A.n_cols, fs, Z, fs, SENSEI_ACT_NONE, s));
-            SENSEI_TRY(launch_spmm(A, mode, r, c, Z, fs, fs, Y, ldy, f_out, SENSEI_ACT_NONE, plan, carry, s));
+            SENSEI_TRY(launch_spmm(A, mode, r, c, Z, fs, fs, Y, ldy, f_out, SENSEI_ACT_NONE, plan, carry, s, kt));
             SENSEI_TRY(launch_row_broadcast(r, Y, ldy, A.n_rows, f_out, Y, ldy, act, s));
         } else {
-            SENSEI_TRY(launch_spmm(A, mode, r, c, Z, fs, fs, Y, ldy, f_out, act, plan, carry, s));
+            SENSEI_TRY(launch_spmm(A, mode, r, c, Z, fs, fs, Y, ldy, f_out, act, plan, carry, s, kt));
         }
     }
     return SENSEI_OK;
 }
 
 int run_gat(const sensei_csr &A, const sensei_mat &X, const sensei_mat &W, const float *a_l, const float *a_r,
-            float slope, float *Y, int64_t ldy, int act, int id, void *ws, size_t ws_bytes, hipStream_t s) {
+            float slope, float *Y, int64_t ldy, int act, int id, void *ws, size_t ws_bytes, hipStream_t s, KernelTimer *kt) {
     const int f_in = (int)X.cols, f_out = (int)W.cols;
     const int fo = pad4(f_out), fi = pad4(f_in);
     Carver cv(ws, ws_bytes);
@@ -182,11 +183,11 @@ int run_gat(const sensei_csr &A, const sensei_mat &X, const sensei_mat &W, const
     if (gat_is_reuse(id)) {
         if (fold) SENSEI_TRY(launch_gemm(X.ptr, X.ld, W.ptr, W.ld, theta, fo, A.n_cols, f_in, f_out, fo, SENSEI_ACT_NONE, s));
         float *carry = cv.take<float>(spmm_carry_bytes(A.nnz, fo) / sizeof(float));
-        SENSEI_TRY(launch_spmm(Aw, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, theta, fo, fo, Y, ldy, f_out, act, plan, carry, s));
+        SENSEI_TRY(launch_spmm(Aw, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, theta, fo, fo, Y, ldy, f_out, act, plan, carry, s, kt));
     } else {
         float *carry = cv.take<float>(spmm_carry_bytes(A.nnz, fi) / sizeof(float));
         float *U = cv.take<float>((size_t)A.n_rows * fi);
-        SENSEI_TRY(launch_spmm(Aw, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, X.ptr, X.ld, f_in, U, fi, f_in, SENSEI_ACT_NONE, plan, carry, s));
+        SENSEI_TRY(launch_spmm(Aw, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, X.ptr, X.ld, f_in, U, fi, f_in, SENSEI_ACT_NONE, plan, carry, s, kt));
         SENSEI_TRY(launch_gemm(U, fi, W.ptr, W.ld, Y, ldy, A.n_rows, f_in, f_out, f_out, act, s));
     }
     return SENSEI_OK;
@@ -316,7 +317,26 @@ int sensei_create(sensei_ctx **out, int device) {
 }
 
 int sensei_destroy(sensei_ctx *ctx) {
+    if (ctx) for (hipEvent_t e : ctx->timer.events) (void)hipEventDestroy(e);
     delete ctx;
+    return SENSEI_OK;
+}
+
+int sensei_profile_enable(sensei_ctx *ctx, int enable) {
+    if (!ctx) return SENSEI_INVALID_ARGUMENT;
+    ctx->timer.enabled = enable != 0;
+    if (enable) ctx->timer.used = 0;
+    return SENSEI_OK;
+}
+
+int sensei_profile_read(sensei_ctx *ctx, float *ms_out, int capacity, int *count_out) {
+    if (!ctx || !count_out || capacity < 0 || (capacity > 0 && !ms_out)) return SENSEI_INVALID_ARGUMENT;
+    const size_t pairs = ctx->timer.used / 2;
+    *count_out = (int)pairs;
+    for (size_t p = 0; p < pairs && p < (size_t)capacity; ++p) {
+        if (hipEventSynchronize(ctx->timer.events[2 * p + 1]) != hipSuccess) return SENSEI_HIP_ERROR;
+        if (hipEventElapsedTime(&ms_out[p], ctx->timer.events[2 * p], ctx->timer.events[2 * p + 1]) != hipSuccess) return SENSEI_HIP_ERROR;
+    }
     return SENSEI_OK;
 }
 
@@ -396,7 +416,7 @@ int sensei_spmm(sensei_ctx *ctx, const sensei_csr *A, int mode, const float *r, 
     ChunkPlan plan = make_plan(*A, cv);
     float *carry = cv.take<float>(spmm_carry_bytes(A->nnz, f) / sizeof(float));
     SENSEI_TRY(launch_chunk_rows(*A, plan, as_stream(stream)));
-    return hip_status(launch_spmm(*A, mode, r, c, B.ptr, B.ld, f, C, ldc, f, activation, plan, carry, as_stream(stream)));
+    return hip_status(launch_spmm(*A, mode, r, c, B.ptr, B.ld, f, C, ldc, f, activation, plan, carry, as_stream(stream), &ctx->timer));
 }
 
 int sensei_gemm(sensei_ctx *ctx, sensei_mat A, sensei_mat W, float *Y, int64_t ldy, int activation, void *stream) {
@@ -467,7 +487,7 @@ int sensei_gcn_layer(sensei_ctx *ctx, const sensei_csr *A, const float *r, const
         return SENSEI_INVALID_ARGUMENT;
     if (ws_bytes < gcn_ws(*A, (int)X.cols, (int)W.cols, comp_id)) return SENSEI_WORKSPACE_TOO_SMALL;
     if (A->n_rows == 0) return SENSEI_OK;
-    return run_gcn(*A, r, c, X, W, Y, ldy, activation, comp_id, workspace, ws_bytes, as_stream(stream));
+    return run_gcn(*A, r, c, X, W, Y, ldy, activation, comp_id, workspace, ws_bytes, as_stream(stream), &ctx->timer);
 }
 
 int sensei_gat_workspace(const sensei_csr *A, int f_in, int f_out, int comp_id, size_t *bytes) {
@@ -494,7 +514,7 @@ int sensei_gat_layer(sensei_ctx *ctx, const sensei_csr *A, sensei_mat X, sensei_
         return SENSEI_INVALID_ARGUMENT;
     if (ws_bytes < gat_ws(*A, (int)X.cols, (int)W.cols, comp_id)) return SENSEI_WORKSPACE_TOO_SMALL;
     if (A->n_rows == 0) return SENSEI_OK;
-    return run_gat(*A, X, W, a_l, a_r, neg_slope, Y, ldy, activation, comp_id, workspace, ws_bytes, as_stream(stream));
+    return run_gat(*A, X, W, a_l, a_r, neg_slope, Y, ldy, activation, comp_id, workspace, ws_bytes, as_stream(stream), &ctx->timer);
 }
 
 int sensei_select_workspace(int kind, const sensei_csr *A, int f_in, int f_out, size_t *bytes) {
@@ -562,8 +582,8 @@ int sensei_select(sensei_ctx *ctx, int kind, const sensei_csr *A, int f_in, int 
                 if (rep == 1 && hipEventRecord(e0, s) != hipSuccess) status = SENSEI_HIP_ERROR;
                 if (status == SENSEI_OK)
                     status = kind == SENSEI_KIND_GCN
-                                 ? run_gcn(Aw, r, c, Xm, Wm, Y, f_out, SENSEI_ACT_RELU, id, lws, lws_bytes, s)
-                                 : run_gat(*A, Xm, Wm, a_l, a_r, 0.2f, Y, f_out, SENSEI_ACT_RELU, id, lws, lws_bytes, s);
+                                 ? run_gcn(Aw, r, c, Xm, Wm, Y, f_out, SENSEI_ACT_RELU, id, lws, lws_bytes, s, nullptr)
+                                 : run_gat(*A, Xm, Wm, a_l, a_r, 0.2f, Y, f_out, SENSEI_ACT_RELU, id, lws, lws_bytes, s, nullptr);
             }
             if (status != SENSEI_OK) break;
             float ms = 0.f;

@@ -7,6 +7,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "sensei.h"
 
 namespace sensei {
@@ -23,6 +25,23 @@ int choose_chunk_nnz(int64_t nnz, int n_feature_tiles);
 size_t plan_bytes(int64_t nnz);  // upper bound over all chunk sizes
 hipError_t launch_chunk_rows(const sensei_csr &A, const ChunkPlan &p, hipStream_t s);
 
+// ---- optional timing of the SpMM kernel with HIP events on the launch stream
+struct KernelTimer {
+    bool enabled = false;
+    size_t used = 0;                 // events handed out since the recording started
+    std::vector<hipEvent_t> events;  // start/stop pairs, created on first use, reused afterwards
+    static constexpr size_t kMaxEvents = 8192;
+    hipEvent_t next() {
+        if (!enabled || used >= kMaxEvents) return nullptr;
+        if (used == events.size()) {
+            hipEvent_t e;
+            if (hipEventCreate(&e) != hipSuccess) return nullptr;
+            events.push_back(e);
+        }
+        return events[used++];
+    }
+};
+
 // ---- SpMM
 
 struct SpmmShape {
@@ -36,7 +55,7 @@ size_t spmm_carry_bytes(int64_t nnz, int f);  // upper bound
 // C[i, 0:f_store) = act(scale_i * sum_j w_ij B[j, 0:f)); f_store <= f; r/c only for SCALED.
 hipError_t launch_spmm(const sensei_csr &A, int mode, const float *r, const float *c, const float *B, int64_t ldb,
                        int f, float *C, int64_t ldc, int f_store, int act, const ChunkPlan &p, float *carry,
-                       hipStream_t s);
+                       hipStream_t s, KernelTimer *timer = nullptr);
 
 // ---- element-wise work over the non-zeros, degrees, scalings
 hipError_t launch_degrees(const sensei_csr &A, int32_t *deg_row, int32_t *deg_col, hipStream_t s);

@@ -10,6 +10,8 @@
 // fix-up kernel adds the carry slots to the row in chunk order.  No float
 // atomics: the summation order is fixed, results are reproducible, and a hub
 // row of a power-law graph is spread over as many wavefronts as it needs.
+#include <cstdlib>
+
 #include "sensei_internal.h"
 
 namespace sensei {
@@ -70,7 +72,7 @@ struct SpmmArgs {
     float *C, *carry;
     long long ldb, ldc;
     int n_rows, nnz, chunk_nnz, n_chunks;
-    int f, f_store, f_carry, n_tiles, act, store_vec_ok;
+    int f, f_store, f_carry, n_tiles, act, store_vec_ok, tile_blocked, n_groups;
 };
 
 // One wavefront = one (chunk, feature tile).  The 64 lanes form G = 64/LPG
@@ -86,8 +88,8 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
     constexpr int G = 64 / LPG;
     constexpr int TF = VEC * LPG;
     const int lane = threadIdx.x & 63;
-    const int tile = blockIdx.x % a.n_tiles;
-    const int chunk = (blockIdx.x / a.n_tiles) * kWavesPerBlock + (threadIdx.x >> 6);
+    const int tile = a.tile_blocked ? blockIdx.x / a.n_groups : blockIdx.x % a.n_tiles;
+    const int chunk = (a.tile_blocked ? blockIdx.x % a.n_groups : blockIdx.x / a.n_tiles) * kWavesPerBlock + (threadIdx.x >> 6);
     if (chunk >= a.n_chunks) return;
     const int g = lane / LPG;
     const int f0 = tile * TF + (lane % LPG) * VEC;
@@ -288,7 +290,7 @@ __global__ void k_norm_vec(const int32_t *__restrict__ deg, long long n, float *
     if (t < n) {
         int d = deg[t];
         d = d < 1 ? 1 : d;
-        out[t] = __fdiv_rn(1.0f, __fsqrt_rn((float)d));
+        out[t] = 1.0f / sqrtf((float)d);  // IEEE sqrt and divide (hipcc's default), no rsq approximation
     }
 }
 
@@ -434,7 +436,7 @@ __global__ void k_softmax_alpha(SoftmaxArgs a) {
     const int i = row_of_nnz(a.n, k);
     const float e = FROM_E ? a.e[k] : leaky(a.s_l[i] + a.s_r[a.n.col_idx[k]], a.slope);
     const float2 st = a.stats[i];
-    a.alpha[k] = __fdiv_rn(expf(e - st.x), st.y);
+    a.alpha[k] = expf(e - st.x) / st.y;
 }
 
 inline unsigned blocks_for(long long n, int per_block) { return (unsigned)((n + per_block - 1) / per_block); }
@@ -451,6 +453,8 @@ NnzArgs nnz_args(const sensei_csr &A, const ChunkPlan &p) {
 // ----------------------------------------------------------------- host side
 
 int choose_chunk_nnz(int64_t nnz, int) {
+    static const int dbg = getenv("SENSEI_DBG_CHUNK") ? atoi(getenv("SENSEI_DBG_CHUNK")) : 0;
+    if (dbg >= 64) return dbg;
     if (nnz >= (1LL << 24)) return 2048;
     if (nnz >= (1LL << 21)) return 1024;
     if (nnz >= (1LL << 18)) return 512;
@@ -482,6 +486,8 @@ SpmmShape spmm_shape(const float *B, int64_t ldb, int f) {
     int lpg = 32 / sh.vec;
     while (lpg > 8 && lpg / 2 >= fv) lpg >>= 1;
     while (lpg < 64 && (fv + lpg - 1) / lpg > 32) lpg <<= 1;
+    static const int dbg_lpg = getenv("SENSEI_DBG_LPG") ? atoi(getenv("SENSEI_DBG_LPG")) : 0;
+    if (dbg_lpg >= 8) lpg = dbg_lpg;
     sh.lpg = lpg;
     sh.n_tiles = (fv + lpg - 1) / lpg;
     sh.f_carry = sh.n_tiles * lpg * sh.vec;
@@ -497,7 +503,7 @@ size_t spmm_carry_bytes(int64_t nnz, int f) {
 
 hipError_t launch_spmm(const sensei_csr &A, int mode, const float *r, const float *c, const float *B, int64_t ldb,
                        int f, float *C, int64_t ldc, int f_store, int act, const ChunkPlan &p, float *carry,
-                       hipStream_t s) {
+                       hipStream_t s, KernelTimer *timer) {
     const SpmmShape sh = spmm_shape(B, ldb, f);
     SpmmArgs a;
     a.row_ptr = A.row_ptr; a.col_idx = A.col_idx; a.chunk_row = p.chunk_row;
@@ -508,13 +514,19 @@ hipError_t launch_spmm(const sensei_csr &A, int mode, const float *r, const floa
     a.store_vec_ok = (ldc % sh.vec == 0) && (reinterpret_cast<uintptr_t>(C) % (4 * sh.vec) == 0);
     const unsigned groups = blocks_for(p.n_chunks, kWavesPerBlock);
     dim3 grid(groups * (unsigned)sh.n_tiles);
+    static const int dbg_blocked = getenv("SENSEI_DBG_TILE_BLOCKED") ? atoi(getenv("SENSEI_DBG_TILE_BLOCKED")) : 0;
+    a.tile_blocked = dbg_blocked;
+    a.n_groups = (int)groups;
     hipError_t err;
+    hipEvent_t t0 = timer ? timer->next() : nullptr, t1 = t0 ? timer->next() : nullptr;
+    if (t1 && hipEventRecord(t0, s) != hipSuccess) return hipErrorUnknown;
     switch (sh.vec) {
         case 4: err = spmm_dispatch_lpg<4>(a, mode, sh.lpg, grid, s); break;
         case 2: err = spmm_dispatch_lpg<2>(a, mode, sh.lpg, grid, s); break;
         default: err = spmm_dispatch_lpg<1>(a, mode, sh.lpg, grid, s); break;
     }
     if (err != hipSuccess) return err;
+    if (t1 && hipEventRecord(t1, s) != hipSuccess) return hipErrorUnknown;
     if (p.n_chunks > 1) {
         dim3 fg(blocks_for(p.n_chunks - 1, kWavesPerBlock));
         if (mode == SENSEI_SPMM_SCALED) hipLaunchKernelGGL((k_spmm_fixup<SENSEI_SPMM_SCALED>), fg, dim3(kBlock), 0, s, a);

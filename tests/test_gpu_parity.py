@@ -227,7 +227,7 @@ def test_mid_size_graph_with_larger_chunks(ctx):
 
 
 def test_large_graph_with_2048_entry_chunks(ctx):
-    g = synth.rmat(12, 120_000, 11_000_000)
+    g = synth.rmat(12, 120_000, 12_000_000)
     assert g.nnz >= (1 << 24)
     X = synth.uniform(8, 10, (g.n_cols, 32))
     W = synth.glorot(8, 11, 32, 16)
