@@ -133,20 +133,26 @@ int run_gcn(const sensei_csr &A, const float *r, const float *c, const sensei_ma
             src = T;
             ld_src = fs;
         }
-        SENSEI_TRY(launch_spmm(A, mode, r, c, src, ld_src, f_in, U, fs, f_in, SENSEI_ACT_NONE, plan, carry, s, kt));
+        const bool scaled = (mode == SENSEI_SPMM_SCALED);
+        SENSEI_TRY(launch_spmm(A, mode, scaled ? r : nullptr, scaled ? c : nullptr, src, ld_src, f_in, U, fs, f_in, SENSEI_ACT_NONE, plan, carry, s, kt));
         if (id == SENSEI_GCN_DYN_AGG) SENSEI_TRY(launch_row_broadcast(r, U, fs, A.n_rows, f_in, U, fs, SENSEI_ACT_NONE, s));
         SENSEI_TRY(launch_gemm(U, fs, W.ptr, W.ld, Y, ldy, A.n_rows, f_in, f_out, f_out, act, s));
     } else {
         const int fs = pad4(f_out);
         float *carry = cv.take<float>(spmm_carry_bytes(A.nnz, fs) / sizeof(float));
         float *Z = cv.take<float>((size_t)A.n_cols * fs);
-        SENSEI_TRY(launch_gemm(X.ptr, X.ld, W.ptr, W.ld, Z, fs, A.n_cols, f_in, f_out, fs, SENSEI_ACT_NONE, s));
+        // DYNF_UPD: the column scaling is a row broadcast on Z = X.W, fused into the GEMM epilogue; the row
+        // scaling and the activation are fused into the SpMM epilogue, so the SpMM itself is value-less.
+        const float *z_scale = (id == SENSEI_GCN_DYNF_UPD) ? c : nullptr;
+        SENSEI_TRY(launch_gemm(X.ptr, X.ld, W.ptr, W.ld, Z, fs, A.n_cols, f_in, f_out, fs, SENSEI_ACT_NONE, s, z_scale));
         if (id == SENSEI_GCN_DYN_UPD) {
             SENSEI_TRY(launch_row_broadcast(c, Z, fs, A.n_cols, fs, Z, fs, SENSEI_ACT_NONE, s));
-            SENSEI_TRY(launch_spmm(A, mode, r, c, Z, fs, fs, Y, ldy, f_out, SENSEI_ACT_NONE, plan, carry, s, kt));
+            SENSEI_TRY(launch_spmm(A, mode, nullptr, nullptr, Z, fs, fs, Y, ldy, f_out, SENSEI_ACT_NONE, plan, carry, s, kt));
             SENSEI_TRY(launch_row_broadcast(r, Y, ldy, A.n_rows, f_out, Y, ldy, act, s));
+        } else if (id == SENSEI_GCN_DYNF_UPD) {
+            SENSEI_TRY(launch_spmm(A, SENSEI_SPMM_PATTERN, r, nullptr, Z, fs, fs, Y, ldy, f_out, act, plan, carry, s, kt));
         } else {
-            SENSEI_TRY(launch_spmm(A, mode, r, c, Z, fs, fs, Y, ldy, f_out, act, plan, carry, s, kt));
+            SENSEI_TRY(launch_spmm(A, mode, nullptr, nullptr, Z, fs, fs, Y, ldy, f_out, act, plan, carry, s, kt));
         }
     }
     return SENSEI_OK;
@@ -416,7 +422,9 @@ int sensei_spmm(sensei_ctx *ctx, const sensei_csr *A, int mode, const float *r, 
     ChunkPlan plan = make_plan(*A, cv);
     float *carry = cv.take<float>(spmm_carry_bytes(A->nnz, f) / sizeof(float));
     SENSEI_TRY(launch_chunk_rows(*A, plan, as_stream(stream)));
-    return hip_status(launch_spmm(*A, mode, r, c, B.ptr, B.ld, f, C, ldc, f, activation, plan, carry, as_stream(stream), &ctx->timer));
+    const bool scaled = (mode == SENSEI_SPMM_SCALED);
+    return hip_status(launch_spmm(*A, mode, scaled ? r : nullptr, scaled ? c : nullptr, B.ptr, B.ld, f, C, ldc, f, activation, plan, carry,
+                                  as_stream(stream), &ctx->timer));
 }
 
 int sensei_gemm(sensei_ctx *ctx, sensei_mat A, sensei_mat W, float *Y, int64_t ldy, int activation, void *stream) {

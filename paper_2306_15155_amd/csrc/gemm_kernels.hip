@@ -13,7 +13,7 @@ constexpr int kThreads = 256;
 constexpr int KT = 16;  // k extent of one LDS tile
 
 struct GemmArgs {
-    const float *A, *W;
+    const float *A, *W, *row_scale;  // row_scale: optional per-row factor applied before the activation
     float *Y;
     long long lda, ldw, ldy, n;
     int k, m, m_store, act, n_bn;
@@ -137,6 +137,7 @@ __global__ __launch_bounds__(kThreads) void k_gemm(GemmArgs g) {
                 const long long row = m0 + (wm * TM + i) * 32 + 8 * (r / 4) + 4 * kh + (r % 4);
                 if (row < g.n) {
                     float y = acc[i][j][r];
+                    if (g.row_scale) y *= g.row_scale[row];
                     if (g.act == SENSEI_ACT_RELU) y = y > 0.f ? y : 0.f;
                     g.Y[row * g.ldy + col] = y;
                 }
@@ -191,9 +192,10 @@ __global__ __launch_bounds__(kThreads) void k_gemv2(const float *__restrict__ A,
 }  // namespace
 
 hipError_t launch_gemm(const float *A, int64_t lda, const float *W, int64_t ldw, float *Y, int64_t ldy, int64_t n,
-                       int k, int m, int m_store, int act, hipStream_t s) {
+                       int k, int m, int m_store, int act, hipStream_t s, const float *row_scale) {
     if (n <= 0 || m_store <= 0) return hipSuccess;
     GemmArgs g;
+    g.row_scale = row_scale;
     g.A = A; g.W = W; g.Y = Y; g.lda = lda; g.ldw = ldw; g.ldy = ldy; g.n = n;
     g.k = k; g.m = m; g.m_store = m_store; g.act = act;
     int avec = 1, bvec = 1;

@@ -52,7 +52,8 @@ struct SpmmShape {
 };
 SpmmShape spmm_shape(const float *B, int64_t ldb, int f);
 size_t spmm_carry_bytes(int64_t nnz, int f);  // upper bound
-// C[i, 0:f_store) = act(scale_i * sum_j w_ij B[j, 0:f)); f_store <= f; r/c only for SCALED.
+// C[i, 0:f_store) = act(r_i * sum_j w_ij B[j, 0:f)); f_store <= f.  w_ij = 1 (PATTERN), val (WEIGHTED) or
+// c_j (SCALED); the row factor r is applied whenever r is non-null, in every mode.
 hipError_t launch_spmm(const sensei_csr &A, int mode, const float *r, const float *c, const float *B, int64_t ldb,
                        int f, float *C, int64_t ldc, int f_store, int act, const ChunkPlan &p, float *carry,
                        hipStream_t s, KernelTimer *timer = nullptr);
@@ -74,9 +75,10 @@ hipError_t launch_softmax(const sensei_csr &A, const float *e, const float *s_l,
 size_t softmax_ws_bytes(const sensei_csr &A);
 
 // ---- dense
-// Y[0:n, 0:m_store) = act(A[n x k] . W[k x m]); columns m..m_store are written as act(0).
+// Y[0:n, 0:m_store) = act(row_scale[i] * (A[n x k] . W[k x m])); columns m..m_store are written as act(0);
+// row_scale may be null (no scaling).
 hipError_t launch_gemm(const float *A, int64_t lda, const float *W, int64_t ldw, float *Y, int64_t ldy, int64_t n,
-                       int k, int m, int m_store, int act, hipStream_t s);
+                       int k, int m, int m_store, int act, hipStream_t s, const float *row_scale = nullptr);
 hipError_t launch_gemv2(const float *A, int64_t lda, int64_t n, int k, const float *v1, const float *v2, float *y1,
                         float *y2, hipStream_t s);
 

@@ -10,8 +10,6 @@
 // fix-up kernel adds the carry slots to the row in chunk order.  No float
 // atomics: the summation order is fixed, results are reproducible, and a hub
 // row of a power-law graph is spread over as many wavefronts as it needs.
-#include <cstdlib>
-
 #include "sensei_internal.h"
 
 namespace sensei {
@@ -20,6 +18,7 @@ namespace {
 
 constexpr int kBlock = 256;
 constexpr int kWavesPerBlock = kBlock / 64;
+constexpr int kShortRowNnz = 12;  // chunks whose rows average fewer non-zeros than this use one neighbour group per row
 
 // ------------------------------------------------------------------ chunk plan
 
@@ -72,28 +71,56 @@ struct SpmmArgs {
     float *C, *carry;
     long long ldb, ldc;
     int n_rows, nnz, chunk_nnz, n_chunks;
-    int f, f_store, f_carry, n_tiles, act, store_vec_ok, tile_blocked, n_groups;
+    int f, f_store, f_carry, n_tiles, act, store_vec_ok;
+    int tiles_live, n_groups;  // feature tiles worked on at the same time; chunk groups (blocks per tile)
 };
+
+// value of `x` held by the lane whose number is byte_lane / 4 (all lanes must be active)
+__device__ __forceinline__ int lane_read(int byte_lane, int x) { return __builtin_amdgcn_ds_bpermute(byte_lane, x); }
+__device__ __forceinline__ float lane_read(int byte_lane, float x) {
+    return __int_as_float(__builtin_amdgcn_ds_bpermute(byte_lane, __float_as_int(x)));
+}
 
 // One wavefront = one (chunk, feature tile).  The 64 lanes form G = 64/LPG
 // neighbour groups of LPG lanes; a group reads VEC*LPG consecutive floats of
-// one neighbour row per step (one or two 128-byte lines), so G neighbours are
-// in flight per step and 4 steps are issued back to back.  Column indices (and
-// weights) are fetched 64 at a time, one per lane, and handed to the groups by
-// cross-lane reads.  Block b works on feature tile b % n_tiles: consecutive
-// workgroups go to consecutive XCDs, so each XCD's L2 keeps seeing the same
-// slice of the feature columns.
-template <int VEC, int LPG, int MODE>
+// one neighbour row per step (one 128-byte line at the default shape), so G
+// neighbours are in flight per step and 4 steps are issued back to back.
+// Column indices (and weights) are fetched 64 at a time, one per lane, and
+// handed to the groups by cross-lane reads.  The inner loop carries no
+// predicates: full steps of G neighbours run unmasked, the ragged end of a row
+// piece is one masked step, and lanes past the last feature column read
+// column 0 and never store.  With OFF32 the gathered matrix is smaller than
+// 4 GiB with fewer than 2^24 rows of fewer than 2^24 bytes, and addresses are
+// a uniform base plus a 32-bit byte offset formed by one 24-bit multiply-add.
+// Block b works on feature tile b % n_tiles: consecutive workgroups go to
+// consecutive XCDs, so each XCD's L2 keeps seeing the same slice of the
+// feature columns.
+template <int VEC, int LPG, int MODE, bool OFF32>
 __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
     constexpr int G = 64 / LPG;
     constexpr int TF = VEC * LPG;
+    constexpr int U = 4;  // steps issued back to back
     const int lane = threadIdx.x & 63;
-    const int tile = a.tile_blocked ? blockIdx.x / a.n_groups : blockIdx.x % a.n_tiles;
-    const int chunk = (a.tile_blocked ? blockIdx.x % a.n_groups : blockIdx.x / a.n_tiles) * kWavesPerBlock + (threadIdx.x >> 6);
+    // blocks are ordered: tile set (tiles_live tiles each) major, then chunk group, then tile within the set
+    const int per_set = a.n_groups * a.tiles_live;
+    const int set = blockIdx.x / per_set, in_set = blockIdx.x % per_set;
+    const int tile = set * a.tiles_live + in_set % a.tiles_live;
+    if (tile >= a.n_tiles) return;
+    // wave-uniform by construction; readfirstlane lets the compiler keep the row walk in scalar registers
+    const int chunk = (in_set / a.tiles_live) * kWavesPerBlock + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (chunk >= a.n_chunks) return;
     const int g = lane / LPG;
     const int f0 = tile * TF + (lane % LPG) * VEC;
     const bool fok = f0 < a.f;
+    const char *Bb = reinterpret_cast<const char *>(a.B);
+    const unsigned f0_b = fok ? (unsigned)f0 * 4u : 0u;
+    const unsigned ldb_b32 = (unsigned)(a.ldb * 4);
+    const size_t ldb_b64 = (size_t)a.ldb * 4;
+
+    auto gather = [&](int j) -> Vec<VEC> {
+        if (OFF32) return Vec<VEC>::load(reinterpret_cast<const float *>(Bb + (__umul24((unsigned)j, ldb_b32) + f0_b)));
+        return Vec<VEC>::load(reinterpret_cast<const float *>(Bb + ((size_t)j * ldb_b64 + f0_b)));
+    };
 
     const long long lo_ll = (long long)chunk * a.chunk_nnz;
     const int lo = (int)lo_ll;
@@ -102,13 +129,23 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
     const int i1 = a.chunk_row[chunk + 1];
 
     // first row touched: the one crossing `lo` if there is one, else the first owned row
+    // (the row walk is wave-uniform; uni() pins its state to scalar registers)
+    auto uni = [](int x) { return __builtin_amdgcn_readfirstlane(x); };
     bool cont = (a.nnz > 0) && (a.row_ptr[i0] > lo);
-    int i = cont ? i0 - 1 : i0;
-    int re = (i < a.n_rows) ? a.row_ptr[i + 1] : 0x7fffffff;
+    int i = uni(cont ? i0 - 1 : i0);
+    int re = uni((i < a.n_rows) ? a.row_ptr[i + 1] : 0x7fffffff);
 
     Vec<VEC> acc;
 #pragma unroll
     for (int e = 0; e < VEC; ++e) acc.v[e] = 0.f;
+
+    auto accumulate = [&](const Vec<VEC> &b, float ww) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            if (MODE == SENSEI_SPMM_PATTERN) acc.v[e] += b.v[e];
+            else acc.v[e] = fmaf(ww, b.v[e], acc.v[e]);
+        }
+    };
 
     auto finish_row = [&](bool complete) {
 #pragma unroll
@@ -121,8 +158,7 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
                 acc.store(a.carry + (size_t)chunk * a.f_carry + f0);
             } else {
                 if (complete) {
-                    float sc = 1.f;
-                    if (MODE == SENSEI_SPMM_SCALED) sc = a.r[i];
+                    const float sc = a.r ? a.r[i] : 1.f;
 #pragma unroll
                     for (int e = 0; e < VEC; ++e) {
                         float y = acc.v[e] * sc;
@@ -143,6 +179,70 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
         for (int e = 0; e < VEC; ++e) acc.v[e] = 0.f;
     };
 
+    // Many short rows in this chunk: walking them one after another would leave most neighbour groups
+    // idle and serialise one memory round trip per row.  Give every group a row of its own instead; a
+    // group then holds the whole feature slice of its row and needs no cross-lane reduction.
+    const int i_first = cont ? i0 - 1 : i0;
+    if ((long long)(i1 - i_first) * kShortRowNnz > (long long)(hi - lo)) {
+        for (int ib = i_first; ib < i1; ib += G) {
+            const int row = ib + g;
+            const bool rok = row < i1;
+            int rs = 0, rend = 0, row_end = 0;
+            if (rok) {
+                rs = a.row_ptr[row];
+                row_end = a.row_ptr[row + 1];
+                rs = rs > lo ? rs : lo;
+                rend = row_end < hi ? row_end : hi;
+            }
+            Vec<VEC> racc;
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) racc.v[e] = 0.f;
+            for (int k = rs; k < rend; k += U) {
+                Vec<VEC> b[U];
+                float ww[U];
+#pragma unroll
+                for (int q = 0; q < U; ++q) {
+                    const bool valid = k + q < rend;
+                    const int kq = valid ? k + q : k;
+                    const int j = a.col_idx[kq];
+                    float wq = 1.f;
+                    if (MODE == SENSEI_SPMM_WEIGHTED) wq = a.val[kq];
+                    if (MODE == SENSEI_SPMM_SCALED) wq = a.c[j];
+                    ww[q] = valid ? wq : 0.f;
+                    b[q] = gather(j);
+                }
+#pragma unroll
+                for (int q = 0; q < U; ++q) {
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) racc.v[e] = fmaf(ww[q], b[q].v[e], racc.v[e]);
+                }
+            }
+            if (rok && fok) {
+                if (cont && row == i_first) {
+                    racc.store(a.carry + (size_t)chunk * a.f_carry + f0);
+                } else {
+                    if (row_end <= hi) {
+                        const float sc = a.r ? a.r[row] : 1.f;
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e) {
+                            float y = racc.v[e] * sc;
+                            if (a.act == SENSEI_ACT_RELU) y = y > 0.f ? y : 0.f;
+                            racc.v[e] = y;
+                        }
+                    }
+                    float *dst = a.C + (size_t)row * a.ldc + f0;
+                    if (a.store_vec_ok && f0 + VEC <= a.f_store) {
+                        racc.store(dst);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e) if (f0 + e < a.f_store) dst[e] = racc.v[e];
+                    }
+                }
+            }
+        }
+        return;
+    }
+
     int pos = lo;
     for (int base = lo; base < hi; base += 64) {
         const int k = base + lane;
@@ -158,51 +258,40 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
             while (re <= pos) {  // rows ending here (or empty): close them and move on
                 finish_row(true);
                 cont = false;
-                ++i;
-                re = a.row_ptr[i + 1];
+                i = uni(i + 1);
+                re = uni(a.row_ptr[i + 1]);
             }
-            const int seg_hi = re < bhi ? re : bhi;
-            const int u0 = pos - base, u1 = seg_hi - base;
-            const int n_it = (u1 - u0 + G - 1) / G;
+            const int seg_hi = uni(re < bhi ? re : bhi);
+            const int u0 = uni(pos - base), n = uni(seg_hi - pos);
+            const int full = n / G;
+            int src4 = (u0 + g) * 4;  // byte-lane address of this group's next neighbour
             int it = 0;
-            for (; it + 4 <= n_it; it += 4) {
-                Vec<VEC> b[4];
-                float ww[4];
-                bool ok[4];
+            for (; it + U <= full; it += U) {
+                Vec<VEC> b[U];
+                float ww[U];
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int u = u0 + (it + q) * G + g;
-                    ok[q] = (u < u1) && fok;
-                    const int src = (u < u1) ? u : u0;
-                    const int j = __shfl(col, src, 64);
-                    ww[q] = (MODE == SENSEI_SPMM_PATTERN) ? 1.f : __shfl(w, src, 64);
-                    if (ok[q]) b[q] = Vec<VEC>::load(a.B + (size_t)j * a.ldb + f0);
+                for (int q = 0; q < U; ++q) {
+                    const int j = lane_read(src4 + q * G * 4, col);
+                    ww[q] = (MODE == SENSEI_SPMM_PATTERN) ? 1.f : lane_read(src4 + q * G * 4, w);
+                    b[q] = gather(j);
                 }
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    if (ok[q]) {
-#pragma unroll
-                        for (int e = 0; e < VEC; ++e) {
-                            if (MODE == SENSEI_SPMM_PATTERN) acc.v[e] += b[q].v[e];
-                            else acc.v[e] = fmaf(ww[q], b[q].v[e], acc.v[e]);
-                        }
-                    }
-                }
+                for (int q = 0; q < U; ++q) accumulate(b[q], ww[q]);
+                src4 += U * G * 4;
             }
-            for (; it < n_it; ++it) {
-                const int u = u0 + it * G + g;
-                const bool ok = (u < u1) && fok;
-                const int src = (u < u1) ? u : u0;
-                const int j = __shfl(col, src, 64);
-                const float ww = (MODE == SENSEI_SPMM_PATTERN) ? 1.f : __shfl(w, src, 64);
-                if (ok) {
-                    Vec<VEC> b = Vec<VEC>::load(a.B + (size_t)j * a.ldb + f0);
-#pragma unroll
-                    for (int e = 0; e < VEC; ++e) {
-                        if (MODE == SENSEI_SPMM_PATTERN) acc.v[e] += b.v[e];
-                        else acc.v[e] = fmaf(ww, b.v[e], acc.v[e]);
-                    }
-                }
+            for (; it < full; ++it) {
+                const int j = lane_read(src4, col);
+                const float ww = (MODE == SENSEI_SPMM_PATTERN) ? 1.f : lane_read(src4, w);
+                accumulate(gather(j), ww);
+                src4 += G * 4;
+            }
+            const int rem = n - full * G;
+            if (rem > 0) {  // ragged end of the piece: groups g < rem take one more neighbour
+                const bool ok = g < rem;
+                const int s4 = ok ? src4 : u0 * 4;
+                const int j = lane_read(s4, col);
+                const float ww = (MODE == SENSEI_SPMM_PATTERN) ? 1.f : lane_read(s4, w);
+                if (ok) accumulate(gather(j), ww);
             }
             pos = seg_hi;
         }
@@ -212,8 +301,8 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
         if (re <= hi) {
             finish_row(true);
             cont = false;
-            ++i;
-            re = (i < a.n_rows) ? a.row_ptr[i + 1] : 0x7fffffff;
+            i = uni(i + 1);
+            re = uni((i < a.n_rows) ? a.row_ptr[i + 1] : 0x7fffffff);
         } else {
             finish_row(false);
             break;
@@ -224,7 +313,6 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
 // Adds the carry slots of a row that spans several chunks to its output row, in chunk order,
 // then applies the row scale and the activation.  One wavefront per chunk; only the chunk that
 // holds the first continuation of a row does the work for that row.
-template <int MODE>
 __global__ __launch_bounds__(kBlock) void k_spmm_fixup(SpmmArgs a) {
     const int c = 1 + blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
     if (c >= a.n_chunks) return;
@@ -237,8 +325,7 @@ __global__ __launch_bounds__(kBlock) void k_spmm_fixup(SpmmArgs a) {
     if (rs < lo - a.chunk_nnz) return;  // the row began before the previous chunk: not its first continuation
     const int re = a.row_ptr[i + 1];
     const int c_last = (re - 1) / a.chunk_nnz;
-    float sc = 1.f;
-    if (MODE == SENSEI_SPMM_SCALED) sc = a.r[i];
+    const float sc = a.r ? a.r[i] : 1.f;
     for (int f = lane; f < a.f_store; f += 64) {
         float acc = a.C[(size_t)i * a.ldc + f];
         for (int cc = c; cc <= c_last; ++cc) acc += a.carry[(size_t)cc * a.f_carry + f];
@@ -248,23 +335,23 @@ __global__ __launch_bounds__(kBlock) void k_spmm_fixup(SpmmArgs a) {
     }
 }
 
-template <int VEC, int LPG>
+template <int VEC, int LPG, bool OFF32>
 hipError_t spmm_dispatch_mode(const SpmmArgs &a, int mode, dim3 grid, hipStream_t s) {
     switch (mode) {
-        case SENSEI_SPMM_PATTERN: hipLaunchKernelGGL((k_spmm<VEC, LPG, SENSEI_SPMM_PATTERN>), grid, dim3(kBlock), 0, s, a); break;
-        case SENSEI_SPMM_WEIGHTED: hipLaunchKernelGGL((k_spmm<VEC, LPG, SENSEI_SPMM_WEIGHTED>), grid, dim3(kBlock), 0, s, a); break;
-        default: hipLaunchKernelGGL((k_spmm<VEC, LPG, SENSEI_SPMM_SCALED>), grid, dim3(kBlock), 0, s, a); break;
+        case SENSEI_SPMM_PATTERN: hipLaunchKernelGGL((k_spmm<VEC, LPG, SENSEI_SPMM_PATTERN, OFF32>), grid, dim3(kBlock), 0, s, a); break;
+        case SENSEI_SPMM_WEIGHTED: hipLaunchKernelGGL((k_spmm<VEC, LPG, SENSEI_SPMM_WEIGHTED, OFF32>), grid, dim3(kBlock), 0, s, a); break;
+        default: hipLaunchKernelGGL((k_spmm<VEC, LPG, SENSEI_SPMM_SCALED, OFF32>), grid, dim3(kBlock), 0, s, a); break;
     }
     return hipGetLastError();
 }
 
 template <int VEC>
-hipError_t spmm_dispatch_lpg(const SpmmArgs &a, int mode, int lpg, dim3 grid, hipStream_t s) {
+hipError_t spmm_dispatch_lpg(const SpmmArgs &a, int mode, int lpg, bool off32, dim3 grid, hipStream_t s) {
     switch (lpg) {
-        case 8: return spmm_dispatch_mode<VEC, 8>(a, mode, grid, s);
-        case 16: return spmm_dispatch_mode<VEC, 16>(a, mode, grid, s);
-        case 32: return spmm_dispatch_mode<VEC, 32>(a, mode, grid, s);
-        default: return spmm_dispatch_mode<VEC, 64>(a, mode, grid, s);
+        case 8: return off32 ? spmm_dispatch_mode<VEC, 8, true>(a, mode, grid, s) : spmm_dispatch_mode<VEC, 8, false>(a, mode, grid, s);
+        case 16: return off32 ? spmm_dispatch_mode<VEC, 16, true>(a, mode, grid, s) : spmm_dispatch_mode<VEC, 16, false>(a, mode, grid, s);
+        case 32: return off32 ? spmm_dispatch_mode<VEC, 32, true>(a, mode, grid, s) : spmm_dispatch_mode<VEC, 32, false>(a, mode, grid, s);
+        default: return off32 ? spmm_dispatch_mode<VEC, 64, true>(a, mode, grid, s) : spmm_dispatch_mode<VEC, 64, false>(a, mode, grid, s);
     }
 }
 
@@ -366,7 +453,7 @@ struct SoftmaxArgs {
 // current row piece, then a wavefront reduction closes the piece.
 template <bool FROM_E>
 __global__ __launch_bounds__(kBlock) void k_softmax_stats(SoftmaxArgs a) {
-    const int chunk = blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+    const int chunk = blockIdx.x * kWavesPerBlock + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (chunk >= a.n.n_chunks) return;
     const int lane = threadIdx.x & 63;
     const long long lo_ll = (long long)chunk * a.n.chunk_nnz;
@@ -453,8 +540,6 @@ NnzArgs nnz_args(const sensei_csr &A, const ChunkPlan &p) {
 // ----------------------------------------------------------------- host side
 
 int choose_chunk_nnz(int64_t nnz, int) {
-    static const int dbg = getenv("SENSEI_DBG_CHUNK") ? atoi(getenv("SENSEI_DBG_CHUNK")) : 0;
-    if (dbg >= 64) return dbg;
     if (nnz >= (1LL << 24)) return 2048;
     if (nnz >= (1LL << 21)) return 1024;
     if (nnz >= (1LL << 18)) return 512;
@@ -480,14 +565,15 @@ SpmmShape spmm_shape(const float *B, int64_t ldb, int f) {
     else if (f % 2 == 0 && ldb % 2 == 0 && addr % 8 == 0) sh.vec = 2;
     else sh.vec = 1;
     const int fv = (f + sh.vec - 1) / sh.vec;  // vector columns
-    // A neighbour group reads one 128-byte line per neighbour (32 floats); narrower rows use
-    // the smallest power-of-two group that covers them, very wide rows use wider groups so
-    // the number of feature tiles stays moderate.
-    int lpg = 32 / sh.vec;
+    // A neighbour group reads one 128-byte line per neighbour (32 floats) and the feature tiles are spread
+    // over the XCDs.  Rows that do not fill whole groups use one wider group instead when that covers the
+    // row in a single tile (measured faster than leaving a nearly empty last tile); very wide rows use
+    // wider groups so the number of tiles stays moderate.
+    const int base = 32 / sh.vec;
+    int lpg = base;
     while (lpg > 8 && lpg / 2 >= fv) lpg >>= 1;
+    if (fv > lpg && fv <= 32 && fv % lpg != 0) while (lpg < fv) lpg <<= 1;
     while (lpg < 64 && (fv + lpg - 1) / lpg > 32) lpg <<= 1;
-    static const int dbg_lpg = getenv("SENSEI_DBG_LPG") ? atoi(getenv("SENSEI_DBG_LPG")) : 0;
-    if (dbg_lpg >= 8) lpg = dbg_lpg;
     sh.lpg = lpg;
     sh.n_tiles = (fv + lpg - 1) / lpg;
     sh.f_carry = sh.n_tiles * lpg * sh.vec;
@@ -513,24 +599,31 @@ hipError_t launch_spmm(const sensei_csr &A, int mode, const float *r, const floa
     a.f = f; a.f_store = f_store; a.f_carry = sh.f_carry; a.n_tiles = sh.n_tiles; a.act = act;
     a.store_vec_ok = (ldc % sh.vec == 0) && (reinterpret_cast<uintptr_t>(C) % (4 * sh.vec) == 0);
     const unsigned groups = blocks_for(p.n_chunks, kWavesPerBlock);
-    dim3 grid(groups * (unsigned)sh.n_tiles);
-    static const int dbg_blocked = getenv("SENSEI_DBG_TILE_BLOCKED") ? atoi(getenv("SENSEI_DBG_TILE_BLOCKED")) : 0;
-    a.tile_blocked = dbg_blocked;
+    // Feature tiles worked on at the same time: as many as keep the gathered slices (one per live tile)
+    // within about 96 MB, so that they stay in the 256 MB memory-side cache next to the index stream.
+    const double slice_bytes = (double)(A.n_cols > 0 ? A.n_cols : 1) * sh.lpg * sh.vec * 4.0;
+    a.tiles_live = 8;
+    while (a.tiles_live > 1 && a.tiles_live * slice_bytes > 96e6) a.tiles_live >>= 1;
+    if (a.tiles_live > sh.n_tiles) a.tiles_live = sh.n_tiles;
     a.n_groups = (int)groups;
+    const unsigned n_sets = (unsigned)((sh.n_tiles + a.tiles_live - 1) / a.tiles_live);
+    dim3 grid(groups * (unsigned)a.tiles_live * n_sets);
+    // byte offsets of the gathered matrix fit 32 bits?
+    const bool off32 = (unsigned long long)(A.n_cols > 0 ? A.n_cols : 1) * (unsigned long long)ldb * 4ull + 4ull * (unsigned long long)f <= 0xffffffffull &&
+                       A.n_cols < (1 << 24) && ldb * 4 < (1 << 24);
     hipError_t err;
     hipEvent_t t0 = timer ? timer->next() : nullptr, t1 = t0 ? timer->next() : nullptr;
     if (t1 && hipEventRecord(t0, s) != hipSuccess) return hipErrorUnknown;
     switch (sh.vec) {
-        case 4: err = spmm_dispatch_lpg<4>(a, mode, sh.lpg, grid, s); break;
-        case 2: err = spmm_dispatch_lpg<2>(a, mode, sh.lpg, grid, s); break;
-        default: err = spmm_dispatch_lpg<1>(a, mode, sh.lpg, grid, s); break;
+        case 4: err = spmm_dispatch_lpg<4>(a, mode, sh.lpg, off32, grid, s); break;
+        case 2: err = spmm_dispatch_lpg<2>(a, mode, sh.lpg, off32, grid, s); break;
+        default: err = spmm_dispatch_lpg<1>(a, mode, sh.lpg, off32, grid, s); break;
     }
     if (err != hipSuccess) return err;
     if (t1 && hipEventRecord(t1, s) != hipSuccess) return hipErrorUnknown;
     if (p.n_chunks > 1) {
         dim3 fg(blocks_for(p.n_chunks - 1, kWavesPerBlock));
-        if (mode == SENSEI_SPMM_SCALED) hipLaunchKernelGGL((k_spmm_fixup<SENSEI_SPMM_SCALED>), fg, dim3(kBlock), 0, s, a);
-        else hipLaunchKernelGGL((k_spmm_fixup<SENSEI_SPMM_PATTERN>), fg, dim3(kBlock), 0, s, a);
+        hipLaunchKernelGGL(k_spmm_fixup, fg, dim3(kBlock), 0, s, a);
         err = hipGetLastError();
     }
     return err;
