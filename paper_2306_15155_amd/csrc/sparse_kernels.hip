@@ -92,9 +92,10 @@ __device__ __forceinline__ float lane_read(int byte_lane, float x) {
 // column 0 and never store.  With OFF32 the gathered matrix is smaller than
 // 4 GiB with fewer than 2^24 rows of fewer than 2^24 bytes, and addresses are
 // a uniform base plus a 32-bit byte offset formed by one 24-bit multiply-add.
-// Block b works on feature tile b % n_tiles: consecutive workgroups go to
-// consecutive XCDs, so each XCD's L2 keeps seeing the same slice of the
-// feature columns.
+// Consecutive workgroups go to consecutive XCDs and take consecutive tiles of
+// the live tile set, so each XCD's L2 keeps seeing the same 128-byte slice of
+// the gathered matrix; the number of live tiles bounds how much of that matrix
+// is in use at one time.
 template <int VEC, int LPG, int MODE, bool OFF32>
 __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
     constexpr int G = 64 / LPG;
