@@ -16,7 +16,7 @@ struct sensei_ctx {
     double gather_l2_bps;  // row-gather bandwidth when the gathered slice fits the L2s
     double gather_far_bps; // row-gather bandwidth when it does not (Infinity Cache / HBM)
     double gemm_flops;     // achieved fp32 MFMA rate on large tiles
-    double l2_slice_bytes; // footprint of one feature-tile slice that still counts as L2 resident
+    double l2_slice_bytes; // feature-slice footprint at which 88 % of the gathers are served by the L2s
     KernelTimer timer;     // optional per-launch timing of the SpMM kernel
 };
 
@@ -209,19 +209,27 @@ double t_stream(const sensei_ctx &c, double bytes) { return c.launch_us * 1e-6 +
 
 double t_gemm(const sensei_ctx &c, double n, double k, double m) {
     const double flops = 2.0 * n * k * m, bytes = 4.0 * (n * k + k * m + n * m);
-    return c.launch_us * 1e-6 + std::fmax(flops / c.gemm_flops, bytes / c.stream_bps);
+    // narrow outputs leave part of each MFMA tile idle
+    const double rate = c.gemm_flops * (m >= 128 ? 1.0 : m >= 64 ? 0.8 : 0.5);
+    return c.launch_us * 1e-6 + std::fmax(flops / rate, bytes / c.stream_bps);
 }
 
-// SpMM: index traffic streams, neighbour rows are gathered; the gather rate depends on whether
-// one 128-byte feature slice of the gathered matrix (n_cols lines) stays resident in an L2.
-double t_spmm(const sensei_ctx &c, const Features &g, double f, bool weighted) {
+enum { kSpmmPattern = 0, kSpmmWeighted = 1, kSpmmScaled = 2 };
+
+// SpMM.  The neighbour rows are gathered at a rate between the L2-resident and the far
+// (memory-side cache / HBM) rate; the share served by the L2s falls with the size of one 128-byte
+// feature slice of the gathered matrix (n_cols lines), fitted on the two R-MAT workloads.  The
+// index stream is read once per feature tile; weights double it; gathering c[j] per non-zero
+// (SCALED) costs about a third on top of the row gather.
+double t_spmm(const sensei_ctx &c, const Features &g, double f, int flavour) {
     const double tiles = std::ceil(f / 32.0);
-    const double idx_bytes = g.nnz * (weighted ? 8.0 : 4.0) * tiles;
+    const double idx_bytes = g.nnz * (flavour == kSpmmWeighted ? 8.0 : 4.0) * tiles;
     const double out_bytes = 4.0 * f * g.n_rows;
-    const double slice = g.n_cols * 128.0;
-    const double hit = std::fmin(1.0, c.l2_slice_bytes / std::fmax(slice, 1.0));
+    const double slice = std::fmax(g.n_cols * 128.0, 1.0);
+    const double hit = std::fmin(0.9, 0.88 * std::pow(c.l2_slice_bytes / slice, 0.7));
     const double bw = 1.0 / (hit / c.gather_l2_bps + (1.0 - hit) / c.gather_far_bps);
-    const double gather = g.nnz * 4.0 * f / bw;
+    double gather = g.nnz * 4.0 * f / bw;
+    if (flavour == kSpmmScaled) gather *= 1.33;
     const double compulsory = (4.0 * f * g.n_cols + out_bytes + idx_bytes) / c.stream_bps;
     return 3.0 * c.launch_us * 1e-6 + std::fmax(gather + idx_bytes / c.stream_bps, compulsory);
 }
@@ -233,13 +241,16 @@ double gcn_cost(const sensei_ctx &c, const Features &g, int f_in, int f_out, int
     double t = c.launch_us * 1e-6 + t_gemm(c, gemm_rows, f_in, f_out);
     switch (id) {
         case SENSEI_GCN_DYN_AGG: case SENSEI_GCN_DYN_UPD:
-            t += t_spmm(c, g, fs, false) + t_stream(c, 8.0 * g.n_cols * fs) + t_stream(c, 8.0 * g.n_rows * fs);
+            t += t_spmm(c, g, fs, kSpmmPattern) + t_stream(c, 8.0 * g.n_cols * fs) + t_stream(c, 8.0 * g.n_rows * fs);
             break;
-        case SENSEI_GCN_DYNF_AGG: case SENSEI_GCN_DYNF_UPD:
-            t += t_spmm(c, g, fs, false);
+        case SENSEI_GCN_DYNF_AGG:
+            t += t_spmm(c, g, fs, kSpmmScaled);
+            break;
+        case SENSEI_GCN_DYNF_UPD:  // scalings live in the GEMM and SpMM epilogues
+            t += t_spmm(c, g, fs, kSpmmPattern);
             break;
         default:
-            t += t_spmm(c, g, fs, true);
+            t += t_spmm(c, g, fs, kSpmmWeighted);
             break;
     }
     return t;
@@ -254,9 +265,9 @@ double gat_cost(const sensei_ctx &c, const Features &g, int f_in, int f_out, int
     else t += t_gemm(c, g.n_cols, f_in, f_out) + t_stream(c, 4.0 * g.n_cols * f_out);
     if (gat_is_reuse(id)) {
         if (fold) t += t_gemm(c, g.n_cols, f_in, f_out);
-        t += t_spmm(c, g, f_out, true);
+        t += t_spmm(c, g, f_out, kSpmmWeighted);
     } else {
-        t += t_spmm(c, g, f_in, true) + t_gemm(c, g.n_rows, f_in, f_out);
+        t += t_spmm(c, g, f_in, kSpmmWeighted) + t_gemm(c, g.n_rows, f_in, f_out);
     }
     return t;
 }
@@ -312,12 +323,12 @@ int sensei_create(sensei_ctx **out, int device) {
     sensei_ctx *c = new (std::nothrow) sensei_ctx;
     if (!c) return SENSEI_HIP_ERROR;
     c->device = device;
-    c->launch_us = 3.0;
-    c->stream_bps = 4.0e12;
-    c->gather_l2_bps = 9.0e12;
-    c->gather_far_bps = 3.5e12;
-    c->gemm_flops = 60.0e12;
-    c->l2_slice_bytes = 3.0e6;
+    c->launch_us = 2.5;
+    c->stream_bps = 4.5e12;
+    c->gather_l2_bps = 19.0e12;
+    c->gather_far_bps = 6.5e12;
+    c->gemm_flops = 100.0e12;
+    c->l2_slice_bytes = 29.8e6;
     *out = c;
     return SENSEI_OK;
 }
