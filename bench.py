@@ -1,10 +1,10 @@
 #!/usr/bin/env python3
 """Benchmark of the GCN / GAT layer hot path on one MI355X.
 
-A step is one pass of the whole hot path over the synthetic Reddit-shaped workload: GCN layer 1
-(602->256, ReLU), GCN layer 2 (256->41) and one single-head GAT layer (602->256), each run in the
-composition sensei_select picked for it.  Inputs are resident in HBM before the timed region.
-Prints ONE JSON line (see the design doc for the meaning of every field).
+A step is one pass of the whole hot path over a synthetic workload: every layer of the workload's
+layer list, each run in the composition sensei_select picked for it.  The default workload is the
+Reddit-shaped one (GCN 602->256 with ReLU, GCN 256->41, single-head GAT 602->256 on the 233k-node
+R-MAT graph).  Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 """
 import argparse
 import json
@@ -16,10 +16,22 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+
+def _gcn(f_in, f_out, act, src):
+    return dict(kind="gcn", f_in=f_in, f_out=f_out, act=act, src=src)
+
+
+def _gat(f_in, f_out, act, src):
+    return dict(kind="gat", f_in=f_in, f_out=f_out, act=act, src=src)
+
+
+# src: "X" = the node features, an integer = output of that earlier layer of the list
 WORKLOADS = {
-    # name: (nodes, R-MAT draws, f_in, hidden, classes)
-    "c2_rmat233k": dict(n=233_000, draws=92_600_000, f_in=602, hidden=256, classes=41, seed=7),
-    "c1_er10k": dict(n=10_000, pairs=50_000, f_in=64, hidden=32, classes=16, seed=1),
+    "c2_rmat233k": dict(graph="rmat", n=233_000, draws=92_600_000, seed=7, f_x=602, x="uniform",
+                        layers=[_gcn(602, 256, 1, "X"), _gcn(256, 41, 0, 0), _gat(602, 256, 1, "X")]),
+    "c3_rmat2450k": dict(graph="rmat", n=2_450_000, draws=84_000_000, seed=7, f_x=100, x="normal",
+                         layers=[l for h in (32, 128, 512, 1024) for l in (_gcn(100, h, 1, "X"), _gcn(h, h, 0, -1))]),
+    "c1_er10k": dict(graph="er", n=10_000, pairs=50_000, seed=1, f_x=64, x="uniform", layers=[_gcn(64, 32, 1, "X")]),
 }
 
 
@@ -47,36 +59,32 @@ def main():
     import torch
 
     import synth
-    from paper_2306_15155_amd import (ACT_NONE, ACT_RELU, GAT_NAMES, GCN_NAMES, KIND_GAT, KIND_GCN, SELECT_MODEL, SELECT_TIMED,
-                                      Context, csr_struct)
+    from paper_2306_15155_amd import (GAT_NAMES, GCN_NAMES, KIND_GAT, KIND_GCN, SELECT_MODEL, SELECT_TIMED, Context, csr_struct)
 
     wl = WORKLOADS[args.workload]
+    layers = wl["layers"]
     dev = "cuda:0"
+    seed = wl["seed"]
     t0 = time.time()
-    if "draws" in wl:
-        g = synth.rmat(wl["seed"], wl["n"], wl["draws"])
-    else:
-        g = synth.erdos_renyi(wl["seed"], wl["n"], wl["pairs"])
+    g = synth.rmat(seed, wl["n"], wl["draws"]) if wl["graph"] == "rmat" else synth.erdos_renyi(seed, wl["n"], wl["pairs"])
     N, nnz = g.n_rows, g.nnz
-    f_in, hid, cls = wl["f_in"], wl["hidden"], wl["classes"]
-    X = synth.uniform(wl["seed"], 10, (N, f_in))
-    W1 = synth.glorot(wl["seed"], 11, f_in, hid)
-    W2 = synth.glorot(wl["seed"], 12, hid, cls)
-    Wg = synth.glorot(wl["seed"], 13, f_in, hid)
-    a_l = synth.normal(wl["seed"], 14, (hid,), 0.0, 0.1)
-    a_r = synth.normal(wl["seed"], 15, (hid,), 0.0, 0.1)
+    X = synth.uniform(seed, 10, (N, wl["f_x"])) if wl["x"] == "uniform" else synth.normal(seed, 10, (N, wl["f_x"]))
+    Ws = [synth.glorot(seed, 100 + i, L["f_in"], L["f_out"]) for i, L in enumerate(layers)]
+    att = [(synth.normal(seed, 200 + i, (L["f_out"],), 0.0, 0.1), synth.normal(seed, 300 + i, (L["f_out"],), 0.0, 0.1))
+           if L["kind"] == "gat" else None for i, L in enumerate(layers)]
     gen_s = time.time() - t0
 
     row_ptr, col_idx = torch.from_numpy(g.row_ptr).to(dev), torch.from_numpy(g.col_idx).to(dev)
-    Xd, W1d, W2d, Wgd = (torch.from_numpy(a).to(dev) for a in (X, W1, W2, Wg))
-    ald, ard = torch.from_numpy(a_l).to(dev), torch.from_numpy(a_r).to(dev)
+    Xd = torch.from_numpy(X).to(dev)
+    Wd = [torch.from_numpy(w).to(dev) for w in Ws]
+    attd = [None if a is None else (torch.from_numpy(a[0]).to(dev), torch.from_numpy(a[1]).to(dev)) for a in att]
     ctx = Context(0)
     A = csr_struct(N, N, row_ptr, col_idx)
 
     def ev():
         return torch.cuda.Event(enable_timing=True)
 
-    # ---- one-off setup (a0, a1), timed separately
+    # ---- one-off set-up (degrees, D^-1/2 vectors, N~), timed separately
     torch.cuda.synchronize()
     e0, e1 = ev(), ev()
     e0.record()
@@ -90,22 +98,25 @@ def main():
 
     # ---- composition choice per layer (cost model: host arithmetic only)
     ts = time.perf_counter()
-    id1, est1 = ctx.select(KIND_GCN, A, f_in, hid, SELECT_MODEL)
-    id2, est2 = ctx.select(KIND_GCN, A, hid, cls, SELECT_MODEL)
-    idg, estg = ctx.select(KIND_GAT, A, f_in, hid, SELECT_MODEL)
+    ids = [ctx.select(KIND_GCN if L["kind"] == "gcn" else KIND_GAT, A, L["f_in"], L["f_out"], SELECT_MODEL)[0] for L in layers]
     select_model_ms = (time.perf_counter() - ts) * 1e3
 
-    H1 = torch.empty((N, hid), device=dev)
-    Y2 = torch.empty((N, cls), device=dev)
-    Yg = torch.empty((N, hid), device=dev)
+    outs = [torch.empty((N, L["f_out"]), device=dev) for L in layers]
 
-    def gcn(cid, Xin, Win, out, act):
-        return ctx.gcn_layer(Apre if cid >= 4 else A, r, c, Xin, Win, cid, act, out=out)
+    def src_of(i):
+        s = layers[i]["src"]
+        return Xd if s == "X" else outs[i + s if s < 0 else s]
+
+    def run_layer(i, cid):
+        L = layers[i]
+        if L["kind"] == "gcn":
+            ctx.gcn_layer(Apre if cid >= 4 else A, r, c, src_of(i), Wd[i], cid, L["act"], out=outs[i])
+        else:
+            ctx.gat_layer(A, src_of(i), Wd[i], attd[i][0], attd[i][1], cid, 0.2, L["act"], out=outs[i])
 
     def step():
-        gcn(id1, Xd, W1d, H1, ACT_RELU)
-        gcn(id2, H1, W2d, Y2, ACT_NONE)
-        ctx.gat_layer(A, Xd, Wgd, ald, ard, idg, 0.2, ACT_RELU, out=Yg)
+        for i in range(len(layers)):
+            run_layer(i, ids[i])
 
     if args.copy_probe:
         src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
@@ -126,34 +137,66 @@ def main():
     e1.record()
     torch.cuda.synchronize()
     total_ms = e0.elapsed_time(e1)
-    spmm_ms = ctx.profile_read()
+    spmm_ms = ctx.profile_read(0)
+    gemm_ms = ctx.profile_read(1)
     ctx.profile_enable(False)
     ms_per_step = total_ms / args.steps
-    ms_per_layer = ms_per_step / 3.0
+    ms_per_layer = ms_per_step / len(layers)
 
-    # ---- roofline of the dominant kernel: the SpMM of GCN layer 1 (3 SpMM launches per step, in order)
-    per_step = len(spmm_ms) // max(args.steps, 1)
-    l1 = spmm_ms[0::per_step] if per_step else []
-    spmm_l1_ms = float(np.mean(l1)) if l1 else float("nan")
-    agg1 = id1 in (0, 2, 4)
-    f_sp = f_in if agg1 else hid
-    weighted = id1 >= 4
-    # compulsory bytes of one launch: indices (+ values), row pointers, every gathered row once, output once,
-    # plus the two scaling vectors when they are applied inside the kernel
-    idx_bytes = nnz * (8 if weighted else 4) + 4 * (N + 1)
-    algo_bytes = idx_bytes + 4 * f_sp * N + 4 * f_sp * N + (8 * N if id1 in (2, 3) else 0)
-    gather_bytes = idx_bytes + 4 * f_sp * nnz + 4 * f_sp * N
-    achieved = algo_bytes / (spmm_l1_ms * 1e-3) / 1e9
-    traffic = None
-    prof = os.path.join(ROOT, "profiles", "k_spmm_c2_rmat233k_pmc.txt")
-    if args.workload == "c2_rmat233k" and os.path.exists(prof):
-        for line in open(prof):
-            if line.startswith("traffic_bytes_per_launch:"):
-                traffic = float(line.split(":")[1])
-    roofline = {"kernel": "k_spmm (GCN layer 1, F=%d, %s)" % (f_sp, GCN_NAMES[id1]), "bound": "hbm", "achieved": round(achieved, 1),
-                "peak": 8000.0, "unit": "GB/s", "frac": round(achieved / 8000.0, 4), "traffic": traffic,
-                "avg_launch_ms": round(spmm_l1_ms, 4), "algorithmic_bytes": algo_bytes,
-                "gather_GBps_no_reuse": round(gather_bytes / (spmm_l1_ms * 1e-3) / 1e9, 1)}
+    def name_of(i, cid=None):
+        cid = ids[i] if cid is None else cid
+        return (GCN_NAMES if layers[i]["kind"] == "gcn" else GAT_NAMES)[cid]
+
+    def tag(i):
+        return "%s%d_%d_%d" % (layers[i]["kind"], i, layers[i]["f_in"], layers[i]["f_out"])
+
+    # ---- roofline of the dominant kernel: the SpMM launch (one per layer per step, in layer order) with the largest mean time
+    per_step = len(layers)
+    spmm_mean = [float(np.mean(spmm_ms[i::per_step])) for i in range(per_step)] if len(spmm_ms) == per_step * args.steps else []
+    roofline = None
+    if spmm_mean:
+        k = int(np.argmax(spmm_mean))
+        L, cid = layers[k], ids[k]
+        if L["kind"] == "gcn":
+            f_sp = L["f_in"] if cid in (0, 2, 4) else L["f_out"]
+            weighted, scaled = cid >= 4, cid in (2, 3)
+        else:
+            f_sp = L["f_out"] if cid in (0, 3) else L["f_in"]
+            weighted, scaled = True, False
+        # compulsory bytes of one launch: indices (+ values), row pointers, every gathered row once, the output once,
+        # plus the scaling vectors when they are applied inside the kernel
+        idx_bytes = nnz * (8 if weighted else 4) + 4 * (N + 1)
+        algo_bytes = idx_bytes + 4 * f_sp * N + 4 * f_sp * N + (8 * N if scaled else 0)
+        gather_bytes = idx_bytes + 4 * f_sp * nnz + 4 * f_sp * N
+        t_s = spmm_mean[k] * 1e-3
+        traffic = None
+        prof = os.path.join(ROOT, "profiles", "k_spmm_%s_pmc.txt" % args.workload)
+        if os.path.exists(prof):
+            for line in open(prof):
+                if line.startswith("traffic_bytes_per_launch %s:" % tag(k)):
+                    traffic = float(line.split(":")[1])
+        roofline = {"kernel": "k_spmm (%s, F=%d, %s)" % (tag(k), f_sp, name_of(k)), "bound": "hbm",
+                    "achieved": round(algo_bytes / t_s / 1e9, 1), "peak": 8000.0, "unit": "GB/s",
+                    "frac": round(algo_bytes / t_s / 1e9 / 8000.0, 4), "traffic": traffic,
+                    "avg_launch_ms": round(spmm_mean[k], 4), "algorithmic_bytes": algo_bytes,
+                    "gather_GBps_no_reuse": round(gather_bytes / t_s / 1e9, 1),
+                    "measured_traffic_GBps": None if traffic is None else round(traffic / t_s / 1e9, 1)}
+
+    # ---- MFMA utilisation of the GEMM launch with the largest mean time (fp32 matrix peak 157.3 TFLOP/s)
+    gemm_info = None
+    n_gemm = [2 if (L["kind"] == "gat" and ids[i] == 1) else 1 for i, L in enumerate(layers)]
+    if len(gemm_ms) == sum(n_gemm) * args.steps:
+        per, off, best = sum(n_gemm), 0, None
+        for i, L in enumerate(layers):
+            for j in range(n_gemm[i]):
+                t = float(np.mean(gemm_ms[off + j::per]))
+                if best is None or t > best[1]:
+                    best = (i, t)
+            off += n_gemm[i]
+        i, t = best
+        flops = 2.0 * N * layers[i]["f_in"] * layers[i]["f_out"]
+        gemm_info = {"kernel": "k_gemm (%s, %dx%dx%d)" % (tag(i), N, layers[i]["f_in"], layers[i]["f_out"]), "avg_launch_ms": round(t, 4),
+                     "tflops": round(flops / t / 1e9, 1), "mfma_peak_tflops": 157.3, "mfma_utilisation": round(flops / t / 1e9 / 157.3, 3)}
 
     # ---- per-layer and per-composition times (outside the timed region)
     def time_fn(fn, iters=3):
@@ -167,61 +210,66 @@ def main():
         torch.cuda.synchronize()
         return a.elapsed_time(b) / iters
 
-    detail = {"layers": {
-        "gcn1_%d_%d" % (f_in, hid): {"id": GCN_NAMES[id1], "ms": round(time_fn(lambda: gcn(id1, Xd, W1d, H1, ACT_RELU)), 4)},
-        "gcn2_%d_%d" % (hid, cls): {"id": GCN_NAMES[id2], "ms": round(time_fn(lambda: gcn(id2, H1, W2d, Y2, ACT_NONE)), 4)},
-        "gat_%d_%d" % (f_in, hid): {"id": GAT_NAMES[idg], "ms": round(time_fn(lambda: ctx.gat_layer(A, Xd, Wgd, ald, ard, idg, 0.2, ACT_RELU, out=Yg)), 4)},
-    }, "setup_ms": round(setup_ms, 4), "select_model_ms": round(select_model_ms, 4), "graph": {"nodes": N, "nnz": nnz,
-        "max_degree": int(np.diff(g.row_ptr).max()), "generate_s": round(gen_s, 2)}}
+    detail = {"layers": {tag(i): {"id": name_of(i), "ms": round(time_fn(lambda: run_layer(i, ids[i])), 4),
+                                  "spmm_kernel_ms": round(spmm_mean[i], 4) if spmm_mean else None} for i in range(len(layers))},
+              "gemm": gemm_info, "setup_ms": round(setup_ms, 4), "select_model_ms": round(select_model_ms, 4),
+              "graph": {"nodes": N, "nnz": nnz, "max_degree": int(np.diff(g.row_ptr).max()), "generate_s": round(gen_s, 2)}}
     if not args.no_sweep:
-        sweep = {}
-        for name, Xin, Win, out, act in (("gcn1", Xd, W1d, H1, ACT_RELU), ("gcn2", H1, W2d, Y2, ACT_NONE)):
-            sweep[name] = {GCN_NAMES[i]: round(time_fn(lambda: gcn(i, Xin, Win, out, act), 2), 4) for i in range(6)}
-        sweep["gat"] = {GAT_NAMES[i]: round(time_fn(lambda: ctx.gat_layer(A, Xd, Wgd, ald, ard, i, 0.2, ACT_RELU, out=Yg), 2), 4)
-                        for i in range(4)}
+        sweep, regret = {}, {}
+        for i, L in enumerate(layers):
+            n_ids = 6 if L["kind"] == "gcn" else 4
+            sweep[tag(i)] = {name_of(i, cid): round(time_fn(lambda: run_layer(i, cid), 2), 4) for cid in range(n_ids)}
+            allowed = [cid for cid, t in enumerate(ctx.select(KIND_GCN if L["kind"] == "gcn" else KIND_GAT, A, L["f_in"], L["f_out"],
+                                                              SELECT_MODEL)[1]) if t >= 0]
+            regret[tag(i)] = round(sweep[tag(i)][name_of(i)] / min(sweep[tag(i)][name_of(i, cid)] for cid in allowed) - 1.0, 4)
+            run_layer(i, ids[i])  # leave the selected composition's output in place for later layers
         detail["all_compositions_ms"] = sweep
-        regret = {}
-        for name, picked, names in (("gcn1", id1, GCN_NAMES), ("gcn2", id2, GCN_NAMES), ("gat", idg, GAT_NAMES)):
-            regret[name] = round(sweep[name][names[picked]] / min(sweep[name].values()) - 1.0, 4)
         detail["selector_regret"] = regret
+        L0 = layers[0]
         ts = time.perf_counter()
-        idt, _ = ctx.select(KIND_GCN, A, f_in, hid, SELECT_TIMED)
+        idt, _ = ctx.select(KIND_GCN if L0["kind"] == "gcn" else KIND_GAT, A, L0["f_in"], L0["f_out"], SELECT_TIMED)
         torch.cuda.synchronize()
-        detail["select_timed"] = {"gcn1_pick": GCN_NAMES[idt], "overhead_ms": round((time.perf_counter() - ts) * 1e3, 3),
-                                  "overhead_in_layers": round((time.perf_counter() - ts) * 1e3 / detail["layers"]["gcn1_%d_%d" % (f_in, hid)]["ms"], 2)}
+        dt = (time.perf_counter() - ts) * 1e3
+        detail["select_timed"] = {"layer": tag(0), "pick": name_of(0, idt), "overhead_ms": round(dt, 3),
+                                  "overhead_in_layers": round(dt / detail["layers"][tag(0)]["ms"], 2)}
 
-    # ---- CPU baseline: the fp64 oracle, single thread, on a bounded row sample, extrapolated by row count
+    # ---- CPU baseline: the fp64 oracle as it stands, one thread, on a bounded sample of output rows of every layer,
+    # extrapolated by row count.  Hidden inputs are seeded stand-ins so that nothing from the GPU reaches the oracle.
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
-        n_s = min(N, 24000 if N > 50_000 else N)
-        rows = np.sort(synth.distinct_nodes(wl["seed"], 40, N, n_s)) if n_s < N else None
+        budget_rows = 72_000 if N > 50_000 else N * len(layers)
+        n_s = min(N, max(500, budget_rows // len(layers)))
+        if args.workload == "c3_rmat2450k":
+            n_s = 3000
+        rows = np.sort(synth.distinct_nodes(seed, 40, N, n_s)) if n_s < N else None
         scale = N / float(n_s)
-        tc = time.perf_counter()
-        Xh1 = oracle.gcn_layer(N, N, g.row_ptr, g.col_idx, X, W1, 1, rows=rows)
-        t1 = time.perf_counter() - tc
-        H1_host = synth.uniform(wl["seed"], 16, (N, hid), 0.0, 1.0)  # stand-in for the hidden activations
-        tc = time.perf_counter()
-        oracle.gcn_layer(N, N, g.row_ptr, g.col_idx, H1_host, W2, 0, rows=rows)
-        t2 = time.perf_counter() - tc
-        tc = time.perf_counter()
-        Yg_ref = oracle.gat_layer(N, N, g.row_ptr, g.col_idx, X, Wg, a_l, a_r, 0.2, 1, rows=rows)
-        t3 = time.perf_counter() - tc
-        cpu = {"value": round((t1 + t2 + t3) * scale * 1e3 / 3.0, 1), "unit": "ms per layer (extrapolated by row count)",
-               "cores": oracle.threads(False), "kind": "oracle",
-               "sample": "%d uniformly drawn output rows of each of the 3 layers (of %d), %.1f s of CPU work" % (n_s, N, t1 + t2 + t3)}
-        # the sampled oracle rows double as a full-size parity check of what was just timed
+        t_cpu, errs = 0.0, {}
         sel = slice(None) if rows is None else torch.from_numpy(rows.astype(np.int64)).to(dev)
-        err1 = float(np.max(np.abs(H1[sel].cpu().numpy() - Xh1) / (1.0 + np.abs(Xh1))))
-        errg = float(np.max(np.abs(Yg[sel].cpu().numpy() - Yg_ref) / (1.0 + np.abs(Yg_ref))))
-        detail["sampled_parity_max_scaled_err"] = {"gcn1": err1, "gat": errg}
+        for i, L in enumerate(layers):
+            from_x = L["src"] == "X"
+            Xin = X if from_x else synth.uniform(seed, 400 + i, (N, L["f_in"]), 0.0, 1.0)
+            tc = time.perf_counter()
+            if L["kind"] == "gcn":
+                ref = oracle.gcn_layer(N, N, g.row_ptr, g.col_idx, Xin, Ws[i], L["act"], rows=rows)
+            else:
+                ref = oracle.gat_layer(N, N, g.row_ptr, g.col_idx, Xin, Ws[i], att[i][0], att[i][1], 0.2, L["act"], rows=rows)
+            t_cpu += time.perf_counter() - tc
+            if from_x:  # same inputs as the timed GPU layer: a full-size parity check of what was just timed
+                got = outs[i][sel].cpu().numpy()
+                errs[tag(i)] = float(np.max(np.abs(got - ref) / (1.0 + np.abs(ref))))
+        cpu = {"value": round(t_cpu * scale * 1e3 / len(layers), 1), "unit": "ms per layer (extrapolated by row count)",
+               "cores": oracle.threads(False), "kind": "oracle",
+               "sample": "%d uniformly drawn output rows of each of the %d layers (of %d rows), %.1f s of CPU work" % (n_s, len(layers), N, t_cpu)}
+        detail["sampled_parity_max_scaled_err"] = errs
 
-    out = {"metric": "ms per GCN/GAT layer (mean over GCN 602->256, GCN 256->41, GAT 602->256)", "value": round(ms_per_layer, 4),
+    desc = ", ".join("%s %d->%d" % (L["kind"].upper(), L["f_in"], L["f_out"]) for L in layers)
+    out = {"metric": "ms per GCN/GAT layer (mean over the %d layers of one step)" % len(layers), "value": round(ms_per_layer, 4),
            "unit": "ms/layer", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
            "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-           "config": {"workload": args.workload, "graph": "R-MAT(0.57,0.19,0.19,0.05) symmetrised + self loops" if "draws" in wl else "G(n,M) + self loops",
-                      "nodes": N, "nnz": nnz, "layers": "GCN %d->%d->%d, GAT %d->%d" % (f_in, hid, cls, f_in, hid),
-                      "compositions": [GCN_NAMES[id1], GCN_NAMES[id2], GAT_NAMES[idg]]},
+           "config": {"workload": args.workload,
+                      "graph": "R-MAT(0.57,0.19,0.19,0.05) symmetrised + self loops" if wl["graph"] == "rmat" else "G(n,M) + self loops",
+                      "nodes": N, "nnz": nnz, "layers": desc, "compositions": [name_of(i) for i in range(len(layers))]},
            "roofline": roofline, "cpu_baseline": cpu, "detail": detail}
     print(json.dumps(out))
     ctx.close()

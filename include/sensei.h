@@ -92,13 +92,14 @@ int sensei_destroy(sensei_ctx *ctx);
  * sensei_select uses built-in MI355X defaults.  `workspace` >= 64 MiB. */
 int sensei_calibrate(sensei_ctx *ctx, void *workspace, size_t ws_bytes, void *stream);
 
-/* Optional instrumentation for benchmarks.  While enabled, every launch of the SpMM kernel made
- * through this context is bracketed by a pair of HIP events on the launch stream (at most 4096
- * launches per recording; enabling starts a new recording).  sensei_profile_read waits for the
- * recorded events and writes the elapsed milliseconds of each launch, in launch order, to ms_out
- * (host, `capacity` floats); count_out (host) receives the number of recorded launches. */
+/* Optional instrumentation for benchmarks.  While enabled, every launch of the SpMM kernel and of the
+ * GEMM kernel made through this context is bracketed by a pair of HIP events on the launch stream (at most
+ * 4096 launches of each per recording; enabling starts a new recording).  sensei_profile_read waits for
+ * the recorded events of one kernel and writes the elapsed milliseconds of each launch, in launch order,
+ * to ms_out (host, `capacity` floats); count_out (host) receives the number of recorded launches. */
+enum { SENSEI_PROFILE_SPMM = 0, SENSEI_PROFILE_GEMM = 1 };
 int sensei_profile_enable(sensei_ctx *ctx, int enable);
-int sensei_profile_read(sensei_ctx *ctx, float *ms_out, int capacity, int *count_out);
+int sensei_profile_read(sensei_ctx *ctx, int kernel, float *ms_out, int capacity, int *count_out);
 
 int sensei_num_compositions(int kind);
 const char *sensei_composition_name(int kind, int comp_id);

@@ -83,7 +83,7 @@ def lib():
         L.sensei_select_workspace.argtypes = [i32, P(CsrStruct), i32, i32, P(sz)]
         L.sensei_select.argtypes = [vp, i32, P(CsrStruct), i32, i32, i32, P(ctypes.c_int), P(f32), vp, sz, vp]
         L.sensei_profile_enable.argtypes = [vp, i32]
-        L.sensei_profile_read.argtypes = [vp, P(f32), i32, P(ctypes.c_int)]
+        L.sensei_profile_read.argtypes = [vp, i32, P(f32), i32, P(ctypes.c_int)]
         for name in EXPORTS:
             if name not in ("sensei_composition_name", "sensei_status_string"):
                 getattr(L, name).restype = ctypes.c_int
@@ -274,12 +274,13 @@ class Context:
     def profile_enable(self, enable: bool):
         _check(lib().sensei_profile_enable(self._h, int(enable)), "sensei_profile_enable")
 
-    def profile_read(self):
-        """Elapsed ms of every SpMM kernel launch recorded since profile_enable(True), in launch order."""
+    def profile_read(self, kernel: int = 0):
+        """Elapsed ms of every launch of the SpMM (kernel=0) or GEMM (kernel=1) kernel recorded since
+        profile_enable(True), in launch order."""
         n = ctypes.c_int(0)
-        _check(lib().sensei_profile_read(self._h, None, 0, ctypes.byref(n)), "sensei_profile_read")
+        _check(lib().sensei_profile_read(self._h, kernel, None, 0, ctypes.byref(n)), "sensei_profile_read")
         buf = (ctypes.c_float * max(n.value, 1))()
-        _check(lib().sensei_profile_read(self._h, buf, n.value, ctypes.byref(n)), "sensei_profile_read")
+        _check(lib().sensei_profile_read(self._h, kernel, buf, n.value, ctypes.byref(n)), "sensei_profile_read")
         return [float(buf[i]) for i in range(n.value)]
 
     def calibrate(self):

@@ -17,7 +17,7 @@ struct sensei_ctx {
     double gather_far_bps; // row-gather bandwidth when it does not (Infinity Cache / HBM)
     double gemm_flops;     // achieved fp32 MFMA rate on large tiles
     double l2_slice_bytes; // feature-slice footprint at which 88 % of the gathers are served by the L2s
-    KernelTimer timer;     // optional per-launch timing of the SpMM kernel
+    Timers timers;         // optional per-launch timing of the SpMM and GEMM kernels
 };
 
 namespace {
@@ -113,7 +113,8 @@ size_t gat_ws(const sensei_csr &A, int f_in, int f_out, int id) {
     } while (0)
 
 int run_gcn(const sensei_csr &A, const float *r, const float *c, const sensei_mat &X, const sensei_mat &W, float *Y,
-            int64_t ldy, int act, int id, void *ws, size_t ws_bytes, hipStream_t s, KernelTimer *kt) {
+            int64_t ldy, int act, int id, void *ws, size_t ws_bytes, hipStream_t s, Timers *tm) {
+    KernelTimer *kt = tm ? &tm->spmm : nullptr, *gt = tm ? &tm->gemm : nullptr;
     const int f_in = (int)X.cols, f_out = (int)W.cols;
     Carver cv(ws, ws_bytes);
     ChunkPlan plan = make_plan(A, cv);
@@ -136,7 +137,7 @@ int run_gcn(const sensei_csr &A, const float *r, const float *c, const sensei_ma
         const bool scaled = (mode == SENSEI_SPMM_SCALED);
         SENSEI_TRY(launch_spmm(A, mode, scaled ? r : nullptr, scaled ? c : nullptr, src, ld_src, f_in, U, fs, f_in, SENSEI_ACT_NONE, plan, carry, s, kt));
         if (id == SENSEI_GCN_DYN_AGG) SENSEI_TRY(launch_row_broadcast(r, U, fs, A.n_rows, f_in, U, fs, SENSEI_ACT_NONE, s));
-        SENSEI_TRY(launch_gemm(U, fs, W.ptr, W.ld, Y, ldy, A.n_rows, f_in, f_out, f_out, act, s));
+        SENSEI_TRY(launch_gemm(U, fs, W.ptr, W.ld, Y, ldy, A.n_rows, f_in, f_out, f_out, act, s, nullptr, gt));
     } else {
         const int fs = pad4(f_out);
         float *carry = cv.take<float>(spmm_carry_bytes(A.nnz, fs) / sizeof(float));
@@ -144,7 +145,7 @@ int run_gcn(const sensei_csr &A, const float *r, const float *c, const sensei_ma
         // DYNF_UPD: the column scaling is a row broadcast on Z = X.W, fused into the GEMM epilogue; the row
         // scaling and the activation are fused into the SpMM epilogue, so the SpMM itself is value-less.
         const float *z_scale = (id == SENSEI_GCN_DYNF_UPD) ? c : nullptr;
-        SENSEI_TRY(launch_gemm(X.ptr, X.ld, W.ptr, W.ld, Z, fs, A.n_cols, f_in, f_out, fs, SENSEI_ACT_NONE, s, z_scale));
+        SENSEI_TRY(launch_gemm(X.ptr, X.ld, W.ptr, W.ld, Z, fs, A.n_cols, f_in, f_out, fs, SENSEI_ACT_NONE, s, z_scale, gt));
         if (id == SENSEI_GCN_DYN_UPD) {
             SENSEI_TRY(launch_row_broadcast(c, Z, fs, A.n_cols, fs, Z, fs, SENSEI_ACT_NONE, s));
             SENSEI_TRY(launch_spmm(A, mode, nullptr, nullptr, Z, fs, fs, Y, ldy, f_out, SENSEI_ACT_NONE, plan, carry, s, kt));
@@ -159,7 +160,8 @@ int run_gcn(const sensei_csr &A, const float *r, const float *c, const sensei_ma
 }
 
 int run_gat(const sensei_csr &A, const sensei_mat &X, const sensei_mat &W, const float *a_l, const float *a_r,
-            float slope, float *Y, int64_t ldy, int act, int id, void *ws, size_t ws_bytes, hipStream_t s, KernelTimer *kt) {
+            float slope, float *Y, int64_t ldy, int act, int id, void *ws, size_t ws_bytes, hipStream_t s, Timers *tm) {
+    KernelTimer *kt = tm ? &tm->spmm : nullptr, *gt = tm ? &tm->gemm : nullptr;
     const int f_in = (int)X.cols, f_out = (int)W.cols;
     const int fo = pad4(f_out), fi = pad4(f_in);
     Carver cv(ws, ws_bytes);
@@ -177,7 +179,7 @@ int run_gat(const sensei_csr &A, const sensei_mat &X, const sensei_mat &W, const
     SENSEI_TRY(launch_chunk_rows(A, plan, s));
     const bool fold = (id == SENSEI_GAT_RECOMP_FOLD || id == SENSEI_GAT_REUSE_FOLD);
     if (!fold) {  // Theta = X.W, then the two projections of Theta
-        SENSEI_TRY(launch_gemm(X.ptr, X.ld, W.ptr, W.ld, theta, fo, A.n_cols, f_in, f_out, fo, SENSEI_ACT_NONE, s));
+        SENSEI_TRY(launch_gemm(X.ptr, X.ld, W.ptr, W.ld, theta, fo, A.n_cols, f_in, f_out, fo, SENSEI_ACT_NONE, s, nullptr, gt));
         SENSEI_TRY(launch_gemv2(theta, fo, A.n_cols, f_out, a_l, a_r, s_l, s_r, s));
     } else {      // (X.W).a = X.(W.a)
         SENSEI_TRY(launch_gemv2(W.ptr, W.ld, f_in, f_out, a_l, a_r, v_l, v_r, s));
@@ -187,14 +189,14 @@ int run_gat(const sensei_csr &A, const sensei_mat &X, const sensei_mat &W, const
     sensei_csr Aw = A;
     Aw.val = alpha;
     if (gat_is_reuse(id)) {
-        if (fold) SENSEI_TRY(launch_gemm(X.ptr, X.ld, W.ptr, W.ld, theta, fo, A.n_cols, f_in, f_out, fo, SENSEI_ACT_NONE, s));
+        if (fold) SENSEI_TRY(launch_gemm(X.ptr, X.ld, W.ptr, W.ld, theta, fo, A.n_cols, f_in, f_out, fo, SENSEI_ACT_NONE, s, nullptr, gt));
         float *carry = cv.take<float>(spmm_carry_bytes(A.nnz, fo) / sizeof(float));
         SENSEI_TRY(launch_spmm(Aw, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, theta, fo, fo, Y, ldy, f_out, act, plan, carry, s, kt));
     } else {
         float *carry = cv.take<float>(spmm_carry_bytes(A.nnz, fi) / sizeof(float));
         float *U = cv.take<float>((size_t)A.n_rows * fi);
         SENSEI_TRY(launch_spmm(Aw, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, X.ptr, X.ld, f_in, U, fi, f_in, SENSEI_ACT_NONE, plan, carry, s, kt));
-        SENSEI_TRY(launch_gemm(U, fi, W.ptr, W.ld, Y, ldy, A.n_rows, f_in, f_out, f_out, act, s));
+        SENSEI_TRY(launch_gemm(U, fi, W.ptr, W.ld, Y, ldy, A.n_rows, f_in, f_out, f_out, act, s, nullptr, gt));
     }
     return SENSEI_OK;
 }
@@ -334,25 +336,32 @@ int sensei_create(sensei_ctx **out, int device) {
 }
 
 int sensei_destroy(sensei_ctx *ctx) {
-    if (ctx) for (hipEvent_t e : ctx->timer.events) (void)hipEventDestroy(e);
+    if (ctx) {
+        for (hipEvent_t e : ctx->timers.spmm.events) (void)hipEventDestroy(e);
+        for (hipEvent_t e : ctx->timers.gemm.events) (void)hipEventDestroy(e);
+    }
     delete ctx;
     return SENSEI_OK;
 }
 
 int sensei_profile_enable(sensei_ctx *ctx, int enable) {
     if (!ctx) return SENSEI_INVALID_ARGUMENT;
-    ctx->timer.enabled = enable != 0;
-    if (enable) ctx->timer.used = 0;
+    for (KernelTimer *t : {&ctx->timers.spmm, &ctx->timers.gemm}) {
+        t->enabled = enable != 0;
+        if (enable) t->used = 0;
+    }
     return SENSEI_OK;
 }
 
-int sensei_profile_read(sensei_ctx *ctx, float *ms_out, int capacity, int *count_out) {
+int sensei_profile_read(sensei_ctx *ctx, int kernel, float *ms_out, int capacity, int *count_out) {
     if (!ctx || !count_out || capacity < 0 || (capacity > 0 && !ms_out)) return SENSEI_INVALID_ARGUMENT;
-    const size_t pairs = ctx->timer.used / 2;
+    if (kernel != SENSEI_PROFILE_SPMM && kernel != SENSEI_PROFILE_GEMM) return SENSEI_INVALID_ARGUMENT;
+    KernelTimer &t = kernel == SENSEI_PROFILE_SPMM ? ctx->timers.spmm : ctx->timers.gemm;
+    const size_t pairs = t.used / 2;
     *count_out = (int)pairs;
     for (size_t p = 0; p < pairs && p < (size_t)capacity; ++p) {
-        if (hipEventSynchronize(ctx->timer.events[2 * p + 1]) != hipSuccess) return SENSEI_HIP_ERROR;
-        if (hipEventElapsedTime(&ms_out[p], ctx->timer.events[2 * p], ctx->timer.events[2 * p + 1]) != hipSuccess) return SENSEI_HIP_ERROR;
+        if (hipEventSynchronize(t.events[2 * p + 1]) != hipSuccess) return SENSEI_HIP_ERROR;
+        if (hipEventElapsedTime(&ms_out[p], t.events[2 * p], t.events[2 * p + 1]) != hipSuccess) return SENSEI_HIP_ERROR;
     }
     return SENSEI_OK;
 }
@@ -435,7 +444,7 @@ int sensei_spmm(sensei_ctx *ctx, const sensei_csr *A, int mode, const float *r, 
     SENSEI_TRY(launch_chunk_rows(*A, plan, as_stream(stream)));
     const bool scaled = (mode == SENSEI_SPMM_SCALED);
     return hip_status(launch_spmm(*A, mode, scaled ? r : nullptr, scaled ? c : nullptr, B.ptr, B.ld, f, C, ldc, f, activation, plan, carry,
-                                  as_stream(stream), &ctx->timer));
+                                  as_stream(stream), &ctx->timers.spmm));
 }
 
 int sensei_gemm(sensei_ctx *ctx, sensei_mat A, sensei_mat W, float *Y, int64_t ldy, int activation, void *stream) {
@@ -445,7 +454,8 @@ int sensei_gemm(sensei_ctx *ctx, sensei_mat A, sensei_mat W, float *Y, int64_t l
     if (A.rows > 0 && W.cols > 0 && !Y) return SENSEI_INVALID_ARGUMENT;
     const size_t ybytes = mat_bytes(Y, A.rows, W.cols, ldy);
     if (overlap(Y, ybytes, A.ptr, mat_bytes(A.ptr, A.rows, A.cols, A.ld)) || overlap(Y, ybytes, W.ptr, mat_bytes(W.ptr, W.rows, W.cols, W.ld))) return SENSEI_INVALID_ARGUMENT;
-    return hip_status(launch_gemm(A.ptr, A.ld, W.ptr, W.ld, Y, ldy, A.rows, (int)A.cols, (int)W.cols, (int)W.cols, activation, as_stream(stream)));
+    return hip_status(launch_gemm(A.ptr, A.ld, W.ptr, W.ld, Y, ldy, A.rows, (int)A.cols, (int)W.cols, (int)W.cols, activation, as_stream(stream), nullptr,
+                                  &ctx->timers.gemm));
 }
 
 int sensei_gemv2(sensei_ctx *ctx, sensei_mat A, const float *v1, const float *v2, float *y1, float *y2, void *stream) {
@@ -506,7 +516,7 @@ int sensei_gcn_layer(sensei_ctx *ctx, const sensei_csr *A, const float *r, const
         return SENSEI_INVALID_ARGUMENT;
     if (ws_bytes < gcn_ws(*A, (int)X.cols, (int)W.cols, comp_id)) return SENSEI_WORKSPACE_TOO_SMALL;
     if (A->n_rows == 0) return SENSEI_OK;
-    return run_gcn(*A, r, c, X, W, Y, ldy, activation, comp_id, workspace, ws_bytes, as_stream(stream), &ctx->timer);
+    return run_gcn(*A, r, c, X, W, Y, ldy, activation, comp_id, workspace, ws_bytes, as_stream(stream), &ctx->timers);
 }
 
 int sensei_gat_workspace(const sensei_csr *A, int f_in, int f_out, int comp_id, size_t *bytes) {
@@ -533,7 +543,7 @@ int sensei_gat_layer(sensei_ctx *ctx, const sensei_csr *A, sensei_mat X, sensei_
         return SENSEI_INVALID_ARGUMENT;
     if (ws_bytes < gat_ws(*A, (int)X.cols, (int)W.cols, comp_id)) return SENSEI_WORKSPACE_TOO_SMALL;
     if (A->n_rows == 0) return SENSEI_OK;
-    return run_gat(*A, X, W, a_l, a_r, neg_slope, Y, ldy, activation, comp_id, workspace, ws_bytes, as_stream(stream), &ctx->timer);
+    return run_gat(*A, X, W, a_l, a_r, neg_slope, Y, ldy, activation, comp_id, workspace, ws_bytes, as_stream(stream), &ctx->timers);
 }
 
 int sensei_select_workspace(int kind, const sensei_csr *A, int f_in, int f_out, size_t *bytes) {

@@ -192,8 +192,14 @@ __global__ __launch_bounds__(kThreads) void k_gemv2(const float *__restrict__ A,
 }  // namespace
 
 hipError_t launch_gemm(const float *A, int64_t lda, const float *W, int64_t ldw, float *Y, int64_t ldy, int64_t n,
-                       int k, int m, int m_store, int act, hipStream_t s, const float *row_scale) {
+                       int k, int m, int m_store, int act, hipStream_t s, const float *row_scale, KernelTimer *timer) {
     if (n <= 0 || m_store <= 0) return hipSuccess;
+    hipEvent_t t0 = timer ? timer->next() : nullptr, t1 = t0 ? timer->next() : nullptr;
+    if (t1 && hipEventRecord(t0, s) != hipSuccess) return hipErrorUnknown;
+    auto done = [&](hipError_t e) {
+        if (e == hipSuccess && t1 && hipEventRecord(t1, s) != hipSuccess) return hipErrorUnknown;
+        return e;
+    };
     GemmArgs g;
     g.row_scale = row_scale;
     g.A = A; g.W = W; g.Y = Y; g.lda = lda; g.ldw = ldw; g.ldy = ldy; g.n = n;
@@ -208,21 +214,21 @@ hipError_t launch_gemm(const float *A, int64_t lda, const float *W, int64_t ldw,
     const long long big_blocks = ((n + 127) / 128) * ((m_store + 127) / 128);
     if (m_store <= 32) {
         g.n_bn = 1;
-        if ((n + 255) / 256 >= 256) return gemm_launch_vec<256, 32, 4, 1>(g, avec, bvec, s);
+        if ((n + 255) / 256 >= 256) return done(gemm_launch_vec<256, 32, 4, 1>(g, avec, bvec, s));
         g.n_bn = (m_store + 63) / 64;
-        return gemm_launch_vec<64, 64, 2, 2>(g, avec, bvec, s);
+        return done(gemm_launch_vec<64, 64, 2, 2>(g, avec, bvec, s));
     }
     if (m_store <= 64) {
         g.n_bn = 1;
-        if ((n + 255) / 256 >= 256) return gemm_launch_vec<256, 64, 4, 1>(g, avec, bvec, s);
-        return gemm_launch_vec<64, 64, 2, 2>(g, avec, bvec, s);
+        if ((n + 255) / 256 >= 256) return done(gemm_launch_vec<256, 64, 4, 1>(g, avec, bvec, s));
+        return done(gemm_launch_vec<64, 64, 2, 2>(g, avec, bvec, s));
     }
     if (big_blocks >= 256) {
         g.n_bn = (m_store + 127) / 128;
-        return gemm_launch_vec<128, 128, 2, 2>(g, avec, bvec, s);
+        return done(gemm_launch_vec<128, 128, 2, 2>(g, avec, bvec, s));
     }
     g.n_bn = (m_store + 63) / 64;
-    return gemm_launch_vec<64, 64, 2, 2>(g, avec, bvec, s);
+    return done(gemm_launch_vec<64, 64, 2, 2>(g, avec, bvec, s));
 }
 
 hipError_t launch_gemv2(const float *A, int64_t lda, int64_t n, int k, const float *v1, const float *v2, float *y1,

@@ -25,7 +25,7 @@ int choose_chunk_nnz(int64_t nnz, int n_feature_tiles);
 size_t plan_bytes(int64_t nnz);  // upper bound over all chunk sizes
 hipError_t launch_chunk_rows(const sensei_csr &A, const ChunkPlan &p, hipStream_t s);
 
-// ---- optional timing of the SpMM kernel with HIP events on the launch stream
+// ---- optional timing of a kernel's launches with HIP events on the launch stream
 struct KernelTimer {
     bool enabled = false;
     size_t used = 0;                 // events handed out since the recording started
@@ -40,6 +40,10 @@ struct KernelTimer {
         }
         return events[used++];
     }
+};
+
+struct Timers {
+    KernelTimer spmm, gemm;
 };
 
 // ---- SpMM
@@ -78,7 +82,8 @@ size_t softmax_ws_bytes(const sensei_csr &A);
 // Y[0:n, 0:m_store) = act(row_scale[i] * (A[n x k] . W[k x m])); columns m..m_store are written as act(0);
 // row_scale may be null (no scaling).
 hipError_t launch_gemm(const float *A, int64_t lda, const float *W, int64_t ldw, float *Y, int64_t ldy, int64_t n,
-                       int k, int m, int m_store, int act, hipStream_t s, const float *row_scale = nullptr);
+                       int k, int m, int m_store, int act, hipStream_t s, const float *row_scale = nullptr,
+                       KernelTimer *timer = nullptr);
 hipError_t launch_gemv2(const float *A, int64_t lda, int64_t n, int k, const float *v1, const float *v2, float *y1,
                         float *y2, hipStream_t s);
 
