@@ -36,16 +36,6 @@ __global__ void k_chunk_rows(const int32_t *__restrict__ row_ptr, int n_rows, in
     chunk_row[c] = lo < n_rows ? lo : n_rows;
 }
 
-// row that holds non-zero k, searched among the rows a chunk touches
-__device__ __forceinline__ int find_row(const int32_t *__restrict__ row_ptr, int lo_i, int hi_i, int k) {
-    int a = lo_i, b = hi_i;  // first index in [lo_i, hi_i) with row_ptr[idx] > k
-    while (a < b) {
-        int mid = (a + b) >> 1;
-        if (row_ptr[mid] <= k) a = mid + 1; else b = mid;
-    }
-    return a - 1;
-}
-
 // ------------------------------------------------------------------------ SpMM
 
 template <int VEC> struct Vec;
@@ -387,26 +377,71 @@ struct NnzArgs {
     int n_rows, nnz, chunk_nnz, n_chunks;
 };
 
-__device__ __forceinline__ int row_of_nnz(const NnzArgs &a, int k) {
-    const int c = k / a.chunk_nnz;
-    const int i0 = a.chunk_row[c];
-    return find_row(a.row_ptr, i0 > 0 ? i0 - 1 : 0, a.chunk_row[c + 1], k);
+constexpr int kShortRowElem = 16;  // element-wise kernels: chunks whose rows average fewer non-zeros use one lane per row
+
+// Visits every non-zero of one chunk with one wavefront.  per_row(i) is evaluated once per row (piece) and its
+// result handed to per_nnz(k, row_data) for each non-zero k of that row inside the chunk.  Long rows: the
+// wavefront walks the rows (row data in scalar registers) and its lanes stride over the non-zeros, so loads
+// and stores are coalesced.  Short rows: one lane per row.  Either way no per-non-zero row search is needed.
+template <class PerRow, class PerNnz>
+__device__ __forceinline__ void walk_chunk(const NnzArgs &a, int chunk, int lane, PerRow per_row, PerNnz per_nnz) {
+    const long long lo_ll = (long long)chunk * a.chunk_nnz;
+    const int lo = (int)lo_ll;
+    const int hi = (int)((lo_ll + a.chunk_nnz < (long long)a.nnz) ? lo_ll + a.chunk_nnz : (long long)a.nnz);
+    if (lo >= hi) return;
+    const int i0 = a.chunk_row[chunk], i1 = a.chunk_row[chunk + 1];
+    const int i_first = (a.row_ptr[i0] > lo) ? i0 - 1 : i0;
+    if ((long long)(i1 - i_first) * kShortRowElem > (long long)(hi - lo)) {
+        for (int ib = i_first; ib < i1; ib += 64) {
+            const int row = ib + lane;
+            if (row < i1) {
+                int rs = a.row_ptr[row], re = a.row_ptr[row + 1];
+                rs = rs > lo ? rs : lo;
+                re = re < hi ? re : hi;
+                if (rs < re) {
+                    const auto rd = per_row(row);
+#pragma unroll 4
+                    for (int k = rs; k < re; ++k) per_nnz(k, rd);
+                }
+            }
+        }
+        return;
+    }
+    int i = __builtin_amdgcn_readfirstlane(i_first);
+    int pos = lo;
+    while (pos < hi) {
+        const int re = __builtin_amdgcn_readfirstlane(a.row_ptr[i + 1]);
+        if (re > pos) {
+            const int seg_hi = re < hi ? re : hi;
+            const auto rd = per_row(i);
+#pragma unroll 4
+            for (int k = pos + lane; k < seg_hi; k += 64) per_nnz(k, rd);
+            pos = seg_hi;
+        }
+        i = __builtin_amdgcn_readfirstlane(i + 1);
+    }
 }
 
-__global__ void k_sddmm_norm(NnzArgs a, const float *__restrict__ r, const float *__restrict__ c, float *__restrict__ val) {
-    long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= a.nnz) return;
-    const int k = (int)t;
-    val[k] = r[row_of_nnz(a, k)] * c[a.col_idx[k]];
+__device__ __forceinline__ int wave_chunk() {
+    return blockIdx.x * kWavesPerBlock + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+}
+
+__global__ __launch_bounds__(kBlock) void k_sddmm_norm(NnzArgs a, const float *__restrict__ r, const float *__restrict__ c,
+                                                        float *__restrict__ val) {
+    const int chunk = wave_chunk();
+    if (chunk >= a.n_chunks) return;
+    walk_chunk(a, chunk, threadIdx.x & 63, [&](int i) { return r[i]; },
+               [&](int k, float ri) { val[k] = ri * c[a.col_idx[k]]; });
 }
 
 __device__ __forceinline__ float leaky(float t, float slope) { return t > 0.f ? t : slope * t; }
 
-__global__ void k_score(NnzArgs a, const float *__restrict__ s_l, const float *__restrict__ s_r, float slope, float *__restrict__ e) {
-    long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= a.nnz) return;
-    const int k = (int)t;
-    e[k] = leaky(s_l[row_of_nnz(a, k)] + s_r[a.col_idx[k]], slope);
+__global__ __launch_bounds__(kBlock) void k_score(NnzArgs a, const float *__restrict__ s_l, const float *__restrict__ s_r, float slope,
+                                                   float *__restrict__ e) {
+    const int chunk = wave_chunk();
+    if (chunk >= a.n_chunks) return;
+    walk_chunk(a, chunk, threadIdx.x & 63, [&](int i) { return s_l[i]; },
+               [&](int k, float sl) { e[k] = leaky(sl + s_r[a.col_idx[k]], slope); });
 }
 
 template <int VEC>
@@ -466,6 +501,30 @@ __global__ __launch_bounds__(kBlock) void k_softmax_stats(SoftmaxArgs a) {
     int re = (i < a.n.n_rows) ? a.n.row_ptr[i + 1] : 0x7fffffff;
     float m = -INFINITY, z = 0.f;
 
+    // many short rows: one lane per row, no cross-lane reduction
+    const int i_first = cont ? i0 - 1 : i0;
+    if ((long long)(i1 - i_first) * kShortRowElem > (long long)(hi - lo)) {
+        for (int ib = i_first; ib < i1; ib += 64) {
+            const int row = ib + lane;
+            if (row >= i1) continue;
+            int rs = a.n.row_ptr[row], rend = a.n.row_ptr[row + 1];
+            rs = rs > lo ? rs : lo;
+            rend = rend < hi ? rend : hi;
+            float rm = -INFINITY, rz = 0.f;
+            const float sl = FROM_E ? 0.f : a.s_l[row];
+#pragma unroll 4
+            for (int k = rs; k < rend; ++k) {
+                float e;
+                if (FROM_E) e = a.e[k];
+                else { e = leaky(sl + a.s_r[a.n.col_idx[k]], a.slope); a.alpha[k] = e; }  // logit kept for the second pass
+                mz_add(rm, rz, e);
+            }
+            if (cont && row == i_first) a.carry[chunk] = make_float2(rm, rz);
+            else a.stats[row] = make_float2(rm, rz);
+        }
+        return;
+    }
+
     auto finish_row = [&]() {
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
@@ -485,8 +544,11 @@ __global__ __launch_bounds__(kBlock) void k_softmax_stats(SoftmaxArgs a) {
         const int seg_hi = re < hi ? re : hi;
         float sl = 0.f;
         if (!FROM_E) sl = a.s_l[i];
+#pragma unroll 4
         for (int k = pos + lane; k < seg_hi; k += 64) {
-            const float e = FROM_E ? a.e[k] : leaky(sl + a.s_r[a.n.col_idx[k]], a.slope);
+            float e;
+            if (FROM_E) e = a.e[k];
+            else { e = leaky(sl + a.s_r[a.n.col_idx[k]], a.slope); a.alpha[k] = e; }  // logit kept for the second pass
             mz_add(m, z, e);
         }
         pos = seg_hi;
@@ -516,15 +578,12 @@ __global__ void k_softmax_fixup(SoftmaxArgs a) {
     a.stats[i] = st;
 }
 
-template <bool FROM_E>
-__global__ void k_softmax_alpha(SoftmaxArgs a) {
-    long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= a.n.nnz) return;
-    const int k = (int)t;
-    const int i = row_of_nnz(a.n, k);
-    const float e = FROM_E ? a.e[k] : leaky(a.s_l[i] + a.s_r[a.n.col_idx[k]], a.slope);
-    const float2 st = a.stats[i];
-    a.alpha[k] = expf(e - st.x) / st.y;
+// alpha = exp(e - m_i) / z_i; `e` may be the alpha array itself (in place)
+__global__ __launch_bounds__(kBlock) void k_softmax_alpha(SoftmaxArgs a) {
+    const int chunk = wave_chunk();
+    if (chunk >= a.n.n_chunks) return;
+    walk_chunk(a.n, chunk, threadIdx.x & 63, [&](int i) { return a.stats[i]; },
+               [&](int k, const float2 &st) { a.alpha[k] = expf(a.e[k] - st.x) / st.y; });
 }
 
 inline unsigned blocks_for(long long n, int per_block) { return (unsigned)((n + per_block - 1) / per_block); }
@@ -643,12 +702,12 @@ hipError_t launch_norm_vectors(const int32_t *deg, int64_t n, float *out, hipStr
 }
 
 hipError_t launch_sddmm_norm(const sensei_csr &A, const float *r, const float *c, float *val, const ChunkPlan &p, hipStream_t s) {
-    if (A.nnz > 0) hipLaunchKernelGGL(k_sddmm_norm, dim3(blocks_for(A.nnz, kBlock)), dim3(kBlock), 0, s, nnz_args(A, p), r, c, val);
+    if (A.nnz > 0) hipLaunchKernelGGL(k_sddmm_norm, dim3(blocks_for(p.n_chunks, kWavesPerBlock)), dim3(kBlock), 0, s, nnz_args(A, p), r, c, val);
     return hipGetLastError();
 }
 
 hipError_t launch_score(const sensei_csr &A, const float *s_l, const float *s_r, float slope, float *e, const ChunkPlan &p, hipStream_t s) {
-    if (A.nnz > 0) hipLaunchKernelGGL(k_score, dim3(blocks_for(A.nnz, kBlock)), dim3(kBlock), 0, s, nnz_args(A, p), s_l, s_r, slope, e);
+    if (A.nnz > 0) hipLaunchKernelGGL(k_score, dim3(blocks_for(p.n_chunks, kWavesPerBlock)), dim3(kBlock), 0, s, nnz_args(A, p), s_l, s_r, slope, e);
     return hipGetLastError();
 }
 
@@ -677,9 +736,9 @@ hipError_t launch_softmax(const sensei_csr &A, const float *e, const float *s_l,
     else hipLaunchKernelGGL((k_softmax_stats<false>), g1, dim3(kBlock), 0, s, a);
     if (p.n_chunks > 1) hipLaunchKernelGGL(k_softmax_fixup, dim3(blocks_for(p.n_chunks - 1, kBlock)), dim3(kBlock), 0, s, a);
     if (A.nnz > 0) {
-        dim3 g3(blocks_for(A.nnz, kBlock));
-        if (e) hipLaunchKernelGGL((k_softmax_alpha<true>), g3, dim3(kBlock), 0, s, a);
-        else hipLaunchKernelGGL((k_softmax_alpha<false>), g3, dim3(kBlock), 0, s, a);
+        dim3 g3(blocks_for(p.n_chunks, kWavesPerBlock));
+        if (!e) a.e = alpha;  // the statistics pass parked the logits there
+        hipLaunchKernelGGL(k_softmax_alpha, g3, dim3(kBlock), 0, s, a);
     }
     return hipGetLastError();
 }
