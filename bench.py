@@ -233,6 +233,19 @@ def main():
         detail["select_timed"] = {"layer": tag(0), "pick": name_of(0, idt), "overhead_ms": round(dt, 3),
                                   "overhead_in_layers": round(dt / detail["layers"][tag(0)]["ms"], 2)}
 
+    # ---- launch-bound workloads: the same step captured once in a HIP graph and replayed
+    if N <= 50_000:
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        with torch.cuda.graph(graph):
+            step()
+        detail["graph_replay_ms_per_layer"] = round(time_fn(graph.replay, 50) / len(layers), 5)
+        detail["eager_ms_per_layer"] = round(time_fn(step, 50) / len(layers), 5)
+
     # ---- CPU baseline: the fp64 oracle as it stands, one thread, on a bounded sample of output rows of every layer,
     # extrapolated by row count.  Hidden inputs are seeded stand-ins so that nothing from the GPU reaches the oracle.
     cpu = None

@@ -602,8 +602,10 @@ NnzArgs nnz_args(const sensei_csr &A, const ChunkPlan &p) {
 int choose_chunk_nnz(int64_t nnz, int) {
     if (nnz >= (1LL << 24)) return 2048;
     if (nnz >= (1LL << 21)) return 1024;
-    if (nnz >= (1LL << 18)) return 512;
-    return 256;
+    if (nnz >= (1LL << 19)) return 512;
+    if (nnz >= (1LL << 18)) return 256;
+    if (nnz >= (1LL << 17)) return 128;
+    return 64;  // small graphs are latency bound: more, shorter wavefronts
 }
 
 static int n_chunks_for(int64_t nnz, int t) { return nnz <= 0 ? 1 : (int)((nnz + t - 1) / t); }

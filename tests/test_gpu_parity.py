@@ -25,7 +25,7 @@ def ctx():
 
 
 def _graphs():
-    """Small graphs that still span several chunks (256 non-zeros each) and leave a ragged tail."""
+    """Small graphs that still span several chunks (64 non-zeros each at this size) and leave a ragged tail."""
     return {
         "er": synth.erdos_renyi(2, 700, 2600),
         "rmat_hub": synth.rmat(3, 3000, 40_000),             # hub rows cross several chunks
@@ -218,6 +218,15 @@ def test_gat_layer_all_compositions(ctx, name, f_in, f_out):
     _gat_case(ctx, g, f_in, f_out, ACT_NONE, 5, scale=1.0)
 
 
+@pytest.mark.parametrize("n,draws,lo,hi", [(8000, 110_000, 1 << 17, 1 << 18), (15000, 230_000, 1 << 18, 1 << 19),
+                                             (40000, 700_000, 1 << 19, 1 << 21)])
+def test_graphs_in_the_128_256_and_512_entry_chunk_ranges(ctx, n, draws, lo, hi):
+    g = synth.rmat(13, n, draws)
+    assert lo <= g.nnz < hi
+    _gcn_case(ctx, g, 24, 40, ACT_RELU, 8)
+    _gat_case(ctx, g, 40, 24, ACT_NONE, 9)
+
+
 def test_mid_size_graph_with_larger_chunks(ctx):
     """~2.6M non-zeros: 1024-entry chunks, hub rows over many chunks; full oracle still takes seconds."""
     g = synth.rmat(11, 50_000, 1_600_000)
@@ -289,3 +298,47 @@ def test_error_paths_launch_nothing(ctx):
     st = binding.lib().sensei_gat_layer(ctx._h, ctypes.byref(A.s), binding.mat_struct(X), binding.mat_struct(W), None, None, 0.2,
                                         Y.data_ptr(), 4, 0, 0, ws.data_ptr(), 1024, None)
     assert st == 1
+
+
+# ------------------------------------------------------------------ graph capture
+
+def test_layers_can_be_captured_in_a_hip_graph(ctx):
+    """The layer calls only enqueue kernels on the given stream (no allocation, no synchronisation, no memset
+    nodes), so a launch-bound loop can be captured once and replayed; every replay must equal the eager result."""
+    g = GRAPHS["rmat_hub"]
+    A = DeviceCSR(g)
+    dr, dc = ctx.degrees(A.s)
+    r, c = ctx.norm_vectors(dr), ctx.norm_vectors(dc)
+    X = dev(synth.uniform(3, 10, (g.n_cols, 64)))
+    W1, W2 = dev(synth.glorot(3, 11, 64, 32)), dev(synth.glorot(3, 12, 32, 16))
+    a_l, a_r = dev(synth.normal(3, 13, (16,), 0.0, 0.1)), dev(synth.normal(3, 14, (16,), 0.0, 0.1))
+    H = torch.empty((g.n_rows, 32), device=DEV)
+    Y = torch.empty((g.n_rows, 16), device=DEV)
+
+    def chain():
+        ctx.gcn_layer(A.s, r, c, X, W1, 3, ACT_RELU, out=H)
+        ctx.gat_layer(A.s, H, W2, a_l, a_r, 0, 0.2, ACT_NONE, out=Y)
+
+    chain()  # sizes the workspace before capture
+    torch.cuda.synchronize()
+    want = Y.clone()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        chain()
+    torch.cuda.current_stream().wait_stream(side)
+    with torch.cuda.graph(graph):
+        chain()
+    for rep in range(3):
+        Y.fill_(-1.0)
+        H.fill_(-1.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(Y, want), f"replay {rep}"
+        # eager work between replays
+        X.mul_(1.0)
+        chain()
+        torch.cuda.synchronize()
+        assert torch.equal(Y, want)
