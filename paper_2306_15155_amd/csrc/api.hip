@@ -68,7 +68,7 @@ size_t sparse_ws(const sensei_csr &A, int f) {
 
 ChunkPlan make_plan(const sensei_csr &A, Carver &cv) {
     ChunkPlan p;
-    p.chunk_nnz = choose_chunk_nnz(A.nnz, 1);
+    p.chunk_nnz = choose_chunk_nnz(A.nnz);
     p.n_chunks = A.nnz <= 0 ? 1 : (int)((A.nnz + p.chunk_nnz - 1) / p.chunk_nnz);
     p.chunk_row = cv.take<int32_t>((size_t)p.n_chunks + 1);
     return p;

@@ -21,7 +21,7 @@ struct ChunkPlan {
     int32_t *chunk_row;   // device, n_chunks + 1: first row starting at or after c*T; [n_chunks] = n_rows
 };
 
-int choose_chunk_nnz(int64_t nnz, int n_feature_tiles);
+int choose_chunk_nnz(int64_t nnz);
 size_t plan_bytes(int64_t nnz);  // upper bound over all chunk sizes
 hipError_t launch_chunk_rows(const sensei_csr &A, const ChunkPlan &p, hipStream_t s);
 

@@ -599,7 +599,7 @@ NnzArgs nnz_args(const sensei_csr &A, const ChunkPlan &p) {
 
 // ----------------------------------------------------------------- host side
 
-int choose_chunk_nnz(int64_t nnz, int) {
+int choose_chunk_nnz(int64_t nnz) {
     if (nnz >= (1LL << 24)) return 2048;
     if (nnz >= (1LL << 21)) return 1024;
     if (nnz >= (1LL << 19)) return 512;
@@ -611,7 +611,7 @@ int choose_chunk_nnz(int64_t nnz, int) {
 static int n_chunks_for(int64_t nnz, int t) { return nnz <= 0 ? 1 : (int)((nnz + t - 1) / t); }
 
 size_t plan_bytes(int64_t nnz) {
-    return align_up(((size_t)n_chunks_for(nnz, choose_chunk_nnz(nnz, 1)) + 1) * sizeof(int32_t), 256);
+    return align_up(((size_t)n_chunks_for(nnz, choose_chunk_nnz(nnz)) + 1) * sizeof(int32_t), 256);
 }
 
 hipError_t launch_chunk_rows(const sensei_csr &A, const ChunkPlan &p, hipStream_t s) {
@@ -643,7 +643,7 @@ SpmmShape spmm_shape(const float *B, int64_t ldb, int f) {
 }
 
 size_t spmm_carry_bytes(int64_t nnz, int f) {
-    const int t = choose_chunk_nnz(nnz, 1);
+    const int t = choose_chunk_nnz(nnz);
     // tiles are at most 256 floats wide, so the padded width stays below f + 256
     const size_t f_carry = align_up((size_t)(f > 0 ? f : 1), 32) + 256;
     return align_up((size_t)n_chunks_for(nnz, t) * f_carry * sizeof(float), 256);
@@ -724,7 +724,7 @@ hipError_t launch_row_broadcast(const float *s_vec, const float *X, int64_t ldx,
 }
 
 size_t softmax_ws_bytes(const sensei_csr &A) {
-    const int t = choose_chunk_nnz(A.nnz, 1);
+    const int t = choose_chunk_nnz(A.nnz);
     return align_up((size_t)(A.n_rows + 1) * sizeof(float2), 256) + align_up((size_t)n_chunks_for(A.nnz, t) * sizeof(float2), 256);
 }
 

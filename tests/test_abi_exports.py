@@ -36,3 +36,35 @@ def test_status_strings_and_names_need_no_gpu():
     assert binding.num_compositions(binding.KIND_GCN) == 6 and binding.num_compositions(binding.KIND_GAT) == 4
     assert [binding.composition_name(0, i) for i in range(6)] == list(binding.GCN_NAMES)
     assert [binding.composition_name(1, i) for i in range(4)] == list(binding.GAT_NAMES)
+
+
+def test_host_only_queries_and_argument_checks_need_no_gpu():
+    """Workspace queries are pure host arithmetic; a call with a null context is rejected before any HIP call."""
+    import ctypes as C
+    from paper_2306_15155_amd import binding
+    L = binding.lib()
+    A = binding.CsrStruct(1000, 1000, 50_000, 0x1000, 0x2000, None)  # pointers are never dereferenced by the queries
+    n = C.c_size_t()
+    sizes = {}
+    for cid in range(6):
+        assert L.sensei_gcn_workspace(C.byref(A), 64, 32, cid, C.byref(n)) == 0
+        sizes[cid] = n.value
+        assert n.value > 0 and n.value % 256 == 0
+    assert sizes[0] > sizes[2]                      # the unfused dynamic composition holds c (x) X as well
+    assert L.sensei_gcn_workspace(C.byref(A), 64, 32, 6, C.byref(n)) == 2
+    assert L.sensei_gcn_workspace(C.byref(A), 0, 32, 0, C.byref(n)) == 1
+    assert L.sensei_gcn_workspace(None, 64, 32, 0, C.byref(n)) == 1
+    for cid in range(4):
+        assert L.sensei_gat_workspace(C.byref(A), 64, 32, cid, C.byref(n)) == 0 and n.value > 0
+    assert L.sensei_gat_workspace(C.byref(A), 64, 32, 4, C.byref(n)) == 2
+    assert L.sensei_sparse_workspace(C.byref(A), 128, C.byref(n)) == 0 and n.value > 0
+    assert L.sensei_select_workspace(0, C.byref(A), 64, 32, C.byref(n)) == 0 and n.value > sizes[0]
+    assert L.sensei_select_workspace(7, C.byref(A), 64, 32, C.byref(n)) == 1
+    bad = binding.CsrStruct(-1, 10, 0, 0x1000, None, None)
+    assert L.sensei_gcn_workspace(C.byref(bad), 64, 32, 0, C.byref(n)) == 1
+    # null context: rejected on the host
+    cid = C.c_int(-1)
+    assert L.sensei_select(None, 0, C.byref(A), 64, 32, 0, C.byref(cid), None, None, 0, None) == 1
+    assert L.sensei_degrees(None, C.byref(A), None, None, None) == 1
+    assert L.sensei_profile_enable(None, 1) == 1
+    assert L.sensei_destroy(None) == 0
