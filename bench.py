@@ -51,7 +51,7 @@ def parse_args():
 def main():
     args = parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (--gpus 1); multi-GPU sharding is a design note in DESIGN.md",
+        print("bench.py: this build runs on one GPU only; pass --gpus 1 (there is no multi-GPU path to measure)",
               file=sys.stderr)
         sys.exit(2)
 

@@ -77,7 +77,7 @@ ChunkPlan make_plan(const sensei_csr &A, Carver &cv) {
 bool gcn_is_agg(int id) { return id == SENSEI_GCN_DYN_AGG || id == SENSEI_GCN_DYNF_AGG || id == SENSEI_GCN_PRE_AGG; }
 
 size_t gcn_ws(const sensei_csr &A, int f_in, int f_out, int id) {
-    const int fs = gcn_is_agg(id) ? pad4(f_in) : pad4(f_out);
+    const int fs = gcn_is_agg(id) ? pad4(f_in) : pad32(f_out);
     size_t b = plan_bytes(A.nnz) + spmm_carry_bytes(A.nnz, fs);
     if (gcn_is_agg(id)) {
         b += align_up((size_t)A.n_rows * fs * sizeof(float), 256);                                    // U
@@ -91,7 +91,7 @@ size_t gcn_ws(const sensei_csr &A, int f_in, int f_out, int id) {
 bool gat_is_reuse(int id) { return id == SENSEI_GAT_REUSE || id == SENSEI_GAT_REUSE_FOLD; }
 
 size_t gat_ws(const sensei_csr &A, int f_in, int f_out, int id) {
-    const int fo = pad4(f_out), fi = pad4(f_in);
+    const int fo = pad32(f_out), fi = pad4(f_in);
     size_t b = plan_bytes(A.nnz) + softmax_ws_bytes(A);
     b += 2 * align_up((size_t)A.n_cols * sizeof(float), 256);                  // s_l, s_r
     b += align_up((size_t)(A.nnz > 0 ? A.nnz : 1) * sizeof(float), 256);       // alpha
@@ -139,7 +139,7 @@ int run_gcn(const sensei_csr &A, const float *r, const float *c, const sensei_ma
         if (id == SENSEI_GCN_DYN_AGG) SENSEI_TRY(launch_row_broadcast(r, U, fs, A.n_rows, f_in, U, fs, SENSEI_ACT_NONE, s));
         SENSEI_TRY(launch_gemm(U, fs, W.ptr, W.ld, Y, ldy, A.n_rows, f_in, f_out, f_out, act, s, nullptr, gt));
     } else {
-        const int fs = pad4(f_out);
+        const int fs = pad32(f_out);
         float *carry = cv.take<float>(spmm_carry_bytes(A.nnz, fs) / sizeof(float));
         float *Z = cv.take<float>((size_t)A.n_cols * fs);
         // DYNF_UPD: the column scaling is a row broadcast on Z = X.W, fused into the GEMM epilogue; the row
@@ -163,7 +163,7 @@ int run_gat(const sensei_csr &A, const sensei_mat &X, const sensei_mat &W, const
             float slope, float *Y, int64_t ldy, int act, int id, void *ws, size_t ws_bytes, hipStream_t s, Timers *tm) {
     KernelTimer *kt = tm ? &tm->spmm : nullptr, *gt = tm ? &tm->gemm : nullptr;
     const int f_in = (int)X.cols, f_out = (int)W.cols;
-    const int fo = pad4(f_out), fi = pad4(f_in);
+    const int fo = pad32(f_out), fi = pad4(f_in);
     Carver cv(ws, ws_bytes);
     ChunkPlan plan = make_plan(A, cv);
     float2 *stats = cv.take<float2>((size_t)A.n_rows + 1);
@@ -399,7 +399,7 @@ int sensei_norm_vectors(sensei_ctx *ctx, const int32_t *deg, int64_t n, float *o
 
 int sensei_sparse_workspace(const sensei_csr *A, int f, size_t *bytes) {
     if (!csr_ok(A, false) || f < 0 || !bytes) return SENSEI_INVALID_ARGUMENT;
-    *bytes = sparse_ws(*A, pad4(f));
+    *bytes = sparse_ws(*A, pad32(f));
     return SENSEI_OK;
 }
 

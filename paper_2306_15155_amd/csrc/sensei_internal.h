@@ -89,5 +89,7 @@ hipError_t launch_gemv2(const float *A, int64_t lda, int64_t n, int k, const flo
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline int pad4(int f) { return (f + 3) & ~3; }
+// width of an internal matrix that an SpMM gathers from: rows start on 128-byte lines and fill whole feature tiles
+inline int pad32(int f) { return (f + 31) & ~31; }
 
 }  // namespace sensei
