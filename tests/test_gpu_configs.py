@@ -153,3 +153,37 @@ def test_config5_sampled_minibatch(ctx, products_like):
         for cid2 in range(6):
             Y = ctx.gcn_layer(A2p.s if cid2 >= 4 else A2.s, r2, c2, H1, dev(W2), cid2, ACT_NONE)
             assert_close(Y, Y_ref, what=f"C5 chain comps {cid1},{cid2}")
+
+
+def _time_ms(fn, iters=3):
+    fn()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(iters):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / iters
+
+
+@pytest.mark.parametrize("kind,f_in,f_out", [("gcn", 602, 256), ("gcn", 256, 41), ("gcn", 32, 256), ("gat", 602, 256), ("gat", 64, 256)])
+def test_selector_pick_is_within_ten_percent_of_the_fastest(ctx, reddit_like, kind, f_in, f_out):
+    """Acceptance bar for the cost model on the Reddit-shaped graph (milliseconds per layer, so timing noise is small)."""
+    g, A = reddit_like
+    N = g.n_rows
+    X = dev(synth.uniform(7, 60, (N, f_in)))
+    W = dev(synth.glorot(7, 61, f_in, f_out))
+    Y = torch.empty((N, f_out), device=DEV)
+    if kind == "gcn":
+        r, c, Apre, _ = _norm(ctx, A)
+        pick, est = ctx.select(KIND_GCN, A.s, f_in, f_out, SELECT_MODEL)
+        run = lambda cid: ctx.gcn_layer(Apre.s if cid >= 4 else A.s, r, c, X, W, cid, ACT_RELU, out=Y)
+    else:
+        a_l, a_r = dev(synth.normal(7, 62, (f_out,), 0.0, 0.1)), dev(synth.normal(7, 63, (f_out,), 0.0, 0.1))
+        pick, est = ctx.select(KIND_GAT, A.s, f_in, f_out, SELECT_MODEL)
+        run = lambda cid: ctx.gat_layer(A.s, X, W, a_l, a_r, cid, 0.2, ACT_RELU, out=Y)
+    allowed = [cid for cid, t in enumerate(est) if t >= 0]
+    assert set(allowed) == set(oracle.select_rules(kind, f_in, f_out))
+    ms = {cid: _time_ms(lambda: run(cid)) for cid in allowed}
+    assert ms[pick] <= 1.10 * min(ms.values()) + 0.02, (pick, ms)
