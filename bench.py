@@ -43,6 +43,8 @@ def parse_args():
     ap.add_argument("--workload", default="c2_rmat233k", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true", help="skip timing every composition id")
+    ap.add_argument("--no-panels", action="store_true", help="do not build the column-panel copy of the graph")
+    ap.add_argument("--panels", type=int, default=0, help="force the number of column panels (0 = let the library choose)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run four 1 GiB device-to-device copies (a kernel of known traffic, for scaling rocprofv3 --pmc byte counters)")
     return ap.parse_args()
@@ -59,7 +61,8 @@ def main():
     import torch
 
     import synth
-    from paper_2306_15155_amd import (GAT_NAMES, GCN_NAMES, KIND_GAT, KIND_GCN, SELECT_MODEL, SELECT_TIMED, Context, csr_struct)
+    from paper_2306_15155_amd import (GAT_NAMES, GCN_NAMES, KIND_GAT, KIND_GCN, SELECT_MODEL, SELECT_TIMED, Context, Panels,
+                                      csr_struct)
 
     wl = WORKLOADS[args.workload]
     layers = wl["layers"]
@@ -94,7 +97,15 @@ def main():
     e1.record()
     torch.cuda.synchronize()
     setup_ms = e0.elapsed_time(e1)
-    Apre = csr_struct(N, N, row_ptr, col_idx, ntil)
+    # optional column-panel copy of the pattern (the library decides from the graph whether to cut it at all)
+    panels, panels_ms = None, 0.0
+    if not args.no_panels:
+        tp = time.perf_counter()
+        panels = Panels(ctx, A, args.panels)
+        torch.cuda.synchronize()
+        panels_ms = (time.perf_counter() - tp) * 1e3
+        A = csr_struct(N, N, row_ptr, col_idx, None, panels)
+    Apre = csr_struct(N, N, row_ptr, col_idx, ntil, panels)
 
     # ---- composition choice per layer (cost model: host arithmetic only)
     ts = time.perf_counter()
@@ -212,7 +223,8 @@ def main():
 
     detail = {"layers": {tag(i): {"id": name_of(i), "ms": round(time_fn(lambda: run_layer(i, ids[i])), 4),
                                   "spmm_kernel_ms": round(spmm_mean[i], 4) if spmm_mean else None} for i in range(len(layers))},
-              "gemm": gemm_info, "setup_ms": round(setup_ms, 4), "select_model_ms": round(select_model_ms, 4),
+              "gemm": gemm_info, "setup_ms": round(setup_ms, 4), "column_panels": None if panels is None else panels.count,
+              "column_panels_build_ms": round(panels_ms, 3), "select_model_ms": round(select_model_ms, 4),
               "graph": {"nodes": N, "nnz": nnz, "max_degree": int(np.diff(g.row_ptr).max()), "generate_s": round(gen_s, 2)}}
     if not args.no_sweep:
         sweep, regret = {}, {}

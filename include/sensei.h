@@ -44,6 +44,8 @@ typedef enum {
 
 typedef struct sensei_ctx sensei_ctx; /* opaque: device id and cost-model calibration only */
 
+typedef struct sensei_panels sensei_panels; /* opaque host object: column-panel copy of a pattern, see below */
+
 typedef struct {
     int32_t n_rows, n_cols;
     int64_t nnz;
@@ -51,6 +53,7 @@ typedef struct {
     const int32_t *col_idx; /* device, nnz */
     const float *val;       /* device, nnz, or NULL: unweighted, only the positions are used
                                (matrix attribute table: sparse weighted / unweighted) */
+    const sensei_panels *panels; /* host, optional (NULL: none): made by sensei_panels_create for this very pattern */
 } sensei_csr;
 
 typedef struct {
@@ -104,6 +107,25 @@ int sensei_profile_read(sensei_ctx *ctx, int kernel, float *ms_out, int capacity
 int sensei_num_compositions(int kind);
 const char *sensei_composition_name(int kind, int comp_id);
 const char *sensei_status_string(int status);
+
+/* Optional, once per graph: a copy of the pattern cut into column panels (columns [q*w, (q+1)*w) of panel q
+ * stored contiguously, with the position of every entry in the original pattern).  When a sensei_csr carries
+ * it, wide SpMMs (128 features and more) run one panel after the other and add the partial results, so the
+ * neighbour rows of the live panel stay resident in the L2s; results are the same up to fp32 summation order.
+ * Not a step of the paper's method: a graph-dependent layout choice in the spirit of its input-sensitive
+ * selection.  n_panels = 0 lets the library choose from the graph features (it may choose 1 = no panels, in
+ * which case the object is ignored by the layer calls); 1..8 forces a count.
+ *   sensei_panels_bytes : device bytes sensei_panels_create needs for this pattern (host pointers).
+ *   sensei_panels_create: builds the copy in `device_buf` (caller-owned device memory, must stay alive and
+ *                         unmodified as long as the object is used); A->row_ptr / A->col_idx must stay
+ *                         unchanged too.  Synchronises `stream` once.  *out is a host object.
+ *   sensei_panels_count : number of panels of the object.
+ *   sensei_panels_destroy frees the host object only. */
+int sensei_panels_bytes(const sensei_csr *A, int n_panels, size_t *device_bytes);
+int sensei_panels_create(sensei_ctx *ctx, const sensei_csr *A, int n_panels, void *device_buf, size_t bytes, void *stream,
+                         sensei_panels **out);
+int sensei_panels_count(const sensei_panels *panels);
+int sensei_panels_destroy(sensei_panels *panels);
 
 /* ------------------------------------------------- primitives (steps of a layer) */
 

@@ -27,7 +27,8 @@ EXPORTS = (
     "sensei_status_string", "sensei_degrees", "sensei_norm_vectors", "sensei_sparse_workspace", "sensei_gcn_precompute",
     "sensei_row_broadcast", "sensei_spmm", "sensei_gemm", "sensei_gemv2", "sensei_sddmm_score", "sensei_edge_softmax",
     "sensei_gcn_workspace", "sensei_gcn_layer", "sensei_gat_workspace", "sensei_gat_layer", "sensei_select_workspace",
-    "sensei_select", "sensei_profile_enable", "sensei_profile_read",
+    "sensei_select", "sensei_profile_enable", "sensei_profile_read", "sensei_panels_bytes", "sensei_panels_create",
+    "sensei_panels_count", "sensei_panels_destroy",
 )
 
 
@@ -39,7 +40,7 @@ class SenseiError(RuntimeError):
 
 class CsrStruct(ctypes.Structure):
     _fields_ = [("n_rows", ctypes.c_int32), ("n_cols", ctypes.c_int32), ("nnz", ctypes.c_int64),
-                ("row_ptr", ctypes.c_void_p), ("col_idx", ctypes.c_void_p), ("val", ctypes.c_void_p)]
+                ("row_ptr", ctypes.c_void_p), ("col_idx", ctypes.c_void_p), ("val", ctypes.c_void_p), ("panels", ctypes.c_void_p)]
 
 
 class MatStruct(ctypes.Structure):
@@ -82,6 +83,10 @@ def lib():
         L.sensei_gat_layer.argtypes = [vp, P(CsrStruct), MatStruct, MatStruct, vp, vp, f32, vp, i64, i32, i32, vp, sz, vp]
         L.sensei_select_workspace.argtypes = [i32, P(CsrStruct), i32, i32, P(sz)]
         L.sensei_select.argtypes = [vp, i32, P(CsrStruct), i32, i32, i32, P(ctypes.c_int), P(f32), vp, sz, vp]
+        L.sensei_panels_bytes.argtypes = [P(CsrStruct), i32, P(sz)]
+        L.sensei_panels_create.argtypes = [vp, P(CsrStruct), i32, vp, sz, vp, P(vp)]
+        L.sensei_panels_count.argtypes = [vp]
+        L.sensei_panels_destroy.argtypes = [vp]
         L.sensei_profile_enable.argtypes = [vp, i32]
         L.sensei_profile_read.argtypes = [vp, i32, P(f32), i32, P(ctypes.c_int)]
         for name in EXPORTS:
@@ -116,11 +121,40 @@ def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
-def csr_struct(n_rows, n_cols, row_ptr, col_idx, val=None) -> CsrStruct:
+def csr_struct(n_rows, n_cols, row_ptr, col_idx, val=None, panels=None) -> CsrStruct:
     assert row_ptr.dtype == torch.int32 and col_idx.dtype == torch.int32
     assert val is None or val.dtype == torch.float32
     return CsrStruct(n_rows, n_cols, int(col_idx.numel()), row_ptr.data_ptr(), col_idx.data_ptr() if col_idx.numel() else None,
-                     None if val is None else val.data_ptr())
+                     None if val is None else val.data_ptr(), None if panels is None else panels.handle)
+
+
+class Panels:
+    """Column-panel copy of a pattern (sensei_panels_create); owns the device buffer it lives in."""
+
+    def __init__(self, ctx: "Context", A: CsrStruct, n_panels: int = 0):
+        need = ctypes.c_size_t()
+        _check(lib().sensei_panels_bytes(ctypes.byref(A), n_panels, ctypes.byref(need)), "sensei_panels_bytes")
+        self.buf = torch.empty(need.value + 256, dtype=torch.uint8, device=ctx.device)
+        p = (self.buf.data_ptr() + 255) // 256 * 256
+        self._h = ctypes.c_void_p()
+        _check(lib().sensei_panels_create(ctx._h, ctypes.byref(A), n_panels, ctypes.c_void_p(p), need.value, _stream(),
+                                          ctypes.byref(self._h)), "sensei_panels_create")
+        self.count = lib().sensei_panels_count(self._h)
+
+    @property
+    def handle(self):
+        return self._h.value
+
+    def close(self):
+        if self._h:
+            lib().sensei_panels_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 def mat_struct(t: torch.Tensor) -> MatStruct:

@@ -20,6 +20,20 @@ struct sensei_ctx {
     Timers timers;         // optional per-launch timing of the SpMM and GEMM kernels
 };
 
+// Column-panel copy of a pattern (host descriptor; the arrays live in the caller's device buffer).
+struct sensei_panels {
+    int n_panels, width;
+    int32_t n_rows, n_cols;
+    int64_t nnz;
+    const int32_t *src_row_ptr, *src_col_idx;  // the pattern it was built from
+    int chunk_nnz;                             // every panel uses the chunk size of the whole pattern
+    int64_t nnz_q[SENSEI_MAX_PANELS];
+    int32_t *row_ptr_q[SENSEI_MAX_PANELS], *col_q[SENSEI_MAX_PANELS], *chunk_row_q[SENSEI_MAX_PANELS];
+    int32_t *position;                         // position[k]: where original entry k sits in the panel copy
+    int32_t off_q[SENSEI_MAX_PANELS + 1];      // first entry of each panel in the copy
+    int n_chunks_q[SENSEI_MAX_PANELS];
+};
+
 namespace {
 
 const char *kGcnNames[] = {"DYN_AGG", "DYN_UPD", "DYNF_AGG", "DYNF_UPD", "PRE_AGG", "PRE_UPD"};
@@ -94,7 +108,7 @@ size_t gat_ws(const sensei_csr &A, int f_in, int f_out, int id) {
     const int fo = pad32(f_out), fi = pad4(f_in);
     size_t b = plan_bytes(A.nnz) + softmax_ws_bytes(A);
     b += 2 * align_up((size_t)A.n_cols * sizeof(float), 256);                  // s_l, s_r
-    b += align_up((size_t)(A.nnz > 0 ? A.nnz : 1) * sizeof(float), 256);       // alpha
+    b += 2 * align_up((size_t)(A.nnz > 0 ? A.nnz : 1) * sizeof(float), 256);   // alpha, logits (panel order only)
     b += 2 * align_up((size_t)fi * sizeof(float), 256);                        // W.a_l, W.a_r
     if (id != SENSEI_GAT_RECOMP_FOLD) b += align_up((size_t)A.n_cols * fo * sizeof(float), 256);  // Theta
     if (gat_is_reuse(id)) {
@@ -111,6 +125,50 @@ size_t gat_ws(const sensei_csr &A, int f_in, int f_out, int id) {
         hipError_t e__ = (expr);                          \
         if (e__ != hipSuccess) return SENSEI_HIP_ERROR;   \
     } while (0)
+
+int auto_panels(const sensei_csr &A) {
+    const double slice = (double)A.n_cols * 128.0;  // one 128-byte feature slice of the gathered matrix
+    const double avg = A.n_rows > 0 ? (double)A.nnz / A.n_rows : 0.0;
+    if (slice < 12e6 || avg < 128.0) return 1;
+    // two panels measured best at a 30 MB slice (6.7 ms against 6.8 with three, 7.2 with four, 7.5 without);
+    // larger slices get one panel more per 40 MB
+    const int q = 2 + (int)(slice / 40e6);
+    return q > 4 ? 4 : q;
+}
+
+bool panels_usable(const sensei_csr &A, int f) {
+    const sensei_panels *p = A.panels;
+    return p && p->n_panels > 1 && f >= 128 && p->src_row_ptr == A.row_ptr && p->src_col_idx == A.col_idx && p->nnz == A.nnz &&
+           p->n_rows == A.n_rows && p->n_cols == A.n_cols;
+}
+
+// SpMM over the whole pattern, or panel after panel when the matrix carries a usable panel copy.  Values
+// (WEIGHTED) can only follow the panels if they are stored in panel order (val_in_panel_order); values in the
+// order of the original pattern use the single pass.
+hipError_t spmm_any(const sensei_csr &A, int mode, const float *r, const float *c, const float *B, int64_t ldb, int f, float *C,
+                    int64_t ldc, int f_store, int act, const ChunkPlan &plan, float *carry, hipStream_t s, KernelTimer *kt,
+                    bool val_in_panel_order = false) {
+    if (!panels_usable(A, f) || (mode == SENSEI_SPMM_WEIGHTED && !val_in_panel_order))
+        return launch_spmm(A, mode, r, c, B, ldb, f, C, ldc, f_store, act, plan, carry, s, kt);
+    const sensei_panels &P = *A.panels;
+    hipEvent_t t0 = kt ? kt->next() : nullptr, t1 = t0 ? kt->next() : nullptr;
+    if (t1 && hipEventRecord(t0, s) != hipSuccess) return hipErrorUnknown;
+    for (int q = 0; q < P.n_panels; ++q) {
+        sensei_csr Aq = A;
+        Aq.nnz = P.nnz_q[q];
+        Aq.row_ptr = P.row_ptr_q[q];
+        Aq.col_idx = P.col_q[q];
+        if (Aq.val) Aq.val = A.val + P.off_q[q];
+        ChunkPlan pq;
+        pq.chunk_nnz = P.chunk_nnz;
+        pq.n_chunks = P.n_chunks_q[q];
+        pq.chunk_row = P.chunk_row_q[q];
+        const hipError_t e = launch_spmm(Aq, mode, r, c, B, ldb, f, C, ldc, f_store, act, pq, carry, s, nullptr, q > 0, q == P.n_panels - 1);
+        if (e != hipSuccess) return e;
+    }
+    if (t1 && hipEventRecord(t1, s) != hipSuccess) return hipErrorUnknown;
+    return hipSuccess;
+}
 
 int run_gcn(const sensei_csr &A, const float *r, const float *c, const sensei_mat &X, const sensei_mat &W, float *Y,
             int64_t ldy, int act, int id, void *ws, size_t ws_bytes, hipStream_t s, Timers *tm) {
@@ -135,7 +193,7 @@ int run_gcn(const sensei_csr &A, const float *r, const float *c, const sensei_ma
             ld_src = fs;
         }
         const bool scaled = (mode == SENSEI_SPMM_SCALED);
-        SENSEI_TRY(launch_spmm(A, mode, scaled ? r : nullptr, scaled ? c : nullptr, src, ld_src, f_in, U, fs, f_in, SENSEI_ACT_NONE, plan, carry, s, kt));
+        SENSEI_TRY(spmm_any(A, mode, scaled ? r : nullptr, scaled ? c : nullptr, src, ld_src, f_in, U, fs, f_in, SENSEI_ACT_NONE, plan, carry, s, kt));
         if (id == SENSEI_GCN_DYN_AGG) SENSEI_TRY(launch_row_broadcast(r, U, fs, A.n_rows, f_in, U, fs, SENSEI_ACT_NONE, s));
         SENSEI_TRY(launch_gemm(U, fs, W.ptr, W.ld, Y, ldy, A.n_rows, f_in, f_out, f_out, act, s, nullptr, gt));
     } else {
@@ -148,12 +206,12 @@ int run_gcn(const sensei_csr &A, const float *r, const float *c, const sensei_ma
         SENSEI_TRY(launch_gemm(X.ptr, X.ld, W.ptr, W.ld, Z, fs, A.n_cols, f_in, f_out, fs, SENSEI_ACT_NONE, s, z_scale, gt));
         if (id == SENSEI_GCN_DYN_UPD) {
             SENSEI_TRY(launch_row_broadcast(c, Z, fs, A.n_cols, fs, Z, fs, SENSEI_ACT_NONE, s));
-            SENSEI_TRY(launch_spmm(A, mode, nullptr, nullptr, Z, fs, fs, Y, ldy, f_out, SENSEI_ACT_NONE, plan, carry, s, kt));
+            SENSEI_TRY(spmm_any(A, mode, nullptr, nullptr, Z, fs, fs, Y, ldy, f_out, SENSEI_ACT_NONE, plan, carry, s, kt));
             SENSEI_TRY(launch_row_broadcast(r, Y, ldy, A.n_rows, f_out, Y, ldy, act, s));
         } else if (id == SENSEI_GCN_DYNF_UPD) {
-            SENSEI_TRY(launch_spmm(A, SENSEI_SPMM_PATTERN, r, nullptr, Z, fs, fs, Y, ldy, f_out, act, plan, carry, s, kt));
+            SENSEI_TRY(spmm_any(A, SENSEI_SPMM_PATTERN, r, nullptr, Z, fs, fs, Y, ldy, f_out, act, plan, carry, s, kt));
         } else {
-            SENSEI_TRY(launch_spmm(A, mode, nullptr, nullptr, Z, fs, fs, Y, ldy, f_out, act, plan, carry, s, kt));
+            SENSEI_TRY(spmm_any(A, mode, nullptr, nullptr, Z, fs, fs, Y, ldy, f_out, act, plan, carry, s, kt));
         }
     }
     return SENSEI_OK;
@@ -185,17 +243,22 @@ int run_gat(const sensei_csr &A, const sensei_mat &X, const sensei_mat &W, const
         SENSEI_TRY(launch_gemv2(W.ptr, W.ld, f_in, f_out, a_l, a_r, v_l, v_r, s));
         SENSEI_TRY(launch_gemv2(X.ptr, X.ld, A.n_cols, f_in, v_l, v_r, s_l, s_r, s));
     }
-    SENSEI_TRY(launch_softmax(A, nullptr, s_l, s_r, slope, alpha, plan, stats, carry_stats, s));
+    // With a panel copy the attention weights are written straight in panel order (the logits then need a
+    // buffer of their own), so the weighted SpMM can follow the panels without an index indirection.
+    const bool by_panel = panels_usable(A, gat_is_reuse(id) ? fo : f_in);
+    float *logits = by_panel ? cv.take<float>((size_t)(A.nnz > 0 ? A.nnz : 1)) : nullptr;
+    SENSEI_TRY(launch_softmax(A, nullptr, s_l, s_r, slope, alpha, plan, stats, carry_stats, s, logits,
+                              by_panel ? A.panels->position : nullptr));
     sensei_csr Aw = A;
     Aw.val = alpha;
     if (gat_is_reuse(id)) {
         if (fold) SENSEI_TRY(launch_gemm(X.ptr, X.ld, W.ptr, W.ld, theta, fo, A.n_cols, f_in, f_out, fo, SENSEI_ACT_NONE, s, nullptr, gt));
         float *carry = cv.take<float>(spmm_carry_bytes(A.nnz, fo) / sizeof(float));
-        SENSEI_TRY(launch_spmm(Aw, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, theta, fo, fo, Y, ldy, f_out, act, plan, carry, s, kt));
+        SENSEI_TRY(spmm_any(Aw, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, theta, fo, fo, Y, ldy, f_out, act, plan, carry, s, kt, by_panel));
     } else {
         float *carry = cv.take<float>(spmm_carry_bytes(A.nnz, fi) / sizeof(float));
         float *U = cv.take<float>((size_t)A.n_rows * fi);
-        SENSEI_TRY(launch_spmm(Aw, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, X.ptr, X.ld, f_in, U, fi, f_in, SENSEI_ACT_NONE, plan, carry, s, kt));
+        SENSEI_TRY(spmm_any(Aw, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, X.ptr, X.ld, f_in, U, fi, f_in, SENSEI_ACT_NONE, plan, carry, s, kt, by_panel));
         SENSEI_TRY(launch_gemm(U, fi, W.ptr, W.ld, Y, ldy, A.n_rows, f_in, f_out, f_out, act, s, nullptr, gt));
     }
     return SENSEI_OK;
@@ -386,6 +449,81 @@ const char *sensei_status_string(int status) {
     }
 }
 
+static size_t panels_layout(const sensei_csr &A, int q_count, size_t *rp_each, size_t *col_bytes, size_t *chunk_each, size_t *temp_bytes) {
+    const int t = choose_chunk_nnz(A.nnz);
+    *rp_each = align_up(((size_t)A.n_rows + 1) * sizeof(int32_t), 256);
+    *col_bytes = align_up((size_t)(A.nnz > 0 ? A.nnz : 1) * sizeof(int32_t), 256);
+    *chunk_each = align_up(((size_t)(A.nnz / t) + 3) * sizeof(int32_t), 256);
+    *temp_bytes = plan_bytes(A.nnz) + scan_temp_bytes(A.n_rows + 1);
+    return (size_t)q_count * (*rp_each + *chunk_each) + 2 * *col_bytes + 256 /* offsets */ + *temp_bytes;
+}
+
+int sensei_panels_bytes(const sensei_csr *A, int n_panels, size_t *device_bytes) {
+    if (!csr_ok(A, false) || !device_bytes || n_panels < 0 || n_panels > SENSEI_MAX_PANELS) return SENSEI_INVALID_ARGUMENT;
+    size_t a, b, c, d;
+    *device_bytes = panels_layout(*A, n_panels > 0 ? n_panels : auto_panels(*A), &a, &b, &c, &d);
+    return SENSEI_OK;
+}
+
+int sensei_panels_create(sensei_ctx *ctx, const sensei_csr *A, int n_panels, void *device_buf, size_t bytes, void *stream,
+                         sensei_panels **out) {
+    if (!ctx || !csr_ok(A, false) || !out || !device_buf || n_panels < 0 || n_panels > SENSEI_MAX_PANELS) return SENSEI_INVALID_ARGUMENT;
+    if (reinterpret_cast<uintptr_t>(device_buf) % 256 != 0) return SENSEI_INVALID_ARGUMENT;
+    const int Q = n_panels > 0 ? n_panels : auto_panels(*A);
+    size_t rp_each, col_bytes, chunk_each, temp_bytes;
+    if (bytes < panels_layout(*A, Q, &rp_each, &col_bytes, &chunk_each, &temp_bytes)) return SENSEI_WORKSPACE_TOO_SMALL;
+    sensei_panels *P = new (std::nothrow) sensei_panels;
+    if (!P) return SENSEI_HIP_ERROR;
+    P->n_panels = Q;
+    P->width = (int)((A->n_cols + Q - 1) / Q);
+    if (P->width < 1) P->width = 1;
+    P->n_rows = A->n_rows; P->n_cols = A->n_cols; P->nnz = A->nnz;
+    P->src_row_ptr = A->row_ptr; P->src_col_idx = A->col_idx;
+    P->chunk_nnz = choose_chunk_nnz(A->nnz);
+    char *base = static_cast<char *>(device_buf);
+    size_t used = 0;
+    for (int q = 0; q < Q; ++q) { P->row_ptr_q[q] = reinterpret_cast<int32_t *>(base + used); used += rp_each; }
+    for (int q = 0; q < Q; ++q) { P->chunk_row_q[q] = reinterpret_cast<int32_t *>(base + used); used += chunk_each; }
+    int32_t *col_all = reinterpret_cast<int32_t *>(base + used); used += col_bytes;
+    int32_t *perm_all = reinterpret_cast<int32_t *>(base + used); used += col_bytes;
+    int32_t *off = reinterpret_cast<int32_t *>(base + used); used += 256;
+    hipStream_t s = as_stream(stream);
+    Carver cv(base + used, temp_bytes);
+    ChunkPlan plan = make_plan(*A, cv);
+    int32_t *scan_temp = cv.take<int32_t>(scan_temp_bytes(A->n_rows + 1) / sizeof(int32_t));
+    int status = SENSEI_OK;
+    int32_t off_host[SENSEI_MAX_PANELS + 1] = {0};
+    if (launch_chunk_rows(*A, plan, s) != hipSuccess ||
+        launch_panel_build(*A, plan, Q, P->width, P->row_ptr_q, off, col_all, perm_all, scan_temp, s) != hipSuccess ||
+        hipMemcpyAsync(off_host, off, (size_t)(Q + 1) * sizeof(int32_t), hipMemcpyDeviceToHost, s) != hipSuccess ||
+        hipStreamSynchronize(s) != hipSuccess)
+        status = SENSEI_HIP_ERROR;
+    for (int q = 0; q < Q && status == SENSEI_OK; ++q) {
+        P->nnz_q[q] = (int64_t)off_host[q + 1] - off_host[q];
+        P->col_q[q] = col_all + off_host[q];
+        P->off_q[q] = off_host[q];
+        P->n_chunks_q[q] = P->nnz_q[q] <= 0 ? 1 : (int)((P->nnz_q[q] + P->chunk_nnz - 1) / P->chunk_nnz);
+        sensei_csr Aq = *A;
+        Aq.nnz = P->nnz_q[q]; Aq.row_ptr = P->row_ptr_q[q]; Aq.col_idx = P->col_q[q];
+        ChunkPlan pq;
+        pq.chunk_nnz = P->chunk_nnz; pq.n_chunks = P->n_chunks_q[q]; pq.chunk_row = P->chunk_row_q[q];
+        if (launch_chunk_rows(Aq, pq, s) != hipSuccess) status = SENSEI_HIP_ERROR;
+    }
+    P->position = perm_all;
+    P->off_q[Q] = off_host[Q];
+    if (status == SENSEI_OK && off_host[Q] != (int32_t)A->nnz) status = SENSEI_INVALID_ARGUMENT;  // malformed pattern
+    if (status != SENSEI_OK) { delete P; return status; }
+    *out = P;
+    return SENSEI_OK;
+}
+
+int sensei_panels_count(const sensei_panels *panels) { return panels ? panels->n_panels : 0; }
+
+int sensei_panels_destroy(sensei_panels *panels) {
+    delete panels;
+    return SENSEI_OK;
+}
+
 int sensei_degrees(sensei_ctx *ctx, const sensei_csr *A, int32_t *deg_row, int32_t *deg_col, void *stream) {
     if (!ctx || !csr_ok(A, false)) return SENSEI_INVALID_ARGUMENT;
     if ((A->n_rows > 0 && !deg_row) || (A->n_cols > 0 && !deg_col)) return SENSEI_INVALID_ARGUMENT;
@@ -443,7 +581,7 @@ int sensei_spmm(sensei_ctx *ctx, const sensei_csr *A, int mode, const float *r, 
     float *carry = cv.take<float>(spmm_carry_bytes(A->nnz, f) / sizeof(float));
     SENSEI_TRY(launch_chunk_rows(*A, plan, as_stream(stream)));
     const bool scaled = (mode == SENSEI_SPMM_SCALED);
-    return hip_status(launch_spmm(*A, mode, scaled ? r : nullptr, scaled ? c : nullptr, B.ptr, B.ld, f, C, ldc, f, activation, plan, carry,
+    return hip_status(spmm_any(*A, mode, scaled ? r : nullptr, scaled ? c : nullptr, B.ptr, B.ld, f, C, ldc, f, activation, plan, carry,
                                   as_stream(stream), &ctx->timers.spmm));
 }
 

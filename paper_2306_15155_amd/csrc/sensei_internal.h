@@ -60,7 +60,16 @@ size_t spmm_carry_bytes(int64_t nnz, int f);  // upper bound
 // c_j (SCALED); the row factor r is applied whenever r is non-null, in every mode.
 hipError_t launch_spmm(const sensei_csr &A, int mode, const float *r, const float *c, const float *B, int64_t ldb,
                        int f, float *C, int64_t ldc, int f_store, int act, const ChunkPlan &p, float *carry,
-                       hipStream_t s, KernelTimer *timer = nullptr);
+                       hipStream_t s, KernelTimer *timer = nullptr, bool accumulate = false, bool finalize = true);
+
+// ---- column panels: a copy of the pattern with the columns of each panel contiguous
+#define SENSEI_MAX_PANELS 8
+size_t scan_temp_bytes(int n);
+// rp[q]: n_rows + 1 ints per panel (row pointers of the panel copy on return); off: n_panels + 1 ints (panel starts in
+// col_out); perm_out[k] = position of original entry k in the panel copy; `plan` is the chunk plan of A (already computed
+// on the stream).
+hipError_t launch_panel_build(const sensei_csr &A, const ChunkPlan &plan, int n_panels, int width, int32_t *const *rp, int32_t *off,
+                              int32_t *col_out, int32_t *perm_out, int32_t *scan_temp, hipStream_t s);
 
 // ---- element-wise work over the non-zeros, degrees, scalings
 hipError_t launch_degrees(const sensei_csr &A, int32_t *deg_row, int32_t *deg_col, hipStream_t s);
@@ -75,7 +84,8 @@ hipError_t launch_score(const sensei_csr &A, const float *s_l, const float *s_r,
                         const ChunkPlan &p, hipStream_t s);
 // stats[i] = (row max, sum of exp(e - max)); logits from `e` when non-null, else from s_l / s_r.
 hipError_t launch_softmax(const sensei_csr &A, const float *e, const float *s_l, const float *s_r, float slope,
-                          float *alpha, const ChunkPlan &p, float2 *stats, float2 *carry_stats, hipStream_t s);
+                          float *alpha, const ChunkPlan &p, float2 *stats, float2 *carry_stats, hipStream_t s,
+                          float *logits_buf = nullptr, const int32_t *dst_index = nullptr);
 size_t softmax_ws_bytes(const sensei_csr &A);
 
 // ---- dense

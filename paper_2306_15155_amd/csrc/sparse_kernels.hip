@@ -18,6 +18,7 @@ namespace {
 
 constexpr int kBlock = 256;
 constexpr int kWavesPerBlock = kBlock / 64;
+constexpr int kMaxPanels = SENSEI_MAX_PANELS;
 constexpr int kShortRowNnz = 12;  // chunks whose rows average fewer non-zeros than this use one neighbour group per row
 
 // ------------------------------------------------------------------ chunk plan
@@ -63,6 +64,7 @@ struct SpmmArgs {
     int n_rows, nnz, chunk_nnz, n_chunks;
     int f, f_store, f_carry, n_tiles, act, store_vec_ok;
     int tiles_live, n_groups;  // feature tiles worked on at the same time; chunk groups (blocks per tile)
+    int accumulate, finalize;  // column panels: add to what C holds; apply row scale and activation (last panel only)
 };
 
 // value of `x` held by the lane whose number is byte_lane / 4 (all lanes must be active)
@@ -148,7 +150,19 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
             if (cont) {
                 acc.store(a.carry + (size_t)chunk * a.f_carry + f0);
             } else {
-                if (complete) {
+                float *dst = a.C + (size_t)i * a.ldc + f0;
+                const bool vec_store = a.store_vec_ok && f0 + VEC <= a.f_store;
+                if (a.accumulate) {  // later column panel: add to what the earlier panels left in C
+                    if (vec_store) {
+                        const Vec<VEC> old = Vec<VEC>::load(dst);
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e) acc.v[e] += old.v[e];
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e) if (f0 + e < a.f_store) acc.v[e] += dst[e];
+                    }
+                }
+                if (complete && a.finalize) {
                     const float sc = a.r ? a.r[i] : 1.f;
 #pragma unroll
                     for (int e = 0; e < VEC; ++e) {
@@ -157,8 +171,7 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
                         acc.v[e] = y;
                     }
                 }
-                float *dst = a.C + (size_t)i * a.ldc + f0;
-                if (a.store_vec_ok && f0 + VEC <= a.f_store) {
+                if (vec_store) {
                     acc.store(dst);
                 } else {
 #pragma unroll
@@ -212,7 +225,19 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
                 if (cont && row == i_first) {
                     racc.store(a.carry + (size_t)chunk * a.f_carry + f0);
                 } else {
-                    if (row_end <= hi) {
+                    float *dst = a.C + (size_t)row * a.ldc + f0;
+                    const bool vec_store = a.store_vec_ok && f0 + VEC <= a.f_store;
+                    if (a.accumulate) {
+                        if (vec_store) {
+                            const Vec<VEC> old = Vec<VEC>::load(dst);
+#pragma unroll
+                            for (int e = 0; e < VEC; ++e) racc.v[e] += old.v[e];
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < VEC; ++e) if (f0 + e < a.f_store) racc.v[e] += dst[e];
+                        }
+                    }
+                    if (row_end <= hi && a.finalize) {
                         const float sc = a.r ? a.r[row] : 1.f;
 #pragma unroll
                         for (int e = 0; e < VEC; ++e) {
@@ -221,8 +246,7 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
                             racc.v[e] = y;
                         }
                     }
-                    float *dst = a.C + (size_t)row * a.ldc + f0;
-                    if (a.store_vec_ok && f0 + VEC <= a.f_store) {
+                    if (vec_store) {
                         racc.store(dst);
                     } else {
 #pragma unroll
@@ -320,8 +344,10 @@ __global__ __launch_bounds__(kBlock) void k_spmm_fixup(SpmmArgs a) {
     for (int f = lane; f < a.f_store; f += 64) {
         float acc = a.C[(size_t)i * a.ldc + f];
         for (int cc = c; cc <= c_last; ++cc) acc += a.carry[(size_t)cc * a.f_carry + f];
-        acc *= sc;
-        if (a.act == SENSEI_ACT_RELU) acc = acc > 0.f ? acc : 0.f;
+        if (a.finalize) {
+            acc *= sc;
+            if (a.act == SENSEI_ACT_RELU) acc = acc > 0.f ? acc : 0.f;
+        }
         a.C[(size_t)i * a.ldc + f] = acc;
     }
 }
@@ -483,6 +509,8 @@ struct SoftmaxArgs {
     float slope;
     float2 *stats, *carry;
     float *alpha;
+    float *logits;             // where the statistics pass parks the logits it computed (alpha itself unless alpha is re-ordered)
+    const int32_t *dst_index;  // optional: alpha of entry k is written to alpha[dst_index[k]] (column-panel order)
 };
 
 // Row statistics with the same chunk ownership as SpMM: lanes stride over the non-zeros of the
@@ -516,7 +544,7 @@ __global__ __launch_bounds__(kBlock) void k_softmax_stats(SoftmaxArgs a) {
             for (int k = rs; k < rend; ++k) {
                 float e;
                 if (FROM_E) e = a.e[k];
-                else { e = leaky(sl + a.s_r[a.n.col_idx[k]], a.slope); a.alpha[k] = e; }  // logit kept for the second pass
+                else { e = leaky(sl + a.s_r[a.n.col_idx[k]], a.slope); a.logits[k] = e; }  // logit kept for the second pass
                 mz_add(rm, rz, e);
             }
             if (cont && row == i_first) a.carry[chunk] = make_float2(rm, rz);
@@ -548,7 +576,7 @@ __global__ __launch_bounds__(kBlock) void k_softmax_stats(SoftmaxArgs a) {
         for (int k = pos + lane; k < seg_hi; k += 64) {
             float e;
             if (FROM_E) e = a.e[k];
-            else { e = leaky(sl + a.s_r[a.n.col_idx[k]], a.slope); a.alpha[k] = e; }  // logit kept for the second pass
+            else { e = leaky(sl + a.s_r[a.n.col_idx[k]], a.slope); a.logits[k] = e; }  // logit kept for the second pass
             mz_add(m, z, e);
         }
         pos = seg_hi;
@@ -583,7 +611,119 @@ __global__ __launch_bounds__(kBlock) void k_softmax_alpha(SoftmaxArgs a) {
     const int chunk = wave_chunk();
     if (chunk >= a.n.n_chunks) return;
     walk_chunk(a.n, chunk, threadIdx.x & 63, [&](int i) { return a.stats[i]; },
-               [&](int k, const float2 &st) { a.alpha[k] = expf(a.e[k] - st.x) / st.y; });
+               [&](int k, const float2 &st) { a.alpha[a.dst_index ? a.dst_index[k] : k] = expf(a.e[k] - st.x) / st.y; });
+}
+
+// ------------------------------------------------------------ column panels
+
+// first position in [lo, hi) of an ascending index run whose column is >= bound
+__device__ __forceinline__ int lower_bound_col(const int32_t *__restrict__ col_idx, int lo, int hi, int bound) {
+    while (lo < hi) {
+        const int mid = (int)(((long long)lo + hi) >> 1);
+        if (col_idx[mid] < bound) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+struct PanelPtrs {
+    int32_t *rp[kMaxPanels];  // per panel: n_rows + 1 entries (counts, then row pointers after the scan)
+};
+
+// cnt[q][i] = entries of row i whose column lies in panel q (panel q = columns [q*width, (q+1)*width))
+__global__ void k_panel_count(const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx, int n_rows, int n_panels,
+                              int width, PanelPtrs pp) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i > n_rows) return;
+    if (i == n_rows) {
+        for (int q = 0; q < n_panels; ++q) pp.rp[q][n_rows] = 0;
+        return;
+    }
+    const int hi = row_ptr[i + 1];
+    int prev = row_ptr[i];
+    for (int q = 0; q < n_panels; ++q) {
+        const int pos = (q + 1 < n_panels) ? lower_bound_col(col_idx, prev, hi, (q + 1) * width) : hi;
+        pp.rp[q][i] = pos - prev;
+        prev = pos;
+    }
+}
+
+// exclusive prefix sum over int32, in place: per-block scan, sequential scan of the block totals, add back
+constexpr int kScanPerBlock = 2048;
+__global__ __launch_bounds__(256) void k_scan_local(int32_t *data, int n, int32_t *block_sums) {
+    __shared__ int part[256];
+    const int base = blockIdx.x * kScanPerBlock + threadIdx.x * 8;
+    int v[8], sum = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { v[e] = (base + e < n) ? data[base + e] : 0; sum += v[e]; }
+    part[threadIdx.x] = sum;
+    __syncthreads();
+    for (int off = 1; off < 256; off <<= 1) {
+        const int add = threadIdx.x >= off ? part[threadIdx.x - off] : 0;
+        __syncthreads();
+        part[threadIdx.x] += add;
+        __syncthreads();
+    }
+    int run = part[threadIdx.x] - sum;  // exclusive prefix of this thread within the block
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { if (base + e < n) data[base + e] = run; run += v[e]; }
+    if (threadIdx.x == 255) block_sums[blockIdx.x] = part[255];
+}
+__global__ void k_scan_sums(int32_t *block_sums, int n_blocks) {
+    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    int run = 0;
+    for (int b = 0; b < n_blocks; ++b) { const int v = block_sums[b]; block_sums[b] = run; run += v; }
+}
+__global__ __launch_bounds__(256) void k_scan_add(int32_t *data, int n, const int32_t *__restrict__ block_sums) {
+    const int add = block_sums[blockIdx.x];
+    const int base = blockIdx.x * kScanPerBlock + threadIdx.x * 8;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) if (base + e < n) data[base + e] += add;
+}
+
+// off[q] = number of entries in panels before q (start of panel q in the concatenated column / perm arrays); off[n_panels] = nnz
+__global__ void k_panel_offsets(PanelPtrs pp, int n_rows, int n_panels, int32_t *off) {
+    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    int run = 0;
+    for (int q = 0; q < n_panels; ++q) { off[q] = run; run += pp.rp[q][n_rows]; }
+    off[n_panels] = run;
+}
+
+struct PanelRow {
+    int pos[kMaxPanels];   // first entry of the row that belongs to panel q (original numbering)
+    int base[kMaxPanels];  // where the row's panel-q entries start in the panel copy
+};
+
+// copies every entry's column into its panel and records where each original entry went
+__global__ __launch_bounds__(kBlock) void k_panel_scatter(NnzArgs a, int n_panels, int width, PanelPtrs pp, const int32_t *__restrict__ off,
+                                                           int32_t *__restrict__ col_out, int32_t *__restrict__ perm_out) {
+    const int chunk = wave_chunk();
+    if (chunk >= a.n_chunks) return;
+    walk_chunk(a, chunk, threadIdx.x & 63,
+               [&](int i) {
+                   PanelRow rd;
+                   const int hi = a.row_ptr[i + 1];
+                   int prev = a.row_ptr[i];
+#pragma unroll
+                   for (int q = 0; q < kMaxPanels; ++q) {
+                       rd.pos[q] = prev;
+                       rd.base[q] = 0;
+                       if (q < n_panels) {
+                           rd.base[q] = off[q] + pp.rp[q][i];
+                           prev = (q + 1 < n_panels) ? lower_bound_col(a.col_idx, prev, hi, (q + 1) * width) : hi;
+                       }
+                   }
+                   return rd;
+               },
+               [&](int k, const PanelRow &rd) {
+                   const int col = a.col_idx[k];
+                   int p = rd.pos[0], b = rd.base[0];
+#pragma unroll
+                   for (int q = 1; q < kMaxPanels; ++q)
+                       if (q < n_panels && col >= q * width) { p = rd.pos[q]; b = rd.base[q]; }
+                   const int d = b + (k - p);
+                   col_out[d] = col;
+                   perm_out[k] = d;
+               });
 }
 
 inline unsigned blocks_for(long long n, int per_block) { return (unsigned)((n + per_block - 1) / per_block); }
@@ -651,7 +791,7 @@ size_t spmm_carry_bytes(int64_t nnz, int f) {
 
 hipError_t launch_spmm(const sensei_csr &A, int mode, const float *r, const float *c, const float *B, int64_t ldb,
                        int f, float *C, int64_t ldc, int f_store, int act, const ChunkPlan &p, float *carry,
-                       hipStream_t s, KernelTimer *timer) {
+                       hipStream_t s, KernelTimer *timer, bool accumulate, bool finalize) {
     const SpmmShape sh = spmm_shape(B, ldb, f);
     SpmmArgs a;
     a.row_ptr = A.row_ptr; a.col_idx = A.col_idx; a.chunk_row = p.chunk_row;
@@ -660,6 +800,7 @@ hipError_t launch_spmm(const sensei_csr &A, int mode, const float *r, const floa
     a.n_rows = A.n_rows; a.nnz = (int)A.nnz; a.chunk_nnz = p.chunk_nnz; a.n_chunks = p.n_chunks;
     a.f = f; a.f_store = f_store; a.f_carry = sh.f_carry; a.n_tiles = sh.n_tiles; a.act = act;
     a.store_vec_ok = (ldc % sh.vec == 0) && (reinterpret_cast<uintptr_t>(C) % (4 * sh.vec) == 0);
+    a.accumulate = accumulate ? 1 : 0; a.finalize = finalize ? 1 : 0;
     const unsigned groups = blocks_for(p.n_chunks, kWavesPerBlock);
     // Feature tiles worked on at the same time: as many as keep the gathered slices (one per live tile)
     // within about 96 MB, so that they stay in the 256 MB memory-side cache next to the index stream.
@@ -729,19 +870,51 @@ size_t softmax_ws_bytes(const sensei_csr &A) {
 }
 
 hipError_t launch_softmax(const sensei_csr &A, const float *e, const float *s_l, const float *s_r, float slope, float *alpha,
-                          const ChunkPlan &p, float2 *stats, float2 *carry_stats, hipStream_t s) {
+                          const ChunkPlan &p, float2 *stats, float2 *carry_stats, hipStream_t s, float *logits_buf,
+                          const int32_t *dst_index) {
     SoftmaxArgs a;
     a.n = nnz_args(A, p);
     a.e = e; a.s_l = s_l; a.s_r = s_r; a.slope = slope; a.stats = stats; a.carry = carry_stats; a.alpha = alpha;
+    a.logits = logits_buf ? logits_buf : alpha;
+    a.dst_index = dst_index;
     dim3 g1(blocks_for(p.n_chunks, kWavesPerBlock));
     if (e) hipLaunchKernelGGL((k_softmax_stats<true>), g1, dim3(kBlock), 0, s, a);
     else hipLaunchKernelGGL((k_softmax_stats<false>), g1, dim3(kBlock), 0, s, a);
     if (p.n_chunks > 1) hipLaunchKernelGGL(k_softmax_fixup, dim3(blocks_for(p.n_chunks - 1, kBlock)), dim3(kBlock), 0, s, a);
     if (A.nnz > 0) {
         dim3 g3(blocks_for(p.n_chunks, kWavesPerBlock));
-        if (!e) a.e = alpha;  // the statistics pass parked the logits there
+        if (!e) a.e = a.logits;  // the statistics pass parked the logits there
         hipLaunchKernelGGL(k_softmax_alpha, g3, dim3(kBlock), 0, s, a);
     }
+    return hipGetLastError();
+}
+
+
+// ------------------------------------------------------------ column panels (host side)
+
+hipError_t launch_exclusive_scan(int32_t *data, int n, int32_t *block_sums, hipStream_t s) {
+    const unsigned nb = blocks_for(n, kScanPerBlock);
+    hipLaunchKernelGGL(k_scan_local, dim3(nb), dim3(256), 0, s, data, n, block_sums);
+    hipLaunchKernelGGL(k_scan_sums, dim3(1), dim3(64), 0, s, block_sums, (int)nb);
+    hipLaunchKernelGGL(k_scan_add, dim3(nb), dim3(256), 0, s, data, n, (const int32_t *)block_sums);
+    return hipGetLastError();
+}
+
+size_t scan_temp_bytes(int n) { return align_up(((size_t)blocks_for(n, kScanPerBlock) + 1) * sizeof(int32_t), 256); }
+
+hipError_t launch_panel_build(const sensei_csr &A, const ChunkPlan &plan, int n_panels, int width, int32_t *const *rp, int32_t *off,
+                              int32_t *col_out, int32_t *perm_out, int32_t *scan_temp, hipStream_t s) {
+    PanelPtrs pp;
+    for (int q = 0; q < kMaxPanels; ++q) pp.rp[q] = q < n_panels ? rp[q] : nullptr;
+    hipLaunchKernelGGL(k_panel_count, dim3(blocks_for((long long)A.n_rows + 1, kBlock)), dim3(kBlock), 0, s, A.row_ptr, A.col_idx, A.n_rows,
+                       n_panels, width, pp);
+    hipError_t err = hipGetLastError();
+    for (int q = 0; q < n_panels && err == hipSuccess; ++q) err = launch_exclusive_scan(rp[q], A.n_rows + 1, scan_temp, s);
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL(k_panel_offsets, dim3(1), dim3(64), 0, s, pp, A.n_rows, n_panels, off);
+    if (A.nnz > 0)
+        hipLaunchKernelGGL(k_panel_scatter, dim3(blocks_for(plan.n_chunks, kWavesPerBlock)), dim3(kBlock), 0, s, nnz_args(A, plan), n_panels,
+                           width, pp, (const int32_t *)off, col_out, perm_out);
     return hipGetLastError();
 }
 

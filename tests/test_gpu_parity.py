@@ -342,3 +342,57 @@ def test_layers_can_be_captured_in_a_hip_graph(ctx):
         chain()
         torch.cuda.synchronize()
         assert torch.equal(Y, want)
+
+
+# ------------------------------------------------------------------ column panels
+
+@pytest.mark.parametrize("name", ["er", "rmat_hub", "hub_empty", "rect"])
+@pytest.mark.parametrize("n_panels", [2, 3, 8])
+def test_spmm_over_column_panels(ctx, name, n_panels):
+    from paper_2306_15155_amd import Panels, csr_struct
+    g = GRAPHS[name]
+    rng = np.random.default_rng(n_panels)
+    val = rng.standard_normal(g.nnz).astype(np.float32)
+    r = (rng.random(g.n_rows) + 0.5).astype(np.float32)
+    c = (rng.random(g.n_cols) + 0.5).astype(np.float32)
+    A = DeviceCSR(g, val)
+    P = Panels(ctx, A.s, n_panels)
+    assert P.count == n_panels
+    Ap = csr_struct(g.n_rows, g.n_cols, A.row_ptr, A.col_idx, A.val, P)
+    for f in (128, 200):
+        B = synth.uniform(f, 30, (g.n_cols, f))
+        Bd = dev(B)
+        assert_close(ctx.spmm(Ap, SPMM_PATTERN, Bd), oracle.spmm(g.row_ptr, g.col_idx, None, B), what="pattern")
+        assert_close(ctx.spmm(Ap, SPMM_WEIGHTED, Bd, activation=ACT_RELU),
+                     oracle.activation(oracle.spmm(g.row_ptr, g.col_idx, val, B), 1), what="weighted+relu")
+        want = oracle.row_broadcast(r, oracle.spmm(g.row_ptr, g.col_idx, c[g.col_idx].astype(np.float64), B))
+        assert_close(ctx.spmm(Ap, SPMM_SCALED, Bd, r=dev(r), c=dev(c)), want, what="scaled")
+    # narrow widths ignore the panels and must still be right
+    B = synth.uniform(9, 30, (g.n_cols, 40))
+    assert_close(ctx.spmm(Ap, SPMM_PATTERN, dev(B)), oracle.spmm(g.row_ptr, g.col_idx, None, B))
+    P.close()
+
+
+def test_layers_over_column_panels(ctx):
+    from paper_2306_15155_amd import Panels, csr_struct
+    g = synth.rmat(21, 6000, 120_000)
+    A = DeviceCSR(g)
+    P = Panels(ctx, A.s, 3)
+    dr, dc = ctx.degrees(A.s)
+    r, c = ctx.norm_vectors(dr), ctx.norm_vectors(dc)
+    ntil = ctx.gcn_precompute(A.s, r, c)
+    Ap = csr_struct(g.n_rows, g.n_cols, A.row_ptr, A.col_idx, None, P)
+    Apre = csr_struct(g.n_rows, g.n_cols, A.row_ptr, A.col_idx, ntil, P)
+    for f_in, f_out in ((200, 128), (136, 160)):
+        X, W = synth.uniform(21, 10, (g.n_cols, f_in)), synth.glorot(21, 11, f_in, f_out)
+        ref = oracle.gcn_layer(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, ACT_RELU)
+        for cid in range(6):
+            assert_close(ctx.gcn_layer(Apre if cid >= 4 else Ap, r, c, dev(X), dev(W), cid, ACT_RELU), ref, what=f"gcn comp {cid}")
+        a_l, a_r = synth.normal(21, 12, (f_out,), 0.0, 0.5), synth.normal(21, 13, (f_out,), 0.0, 0.5)
+        refg = oracle.gat_layer(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, a_l, a_r, 0.2, ACT_NONE)
+        for cid in range(4):
+            assert_close(ctx.gat_layer(Ap, dev(X), dev(W), dev(a_l), dev(a_r), cid, 0.2, ACT_NONE), refg, what=f"gat comp {cid}")
+    auto = Panels(ctx, A.s, 0)
+    assert auto.count == 1  # a small graph keeps the single-pass path
+    P.close()
+    auto.close()
