@@ -108,7 +108,7 @@ size_t gat_ws(const sensei_csr &A, int f_in, int f_out, int id) {
     const int fo = pad32(f_out), fi = pad4(f_in);
     size_t b = plan_bytes(A.nnz) + softmax_ws_bytes(A);
     b += 2 * align_up((size_t)A.n_cols * sizeof(float), 256);                  // s_l, s_r
-    b += 2 * align_up((size_t)(A.nnz > 0 ? A.nnz : 1) * sizeof(float), 256);   // alpha, logits (panel order only)
+    b += align_up((size_t)(A.nnz > 0 ? A.nnz : 1) * sizeof(float), 256);       // attention logits
     b += 2 * align_up((size_t)fi * sizeof(float), 256);                        // W.a_l, W.a_r
     if (id != SENSEI_GAT_RECOMP_FOLD) b += align_up((size_t)A.n_cols * fo * sizeof(float), 256);  // Theta
     if (gat_is_reuse(id)) {
@@ -143,13 +143,14 @@ bool panels_usable(const sensei_csr &A, int f) {
 }
 
 // SpMM over the whole pattern, or panel after panel when the matrix carries a usable panel copy.  Values
-// (WEIGHTED) can only follow the panels if they are stored in panel order (val_in_panel_order); values in the
-// order of the original pattern use the single pass.
+// (WEIGHTED, kSpmmSoftmax) can only follow the panels if they are stored in panel order (val_in_panel_order);
+// values in the order of the original pattern use the single pass.
 hipError_t spmm_any(const sensei_csr &A, int mode, const float *r, const float *c, const float *B, int64_t ldb, int f, float *C,
                     int64_t ldc, int f_store, int act, const ChunkPlan &plan, float *carry, hipStream_t s, KernelTimer *kt,
-                    bool val_in_panel_order = false) {
-    if (!panels_usable(A, f) || (mode == SENSEI_SPMM_WEIGHTED && !val_in_panel_order))
-        return launch_spmm(A, mode, r, c, B, ldb, f, C, ldc, f_store, act, plan, carry, s, kt);
+                    bool val_in_panel_order = false, const float2 *mz = nullptr) {
+    const bool has_val = (mode == SENSEI_SPMM_WEIGHTED || mode == kSpmmSoftmax);
+    if (!panels_usable(A, f) || (has_val && !val_in_panel_order))
+        return launch_spmm(A, mode, r, c, B, ldb, f, C, ldc, f_store, act, plan, carry, s, kt, false, true, mz);
     const sensei_panels &P = *A.panels;
     hipEvent_t t0 = kt ? kt->next() : nullptr, t1 = t0 ? kt->next() : nullptr;
     if (t1 && hipEventRecord(t0, s) != hipSuccess) return hipErrorUnknown;
@@ -163,7 +164,7 @@ hipError_t spmm_any(const sensei_csr &A, int mode, const float *r, const float *
         pq.chunk_nnz = P.chunk_nnz;
         pq.n_chunks = P.n_chunks_q[q];
         pq.chunk_row = P.chunk_row_q[q];
-        const hipError_t e = launch_spmm(Aq, mode, r, c, B, ldb, f, C, ldc, f_store, act, pq, carry, s, nullptr, q > 0, q == P.n_panels - 1);
+        const hipError_t e = launch_spmm(Aq, mode, r, c, B, ldb, f, C, ldc, f_store, act, pq, carry, s, nullptr, q > 0, q == P.n_panels - 1, mz);
         if (e != hipSuccess) return e;
     }
     if (t1 && hipEventRecord(t1, s) != hipSuccess) return hipErrorUnknown;
@@ -228,7 +229,7 @@ int run_gat(const sensei_csr &A, const sensei_mat &X, const sensei_mat &W, const
     float2 *carry_stats = cv.take<float2>((size_t)plan.n_chunks);
     float *s_l = cv.take<float>((size_t)A.n_cols);
     float *s_r = cv.take<float>((size_t)A.n_cols);
-    float *alpha = cv.take<float>((size_t)(A.nnz > 0 ? A.nnz : 1));
+    float *logits = cv.take<float>((size_t)(A.nnz > 0 ? A.nnz : 1));
     float *v_l = cv.take<float>((size_t)fi);
     float *v_r = cv.take<float>((size_t)fi);
     float *theta = nullptr;
@@ -243,22 +244,21 @@ int run_gat(const sensei_csr &A, const sensei_mat &X, const sensei_mat &W, const
         SENSEI_TRY(launch_gemv2(W.ptr, W.ld, f_in, f_out, a_l, a_r, v_l, v_r, s));
         SENSEI_TRY(launch_gemv2(X.ptr, X.ld, A.n_cols, f_in, v_l, v_r, s_l, s_r, s));
     }
-    // With a panel copy the attention weights are written straight in panel order (the logits then need a
-    // buffer of their own), so the weighted SpMM can follow the panels without an index indirection.
+    // One pass computes the logits and the per-row softmax statistics; the aggregation then weighs each neighbour
+    // by exp(e - max) and scales the row by 1 / sum, so the attention weights themselves are never stored.  With a
+    // panel copy the logits are written straight in panel order and the SpMM follows the panels.
     const bool by_panel = panels_usable(A, gat_is_reuse(id) ? fo : f_in);
-    float *logits = by_panel ? cv.take<float>((size_t)(A.nnz > 0 ? A.nnz : 1)) : nullptr;
-    SENSEI_TRY(launch_softmax(A, nullptr, s_l, s_r, slope, alpha, plan, stats, carry_stats, s, logits,
-                              by_panel ? A.panels->position : nullptr));
+    SENSEI_TRY(launch_attention_stats(A, s_l, s_r, slope, logits, by_panel ? A.panels->position : nullptr, plan, stats, carry_stats, s));
     sensei_csr Aw = A;
-    Aw.val = alpha;
+    Aw.val = logits;
     if (gat_is_reuse(id)) {
         if (fold) SENSEI_TRY(launch_gemm(X.ptr, X.ld, W.ptr, W.ld, theta, fo, A.n_cols, f_in, f_out, fo, SENSEI_ACT_NONE, s, nullptr, gt));
         float *carry = cv.take<float>(spmm_carry_bytes(A.nnz, fo) / sizeof(float));
-        SENSEI_TRY(spmm_any(Aw, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, theta, fo, fo, Y, ldy, f_out, act, plan, carry, s, kt, by_panel));
+        SENSEI_TRY(spmm_any(Aw, kSpmmSoftmax, nullptr, nullptr, theta, fo, fo, Y, ldy, f_out, act, plan, carry, s, kt, by_panel, stats));
     } else {
         float *carry = cv.take<float>(spmm_carry_bytes(A.nnz, fi) / sizeof(float));
         float *U = cv.take<float>((size_t)A.n_rows * fi);
-        SENSEI_TRY(spmm_any(Aw, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, X.ptr, X.ld, f_in, U, fi, f_in, SENSEI_ACT_NONE, plan, carry, s, kt, by_panel));
+        SENSEI_TRY(spmm_any(Aw, kSpmmSoftmax, nullptr, nullptr, X.ptr, X.ld, f_in, U, fi, f_in, SENSEI_ACT_NONE, plan, carry, s, kt, by_panel, stats));
         SENSEI_TRY(launch_gemm(U, fi, W.ptr, W.ld, Y, ldy, A.n_rows, f_in, f_out, f_out, act, s, nullptr, gt));
     }
     return SENSEI_OK;
@@ -324,8 +324,8 @@ double gcn_cost(const sensei_ctx &c, const Features &g, int f_in, int f_out, int
 double gat_cost(const sensei_ctx &c, const Features &g, int f_in, int f_out, int id) {
     const bool fold = (id == SENSEI_GAT_RECOMP_FOLD || id == SENSEI_GAT_REUSE_FOLD);
     double t = c.launch_us * 1e-6;
-    // attention: stats + alpha passes over the pattern
-    t += 3.0 * c.launch_us * 1e-6 + (g.nnz * 12.0 + g.n_rows * 16.0) / c.stream_bps;
+    // attention: one pass over the pattern for the logits and the row statistics (the normalisation is part of the SpMM)
+    t += 2.0 * c.launch_us * 1e-6 + (g.nnz * 8.0 + g.n_rows * 16.0) / c.stream_bps;
     if (fold) t += t_stream(c, 4.0 * f_in * f_out) + t_stream(c, 4.0 * g.n_cols * f_in);
     else t += t_gemm(c, g.n_cols, f_in, f_out) + t_stream(c, 4.0 * g.n_cols * f_out);
     if (gat_is_reuse(id)) {
@@ -627,7 +627,7 @@ int sensei_edge_softmax(sensei_ctx *ctx, const sensei_csr *A, const float *e, fl
     float2 *stats = cv.take<float2>((size_t)A->n_rows + 1);
     float2 *carry_stats = cv.take<float2>((size_t)plan.n_chunks);
     SENSEI_TRY(launch_chunk_rows(*A, plan, as_stream(stream)));
-    return hip_status(launch_softmax(*A, e, nullptr, nullptr, 0.f, alpha_out, plan, stats, carry_stats, as_stream(stream)));
+    return hip_status(launch_softmax(*A, e, alpha_out, plan, stats, carry_stats, as_stream(stream)));
 }
 
 int sensei_gcn_workspace(const sensei_csr *A, int f_in, int f_out, int comp_id, size_t *bytes) {

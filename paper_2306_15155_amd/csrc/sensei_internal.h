@@ -60,7 +60,12 @@ size_t spmm_carry_bytes(int64_t nnz, int f);  // upper bound
 // c_j (SCALED); the row factor r is applied whenever r is non-null, in every mode.
 hipError_t launch_spmm(const sensei_csr &A, int mode, const float *r, const float *c, const float *B, int64_t ldb,
                        int f, float *C, int64_t ldc, int f_store, int act, const ChunkPlan &p, float *carry,
-                       hipStream_t s, KernelTimer *timer = nullptr, bool accumulate = false, bool finalize = true);
+                       hipStream_t s, KernelTimer *timer = nullptr, bool accumulate = false, bool finalize = true,
+                       const float2 *mz = nullptr);
+// Internal SpMM mode (not part of the C ABI): A.val holds attention logits e_ij, `mz[i]` = (max_j e_ij, sum_j exp(e_ij - max));
+// the kernel weighs neighbour j of row i by exp(e_ij - max_i) and scales the finished row by 1 / sum, i.e. it aggregates
+// with the softmax weights of Eq. 6 without storing them.
+constexpr int kSpmmSoftmax = 3;
 
 // ---- column panels: a copy of the pattern with the columns of each panel contiguous
 #define SENSEI_MAX_PANELS 8
@@ -82,10 +87,13 @@ hipError_t launch_row_broadcast(const float *s_vec, const float *X, int64_t ldx,
 // ---- attention: logits, per-row softmax statistics, normalised weights
 hipError_t launch_score(const sensei_csr &A, const float *s_l, const float *s_r, float slope, float *e,
                         const ChunkPlan &p, hipStream_t s);
-// stats[i] = (row max, sum of exp(e - max)); logits from `e` when non-null, else from s_l / s_r.
-hipError_t launch_softmax(const sensei_csr &A, const float *e, const float *s_l, const float *s_r, float slope,
-                          float *alpha, const ChunkPlan &p, float2 *stats, float2 *carry_stats, hipStream_t s,
-                          float *logits_buf = nullptr, const int32_t *dst_index = nullptr);
+// alpha = row-wise softmax of the logits e (in place allowed); stats[i] = (row max, sum of exp(e - max)) as a by-product.
+hipError_t launch_softmax(const sensei_csr &A, const float *e, float *alpha, const ChunkPlan &p, float2 *stats, float2 *carry_stats,
+                          hipStream_t s);
+// Logits e_ij = LeakyReLU(s_l[i] + s_r[j]) of every stored entry, written to logits[k] (or logits[dst_index[k]]), and the
+// statistics stats[i] = (row max, sum of exp(e - max)) that kSpmmSoftmax needs.
+hipError_t launch_attention_stats(const sensei_csr &A, const float *s_l, const float *s_r, float slope, float *logits,
+                                  const int32_t *dst_index, const ChunkPlan &p, float2 *stats, float2 *carry_stats, hipStream_t s);
 size_t softmax_ws_bytes(const sensei_csr &A);
 
 // ---- dense

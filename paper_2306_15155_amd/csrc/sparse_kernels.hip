@@ -59,6 +59,7 @@ template <> struct Vec<4> {
 struct SpmmArgs {
     const int32_t *row_ptr, *col_idx, *chunk_row;
     const float *val, *r, *c, *B;
+    const float2 *mz;  // softmax mode: per-row (max logit, sum of exp(logit - max))
     float *C, *carry;
     long long ldb, ldc;
     int n_rows, nnz, chunk_nnz, n_chunks;
@@ -72,6 +73,10 @@ __device__ __forceinline__ int lane_read(int byte_lane, int x) { return __builti
 __device__ __forceinline__ float lane_read(int byte_lane, float x) {
     return __int_as_float(__builtin_amdgcn_ds_bpermute(byte_lane, __float_as_int(x)));
 }
+
+__device__ __forceinline__ float uni_f(float x) { return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(x))); }
+// 1/z of a softmax row; a row without entries (z = 0) gives 0, never inf
+__device__ __forceinline__ float inv_z(float z) { return z > 0.f ? 1.f / z : 0.f; }
 
 // One wavefront = one (chunk, feature tile).  The 64 lanes form G = 64/LPG
 // neighbour groups of LPG lanes; a group reads VEC*LPG consecutive floats of
@@ -88,6 +93,8 @@ __device__ __forceinline__ float lane_read(int byte_lane, float x) {
 // the live tile set, so each XCD's L2 keeps seeing the same 128-byte slice of
 // the gathered matrix; the number of live tiles bounds how much of that matrix
 // is in use at one time.
+// MODE kSpmmSoftmax: `val` holds attention logits; the weight of an entry is exp(logit - m_i) and the row is
+// scaled by 1/z_i when it is complete, so the normalised attention weights are never stored (Eq. 6).
 template <int VEC, int LPG, int MODE, bool OFF32>
 __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
     constexpr int G = 64 / LPG;
@@ -127,6 +134,8 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
     bool cont = (a.nnz > 0) && (a.row_ptr[i0] > lo);
     int i = uni(cont ? i0 - 1 : i0);
     int re = uni((i < a.n_rows) ? a.row_ptr[i + 1] : 0x7fffffff);
+    float m_row = 0.f;  // softmax mode: max logit of row i
+    if (MODE == kSpmmSoftmax) m_row = uni_f((i < a.n_rows) ? a.mz[i].x : 0.f);
 
     Vec<VEC> acc;
 #pragma unroll
@@ -163,7 +172,7 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
                     }
                 }
                 if (complete && a.finalize) {
-                    const float sc = a.r ? a.r[i] : 1.f;
+                    const float sc = (MODE == kSpmmSoftmax) ? inv_z(a.mz[i].y) : (a.r ? a.r[i] : 1.f);
 #pragma unroll
                     for (int e = 0; e < VEC; ++e) {
                         float y = acc.v[e] * sc;
@@ -192,7 +201,9 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
             const int row = ib + g;
             const bool rok = row < i1;
             int rs = 0, rend = 0, row_end = 0;
+            float2 mz_g = make_float2(0.f, 0.f);
             if (rok) {
+                if (MODE == kSpmmSoftmax) mz_g = a.mz[row];
                 rs = a.row_ptr[row];
                 row_end = a.row_ptr[row + 1];
                 rs = rs > lo ? rs : lo;
@@ -212,6 +223,7 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
                     float wq = 1.f;
                     if (MODE == SENSEI_SPMM_WEIGHTED) wq = a.val[kq];
                     if (MODE == SENSEI_SPMM_SCALED) wq = a.c[j];
+                    if (MODE == kSpmmSoftmax) wq = __expf(a.val[kq] - mz_g.x);
                     ww[q] = valid ? wq : 0.f;
                     b[q] = gather(j);
                 }
@@ -238,7 +250,7 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
                         }
                     }
                     if (row_end <= hi && a.finalize) {
-                        const float sc = a.r ? a.r[row] : 1.f;
+                        const float sc = (MODE == kSpmmSoftmax) ? inv_z(mz_g.y) : (a.r ? a.r[row] : 1.f);
 #pragma unroll
                         for (int e = 0; e < VEC; ++e) {
                             float y = racc.v[e] * sc;
@@ -265,7 +277,7 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
         float w = 0.f;
         if (k < hi) {
             col = a.col_idx[k];
-            if (MODE == SENSEI_SPMM_WEIGHTED) w = a.val[k];
+            if (MODE == SENSEI_SPMM_WEIGHTED || MODE == kSpmmSoftmax) w = a.val[k];
             if (MODE == SENSEI_SPMM_SCALED) w = a.c[col];
         }
         const int bhi = (base + 64 < hi) ? base + 64 : hi;
@@ -275,6 +287,7 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
                 cont = false;
                 i = uni(i + 1);
                 re = uni(a.row_ptr[i + 1]);
+                if (MODE == kSpmmSoftmax) m_row = uni_f(a.mz[i].x);
             }
             const int seg_hi = uni(re < bhi ? re : bhi);
             const int u0 = uni(pos - base), n = uni(seg_hi - pos);
@@ -288,6 +301,7 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
                 for (int q = 0; q < U; ++q) {
                     const int j = lane_read(src4 + q * G * 4, col);
                     ww[q] = (MODE == SENSEI_SPMM_PATTERN) ? 1.f : lane_read(src4 + q * G * 4, w);
+                    if (MODE == kSpmmSoftmax) ww[q] = __expf(ww[q] - m_row);
                     b[q] = gather(j);
                 }
 #pragma unroll
@@ -296,7 +310,8 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
             }
             for (; it < full; ++it) {
                 const int j = lane_read(src4, col);
-                const float ww = (MODE == SENSEI_SPMM_PATTERN) ? 1.f : lane_read(src4, w);
+                float ww = (MODE == SENSEI_SPMM_PATTERN) ? 1.f : lane_read(src4, w);
+                if (MODE == kSpmmSoftmax) ww = __expf(ww - m_row);
                 accumulate(gather(j), ww);
                 src4 += G * 4;
             }
@@ -305,7 +320,8 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
                 const bool ok = g < rem;
                 const int s4 = ok ? src4 : u0 * 4;
                 const int j = lane_read(s4, col);
-                const float ww = (MODE == SENSEI_SPMM_PATTERN) ? 1.f : lane_read(s4, w);
+                float ww = (MODE == SENSEI_SPMM_PATTERN) ? 1.f : lane_read(s4, w);
+                if (MODE == kSpmmSoftmax) ww = __expf(ww - m_row);
                 if (ok) accumulate(gather(j), ww);
             }
             pos = seg_hi;
@@ -340,7 +356,7 @@ __global__ __launch_bounds__(kBlock) void k_spmm_fixup(SpmmArgs a) {
     if (rs < lo - a.chunk_nnz) return;  // the row began before the previous chunk: not its first continuation
     const int re = a.row_ptr[i + 1];
     const int c_last = (re - 1) / a.chunk_nnz;
-    const float sc = a.r ? a.r[i] : 1.f;
+    const float sc = a.mz ? inv_z(a.mz[i].y) : (a.r ? a.r[i] : 1.f);
     for (int f = lane; f < a.f_store; f += 64) {
         float acc = a.C[(size_t)i * a.ldc + f];
         for (int cc = c; cc <= c_last; ++cc) acc += a.carry[(size_t)cc * a.f_carry + f];
@@ -357,6 +373,7 @@ hipError_t spmm_dispatch_mode(const SpmmArgs &a, int mode, dim3 grid, hipStream_
     switch (mode) {
         case SENSEI_SPMM_PATTERN: hipLaunchKernelGGL((k_spmm<VEC, LPG, SENSEI_SPMM_PATTERN, OFF32>), grid, dim3(kBlock), 0, s, a); break;
         case SENSEI_SPMM_WEIGHTED: hipLaunchKernelGGL((k_spmm<VEC, LPG, SENSEI_SPMM_WEIGHTED, OFF32>), grid, dim3(kBlock), 0, s, a); break;
+        case kSpmmSoftmax: hipLaunchKernelGGL((k_spmm<VEC, LPG, kSpmmSoftmax, OFF32>), grid, dim3(kBlock), 0, s, a); break;
         default: hipLaunchKernelGGL((k_spmm<VEC, LPG, SENSEI_SPMM_SCALED, OFF32>), grid, dim3(kBlock), 0, s, a); break;
     }
     return hipGetLastError();
@@ -509,8 +526,8 @@ struct SoftmaxArgs {
     float slope;
     float2 *stats, *carry;
     float *alpha;
-    float *logits;             // where the statistics pass parks the logits it computed (alpha itself unless alpha is re-ordered)
-    const int32_t *dst_index;  // optional: alpha of entry k is written to alpha[dst_index[k]] (column-panel order)
+    float *logits;             // where the statistics pass parks the logits it computed from s_l, s_r
+    const int32_t *dst_index;  // optional: the logit of entry k goes to logits[dst_index[k]] (column-panel order)
 };
 
 // Row statistics with the same chunk ownership as SpMM: lanes stride over the non-zeros of the
@@ -544,7 +561,7 @@ __global__ __launch_bounds__(kBlock) void k_softmax_stats(SoftmaxArgs a) {
             for (int k = rs; k < rend; ++k) {
                 float e;
                 if (FROM_E) e = a.e[k];
-                else { e = leaky(sl + a.s_r[a.n.col_idx[k]], a.slope); a.logits[k] = e; }  // logit kept for the second pass
+                else { e = leaky(sl + a.s_r[a.n.col_idx[k]], a.slope); a.logits[a.dst_index ? a.dst_index[k] : k] = e; }  // kept for the second pass
                 mz_add(rm, rz, e);
             }
             if (cont && row == i_first) a.carry[chunk] = make_float2(rm, rz);
@@ -576,7 +593,7 @@ __global__ __launch_bounds__(kBlock) void k_softmax_stats(SoftmaxArgs a) {
         for (int k = pos + lane; k < seg_hi; k += 64) {
             float e;
             if (FROM_E) e = a.e[k];
-            else { e = leaky(sl + a.s_r[a.n.col_idx[k]], a.slope); a.logits[k] = e; }  // logit kept for the second pass
+            else { e = leaky(sl + a.s_r[a.n.col_idx[k]], a.slope); a.logits[a.dst_index ? a.dst_index[k] : k] = e; }  // kept for the second pass
             mz_add(m, z, e);
         }
         pos = seg_hi;
@@ -611,7 +628,7 @@ __global__ __launch_bounds__(kBlock) void k_softmax_alpha(SoftmaxArgs a) {
     const int chunk = wave_chunk();
     if (chunk >= a.n.n_chunks) return;
     walk_chunk(a.n, chunk, threadIdx.x & 63, [&](int i) { return a.stats[i]; },
-               [&](int k, const float2 &st) { a.alpha[a.dst_index ? a.dst_index[k] : k] = expf(a.e[k] - st.x) / st.y; });
+               [&](int k, const float2 &st) { a.alpha[k] = expf(a.e[k] - st.x) / st.y; });
 }
 
 // ------------------------------------------------------------ column panels
@@ -791,9 +808,10 @@ size_t spmm_carry_bytes(int64_t nnz, int f) {
 
 hipError_t launch_spmm(const sensei_csr &A, int mode, const float *r, const float *c, const float *B, int64_t ldb,
                        int f, float *C, int64_t ldc, int f_store, int act, const ChunkPlan &p, float *carry,
-                       hipStream_t s, KernelTimer *timer, bool accumulate, bool finalize) {
+                       hipStream_t s, KernelTimer *timer, bool accumulate, bool finalize, const float2 *mz) {
     const SpmmShape sh = spmm_shape(B, ldb, f);
     SpmmArgs a;
+    a.mz = (mode == kSpmmSoftmax) ? mz : nullptr;
     a.row_ptr = A.row_ptr; a.col_idx = A.col_idx; a.chunk_row = p.chunk_row;
     a.val = A.val; a.r = r; a.c = c; a.B = B; a.C = C; a.carry = carry;
     a.ldb = ldb; a.ldc = ldc;
@@ -869,23 +887,27 @@ size_t softmax_ws_bytes(const sensei_csr &A) {
     return align_up((size_t)(A.n_rows + 1) * sizeof(float2), 256) + align_up((size_t)n_chunks_for(A.nnz, t) * sizeof(float2), 256);
 }
 
-hipError_t launch_softmax(const sensei_csr &A, const float *e, const float *s_l, const float *s_r, float slope, float *alpha,
-                          const ChunkPlan &p, float2 *stats, float2 *carry_stats, hipStream_t s, float *logits_buf,
-                          const int32_t *dst_index) {
+hipError_t launch_softmax(const sensei_csr &A, const float *e, float *alpha, const ChunkPlan &p, float2 *stats, float2 *carry_stats,
+                          hipStream_t s) {
     SoftmaxArgs a;
     a.n = nnz_args(A, p);
-    a.e = e; a.s_l = s_l; a.s_r = s_r; a.slope = slope; a.stats = stats; a.carry = carry_stats; a.alpha = alpha;
-    a.logits = logits_buf ? logits_buf : alpha;
-    a.dst_index = dst_index;
+    a.e = e; a.s_l = nullptr; a.s_r = nullptr; a.slope = 0.f; a.stats = stats; a.carry = carry_stats; a.alpha = alpha;
+    a.logits = nullptr; a.dst_index = nullptr;
     dim3 g1(blocks_for(p.n_chunks, kWavesPerBlock));
-    if (e) hipLaunchKernelGGL((k_softmax_stats<true>), g1, dim3(kBlock), 0, s, a);
-    else hipLaunchKernelGGL((k_softmax_stats<false>), g1, dim3(kBlock), 0, s, a);
+    hipLaunchKernelGGL((k_softmax_stats<true>), g1, dim3(kBlock), 0, s, a);
     if (p.n_chunks > 1) hipLaunchKernelGGL(k_softmax_fixup, dim3(blocks_for(p.n_chunks - 1, kBlock)), dim3(kBlock), 0, s, a);
-    if (A.nnz > 0) {
-        dim3 g3(blocks_for(p.n_chunks, kWavesPerBlock));
-        if (!e) a.e = a.logits;  // the statistics pass parked the logits there
-        hipLaunchKernelGGL(k_softmax_alpha, g3, dim3(kBlock), 0, s, a);
-    }
+    if (A.nnz > 0) hipLaunchKernelGGL(k_softmax_alpha, g1, dim3(kBlock), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_attention_stats(const sensei_csr &A, const float *s_l, const float *s_r, float slope, float *logits,
+                                  const int32_t *dst_index, const ChunkPlan &p, float2 *stats, float2 *carry_stats, hipStream_t s) {
+    SoftmaxArgs a;
+    a.n = nnz_args(A, p);
+    a.e = nullptr; a.s_l = s_l; a.s_r = s_r; a.slope = slope; a.stats = stats; a.carry = carry_stats; a.alpha = nullptr;
+    a.logits = logits; a.dst_index = dst_index;
+    hipLaunchKernelGGL((k_softmax_stats<false>), dim3(blocks_for(p.n_chunks, kWavesPerBlock)), dim3(kBlock), 0, s, a);
+    if (p.n_chunks > 1) hipLaunchKernelGGL(k_softmax_fixup, dim3(blocks_for(p.n_chunks - 1, kBlock)), dim3(kBlock), 0, s, a);
     return hipGetLastError();
 }
 
