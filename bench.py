@@ -31,6 +31,12 @@ WORKLOADS = {
                         layers=[_gcn(602, 256, 1, "X"), _gcn(256, 41, 0, 0), _gat(602, 256, 1, "X")]),
     "c3_rmat2450k": dict(graph="rmat", n=2_450_000, draws=84_000_000, seed=7, f_x=100, x="normal",
                          layers=[l for h in (32, 128, 512, 1024) for l in (_gcn(100, h, 1, "X"), _gcn(h, h, 0, -1))]),
+    # shapes of the two extremes of the paper's graph table: very dense (98 k nodes, 1e8 stored entries) and
+    # road-network-like (12 M nodes, about two links per node)
+    "dense98k": dict(graph="er", n=98_000, pairs=50_000_000, seed=3, f_x=256, x="uniform",
+                     layers=[_gcn(256, 64, 1, "X"), _gcn(64, 256, 0, 0), _gat(64, 256, 1, 0)]),
+    "road12m": dict(graph="grid", side=3464, keep=0.53, seed=5, f_x=128, x="normal",
+                    layers=[_gcn(128, 32, 1, "X"), _gcn(32, 128, 0, 0), _gat(32, 128, 1, 0)]),
     "c1_er10k": dict(graph="er", n=10_000, pairs=50_000, seed=1, f_x=64, x="uniform", layers=[_gcn(64, 32, 1, "X")]),
 }
 
@@ -44,7 +50,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true", help="skip timing every composition id")
     ap.add_argument("--no-panels", action="store_true", help="do not build the column-panel copy of the graph")
-    ap.add_argument("--panels", type=int, default=0, help="force the number of column panels (0 = let the library choose)")
+    ap.add_argument("--panels", type=int, default=0, help="force the number of column panels (0 = let the library measure)")
+    ap.add_argument("--no-gather-probe", action="store_true", help="skip the L2-resident gather probe")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run four 1 GiB device-to-device copies (a kernel of known traffic, for scaling rocprofv3 --pmc byte counters)")
     return ap.parse_args()
@@ -69,7 +76,12 @@ def main():
     dev = "cuda:0"
     seed = wl["seed"]
     t0 = time.time()
-    g = synth.rmat(seed, wl["n"], wl["draws"]) if wl["graph"] == "rmat" else synth.erdos_renyi(seed, wl["n"], wl["pairs"])
+    if wl["graph"] == "rmat":
+        g = synth.rmat(seed, wl["n"], wl["draws"])
+    elif wl["graph"] == "grid":
+        g = synth.thinned_grid(seed, wl["side"], wl["keep"])
+    else:
+        g = synth.erdos_renyi(seed, wl["n"], wl["pairs"])
     N, nnz = g.n_rows, g.nnz
     X = synth.uniform(seed, 10, (N, wl["f_x"])) if wl["x"] == "uniform" else synth.normal(seed, 10, (N, wl["f_x"]))
     Ws = [synth.glorot(seed, 100 + i, L["f_in"], L["f_out"]) for i, L in enumerate(layers)]
@@ -101,9 +113,9 @@ def main():
     panels, panels_ms = None, 0.0
     if not args.no_panels:
         tp = time.perf_counter()
-        panels = Panels(ctx, A, args.panels)
+        panels = Panels(ctx, A, args.panels, tune=(args.panels == 0))
         torch.cuda.synchronize()
-        panels_ms = (time.perf_counter() - tp) * 1e3
+        panels_ms = (time.perf_counter() - tp) * 1e3  # includes the timed trials when the count is measured
         A = csr_struct(N, N, row_ptr, col_idx, None, panels)
     Apre = csr_struct(N, N, row_ptr, col_idx, ntil, panels)
 
@@ -229,7 +241,9 @@ def main():
                                   "spmm_kernel_ms": round(spmm_mean[i], 4) if spmm_mean else None} for i in range(len(layers))},
               "step_ms_median": round(float(np.median(each_ms)), 4), "step_ms_min": round(float(np.min(each_ms)), 4),
               "gemm": gemm_info, "setup_ms": round(setup_ms, 4), "column_panels": None if panels is None else panels.count,
-              "column_panels_build_ms": round(panels_ms, 3), "select_model_ms": round(select_model_ms, 4),
+              "column_panels_min_width": None if panels is None else panels.min_width,
+              "column_panels_setup_ms": round(panels_ms, 3),
+              "column_panels_trial_ms": None if panels is None or panels.tune_ms is None else [round(x, 3) for x in panels.tune_ms], "select_model_ms": round(select_model_ms, 4),
               "graph": {"nodes": N, "nnz": nnz, "max_degree": int(np.diff(g.row_ptr).max()), "generate_s": round(gen_s, 2)}}
     if not args.no_sweep:
         sweep, regret = {}, {}
@@ -249,6 +263,30 @@ def main():
         dt = (time.perf_counter() - ts) * 1e3
         detail["select_timed"] = {"layer": tag(0), "pick": name_of(0, idt), "overhead_ms": round(dt, 3),
                                   "overhead_in_layers": round(dt / detail["layers"][tag(0)]["ms"], 2)}
+
+    # ---- ceiling of the neighbour gather: the same SpMM kernel (value-less, F = 256) on a synthetic pattern whose
+    # columns span only 8192 rows of the gathered matrix, so every 128-byte feature slice (1 MB) stays in one L2.
+    # The rate it reaches bounds what any SpMM of this shape can consume, whatever the graph.
+    if not args.no_gather_probe:
+        from paper_2306_15155_amd import SPMM_PATTERN
+        n_c, n_r, d, f_p = 8192, 65536, 512, 256
+        rng = np.random.default_rng(7)
+        start = rng.integers(0, n_c, n_r, dtype=np.int64)
+        stride = rng.integers(0, n_c // 2, n_r, dtype=np.int64) * 2 + 1  # odd stride modulo a power of two: d distinct columns
+        cols = ((start[:, None] + stride[:, None] * np.arange(d, dtype=np.int64)[None, :]) % n_c).astype(np.int32)
+        cols.sort(axis=1)
+        p_rp = torch.arange(0, (n_r + 1) * d, d, dtype=torch.int32, device=dev)
+        p_ci = torch.from_numpy(cols.reshape(-1)).to(dev)
+        p_B = torch.rand((n_c, f_p), device=dev)
+        p_C = torch.empty((n_r, f_p), device=dev)
+        p_A = csr_struct(n_r, n_c, p_rp, p_ci)
+        p_ms = time_fn(lambda: ctx.spmm(p_A, SPMM_PATTERN, p_B, out=p_C), 5)
+        p_rate = n_r * d * 4.0 * f_p / p_ms / 1e6
+        detail["l2_resident_gather_probe"] = {"pattern": "%d x %d, %d entries per row" % (n_r, n_c, d), "f": f_p, "ms": round(p_ms, 4),
+                                              "gather_GBps": round(p_rate, 1)}
+        if roofline is not None:
+            roofline["gather_frac_of_l2_resident_rate"] = round(roofline["gather_GBps_no_reuse"] / p_rate, 3)
+        del p_rp, p_ci, p_B, p_C, cols
 
     # ---- launch-bound workloads: the same step captured once in a HIP graph and replayed
     if N <= 50_000:
@@ -306,7 +344,8 @@ def main():
            "unit": "ms/layer", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
            "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
            "config": {"workload": args.workload,
-                      "graph": "R-MAT(0.57,0.19,0.19,0.05) symmetrised + self loops" if wl["graph"] == "rmat" else "G(n,M) + self loops",
+                      "graph": {"rmat": "R-MAT(0.57,0.19,0.19,0.05) symmetrised + self loops", "er": "G(n,M) + self loops",
+                                "grid": "square grid, links kept with probability %s, + self loops" % wl.get("keep")}[wl["graph"]],
                       "nodes": N, "nnz": nnz, "layers": desc, "compositions": [name_of(i) for i in range(len(layers))]},
            "roofline": roofline, "cpu_baseline": cpu, "detail": detail}
     print(json.dumps(out))

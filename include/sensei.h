@@ -110,7 +110,7 @@ const char *sensei_status_string(int status);
 
 /* Optional, once per graph: a copy of the pattern cut into column panels (columns [q*w, (q+1)*w) of panel q
  * stored contiguously, with the position of every entry in the original pattern).  When a sensei_csr carries
- * it, wide SpMMs (128 features and more) run one panel after the other and add the partial results, so the
+ * it, wide SpMMs (at least `min_width` floats per gathered row, 128 by default) run one panel after the other and add the partial results, so the
  * neighbour rows of the live panel stay resident in the L2s; results are the same up to fp32 summation order.
  * Not a step of the paper's method: a graph-dependent layout choice in the spirit of its input-sensitive
  * selection.  n_panels = 0 lets the library choose from the graph features (it may choose 1 = no panels, in
@@ -120,12 +120,30 @@ const char *sensei_status_string(int status);
  *                         unmodified as long as the object is used); A->row_ptr / A->col_idx must stay
  *                         unchanged too.  Synchronises `stream` once.  *out is a host object.
  *   sensei_panels_count : number of panels of the object.
- *   sensei_panels_destroy frees the host object only. */
+ *   sensei_panels_set_min_width: narrowest SpMM (floats per gathered row, after the internal padding of
+ *                         intermediates to a multiple of 32) that uses the panels; min_width >= 1.
+ *   sensei_panels_destroy frees the host object only.
+ * Measured choice (the analytic guess cannot see how skewed the column degrees are: the Reddit-shaped R-MAT
+ * graph is fastest with 2 panels from width 128 on, a uniform graph of the same density with 4 from width 64 on):
+ *   sensei_panels_tune_bytes: device scratch bytes sensei_panels_tune needs (256 when the graph features
+ *                         alone rule panels out).
+ *   sensei_panels_tune  : times the value-less SpMM of width 256 over the pattern with 1, 2, 3, 4, 6, 8 panels
+ *                         (stopping once times rise again) on scratch operands, then width 64 with and without
+ *                         the best count.  Returns the count (1 = keep the single pass; a gain under 3 % does
+ *                         not count) and the min_width to set (64 or 128).  ms_per_count: optional host array of
+ *                         2 * (SENSEI_PANELS_MAX + 1) floats, [q] = ms of the width-256 SpMM with q panels,
+ *                         [SENSEI_PANELS_MAX + 1 + q] = ms of the width-64 SpMM, -1 where not tried.  `scratch`: caller-owned device memory, 256-byte aligned, free to reuse
+ *                         afterwards.  Synchronises `stream` repeatedly; must not run under stream capture. */
 int sensei_panels_bytes(const sensei_csr *A, int n_panels, size_t *device_bytes);
 int sensei_panels_create(sensei_ctx *ctx, const sensei_csr *A, int n_panels, void *device_buf, size_t bytes, void *stream,
                          sensei_panels **out);
 int sensei_panels_count(const sensei_panels *panels);
+int sensei_panels_set_min_width(sensei_panels *panels, int min_width);
 int sensei_panels_destroy(sensei_panels *panels);
+#define SENSEI_PANELS_MAX 8
+int sensei_panels_tune_bytes(const sensei_csr *A, size_t *bytes);
+int sensei_panels_tune(sensei_ctx *ctx, const sensei_csr *A, void *scratch, size_t bytes, void *stream, int *n_panels_out,
+                       int *min_width_out, float *ms_per_count);
 
 /* ------------------------------------------------- primitives (steps of a layer) */
 

@@ -28,7 +28,8 @@ EXPORTS = (
     "sensei_row_broadcast", "sensei_spmm", "sensei_gemm", "sensei_gemv2", "sensei_sddmm_score", "sensei_edge_softmax",
     "sensei_gcn_workspace", "sensei_gcn_layer", "sensei_gat_workspace", "sensei_gat_layer", "sensei_select_workspace",
     "sensei_select", "sensei_profile_enable", "sensei_profile_read", "sensei_panels_bytes", "sensei_panels_create",
-    "sensei_panels_count", "sensei_panels_destroy",
+    "sensei_panels_count", "sensei_panels_destroy", "sensei_panels_set_min_width", "sensei_panels_tune_bytes",
+    "sensei_panels_tune",
 )
 
 
@@ -87,6 +88,9 @@ def lib():
         L.sensei_panels_create.argtypes = [vp, P(CsrStruct), i32, vp, sz, vp, P(vp)]
         L.sensei_panels_count.argtypes = [vp]
         L.sensei_panels_destroy.argtypes = [vp]
+        L.sensei_panels_set_min_width.argtypes = [vp, i32]
+        L.sensei_panels_tune_bytes.argtypes = [P(CsrStruct), P(sz)]
+        L.sensei_panels_tune.argtypes = [vp, P(CsrStruct), vp, sz, vp, P(ctypes.c_int), P(ctypes.c_int), P(f32)]
         L.sensei_profile_enable.argtypes = [vp, i32]
         L.sensei_profile_read.argtypes = [vp, i32, P(f32), i32, P(ctypes.c_int)]
         for name in EXPORTS:
@@ -131,7 +135,12 @@ def csr_struct(n_rows, n_cols, row_ptr, col_idx, val=None, panels=None) -> CsrSt
 class Panels:
     """Column-panel copy of a pattern (sensei_panels_create); owns the device buffer it lives in."""
 
-    def __init__(self, ctx: "Context", A: CsrStruct, n_panels: int = 0):
+    def __init__(self, ctx: "Context", A: CsrStruct, n_panels: int = 0, tune: bool = False):
+        """n_panels 1..8 forces a count, 0 lets the library guess from the graph features; tune=True measures instead."""
+        self.tune_ms = None
+        min_width = None
+        if tune:
+            n_panels, min_width, self.tune_ms = self.measure(ctx, A)
         need = ctypes.c_size_t()
         _check(lib().sensei_panels_bytes(ctypes.byref(A), n_panels, ctypes.byref(need)), "sensei_panels_bytes")
         self.buf = torch.empty(need.value + 256, dtype=torch.uint8, device=ctx.device)
@@ -140,6 +149,24 @@ class Panels:
         _check(lib().sensei_panels_create(ctx._h, ctypes.byref(A), n_panels, ctypes.c_void_p(p), need.value, _stream(),
                                           ctypes.byref(self._h)), "sensei_panels_create")
         self.count = lib().sensei_panels_count(self._h)
+        if min_width is not None:
+            _check(lib().sensei_panels_set_min_width(self._h, min_width), "sensei_panels_set_min_width")
+        self.min_width = 128 if min_width is None else min_width
+
+    @staticmethod
+    def measure(ctx: "Context", A: CsrStruct):
+        """sensei_panels_tune on a scratch buffer that is released afterwards -> (count, min_width, trial times:
+        [q] at width 256 and [9 + q] at width 64, -1 where not tried)."""
+        need = ctypes.c_size_t()
+        _check(lib().sensei_panels_tune_bytes(ctypes.byref(A), ctypes.byref(need)), "sensei_panels_tune_bytes")
+        buf = torch.empty(need.value + 256, dtype=torch.uint8, device=ctx.device)
+        p = (buf.data_ptr() + 255) // 256 * 256
+        count, width = ctypes.c_int(), ctypes.c_int()
+        ms = (ctypes.c_float * 18)()
+        _check(lib().sensei_panels_tune(ctx._h, ctypes.byref(A), ctypes.c_void_p(p), need.value, _stream(), ctypes.byref(count),
+                                        ctypes.byref(width), ms), "sensei_panels_tune")
+        del buf
+        return count.value, width.value, [float(x) for x in ms]
 
     @property
     def handle(self):

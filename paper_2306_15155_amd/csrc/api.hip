@@ -32,6 +32,7 @@ struct sensei_panels {
     int32_t *position;                         // position[k]: where original entry k sits in the panel copy
     int32_t off_q[SENSEI_MAX_PANELS + 1];      // first entry of each panel in the copy
     int n_chunks_q[SENSEI_MAX_PANELS];
+    int min_width = 128;                       // narrowest SpMM (floats per gathered row) that goes panel by panel
 };
 
 namespace {
@@ -90,12 +91,16 @@ ChunkPlan make_plan(const sensei_csr &A, Carver &cv) {
 
 bool gcn_is_agg(int id) { return id == SENSEI_GCN_DYN_AGG || id == SENSEI_GCN_DYNF_AGG || id == SENSEI_GCN_PRE_AGG; }
 
+// A slice-major copy of a user matrix the SpMM gathers from costs one pass over it (8 bytes per element); it pays
+// once every row is gathered many times.
+bool relayout_pays(const sensei_csr &A) { return A.nnz >= 16 * (int64_t)A.n_cols; }
+
 size_t gcn_ws(const sensei_csr &A, int f_in, int f_out, int id) {
     const int fs = gcn_is_agg(id) ? pad4(f_in) : pad32(f_out);
     size_t b = plan_bytes(A.nnz) + spmm_carry_bytes(A.nnz, fs);
     if (gcn_is_agg(id)) {
         b += align_up((size_t)A.n_rows * fs * sizeof(float), 256);                                    // U
-        if (id == SENSEI_GCN_DYN_AGG) b += align_up((size_t)A.n_cols * fs * sizeof(float), 256);      // c (x) X
+        b += align_up((size_t)A.n_cols * pad32(f_in) * sizeof(float), 256);                           // c (x) X, or the slice-major copy of X
     } else {
         b += align_up((size_t)A.n_cols * fs * sizeof(float), 256);                                    // Z = X.W
     }
@@ -116,6 +121,7 @@ size_t gat_ws(const sensei_csr &A, int f_in, int f_out, int id) {
     } else {
         b += spmm_carry_bytes(A.nnz, fi);
         b += align_up((size_t)A.n_rows * fi * sizeof(float), 256);             // U = alpha.X
+        b += align_up((size_t)A.n_cols * pad32(f_in) * sizeof(float), 256);    // slice-major copy of X
     }
     return b + 256;
 }
@@ -138,7 +144,7 @@ int auto_panels(const sensei_csr &A) {
 
 bool panels_usable(const sensei_csr &A, int f) {
     const sensei_panels *p = A.panels;
-    return p && p->n_panels > 1 && f >= 128 && p->src_row_ptr == A.row_ptr && p->src_col_idx == A.col_idx && p->nnz == A.nnz &&
+    return p && p->n_panels > 1 && f >= p->min_width && p->src_row_ptr == A.row_ptr && p->src_col_idx == A.col_idx && p->nnz == A.nnz &&
            p->n_rows == A.n_rows && p->n_cols == A.n_cols;
 }
 
@@ -147,10 +153,10 @@ bool panels_usable(const sensei_csr &A, int f) {
 // values in the order of the original pattern use the single pass.
 hipError_t spmm_any(const sensei_csr &A, int mode, const float *r, const float *c, const float *B, int64_t ldb, int f, float *C,
                     int64_t ldc, int f_store, int act, const ChunkPlan &plan, float *carry, hipStream_t s, KernelTimer *kt,
-                    bool val_in_panel_order = false, const float2 *mz = nullptr) {
+                    bool val_in_panel_order = false, const float2 *mz = nullptr, bool b_sliced = false) {
     const bool has_val = (mode == SENSEI_SPMM_WEIGHTED || mode == kSpmmSoftmax);
     if (!panels_usable(A, f) || (has_val && !val_in_panel_order))
-        return launch_spmm(A, mode, r, c, B, ldb, f, C, ldc, f_store, act, plan, carry, s, kt, false, true, mz);
+        return launch_spmm(A, mode, r, c, B, ldb, f, C, ldc, f_store, act, plan, carry, s, kt, false, true, mz, b_sliced);
     const sensei_panels &P = *A.panels;
     hipEvent_t t0 = kt ? kt->next() : nullptr, t1 = t0 ? kt->next() : nullptr;
     if (t1 && hipEventRecord(t0, s) != hipSuccess) return hipErrorUnknown;
@@ -164,7 +170,7 @@ hipError_t spmm_any(const sensei_csr &A, int mode, const float *r, const float *
         pq.chunk_nnz = P.chunk_nnz;
         pq.n_chunks = P.n_chunks_q[q];
         pq.chunk_row = P.chunk_row_q[q];
-        const hipError_t e = launch_spmm(Aq, mode, r, c, B, ldb, f, C, ldc, f_store, act, pq, carry, s, nullptr, q > 0, q == P.n_panels - 1, mz);
+        const hipError_t e = launch_spmm(Aq, mode, r, c, B, ldb, f, C, ldc, f_store, act, pq, carry, s, nullptr, q > 0, q == P.n_panels - 1, mz, b_sliced);
         if (e != hipSuccess) return e;
     }
     if (t1 && hipEventRecord(t1, s) != hipSuccess) return hipErrorUnknown;
@@ -185,16 +191,22 @@ int run_gcn(const sensei_csr &A, const float *r, const float *c, const sensei_ma
         const int fs = pad4(f_in);
         float *carry = cv.take<float>(spmm_carry_bytes(A.nnz, fs) / sizeof(float));
         float *U = cv.take<float>((size_t)A.n_rows * fs);
+        // The SpMM gathers from c (x) X (DYN_AGG, Eq. 3) or from X itself; either way from a slice-major copy when the
+        // rows are gathered often enough to pay for writing it.
         const float *src = X.ptr;
         int64_t ld_src = X.ld;
-        if (id == SENSEI_GCN_DYN_AGG) {  // row broadcast, value-less SpMM, row broadcast (Eq. 3)
-            float *T = cv.take<float>((size_t)A.n_cols * fs);
-            SENSEI_TRY(launch_row_broadcast(c, X.ptr, X.ld, A.n_cols, f_in, T, fs, SENSEI_ACT_NONE, s));
+        const bool sliced = relayout_pays(A);
+        if (sliced || id == SENSEI_GCN_DYN_AGG) {
+            float *T = cv.take<float>((size_t)A.n_cols * pad32(f_in));
+            const float *scale = (id == SENSEI_GCN_DYN_AGG) ? c : nullptr;
+            if (sliced) SENSEI_TRY(launch_to_slices(scale, X.ptr, X.ld, A.n_cols, f_in, T, s));
+            else SENSEI_TRY(launch_row_broadcast(scale, X.ptr, X.ld, A.n_cols, f_in, T, fs, SENSEI_ACT_NONE, s));
             src = T;
             ld_src = fs;
         }
         const bool scaled = (mode == SENSEI_SPMM_SCALED);
-        SENSEI_TRY(spmm_any(A, mode, scaled ? r : nullptr, scaled ? c : nullptr, src, ld_src, f_in, U, fs, f_in, SENSEI_ACT_NONE, plan, carry, s, kt));
+        SENSEI_TRY(spmm_any(A, mode, scaled ? r : nullptr, scaled ? c : nullptr, src, ld_src, f_in, U, fs, f_in, SENSEI_ACT_NONE, plan, carry, s, kt,
+                            false, nullptr, sliced));
         if (id == SENSEI_GCN_DYN_AGG) SENSEI_TRY(launch_row_broadcast(r, U, fs, A.n_rows, f_in, U, fs, SENSEI_ACT_NONE, s));
         SENSEI_TRY(launch_gemm(U, fs, W.ptr, W.ld, Y, ldy, A.n_rows, f_in, f_out, f_out, act, s, nullptr, gt));
     } else {
@@ -204,15 +216,18 @@ int run_gcn(const sensei_csr &A, const float *r, const float *c, const sensei_ma
         // DYNF_UPD: the column scaling is a row broadcast on Z = X.W, fused into the GEMM epilogue; the row
         // scaling and the activation are fused into the SpMM epilogue, so the SpMM itself is value-less.
         const float *z_scale = (id == SENSEI_GCN_DYNF_UPD) ? c : nullptr;
-        SENSEI_TRY(launch_gemm(X.ptr, X.ld, W.ptr, W.ld, Z, fs, A.n_cols, f_in, f_out, fs, SENSEI_ACT_NONE, s, z_scale, gt));
+        // Z is only ever gathered by the SpMM, so the GEMM writes it slice-major (the in-place row broadcast of
+        // DYN_UPD keeps the row-major form)
+        const bool sliced = (id != SENSEI_GCN_DYN_UPD);
+        SENSEI_TRY(launch_gemm(X.ptr, X.ld, W.ptr, W.ld, Z, fs, A.n_cols, f_in, f_out, fs, SENSEI_ACT_NONE, s, z_scale, gt, sliced));
         if (id == SENSEI_GCN_DYN_UPD) {
             SENSEI_TRY(launch_row_broadcast(c, Z, fs, A.n_cols, fs, Z, fs, SENSEI_ACT_NONE, s));
             SENSEI_TRY(spmm_any(A, mode, nullptr, nullptr, Z, fs, fs, Y, ldy, f_out, SENSEI_ACT_NONE, plan, carry, s, kt));
             SENSEI_TRY(launch_row_broadcast(r, Y, ldy, A.n_rows, f_out, Y, ldy, act, s));
         } else if (id == SENSEI_GCN_DYNF_UPD) {
-            SENSEI_TRY(spmm_any(A, SENSEI_SPMM_PATTERN, r, nullptr, Z, fs, fs, Y, ldy, f_out, act, plan, carry, s, kt));
+            SENSEI_TRY(spmm_any(A, SENSEI_SPMM_PATTERN, r, nullptr, Z, fs, fs, Y, ldy, f_out, act, plan, carry, s, kt, false, nullptr, true));
         } else {
-            SENSEI_TRY(spmm_any(A, mode, nullptr, nullptr, Z, fs, fs, Y, ldy, f_out, act, plan, carry, s, kt));
+            SENSEI_TRY(spmm_any(A, mode, nullptr, nullptr, Z, fs, fs, Y, ldy, f_out, act, plan, carry, s, kt, false, nullptr, true));
         }
     }
     return SENSEI_OK;
@@ -237,9 +252,11 @@ int run_gat(const sensei_csr &A, const sensei_mat &X, const sensei_mat &W, const
 
     SENSEI_TRY(launch_chunk_rows(A, plan, s));
     const bool fold = (id == SENSEI_GAT_RECOMP_FOLD || id == SENSEI_GAT_REUSE_FOLD);
+    const bool theta_sliced = gat_is_reuse(id);
     if (!fold) {  // Theta = X.W, then the two projections of Theta
-        SENSEI_TRY(launch_gemm(X.ptr, X.ld, W.ptr, W.ld, theta, fo, A.n_cols, f_in, f_out, fo, SENSEI_ACT_NONE, s, nullptr, gt));
-        SENSEI_TRY(launch_gemv2(theta, fo, A.n_cols, f_out, a_l, a_r, s_l, s_r, s));
+        // Theta is slice-major when the SpMM gathers from it (reuse); the recompute id only projects it
+        SENSEI_TRY(launch_gemm(X.ptr, X.ld, W.ptr, W.ld, theta, fo, A.n_cols, f_in, f_out, fo, SENSEI_ACT_NONE, s, nullptr, gt, theta_sliced));
+        SENSEI_TRY(launch_gemv2(theta, fo, A.n_cols, f_out, a_l, a_r, s_l, s_r, s, theta_sliced));
     } else {      // (X.W).a = X.(W.a)
         SENSEI_TRY(launch_gemv2(W.ptr, W.ld, f_in, f_out, a_l, a_r, v_l, v_r, s));
         SENSEI_TRY(launch_gemv2(X.ptr, X.ld, A.n_cols, f_in, v_l, v_r, s_l, s_r, s));
@@ -252,13 +269,20 @@ int run_gat(const sensei_csr &A, const sensei_mat &X, const sensei_mat &W, const
     sensei_csr Aw = A;
     Aw.val = logits;
     if (gat_is_reuse(id)) {
-        if (fold) SENSEI_TRY(launch_gemm(X.ptr, X.ld, W.ptr, W.ld, theta, fo, A.n_cols, f_in, f_out, fo, SENSEI_ACT_NONE, s, nullptr, gt));
+        if (fold) SENSEI_TRY(launch_gemm(X.ptr, X.ld, W.ptr, W.ld, theta, fo, A.n_cols, f_in, f_out, fo, SENSEI_ACT_NONE, s, nullptr, gt, true));
         float *carry = cv.take<float>(spmm_carry_bytes(A.nnz, fo) / sizeof(float));
-        SENSEI_TRY(spmm_any(Aw, kSpmmSoftmax, nullptr, nullptr, theta, fo, fo, Y, ldy, f_out, act, plan, carry, s, kt, by_panel, stats));
+        SENSEI_TRY(spmm_any(Aw, kSpmmSoftmax, nullptr, nullptr, theta, fo, fo, Y, ldy, f_out, act, plan, carry, s, kt, by_panel, stats, true));
     } else {
         float *carry = cv.take<float>(spmm_carry_bytes(A.nnz, fi) / sizeof(float));
         float *U = cv.take<float>((size_t)A.n_rows * fi);
-        SENSEI_TRY(spmm_any(Aw, kSpmmSoftmax, nullptr, nullptr, X.ptr, X.ld, f_in, U, fi, f_in, SENSEI_ACT_NONE, plan, carry, s, kt, by_panel, stats));
+        const float *src = X.ptr;
+        const bool sliced = relayout_pays(A);
+        if (sliced) {
+            float *T = cv.take<float>((size_t)A.n_cols * pad32(f_in));
+            SENSEI_TRY(launch_to_slices(nullptr, X.ptr, X.ld, A.n_cols, f_in, T, s));
+            src = T;
+        }
+        SENSEI_TRY(spmm_any(Aw, kSpmmSoftmax, nullptr, nullptr, src, X.ld, f_in, U, fi, f_in, SENSEI_ACT_NONE, plan, carry, s, kt, by_panel, stats, sliced));
         SENSEI_TRY(launch_gemm(U, fi, W.ptr, W.ld, Y, ldy, A.n_rows, f_in, f_out, f_out, act, s, nullptr, gt));
     }
     return SENSEI_OK;
@@ -310,12 +334,14 @@ double gcn_cost(const sensei_ctx &c, const Features &g, int f_in, int f_out, int
             break;
         case SENSEI_GCN_DYNF_AGG:
             t += t_spmm(c, g, fs, kSpmmScaled);
+            if (g.nnz >= 16.0 * g.n_cols) t += t_stream(c, 8.0 * g.n_cols * fs);  // slice-major copy of X
             break;
         case SENSEI_GCN_DYNF_UPD:  // scalings live in the GEMM and SpMM epilogues
             t += t_spmm(c, g, fs, kSpmmPattern);
             break;
         default:
             t += t_spmm(c, g, fs, kSpmmWeighted);
+            if (agg && g.nnz >= 16.0 * g.n_cols) t += t_stream(c, 8.0 * g.n_cols * fs);
             break;
     }
     return t;
@@ -333,6 +359,7 @@ double gat_cost(const sensei_ctx &c, const Features &g, int f_in, int f_out, int
         t += t_spmm(c, g, f_out, kSpmmWeighted);
     } else {
         t += t_spmm(c, g, f_in, kSpmmWeighted) + t_gemm(c, g.n_rows, f_in, f_out);
+        if (g.nnz >= 16.0 * g.n_cols) t += t_stream(c, 8.0 * g.n_cols * f_in);  // slice-major copy of X
     }
     return t;
 }
@@ -465,6 +492,48 @@ int sensei_panels_bytes(const sensei_csr *A, int n_panels, size_t *device_bytes)
     return SENSEI_OK;
 }
 
+// Builds the panel copy for Q panels into `base` (laid out as panels_layout says) and waits for it.
+static int build_panels(sensei_panels *P, const sensei_csr &A, int Q, char *base, hipStream_t s) {
+    size_t rp_each, col_bytes, chunk_each, temp_bytes;
+    panels_layout(A, Q, &rp_each, &col_bytes, &chunk_each, &temp_bytes);
+    P->n_panels = Q;
+    P->width = (int)((A.n_cols + Q - 1) / Q);
+    if (P->width < 1) P->width = 1;
+    P->n_rows = A.n_rows; P->n_cols = A.n_cols; P->nnz = A.nnz;
+    P->src_row_ptr = A.row_ptr; P->src_col_idx = A.col_idx;
+    P->chunk_nnz = choose_chunk_nnz(A.nnz);
+    size_t used = 0;
+    for (int q = 0; q < Q; ++q) { P->row_ptr_q[q] = reinterpret_cast<int32_t *>(base + used); used += rp_each; }
+    for (int q = 0; q < Q; ++q) { P->chunk_row_q[q] = reinterpret_cast<int32_t *>(base + used); used += chunk_each; }
+    int32_t *col_all = reinterpret_cast<int32_t *>(base + used); used += col_bytes;
+    int32_t *perm_all = reinterpret_cast<int32_t *>(base + used); used += col_bytes;
+    int32_t *off = reinterpret_cast<int32_t *>(base + used); used += 256;
+    Carver cv(base + used, temp_bytes);
+    ChunkPlan plan = make_plan(A, cv);
+    int32_t *scan_temp = cv.take<int32_t>(scan_temp_bytes(A.n_rows + 1) / sizeof(int32_t));
+    int32_t off_host[SENSEI_MAX_PANELS + 1] = {0};
+    if (launch_chunk_rows(A, plan, s) != hipSuccess ||
+        launch_panel_build(A, plan, Q, P->width, P->row_ptr_q, off, col_all, perm_all, scan_temp, s) != hipSuccess ||
+        hipMemcpyAsync(off_host, off, (size_t)(Q + 1) * sizeof(int32_t), hipMemcpyDeviceToHost, s) != hipSuccess ||
+        hipStreamSynchronize(s) != hipSuccess)
+        return SENSEI_HIP_ERROR;
+    for (int q = 0; q < Q; ++q) {
+        P->nnz_q[q] = (int64_t)off_host[q + 1] - off_host[q];
+        P->col_q[q] = col_all + off_host[q];
+        P->off_q[q] = off_host[q];
+        P->n_chunks_q[q] = P->nnz_q[q] <= 0 ? 1 : (int)((P->nnz_q[q] + P->chunk_nnz - 1) / P->chunk_nnz);
+        sensei_csr Aq = A;
+        Aq.nnz = P->nnz_q[q]; Aq.row_ptr = P->row_ptr_q[q]; Aq.col_idx = P->col_q[q];
+        ChunkPlan pq;
+        pq.chunk_nnz = P->chunk_nnz; pq.n_chunks = P->n_chunks_q[q]; pq.chunk_row = P->chunk_row_q[q];
+        if (launch_chunk_rows(Aq, pq, s) != hipSuccess) return SENSEI_HIP_ERROR;
+    }
+    P->position = perm_all;
+    P->off_q[Q] = off_host[Q];
+    if (off_host[Q] != (int32_t)A.nnz) return SENSEI_INVALID_ARGUMENT;  // malformed pattern
+    return SENSEI_OK;
+}
+
 int sensei_panels_create(sensei_ctx *ctx, const sensei_csr *A, int n_panels, void *device_buf, size_t bytes, void *stream,
                          sensei_panels **out) {
     if (!ctx || !csr_ok(A, false) || !out || !device_buf || n_panels < 0 || n_panels > SENSEI_MAX_PANELS) return SENSEI_INVALID_ARGUMENT;
@@ -474,47 +543,130 @@ int sensei_panels_create(sensei_ctx *ctx, const sensei_csr *A, int n_panels, voi
     if (bytes < panels_layout(*A, Q, &rp_each, &col_bytes, &chunk_each, &temp_bytes)) return SENSEI_WORKSPACE_TOO_SMALL;
     sensei_panels *P = new (std::nothrow) sensei_panels;
     if (!P) return SENSEI_HIP_ERROR;
-    P->n_panels = Q;
-    P->width = (int)((A->n_cols + Q - 1) / Q);
-    if (P->width < 1) P->width = 1;
-    P->n_rows = A->n_rows; P->n_cols = A->n_cols; P->nnz = A->nnz;
-    P->src_row_ptr = A->row_ptr; P->src_col_idx = A->col_idx;
-    P->chunk_nnz = choose_chunk_nnz(A->nnz);
-    char *base = static_cast<char *>(device_buf);
-    size_t used = 0;
-    for (int q = 0; q < Q; ++q) { P->row_ptr_q[q] = reinterpret_cast<int32_t *>(base + used); used += rp_each; }
-    for (int q = 0; q < Q; ++q) { P->chunk_row_q[q] = reinterpret_cast<int32_t *>(base + used); used += chunk_each; }
-    int32_t *col_all = reinterpret_cast<int32_t *>(base + used); used += col_bytes;
-    int32_t *perm_all = reinterpret_cast<int32_t *>(base + used); used += col_bytes;
-    int32_t *off = reinterpret_cast<int32_t *>(base + used); used += 256;
-    hipStream_t s = as_stream(stream);
-    Carver cv(base + used, temp_bytes);
-    ChunkPlan plan = make_plan(*A, cv);
-    int32_t *scan_temp = cv.take<int32_t>(scan_temp_bytes(A->n_rows + 1) / sizeof(int32_t));
-    int status = SENSEI_OK;
-    int32_t off_host[SENSEI_MAX_PANELS + 1] = {0};
-    if (launch_chunk_rows(*A, plan, s) != hipSuccess ||
-        launch_panel_build(*A, plan, Q, P->width, P->row_ptr_q, off, col_all, perm_all, scan_temp, s) != hipSuccess ||
-        hipMemcpyAsync(off_host, off, (size_t)(Q + 1) * sizeof(int32_t), hipMemcpyDeviceToHost, s) != hipSuccess ||
-        hipStreamSynchronize(s) != hipSuccess)
-        status = SENSEI_HIP_ERROR;
-    for (int q = 0; q < Q && status == SENSEI_OK; ++q) {
-        P->nnz_q[q] = (int64_t)off_host[q + 1] - off_host[q];
-        P->col_q[q] = col_all + off_host[q];
-        P->off_q[q] = off_host[q];
-        P->n_chunks_q[q] = P->nnz_q[q] <= 0 ? 1 : (int)((P->nnz_q[q] + P->chunk_nnz - 1) / P->chunk_nnz);
-        sensei_csr Aq = *A;
-        Aq.nnz = P->nnz_q[q]; Aq.row_ptr = P->row_ptr_q[q]; Aq.col_idx = P->col_q[q];
-        ChunkPlan pq;
-        pq.chunk_nnz = P->chunk_nnz; pq.n_chunks = P->n_chunks_q[q]; pq.chunk_row = P->chunk_row_q[q];
-        if (launch_chunk_rows(Aq, pq, s) != hipSuccess) status = SENSEI_HIP_ERROR;
-    }
-    P->position = perm_all;
-    P->off_q[Q] = off_host[Q];
-    if (status == SENSEI_OK && off_host[Q] != (int32_t)A->nnz) status = SENSEI_INVALID_ARGUMENT;  // malformed pattern
+    const int status = build_panels(P, *A, Q, static_cast<char *>(device_buf), as_stream(stream));
     if (status != SENSEI_OK) { delete P; return status; }
     *out = P;
     return SENSEI_OK;
+}
+
+int sensei_panels_set_min_width(sensei_panels *panels, int min_width) {
+    if (!panels || min_width < 1) return SENSEI_INVALID_ARGUMENT;
+    panels->min_width = min_width;
+    return SENSEI_OK;
+}
+
+// ---- measured choice of the panel count
+namespace {
+constexpr int kTuneWide = 256, kTuneNarrow = 64;
+constexpr int kTuneCounts[] = {1, 2, 3, 4, 6, 8};
+
+bool tune_worthwhile(const sensei_csr &A) {
+    const double slice = (double)A.n_cols * 128.0;
+    const double avg = A.n_rows > 0 ? (double)A.nnz / A.n_rows : 0.0;
+    return slice >= 6e6 && avg >= 32.0;  // a slice the L2s hold, or rows too short to be visited once per panel
+}
+
+struct TuneLayout {
+    size_t b_bytes, c_bytes, sparse_bytes, panel_bytes, total;
+};
+TuneLayout tune_layout(const sensei_csr &A) {
+    TuneLayout t;
+    t.b_bytes = align_up((size_t)A.n_cols * kTuneWide * sizeof(float), 256);
+    t.c_bytes = align_up((size_t)A.n_rows * kTuneWide * sizeof(float), 256);
+    t.sparse_bytes = plan_bytes(A.nnz) + spmm_carry_bytes(A.nnz, kTuneWide) + 256;
+    size_t a, b, c, d;
+    t.panel_bytes = panels_layout(A, SENSEI_MAX_PANELS, &a, &b, &c, &d);
+    t.total = t.b_bytes + t.c_bytes + t.sparse_bytes + t.panel_bytes + 256;
+    return t;
+}
+}  // namespace
+
+int sensei_panels_tune_bytes(const sensei_csr *A, size_t *bytes) {
+    if (!csr_ok(A, false) || !bytes) return SENSEI_INVALID_ARGUMENT;
+    *bytes = tune_worthwhile(*A) ? tune_layout(*A).total : 256;
+    return SENSEI_OK;
+}
+
+int sensei_panels_tune(sensei_ctx *ctx, const sensei_csr *A, void *scratch, size_t bytes, void *stream, int *n_panels_out,
+                       int *min_width_out, float *ms_per_count) {
+    if (!ctx || !csr_ok(A, false) || !n_panels_out || !min_width_out) return SENSEI_INVALID_ARGUMENT;
+    if (ms_per_count) for (int q = 0; q < 2 * (SENSEI_MAX_PANELS + 1); ++q) ms_per_count[q] = -1.f;
+    *n_panels_out = 1;
+    *min_width_out = 128;
+    if (!tune_worthwhile(*A)) return SENSEI_OK;
+    const TuneLayout L = tune_layout(*A);
+    if (!scratch || reinterpret_cast<uintptr_t>(scratch) % 256 != 0) return SENSEI_INVALID_ARGUMENT;
+    if (bytes < L.total) return SENSEI_WORKSPACE_TOO_SMALL;
+    hipStream_t s = as_stream(stream);
+    char *base = static_cast<char *>(scratch);
+    float *B = reinterpret_cast<float *>(base);
+    float *C = reinterpret_cast<float *>(base + L.b_bytes);
+    char *sparse = base + L.b_bytes + L.c_bytes;
+    char *panel_buf = sparse + L.sparse_bytes;
+    if (hipMemsetAsync(B, 0, L.b_bytes, s) != hipSuccess) return SENSEI_HIP_ERROR;
+    Carver cv(sparse, L.sparse_bytes);
+    ChunkPlan plan = make_plan(*A, cv);
+    float *carry = cv.take<float>(spmm_carry_bytes(A->nnz, kTuneWide) / sizeof(float));
+    if (launch_chunk_rows(*A, plan, s) != hipSuccess) return SENSEI_HIP_ERROR;
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) return SENSEI_HIP_ERROR;
+    if (hipEventCreate(&e1) != hipSuccess) { hipEventDestroy(e0); return SENSEI_HIP_ERROR; }
+    sensei_panels P;
+    P.min_width = 1;
+    // fastest of two timed runs after a warm-up, gathered operand slice-major to the width as the layers' intermediates are;
+    // Q = 1 runs the plain single pass
+    auto time_spmm = [&](int Q, int f, float *ms) -> int {
+        sensei_csr Aq = *A;
+        Aq.val = nullptr;
+        Aq.panels = Q > 1 ? &P : nullptr;
+        float best = 1e30f;
+        for (int it = 0; it < 3; ++it) {
+            if (hipEventRecord(e0, s) != hipSuccess) return SENSEI_HIP_ERROR;
+            if (spmm_any(Aq, SENSEI_SPMM_PATTERN, nullptr, nullptr, B, f, f, C, f, f, SENSEI_ACT_NONE, plan, carry, s, nullptr, false, nullptr, true) != hipSuccess)
+                return SENSEI_HIP_ERROR;
+            float t = 0.f;
+            if (hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&t, e0, e1) != hipSuccess)
+                return SENSEI_HIP_ERROR;
+            if (it > 0 && t < best) best = t;
+        }
+        *ms = best;
+        return SENSEI_OK;
+    };
+    int status = SENSEI_OK, best_q = 1, built = 0;
+    float best_ms = 1e30f, single_ms = 0.f;
+    const double slice = (double)A->n_cols * 128.0;
+    for (int Q : kTuneCounts) {
+        if (Q > 1 && slice / Q < 1e6) break;  // panels far smaller than one L2 gain nothing
+        if (Q > 1) {
+            status = build_panels(&P, *A, Q, panel_buf, s);
+            if (status != SENSEI_OK) break;
+            built = Q;
+        }
+        float ms = 0.f;
+        status = time_spmm(Q, kTuneWide, &ms);
+        if (status != SENSEI_OK) break;
+        if (ms_per_count) ms_per_count[Q] = ms;
+        if (Q == 1) single_ms = ms;
+        if (ms < 0.98f * best_ms) { best_ms = ms; best_q = Q; }  // one more pass over the rows must buy at least 2 %
+        else if (ms > 1.03f * best_ms || best_q == 1) break;     // past the minimum, or two panels gain nothing
+    }
+    if (status == SENSEI_OK && best_q > 1 && best_ms > 0.97f * single_ms) best_q = 1;  // not worth a second copy of the pattern
+    if (status == SENSEI_OK && best_q > 1) {
+        // do narrow SpMMs gain as well?
+        if (built != best_q) status = build_panels(&P, *A, best_q, panel_buf, s);
+        float with_ms = 0.f, without_ms = 0.f;
+        if (status == SENSEI_OK) status = time_spmm(best_q, kTuneNarrow, &with_ms);
+        if (status == SENSEI_OK) status = time_spmm(1, kTuneNarrow, &without_ms);
+        if (status == SENSEI_OK && with_ms < 0.97f * without_ms) *min_width_out = kTuneNarrow;
+        if (status == SENSEI_OK && ms_per_count) {
+            ms_per_count[SENSEI_MAX_PANELS + 1 + 1] = without_ms;
+            ms_per_count[SENSEI_MAX_PANELS + 1 + best_q] = with_ms;
+        }
+    }
+    hipEventDestroy(e0);
+    hipEventDestroy(e1);
+    if (status == SENSEI_OK) *n_panels_out = best_q;
+    return status;
 }
 
 int sensei_panels_count(const sensei_panels *panels) { return panels ? panels->n_panels : 0; }

@@ -17,6 +17,7 @@ struct GemmArgs {
     float *Y;
     long long lda, ldw, ldy, n;
     int k, m, m_store, act, n_bn;
+    int y_sliced;  // Y stored slice-major in tiles of 32 columns: (row, col) at Y[(col / 32) * n * 32 + row * 32 + col % 32]
 };
 
 // Block tile BM x BN, 4 wavefronts laid out WGM x WGN, each computing TM x TN tiles of 32 x 32
@@ -132,6 +133,8 @@ __global__ __launch_bounds__(kThreads) void k_gemm(GemmArgs g) {
         for (int j = 0; j < TN; ++j) {
             const int col = n0 + (wn * TN + j) * 32 + ll;
             if (col >= g.m_store) continue;
+            const long long y_col = g.y_sliced ? (long long)(col >> 5) * g.n * 32 + (col & 31) : (long long)col;
+            const long long y_ld = g.y_sliced ? 32 : g.ldy;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const long long row = m0 + (wm * TM + i) * 32 + 8 * (r / 4) + 4 * kh + (r % 4);
@@ -139,7 +142,7 @@ __global__ __launch_bounds__(kThreads) void k_gemm(GemmArgs g) {
                     float y = acc[i][j][r];
                     if (g.row_scale) y *= g.row_scale[row];
                     if (g.act == SENSEI_ACT_RELU) y = y > 0.f ? y : 0.f;
-                    g.Y[row * g.ldy + col] = y;
+                    g.Y[row * y_ld + y_col] = y;
                 }
             }
         }
@@ -164,13 +167,15 @@ hipError_t gemm_launch_vec(const GemmArgs &g, int avec, int bvec, hipStream_t s)
 template <int VEC>
 __global__ __launch_bounds__(kThreads) void k_gemv2(const float *__restrict__ A, long long lda, long long n, int k,
                                                      const float *__restrict__ v1, const float *__restrict__ v2,
-                                                     float *__restrict__ y1, float *__restrict__ y2) {
+                                                     float *__restrict__ y1, float *__restrict__ y2, int a_sliced) {
     const long long row = (long long)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
     if (row >= n) return;
     const int lane = threadIdx.x & 63;
-    const float *a = A + row * lda;
+    const float *a0 = a_sliced ? A + row * 32 : A + row * lda;
     float d1 = 0.f, d2 = 0.f;
     for (int kk = lane * VEC; kk < k; kk += 64 * VEC) {
+        // slice-major: columns kk.. of this row sit in tile kk / 32 (a 4-float piece never straddles tiles)
+        const float *a = a_sliced ? a0 + (long long)(kk >> 5) * n * 32 + (kk & 31) - kk : a0;
         float x[VEC];
         if (VEC == 4) { float4 v = *reinterpret_cast<const float4 *>(a + kk); x[0] = v.x; x[1 % VEC] = v.y; x[2 % VEC] = v.z; x[3 % VEC] = v.w; }
         else if (VEC == 2) { float2 v = *reinterpret_cast<const float2 *>(a + kk); x[0] = v.x; x[1 % VEC] = v.y; }
@@ -192,7 +197,7 @@ __global__ __launch_bounds__(kThreads) void k_gemv2(const float *__restrict__ A,
 }  // namespace
 
 hipError_t launch_gemm(const float *A, int64_t lda, const float *W, int64_t ldw, float *Y, int64_t ldy, int64_t n,
-                       int k, int m, int m_store, int act, hipStream_t s, const float *row_scale, KernelTimer *timer) {
+                       int k, int m, int m_store, int act, hipStream_t s, const float *row_scale, KernelTimer *timer, bool y_sliced) {
     if (n <= 0 || m_store <= 0) return hipSuccess;
     hipEvent_t t0 = timer ? timer->next() : nullptr, t1 = t0 ? timer->next() : nullptr;
     if (t1 && hipEventRecord(t0, s) != hipSuccess) return hipErrorUnknown;
@@ -203,7 +208,7 @@ hipError_t launch_gemm(const float *A, int64_t lda, const float *W, int64_t ldw,
     GemmArgs g;
     g.row_scale = row_scale;
     g.A = A; g.W = W; g.Y = Y; g.lda = lda; g.ldw = ldw; g.ldy = ldy; g.n = n;
-    g.k = k; g.m = m; g.m_store = m_store; g.act = act;
+    g.k = k; g.m = m; g.m_store = m_store; g.act = act; g.y_sliced = y_sliced ? 1 : 0;
     int avec = 1, bvec = 1;
     const uintptr_t aa = reinterpret_cast<uintptr_t>(A), wa = reinterpret_cast<uintptr_t>(W);
     if (k % 4 == 0 && lda % 4 == 0 && aa % 16 == 0) avec = 4;
@@ -232,16 +237,18 @@ hipError_t launch_gemm(const float *A, int64_t lda, const float *W, int64_t ldw,
 }
 
 hipError_t launch_gemv2(const float *A, int64_t lda, int64_t n, int k, const float *v1, const float *v2, float *y1,
-                        float *y2, hipStream_t s) {
+                        float *y2, hipStream_t s, bool a_sliced) {
     if (n <= 0) return hipSuccess;
     dim3 grid((unsigned)((n + kThreads / 64 - 1) / (kThreads / 64)));
     const uintptr_t aa = reinterpret_cast<uintptr_t>(A);
+    if (a_sliced) lda = 32;
+    const int sl = a_sliced ? 1 : 0;
     if (k % 4 == 0 && lda % 4 == 0 && aa % 16 == 0)
-        hipLaunchKernelGGL((k_gemv2<4>), grid, dim3(kThreads), 0, s, A, (long long)lda, (long long)n, k, v1, v2, y1, y2);
+        hipLaunchKernelGGL((k_gemv2<4>), grid, dim3(kThreads), 0, s, A, (long long)lda, (long long)n, k, v1, v2, y1, y2, sl);
     else if (k % 2 == 0 && lda % 2 == 0 && aa % 8 == 0)
-        hipLaunchKernelGGL((k_gemv2<2>), grid, dim3(kThreads), 0, s, A, (long long)lda, (long long)n, k, v1, v2, y1, y2);
+        hipLaunchKernelGGL((k_gemv2<2>), grid, dim3(kThreads), 0, s, A, (long long)lda, (long long)n, k, v1, v2, y1, y2, sl);
     else
-        hipLaunchKernelGGL((k_gemv2<1>), grid, dim3(kThreads), 0, s, A, (long long)lda, (long long)n, k, v1, v2, y1, y2);
+        hipLaunchKernelGGL((k_gemv2<1>), grid, dim3(kThreads), 0, s, A, (long long)lda, (long long)n, k, v1, v2, y1, y2, sl);
     return hipGetLastError();
 }
 

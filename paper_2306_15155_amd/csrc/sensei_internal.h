@@ -61,14 +61,17 @@ size_t spmm_carry_bytes(int64_t nnz, int f);  // upper bound
 hipError_t launch_spmm(const sensei_csr &A, int mode, const float *r, const float *c, const float *B, int64_t ldb,
                        int f, float *C, int64_t ldc, int f_store, int act, const ChunkPlan &p, float *carry,
                        hipStream_t s, KernelTimer *timer = nullptr, bool accumulate = false, bool finalize = true,
-                       const float2 *mz = nullptr);
+                       const float2 *mz = nullptr, bool b_sliced = false);
+// b_sliced: B is stored slice-major in tiles of 32 floats, element (j, col) at B[(col / 32) * n_cols * 32 + j * 32 + col % 32]
+// (f padded to a multiple of 32, B 128-byte aligned); `ldb` is ignored.
+inline size_t sliced_index(int64_t n_rows, int64_t row, int col) { return (size_t)(col >> 5) * (size_t)n_rows * 32 + (size_t)row * 32 + (col & 31); }
 // Internal SpMM mode (not part of the C ABI): A.val holds attention logits e_ij, `mz[i]` = (max_j e_ij, sum_j exp(e_ij - max));
 // the kernel weighs neighbour j of row i by exp(e_ij - max_i) and scales the finished row by 1 / sum, i.e. it aggregates
 // with the softmax weights of Eq. 6 without storing them.
 constexpr int kSpmmSoftmax = 3;
 
 // ---- column panels: a copy of the pattern with the columns of each panel contiguous
-#define SENSEI_MAX_PANELS 8
+#define SENSEI_MAX_PANELS SENSEI_PANELS_MAX
 size_t scan_temp_bytes(int n);
 // rp[q]: n_rows + 1 ints per panel (row pointers of the panel copy on return); off: n_panels + 1 ints (panel starts in
 // col_out); perm_out[k] = position of original entry k in the panel copy; `plan` is the chunk plan of A (already computed
@@ -83,6 +86,9 @@ hipError_t launch_sddmm_norm(const sensei_csr &A, const float *r, const float *c
                              hipStream_t s);
 hipError_t launch_row_broadcast(const float *s_vec, const float *X, int64_t ldx, int64_t n, int f, float *Y,
                                 int64_t ldy, int act, hipStream_t s);
+
+// Y (slice-major, pad32(f) columns, 128-byte aligned, n * pad32(f) floats) = s_vec (x) X, s_vec optional; pad columns = 0
+hipError_t launch_to_slices(const float *s_vec, const float *X, int64_t ldx, int64_t n, int f, float *Y, hipStream_t s);
 
 // ---- attention: logits, per-row softmax statistics, normalised weights
 hipError_t launch_score(const sensei_csr &A, const float *s_l, const float *s_r, float slope, float *e,
@@ -101,9 +107,10 @@ size_t softmax_ws_bytes(const sensei_csr &A);
 // row_scale may be null (no scaling).
 hipError_t launch_gemm(const float *A, int64_t lda, const float *W, int64_t ldw, float *Y, int64_t ldy, int64_t n,
                        int k, int m, int m_store, int act, hipStream_t s, const float *row_scale = nullptr,
-                       KernelTimer *timer = nullptr);
+                       KernelTimer *timer = nullptr, bool y_sliced = false);
+// y_sliced / a_sliced: that matrix is stored slice-major in tiles of 32 floats (see launch_spmm); its leading dimension is ignored.
 hipError_t launch_gemv2(const float *A, int64_t lda, int64_t n, int k, const float *v1, const float *v2, float *y1,
-                        float *y2, hipStream_t s);
+                        float *y2, hipStream_t s, bool a_sliced = false);
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline int pad4(int f) { return (f + 3) & ~3; }

@@ -62,6 +62,7 @@ struct SpmmArgs {
     const float2 *mz;  // softmax mode: per-row (max logit, sum of exp(logit - max))
     float *C, *carry;
     long long ldb, ldc;
+    long long tile_stride_b;  // bytes from feature tile t of B to tile t + 1: 4*VEC*LPG when rows are contiguous, a whole slice otherwise
     int n_rows, nnz, chunk_nnz, n_chunks;
     int f, f_store, f_carry, n_tiles, act, store_vec_ok;
     int tiles_live, n_groups;  // feature tiles worked on at the same time; chunk groups (blocks per tile)
@@ -92,7 +93,10 @@ __device__ __forceinline__ float inv_z(float z) { return z > 0.f ? 1.f / z : 0.f
 // Consecutive workgroups go to consecutive XCDs and take consecutive tiles of
 // the live tile set, so each XCD's L2 keeps seeing the same 128-byte slice of
 // the gathered matrix; the number of live tiles bounds how much of that matrix
-// is in use at one time.
+// is in use at one time.  B is either row-major (a row holds all its tiles) or
+// slice-major (all rows of tile 0, then all rows of tile 1, ...: what an XCD
+// gathers from is then one contiguous range, which spreads evenly over the
+// memory channels whatever the row pitch).
 // MODE kSpmmSoftmax: `val` holds attention logits; the weight of an entry is exp(logit - m_i) and the row is
 // scaled by 1/z_i when it is complete, so the normalised attention weights are never stored (Eq. 6).
 template <int VEC, int LPG, int MODE, bool OFF32>
@@ -112,8 +116,8 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
     const int g = lane / LPG;
     const int f0 = tile * TF + (lane % LPG) * VEC;
     const bool fok = f0 < a.f;
-    const char *Bb = reinterpret_cast<const char *>(a.B);
-    const unsigned f0_b = fok ? (unsigned)f0 * 4u : 0u;
+    const char *Bb = reinterpret_cast<const char *>(a.B) + (long long)tile * a.tile_stride_b;
+    const unsigned f0_b = fok ? (unsigned)((lane % LPG) * VEC) * 4u : 0u;
     const unsigned ldb_b32 = (unsigned)(a.ldb * 4);
     const size_t ldb_b64 = (size_t)a.ldb * 4;
 
@@ -506,6 +510,34 @@ __global__ void k_row_broadcast(const float *__restrict__ s, const float *X, lon
     x.store(Y + i * ldy + q);
 }
 
+// Copy of X (n x f, row-major) into slice-major tiles of 32 columns, optionally scaled per row; the pad columns
+// up to the next multiple of 32 are written as zeros.  One thread per (row, 4 columns).
+__global__ void k_to_slices(const float *__restrict__ s, const float *__restrict__ X, long long ldx, long long n, int f,
+                            float *__restrict__ Y, int x_vec_ok) {
+    const int fp4 = ((f + 31) & ~31) / 4;
+    const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= n * fp4) return;
+    // consecutive threads walk the rows of one tile: reads are 16-byte pieces 8 to a row, writes are contiguous
+    const long long per_tile = n * 8;
+    const int tile = (int)(t / per_tile);
+    const long long in_tile = t % per_tile;
+    const long long i = in_tile >> 3;
+    const int q = tile * 32 + (int)(in_tile & 7) * 4;
+    const float sc = s ? s[i] : 1.f;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    const float *x = X + i * ldx + q;
+    if (x_vec_ok && q + 4 <= f) {
+        v = *reinterpret_cast<const float4 *>(x);
+    } else {
+        if (q < f) v.x = x[0];
+        if (q + 1 < f) v.y = x[1];
+        if (q + 2 < f) v.z = x[2];
+        if (q + 3 < f) v.w = x[3];
+    }
+    v.x *= sc; v.y *= sc; v.z *= sc; v.w *= sc;
+    *reinterpret_cast<float4 *>(Y + (size_t)tile * (size_t)n * 32 + (size_t)in_tile * 4) = v;
+}
+
 // ------------------------------------------------------------- edge softmax
 
 // (m, z) pairs: z = sum of exp(e - m).  Merge keeps m the larger maximum.
@@ -808,9 +840,14 @@ size_t spmm_carry_bytes(int64_t nnz, int f) {
 
 hipError_t launch_spmm(const sensei_csr &A, int mode, const float *r, const float *c, const float *B, int64_t ldb,
                        int f, float *C, int64_t ldc, int f_store, int act, const ChunkPlan &p, float *carry,
-                       hipStream_t s, KernelTimer *timer, bool accumulate, bool finalize, const float2 *mz) {
-    const SpmmShape sh = spmm_shape(B, ldb, f);
+                       hipStream_t s, KernelTimer *timer, bool accumulate, bool finalize, const float2 *mz, bool b_sliced) {
+    SpmmShape sh = spmm_shape(B, ldb, f);
+    if (b_sliced) {  // slices of 32 floats per row: one 128-byte line per neighbour and tile
+        sh.vec = 4; sh.lpg = 8; sh.n_tiles = (f + 31) / 32; sh.f_carry = sh.n_tiles * 32;
+        ldb = 32;
+    }
     SpmmArgs a;
+    a.tile_stride_b = b_sliced ? (long long)(A.n_cols > 0 ? A.n_cols : 1) * 128 : (long long)sh.vec * sh.lpg * 4;
     a.mz = (mode == kSpmmSoftmax) ? mz : nullptr;
     a.row_ptr = A.row_ptr; a.col_idx = A.col_idx; a.chunk_row = p.chunk_row;
     a.val = A.val; a.r = r; a.c = c; a.B = B; a.C = C; a.carry = carry;
@@ -879,6 +916,14 @@ hipError_t launch_row_broadcast(const float *s_vec, const float *X, int64_t ldx,
         hipLaunchKernelGGL((k_row_broadcast<4>), dim3(blocks_for(n * (f / 4), kBlock)), dim3(kBlock), 0, s, s_vec, X, (long long)ldx, (long long)n, f, Y, (long long)ldy, act);
     else
         hipLaunchKernelGGL((k_row_broadcast<1>), dim3(blocks_for(n * f, kBlock)), dim3(kBlock), 0, s, s_vec, X, (long long)ldx, (long long)n, f, Y, (long long)ldy, act);
+    return hipGetLastError();
+}
+
+hipError_t launch_to_slices(const float *s_vec, const float *X, int64_t ldx, int64_t n, int f, float *Y, hipStream_t s) {
+    if (n <= 0 || f <= 0) return hipSuccess;
+    const int x_vec_ok = (ldx % 4 == 0 && reinterpret_cast<uintptr_t>(X) % 16 == 0) ? 1 : 0;
+    const long long threads = n * (long long)(pad32(f) / 4);
+    hipLaunchKernelGGL(k_to_slices, dim3(blocks_for(threads, kBlock)), dim3(kBlock), 0, s, s_vec, X, (long long)ldx, (long long)n, f, Y, x_vec_ok);
     return hipGetLastError();
 }
 

@@ -140,6 +140,19 @@ def ring_lattice(n: int, k_half: int, self_loops: bool = True) -> CSR:
     return build_csr(n, n, i.astype(np.int32), ((i + d) % n).astype(np.int32), True, self_loops)
 
 
+def thinned_grid(seed: int, side: int, keep: float, self_loops: bool = True) -> CSR:
+    """side x side square grid whose right/down links are each kept with probability ``keep``: a planar,
+    near-constant-degree pattern with the shape of a road network (row-major node numbering)."""
+    n = side * side
+    idx = np.arange(n, dtype=np.int64)
+    right = idx[(idx % side) != side - 1]
+    down = idx[idx < n - side]
+    u = np.concatenate([right, down])
+    v = np.concatenate([right + 1, down + side])
+    m = uniform(seed, 3, (u.size,), 0.0, 1.0) < keep
+    return build_csr(n, n, u[m].astype(np.int32), v[m].astype(np.int32), True, self_loops)
+
+
 def complete(n: int) -> CSR:
     i, j = np.triu_indices(n, 1)
     return build_csr(n, n, i.astype(np.int32), j.astype(np.int32), True, True)

@@ -50,7 +50,7 @@ def test_host_only_queries_and_argument_checks_need_no_gpu():
         assert L.sensei_gcn_workspace(C.byref(A), 64, 32, cid, C.byref(n)) == 0
         sizes[cid] = n.value
         assert n.value > 0 and n.value % 256 == 0
-    assert sizes[0] > sizes[2]                      # the unfused dynamic composition holds c (x) X as well
+    assert sizes[0] == sizes[2] == sizes[4]         # aggregate-first ids: U plus one (possibly slice-major) copy of X
     assert L.sensei_gcn_workspace(C.byref(A), 64, 32, 6, C.byref(n)) == 2
     assert L.sensei_gcn_workspace(C.byref(A), 0, 32, 0, C.byref(n)) == 1
     assert L.sensei_gcn_workspace(None, 64, 32, 0, C.byref(n)) == 1

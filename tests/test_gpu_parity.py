@@ -396,3 +396,46 @@ def test_layers_over_column_panels(ctx):
     assert auto.count == 1  # a small graph keeps the single-pass path
     P.close()
     auto.close()
+
+
+def test_panels_min_width_and_measured_choice(ctx):
+    """Narrow SpMMs follow the panels once min_width allows it; the measured choice returns a valid pair."""
+    from paper_2306_15155_amd import Panels, binding, csr_struct
+    g = synth.rmat(23, 5000, 90_000)
+    A = DeviceCSR(g)
+    P = Panels(ctx, A.s, 4)
+    assert binding.lib().sensei_panels_set_min_width(P._h, 1) == 0
+    Ap = csr_struct(g.n_rows, g.n_cols, A.row_ptr, A.col_idx, None, P)
+    for f in (41, 64, 7):
+        B = synth.uniform(f, 31, (g.n_cols, f))
+        assert_close(ctx.spmm(Ap, SPMM_PATTERN, dev(B)), oracle.spmm(g.row_ptr, g.col_idx, None, B), what=f"pattern f={f}")
+    # layers with narrow intermediates (GCN 100 -> 41 update-first, GAT 40 -> 72 recompute)
+    dr, dc = ctx.degrees(A.s)
+    r, c = ctx.norm_vectors(dr), ctx.norm_vectors(dc)
+    X, W = synth.uniform(23, 10, (g.n_cols, 100)), synth.glorot(23, 11, 100, 41)
+    ref = oracle.gcn_layer(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, ACT_RELU)
+    for cid in (1, 3):
+        assert_close(ctx.gcn_layer(Ap, r, c, dev(X), dev(W), cid, ACT_RELU), ref, what=f"gcn comp {cid}")
+    X, W = synth.uniform(23, 12, (g.n_cols, 40)), synth.glorot(23, 13, 40, 72)
+    a_l, a_r = synth.normal(23, 14, (72,), 0.0, 0.5), synth.normal(23, 15, (72,), 0.0, 0.5)
+    refg = oracle.gat_layer(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, a_l, a_r, 0.2, ACT_NONE)
+    for cid in range(4):
+        assert_close(ctx.gat_layer(Ap, dev(X), dev(W), dev(a_l), dev(a_r), cid, 0.2, ACT_NONE), refg, what=f"gat comp {cid}")
+    P.close()
+    # a graph whose 128-byte feature slice fits the L2s is not worth trials: (1, 128), nothing timed
+    count, width, ms = Panels.measure(ctx, A.s)
+    assert (count, width) == (1, 128) and all(t < 0 for t in ms)
+    # a graph large enough for trials: 60,000 columns (7.7 MB slice), about 50 entries per row
+    g2 = synth.erdos_renyi(24, 60_000, 1_500_000)
+    A2 = DeviceCSR(g2)
+    count, width, ms = Panels.measure(ctx, A2.s)
+    assert 1 <= count <= 8 and width in (64, 128)
+    assert ms[1] > 0 and ms[0] < 0  # the single pass is always timed; index 0 is unused
+    tried = [q for q in range(1, 9) if ms[q] > 0]
+    assert len(ms) == 18
+    assert count in tried and (count == 1 or ms[count] <= 0.97 * ms[1])
+    T = Panels(ctx, A2.s, tune=True)
+    A2p = csr_struct(g2.n_rows, g2.n_cols, A2.row_ptr, A2.col_idx, None, T)
+    B = synth.uniform(24, 32, (g2.n_cols, 128))
+    assert_close(ctx.spmm(A2p, SPMM_PATTERN, dev(B)), oracle.spmm(g2.row_ptr, g2.col_idx, None, B), what="measured panels")
+    T.close()
