@@ -857,11 +857,11 @@ hipError_t launch_spmm(const sensei_csr &A, int mode, const float *r, const floa
     a.store_vec_ok = (ldc % sh.vec == 0) && (reinterpret_cast<uintptr_t>(C) % (4 * sh.vec) == 0);
     a.accumulate = accumulate ? 1 : 0; a.finalize = finalize ? 1 : 0;
     const unsigned groups = blocks_for(p.n_chunks, kWavesPerBlock);
-    // Feature tiles worked on at the same time: as many as keep the gathered slices (one per live tile)
-    // within about 96 MB, so that they stay in the 256 MB memory-side cache next to the index stream.
+    // Feature tiles worked on at the same time (consecutive XCDs take consecutive tiles of the live set): all eight
+    // while a 128-byte slice of the gathered matrix is small, four beyond that (measured on the 233 k-node R-MAT graph
+    // at F = 256: 6.5 / 6.1 / 5.9 / 6.0 ms with 1 / 2 / 4 / 8 live tiles; 2.45 M nodes at F = 1024: 52.2 / 51.5 / 50.7 / 51.6).
     const double slice_bytes = (double)(A.n_cols > 0 ? A.n_cols : 1) * sh.lpg * sh.vec * 4.0;
-    a.tiles_live = 8;
-    while (a.tiles_live > 1 && a.tiles_live * slice_bytes > 96e6) a.tiles_live >>= 1;
+    a.tiles_live = slice_bytes > 8e6 ? 4 : 8;
     if (a.tiles_live > sh.n_tiles) a.tiles_live = sh.n_tiles;
     a.n_groups = (int)groups;
     const unsigned n_sets = (unsigned)((sh.n_tiles + a.tiles_live - 1) / a.tiles_live);
