@@ -193,6 +193,48 @@ def gat_layer(n_rows, n_cols, row_ptr, col_idx, X, W, a_l, a_r, slope=0.2, act=0
     return Y
 
 
+def gcn_backward(n_rows, n_cols, row_ptr, col_idx, X, W, dY, Y=None, act=0, rows=None, want_dw=True, omp=False):
+    """Gradient of sum(dY * Y) for the GCN layer (chain rule on Eq. 3) -> (dX, dW).
+
+    ``Y`` (the fp32 forward output) supplies the ReLU mask when ``act`` == 1; ``rows`` selects rows of dX."""
+    row_ptr, col_idx, X, W, dY = _i32(row_ptr), _i32(col_idx), _f32(X), _f32(W), _f32(dY)
+    F_in, F_out = W.shape
+    assert X.shape == (n_cols, F_in) and dY.shape == (n_rows, F_out)
+    if act == 1:
+        Y = _f32(Y)
+        assert Y.shape == dY.shape
+    sel = None if rows is None else _i32(rows)
+    n_out = n_cols if sel is None else sel.size
+    dX = np.empty((n_out, F_in), dtype=np.float64)
+    dW = np.empty((F_in, F_out), dtype=np.float64) if (want_dw or sel is None) else None
+    rc = _lib(omp).orc_gcn_backward(I32(n_rows), I32(n_cols), _p(row_ptr), _p(col_idx), _p(X), I64(F_in), I32(F_in), _p(W), I64(F_out),
+                                   I32(F_out), _p(Y) if act == 1 else None, I64(F_out), _p(dY), I64(F_out), ctypes.c_int(act),
+                                   None if sel is None else _p(sel), I32(0 if sel is None else sel.size),
+                                   ctypes.c_int(1 if dW is not None else 0), _p(dX), None if dW is None else _p(dW))
+    if rc != 0:
+        raise RuntimeError(f"oracle gcn_backward failed ({rc})")
+    return dX, dW
+
+
+def gat_backward(n_rows, n_cols, row_ptr, col_idx, X, W, a_l, a_r, dY, Y=None, slope=0.2, act=0, omp=False):
+    """Gradient of sum(dY * Y) for the GAT layer (chain rule on Eq. 5 / 6) -> (dX, dW, da_l, da_r)."""
+    row_ptr, col_idx, X, W, a_l, a_r, dY = _i32(row_ptr), _i32(col_idx), _f32(X), _f32(W), _f32(a_l), _f32(a_r), _f32(dY)
+    F_in, F_out = W.shape
+    assert X.shape == (n_cols, F_in) and dY.shape == (n_rows, F_out)
+    if act == 1:
+        Y = _f32(Y)
+        assert Y.shape == dY.shape
+    dX = np.empty((n_cols, F_in), dtype=np.float64)
+    dW = np.empty((F_in, F_out), dtype=np.float64)
+    dal, dar = np.empty(F_out, dtype=np.float64), np.empty(F_out, dtype=np.float64)
+    rc = _lib(omp).orc_gat_backward(I32(n_rows), I32(n_cols), _p(row_ptr), _p(col_idx), _p(X), I64(F_in), I32(F_in), _p(W), I64(F_out),
+                                   I32(F_out), _p(a_l), _p(a_r), DBL(slope), _p(Y) if act == 1 else None, I64(F_out), _p(dY),
+                                   I64(F_out), ctypes.c_int(act), _p(dX), _p(dW), _p(dal), _p(dar))
+    if rc != 0:
+        raise RuntimeError(f"oracle gat_backward failed ({rc})")
+    return dX, dW, dal, dar
+
+
 # ------------------------------------------------------------- re-associations
 
 GCN_COMPOSITIONS = ("DYN_AGG", "DYN_UPD", "DYNF_AGG", "DYNF_UPD", "PRE_AGG", "PRE_UPD")

@@ -10,6 +10,7 @@
  *   - g-SDDMM with k = 1                    : Background, Eq. 2
  *   - GCN layer                             : Case study GCN, Eq. 3 (== Eq. 4)
  *   - GAT layer                             : Case study GAT, Eq. 5-6
+ *   - backward of both layers (training)    : chain rule on Eq. 3 and Eq. 5-6
  * Readings where the paper is silent (degree clamp, score function, softmax
  * over the stored entries of a row) are stated at each function.
  *
@@ -17,7 +18,9 @@
  * forms (self-loop graph, regular ring, complete graph, star), softmax
  * invariants, agreement of every re-association, library routines on special
  * cases.  The row-sampled entry points (*_rows) are pinned against the full
- * ones.
+ * ones.  The backward functions are pinned against central finite
+ * differences of the forward functions, dense linear algebra and closed forms
+ * (tests/test_oracle_backward.py).
  *
  * Build: gcc -O2 -shared -fPIC sensei_oracle.c -o liboracle.so -lm
  *        (-fopenmp -DORC_OMP builds the row-parallel timing variant of the
@@ -330,5 +333,250 @@ int orc_gat_layer_rows(int32_t n_rows, int32_t n_cols, const int32_t *row_ptr, c
         free(e); free(u);
     }
     free(vl); free(vr); free(sl); free(sr);
+    return 0;
+}
+
+/* ------------------------------------------- training: gradients of a layer
+ *
+ * The evaluation section trains the models (forward + backward per
+ * iteration); the paper leaves the backward pass to the framework's automatic
+ * differentiation.  Reading: the backward of a layer is the gradient of the
+ * scalar  L = sum_{i,k} dY[i,k] * Y[i,k]  with respect to the layer's inputs,
+ * written out by the chain rule on the plain forward definition above, in
+ * fp64.  The ReLU mask is taken from the forward output the caller passes
+ * (Y[i,k] > 0), so that both sides of a comparison take that decision on the
+ * same fp32 values.
+ * Pins (tests/test_oracle_backward.py): central finite differences of the
+ * forward oracle, closed forms (self-loop graph = dense linear layer; zero
+ * attention vectors = mean aggregation), linearity in dY. */
+
+/* col_ptr / row_of: the stored entries grouped by column (the transposed
+ * pattern), entries of one column in ascending row order; pos[k] = place of
+ * entry k in that order. */
+static int orc_transpose(int32_t n_rows, int32_t n_cols, const int32_t *row_ptr, const int32_t *col_idx,
+                         int32_t **col_ptr_out, int32_t **row_of_out, int32_t **pos_out) {
+    const int64_t nnz = row_ptr[n_rows];
+    int32_t *col_ptr = (int32_t *)calloc((size_t)n_cols + 2, sizeof(int32_t));
+    int32_t *row_of = (int32_t *)malloc(((size_t)nnz + 1) * sizeof(int32_t));
+    int32_t *pos = (int32_t *)malloc(((size_t)nnz + 1) * sizeof(int32_t));
+    if (!col_ptr || !row_of || !pos) { free(col_ptr); free(row_of); free(pos); return 1; }
+    for (int64_t k = 0; k < nnz; ++k) col_ptr[col_idx[k] + 1]++;
+    for (int32_t j = 0; j < n_cols; ++j) col_ptr[j + 1] += col_ptr[j];
+    int32_t *fill = (int32_t *)malloc(((size_t)n_cols + 1) * sizeof(int32_t));
+    if (!fill) { free(col_ptr); free(row_of); free(pos); return 1; }
+    memcpy(fill, col_ptr, (size_t)n_cols * sizeof(int32_t));
+    for (int32_t i = 0; i < n_rows; ++i)
+        for (int32_t k = row_ptr[i]; k < row_ptr[i + 1]; ++k) {
+            int32_t p = fill[col_idx[k]]++;
+            row_of[p] = i;
+            pos[k] = p;
+        }
+    free(fill);
+    *col_ptr_out = col_ptr; *row_of_out = row_of; *pos_out = pos;
+    return 0;
+}
+
+/* GCN layer, Y = act(P), P = R A~ C (X W):
+ *   dP = dY (.) [Y > 0]            (identity activation: dP = dY)
+ *   dZ[j,:] = c_j sum_{i : (i,j) stored} r_i dP[i,:]        (Z = X W)
+ *   dW = X^T dZ ,  dX = dZ W^T.
+ * Y may be NULL when act == 0.  dX: n_cols x F_in, dW: F_in x F_out (fp64).
+ * sel / n_sel: when sel != NULL only the rows sel[0..n_sel) of dX are computed
+ * (dX is n_sel x F_in) and dW is not touched unless want_dw != 0. */
+int orc_gcn_backward(int32_t n_rows, int32_t n_cols, const int32_t *row_ptr, const int32_t *col_idx,
+                     const float *X, int64_t ldx, int32_t F_in, const float *W, int64_t ldw, int32_t F_out,
+                     const float *Y, int64_t ldy, const float *dY, int64_t lddy, int act,
+                     const int32_t *sel, int32_t n_sel, int want_dw, double *dX, double *dW) {
+    int32_t *dr = (int32_t *)malloc((size_t)(n_rows + 1) * sizeof(int32_t));
+    int32_t *dc = (int32_t *)malloc((size_t)(n_cols + 1) * sizeof(int32_t));
+    double *r = (double *)malloc((size_t)(n_rows + 1) * sizeof(double));
+    double *c = (double *)malloc((size_t)(n_cols + 1) * sizeof(double));
+    int32_t *col_ptr = NULL, *row_of = NULL, *pos = NULL;
+    if (!dr || !dc || !r || !c || orc_transpose(n_rows, n_cols, row_ptr, col_idx, &col_ptr, &row_of, &pos)) {
+        free(dr); free(dc); free(r); free(c); return 1;
+    }
+    orc_degrees(n_rows, n_cols, row_ptr, col_idx, dr, dc);
+    orc_inv_sqrt_deg(dr, n_rows, r);
+    orc_inv_sqrt_deg(dc, n_cols, c);
+    const int full = (sel == NULL);
+    const int32_t n_out = full ? n_cols : n_sel;
+    int rc = 0;
+    double *dZ = NULL;
+    if (full || want_dw) {
+        dZ = (double *)malloc((size_t)n_cols * (size_t)F_out * sizeof(double) + 8);
+        if (!dZ) rc = 1;
+    }
+    if (rc == 0 && dZ) {
+        ORC_PAR
+        for (int32_t j = 0; j < n_cols; ++j) {
+            double *z = dZ + (int64_t)j * F_out;
+            for (int32_t m = 0; m < F_out; ++m) z[m] = 0.0;
+            for (int32_t p = col_ptr[j]; p < col_ptr[j + 1]; ++p) {
+                const int32_t i = row_of[p];
+                for (int32_t m = 0; m < F_out; ++m) {
+                    double g = (double)dY[(int64_t)i * lddy + m];
+                    if (act == 1 && !(Y[(int64_t)i * ldy + m] > 0.0f)) g = 0.0;
+                    z[m] += r[i] * g;
+                }
+            }
+            for (int32_t m = 0; m < F_out; ++m) z[m] *= c[j];
+        }
+        if (full || want_dw) {
+            ORC_PAR
+            for (int32_t f = 0; f < F_in; ++f)
+                for (int32_t m = 0; m < F_out; ++m) {
+                    double s = 0.0;
+                    for (int32_t j = 0; j < n_cols; ++j) s += (double)X[(int64_t)j * ldx + f] * dZ[(int64_t)j * F_out + m];
+                    dW[(int64_t)f * F_out + m] = s;
+                }
+        }
+    }
+    if (rc == 0) {
+        ORC_PAR
+        for (int32_t t = 0; t < n_out; ++t) {
+            const int32_t j = full ? t : sel[t];
+            double *z = (double *)calloc((size_t)F_out + 1, sizeof(double));
+            if (dZ) {
+                memcpy(z, dZ + (int64_t)j * F_out, (size_t)F_out * sizeof(double));
+            } else {
+                for (int32_t p = col_ptr[j]; p < col_ptr[j + 1]; ++p) {
+                    const int32_t i = row_of[p];
+                    for (int32_t m = 0; m < F_out; ++m) {
+                        double g = (double)dY[(int64_t)i * lddy + m];
+                        if (act == 1 && !(Y[(int64_t)i * ldy + m] > 0.0f)) g = 0.0;
+                        z[m] += r[i] * g;
+                    }
+                }
+                for (int32_t m = 0; m < F_out; ++m) z[m] *= c[j];
+            }
+            for (int32_t f = 0; f < F_in; ++f) {
+                double s = 0.0;
+                for (int32_t m = 0; m < F_out; ++m) s += z[m] * (double)W[(int64_t)f * ldw + m];
+                dX[(int64_t)t * F_in + f] = s;
+            }
+            free(z);
+        }
+    }
+    free(dr); free(dc); free(r); free(c); free(col_ptr); free(row_of); free(pos); free(dZ);
+    return rc;
+}
+
+/* GAT layer, Y = act(P), P = alpha Theta, Theta = X W, s_l = Theta a_l, s_r = Theta a_r,
+ * t_ij = s_l[i] + s_r[j], e_ij = LeakyReLU(t_ij), alpha = row softmax of e:
+ *   dP = dY (.) [Y > 0]
+ *   dalpha_ij = <dP[i,:], Theta[j,:]>
+ *   de_ij = alpha_ij (dalpha_ij - sum_j' alpha_ij' dalpha_ij')        (softmax)
+ *   dt_ij = de_ij * (t_ij > 0 ? 1 : slope)
+ *   ds_l[i] = sum_j dt_ij ,  ds_r[j] = sum_i dt_ij
+ *   dTheta[j,:] = sum_i alpha_ij dP[i,:] + ds_l[j] a_l + ds_r[j] a_r
+ *   da_l = Theta^T ds_l , da_r = Theta^T ds_r , dW = X^T dTheta , dX = dTheta W^T.
+ * Square pattern only (destinations = the first n_rows sources, as in the
+ * forward).  Outputs fp64: dX n_cols x F_in, dW F_in x F_out, da_l, da_r F_out. */
+int orc_gat_backward(int32_t n_rows, int32_t n_cols, const int32_t *row_ptr, const int32_t *col_idx,
+                     const float *X, int64_t ldx, int32_t F_in, const float *W, int64_t ldw, int32_t F_out,
+                     const float *a_l, const float *a_r, double slope,
+                     const float *Y, int64_t ldy, const float *dY, int64_t lddy, int act,
+                     double *dX, double *dW, double *da_l, double *da_r) {
+    if (n_rows > n_cols) return 2;
+    const int64_t nnz = row_ptr[n_rows];
+    double *Th = (double *)malloc((size_t)n_cols * (size_t)F_out * sizeof(double) + 8);
+    double *dTh = (double *)calloc((size_t)n_cols * (size_t)F_out + 1, sizeof(double));
+    double *sl = (double *)calloc((size_t)n_cols + 1, sizeof(double));
+    double *sr = (double *)calloc((size_t)n_cols + 1, sizeof(double));
+    double *dsl = (double *)calloc((size_t)n_cols + 1, sizeof(double));
+    double *dsr = (double *)calloc((size_t)n_cols + 1, sizeof(double));
+    double *alpha = (double *)malloc(((size_t)nnz + 1) * sizeof(double));
+    double *dt = (double *)malloc(((size_t)nnz + 1) * sizeof(double));
+    double *dP = (double *)malloc((size_t)n_rows * (size_t)F_out * sizeof(double) + 8);
+    if (!Th || !dTh || !sl || !sr || !dsl || !dsr || !alpha || !dt || !dP) {
+        free(Th); free(dTh); free(sl); free(sr); free(dsl); free(dsr); free(alpha); free(dt); free(dP);
+        return 1;
+    }
+    ORC_PAR
+    for (int32_t j = 0; j < n_cols; ++j) {
+        for (int32_t m = 0; m < F_out; ++m) {
+            double s = 0.0;
+            for (int32_t f = 0; f < F_in; ++f) s += (double)X[(int64_t)j * ldx + f] * (double)W[(int64_t)f * ldw + m];
+            Th[(int64_t)j * F_out + m] = s;
+        }
+        double a = 0.0, b = 0.0;
+        for (int32_t m = 0; m < F_out; ++m) {
+            a += Th[(int64_t)j * F_out + m] * (double)a_l[m];
+            b += Th[(int64_t)j * F_out + m] * (double)a_r[m];
+        }
+        sl[j] = a; sr[j] = b;
+    }
+    ORC_PAR
+    for (int32_t i = 0; i < n_rows; ++i)
+        for (int32_t m = 0; m < F_out; ++m) {
+            double g = (double)dY[(int64_t)i * lddy + m];
+            if (act == 1 && !(Y[(int64_t)i * ldy + m] > 0.0f)) g = 0.0;
+            dP[(int64_t)i * F_out + m] = g;
+        }
+    /* per destination row: alpha, dalpha, softmax and LeakyReLU backward */
+    ORC_PAR
+    for (int32_t i = 0; i < n_rows; ++i) {
+        const int32_t b = row_ptr[i], e = row_ptr[i + 1];
+        if (b == e) continue;
+        double mx = -INFINITY;
+        for (int32_t k = b; k < e; ++k) {
+            double t = sl[i] + sr[col_idx[k]];
+            double v = t > 0.0 ? t : slope * t;
+            if (v > mx) mx = v;
+        }
+        double z = 0.0;
+        for (int32_t k = b; k < e; ++k) {
+            double t = sl[i] + sr[col_idx[k]];
+            double v = t > 0.0 ? t : slope * t;
+            alpha[k] = exp(v - mx);
+            z += alpha[k];
+        }
+        double dot = 0.0;
+        for (int32_t k = b; k < e; ++k) {
+            alpha[k] /= z;
+            const int32_t j = col_idx[k];
+            double da = 0.0;
+            for (int32_t m = 0; m < F_out; ++m) da += dP[(int64_t)i * F_out + m] * Th[(int64_t)j * F_out + m];
+            dt[k] = da;  /* dalpha for now */
+            dot += alpha[k] * da;
+        }
+        double acc = 0.0;
+        for (int32_t k = b; k < e; ++k) {
+            double t = sl[i] + sr[col_idx[k]];
+            double de = alpha[k] * (dt[k] - dot);
+            dt[k] = de * (t > 0.0 ? 1.0 : slope);
+            acc += dt[k];
+        }
+        dsl[i] = acc;
+    }
+    /* scatter over columns: serial, the plain transposed sums */
+    for (int32_t i = 0; i < n_rows; ++i)
+        for (int32_t k = row_ptr[i]; k < row_ptr[i + 1]; ++k) {
+            const int32_t j = col_idx[k];
+            dsr[j] += dt[k];
+            for (int32_t m = 0; m < F_out; ++m) dTh[(int64_t)j * F_out + m] += alpha[k] * dP[(int64_t)i * F_out + m];
+        }
+    for (int32_t m = 0; m < F_out; ++m) { da_l[m] = 0.0; da_r[m] = 0.0; }
+    for (int32_t j = 0; j < n_cols; ++j)
+        for (int32_t m = 0; m < F_out; ++m) {
+            da_l[m] += Th[(int64_t)j * F_out + m] * dsl[j];
+            da_r[m] += Th[(int64_t)j * F_out + m] * dsr[j];
+            dTh[(int64_t)j * F_out + m] += dsl[j] * (double)a_l[m] + dsr[j] * (double)a_r[m];
+        }
+    ORC_PAR
+    for (int32_t f = 0; f < F_in; ++f)
+        for (int32_t m = 0; m < F_out; ++m) {
+            double s = 0.0;
+            for (int32_t j = 0; j < n_cols; ++j) s += (double)X[(int64_t)j * ldx + f] * dTh[(int64_t)j * F_out + m];
+            dW[(int64_t)f * F_out + m] = s;
+        }
+    ORC_PAR
+    for (int32_t j = 0; j < n_cols; ++j)
+        for (int32_t f = 0; f < F_in; ++f) {
+            double s = 0.0;
+            for (int32_t m = 0; m < F_out; ++m) s += dTh[(int64_t)j * F_out + m] * (double)W[(int64_t)f * ldw + m];
+            dX[(int64_t)j * F_in + f] = s;
+        }
+    free(Th); free(dTh); free(sl); free(sr); free(dsl); free(dsr); free(alpha); free(dt); free(dP);
     return 0;
 }

@@ -1,0 +1,219 @@
+"""Pins for the backward-pass oracle: the gradients are checked against central finite differences of the
+forward oracle, against dense linear algebra written here from the chain rule, and against closed forms."""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from oracle import dense
+
+
+def _grid(rng, shape, step=2.0 ** -6, span=32):
+    """fp32 values on a coarse binary grid, so that value +- h is exact in fp32 for h a power of two >= 2^-12."""
+    return (rng.integers(-span, span + 1, size=shape) * step).astype(np.float32)
+
+
+def _rect_block(seed, n_rows, n_cols, per_row):
+    rng = np.random.default_rng(seed)
+    u = np.repeat(np.arange(n_rows), per_row)
+    v = rng.integers(0, n_cols, size=u.size)
+    return synth.build_csr(n_rows, n_cols, u, v, False, True)
+
+
+def _close(a, b, tol):
+    a, b = np.asarray(a, dtype=np.float64), np.asarray(b, dtype=np.float64)
+    assert a.shape == b.shape
+    err = np.max(np.abs(a - b) / (1.0 + np.abs(b)))
+    assert err < tol, err
+
+
+def _central(f, x, h):
+    """d f / d x by central differences, x an fp32 array perturbed in place, f() -> float (fp64)."""
+    g = np.zeros(x.shape, dtype=np.float64)
+    it = np.nditer(x, flags=["multi_index"])
+    for _ in it:
+        idx = it.multi_index
+        keep = x[idx]
+        x[idx] = keep + np.float32(h)
+        up = f()
+        x[idx] = keep - np.float32(h)
+        dn = f()
+        x[idx] = keep
+        g[idx] = (up - dn) / (2.0 * h)
+    return g
+
+
+def _richardson(f, x, h):
+    return (4.0 * _central(f, x, h / 2) - _central(f, x, h)) / 3.0
+
+
+# ------------------------------------------------------------------ GCN
+
+@pytest.mark.parametrize("shape", ["square", "rect"])
+def test_gcn_backward_is_the_gradient_of_the_forward(shape):
+    rng = np.random.default_rng(5)
+    g = synth.erdos_renyi(5, 14, 30) if shape == "square" else _rect_block(6, 6, 15, 3)
+    f_in, f_out = 5, 4
+    X, W, dY = _grid(rng, (g.n_cols, f_in)), _grid(rng, (f_in, f_out)), _grid(rng, (g.n_rows, f_out))
+
+    def loss():
+        return float(np.sum(dY.astype(np.float64) * oracle.gcn_layer(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, 0)))
+
+    dX, dW = oracle.gcn_backward(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, dY)
+    # the identity-activation layer is linear in X and in W: central differences are exact up to rounding
+    _close(dX, _central(loss, X, 2.0 ** -4), 1e-10)
+    _close(dW, _central(loss, W, 2.0 ** -4), 1e-10)
+
+
+def test_gcn_backward_with_relu_mask_matches_finite_differences():
+    rng = np.random.default_rng(8)
+    g = synth.erdos_renyi(8, 12, 25)
+    f_in, f_out = 4, 3
+    X, W, dY = _grid(rng, (12, f_in)), _grid(rng, (f_in, f_out)), _grid(rng, (12, f_out))
+    P = oracle.gcn_layer(12, 12, g.row_ptr, g.col_idx, X, W, 0)
+    h = 2.0 ** -12
+    ok = np.abs(P) > 64 * h  # pre-activations close enough to zero for a +-h step to cross the kink are left out of the loss
+    assert ok.mean() > 0.5 and (P[ok] > 0).any() and (P[ok] < 0).any()
+    dY = (dY * ok).astype(np.float32)
+    Y = np.maximum(P, 0.0).astype(np.float32)
+
+    def loss():
+        return float(np.sum(dY.astype(np.float64) * oracle.gcn_layer(12, 12, g.row_ptr, g.col_idx, X, W, 1)))
+
+    dX, dW = oracle.gcn_backward(12, 12, g.row_ptr, g.col_idx, X, W, dY, Y=Y, act=1)
+    _close(dX, _central(loss, X, h), 1e-9)
+    _close(dW, _central(loss, W, h), 1e-9)
+    # and the mask really matters
+    dX0, _ = oracle.gcn_backward(12, 12, g.row_ptr, g.col_idx, X, W, dY)
+    assert np.max(np.abs(dX0 - dX)) > 1e-3
+
+
+@pytest.mark.parametrize("shape", ["square", "rect"])
+def test_gcn_backward_matches_dense_chain_rule(shape):
+    rng = np.random.default_rng(11)
+    g = synth.rmat(11, 40, 120) if shape == "square" else _rect_block(12, 9, 30, 4)
+    f_in, f_out = 6, 5
+    X = rng.standard_normal((g.n_cols, f_in)).astype(np.float32)
+    W = rng.standard_normal((f_in, f_out)).astype(np.float32)
+    dY = rng.standard_normal((g.n_rows, f_out)).astype(np.float32)
+    A = dense.dense_pattern(g.n_rows, g.n_cols, g.row_ptr, g.col_idx)
+    r = 1.0 / np.sqrt(np.maximum(A.sum(axis=1), 1.0))
+    c = 1.0 / np.sqrt(np.maximum(A.sum(axis=0), 1.0))
+    Ahat = r[:, None] * A * c[None, :]
+    Y = np.maximum(Ahat @ X.astype(np.float64) @ W.astype(np.float64), 0.0).astype(np.float32)
+    dP = dY.astype(np.float64) * (Y > 0)
+    dX, dW = oracle.gcn_backward(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, dY, Y=Y, act=1)
+    _close(dX, Ahat.T @ dP @ W.astype(np.float64).T, 1e-11)
+    _close(dW, (Ahat @ X.astype(np.float64)).T @ dP, 1e-11)
+    # selected rows of dX, with and without the dW reduction
+    rows = np.array([0, g.n_cols - 1, 3, 3], dtype=np.int32)
+    dXs, dWs = oracle.gcn_backward(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, dY, Y=Y, act=1, rows=rows)
+    _close(dXs, dX[rows], 1e-12)
+    _close(dWs, dW, 1e-12)
+    dXs2, none = oracle.gcn_backward(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, dY, Y=Y, act=1, rows=rows, want_dw=False)
+    assert none is None
+    _close(dXs2, dX[rows], 1e-12)
+
+
+def test_gcn_backward_on_self_loops_is_a_dense_linear_layer():
+    rng = np.random.default_rng(2)
+    g = synth.self_loops_only(17)
+    X, W, dY = (rng.standard_normal(s).astype(np.float32) for s in ((17, 6), (6, 3), (17, 3)))
+    dX, dW = oracle.gcn_backward(17, 17, g.row_ptr, g.col_idx, X, W, dY)
+    _close(dX, dY.astype(np.float64) @ W.astype(np.float64).T, 1e-12)
+    _close(dW, X.astype(np.float64).T @ dY.astype(np.float64), 1e-12)
+
+
+# ------------------------------------------------------------------ GAT
+
+def test_gat_backward_is_the_gradient_of_the_forward():
+    rng = np.random.default_rng(21)
+    g = synth.erdos_renyi(21, 10, 18)
+    f_in, f_out = 4, 3
+    X, W, dY = _grid(rng, (10, f_in)), _grid(rng, (f_in, f_out)), _grid(rng, (10, f_out))
+    a_l, a_r = _grid(rng, (f_out,)), _grid(rng, (f_out,))
+
+    def loss():
+        return float(np.sum(dY.astype(np.float64) * oracle.gat_layer(10, 10, g.row_ptr, g.col_idx, X, W, a_l, a_r, 0.2, 0)))
+
+    # stay clear of the LeakyReLU kink: every t_ij = s_l[i] + s_r[j] well away from zero
+    Th = X.astype(np.float64) @ W.astype(np.float64)
+    sl, sr = Th @ a_l.astype(np.float64), Th @ a_r.astype(np.float64)
+    t = np.concatenate([sl[i] + sr[g.col_idx[g.row_ptr[i]:g.row_ptr[i + 1]]] for i in range(10)])
+    h = 2.0 ** -11  # a step of h moves a logit by less than 3 h for these value ranges
+    assert np.min(np.abs(t)) > 8 * h
+    dX, dW, dal, dar = oracle.gat_backward(10, 10, g.row_ptr, g.col_idx, X, W, a_l, a_r, dY)
+    _close(dX, _richardson(loss, X, h), 1e-7)
+    _close(dW, _richardson(loss, W, h), 1e-7)
+    _close(dal, _richardson(loss, a_l, h), 1e-7)
+    _close(dar, _richardson(loss, a_r, h), 1e-7)
+    assert np.max(np.abs(dal)) > 1e-3 and np.max(np.abs(dar)) > 1e-3  # the attention path carries gradient
+
+
+def test_gat_backward_with_relu_and_other_slope():
+    f_in, f_out = 3, 4
+    h = 2.0 ** -11
+    g = synth.rmat(22, 12, 30)
+    for seed in range(22, 40):  # first seed whose logits all stay clear of the LeakyReLU kink
+        rng = np.random.default_rng(seed)
+        X, W, dY = _grid(rng, (12, f_in)), _grid(rng, (f_in, f_out)), _grid(rng, (12, f_out))
+        a_l, a_r = _grid(rng, (f_out,)), _grid(rng, (f_out,))
+        Th = X.astype(np.float64) @ W.astype(np.float64)
+        sl, sr = Th @ a_l.astype(np.float64), Th @ a_r.astype(np.float64)
+        t = np.concatenate([sl[i] + sr[g.col_idx[g.row_ptr[i]:g.row_ptr[i + 1]]] for i in range(12)])
+        if np.min(np.abs(t)) > 8 * h:
+            break
+    else:
+        raise AssertionError("no seed keeps the logits away from zero")
+    P = oracle.gat_layer(12, 12, g.row_ptr, g.col_idx, X, W, a_l, a_r, 0.05, 0)
+    ok = np.abs(P) > 64 * h  # outputs near the ReLU kink are left out of the loss
+    assert ok.mean() > 0.5 and (P[ok] > 0).any() and (P[ok] < 0).any()
+    dYm = (dY * ok).astype(np.float32)
+    Y = np.maximum(P, 0.0).astype(np.float32)
+
+    def loss():
+        return float(np.sum(dYm.astype(np.float64) * oracle.gat_layer(12, 12, g.row_ptr, g.col_idx, X, W, a_l, a_r, 0.05, 1)))
+
+    dX, dW, dal, dar = oracle.gat_backward(12, 12, g.row_ptr, g.col_idx, X, W, a_l, a_r, dYm, Y=Y, slope=0.05, act=1)
+    _close(dX, _richardson(loss, X, h), 1e-7)
+    _close(dW, _richardson(loss, W, h), 1e-7)
+    _close(dal, _richardson(loss, a_l, h), 1e-7)
+    _close(dar, _richardson(loss, a_r, h), 1e-7)
+    # the slope enters: the default slope gives another gradient
+    dX2 = oracle.gat_backward(12, 12, g.row_ptr, g.col_idx, X, W, a_l, a_r, dYm, Y=Y, slope=0.2, act=1)[0]
+    assert np.max(np.abs(dX2 - dX)) > 1e-6
+
+
+def test_gat_backward_with_zero_attention_vectors_is_mean_aggregation():
+    rng = np.random.default_rng(23)
+    g = synth.erdos_renyi(23, 15, 30)
+    f_in, f_out = 5, 4
+    X = rng.standard_normal((15, f_in)).astype(np.float32)
+    W = rng.standard_normal((f_in, f_out)).astype(np.float32)
+    dY = rng.standard_normal((15, f_out)).astype(np.float32)
+    z = np.zeros(f_out, dtype=np.float32)
+    A = dense.dense_pattern(15, 15, g.row_ptr, g.col_idx)
+    M = A / A.sum(axis=1, keepdims=True)
+    dX, dW, dal, dar = oracle.gat_backward(15, 15, g.row_ptr, g.col_idx, X, W, z, z, dY)
+    _close(dX, M.T @ dY.astype(np.float64) @ W.astype(np.float64).T, 1e-11)
+    _close(dW, X.astype(np.float64).T @ M.T @ dY.astype(np.float64), 1e-11)
+    # d/da of the logits at a = 0: uniform alpha, softmax backward still active, LeakyReLU slope at t = 0 is `slope`
+    Th = X.astype(np.float64) @ W.astype(np.float64)
+    dalpha = dY.astype(np.float64) @ Th.T                       # <dP_i, Theta_j>
+    de = M * (dalpha - np.sum(M * dalpha, axis=1, keepdims=True)) * (A != 0)
+    dt = 0.2 * de
+    _close(dal, Th.T @ dt.sum(axis=1), 1e-11)
+    _close(dar, Th.T @ dt.sum(axis=0), 1e-11)
+
+
+def test_backward_is_linear_in_the_upstream_gradient():
+    rng = np.random.default_rng(31)
+    g = synth.rmat(31, 30, 90)
+    X = rng.standard_normal((30, 5)).astype(np.float32)
+    W = rng.standard_normal((5, 4)).astype(np.float32)
+    a_l, a_r = rng.standard_normal(4).astype(np.float32), rng.standard_normal(4).astype(np.float32)
+    d1, d2 = _grid(rng, (30, 4)), _grid(rng, (30, 4))
+    for fn in (lambda d: oracle.gcn_backward(30, 30, g.row_ptr, g.col_idx, X, W, d),
+               lambda d: oracle.gat_backward(30, 30, g.row_ptr, g.col_idx, X, W, a_l, a_r, d)):
+        for a, b, s in zip(fn(d1), fn(d2), fn((d1 + d2).astype(np.float32))):
+            _close(np.asarray(a) + np.asarray(b), s, 1e-11)
