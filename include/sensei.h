@@ -205,6 +205,28 @@ int sensei_gcn_workspace(const sensei_csr *A, int f_in, int f_out, int comp_id, 
 int sensei_gcn_layer(sensei_ctx *ctx, const sensei_csr *A, const float *r, const float *c, sensei_mat X, sensei_mat W,
                      float *Y, int64_t ldy, int activation, int comp_id, void *workspace, size_t ws_bytes, void *stream);
 
+/* Backward of the GCN layer (the paper's evaluation trains the models: one forward and one backward per
+ * iteration; the backward is the gradient of the forward by the chain rule, with the same freedom of
+ * association): given dY = dL/dY it computes
+ *     dP = dY (.) [Y > 0]  (ReLU; dP = dY without activation),
+ *     dW = X^T D_c^(-1/2) A~^T D_r^(-1/2) dP     (f_in x f_out),
+ *     dX = D_c^(-1/2) A~^T D_r^(-1/2) dP W^T     (n_cols x f_in; skipped when dX is NULL).
+ * bwd_id chooses where the transposed aggregation runs:
+ *     SENSEI_GCN_BWD_AGG: G = D_c^(-1/2) A~^T D_r^(-1/2) dP at width f_out, dW = X^T G, dX = G W^T
+ *                         (the choice for f_out <= f_in, the mirror of the update-first forward);
+ *     SENSEI_GCN_BWD_UPD: dW = U^T dP with U = D_r^(-1/2) A~ D_c^(-1/2) X (taken from `U_saved` if given, else
+ *                         recomputed by one SpMM at width f_in), dX = D_c^(-1/2) A~^T D_r^(-1/2) (dP W^T) at
+ *                         width f_in (the choice for f_in < f_out).
+ * At: the transposed pattern (n_cols x n_rows, CSR); for a symmetric pattern pass A itself.  Y: the forward
+ * output (n_rows x f_out, ldy), needed only with SENSEI_ACT_RELU.  U_saved: optional n_rows x f_in, ldu.
+ * Outputs must not alias inputs or the workspace.  Results equal the plain chain rule up to fp32 summation
+ * order; dW is reduced over the nodes in fixed slabs, so it does not depend on scheduling. */
+enum { SENSEI_GCN_BWD_AGG = 0, SENSEI_GCN_BWD_UPD = 1 };
+int sensei_gcn_backward_workspace(const sensei_csr *A, int f_in, int f_out, int bwd_id, size_t *bytes);
+int sensei_gcn_backward(sensei_ctx *ctx, const sensei_csr *A, const sensei_csr *At, const float *r, const float *c, sensei_mat X,
+                        sensei_mat W, const float *Y, int64_t ldy, sensei_mat dY, int activation, const float *U_saved, int64_t ldu,
+                        float *dX, int64_t lddx, float *dW, int64_t lddw, int bwd_id, void *workspace, size_t ws_bytes, void *stream);
+
 int sensei_gat_workspace(const sensei_csr *A, int f_in, int f_out, int comp_id, size_t *bytes);
 
 /* One single-head GAT layer (Eq. 5-7): Theta = X.W; s_l = Theta.a_l, s_r = Theta.a_r;

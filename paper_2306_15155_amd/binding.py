@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libsensei_hip.so")
 ACT_NONE, ACT_RELU = 0, 1
 KIND_GCN, KIND_GAT = 0, 1
 SPMM_PATTERN, SPMM_WEIGHTED, SPMM_SCALED = 0, 1, 2
+GCN_BWD_AGG, GCN_BWD_UPD = 0, 1
 SELECT_MODEL, SELECT_TIMED = 0, 1
 GCN_NAMES = ("DYN_AGG", "DYN_UPD", "DYNF_AGG", "DYNF_UPD", "PRE_AGG", "PRE_UPD")
 GAT_NAMES = ("REUSE", "RECOMP", "RECOMP_FOLD", "REUSE_FOLD")
@@ -29,7 +30,7 @@ EXPORTS = (
     "sensei_gcn_workspace", "sensei_gcn_layer", "sensei_gat_workspace", "sensei_gat_layer", "sensei_select_workspace",
     "sensei_select", "sensei_profile_enable", "sensei_profile_read", "sensei_panels_bytes", "sensei_panels_create",
     "sensei_panels_count", "sensei_panels_destroy", "sensei_panels_set_min_width", "sensei_panels_tune_bytes",
-    "sensei_panels_tune",
+    "sensei_panels_tune", "sensei_gcn_backward_workspace", "sensei_gcn_backward",
 )
 
 
@@ -80,6 +81,9 @@ def lib():
         L.sensei_edge_softmax.argtypes = [vp, P(CsrStruct), vp, vp, vp, sz, vp]
         L.sensei_gcn_workspace.argtypes = [P(CsrStruct), i32, i32, i32, P(sz)]
         L.sensei_gcn_layer.argtypes = [vp, P(CsrStruct), vp, vp, MatStruct, MatStruct, vp, i64, i32, i32, vp, sz, vp]
+        L.sensei_gcn_backward_workspace.argtypes = [P(CsrStruct), i32, i32, i32, P(sz)]
+        L.sensei_gcn_backward.argtypes = [vp, P(CsrStruct), P(CsrStruct), vp, vp, MatStruct, MatStruct, vp, i64, MatStruct, i32, vp, i64,
+                                          vp, i64, vp, i64, i32, vp, sz, vp]
         L.sensei_gat_workspace.argtypes = [P(CsrStruct), i32, i32, i32, P(sz)]
         L.sensei_gat_layer.argtypes = [vp, P(CsrStruct), MatStruct, MatStruct, vp, vp, f32, vp, i64, i32, i32, vp, sz, vp]
         L.sensei_select_workspace.argtypes = [i32, P(CsrStruct), i32, i32, P(sz)]
@@ -308,6 +312,21 @@ class Context:
         n = ctypes.c_size_t()
         _check(lib().sensei_gat_workspace(ctypes.byref(A), f_in, f_out, comp_id, ctypes.byref(n)), "sensei_gat_workspace")
         return n.value
+
+    def gcn_backward(self, A: CsrStruct, At: CsrStruct, r, c, X, W, dY, bwd_id, Y=None, activation=ACT_NONE, U_saved=None, want_dx=True):
+        """Backward of gcn_layer -> (dX or None, dW); ``At`` is the transposed pattern (A itself when symmetric)."""
+        f_in, f_out = W.size(0), W.size(1)
+        dX = torch.empty((A.n_cols, f_in), dtype=torch.float32, device=self.device) if want_dx else None
+        dW = torch.empty((f_in, f_out), dtype=torch.float32, device=self.device)
+        need = ctypes.c_size_t()
+        _check(lib().sensei_gcn_backward_workspace(ctypes.byref(A), f_in, f_out, bwd_id, ctypes.byref(need)), "sensei_gcn_backward_workspace")
+        self.ws.ensure(need.value)
+        _check(lib().sensei_gcn_backward(self._h, ctypes.byref(A), ctypes.byref(At), _ptr(r), _ptr(c), mat_struct(X), mat_struct(W), _ptr(Y),
+                                         mat_struct(Y).ld if Y is not None else 0, mat_struct(dY), activation, _ptr(U_saved),
+                                         mat_struct(U_saved).ld if U_saved is not None else 0, _ptr(dX),
+                                         mat_struct(dX).ld if dX is not None else 0, _ptr(dW), mat_struct(dW).ld, bwd_id, self.ws.ptr,
+                                         self.ws.nbytes, _stream()), "sensei_gcn_backward")
+        return dX, dW
 
     def gat_layer(self, A: CsrStruct, X, W, a_l, a_r, comp_id, neg_slope=0.2, activation=ACT_NONE, out=None):
         Y = torch.empty((A.n_rows, W.size(1)), dtype=torch.float32, device=self.device) if out is None else out

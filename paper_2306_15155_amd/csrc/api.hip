@@ -233,6 +233,91 @@ int run_gcn(const sensei_csr &A, const float *r, const float *c, const sensei_ma
     return SENSEI_OK;
 }
 
+// ---- backward of the GCN layer
+size_t gcn_bwd_ws(const sensei_csr &A, int f_in, int f_out, int id) {
+    const int64_t nnz = A.nnz;
+    size_t b = 2 * plan_bytes(nnz) + 256;
+    b += align_up((size_t)pad4(f_in) * pad4(f_out) * sizeof(float), 256);                             // W^T
+    if (id == SENSEI_GCN_BWD_AGG) {
+        b += spmm_carry_bytes(nnz, pad32(f_out));
+        b += align_up((size_t)A.n_rows * pad32(f_out) * sizeof(float), 256);                          // r (x) dP
+        b += align_up((size_t)A.n_cols * pad4(f_out) * sizeof(float), 256);                           // G
+        b += gemm_tn_bytes(A.n_cols, f_in, f_out);
+    } else {
+        b += spmm_carry_bytes(nnz, pad32(f_in));
+        b += align_up((size_t)A.n_rows * pad4(f_out) * sizeof(float), 256);                           // dP
+        b += align_up((size_t)A.n_cols * pad32(f_in) * sizeof(float), 256);                           // c (x) X
+        b += align_up((size_t)A.n_rows * pad4(f_in) * sizeof(float), 256);                            // U
+        b += align_up((size_t)A.n_rows * pad32(f_in) * sizeof(float), 256);                           // r (x) dP.W^T
+        b += gemm_tn_bytes(A.n_rows, f_in, f_out);
+    }
+    return b;
+}
+
+int run_gcn_backward(const sensei_csr &A, const sensei_csr &At, const float *r, const float *c, const sensei_mat &X, const sensei_mat &W,
+                     const float *Y, int64_t ldy, const sensei_mat &dY, int act, const float *U_saved, int64_t ldu, float *dX, int64_t lddx,
+                     float *dW, int64_t lddw, int id, void *ws, size_t ws_bytes, hipStream_t s) {
+    const int f_in = (int)X.cols, f_out = (int)W.cols;
+    const float *mask = (act == SENSEI_ACT_RELU) ? Y : nullptr;
+    Carver cv(ws, ws_bytes);
+    ChunkPlan plan_t = make_plan(At, cv);
+    SENSEI_TRY(launch_chunk_rows(At, plan_t, s));
+    if (id == SENSEI_GCN_BWD_AGG) {
+        const int fo4 = pad4(f_out);
+        float *carry = cv.take<float>(spmm_carry_bytes(At.nnz, pad32(f_out)) / sizeof(float));
+        float *T = cv.take<float>((size_t)A.n_rows * pad32(f_out));
+        float *G = cv.take<float>((size_t)A.n_cols * fo4);
+        float *part = cv.take<float>(gemm_tn_bytes(A.n_cols, f_in, f_out) / sizeof(float));
+        // T = r (x) (dY (.) mask), slice-major when the transposed SpMM gathers each row often enough
+        const bool sliced = relayout_pays(At);
+        if (sliced) SENSEI_TRY(launch_to_slices(r, dY.ptr, dY.ld, A.n_rows, f_out, T, s, mask, ldy));
+        else SENSEI_TRY(launch_row_broadcast(r, dY.ptr, dY.ld, A.n_rows, f_out, T, fo4, SENSEI_ACT_NONE, s, mask, ldy));
+        // G = c (x) (A~^T T)
+        SENSEI_TRY(spmm_any(At, SENSEI_SPMM_PATTERN, c, nullptr, T, fo4, f_out, G, fo4, f_out, SENSEI_ACT_NONE, plan_t, carry, s, nullptr, false,
+                            nullptr, sliced));
+        SENSEI_TRY(launch_gemm_tn(X.ptr, X.ld, G, fo4, A.n_cols, f_in, f_out, dW, lddw, part, s));
+        if (dX) {
+            float *Wt = cv.take<float>((size_t)f_out * pad4(f_in));
+            SENSEI_TRY(launch_transpose(W.ptr, W.ld, f_in, f_out, Wt, pad4(f_in), s));
+            SENSEI_TRY(launch_gemm(G, fo4, Wt, pad4(f_in), dX, lddx, A.n_cols, f_out, f_in, f_in, SENSEI_ACT_NONE, s));
+        }
+    } else {
+        const int fo4 = pad4(f_out), fi4 = pad4(f_in), fi32 = pad32(f_in);
+        float *carry = cv.take<float>(spmm_carry_bytes(A.nnz, fi32) / sizeof(float));
+        float *dP = cv.take<float>((size_t)A.n_rows * fo4);
+        float *part = cv.take<float>(gemm_tn_bytes(A.n_rows, f_in, f_out) / sizeof(float));
+        SENSEI_TRY(launch_row_broadcast(nullptr, dY.ptr, dY.ld, A.n_rows, f_out, dP, fo4, SENSEI_ACT_NONE, s, mask, ldy));
+        const float *U = U_saved;
+        int64_t ld_u = ldu;
+        if (!U) {  // recompute U = r (x) (A~ (c (x) X)), the aggregate-first half of the forward
+            ChunkPlan plan = make_plan(A, cv);
+            SENSEI_TRY(launch_chunk_rows(A, plan, s));
+            float *T = cv.take<float>((size_t)A.n_cols * fi32);
+            float *Uw = cv.take<float>((size_t)A.n_rows * fi4);
+            const bool sliced = relayout_pays(A);
+            if (sliced) SENSEI_TRY(launch_to_slices(c, X.ptr, X.ld, A.n_cols, f_in, T, s));
+            else SENSEI_TRY(launch_row_broadcast(c, X.ptr, X.ld, A.n_cols, f_in, T, fi4, SENSEI_ACT_NONE, s));
+            SENSEI_TRY(spmm_any(A, SENSEI_SPMM_PATTERN, r, nullptr, T, fi4, f_in, Uw, fi4, f_in, SENSEI_ACT_NONE, plan, carry, s, nullptr, false,
+                                nullptr, sliced));
+            U = Uw;
+            ld_u = fi4;
+        }
+        SENSEI_TRY(launch_gemm_tn(U, ld_u, dP, fo4, A.n_rows, f_in, f_out, dW, lddw, part, s));
+        if (dX) {
+            float *Wt = cv.take<float>((size_t)f_out * fi4);
+            float *V = cv.take<float>((size_t)A.n_rows * fi32);
+            SENSEI_TRY(launch_transpose(W.ptr, W.ld, f_in, f_out, Wt, fi4, s));
+            // V = r (x) (dP W^T), written slice-major by the GEMM epilogue; dX = c (x) (A~^T V)
+            const bool sliced = relayout_pays(At);
+            SENSEI_TRY(launch_gemm(dP, fo4, Wt, fi4, V, sliced ? fi32 : fi4, A.n_rows, f_out, f_in, sliced ? fi32 : f_in, SENSEI_ACT_NONE, s, r,
+                                   nullptr, sliced));
+            SENSEI_TRY(spmm_any(At, SENSEI_SPMM_PATTERN, c, nullptr, V, fi4, f_in, dX, lddx, f_in, SENSEI_ACT_NONE, plan_t, carry, s, nullptr, false,
+                                nullptr, sliced));
+        }
+    }
+    return SENSEI_OK;
+}
+
 int run_gat(const sensei_csr &A, const sensei_mat &X, const sensei_mat &W, const float *a_l, const float *a_r,
             float slope, float *Y, int64_t ldy, int act, int id, void *ws, size_t ws_bytes, hipStream_t s, Timers *tm) {
     KernelTimer *kt = tm ? &tm->spmm : nullptr, *gt = tm ? &tm->gemm : nullptr;
@@ -807,6 +892,41 @@ int sensei_gcn_layer(sensei_ctx *ctx, const sensei_csr *A, const float *r, const
     if (ws_bytes < gcn_ws(*A, (int)X.cols, (int)W.cols, comp_id)) return SENSEI_WORKSPACE_TOO_SMALL;
     if (A->n_rows == 0) return SENSEI_OK;
     return run_gcn(*A, r, c, X, W, Y, ldy, activation, comp_id, workspace, ws_bytes, as_stream(stream), &ctx->timers);
+}
+
+int sensei_gcn_backward_workspace(const sensei_csr *A, int f_in, int f_out, int bwd_id, size_t *bytes) {
+    if (!csr_ok(A, false) || f_in <= 0 || f_out <= 0 || !bytes) return SENSEI_INVALID_ARGUMENT;
+    if (bwd_id != SENSEI_GCN_BWD_AGG && bwd_id != SENSEI_GCN_BWD_UPD) return SENSEI_INVALID_COMPOSITION;
+    *bytes = gcn_bwd_ws(*A, f_in, f_out, bwd_id);
+    return SENSEI_OK;
+}
+
+int sensei_gcn_backward(sensei_ctx *ctx, const sensei_csr *A, const sensei_csr *At, const float *r, const float *c, sensei_mat X,
+                        sensei_mat W, const float *Y, int64_t ldy, sensei_mat dY, int activation, const float *U_saved, int64_t ldu,
+                        float *dX, int64_t lddx, float *dW, int64_t lddw, int bwd_id, void *workspace, size_t ws_bytes, void *stream) {
+    if (bwd_id != SENSEI_GCN_BWD_AGG && bwd_id != SENSEI_GCN_BWD_UPD) return SENSEI_INVALID_COMPOSITION;
+    if (!ctx || !csr_ok(A, false) || !csr_ok(At, false) || !mat_ok(X) || !mat_ok(W) || !mat_ok(dY)) return SENSEI_INVALID_ARGUMENT;
+    if (At->n_rows != A->n_cols || At->n_cols != A->n_rows || At->nnz != A->nnz) return SENSEI_INVALID_ARGUMENT;
+    if (activation != SENSEI_ACT_NONE && activation != SENSEI_ACT_RELU) return SENSEI_INVALID_ARGUMENT;
+    if (X.rows != A->n_cols || X.cols != W.rows || X.cols <= 0 || W.cols <= 0) return SENSEI_INVALID_ARGUMENT;
+    if (X.cols > (1 << 20) || W.cols > (1 << 20)) return SENSEI_INVALID_ARGUMENT;
+    if (dY.rows != A->n_rows || dY.cols != W.cols) return SENSEI_INVALID_ARGUMENT;
+    if ((!X.ptr && A->n_cols > 0) || !W.ptr || (!dY.ptr && A->n_rows > 0) || !dW || !workspace) return SENSEI_INVALID_ARGUMENT;
+    if (lddw < W.cols || (dX && lddx < X.cols)) return SENSEI_INVALID_ARGUMENT;
+    if (activation == SENSEI_ACT_RELU && ((!Y && A->n_rows > 0) || ldy < W.cols)) return SENSEI_INVALID_ARGUMENT;
+    if (U_saved && ldu < X.cols) return SENSEI_INVALID_ARGUMENT;
+    if ((A->n_rows > 0 && !r) || (A->n_cols > 0 && !c)) return SENSEI_INVALID_ARGUMENT;
+    const size_t dwb = mat_bytes(dW, W.rows, W.cols, lddw), dxb = dX ? mat_bytes(dX, A->n_cols, X.cols, lddx) : 0;
+    const size_t xb = mat_bytes(X.ptr, X.rows, X.cols, X.ld), wb = mat_bytes(W.ptr, W.rows, W.cols, W.ld),
+                 dyb = mat_bytes(dY.ptr, dY.rows, dY.cols, dY.ld);
+    if (overlap(dW, dwb, workspace, ws_bytes) || overlap(dW, dwb, X.ptr, xb) || overlap(dW, dwb, W.ptr, wb) || overlap(dW, dwb, dY.ptr, dyb))
+        return SENSEI_INVALID_ARGUMENT;
+    if (dX && (overlap(dX, dxb, workspace, ws_bytes) || overlap(dX, dxb, X.ptr, xb) || overlap(dX, dxb, W.ptr, wb) ||
+               overlap(dX, dxb, dY.ptr, dyb) || overlap(dX, dxb, dW, dwb)))
+        return SENSEI_INVALID_ARGUMENT;
+    if (ws_bytes < gcn_bwd_ws(*A, (int)X.cols, (int)W.cols, bwd_id)) return SENSEI_WORKSPACE_TOO_SMALL;
+    return run_gcn_backward(*A, *At, r, c, X, W, Y, ldy, dY, activation, U_saved, ldu, dX, lddx, dW, lddw, bwd_id, workspace, ws_bytes,
+                            as_stream(stream));
 }
 
 int sensei_gat_workspace(const sensei_csr *A, int f_in, int f_out, int comp_id, size_t *bytes) {

@@ -163,6 +163,153 @@ hipError_t gemm_launch_vec(const GemmArgs &g, int avec, int bvec, hipStream_t s)
     return hipGetLastError();
 }
 
+// ---- C[M x N] = A^T . B with A stored [K x M] and B stored [K x N] (both row-major), K very long: the weight
+// gradient dW = X^T . G of a layer, reduced over all nodes.  The K range is cut into `splits` slabs, one
+// workgroup per (output tile, slab); slab s writes its partial tile to part[s] and k_sum_splits adds the slabs
+// in order, so the result does not depend on scheduling.  Both operands arrive k-major, which is the layout the
+// MFMA operand reads want, so both use the loader the forward kernel uses for W.
+struct GemmTnArgs {
+    const float *A, *B;
+    float *part;      // splits x M x N
+    long long lda, ldb, k;
+    int m, n, n_bn, n_tiles, k_per_split;
+};
+
+template <int VA, int VB>
+__global__ __launch_bounds__(kThreads) void k_gemm_tn(GemmTnArgs g) {
+    constexpr int BM = 128, BN = 128, TM = 2, TN = 2, PAD = 4;
+    __shared__ __attribute__((aligned(16))) float As[KT][BM + PAD];
+    __shared__ __attribute__((aligned(16))) float Bs[KT][BN + PAD];
+    const int t = threadIdx.x;
+    const int wave = t >> 6, lane = t & 63;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int tile = (int)(blockIdx.x % g.n_tiles), split = (int)(blockIdx.x / g.n_tiles);
+    const int m0 = (tile / g.n_bn) * BM, n0 = (tile % g.n_bn) * BN;
+    const long long k_lo = (long long)split * g.k_per_split;
+    const long long k_hi = (k_lo + g.k_per_split < g.k) ? k_lo + g.k_per_split : g.k;
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // loader: KT rows of 128 floats per operand; VEC floats per thread and pass
+    constexpr int A_TPR = BM / VA, A_RPP = kThreads / A_TPR, A_PASSES = (KT + A_RPP - 1) / A_RPP;
+    constexpr int B_TPR = BN / VB, B_RPP = kThreads / B_TPR, B_PASSES = (KT + B_RPP - 1) / B_RPP;
+    float ra[A_PASSES][VA], rb[B_PASSES][VB];
+    const int a_row = t / A_TPR, a_cc = (t % A_TPR) * VA;
+    const int b_row = t / B_TPR, b_cc = (t % B_TPR) * VB;
+
+    auto fetch = [&](long long k0) {
+#pragma unroll
+        for (int p = 0; p < A_PASSES; ++p) {
+            const int kr = p * A_RPP + a_row;
+            const long long kk = k0 + kr;
+            const int col = m0 + a_cc;
+            if (kr < KT && kk < k_hi && col < g.m) {  // VA == 4 implies m % 4 == 0: a piece never straddles the edge
+                const float *src = g.A + kk * g.lda + col;
+                if (VA == 4) { float4 v = *reinterpret_cast<const float4 *>(src); ra[p][0] = v.x; ra[p][1 % VA] = v.y; ra[p][2 % VA] = v.z; ra[p][3 % VA] = v.w; }
+                else ra[p][0] = *src;
+            } else {
+#pragma unroll
+                for (int e = 0; e < VA; ++e) ra[p][e] = 0.f;
+            }
+        }
+#pragma unroll
+        for (int p = 0; p < B_PASSES; ++p) {
+            const int kr = p * B_RPP + b_row;
+            const long long kk = k0 + kr;
+            const int col = n0 + b_cc;
+            if (kr < KT && kk < k_hi && col < g.n) {
+                const float *src = g.B + kk * g.ldb + col;
+                if (VB == 4) { float4 v = *reinterpret_cast<const float4 *>(src); rb[p][0] = v.x; rb[p][1 % VB] = v.y; rb[p][2 % VB] = v.z; rb[p][3 % VB] = v.w; }
+                else rb[p][0] = *src;
+            } else {
+#pragma unroll
+                for (int e = 0; e < VB; ++e) rb[p][e] = 0.f;
+            }
+        }
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int p = 0; p < A_PASSES; ++p) {
+            const int kr = p * A_RPP + a_row;
+            if (kr < KT) {
+#pragma unroll
+                for (int e = 0; e < VA; ++e) As[kr][a_cc + e] = ra[p][e];
+            }
+        }
+#pragma unroll
+        for (int p = 0; p < B_PASSES; ++p) {
+            const int kr = p * B_RPP + b_row;
+            if (kr < KT) {
+#pragma unroll
+                for (int e = 0; e < VB; ++e) Bs[kr][b_cc + e] = rb[p][e];
+            }
+        }
+    };
+
+    const int kh = lane >> 5, ll = lane & 31;
+    if (k_lo < k_hi) fetch(k_lo);
+    for (long long k0 = k_lo; k0 < k_hi; k0 += KT) {
+        stash();
+        __syncthreads();
+        if (k0 + KT < k_hi) fetch(k0 + KT);
+#pragma unroll
+        for (int kk = 0; kk < KT; kk += 2) {
+            float av[TM], bv[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) av[i] = As[kk + kh][(wm * TM + i) * 32 + ll];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) bv[j] = Bs[kk + kh][(wn * TN + j) * 32 + ll];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+
+    float *out = g.part + (size_t)split * (size_t)g.m * (size_t)g.n;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = n0 + (wn * TN + j) * 32 + ll;
+            if (col >= g.n) continue;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = m0 + (wm * TM + i) * 32 + 8 * (r / 4) + 4 * kh + (r % 4);
+                if (row < g.m) out[(size_t)row * g.n + col] = acc[i][j][r];
+            }
+        }
+}
+
+// C[i] = sum over the slabs, in slab order
+__global__ void k_sum_splits(const float *__restrict__ part, int splits, long long mn, int n, float *__restrict__ C, long long ldc) {
+    const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= mn) return;
+    float s = 0.f;
+    for (int p = 0; p < splits; ++p) s += part[(size_t)p * (size_t)mn + e];
+    C[(e / n) * ldc + (e % n)] = s;
+}
+
+// Wt[c][r] = W[r][c] for a small matrix (the layer weights)
+__global__ void k_transpose(const float *__restrict__ W, long long ldw, int rows, int cols, float *__restrict__ Wt, long long ldt) {
+    __shared__ float tile[32][33];
+    const int c0 = blockIdx.x * 32, r0 = blockIdx.y * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+    for (int y = ty; y < 32; y += 8)
+        if (r0 + y < rows && c0 + tx < cols) tile[y][tx] = W[(long long)(r0 + y) * ldw + c0 + tx];
+    __syncthreads();
+    for (int y = ty; y < 32; y += 8)
+        if (c0 + y < cols && r0 + tx < rows) Wt[(long long)(c0 + y) * ldt + r0 + tx] = tile[tx][y];
+}
+
 // y1 = A.v1, y2 = A.v2; one wavefront per row, lanes stride over k.
 template <int VEC>
 __global__ __launch_bounds__(kThreads) void k_gemv2(const float *__restrict__ A, long long lda, long long n, int k,
@@ -249,6 +396,45 @@ hipError_t launch_gemv2(const float *A, int64_t lda, int64_t n, int k, const flo
         hipLaunchKernelGGL((k_gemv2<2>), grid, dim3(kThreads), 0, s, A, (long long)lda, (long long)n, k, v1, v2, y1, y2, sl);
     else
         hipLaunchKernelGGL((k_gemv2<1>), grid, dim3(kThreads), 0, s, A, (long long)lda, (long long)n, k, v1, v2, y1, y2, sl);
+    return hipGetLastError();
+}
+
+int gemm_tn_splits(int64_t k, int m, int n) {
+    const long long tiles = (long long)((m + 127) / 128) * ((n + 127) / 128);
+    long long s = (768 + tiles - 1) / tiles;              // about three workgroups per compute unit
+    const long long max_s = (k + 4 * KT - 1) / (4 * KT);  // at least four k-tiles per slab
+    if (s > max_s) s = max_s;
+    return (int)(s < 1 ? 1 : s);
+}
+
+size_t gemm_tn_bytes(int64_t k, int m, int n) { return align_up((size_t)gemm_tn_splits(k, m, n) * (size_t)m * (size_t)n * sizeof(float), 256); }
+
+hipError_t launch_gemm_tn(const float *A, int64_t lda, const float *B, int64_t ldb, int64_t k, int m, int n, float *C, int64_t ldc,
+                          float *part, hipStream_t s) {
+    if (m <= 0 || n <= 0) return hipSuccess;
+    GemmTnArgs g;
+    g.A = A; g.B = B; g.part = part; g.lda = lda; g.ldb = ldb; g.k = k > 0 ? k : 0; g.m = m; g.n = n;
+    g.n_bn = (n + 127) / 128;
+    g.n_tiles = ((m + 127) / 128) * g.n_bn;
+    const int splits = gemm_tn_splits(k, m, n);
+    g.k_per_split = (int)(((g.k + splits - 1) / splits + KT - 1) / KT * KT);
+    if (g.k_per_split < KT) g.k_per_split = KT;
+    const bool va = (m % 4 == 0 && lda % 4 == 0 && reinterpret_cast<uintptr_t>(A) % 16 == 0);
+    const bool vb = (n % 4 == 0 && ldb % 4 == 0 && reinterpret_cast<uintptr_t>(B) % 16 == 0);
+    dim3 grid((unsigned)(g.n_tiles * splits));
+    if (va && vb) hipLaunchKernelGGL((k_gemm_tn<4, 4>), grid, dim3(kThreads), 0, s, g);
+    else if (va) hipLaunchKernelGGL((k_gemm_tn<4, 1>), grid, dim3(kThreads), 0, s, g);
+    else if (vb) hipLaunchKernelGGL((k_gemm_tn<1, 4>), grid, dim3(kThreads), 0, s, g);
+    else hipLaunchKernelGGL((k_gemm_tn<1, 1>), grid, dim3(kThreads), 0, s, g);
+    const long long mn = (long long)m * n;
+    hipLaunchKernelGGL(k_sum_splits, dim3((unsigned)((mn + 255) / 256)), dim3(256), 0, s, part, splits, mn, n, C, (long long)ldc);
+    return hipGetLastError();
+}
+
+hipError_t launch_transpose(const float *W, int64_t ldw, int rows, int cols, float *Wt, int64_t ldt, hipStream_t s) {
+    if (rows <= 0 || cols <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_transpose, dim3((unsigned)((cols + 31) / 32), (unsigned)((rows + 31) / 32)), dim3(256), 0, s, W, (long long)ldw, rows, cols,
+                       Wt, (long long)ldt);
     return hipGetLastError();
 }
 

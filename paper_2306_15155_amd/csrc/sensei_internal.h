@@ -84,11 +84,13 @@ hipError_t launch_degrees(const sensei_csr &A, int32_t *deg_row, int32_t *deg_co
 hipError_t launch_norm_vectors(const int32_t *deg, int64_t n, float *out, hipStream_t s);
 hipError_t launch_sddmm_norm(const sensei_csr &A, const float *r, const float *c, float *val, const ChunkPlan &p,
                              hipStream_t s);
+// mask (optional, n x f, ldm): elements whose mask value is not > 0 are written as 0 (backward of ReLU)
 hipError_t launch_row_broadcast(const float *s_vec, const float *X, int64_t ldx, int64_t n, int f, float *Y,
-                                int64_t ldy, int act, hipStream_t s);
+                                int64_t ldy, int act, hipStream_t s, const float *mask = nullptr, int64_t ldm = 0);
 
 // Y (slice-major, pad32(f) columns, 128-byte aligned, n * pad32(f) floats) = s_vec (x) X, s_vec optional; pad columns = 0
-hipError_t launch_to_slices(const float *s_vec, const float *X, int64_t ldx, int64_t n, int f, float *Y, hipStream_t s);
+hipError_t launch_to_slices(const float *s_vec, const float *X, int64_t ldx, int64_t n, int f, float *Y, hipStream_t s,
+                            const float *mask = nullptr, int64_t ldm = 0);
 
 // ---- attention: logits, per-row softmax statistics, normalised weights
 hipError_t launch_score(const sensei_csr &A, const float *s_l, const float *s_r, float slope, float *e,
@@ -111,6 +113,13 @@ hipError_t launch_gemm(const float *A, int64_t lda, const float *W, int64_t ldw,
 // y_sliced / a_sliced: that matrix is stored slice-major in tiles of 32 floats (see launch_spmm); its leading dimension is ignored.
 hipError_t launch_gemv2(const float *A, int64_t lda, int64_t n, int k, const float *v1, const float *v2, float *y1,
                         float *y2, hipStream_t s, bool a_sliced = false);
+
+// C[m x n] (row-major, ldc) = A^T . B with A stored k x m and B stored k x n; `part` holds gemm_tn_bytes(k, m, n) bytes.
+// The k range is cut into slabs whose partial products are added in slab order (deterministic).
+size_t gemm_tn_bytes(int64_t k, int m, int n);
+hipError_t launch_gemm_tn(const float *A, int64_t lda, const float *B, int64_t ldb, int64_t k, int m, int n, float *C, int64_t ldc,
+                          float *part, hipStream_t s);
+hipError_t launch_transpose(const float *W, int64_t ldw, int rows, int cols, float *Wt, int64_t ldt, hipStream_t s);
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline int pad4(int f) { return (f + 3) & ~3; }

@@ -493,7 +493,7 @@ __global__ __launch_bounds__(kBlock) void k_score(NnzArgs a, const float *__rest
 
 template <int VEC>
 __global__ void k_row_broadcast(const float *__restrict__ s, const float *X, long long ldx, long long n, int f, float *Y,
-                                long long ldy, int act) {  // Y may be X (in place)
+                                long long ldy, int act, const float *__restrict__ mask, long long ldm) {  // Y may be X (in place)
     const int fv = f / VEC;
     long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= n * fv) return;
@@ -505,6 +505,7 @@ __global__ void k_row_broadcast(const float *__restrict__ s, const float *X, lon
     for (int e = 0; e < VEC; ++e) {
         float y = x.v[e] * sc;
         if (act == SENSEI_ACT_RELU) y = y > 0.f ? y : 0.f;
+        if (mask && !(mask[i * ldm + q + e] > 0.f)) y = 0.f;  // gradient of ReLU: passes where the forward output is positive
         x.v[e] = y;
     }
     x.store(Y + i * ldy + q);
@@ -513,7 +514,7 @@ __global__ void k_row_broadcast(const float *__restrict__ s, const float *X, lon
 // Copy of X (n x f, row-major) into slice-major tiles of 32 columns, optionally scaled per row; the pad columns
 // up to the next multiple of 32 are written as zeros.  One thread per (row, 4 columns).
 __global__ void k_to_slices(const float *__restrict__ s, const float *__restrict__ X, long long ldx, long long n, int f,
-                            float *__restrict__ Y, int x_vec_ok) {
+                            float *__restrict__ Y, int x_vec_ok, const float *__restrict__ mask, long long ldm) {
     const int fp4 = ((f + 31) & ~31) / 4;
     const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= n * fp4) return;
@@ -535,6 +536,13 @@ __global__ void k_to_slices(const float *__restrict__ s, const float *__restrict
         if (q + 3 < f) v.w = x[3];
     }
     v.x *= sc; v.y *= sc; v.z *= sc; v.w *= sc;
+    if (mask) {  // gradient of ReLU: passes where the forward output is positive
+        const float *mk = mask + i * ldm + q;
+        if (!(q < f && mk[0] > 0.f)) v.x = 0.f;
+        if (!(q + 1 < f && mk[1] > 0.f)) v.y = 0.f;
+        if (!(q + 2 < f && mk[2] > 0.f)) v.z = 0.f;
+        if (!(q + 3 < f && mk[3] > 0.f)) v.w = 0.f;
+    }
     *reinterpret_cast<float4 *>(Y + (size_t)tile * (size_t)n * 32 + (size_t)in_tile * 4) = v;
 }
 
@@ -909,21 +917,23 @@ hipError_t launch_score(const sensei_csr &A, const float *s_l, const float *s_r,
     return hipGetLastError();
 }
 
-hipError_t launch_row_broadcast(const float *s_vec, const float *X, int64_t ldx, int64_t n, int f, float *Y, int64_t ldy, int act, hipStream_t s) {
+hipError_t launch_row_broadcast(const float *s_vec, const float *X, int64_t ldx, int64_t n, int f, float *Y, int64_t ldy, int act, hipStream_t s,
+                                const float *mask, int64_t ldm) {
     if (n <= 0 || f <= 0) return hipSuccess;
     const bool a16 = reinterpret_cast<uintptr_t>(X) % 16 == 0 && reinterpret_cast<uintptr_t>(Y) % 16 == 0;
     if (f % 4 == 0 && ldx % 4 == 0 && ldy % 4 == 0 && a16)
-        hipLaunchKernelGGL((k_row_broadcast<4>), dim3(blocks_for(n * (f / 4), kBlock)), dim3(kBlock), 0, s, s_vec, X, (long long)ldx, (long long)n, f, Y, (long long)ldy, act);
+        hipLaunchKernelGGL((k_row_broadcast<4>), dim3(blocks_for(n * (f / 4), kBlock)), dim3(kBlock), 0, s, s_vec, X, (long long)ldx, (long long)n, f, Y, (long long)ldy, act, mask, (long long)ldm);
     else
-        hipLaunchKernelGGL((k_row_broadcast<1>), dim3(blocks_for(n * f, kBlock)), dim3(kBlock), 0, s, s_vec, X, (long long)ldx, (long long)n, f, Y, (long long)ldy, act);
+        hipLaunchKernelGGL((k_row_broadcast<1>), dim3(blocks_for(n * f, kBlock)), dim3(kBlock), 0, s, s_vec, X, (long long)ldx, (long long)n, f, Y, (long long)ldy, act, mask, (long long)ldm);
     return hipGetLastError();
 }
 
-hipError_t launch_to_slices(const float *s_vec, const float *X, int64_t ldx, int64_t n, int f, float *Y, hipStream_t s) {
+hipError_t launch_to_slices(const float *s_vec, const float *X, int64_t ldx, int64_t n, int f, float *Y, hipStream_t s, const float *mask,
+                            int64_t ldm) {
     if (n <= 0 || f <= 0) return hipSuccess;
     const int x_vec_ok = (ldx % 4 == 0 && reinterpret_cast<uintptr_t>(X) % 16 == 0) ? 1 : 0;
     const long long threads = n * (long long)(pad32(f) / 4);
-    hipLaunchKernelGGL(k_to_slices, dim3(blocks_for(threads, kBlock)), dim3(kBlock), 0, s, s_vec, X, (long long)ldx, (long long)n, f, Y, x_vec_ok);
+    hipLaunchKernelGGL(k_to_slices, dim3(blocks_for(threads, kBlock)), dim3(kBlock), 0, s, s_vec, X, (long long)ldx, (long long)n, f, Y, x_vec_ok, mask, (long long)ldm);
     return hipGetLastError();
 }
 

@@ -168,6 +168,12 @@ def self_loops_only(n: int) -> CSR:
     return build_csr(n, n, e, e, False, True)
 
 
+def transpose(g: CSR) -> CSR:
+    """The transposed pattern (n_cols x n_rows), columns ascending within a row."""
+    rows = np.repeat(np.arange(g.n_rows, dtype=np.int32), np.diff(g.row_ptr))
+    return build_csr(g.n_cols, g.n_rows, g.col_idx, rows, False, False)
+
+
 def sample_block(seed: int, stream: int, g: CSR, dst: np.ndarray, fanout: int):
     """One hop of fan-out sampling -> (block CSR with local columns, global ids of its columns)."""
     dst = np.ascontiguousarray(dst, dtype=np.int32)

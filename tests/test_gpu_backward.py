@@ -1,0 +1,108 @@
+"""GPU parity of the backward pass (through the C ABI) against the fp64 chain-rule oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+from paper_2306_15155_amd import ACT_NONE, ACT_RELU, GCN_BWD_AGG, GCN_BWD_UPD, Context
+
+from gpu_util import DeviceCSR, assert_close, dev, hub_and_empty_graph, rect_block
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = Context(0)
+    yield c
+    c.close()
+
+
+GRAPHS = {
+    "er": lambda: synth.erdos_renyi(41, 3000, 40_000),                 # symmetric, several chunks
+    "rmat_hub": lambda: synth.rmat(42, 5000, 150_000),                 # skewed, rows crossing chunk boundaries
+    "hub_empty": lambda: hub_and_empty_graph(43, 2500, 30_000, 1800, 40),  # not symmetric, empty rows, no self loops
+    "rect": lambda: rect_block(44, 700, 4000, 9),                      # bipartite block
+    "dense_small": lambda: synth.erdos_renyi(45, 600, 60_000),         # every row gathered often: slice-major path
+}
+
+
+def _inputs(g, f_in, f_out, seed):
+    X = synth.uniform(seed, 10, (g.n_cols, f_in))
+    W = synth.glorot(seed, 11, f_in, f_out)
+    dY = synth.normal(seed, 12, (g.n_rows, f_out), 0.0, 1.0)
+    return X, W, dY
+
+
+@pytest.mark.parametrize("name", sorted(GRAPHS))
+@pytest.mark.parametrize("widths", [(40, 24), (24, 40), (100, 41), (33, 130)])
+@pytest.mark.parametrize("act", [ACT_NONE, ACT_RELU])
+def test_gcn_backward_matches_chain_rule(ctx, name, widths, act):
+    g = GRAPHS[name]()
+    gt = synth.transpose(g)
+    f_in, f_out = widths
+    X, W, dY = _inputs(g, f_in, f_out, 50 + f_in)
+    Y = None
+    if act == ACT_RELU:  # the mask comes from the forward output; both sides get the oracle's, rounded to fp32
+        Y = oracle.gcn_layer(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, 1).astype(np.float32)
+    want_dx, want_dw = oracle.gcn_backward(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, dY, Y=Y, act=act)
+    A, At = DeviceCSR(g), DeviceCSR(gt)
+    dr, dc = ctx.degrees(A.s)
+    r, c = ctx.norm_vectors(dr), ctx.norm_vectors(dc)
+    Yd = None if Y is None else dev(Y)
+    for bwd in (GCN_BWD_AGG, GCN_BWD_UPD):
+        dX, dW = ctx.gcn_backward(A.s, At.s, r, c, dev(X), dev(W), dev(dY), bwd, Y=Yd, activation=act)
+        assert_close(dX, want_dx, what=f"dX bwd {bwd}")
+        assert_close(dW, want_dw, what=f"dW bwd {bwd}")
+    # weight gradient only (first layer of a model)
+    none, dW = ctx.gcn_backward(A.s, At.s, r, c, dev(X), dev(W), dev(dY), GCN_BWD_AGG, Y=Yd, activation=act, want_dx=False)
+    assert none is None
+    assert_close(dW, want_dw, what="dW only")
+
+
+def test_gcn_backward_with_saved_aggregate_and_strided_operands(ctx):
+    g = synth.rmat(46, 4000, 100_000)
+    f_in, f_out = 52, 96
+    X, W, dY = _inputs(g, f_in, f_out, 60)
+    r64 = 1.0 / np.sqrt(np.maximum(np.diff(g.row_ptr), 1).astype(np.float64))
+    U = oracle.row_broadcast(r64, oracle.spmm(g.row_ptr, g.col_idx, r64[g.col_idx], X)).astype(np.float32)  # symmetric: c = r
+    want_dx, want_dw = oracle.gcn_backward(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, dY)
+    A = DeviceCSR(g)
+    dr, dc = ctx.degrees(A.s)
+    r, c = ctx.norm_vectors(dr), ctx.norm_vectors(dc)
+    # operands as column slices of wider buffers (leading dimension > width, odd offsets)
+    Xw = torch.zeros((g.n_cols, f_in + 7), device="cuda:0"); Xw[:, 3:3 + f_in] = dev(X)
+    dYw = torch.zeros((g.n_rows, f_out + 5), device="cuda:0"); dYw[:, 1:1 + f_out] = dev(dY)
+    Uw = torch.zeros((g.n_rows, f_in + 2), device="cuda:0"); Uw[:, 1:1 + f_in] = dev(U)
+    dX, dW = ctx.gcn_backward(A.s, A.s, r, c, Xw[:, 3:3 + f_in], dev(W), dYw[:, 1:1 + f_out], GCN_BWD_UPD, U_saved=Uw[:, 1:1 + f_in])
+    assert_close(dX, want_dx, what="dX saved U")
+    assert_close(dW, want_dw, what="dW saved U")
+    dX, dW = ctx.gcn_backward(A.s, A.s, r, c, Xw[:, 3:3 + f_in], dev(W), dYw[:, 1:1 + f_out], GCN_BWD_AGG)
+    assert_close(dX, want_dx, what="dX strided")
+    assert_close(dW, want_dw, what="dW strided")
+
+
+def test_gcn_backward_argument_checks(ctx):
+    import ctypes
+    from paper_2306_15155_amd import binding
+    g = synth.erdos_renyi(47, 200, 600)
+    A = DeviceCSR(g)
+    X, W, dY = (torch.zeros(s, device="cuda:0") for s in ((200, 8), (8, 4), (200, 4)))
+    dX, dW, ws = torch.zeros((200, 8), device="cuda:0"), torch.zeros((8, 4), device="cuda:0"), torch.zeros(1 << 22, dtype=torch.uint8, device="cuda:0")
+    r = torch.ones(200, device="cuda:0")
+    L = binding.lib()
+
+    def call(bwd=0, act=0, Y=None, dXp=dX, wsb=ws.numel(), At=A.s):
+        return L.sensei_gcn_backward(ctx._h, ctypes.byref(A.s), ctypes.byref(At), r.data_ptr(), r.data_ptr(), binding.mat_struct(X),
+                                     binding.mat_struct(W), None if Y is None else Y.data_ptr(), 4, binding.mat_struct(dY), act, None, 0,
+                                     dXp.data_ptr(), 8, dW.data_ptr(), 4, bwd, ws.data_ptr(), wsb, None)
+
+    assert call() == 0
+    assert call(bwd=2) == 2                       # unknown association
+    assert call(act=1) == 1                       # ReLU without the forward output
+    assert call(wsb=1024) == 3                    # workspace too small
+    assert call(dXp=X) == 1                       # output aliases an input
+    g2 = synth.erdos_renyi(48, 100, 300)
+    assert call(At=DeviceCSR(g2).s) == 1          # transposed pattern of another shape
+    torch.cuda.synchronize()
