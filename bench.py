@@ -264,6 +264,23 @@ def main():
         detail["select_timed"] = {"layer": tag(0), "pick": name_of(0, idt), "overhead_ms": round(dt, 3),
                                   "overhead_in_layers": round(dt / detail["layers"][tag(0)]["ms"], 2)}
 
+    # ---- training: backward of the GCN layers in both associations (symmetric pattern: it is its own transpose)
+    if not args.no_sweep:
+        bwd = {}
+        for i, L in enumerate(layers):
+            if L["kind"] != "gcn":
+                continue
+            dYt = torch.randn((N, L["f_out"]), device=dev)
+            Ymask = outs[i] if L["act"] else None
+            t = {nm: round(time_fn(lambda: ctx.gcn_backward(A, A, r, c, src_of(i), Wd[i], dYt, bid, Y=Ymask, activation=L["act"]), 2), 4)
+                 for bid, nm in ((0, "BWD_AGG"), (1, "BWD_UPD"))}
+            pick, _ = ctx.select_gcn_backward(A, L["f_in"], L["f_out"])
+            t["picked"] = ("BWD_AGG", "BWD_UPD")[pick]
+            t["regret"] = round(t[t["picked"]] / min(t["BWD_AGG"], t["BWD_UPD"]) - 1.0, 4)
+            bwd[tag(i)] = t
+            del dYt
+        detail["gcn_backward_ms"] = bwd
+
     # ---- ceiling of the neighbour gather: the same SpMM kernel (value-less, F = 256) on a synthetic pattern whose
     # columns span only 8192 rows of the gathered matrix, so every 128-byte feature slice (1 MB) stays in one L2.
     # The rate it reaches bounds what any SpMM of this shape can consume, whatever the graph.

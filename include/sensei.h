@@ -227,6 +227,12 @@ int sensei_gcn_backward(sensei_ctx *ctx, const sensei_csr *A, const sensei_csr *
                         sensei_mat W, const float *Y, int64_t ldy, sensei_mat dY, int activation, const float *U_saved, int64_t ldu,
                         float *dX, int64_t lddx, float *dW, int64_t lddw, int bwd_id, void *workspace, size_t ws_bytes, void *stream);
 
+/* Which association of the GCN backward is predicted faster for this graph and these sizes (the additive
+ * per-primitive cost model of sensei_select, host arithmetic only).  have_saved_u: the forward kept
+ * U = D_r^(-1/2) A~ D_c^(-1/2) X; want_dx: the input gradient is needed.  est_ms: optional, 2 entries. */
+int sensei_select_gcn_backward(sensei_ctx *ctx, const sensei_csr *A, int f_in, int f_out, int have_saved_u, int want_dx,
+                               int *bwd_id_out, float *est_ms);
+
 int sensei_gat_workspace(const sensei_csr *A, int f_in, int f_out, int comp_id, size_t *bytes);
 
 /* One single-head GAT layer (Eq. 5-7): Theta = X.W; s_l = Theta.a_l, s_r = Theta.a_r;

@@ -30,7 +30,7 @@ EXPORTS = (
     "sensei_gcn_workspace", "sensei_gcn_layer", "sensei_gat_workspace", "sensei_gat_layer", "sensei_select_workspace",
     "sensei_select", "sensei_profile_enable", "sensei_profile_read", "sensei_panels_bytes", "sensei_panels_create",
     "sensei_panels_count", "sensei_panels_destroy", "sensei_panels_set_min_width", "sensei_panels_tune_bytes",
-    "sensei_panels_tune", "sensei_gcn_backward_workspace", "sensei_gcn_backward",
+    "sensei_panels_tune", "sensei_gcn_backward_workspace", "sensei_gcn_backward", "sensei_select_gcn_backward",
 )
 
 
@@ -84,6 +84,7 @@ def lib():
         L.sensei_gcn_backward_workspace.argtypes = [P(CsrStruct), i32, i32, i32, P(sz)]
         L.sensei_gcn_backward.argtypes = [vp, P(CsrStruct), P(CsrStruct), vp, vp, MatStruct, MatStruct, vp, i64, MatStruct, i32, vp, i64,
                                           vp, i64, vp, i64, i32, vp, sz, vp]
+        L.sensei_select_gcn_backward.argtypes = [vp, P(CsrStruct), i32, i32, i32, i32, P(ctypes.c_int), P(f32)]
         L.sensei_gat_workspace.argtypes = [P(CsrStruct), i32, i32, i32, P(sz)]
         L.sensei_gat_layer.argtypes = [vp, P(CsrStruct), MatStruct, MatStruct, vp, vp, f32, vp, i64, i32, i32, vp, sz, vp]
         L.sensei_select_workspace.argtypes = [i32, P(CsrStruct), i32, i32, P(sz)]
@@ -327,6 +328,13 @@ class Context:
                                          mat_struct(dX).ld if dX is not None else 0, _ptr(dW), mat_struct(dW).ld, bwd_id, self.ws.ptr,
                                          self.ws.nbytes, _stream()), "sensei_gcn_backward")
         return dX, dW
+
+    def select_gcn_backward(self, A: CsrStruct, f_in, f_out, have_saved_u=False, want_dx=True):
+        pick = ctypes.c_int()
+        est = (ctypes.c_float * 2)()
+        _check(lib().sensei_select_gcn_backward(self._h, ctypes.byref(A), f_in, f_out, int(have_saved_u), int(want_dx), ctypes.byref(pick), est),
+               "sensei_select_gcn_backward")
+        return pick.value, [float(x) for x in est]
 
     def gat_layer(self, A: CsrStruct, X, W, a_l, a_r, comp_id, neg_slope=0.2, activation=ACT_NONE, out=None):
         Y = torch.empty((A.n_rows, W.size(1)), dtype=torch.float32, device=self.device) if out is None else out

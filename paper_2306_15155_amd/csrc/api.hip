@@ -267,7 +267,7 @@ int run_gcn_backward(const sensei_csr &A, const sensei_csr &At, const float *r, 
         float *carry = cv.take<float>(spmm_carry_bytes(At.nnz, pad32(f_out)) / sizeof(float));
         float *T = cv.take<float>((size_t)A.n_rows * pad32(f_out));
         float *G = cv.take<float>((size_t)A.n_cols * fo4);
-        float *part = cv.take<float>(gemm_tn_bytes(A.n_cols, f_in, f_out) / sizeof(float));
+        double *part = cv.take<double>(gemm_tn_bytes(A.n_cols, f_in, f_out) / sizeof(double));
         // T = r (x) (dY (.) mask), slice-major when the transposed SpMM gathers each row often enough
         const bool sliced = relayout_pays(At);
         if (sliced) SENSEI_TRY(launch_to_slices(r, dY.ptr, dY.ld, A.n_rows, f_out, T, s, mask, ldy));
@@ -285,7 +285,7 @@ int run_gcn_backward(const sensei_csr &A, const sensei_csr &At, const float *r, 
         const int fo4 = pad4(f_out), fi4 = pad4(f_in), fi32 = pad32(f_in);
         float *carry = cv.take<float>(spmm_carry_bytes(A.nnz, fi32) / sizeof(float));
         float *dP = cv.take<float>((size_t)A.n_rows * fo4);
-        float *part = cv.take<float>(gemm_tn_bytes(A.n_rows, f_in, f_out) / sizeof(float));
+        double *part = cv.take<double>(gemm_tn_bytes(A.n_rows, f_in, f_out) / sizeof(double));
         SENSEI_TRY(launch_row_broadcast(nullptr, dY.ptr, dY.ld, A.n_rows, f_out, dP, fo4, SENSEI_ACT_NONE, s, mask, ldy));
         const float *U = U_saved;
         int64_t ld_u = ldu;
@@ -445,6 +445,21 @@ double gat_cost(const sensei_ctx &c, const Features &g, int f_in, int f_out, int
     } else {
         t += t_spmm(c, g, f_in, kSpmmWeighted) + t_gemm(c, g.n_rows, f_in, f_out);
         if (g.nnz >= 16.0 * g.n_cols) t += t_stream(c, 8.0 * g.n_cols * f_in);  // slice-major copy of X
+    }
+    return t;
+}
+
+double gcn_bwd_cost(const sensei_ctx &c, const Features &g, int f_in, int f_out, int id, bool saved_u, bool want_dx) {
+    Features gt = g;  // the transposed pattern
+    gt.n_rows = g.n_cols; gt.n_cols = g.n_rows;
+    double t = t_stream(c, 12.0 * g.n_rows * f_out);  // dP = dY (.) mask, scaled / re-laid
+    if (id == SENSEI_GCN_BWD_AGG) {
+        t += t_spmm(c, gt, f_out, kSpmmPattern) + t_gemm(c, f_in, g.n_cols, f_out);
+        if (want_dx) t += t_gemm(c, g.n_cols, f_out, f_in);
+    } else {
+        if (!saved_u) t += t_stream(c, 8.0 * g.n_cols * f_in) + t_spmm(c, g, f_in, kSpmmPattern);
+        t += t_gemm(c, f_in, g.n_rows, f_out);
+        if (want_dx) t += t_gemm(c, g.n_rows, f_out, f_in) + t_spmm(c, gt, f_in, kSpmmPattern);
     }
     return t;
 }
@@ -960,6 +975,21 @@ int sensei_select_workspace(int kind, const sensei_csr *A, int f_in, int f_out, 
     if ((kind != SENSEI_KIND_GCN && kind != SENSEI_KIND_GAT) || !csr_ok(A, false) || f_in <= 0 || f_out <= 0 || !bytes)
         return SENSEI_INVALID_ARGUMENT;
     *bytes = select_scratch_bytes(kind, *A, f_in, f_out);
+    return SENSEI_OK;
+}
+
+int sensei_select_gcn_backward(sensei_ctx *ctx, const sensei_csr *A, int f_in, int f_out, int have_saved_u, int want_dx,
+                               int *bwd_id_out, float *est_ms) {
+    if (!ctx || !csr_ok(A, false) || f_in <= 0 || f_out <= 0 || !bwd_id_out) return SENSEI_INVALID_ARGUMENT;
+    Features g;
+    g.n_rows = A->n_rows; g.n_cols = A->n_cols; g.nnz = (double)A->nnz;
+    g.density = (A->n_rows > 0 && A->n_cols > 0) ? g.nnz / (g.n_rows * g.n_cols) : 0.0;
+    double cost[2];
+    for (int id = 0; id < 2; ++id) {
+        cost[id] = 1e3 * gcn_bwd_cost(*ctx, g, f_in, f_out, id, have_saved_u != 0, want_dx != 0);
+        if (est_ms) est_ms[id] = (float)cost[id];
+    }
+    *bwd_id_out = cost[SENSEI_GCN_BWD_UPD] < cost[SENSEI_GCN_BWD_AGG] ? SENSEI_GCN_BWD_UPD : SENSEI_GCN_BWD_AGG;
     return SENSEI_OK;
 }
 

@@ -167,13 +167,18 @@ hipError_t gemm_launch_vec(const GemmArgs &g, int avec, int bvec, hipStream_t s)
 // gradient dW = X^T . G of a layer, reduced over all nodes.  The K range is cut into `splits` slabs, one
 // workgroup per (output tile, slab); slab s writes its partial tile to part[s] and k_sum_splits adds the slabs
 // in order, so the result does not depend on scheduling.  Both operands arrive k-major, which is the layout the
-// MFMA operand reads want, so both use the loader the forward kernel uses for W.
+// MFMA operand reads want, so both use the loader the forward kernel uses for W.  A sum over 10^5..10^7 nodes
+// in one fp32 accumulator would lose the small entries of dW (rounding grows with the running sum, about
+// 6e-4 of a term's spread at K = 233,000): the fp32 MFMA accumulators are therefore emptied into fp64 registers
+// after every kFlushTiles k-tiles, the slabs are stored and added in fp64, and only the final sum is rounded to fp32.
 struct GemmTnArgs {
     const float *A, *B;
-    float *part;      // splits x M x N
+    double *part;     // splits x M x N
     long long lda, ldb, k;
     int m, n, n_bn, n_tiles, k_per_split;
 };
+
+constexpr int kFlushTiles = 1;  // k-tiles (of KT = 16) summed in fp32 before the accumulators move to fp64
 
 template <int VA, int VB>
 __global__ __launch_bounds__(kThreads) void k_gemm_tn(GemmTnArgs g) {
@@ -189,12 +194,21 @@ __global__ __launch_bounds__(kThreads) void k_gemm_tn(GemmTnArgs g) {
     const long long k_hi = (k_lo + g.k_per_split < g.k) ? k_lo + g.k_per_split : g.k;
 
     floatx16 acc[TM][TN];
+    double dacc[TM][TN][16];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+            for (int r = 0; r < 16; ++r) { acc[i][j][r] = 0.f; dacc[i][j][r] = 0.0; }
+    auto flush = [&]() {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) { dacc[i][j][r] += (double)acc[i][j][r]; acc[i][j][r] = 0.f; }
+    };
 
     // loader: KT rows of 128 floats per operand; VEC floats per thread and pass
     constexpr int A_TPR = BM / VA, A_RPP = kThreads / A_TPR, A_PASSES = (KT + A_RPP - 1) / A_RPP;
@@ -254,6 +268,7 @@ __global__ __launch_bounds__(kThreads) void k_gemm_tn(GemmTnArgs g) {
 
     const int kh = lane >> 5, ll = lane & 31;
     if (k_lo < k_hi) fetch(k_lo);
+    int since_flush = 0;
     for (long long k0 = k_lo; k0 < k_hi; k0 += KT) {
         stash();
         __syncthreads();
@@ -271,10 +286,12 @@ __global__ __launch_bounds__(kThreads) void k_gemm_tn(GemmTnArgs g) {
                 for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
         }
+        if (++since_flush == kFlushTiles) { flush(); since_flush = 0; }
         __syncthreads();
     }
+    flush();
 
-    float *out = g.part + (size_t)split * (size_t)g.m * (size_t)g.n;
+    double *out = g.part + (size_t)split * (size_t)g.m * (size_t)g.n;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -284,18 +301,18 @@ __global__ __launch_bounds__(kThreads) void k_gemm_tn(GemmTnArgs g) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int row = m0 + (wm * TM + i) * 32 + 8 * (r / 4) + 4 * kh + (r % 4);
-                if (row < g.m) out[(size_t)row * g.n + col] = acc[i][j][r];
+                if (row < g.m) out[(size_t)row * g.n + col] = dacc[i][j][r];
             }
         }
 }
 
 // C[i] = sum over the slabs, in slab order
-__global__ void k_sum_splits(const float *__restrict__ part, int splits, long long mn, int n, float *__restrict__ C, long long ldc) {
+__global__ void k_sum_splits(const double *__restrict__ part, int splits, long long mn, int n, float *__restrict__ C, long long ldc) {
     const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= mn) return;
-    float s = 0.f;
+    double s = 0.0;
     for (int p = 0; p < splits; ++p) s += part[(size_t)p * (size_t)mn + e];
-    C[(e / n) * ldc + (e % n)] = s;
+    C[(e / n) * ldc + (e % n)] = (float)s;
 }
 
 // Wt[c][r] = W[r][c] for a small matrix (the layer weights)
@@ -407,10 +424,10 @@ int gemm_tn_splits(int64_t k, int m, int n) {
     return (int)(s < 1 ? 1 : s);
 }
 
-size_t gemm_tn_bytes(int64_t k, int m, int n) { return align_up((size_t)gemm_tn_splits(k, m, n) * (size_t)m * (size_t)n * sizeof(float), 256); }
+size_t gemm_tn_bytes(int64_t k, int m, int n) { return align_up((size_t)gemm_tn_splits(k, m, n) * (size_t)m * (size_t)n * sizeof(double), 256); }
 
 hipError_t launch_gemm_tn(const float *A, int64_t lda, const float *B, int64_t ldb, int64_t k, int m, int n, float *C, int64_t ldc,
-                          float *part, hipStream_t s) {
+                          double *part, hipStream_t s) {
     if (m <= 0 || n <= 0) return hipSuccess;
     GemmTnArgs g;
     g.A = A; g.B = B; g.part = part; g.lda = lda; g.ldb = ldb; g.k = k > 0 ? k : 0; g.m = m; g.n = n;

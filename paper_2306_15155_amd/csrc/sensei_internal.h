@@ -115,10 +115,10 @@ hipError_t launch_gemv2(const float *A, int64_t lda, int64_t n, int k, const flo
                         float *y2, hipStream_t s, bool a_sliced = false);
 
 // C[m x n] (row-major, ldc) = A^T . B with A stored k x m and B stored k x n; `part` holds gemm_tn_bytes(k, m, n) bytes.
-// The k range is cut into slabs whose partial products are added in slab order (deterministic).
+// The k range is cut into slabs whose partial products are kept and added in fp64, in slab order (deterministic).
 size_t gemm_tn_bytes(int64_t k, int m, int n);
 hipError_t launch_gemm_tn(const float *A, int64_t lda, const float *B, int64_t ldb, int64_t k, int m, int n, float *C, int64_t ldc,
-                          float *part, hipStream_t s);
+                          double *part, hipStream_t s);
 hipError_t launch_transpose(const float *W, int64_t ldw, int rows, int cols, float *Wt, int64_t ldt, hipStream_t s);
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }

@@ -187,3 +187,23 @@ def test_selector_pick_is_within_ten_percent_of_the_fastest(ctx, reddit_like, ki
     assert set(allowed) == set(oracle.select_rules(kind, f_in, f_out))
     ms = {cid: _time_ms(lambda: run(cid)) for cid in allowed}
     assert ms[pick] <= 1.10 * min(ms.values()) + 0.02, (pick, ms)
+
+
+def test_config2_gcn_backward_full_size(ctx, reddit_like):
+    """Training step of the Reddit-shaped layer 602 -> 256: sampled rows of dX and the whole dW against the oracle."""
+    from paper_2306_15155_amd import GCN_BWD_AGG, GCN_BWD_UPD
+    g, A = reddit_like
+    f_in, f_out = 602, 256
+    X, W = synth.uniform(7, 10, (g.n_cols, f_in)), synth.glorot(7, 100, f_in, f_out)
+    dY = synth.normal(7, 500, (g.n_rows, f_out), 0.0, 1.0)
+    rows = _sample_rows(g, 9, 500)
+    want_dx, want_dw = oracle.gcn_backward(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, dY, rows=rows, want_dw=True, omp=True)
+    r, c, _, _ = _norm(ctx, A)
+    sel = torch.from_numpy(rows.astype(np.int64)).to(DEV)
+    Xd, Wd, dYd = dev(X), dev(W), dev(dY)
+    for bwd in (GCN_BWD_AGG, GCN_BWD_UPD):
+        dX, dW = ctx.gcn_backward(A.s, A.s, r, c, Xd, Wd, dYd, bwd)  # the pattern is symmetric: it is its own transpose
+        assert_close(dX[sel], want_dx, what=f"dX bwd {bwd}")
+        assert_close(dW, want_dw, what=f"dW bwd {bwd}")
+    pick, est = ctx.select_gcn_backward(A.s, f_in, f_out)
+    assert pick == GCN_BWD_AGG and est[0] < est[1]  # f_out < f_in: aggregate the gradient at the narrow width
