@@ -145,6 +145,26 @@ int sensei_panels_tune_bytes(const sensei_csr *A, size_t *bytes);
 int sensei_panels_tune(sensei_ctx *ctx, const sensei_csr *A, void *scratch, size_t bytes, void *stream, int *n_panels_out,
                        int *min_width_out, float *ms_per_count);
 
+/* Backward of the GAT layer (training; chain rule on Eq. 5-6).  With Theta = X.W, t_ij = s_l[i] + s_r[j],
+ * e = LeakyReLU(t), alpha = row softmax(e), P = alpha.Theta, Y = act(P) and dP = dY (.) [Y > 0]:
+ *     dalpha_ij = <dP[i,:], Theta[j,:]>                         (g-SDDMM, Eq. 2 with a dot product)
+ *     de_ij = alpha_ij (dalpha_ij - sum_j' alpha_ij' dalpha_ij'),  dt_ij = de_ij * (t_ij > 0 ? 1 : slope)
+ *     ds_l[i] = sum_j dt_ij,  ds_r[j] = sum_i dt_ij
+ *     dTheta = alpha^T.dP + ds_l a_l^T + ds_r a_r^T,  da_l = Theta^T ds_l,  da_r = Theta^T ds_r
+ *     dW = X^T.dTheta,  dX = dTheta.W^T  (skipped when dX is NULL).
+ * Theta, the logits and the softmax statistics are recomputed from X, W, a_l, a_r (nothing is kept from the
+ * forward call).  At: the transposed pattern (A itself when symmetric); t_pos: nnz int32 (device), the place of
+ * each stored entry of A in At, from sensei_transpose_positions.  n_rows <= n_cols as in the forward.
+ *   sensei_transpose_positions: fills t_pos; synchronises `stream`; INVALID_ARGUMENT if At is not the transpose
+ *   of A (an entry of A has no counterpart).  Columns must be ascending within each row of At. */
+int sensei_transpose_positions(sensei_ctx *ctx, const sensei_csr *A, const sensei_csr *At, int32_t *t_pos, void *workspace,
+                               size_t ws_bytes, void *stream);
+int sensei_gat_backward_workspace(const sensei_csr *A, int f_in, int f_out, size_t *bytes);
+int sensei_gat_backward(sensei_ctx *ctx, const sensei_csr *A, const sensei_csr *At, const int32_t *t_pos, sensei_mat X, sensei_mat W,
+                        const float *a_l, const float *a_r, float neg_slope, const float *Y, int64_t ldy, sensei_mat dY, int activation,
+                        float *dX, int64_t lddx, float *dW, int64_t lddw, float *da_l, float *da_r, void *workspace, size_t ws_bytes,
+                        void *stream);
+
 /* ------------------------------------------------- primitives (steps of a layer) */
 
 /* Degrees of the stored pattern, which holds the self edges (case study GCN: D~ is the degree

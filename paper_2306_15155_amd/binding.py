@@ -30,7 +30,8 @@ EXPORTS = (
     "sensei_gcn_workspace", "sensei_gcn_layer", "sensei_gat_workspace", "sensei_gat_layer", "sensei_select_workspace",
     "sensei_select", "sensei_profile_enable", "sensei_profile_read", "sensei_panels_bytes", "sensei_panels_create",
     "sensei_panels_count", "sensei_panels_destroy", "sensei_panels_set_min_width", "sensei_panels_tune_bytes",
-    "sensei_panels_tune", "sensei_gcn_backward_workspace", "sensei_gcn_backward", "sensei_select_gcn_backward",
+    "sensei_panels_tune", "sensei_gcn_backward_workspace", "sensei_gcn_backward", "sensei_select_gcn_backward", "sensei_transpose_positions",
+    "sensei_gat_backward_workspace", "sensei_gat_backward",
 )
 
 
@@ -85,6 +86,10 @@ def lib():
         L.sensei_gcn_backward.argtypes = [vp, P(CsrStruct), P(CsrStruct), vp, vp, MatStruct, MatStruct, vp, i64, MatStruct, i32, vp, i64,
                                           vp, i64, vp, i64, i32, vp, sz, vp]
         L.sensei_select_gcn_backward.argtypes = [vp, P(CsrStruct), i32, i32, i32, i32, P(ctypes.c_int), P(f32)]
+        L.sensei_transpose_positions.argtypes = [vp, P(CsrStruct), P(CsrStruct), vp, vp, sz, vp]
+        L.sensei_gat_backward_workspace.argtypes = [P(CsrStruct), i32, i32, P(sz)]
+        L.sensei_gat_backward.argtypes = [vp, P(CsrStruct), P(CsrStruct), vp, MatStruct, MatStruct, vp, vp, f32, vp, i64, MatStruct, i32,
+                                          vp, i64, vp, i64, vp, vp, vp, sz, vp]
         L.sensei_gat_workspace.argtypes = [P(CsrStruct), i32, i32, i32, P(sz)]
         L.sensei_gat_layer.argtypes = [vp, P(CsrStruct), MatStruct, MatStruct, vp, vp, f32, vp, i64, i32, i32, vp, sz, vp]
         L.sensei_select_workspace.argtypes = [i32, P(CsrStruct), i32, i32, P(sz)]
@@ -328,6 +333,30 @@ class Context:
                                          mat_struct(dX).ld if dX is not None else 0, _ptr(dW), mat_struct(dW).ld, bwd_id, self.ws.ptr,
                                          self.ws.nbytes, _stream()), "sensei_gcn_backward")
         return dX, dW
+
+    def transpose_positions(self, A: CsrStruct, At: CsrStruct):
+        """int32 tensor: place of every stored entry of A in the transposed pattern At."""
+        pos = torch.empty(max(A.nnz, 1), dtype=torch.int32, device=self.device)
+        self.ws.ensure(self.sparse_workspace(A, 1) + 1024)
+        _check(lib().sensei_transpose_positions(self._h, ctypes.byref(A), ctypes.byref(At), _ptr(pos), self.ws.ptr, self.ws.nbytes, _stream()),
+               "sensei_transpose_positions")
+        return pos
+
+    def gat_backward(self, A: CsrStruct, At: CsrStruct, t_pos, X, W, a_l, a_r, dY, Y=None, neg_slope=0.2, activation=ACT_NONE, want_dx=True):
+        """Backward of gat_layer -> (dX or None, dW, da_l, da_r)."""
+        f_in, f_out = W.size(0), W.size(1)
+        dX = torch.empty((A.n_cols, f_in), dtype=torch.float32, device=self.device) if want_dx else None
+        dW = torch.empty((f_in, f_out), dtype=torch.float32, device=self.device)
+        dal = torch.empty(f_out, dtype=torch.float32, device=self.device)
+        dar = torch.empty(f_out, dtype=torch.float32, device=self.device)
+        need = ctypes.c_size_t()
+        _check(lib().sensei_gat_backward_workspace(ctypes.byref(A), f_in, f_out, ctypes.byref(need)), "sensei_gat_backward_workspace")
+        self.ws.ensure(need.value)
+        _check(lib().sensei_gat_backward(self._h, ctypes.byref(A), ctypes.byref(At), _ptr(t_pos), mat_struct(X), mat_struct(W), _ptr(a_l),
+                                         _ptr(a_r), neg_slope, _ptr(Y), mat_struct(Y).ld if Y is not None else 0, mat_struct(dY), activation,
+                                         _ptr(dX), mat_struct(dX).ld if dX is not None else 0, _ptr(dW), mat_struct(dW).ld, _ptr(dal),
+                                         _ptr(dar), self.ws.ptr, self.ws.nbytes, _stream()), "sensei_gat_backward")
+        return dX, dW, dal, dar
 
     def select_gcn_backward(self, A: CsrStruct, f_in, f_out, have_saved_u=False, want_dx=True):
         pick = ctypes.c_int()

@@ -373,6 +373,82 @@ int run_gat(const sensei_csr &A, const sensei_mat &X, const sensei_mat &W, const
     return SENSEI_OK;
 }
 
+// ---- backward of the GAT layer
+size_t gat_bwd_ws(const sensei_csr &A, int f_in, int f_out) {
+    const size_t nz = (size_t)(A.nnz > 0 ? A.nnz : 1), fo32 = pad32(f_out), fo4 = pad4(f_out), fi4 = pad4(f_in);
+    const int t = choose_chunk_nnz(A.nnz);
+    const size_t n_chunks = A.nnz <= 0 ? 1 : (size_t)((A.nnz + t - 1) / t);
+    size_t b = 2 * plan_bytes(A.nnz) + softmax_ws_bytes(A) + 512;
+    b += 2 * align_up((size_t)A.n_cols * sizeof(float), 256);        // s_l, s_r
+    b += align_up((size_t)A.n_cols * fo32 * sizeof(float), 256);     // Theta (slice-major)
+    b += align_up((size_t)A.n_rows * fo32 * sizeof(float), 256);     // dP (slice-major)
+    b += 4 * align_up(nz * sizeof(float), 256);                      // logits, dalpha / dt, alpha^T, dt^T
+    b += align_up((size_t)(A.n_rows + 1) * sizeof(float), 256);      // row dots
+    b += align_up(n_chunks * sizeof(float), 256);                    // carry of the row sums
+    b += 2 * align_up((size_t)(A.n_cols + 1) * sizeof(float), 256);  // ds_l, ds_r
+    b += align_up((size_t)A.n_cols * fo4 * sizeof(float), 256);      // dTheta
+    b += spmm_carry_bytes(A.nnz, (int)fo32);
+    b += align_up(fo4 * fi4 * sizeof(float), 256);                   // W^T
+    b += gemm_tn_bytes(A.n_cols, f_in, f_out) + theta_t_vec_bytes(A.n_cols, f_out);
+    return b;
+}
+
+int run_gat_backward(const sensei_csr &A, const sensei_csr &At, const int32_t *t_pos, const sensei_mat &X, const sensei_mat &W,
+                     const float *a_l, const float *a_r, float slope, const float *Y, int64_t ldy, const sensei_mat &dY, int act, float *dX,
+                     int64_t lddx, float *dW, int64_t lddw, float *da_l, float *da_r, void *ws, size_t ws_bytes, hipStream_t s) {
+    const int f_in = (int)X.cols, f_out = (int)W.cols;
+    const int fo32 = pad32(f_out), fo4 = pad4(f_out), fi4 = pad4(f_in);
+    const size_t nz = (size_t)(A.nnz > 0 ? A.nnz : 1);
+    Carver cv(ws, ws_bytes);
+    ChunkPlan plan = make_plan(A, cv), plan_t = make_plan(At, cv);
+    float2 *stats = cv.take<float2>((size_t)A.n_rows + 1);
+    float2 *carry_stats = cv.take<float2>((size_t)plan.n_chunks);
+    float *s_l = cv.take<float>((size_t)A.n_cols);
+    float *s_r = cv.take<float>((size_t)A.n_cols);
+    float *theta = cv.take<float>((size_t)A.n_cols * fo32);
+    float *T = cv.take<float>((size_t)A.n_rows * fo32);
+    float *logits = cv.take<float>(nz);
+    float *dt = cv.take<float>(nz);
+    float *alpha_t = cv.take<float>(nz);
+    float *dt_t = cv.take<float>(nz);
+    float *rowdot = cv.take<float>((size_t)A.n_rows + 1);
+    float *sum_carry = cv.take<float>((size_t)plan.n_chunks);
+    float *ds_l = cv.take<float>((size_t)A.n_cols + 1);
+    float *ds_r = cv.take<float>((size_t)A.n_cols + 1);
+    float *dTheta = cv.take<float>((size_t)A.n_cols * fo4);
+    float *carry = cv.take<float>(spmm_carry_bytes(A.nnz, fo32) / sizeof(float));
+    float *Wt = cv.take<float>((size_t)fo4 * fi4);
+    double *part = cv.take<double>(gemm_tn_bytes(A.n_cols, f_in, f_out) / sizeof(double));
+    double *part_a = cv.take<double>(theta_t_vec_bytes(A.n_cols, f_out) / sizeof(double));
+
+    SENSEI_TRY(launch_chunk_rows(A, plan, s));
+    SENSEI_TRY(launch_chunk_rows(At, plan_t, s));
+    // forward quantities: Theta (slice-major: the edge kernel gathers its rows), projections, logits, row statistics
+    SENSEI_TRY(launch_gemm(X.ptr, X.ld, W.ptr, W.ld, theta, fo32, A.n_cols, f_in, f_out, fo32, SENSEI_ACT_NONE, s, nullptr, nullptr, true));
+    SENSEI_TRY(launch_gemv2(theta, fo32, A.n_cols, f_out, a_l, a_r, s_l, s_r, s, true));
+    SENSEI_TRY(launch_attention_stats(A, s_l, s_r, slope, logits, nullptr, plan, stats, carry_stats, s));
+    // dP = dY (.) [Y > 0], slice-major
+    SENSEI_TRY(launch_to_slices(nullptr, dY.ptr, dY.ld, A.n_rows, f_out, T, s, act == SENSEI_ACT_RELU ? Y : nullptr, ldy));
+    // per stored entry: dalpha, then softmax and LeakyReLU backward; alpha and dt also in transposed order
+    SENSEI_TRY(launch_gat_dalpha(A, theta, T, f_out, logits, stats, dt, rowdot, plan, sum_carry, s));
+    SENSEI_TRY(launch_gat_dt(A, logits, dt, rowdot, stats, t_pos, slope, dt, alpha_t, dt_t, plan, s));
+    SENSEI_TRY(launch_row_sum(A, dt, ds_l, plan, sum_carry, s));
+    SENSEI_TRY(launch_row_sum(At, dt_t, ds_r, plan_t, sum_carry, s));
+    // dTheta = alpha^T.dP + ds_l a_l^T + ds_r a_r^T
+    sensei_csr Aw = At;
+    Aw.val = alpha_t;
+    SENSEI_TRY(spmm_any(Aw, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, T, fo32, f_out, dTheta, fo4, f_out, SENSEI_ACT_NONE, plan_t, carry, s, nullptr,
+                        false, nullptr, true));
+    SENSEI_TRY(launch_rank1_add(dTheta, fo4, A.n_cols, f_out, ds_l, A.n_rows, ds_r, a_l, a_r, s));
+    SENSEI_TRY(launch_theta_t_vec(theta, A.n_cols, f_out, ds_l, A.n_rows, ds_r, da_l, da_r, part_a, s));
+    SENSEI_TRY(launch_gemm_tn(X.ptr, X.ld, dTheta, fo4, A.n_cols, f_in, f_out, dW, lddw, part, s));
+    if (dX) {
+        SENSEI_TRY(launch_transpose(W.ptr, W.ld, f_in, f_out, Wt, fi4, s));
+        SENSEI_TRY(launch_gemm(dTheta, fo4, Wt, fi4, dX, lddx, A.n_cols, f_out, f_in, f_in, SENSEI_ACT_NONE, s));
+    }
+    return SENSEI_OK;
+}
+
 // ------------------------------------------------------------------ cost model
 
 struct Features {
@@ -942,6 +1018,58 @@ int sensei_gcn_backward(sensei_ctx *ctx, const sensei_csr *A, const sensei_csr *
     if (ws_bytes < gcn_bwd_ws(*A, (int)X.cols, (int)W.cols, bwd_id)) return SENSEI_WORKSPACE_TOO_SMALL;
     return run_gcn_backward(*A, *At, r, c, X, W, Y, ldy, dY, activation, U_saved, ldu, dX, lddx, dW, lddw, bwd_id, workspace, ws_bytes,
                             as_stream(stream));
+}
+
+int sensei_transpose_positions(sensei_ctx *ctx, const sensei_csr *A, const sensei_csr *At, int32_t *t_pos, void *workspace,
+                               size_t ws_bytes, void *stream) {
+    if (!ctx || !csr_ok(A, false) || !csr_ok(At, false) || (!t_pos && A->nnz > 0) || !workspace) return SENSEI_INVALID_ARGUMENT;
+    if (At->n_rows != A->n_cols || At->n_cols != A->n_rows || At->nnz != A->nnz) return SENSEI_INVALID_ARGUMENT;
+    if (ws_bytes < plan_bytes(A->nnz) + 512) return SENSEI_WORKSPACE_TOO_SMALL;
+    if (A->nnz == 0) return SENSEI_OK;
+    hipStream_t s = as_stream(stream);
+    Carver cv(workspace, ws_bytes);
+    ChunkPlan plan = make_plan(*A, cv);
+    int32_t *miss = cv.take<int32_t>(1);
+    int32_t miss_host = 0;
+    if (launch_chunk_rows(*A, plan, s) != hipSuccess ||
+        launch_transpose_pos(*A, *At, plan, t_pos, miss, s) != hipSuccess ||
+        hipMemcpyAsync(&miss_host, miss, sizeof(int32_t), hipMemcpyDeviceToHost, s) != hipSuccess || hipStreamSynchronize(s) != hipSuccess)
+        return SENSEI_HIP_ERROR;
+    return miss_host == 0 ? SENSEI_OK : SENSEI_INVALID_ARGUMENT;
+}
+
+int sensei_gat_backward_workspace(const sensei_csr *A, int f_in, int f_out, size_t *bytes) {
+    if (!csr_ok(A, false) || f_in <= 0 || f_out <= 0 || !bytes) return SENSEI_INVALID_ARGUMENT;
+    *bytes = gat_bwd_ws(*A, f_in, f_out);
+    return SENSEI_OK;
+}
+
+int sensei_gat_backward(sensei_ctx *ctx, const sensei_csr *A, const sensei_csr *At, const int32_t *t_pos, sensei_mat X, sensei_mat W,
+                        const float *a_l, const float *a_r, float neg_slope, const float *Y, int64_t ldy, sensei_mat dY, int activation,
+                        float *dX, int64_t lddx, float *dW, int64_t lddw, float *da_l, float *da_r, void *workspace, size_t ws_bytes,
+                        void *stream) {
+    if (!ctx || !csr_ok(A, false) || !csr_ok(At, false) || !mat_ok(X) || !mat_ok(W) || !mat_ok(dY)) return SENSEI_INVALID_ARGUMENT;
+    if (At->n_rows != A->n_cols || At->n_cols != A->n_rows || At->nnz != A->nnz || A->n_rows > A->n_cols) return SENSEI_INVALID_ARGUMENT;
+    if (activation != SENSEI_ACT_NONE && activation != SENSEI_ACT_RELU) return SENSEI_INVALID_ARGUMENT;
+    if (X.rows != A->n_cols || X.cols != W.rows || X.cols <= 0 || W.cols <= 0) return SENSEI_INVALID_ARGUMENT;
+    if (X.cols > (1 << 20) || W.cols > (1 << 20)) return SENSEI_INVALID_ARGUMENT;
+    if (dY.rows != A->n_rows || dY.cols != W.cols) return SENSEI_INVALID_ARGUMENT;
+    if ((!X.ptr && A->n_cols > 0) || !W.ptr || (!dY.ptr && A->n_rows > 0) || !dW || !da_l || !da_r || !a_l || !a_r || !workspace)
+        return SENSEI_INVALID_ARGUMENT;
+    if (!t_pos && A->nnz > 0) return SENSEI_INVALID_ARGUMENT;
+    if (lddw < W.cols || (dX && lddx < X.cols)) return SENSEI_INVALID_ARGUMENT;
+    if (activation == SENSEI_ACT_RELU && ((!Y && A->n_rows > 0) || ldy < W.cols)) return SENSEI_INVALID_ARGUMENT;
+    const size_t dwb = mat_bytes(dW, W.rows, W.cols, lddw), dxb = dX ? mat_bytes(dX, A->n_cols, X.cols, lddx) : 0;
+    const size_t xb = mat_bytes(X.ptr, X.rows, X.cols, X.ld), wb = mat_bytes(W.ptr, W.rows, W.cols, W.ld),
+                 dyb = mat_bytes(dY.ptr, dY.rows, dY.cols, dY.ld);
+    if (overlap(dW, dwb, workspace, ws_bytes) || overlap(dW, dwb, X.ptr, xb) || overlap(dW, dwb, W.ptr, wb) || overlap(dW, dwb, dY.ptr, dyb))
+        return SENSEI_INVALID_ARGUMENT;
+    if (dX && (overlap(dX, dxb, workspace, ws_bytes) || overlap(dX, dxb, X.ptr, xb) || overlap(dX, dxb, W.ptr, wb) ||
+               overlap(dX, dxb, dY.ptr, dyb) || overlap(dX, dxb, dW, dwb)))
+        return SENSEI_INVALID_ARGUMENT;
+    if (ws_bytes < gat_bwd_ws(*A, (int)X.cols, (int)W.cols)) return SENSEI_WORKSPACE_TOO_SMALL;
+    return run_gat_backward(*A, *At, t_pos, X, W, a_l, a_r, neg_slope, Y, ldy, dY, activation, dX, lddx, dW, lddw, da_l, da_r, workspace,
+                            ws_bytes, as_stream(stream));
 }
 
 int sensei_gat_workspace(const sensei_csr *A, int f_in, int f_out, int comp_id, size_t *bytes) {

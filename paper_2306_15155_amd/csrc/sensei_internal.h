@@ -104,6 +104,24 @@ hipError_t launch_attention_stats(const sensei_csr &A, const float *s_l, const f
                                   const int32_t *dst_index, const ChunkPlan &p, float2 *stats, float2 *carry_stats, hipStream_t s);
 size_t softmax_ws_bytes(const sensei_csr &A);
 
+// ---- backward of the attention layer
+// out[i] = sum of val over row i; carry: n_chunks floats
+hipError_t launch_row_sum(const sensei_csr &A, const float *val, float *out, const ChunkPlan &p, float *carry, hipStream_t s);
+// dalpha[k] = <dP[i,:], Theta[j,:]> per stored entry, rowdot[i] = sum_j alpha_ij dalpha_ij; theta, dP slice-major
+hipError_t launch_gat_dalpha(const sensei_csr &A, const float *theta, const float *dP, int f, const float *logits, const float2 *mz,
+                             float *dalpha, float *rowdot, const ChunkPlan &p, float *carry, hipStream_t s);
+// dt[k] = alpha (dalpha - rowdot_i) LeakyReLU'(e); dt may be dalpha; alpha_t / dt_t: the same values at t_pos[k]
+hipError_t launch_gat_dt(const sensei_csr &A, const float *logits, const float *dalpha, const float *rowdot, const float2 *mz,
+                         const int32_t *t_pos, float slope, float *dt, float *alpha_t, float *dt_t, const ChunkPlan &p, hipStream_t s);
+hipError_t launch_rank1_add(float *D, int64_t ldd, int64_t n, int f, const float *ds_l, int64_t n_l, const float *ds_r, const float *a_l,
+                            const float *a_r, hipStream_t s);
+// out_l = Theta^T v_l (v_l counted for the first n_l rows), out_r = Theta^T v_r; Theta slice-major n x pad32(f); sums in fp64
+size_t theta_t_vec_bytes(int64_t n, int f);
+hipError_t launch_theta_t_vec(const float *theta_sliced, int64_t n, int f, const float *v_l, int64_t n_l, const float *v_r, float *out_l,
+                              float *out_r, double *part, hipStream_t s);
+// pos[k] = place of entry k of A in At (binary search in the ascending columns of At); *miss (cleared first) counts entries not found
+hipError_t launch_transpose_pos(const sensei_csr &A, const sensei_csr &At, const ChunkPlan &p, int32_t *pos, int32_t *miss, hipStream_t s);
+
 // ---- dense
 // Y[0:n, 0:m_store) = act(row_scale[i] * (A[n x k] . W[k x m])); columns m..m_store are written as act(0);
 // row_scale may be null (no scaling).

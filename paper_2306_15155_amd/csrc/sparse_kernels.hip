@@ -785,6 +785,230 @@ __global__ __launch_bounds__(kBlock) void k_panel_scatter(NnzArgs a, int n_panel
 
 inline unsigned blocks_for(long long n, int per_block) { return (unsigned)((n + per_block - 1) / per_block); }
 
+// ------------------------------------------------------- backward of the attention layer
+
+// Row walk shared by the row reductions below: one wavefront per chunk; `piece(i, lo, hi)` handles the stored
+// entries [lo, hi) of row i and returns this lane's partial sum, `done(i, sum, cont)` receives the wavefront-wide
+// sum of a row piece (cont: the row began in an earlier chunk, the sum goes to the chunk's carry slot).
+template <class Piece>
+__device__ __forceinline__ void reduce_rows(const NnzArgs &a, int chunk, int lane, float *__restrict__ out, float *__restrict__ carry,
+                                            Piece piece) {
+    const long long lo_ll = (long long)chunk * a.chunk_nnz;
+    const int lo = (int)lo_ll;
+    const int hi = (int)((lo_ll + a.chunk_nnz < (long long)a.nnz) ? lo_ll + a.chunk_nnz : (long long)a.nnz);
+    const int i0 = a.chunk_row[chunk], i1 = a.chunk_row[chunk + 1];
+    bool cont = (a.nnz > 0) && (a.row_ptr[i0] > lo);
+    int i = __builtin_amdgcn_readfirstlane(cont ? i0 - 1 : i0);
+    int re = __builtin_amdgcn_readfirstlane((i < a.n_rows) ? a.row_ptr[i + 1] : 0x7fffffff);
+    float acc = 0.f;
+    auto finish_row = [&]() {
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) acc += __shfl_xor(acc, off, 64);
+        if (lane == 0) {
+            if (cont) carry[chunk] = acc;
+            else out[i] = acc;
+        }
+        acc = 0.f;
+    };
+    int pos = lo;
+    while (pos < hi) {
+        while (re <= pos) {
+            finish_row();
+            cont = false;
+            i = __builtin_amdgcn_readfirstlane(i + 1);
+            re = __builtin_amdgcn_readfirstlane(a.row_ptr[i + 1]);
+        }
+        const int seg_hi = re < hi ? re : hi;
+        acc += piece(i, pos, seg_hi);
+        pos = seg_hi;
+    }
+    while (i < i1) {
+        finish_row();
+        if (re <= hi) {
+            cont = false;
+            i = __builtin_amdgcn_readfirstlane(i + 1);
+            re = __builtin_amdgcn_readfirstlane((i < a.n_rows) ? a.row_ptr[i + 1] : 0x7fffffff);
+        } else {
+            break;
+        }
+    }
+}
+
+// adds the carried pieces of rows that span several chunks, in chunk order
+__global__ void k_sum_fixup(NnzArgs a, float *__restrict__ out, const float *__restrict__ carry) {
+    const int c = 1 + blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= a.n_chunks) return;
+    const long long lo = (long long)c * a.chunk_nnz;
+    const int i0 = a.chunk_row[c];
+    if ((long long)a.row_ptr[i0] <= lo) return;
+    const int i = i0 - 1;
+    if ((long long)a.row_ptr[i] < lo - a.chunk_nnz) return;
+    const int c_last = (a.row_ptr[i + 1] - 1) / a.chunk_nnz;
+    float s = out[i];
+    for (int cc = c; cc <= c_last; ++cc) s += carry[cc];
+    out[i] = s;
+}
+
+// out[i] = sum of val over the stored entries of row i
+__global__ __launch_bounds__(kBlock) void k_row_sum(NnzArgs a, const float *__restrict__ val, float *__restrict__ out, float *__restrict__ carry) {
+    const int chunk = wave_chunk();
+    if (chunk >= a.n_chunks) return;
+    const int lane = threadIdx.x & 63;
+    reduce_rows(a, chunk, lane, out, carry, [&](int, int lo, int hi) {
+        float s = 0.f;
+        for (int k = lo + lane; k < hi; k += 64) s += val[k];
+        return s;
+    });
+}
+
+struct GatBwdArgs {
+    NnzArgs n;
+    const float *theta, *dP;  // slice-major (tiles of 32 columns): Theta over the source nodes, dP over the destinations
+    const float *logits;      // e_ij per stored entry
+    const float2 *mz;         // per row: (max logit, sum of exp(logit - max))
+    float *dalpha;            // out, per stored entry: <dP_i, Theta_j>
+    float *rowdot, *carry;    // out, per row: sum_j alpha_ij dalpha_ij (+ per-chunk carry slots)
+    long long theta_tile, dp_tile;  // floats from one tile to the next
+    int n_tiles;
+};
+
+// dalpha_ij = <dP[i,:], Theta[j,:]> for every stored entry (the general g-SDDMM of Eq. 2 with a dot product as the
+// inner operator) together with the row sums sum_j alpha_ij dalpha_ij that the softmax backward needs.  Eight lanes
+// take one neighbour: each reads 16 bytes of every 128-byte slice of Theta_j and of dP_i, eight neighbours per step.
+__global__ __launch_bounds__(kBlock) void k_gat_dalpha(GatBwdArgs a) {
+    const int chunk = wave_chunk();
+    if (chunk >= a.n.n_chunks) return;
+    const int lane = threadIdx.x & 63;
+    const int g = lane >> 3, sub = lane & 7;
+    reduce_rows(a.n, chunk, lane, a.rowdot, a.carry, [&](int i, int lo, int hi) {
+        const float2 st = a.mz[i];
+        const float m = st.x, iz = inv_z(st.y);
+        const float *dp = a.dP + (size_t)i * 32 + sub * 4;
+        float s = 0.f;
+        for (int k0 = lo; k0 < hi; k0 += 8) {
+            const int k = k0 + g;
+            const bool ok = k < hi;
+            const int j = a.n.col_idx[ok ? k : lo];
+            const float *th = a.theta + (size_t)j * 32 + sub * 4;
+            float d = 0.f;
+#pragma unroll 4
+            for (int t = 0; t < a.n_tiles; ++t) {
+                const float4 b = *reinterpret_cast<const float4 *>(th + (size_t)t * a.theta_tile);
+                const float4 p = *reinterpret_cast<const float4 *>(dp + (size_t)t * a.dp_tile);
+                d = fmaf(b.x, p.x, d); d = fmaf(b.y, p.y, d); d = fmaf(b.z, p.z, d); d = fmaf(b.w, p.w, d);
+            }
+            d += __shfl_xor(d, 1, 64);
+            d += __shfl_xor(d, 2, 64);
+            d += __shfl_xor(d, 4, 64);
+            if (ok && sub == 0) {
+                a.dalpha[k] = d;
+                s = fmaf(expf(a.logits[k] - m) * iz, d, s);
+            }
+        }
+        return s;
+    });
+}
+
+struct GatDtArgs {
+    NnzArgs n;
+    const float *logits, *dalpha, *rowdot;
+    const float2 *mz;
+    const int32_t *t_pos;   // place of entry k in the transposed pattern
+    float *dt, *alpha_t, *dt_t;
+    float slope;
+};
+
+// Softmax and LeakyReLU backward per stored entry: alpha = exp(e - m_i) / z_i, de = alpha (dalpha - rowdot_i),
+// dt = de * (e > 0 ? 1 : slope) (e > 0 exactly when the pre-activation is).  dt is kept in row order (for the row
+// sums ds_l) and, like alpha, written at its place in the transposed pattern (for ds_r and alpha^T dP).
+__global__ __launch_bounds__(kBlock) void k_gat_dt(GatDtArgs a) {
+    const int chunk = wave_chunk();
+    if (chunk >= a.n.n_chunks) return;
+    struct RowData { float m, iz, dot; };
+    walk_chunk(a.n, chunk, threadIdx.x & 63,
+               [&](int i) { const float2 st = a.mz[i]; return RowData{st.x, inv_z(st.y), a.rowdot[i]}; },
+               [&](int k, const RowData &rd) {
+                   const float e = a.logits[k];
+                   const float al = expf(e - rd.m) * rd.iz;
+                   const float dt = al * (a.dalpha[k] - rd.dot) * (e > 0.f ? 1.f : a.slope);
+                   const int p = a.t_pos[k];
+                   a.dt[k] = dt;
+                   a.alpha_t[p] = al;
+                   a.dt_t[p] = dt;
+               });
+}
+
+// dTheta[j, :] += ds_l[j] a_l + ds_r[j] a_r (ds_l counts only for j < n_l)
+__global__ void k_rank1_add(float *__restrict__ D, long long ldd, long long n, int f, const float *__restrict__ ds_l, long long n_l,
+                            const float *__restrict__ ds_r, const float *__restrict__ a_l, const float *__restrict__ a_r) {
+    const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= n * f) return;
+    const long long j = t / f;
+    const int q = (int)(t % f);
+    const float l = j < n_l ? ds_l[j] : 0.f;
+    D[j * ldd + q] += l * a_l[q] + ds_r[j] * a_r[q];
+}
+
+// part[slab][0][q] = sum_j Theta[j, q] v_l[j], part[slab][1][q] = sum_j Theta[j, q] v_r[j] over the rows of the slab,
+// Theta slice-major, sums in fp64.  One workgroup per (tile, slab): 32 columns x 8 rows per pass.
+__global__ __launch_bounds__(256) void k_theta_t_vec(const float *__restrict__ theta, long long n, int f_pad, const float *__restrict__ v_l,
+                                                     long long n_l, const float *__restrict__ v_r, int rows_per_slab,
+                                                     double *__restrict__ part) {
+    __shared__ double red[2][8][32];
+    const int tile = blockIdx.x, slab = blockIdx.y;
+    const int c = threadIdx.x & 31, rr = threadIdx.x >> 5;
+    const long long j_lo = (long long)slab * rows_per_slab;
+    const long long j_hi = (j_lo + rows_per_slab < n) ? j_lo + rows_per_slab : n;
+    const float *th = theta + (size_t)tile * (size_t)n * 32;
+    double sl = 0.0, sr = 0.0;
+    for (long long j = j_lo + rr; j < j_hi; j += 8) {
+        const double x = (double)th[j * 32 + c];
+        if (j < n_l) sl += x * (double)v_l[j];
+        sr += x * (double)v_r[j];
+    }
+    red[0][rr][c] = sl;
+    red[1][rr][c] = sr;
+    __syncthreads();
+    if (rr < 2) {
+        double s = 0.0;
+        for (int y = 0; y < 8; ++y) s += red[rr][y][c];
+        part[((size_t)slab * 2 + rr) * f_pad + tile * 32 + c] = s;
+    }
+}
+
+__global__ void k_sum_slabs(const double *__restrict__ part, int slabs, int f_pad, int f, float *__restrict__ out_l, float *__restrict__ out_r) {
+    const int q = blockIdx.x * blockDim.x + threadIdx.x;
+    if (q >= f) return;
+    double l = 0.0, r = 0.0;
+    for (int s = 0; s < slabs; ++s) {
+        l += part[((size_t)s * 2 + 0) * f_pad + q];
+        r += part[((size_t)s * 2 + 1) * f_pad + q];
+    }
+    out_l[q] = (float)l;
+    out_r[q] = (float)r;
+}
+
+// pos[k] = index in the transposed pattern of the entry (i, j) stored at k: the place of i among the ascending
+// columns of row j of At.  miss counts entries that are not there (At is not the transpose of A).
+__global__ __launch_bounds__(kBlock) void k_transpose_pos(NnzArgs a, const int32_t *__restrict__ t_row_ptr, const int32_t *__restrict__ t_col_idx,
+                                                           int32_t *__restrict__ pos, int32_t *__restrict__ miss) {
+    const int chunk = wave_chunk();
+    if (chunk >= a.n_chunks) return;
+    walk_chunk(a, chunk, threadIdx.x & 63, [&](int i) { return i; },
+               [&](int k, int i) {
+                   const int j = a.col_idx[k];
+                   int lo = t_row_ptr[j], hi = t_row_ptr[j + 1];
+                   const int end = hi;
+                   while (lo < hi) {
+                       const int mid = (int)(((long long)lo + hi) >> 1);
+                       if (t_col_idx[mid] < i) lo = mid + 1; else hi = mid;
+                   }
+                   const bool found = lo < end && t_col_idx[lo] == i;
+                   pos[k] = found ? lo : 0;
+                   if (!found) atomicAdd(miss, 1);
+               });
+}
+
 NnzArgs nnz_args(const sensei_csr &A, const ChunkPlan &p) {
     NnzArgs n;
     n.row_ptr = A.row_ptr; n.col_idx = A.col_idx; n.chunk_row = p.chunk_row;
@@ -963,6 +1187,74 @@ hipError_t launch_attention_stats(const sensei_csr &A, const float *s_l, const f
     a.logits = logits; a.dst_index = dst_index;
     hipLaunchKernelGGL((k_softmax_stats<false>), dim3(blocks_for(p.n_chunks, kWavesPerBlock)), dim3(kBlock), 0, s, a);
     if (p.n_chunks > 1) hipLaunchKernelGGL(k_softmax_fixup, dim3(blocks_for(p.n_chunks - 1, kBlock)), dim3(kBlock), 0, s, a);
+    return hipGetLastError();
+}
+
+
+// ------------------------------------------------------------ backward of the attention layer (host side)
+
+hipError_t launch_row_sum(const sensei_csr &A, const float *val, float *out, const ChunkPlan &p, float *carry, hipStream_t s) {
+    const NnzArgs n = nnz_args(A, p);
+    hipLaunchKernelGGL(k_row_sum, dim3(blocks_for(p.n_chunks, kWavesPerBlock)), dim3(kBlock), 0, s, n, val, out, carry);
+    if (p.n_chunks > 1) hipLaunchKernelGGL(k_sum_fixup, dim3(blocks_for(p.n_chunks - 1, kBlock)), dim3(kBlock), 0, s, n, out, carry);
+    return hipGetLastError();
+}
+
+hipError_t launch_gat_dalpha(const sensei_csr &A, const float *theta, const float *dP, int f, const float *logits, const float2 *mz,
+                             float *dalpha, float *rowdot, const ChunkPlan &p, float *carry, hipStream_t s) {
+    GatBwdArgs a;
+    a.n = nnz_args(A, p);
+    a.theta = theta; a.dP = dP; a.logits = logits; a.mz = mz; a.dalpha = dalpha; a.rowdot = rowdot; a.carry = carry;
+    a.theta_tile = (long long)(A.n_cols > 0 ? A.n_cols : 1) * 32;
+    a.dp_tile = (long long)(A.n_rows > 0 ? A.n_rows : 1) * 32;
+    a.n_tiles = (f + 31) / 32;
+    hipLaunchKernelGGL(k_gat_dalpha, dim3(blocks_for(p.n_chunks, kWavesPerBlock)), dim3(kBlock), 0, s, a);
+    if (p.n_chunks > 1) hipLaunchKernelGGL(k_sum_fixup, dim3(blocks_for(p.n_chunks - 1, kBlock)), dim3(kBlock), 0, s, a.n, rowdot, carry);
+    return hipGetLastError();
+}
+
+hipError_t launch_gat_dt(const sensei_csr &A, const float *logits, const float *dalpha, const float *rowdot, const float2 *mz,
+                         const int32_t *t_pos, float slope, float *dt, float *alpha_t, float *dt_t, const ChunkPlan &p, hipStream_t s) {
+    if (A.nnz <= 0) return hipSuccess;
+    GatDtArgs a;
+    a.n = nnz_args(A, p);
+    a.logits = logits; a.dalpha = dalpha; a.rowdot = rowdot; a.mz = mz; a.t_pos = t_pos; a.dt = dt; a.alpha_t = alpha_t; a.dt_t = dt_t;
+    a.slope = slope;
+    hipLaunchKernelGGL(k_gat_dt, dim3(blocks_for(p.n_chunks, kWavesPerBlock)), dim3(kBlock), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_rank1_add(float *D, int64_t ldd, int64_t n, int f, const float *ds_l, int64_t n_l, const float *ds_r, const float *a_l,
+                            const float *a_r, hipStream_t s) {
+    if (n <= 0 || f <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_rank1_add, dim3(blocks_for(n * f, kBlock)), dim3(kBlock), 0, s, D, (long long)ldd, (long long)n, f, ds_l, (long long)n_l,
+                       ds_r, a_l, a_r);
+    return hipGetLastError();
+}
+
+static int theta_t_slabs(int64_t n) {
+    const long long s = (n + 4095) / 4096;
+    return (int)(s < 1 ? 1 : s > 256 ? 256 : s);
+}
+
+size_t theta_t_vec_bytes(int64_t n, int f) { return align_up((size_t)theta_t_slabs(n) * 2 * (size_t)pad32(f) * sizeof(double), 256); }
+
+hipError_t launch_theta_t_vec(const float *theta_sliced, int64_t n, int f, const float *v_l, int64_t n_l, const float *v_r, float *out_l,
+                              float *out_r, double *part, hipStream_t s) {
+    if (f <= 0) return hipSuccess;
+    const int slabs = theta_t_slabs(n), f_pad = pad32(f);
+    const int rows_per_slab = (int)((((n > 0 ? n : 1) + slabs - 1) / slabs + 7) / 8 * 8);
+    hipLaunchKernelGGL(k_theta_t_vec, dim3((unsigned)(f_pad / 32), (unsigned)slabs), dim3(256), 0, s, theta_sliced, (long long)n, f_pad, v_l,
+                       (long long)n_l, v_r, rows_per_slab, part);
+    hipLaunchKernelGGL(k_sum_slabs, dim3(blocks_for(f, 256)), dim3(256), 0, s, part, slabs, f_pad, f, out_l, out_r);
+    return hipGetLastError();
+}
+
+hipError_t launch_transpose_pos(const sensei_csr &A, const sensei_csr &At, const ChunkPlan &p, int32_t *pos, int32_t *miss, hipStream_t s) {
+    hipLaunchKernelGGL(k_fill_i32, dim3(1), dim3(64), 0, s, miss, 1LL, 0);  // a fill kernel, not a memset: safe under stream capture too
+    if (A.nnz <= 0) return hipGetLastError();
+    hipLaunchKernelGGL(k_transpose_pos, dim3(blocks_for(p.n_chunks, kWavesPerBlock)), dim3(kBlock), 0, s, nnz_args(A, p), At.row_ptr, At.col_idx,
+                       pos, miss);
     return hipGetLastError();
 }
 
