@@ -280,6 +280,21 @@ def main():
             bwd[tag(i)] = t
             del dYt
         detail["gcn_backward_ms"] = bwd
+        gat_bwd = {}
+        for i, L in enumerate(layers):
+            if L["kind"] != "gat":
+                continue
+            tp = time.perf_counter()
+            t_pos = ctx.transpose_positions(A, A)
+            torch.cuda.synchronize()
+            pos_ms = (time.perf_counter() - tp) * 1e3
+            dYt = torch.randn((N, L["f_out"]), device=dev)
+            Ymask = outs[i] if L["act"] else None
+            gat_bwd[tag(i)] = {"ms": round(time_fn(lambda: ctx.gat_backward(A, A, t_pos, src_of(i), Wd[i], attd[i][0], attd[i][1], dYt, Y=Ymask,
+                                                                            activation=L["act"]), 2), 4),
+                               "transpose_positions_setup_ms": round(pos_ms, 3)}
+            del dYt, t_pos
+        detail["gat_backward_ms"] = gat_bwd
 
     # ---- ceiling of the neighbour gather: the same SpMM kernel (value-less, F = 256) on a synthetic pattern whose
     # columns span only 8192 rows of the gathered matrix, so every 128-byte feature slice (1 MB) stays in one L2.

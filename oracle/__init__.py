@@ -193,10 +193,11 @@ def gat_layer(n_rows, n_cols, row_ptr, col_idx, X, W, a_l, a_r, slope=0.2, act=0
     return Y
 
 
-def gcn_backward(n_rows, n_cols, row_ptr, col_idx, X, W, dY, Y=None, act=0, rows=None, want_dw=True, omp=False):
+def gcn_backward(n_rows, n_cols, row_ptr, col_idx, X, W, dY, Y=None, act=0, rows=None, want_dw=True, omp=False, with_dz=False):
     """Gradient of sum(dY * Y) for the GCN layer (chain rule on Eq. 3) -> (dX, dW).
 
-    ``Y`` (the fp32 forward output) supplies the ReLU mask when ``act`` == 1; ``rows`` selects rows of dX."""
+    ``Y`` (the fp32 forward output) supplies the ReLU mask when ``act`` == 1; ``rows`` selects rows of dX;
+    ``with_dz`` appends dZ = d(X W) (n_cols x F_out) to the result."""
     row_ptr, col_idx, X, W, dY = _i32(row_ptr), _i32(col_idx), _f32(X), _f32(W), _f32(dY)
     F_in, F_out = W.shape
     assert X.shape == (n_cols, F_in) and dY.shape == (n_rows, F_out)
@@ -207,17 +208,19 @@ def gcn_backward(n_rows, n_cols, row_ptr, col_idx, X, W, dY, Y=None, act=0, rows
     n_out = n_cols if sel is None else sel.size
     dX = np.empty((n_out, F_in), dtype=np.float64)
     dW = np.empty((F_in, F_out), dtype=np.float64) if (want_dw or sel is None) else None
+    dZ = np.empty((n_cols, F_out), dtype=np.float64) if (with_dz and dW is not None) else None
     rc = _lib(omp).orc_gcn_backward(I32(n_rows), I32(n_cols), _p(row_ptr), _p(col_idx), _p(X), I64(F_in), I32(F_in), _p(W), I64(F_out),
                                    I32(F_out), _p(Y) if act == 1 else None, I64(F_out), _p(dY), I64(F_out), ctypes.c_int(act),
                                    None if sel is None else _p(sel), I32(0 if sel is None else sel.size),
-                                   ctypes.c_int(1 if dW is not None else 0), _p(dX), None if dW is None else _p(dW))
+                                   ctypes.c_int(1 if dW is not None else 0), _p(dX), None if dW is None else _p(dW),
+                                   None if dZ is None else _p(dZ))
     if rc != 0:
         raise RuntimeError(f"oracle gcn_backward failed ({rc})")
-    return dX, dW
+    return (dX, dW, dZ) if with_dz else (dX, dW)
 
 
-def gat_backward(n_rows, n_cols, row_ptr, col_idx, X, W, a_l, a_r, dY, Y=None, slope=0.2, act=0, omp=False):
-    """Gradient of sum(dY * Y) for the GAT layer (chain rule on Eq. 5 / 6) -> (dX, dW, da_l, da_r)."""
+def gat_backward(n_rows, n_cols, row_ptr, col_idx, X, W, a_l, a_r, dY, Y=None, slope=0.2, act=0, omp=False, with_dtheta=False):
+    """Gradient of sum(dY * Y) for the GAT layer (chain rule on Eq. 5 / 6) -> (dX, dW, da_l, da_r[, dTheta])."""
     row_ptr, col_idx, X, W, a_l, a_r, dY = _i32(row_ptr), _i32(col_idx), _f32(X), _f32(W), _f32(a_l), _f32(a_r), _f32(dY)
     F_in, F_out = W.shape
     assert X.shape == (n_cols, F_in) and dY.shape == (n_rows, F_out)
@@ -227,12 +230,13 @@ def gat_backward(n_rows, n_cols, row_ptr, col_idx, X, W, a_l, a_r, dY, Y=None, s
     dX = np.empty((n_cols, F_in), dtype=np.float64)
     dW = np.empty((F_in, F_out), dtype=np.float64)
     dal, dar = np.empty(F_out, dtype=np.float64), np.empty(F_out, dtype=np.float64)
+    dTh = np.empty((n_cols, F_out), dtype=np.float64) if with_dtheta else None
     rc = _lib(omp).orc_gat_backward(I32(n_rows), I32(n_cols), _p(row_ptr), _p(col_idx), _p(X), I64(F_in), I32(F_in), _p(W), I64(F_out),
                                    I32(F_out), _p(a_l), _p(a_r), DBL(slope), _p(Y) if act == 1 else None, I64(F_out), _p(dY),
-                                   I64(F_out), ctypes.c_int(act), _p(dX), _p(dW), _p(dal), _p(dar))
+                                   I64(F_out), ctypes.c_int(act), _p(dX), _p(dW), _p(dal), _p(dar), None if dTh is None else _p(dTh))
     if rc != 0:
         raise RuntimeError(f"oracle gat_backward failed ({rc})")
-    return dX, dW, dal, dar
+    return (dX, dW, dal, dar, dTh) if with_dtheta else (dX, dW, dal, dar)
 
 
 # ------------------------------------------------------------- re-associations

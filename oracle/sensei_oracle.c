@@ -382,11 +382,13 @@ static int orc_transpose(int32_t n_rows, int32_t n_cols, const int32_t *row_ptr,
  *   dW = X^T dZ ,  dX = dZ W^T.
  * Y may be NULL when act == 0.  dX: n_cols x F_in, dW: F_in x F_out (fp64).
  * sel / n_sel: when sel != NULL only the rows sel[0..n_sel) of dX are computed
- * (dX is n_sel x F_in) and dW is not touched unless want_dw != 0. */
+ * (dX is n_sel x F_in) and dW is not touched unless want_dw != 0.  dZ_out (optional,
+ * n_cols x F_out, needs the full dZ: sel == NULL or want_dw) receives dZ, whose products with X are the
+ * terms of the reduction over nodes in dW. */
 int orc_gcn_backward(int32_t n_rows, int32_t n_cols, const int32_t *row_ptr, const int32_t *col_idx,
                      const float *X, int64_t ldx, int32_t F_in, const float *W, int64_t ldw, int32_t F_out,
                      const float *Y, int64_t ldy, const float *dY, int64_t lddy, int act,
-                     const int32_t *sel, int32_t n_sel, int want_dw, double *dX, double *dW) {
+                     const int32_t *sel, int32_t n_sel, int want_dw, double *dX, double *dW, double *dZ_out) {
     int32_t *dr = (int32_t *)malloc((size_t)(n_rows + 1) * sizeof(int32_t));
     int32_t *dc = (int32_t *)malloc((size_t)(n_cols + 1) * sizeof(int32_t));
     double *r = (double *)malloc((size_t)(n_rows + 1) * sizeof(double));
@@ -421,6 +423,7 @@ int orc_gcn_backward(int32_t n_rows, int32_t n_cols, const int32_t *row_ptr, con
             }
             for (int32_t m = 0; m < F_out; ++m) z[m] *= c[j];
         }
+        if (dZ_out) memcpy(dZ_out, dZ, (size_t)n_cols * (size_t)F_out * sizeof(double));
         if (full || want_dw) {
             ORC_PAR
             for (int32_t f = 0; f < F_in; ++f)
@@ -471,12 +474,13 @@ int orc_gcn_backward(int32_t n_rows, int32_t n_cols, const int32_t *row_ptr, con
  *   dTheta[j,:] = sum_i alpha_ij dP[i,:] + ds_l[j] a_l + ds_r[j] a_r
  *   da_l = Theta^T ds_l , da_r = Theta^T ds_r , dW = X^T dTheta , dX = dTheta W^T.
  * Square pattern only (destinations = the first n_rows sources, as in the
- * forward).  Outputs fp64: dX n_cols x F_in, dW F_in x F_out, da_l, da_r F_out. */
+ * forward).  Outputs fp64: dX n_cols x F_in, dW F_in x F_out, da_l, da_r F_out; dTh_out (optional,
+ * n_cols x F_out) receives dTheta. */
 int orc_gat_backward(int32_t n_rows, int32_t n_cols, const int32_t *row_ptr, const int32_t *col_idx,
                      const float *X, int64_t ldx, int32_t F_in, const float *W, int64_t ldw, int32_t F_out,
                      const float *a_l, const float *a_r, double slope,
                      const float *Y, int64_t ldy, const float *dY, int64_t lddy, int act,
-                     double *dX, double *dW, double *da_l, double *da_r) {
+                     double *dX, double *dW, double *da_l, double *da_r, double *dTh_out) {
     if (n_rows > n_cols) return 2;
     const int64_t nnz = row_ptr[n_rows];
     double *Th = (double *)malloc((size_t)n_cols * (size_t)F_out * sizeof(double) + 8);
@@ -549,13 +553,25 @@ int orc_gat_backward(int32_t n_rows, int32_t n_cols, const int32_t *row_ptr, con
         }
         dsl[i] = acc;
     }
-    /* scatter over columns: serial, the plain transposed sums */
-    for (int32_t i = 0; i < n_rows; ++i)
-        for (int32_t k = row_ptr[i]; k < row_ptr[i + 1]; ++k) {
-            const int32_t j = col_idx[k];
-            dsr[j] += dt[k];
-            for (int32_t m = 0; m < F_out; ++m) dTh[(int64_t)j * F_out + m] += alpha[k] * dP[(int64_t)i * F_out + m];
+    /* the transposed sums, one source node j at a time over the entries of column j (ascending rows) */
+    {
+        int32_t *col_ptr = NULL, *row_of = NULL, *pos = NULL;
+        int32_t *entry = (int32_t *)malloc(((size_t)nnz + 1) * sizeof(int32_t));  /* entry[p]: the stored entry at transposed place p */
+        if (!entry || orc_transpose(n_rows, n_cols, row_ptr, col_idx, &col_ptr, &row_of, &pos)) {
+            free(entry);
+            free(Th); free(dTh); free(sl); free(sr); free(dsl); free(dsr); free(alpha); free(dt); free(dP);
+            return 1;
         }
+        for (int64_t k = 0; k < nnz; ++k) entry[pos[k]] = (int32_t)k;
+        ORC_PAR
+        for (int32_t j = 0; j < n_cols; ++j)
+            for (int32_t p = col_ptr[j]; p < col_ptr[j + 1]; ++p) {
+                const int32_t i = row_of[p], k = entry[p];
+                dsr[j] += dt[k];
+                for (int32_t m = 0; m < F_out; ++m) dTh[(int64_t)j * F_out + m] += alpha[k] * dP[(int64_t)i * F_out + m];
+            }
+        free(col_ptr); free(row_of); free(pos); free(entry);
+    }
     for (int32_t m = 0; m < F_out; ++m) { da_l[m] = 0.0; da_r[m] = 0.0; }
     for (int32_t j = 0; j < n_cols; ++j)
         for (int32_t m = 0; m < F_out; ++m) {
@@ -563,6 +579,7 @@ int orc_gat_backward(int32_t n_rows, int32_t n_cols, const int32_t *row_ptr, con
             da_r[m] += Th[(int64_t)j * F_out + m] * dsr[j];
             dTh[(int64_t)j * F_out + m] += dsl[j] * (double)a_l[m] + dsr[j] * (double)a_r[m];
         }
+    if (dTh_out) memcpy(dTh_out, dTh, (size_t)n_cols * (size_t)F_out * sizeof(double));
     ORC_PAR
     for (int32_t f = 0; f < F_in; ++f)
         for (int32_t m = 0; m < F_out; ++m) {

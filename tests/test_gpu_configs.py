@@ -10,7 +10,7 @@ import oracle
 import synth
 from paper_2306_15155_amd import ACT_NONE, ACT_RELU, KIND_GAT, KIND_GCN, SELECT_MODEL, Context
 
-from gpu_util import DEV, DeviceCSR, assert_close, dev
+from gpu_util import DEV, DeviceCSR, assert_close, assert_close_reduced, dev
 
 pytestmark = pytest.mark.gpu
 
@@ -197,13 +197,48 @@ def test_config2_gcn_backward_full_size(ctx, reddit_like):
     X, W = synth.uniform(7, 10, (g.n_cols, f_in)), synth.glorot(7, 100, f_in, f_out)
     dY = synth.normal(7, 500, (g.n_rows, f_out), 0.0, 1.0)
     rows = _sample_rows(g, 9, 500)
-    want_dx, want_dw = oracle.gcn_backward(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, dY, rows=rows, want_dw=True, omp=True)
+    want_dx, want_dw, dz = oracle.gcn_backward(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, dY, rows=rows, want_dw=True, omp=True,
+                                               with_dz=True)
+    rss = np.sqrt((X.astype(np.float64) ** 2).T @ (dz ** 2))  # of the terms X[j, f] dZ[j, m] of dW
     r, c, _, _ = _norm(ctx, A)
     sel = torch.from_numpy(rows.astype(np.int64)).to(DEV)
     Xd, Wd, dYd = dev(X), dev(W), dev(dY)
     for bwd in (GCN_BWD_AGG, GCN_BWD_UPD):
         dX, dW = ctx.gcn_backward(A.s, A.s, r, c, Xd, Wd, dYd, bwd)  # the pattern is symmetric: it is its own transpose
         assert_close(dX[sel], want_dx, what=f"dX bwd {bwd}")
-        assert_close(dW, want_dw, what=f"dW bwd {bwd}")
+        assert_close_reduced(dW, want_dw, rss, what=f"dW bwd {bwd}")
     pick, est = ctx.select_gcn_backward(A.s, f_in, f_out)
     assert pick == GCN_BWD_AGG and est[0] < est[1]  # f_out < f_in: aggregate the gradient at the narrow width
+
+
+def test_config4_gat_backward_full_size(ctx, reddit_like):
+    """Training step of the GAT layer 602 -> 64 on the Reddit-shaped graph: every gradient against the oracle.
+
+    The derivative of LeakyReLU jumps at t = s_l[i] + s_r[j] = 0, and with 1.15e8 stored entries some |t| fall below
+    fp32 resolution, where the fp32 path and the fp64 oracle may legitimately take different branches (seen: a scaled
+    error of 8e-4 in dX from a handful of such entries).  The inputs therefore keep every t away from zero while both
+    branches stay in use inside every row: feature 0 is +1 / -1 by node parity and only a_r sees it (W[0, 0] = 1,
+    a_r[0] = 2.5, a_l[0] = 0), so s_r[j] is about +-2.5 by the parity of the neighbour while |s_l[i]| and the rest of
+    s_r stay below 1."""
+    g, A = reddit_like
+    f_in, f_out = 602, 64
+    X, W = synth.uniform(7, 10, (g.n_cols, f_in)), synth.glorot(7, 110, f_in, f_out)
+    a_l, a_r = synth.normal(7, 210, (f_out,), 0.0, 0.03), synth.normal(7, 310, (f_out,), 0.0, 0.03)
+    X[:, 0] = np.where(np.arange(g.n_cols) % 2 == 0, 1.0, -1.0)
+    W[0, :] = 0.0
+    W[:, 0] = 0.0
+    W[0, 0] = 1.0
+    a_l[0], a_r[0] = 0.0, 2.5
+    Th = X.astype(np.float64) @ W.astype(np.float64)
+    s_l, s_r = Th @ a_l.astype(np.float64), Th @ a_r.astype(np.float64)
+    assert np.min(np.abs(s_r)) - np.max(np.abs(s_l)) > 0.5 and (s_r > 0).any() and (s_r < 0).any()
+    dY = synth.normal(7, 510, (g.n_rows, f_out), 0.0, 1.0)
+    want = oracle.gat_backward(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, a_l, a_r, dY, omp=True, with_dtheta=True)
+    pos = ctx.transpose_positions(A.s, A.s)
+    got = ctx.gat_backward(A.s, A.s, pos, dev(X), dev(W), dev(a_l), dev(a_r), dev(dY))
+    assert_close(got[0], want[0], what="dX")
+    # dW[f, m] = sum_j X[j, f] dTheta[j, m]: root-sum-square of those terms
+    rss = np.sqrt((X.astype(np.float64) ** 2).T @ (want[4] ** 2))
+    assert_close_reduced(got[1], want[1], rss, what="dW")
+    assert_close(got[2], want[2], what="da_l")
+    assert_close(got[3], want[3], what="da_r")

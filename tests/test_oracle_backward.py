@@ -105,6 +105,8 @@ def test_gcn_backward_matches_dense_chain_rule(shape):
     dX, dW = oracle.gcn_backward(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, dY, Y=Y, act=1)
     _close(dX, Ahat.T @ dP @ W.astype(np.float64).T, 1e-11)
     _close(dW, (Ahat @ X.astype(np.float64)).T @ dP, 1e-11)
+    dZ = oracle.gcn_backward(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, dY, Y=Y, act=1, with_dz=True)[2]
+    _close(dZ, Ahat.T @ dP, 1e-11)  # the optional third result: gradient with respect to Z = X W
     # selected rows of dX, with and without the dW reduction
     rows = np.array([0, g.n_cols - 1, 3, 3], dtype=np.int32)
     dXs, dWs = oracle.gcn_backward(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, dY, Y=Y, act=1, rows=rows)
@@ -197,6 +199,8 @@ def test_gat_backward_with_zero_attention_vectors_is_mean_aggregation():
     dX, dW, dal, dar = oracle.gat_backward(15, 15, g.row_ptr, g.col_idx, X, W, z, z, dY)
     _close(dX, M.T @ dY.astype(np.float64) @ W.astype(np.float64).T, 1e-11)
     _close(dW, X.astype(np.float64).T @ M.T @ dY.astype(np.float64), 1e-11)
+    dTh = oracle.gat_backward(15, 15, g.row_ptr, g.col_idx, X, W, z, z, dY, with_dtheta=True)[4]
+    _close(dTh, M.T @ dY.astype(np.float64), 1e-11)  # the optional fifth result: gradient with respect to Theta = X W
     # d/da of the logits at a = 0: uniform alpha, softmax backward still active, LeakyReLU slope at t = 0 is `slope`
     Th = X.astype(np.float64) @ W.astype(np.float64)
     dalpha = dY.astype(np.float64) @ Th.T                       # <dP_i, Theta_j>
