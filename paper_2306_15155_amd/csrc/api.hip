@@ -409,8 +409,7 @@ int run_gat_backward(const sensei_csr &A, const sensei_csr &At, const int32_t *t
     float *T = cv.take<float>((size_t)A.n_rows * fo32);
     float *logits = cv.take<float>(nz);
     float *dt = cv.take<float>(nz);
-    float *alpha_t = cv.take<float>(nz);
-    float *dt_t = cv.take<float>(nz);
+    float2 *adt_t = cv.take<float2>(nz);  // (alpha, dt) in the order of the transposed pattern
     float *rowdot = cv.take<float>((size_t)A.n_rows + 1);
     float *sum_carry = cv.take<float>((size_t)plan.n_chunks);
     float *ds_l = cv.take<float>((size_t)A.n_cols + 1);
@@ -431,14 +430,15 @@ int run_gat_backward(const sensei_csr &A, const sensei_csr &At, const int32_t *t
     SENSEI_TRY(launch_to_slices(nullptr, dY.ptr, dY.ld, A.n_rows, f_out, T, s, act == SENSEI_ACT_RELU ? Y : nullptr, ldy));
     // per stored entry: dalpha, then softmax and LeakyReLU backward; alpha and dt also in transposed order
     SENSEI_TRY(launch_gat_dalpha(A, theta, T, f_out, logits, stats, dt, rowdot, plan, sum_carry, s));
-    SENSEI_TRY(launch_gat_dt(A, logits, dt, rowdot, stats, t_pos, slope, dt, alpha_t, dt_t, plan, s));
-    SENSEI_TRY(launch_row_sum(A, dt, ds_l, plan, sum_carry, s));
-    SENSEI_TRY(launch_row_sum(At, dt_t, ds_r, plan_t, sum_carry, s));
+    SENSEI_TRY(launch_gat_dt(A, logits, dt, rowdot, stats, t_pos, slope, dt, adt_t, plan, s));
+    SENSEI_TRY(launch_row_sum(A, dt, 1, ds_l, plan, sum_carry, s));
+    SENSEI_TRY(launch_row_sum(At, reinterpret_cast<const float *>(adt_t) + 1, 2, ds_r, plan_t, sum_carry, s));
     // dTheta = alpha^T.dP + ds_l a_l^T + ds_r a_r^T
     sensei_csr Aw = At;
-    Aw.val = alpha_t;
-    SENSEI_TRY(spmm_any(Aw, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, T, fo32, f_out, dTheta, fo4, f_out, SENSEI_ACT_NONE, plan_t, carry, s, nullptr,
-                        false, nullptr, true));
+    Aw.val = reinterpret_cast<const float *>(adt_t);
+    Aw.panels = nullptr;  // the values follow the order of At itself
+    SENSEI_TRY(launch_spmm(Aw, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, T, fo32, f_out, dTheta, fo4, f_out, SENSEI_ACT_NONE, plan_t, carry, s, nullptr,
+                           false, true, nullptr, true, 2));
     SENSEI_TRY(launch_rank1_add(dTheta, fo4, A.n_cols, f_out, ds_l, A.n_rows, ds_r, a_l, a_r, s));
     SENSEI_TRY(launch_theta_t_vec(theta, A.n_cols, f_out, ds_l, A.n_rows, ds_r, da_l, da_r, part_a, s));
     SENSEI_TRY(launch_gemm_tn(X.ptr, X.ld, dTheta, fo4, A.n_cols, f_in, f_out, dW, lddw, part, s));

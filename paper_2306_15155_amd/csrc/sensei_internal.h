@@ -61,9 +61,9 @@ size_t spmm_carry_bytes(int64_t nnz, int f);  // upper bound
 hipError_t launch_spmm(const sensei_csr &A, int mode, const float *r, const float *c, const float *B, int64_t ldb,
                        int f, float *C, int64_t ldc, int f_store, int act, const ChunkPlan &p, float *carry,
                        hipStream_t s, KernelTimer *timer = nullptr, bool accumulate = false, bool finalize = true,
-                       const float2 *mz = nullptr, bool b_sliced = false);
+                       const float2 *mz = nullptr, bool b_sliced = false, int val_stride = 1);
 // b_sliced: B is stored slice-major in tiles of 32 floats, element (j, col) at B[(col / 32) * n_cols * 32 + j * 32 + col % 32]
-// (f padded to a multiple of 32, B 128-byte aligned); `ldb` is ignored.
+// (f padded to a multiple of 32, B 128-byte aligned); `ldb` is ignored.  val_stride: floats between consecutive values of A.val.
 inline size_t sliced_index(int64_t n_rows, int64_t row, int col) { return (size_t)(col >> 5) * (size_t)n_rows * 32 + (size_t)row * 32 + (col & 31); }
 // Internal SpMM mode (not part of the C ABI): A.val holds attention logits e_ij, `mz[i]` = (max_j e_ij, sum_j exp(e_ij - max));
 // the kernel weighs neighbour j of row i by exp(e_ij - max_i) and scales the finished row by 1 / sum, i.e. it aggregates
@@ -105,14 +105,14 @@ hipError_t launch_attention_stats(const sensei_csr &A, const float *s_l, const f
 size_t softmax_ws_bytes(const sensei_csr &A);
 
 // ---- backward of the attention layer
-// out[i] = sum of val over row i; carry: n_chunks floats
-hipError_t launch_row_sum(const sensei_csr &A, const float *val, float *out, const ChunkPlan &p, float *carry, hipStream_t s);
+// out[i] = sum of val[k * stride] over the entries k of row i; carry: n_chunks floats
+hipError_t launch_row_sum(const sensei_csr &A, const float *val, int stride, float *out, const ChunkPlan &p, float *carry, hipStream_t s);
 // dalpha[k] = <dP[i,:], Theta[j,:]> per stored entry, rowdot[i] = sum_j alpha_ij dalpha_ij; theta, dP slice-major
 hipError_t launch_gat_dalpha(const sensei_csr &A, const float *theta, const float *dP, int f, const float *logits, const float2 *mz,
                              float *dalpha, float *rowdot, const ChunkPlan &p, float *carry, hipStream_t s);
-// dt[k] = alpha (dalpha - rowdot_i) LeakyReLU'(e); dt may be dalpha; alpha_t / dt_t: the same values at t_pos[k]
+// dt[k] = alpha (dalpha - rowdot_i) LeakyReLU'(e); dt may be dalpha; adt_t[t_pos[k]] = (alpha, dt)
 hipError_t launch_gat_dt(const sensei_csr &A, const float *logits, const float *dalpha, const float *rowdot, const float2 *mz,
-                         const int32_t *t_pos, float slope, float *dt, float *alpha_t, float *dt_t, const ChunkPlan &p, hipStream_t s);
+                         const int32_t *t_pos, float slope, float *dt, float2 *adt_t, const ChunkPlan &p, hipStream_t s);
 hipError_t launch_rank1_add(float *D, int64_t ldd, int64_t n, int f, const float *ds_l, int64_t n_l, const float *ds_r, const float *a_l,
                             const float *a_r, hipStream_t s);
 // out_l = Theta^T v_l (v_l counted for the first n_l rows), out_r = Theta^T v_r; Theta slice-major n x pad32(f); sums in fp64

@@ -60,6 +60,7 @@ struct SpmmArgs {
     const int32_t *row_ptr, *col_idx, *chunk_row;
     const float *val, *r, *c, *B;
     const float2 *mz;  // softmax mode: per-row (max logit, sum of exp(logit - max))
+    int val_stride;    // floats from the value of one entry to the next (1, or 2 when the values sit in (value, other) pairs)
     float *C, *carry;
     long long ldb, ldc;
     long long tile_stride_b;  // bytes from feature tile t of B to tile t + 1: 4*VEC*LPG when rows are contiguous, a whole slice otherwise
@@ -225,9 +226,9 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
                     const int kq = valid ? k + q : k;
                     const int j = a.col_idx[kq];
                     float wq = 1.f;
-                    if (MODE == SENSEI_SPMM_WEIGHTED) wq = a.val[kq];
+                    if (MODE == SENSEI_SPMM_WEIGHTED) wq = a.val[(size_t)kq * a.val_stride];
                     if (MODE == SENSEI_SPMM_SCALED) wq = a.c[j];
-                    if (MODE == kSpmmSoftmax) wq = __expf(a.val[kq] - mz_g.x);
+                    if (MODE == kSpmmSoftmax) wq = __expf(a.val[(size_t)kq * a.val_stride] - mz_g.x);
                     ww[q] = valid ? wq : 0.f;
                     b[q] = gather(j);
                 }
@@ -281,7 +282,7 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
         float w = 0.f;
         if (k < hi) {
             col = a.col_idx[k];
-            if (MODE == SENSEI_SPMM_WEIGHTED || MODE == kSpmmSoftmax) w = a.val[k];
+            if (MODE == SENSEI_SPMM_WEIGHTED || MODE == kSpmmSoftmax) w = a.val[(size_t)k * a.val_stride];
             if (MODE == SENSEI_SPMM_SCALED) w = a.c[col];
         }
         const int bhi = (base + 64 < hi) ? base + 64 : hi;
@@ -850,13 +851,14 @@ __global__ void k_sum_fixup(NnzArgs a, float *__restrict__ out, const float *__r
 }
 
 // out[i] = sum of val over the stored entries of row i
-__global__ __launch_bounds__(kBlock) void k_row_sum(NnzArgs a, const float *__restrict__ val, float *__restrict__ out, float *__restrict__ carry) {
+__global__ __launch_bounds__(kBlock) void k_row_sum(NnzArgs a, const float *__restrict__ val, int stride, float *__restrict__ out,
+                                                     float *__restrict__ carry) {
     const int chunk = wave_chunk();
     if (chunk >= a.n_chunks) return;
     const int lane = threadIdx.x & 63;
     reduce_rows(a, chunk, lane, out, carry, [&](int, int lo, int hi) {
         float s = 0.f;
-        for (int k = lo + lane; k < hi; k += 64) s += val[k];
+        for (int k = lo + lane; k < hi; k += 64) s += val[(size_t)k * stride];
         return s;
     });
 }
@@ -875,6 +877,8 @@ struct GatBwdArgs {
 // dalpha_ij = <dP[i,:], Theta[j,:]> for every stored entry (the general g-SDDMM of Eq. 2 with a dot product as the
 // inner operator) together with the row sums sum_j alpha_ij dalpha_ij that the softmax backward needs.  Eight lanes
 // take one neighbour: each reads 16 bytes of every 128-byte slice of Theta_j and of dP_i, eight neighbours per step.
+// NT > 0: at most NT tiles, the row of dP is held in registers; NT == 0: any width, dP re-read per neighbour (L1 hits).
+template <int NT>
 __global__ __launch_bounds__(kBlock) void k_gat_dalpha(GatBwdArgs a) {
     const int chunk = wave_chunk();
     if (chunk >= a.n.n_chunks) return;
@@ -884,6 +888,12 @@ __global__ __launch_bounds__(kBlock) void k_gat_dalpha(GatBwdArgs a) {
         const float2 st = a.mz[i];
         const float m = st.x, iz = inv_z(st.y);
         const float *dp = a.dP + (size_t)i * 32 + sub * 4;
+        float4 dpr[NT > 0 ? NT : 1];
+        if (NT > 0) {
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+                dpr[t] = t < a.n_tiles ? *reinterpret_cast<const float4 *>(dp + (size_t)t * a.dp_tile) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
         float s = 0.f;
         for (int k0 = lo; k0 < hi; k0 += 8) {
             const int k = k0 + g;
@@ -891,11 +901,24 @@ __global__ __launch_bounds__(kBlock) void k_gat_dalpha(GatBwdArgs a) {
             const int j = a.n.col_idx[ok ? k : lo];
             const float *th = a.theta + (size_t)j * 32 + sub * 4;
             float d = 0.f;
+            if (NT > 0) {
+                float4 b[NT > 0 ? NT : 1];
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+                    if (t < a.n_tiles) b[t] = *reinterpret_cast<const float4 *>(th + (size_t)t * a.theta_tile);
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+                    if (t < a.n_tiles) {
+                        d = fmaf(b[t].x, dpr[t].x, d); d = fmaf(b[t].y, dpr[t].y, d);
+                        d = fmaf(b[t].z, dpr[t].z, d); d = fmaf(b[t].w, dpr[t].w, d);
+                    }
+            } else {
 #pragma unroll 4
-            for (int t = 0; t < a.n_tiles; ++t) {
-                const float4 b = *reinterpret_cast<const float4 *>(th + (size_t)t * a.theta_tile);
-                const float4 p = *reinterpret_cast<const float4 *>(dp + (size_t)t * a.dp_tile);
-                d = fmaf(b.x, p.x, d); d = fmaf(b.y, p.y, d); d = fmaf(b.z, p.z, d); d = fmaf(b.w, p.w, d);
+                for (int t = 0; t < a.n_tiles; ++t) {
+                    const float4 b = *reinterpret_cast<const float4 *>(th + (size_t)t * a.theta_tile);
+                    const float4 p = *reinterpret_cast<const float4 *>(dp + (size_t)t * a.dp_tile);
+                    d = fmaf(b.x, p.x, d); d = fmaf(b.y, p.y, d); d = fmaf(b.z, p.z, d); d = fmaf(b.w, p.w, d);
+                }
             }
             d += __shfl_xor(d, 1, 64);
             d += __shfl_xor(d, 2, 64);
@@ -914,13 +937,14 @@ struct GatDtArgs {
     const float *logits, *dalpha, *rowdot;
     const float2 *mz;
     const int32_t *t_pos;   // place of entry k in the transposed pattern
-    float *dt, *alpha_t, *dt_t;
+    float *dt;
+    float2 *adt_t;          // (alpha, dt) at the entry's place in the transposed pattern: one 8-byte scattered store
     float slope;
 };
 
 // Softmax and LeakyReLU backward per stored entry: alpha = exp(e - m_i) / z_i, de = alpha (dalpha - rowdot_i),
 // dt = de * (e > 0 ? 1 : slope) (e > 0 exactly when the pre-activation is).  dt is kept in row order (for the row
-// sums ds_l) and, like alpha, written at its place in the transposed pattern (for ds_r and alpha^T dP).
+// sums ds_l) and, together with alpha, written at its place in the transposed pattern (for ds_r and alpha^T dP).
 __global__ __launch_bounds__(kBlock) void k_gat_dt(GatDtArgs a) {
     const int chunk = wave_chunk();
     if (chunk >= a.n.n_chunks) return;
@@ -933,8 +957,7 @@ __global__ __launch_bounds__(kBlock) void k_gat_dt(GatDtArgs a) {
                    const float dt = al * (a.dalpha[k] - rd.dot) * (e > 0.f ? 1.f : a.slope);
                    const int p = a.t_pos[k];
                    a.dt[k] = dt;
-                   a.alpha_t[p] = al;
-                   a.dt_t[p] = dt;
+                   a.adt_t[p] = make_float2(al, dt);
                });
 }
 
@@ -1072,7 +1095,7 @@ size_t spmm_carry_bytes(int64_t nnz, int f) {
 
 hipError_t launch_spmm(const sensei_csr &A, int mode, const float *r, const float *c, const float *B, int64_t ldb,
                        int f, float *C, int64_t ldc, int f_store, int act, const ChunkPlan &p, float *carry,
-                       hipStream_t s, KernelTimer *timer, bool accumulate, bool finalize, const float2 *mz, bool b_sliced) {
+                       hipStream_t s, KernelTimer *timer, bool accumulate, bool finalize, const float2 *mz, bool b_sliced, int val_stride) {
     SpmmShape sh = spmm_shape(B, ldb, f);
     if (b_sliced) {  // slices of 32 floats per row: one 128-byte line per neighbour and tile
         sh.vec = 4; sh.lpg = 8; sh.n_tiles = (f + 31) / 32; sh.f_carry = sh.n_tiles * 32;
@@ -1081,6 +1104,7 @@ hipError_t launch_spmm(const sensei_csr &A, int mode, const float *r, const floa
     SpmmArgs a;
     a.tile_stride_b = b_sliced ? (long long)(A.n_cols > 0 ? A.n_cols : 1) * 128 : (long long)sh.vec * sh.lpg * 4;
     a.mz = (mode == kSpmmSoftmax) ? mz : nullptr;
+    a.val_stride = val_stride;
     a.row_ptr = A.row_ptr; a.col_idx = A.col_idx; a.chunk_row = p.chunk_row;
     a.val = A.val; a.r = r; a.c = c; a.B = B; a.C = C; a.carry = carry;
     a.ldb = ldb; a.ldc = ldc;
@@ -1193,9 +1217,9 @@ hipError_t launch_attention_stats(const sensei_csr &A, const float *s_l, const f
 
 // ------------------------------------------------------------ backward of the attention layer (host side)
 
-hipError_t launch_row_sum(const sensei_csr &A, const float *val, float *out, const ChunkPlan &p, float *carry, hipStream_t s) {
+hipError_t launch_row_sum(const sensei_csr &A, const float *val, int stride, float *out, const ChunkPlan &p, float *carry, hipStream_t s) {
     const NnzArgs n = nnz_args(A, p);
-    hipLaunchKernelGGL(k_row_sum, dim3(blocks_for(p.n_chunks, kWavesPerBlock)), dim3(kBlock), 0, s, n, val, out, carry);
+    hipLaunchKernelGGL(k_row_sum, dim3(blocks_for(p.n_chunks, kWavesPerBlock)), dim3(kBlock), 0, s, n, val, stride, out, carry);
     if (p.n_chunks > 1) hipLaunchKernelGGL(k_sum_fixup, dim3(blocks_for(p.n_chunks - 1, kBlock)), dim3(kBlock), 0, s, n, out, carry);
     return hipGetLastError();
 }
@@ -1208,17 +1232,21 @@ hipError_t launch_gat_dalpha(const sensei_csr &A, const float *theta, const floa
     a.theta_tile = (long long)(A.n_cols > 0 ? A.n_cols : 1) * 32;
     a.dp_tile = (long long)(A.n_rows > 0 ? A.n_rows : 1) * 32;
     a.n_tiles = (f + 31) / 32;
-    hipLaunchKernelGGL(k_gat_dalpha, dim3(blocks_for(p.n_chunks, kWavesPerBlock)), dim3(kBlock), 0, s, a);
+    const dim3 grid(blocks_for(p.n_chunks, kWavesPerBlock));
+    if (a.n_tiles <= 2) hipLaunchKernelGGL((k_gat_dalpha<2>), grid, dim3(kBlock), 0, s, a);
+    else if (a.n_tiles <= 4) hipLaunchKernelGGL((k_gat_dalpha<4>), grid, dim3(kBlock), 0, s, a);
+    else if (a.n_tiles <= 8) hipLaunchKernelGGL((k_gat_dalpha<8>), grid, dim3(kBlock), 0, s, a);
+    else hipLaunchKernelGGL((k_gat_dalpha<0>), grid, dim3(kBlock), 0, s, a);
     if (p.n_chunks > 1) hipLaunchKernelGGL(k_sum_fixup, dim3(blocks_for(p.n_chunks - 1, kBlock)), dim3(kBlock), 0, s, a.n, rowdot, carry);
     return hipGetLastError();
 }
 
 hipError_t launch_gat_dt(const sensei_csr &A, const float *logits, const float *dalpha, const float *rowdot, const float2 *mz,
-                         const int32_t *t_pos, float slope, float *dt, float *alpha_t, float *dt_t, const ChunkPlan &p, hipStream_t s) {
+                         const int32_t *t_pos, float slope, float *dt, float2 *adt_t, const ChunkPlan &p, hipStream_t s) {
     if (A.nnz <= 0) return hipSuccess;
     GatDtArgs a;
     a.n = nnz_args(A, p);
-    a.logits = logits; a.dalpha = dalpha; a.rowdot = rowdot; a.mz = mz; a.t_pos = t_pos; a.dt = dt; a.alpha_t = alpha_t; a.dt_t = dt_t;
+    a.logits = logits; a.dalpha = dalpha; a.rowdot = rowdot; a.mz = mz; a.t_pos = t_pos; a.dt = dt; a.adt_t = adt_t;
     a.slope = slope;
     hipLaunchKernelGGL(k_gat_dt, dim3(blocks_for(p.n_chunks, kWavesPerBlock)), dim3(kBlock), 0, s, a);
     return hipGetLastError();
