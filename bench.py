@@ -68,7 +68,7 @@ def main():
     import torch
 
     import synth
-    from paper_2306_15155_amd import (GAT_NAMES, GCN_NAMES, KIND_GAT, KIND_GCN, SELECT_MODEL, SELECT_TIMED, Context, Panels,
+    from paper_2306_15155_amd import (GAT_NAMES, GCN_NAMES, KIND_GAT, KIND_GCN, SELECT_LEARNED, SELECT_MODEL, SELECT_TIMED, Context, Panels,
                                       csr_struct)
 
     wl = WORKLOADS[args.workload]
@@ -256,6 +256,16 @@ def main():
             run_layer(i, ids[i])  # leave the selected composition's output in place for later layers
         detail["all_compositions_ms"] = sweep
         detail["selector_regret"] = regret
+        # the same question to the learned per-primitive models (gradient-boosted trees fitted to MI355X timings)
+        learned = {}
+        for i, L in enumerate(layers):
+            kind = KIND_GCN if L["kind"] == "gcn" else KIND_GAT
+            pick, est = ctx.select(kind, A, L["f_in"], L["f_out"], SELECT_LEARNED)
+            allowed = [cid for cid, t in enumerate(est) if t >= 0]
+            best = min(sweep[tag(i)][name_of(i, cid)] for cid in allowed)
+            learned[tag(i)] = {"pick": name_of(i, pick), "regret": round(sweep[tag(i)][name_of(i, pick)] / best - 1.0, 4),
+                               "predicted_ms": round(est[pick], 4)}
+        detail["selector_learned"] = learned
         L0 = layers[0]
         ts = time.perf_counter()
         idt, _ = ctx.select(KIND_GCN if L0["kind"] == "gcn" else KIND_GAT, A, L0["f_in"], L0["f_out"], SELECT_TIMED)

@@ -265,9 +265,10 @@ int sensei_gat_layer(sensei_ctx *ctx, const sensei_csr *A, sensei_mat X, sensei_
 
 /* --------------------------------------------------------------------- selector */
 
-enum { SENSEI_SELECT_MODEL = 0, SENSEI_SELECT_TIMED = 1 };
+enum { SENSEI_SELECT_MODEL = 0, SENSEI_SELECT_TIMED = 1, SENSEI_SELECT_LEARNED = 2 };
 
-/* Bytes sensei_select needs in timed mode (it runs every candidate once on scratch operands). */
+/* Bytes sensei_select needs in timed mode (it runs every candidate once on scratch operands); learned mode needs
+ * 256 bytes. */
 int sensei_select_workspace(int kind, const sensei_csr *A, int f_in, int f_out, size_t *bytes);
 
 /* Chooses a composition for (graph, f_in, f_out) (online stage; code generation of promoted
@@ -279,6 +280,11 @@ int sensei_select_workspace(int kind, const sensei_csr *A, int f_in, int f_out, 
  *   mode TIMED: every remaining candidate is run once after one warm-up on scratch operands in
  *               `workspace` and the fastest is kept (the "run all once, keep the best" strategy);
  *               synchronises `stream`.
+ *   mode LEARNED: as MODEL, but the SpMM and GEMM times come from gradient-boosted regression trees fitted to
+ *               timings of these primitives on MI355X over a grid of synthetic graphs (the learned per-primitive
+ *               cost models of Section 3.5; tables generated by paper_2306_15155_amd/costmodel/train.py).  The graph
+ *               feature extractor adds two measures of skew read from row_ptr by one small kernel (largest row,
+ *               second moment of the row lengths): needs 256 bytes of `workspace`, synchronises `stream`.
  * comp_id_out: host int.  est_ms (host, nullable): sensei_num_compositions(kind) floats,
  * predicted or measured ms per id, negative for ids the conditions dropped. */
 int sensei_select(sensei_ctx *ctx, int kind, const sensei_csr *A, int f_in, int f_out, int mode, int *comp_id_out,

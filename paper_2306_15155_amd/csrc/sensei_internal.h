@@ -122,6 +122,9 @@ hipError_t launch_theta_t_vec(const float *theta_sliced, int64_t n, int f, const
 // pos[k] = place of entry k of A in At (binary search in the ascending columns of At); *miss (cleared first) counts entries not found
 hipError_t launch_transpose_pos(const sensei_csr &A, const sensei_csr &At, const ChunkPlan &p, int32_t *pos, int32_t *miss, hipStream_t s);
 
+// out2[0] = largest row length, out2[1] = sum of squared row lengths (device, 16 bytes)
+hipError_t launch_row_moments(const sensei_csr &A, unsigned long long *out2, hipStream_t s);
+
 // ---- dense
 // Y[0:n, 0:m_store) = act(row_scale[i] * (A[n x k] . W[k x m])); columns m..m_store are written as act(0);
 // row_scale may be null (no scaling).

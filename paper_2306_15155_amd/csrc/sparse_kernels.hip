@@ -1032,6 +1032,30 @@ __global__ __launch_bounds__(kBlock) void k_transpose_pos(NnzArgs a, const int32
                });
 }
 
+// graph feature extractor: out[0] = largest row length, out[1] = sum of squared row lengths (as two 32-bit halves are
+// not needed: 64-bit integer atomics), both exact
+__global__ void k_row_moments(const int32_t *__restrict__ row_ptr, int n_rows, unsigned long long *__restrict__ out) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    unsigned long long d = 0;
+    if (i < n_rows) d = (unsigned long long)(row_ptr[i + 1] - row_ptr[i]);
+    unsigned long long mx = d, sq = d * d;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const unsigned long long m2 = __shfl_xor(mx, off, 64), s2 = __shfl_xor(sq, off, 64);
+        mx = mx > m2 ? mx : m2;
+        sq += s2;
+    }
+    if ((threadIdx.x & 63) == 0) {
+        atomicMax(&out[0], mx);
+        atomicAdd(&out[1], sq);
+    }
+}
+
+__global__ void k_fill_u64(unsigned long long *p, int n, unsigned long long v) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
 NnzArgs nnz_args(const sensei_csr &A, const ChunkPlan &p) {
     NnzArgs n;
     n.row_ptr = A.row_ptr; n.col_idx = A.col_idx; n.chunk_row = p.chunk_row;
@@ -1286,6 +1310,12 @@ hipError_t launch_transpose_pos(const sensei_csr &A, const sensei_csr &At, const
     return hipGetLastError();
 }
 
+
+hipError_t launch_row_moments(const sensei_csr &A, unsigned long long *out2, hipStream_t s) {
+    hipLaunchKernelGGL(k_fill_u64, dim3(1), dim3(64), 0, s, out2, 2, 0ull);
+    if (A.n_rows > 0) hipLaunchKernelGGL(k_row_moments, dim3(blocks_for(A.n_rows, kBlock)), dim3(kBlock), 0, s, A.row_ptr, A.n_rows, out2);
+    return hipGetLastError();
+}
 
 // ------------------------------------------------------------ column panels (host side)
 

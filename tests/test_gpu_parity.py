@@ -8,7 +8,7 @@ import torch
 
 import oracle
 import synth
-from paper_2306_15155_amd import (ACT_NONE, ACT_RELU, KIND_GAT, KIND_GCN, SELECT_MODEL, SELECT_TIMED, SPMM_PATTERN, SPMM_SCALED,
+from paper_2306_15155_amd import (ACT_NONE, ACT_RELU, KIND_GAT, KIND_GCN, SELECT_LEARNED, SELECT_MODEL, SELECT_TIMED, SPMM_PATTERN, SPMM_SCALED,
                                   SPMM_WEIGHTED, Context, SenseiError)
 
 from gpu_util import DEV, TOL, DeviceCSR, assert_close, dev, hub_and_empty_graph, rect_block
@@ -259,11 +259,41 @@ def test_selector_rules_and_modes(ctx):
         for f_in, f_out in ((32, 256), (256, 32), (64, 64)):
             kind_name = "gcn" if kind == KIND_GCN else "gat"
             allowed = set(oracle.select_rules(kind_name, f_in, f_out))
-            for mode in (SELECT_MODEL, SELECT_TIMED):
+            for mode in (SELECT_MODEL, SELECT_TIMED, SELECT_LEARNED):
                 cid, est = ctx.select(kind, A.s, f_in, f_out, mode)
                 assert cid in allowed and len(est) == n
                 assert {i for i, t in enumerate(est) if t >= 0} == allowed
                 assert est[cid] == min(t for t in est if t >= 0)
+
+
+def test_learned_selector_reads_the_graph_and_predicts_the_layer_time(ctx):
+    """The learned mode extracts its skew features on the GPU (bit-exact integers) and its additive prediction lands
+    within a factor of three of the measured layer time on a graph that is not in its training grid."""
+    import ctypes
+    from paper_2306_15155_amd import binding
+    g = synth.rmat(61, 120_000, 4_000_000)
+    A = DeviceCSR(g)
+    f_in, f_out = 160, 72
+    cid, est = ctx.select(KIND_GCN, A.s, f_in, f_out, SELECT_LEARNED)
+    X, W = dev(synth.uniform(61, 10, (g.n_cols, f_in))), dev(synth.glorot(61, 11, f_in, f_out))
+    dr, dc = ctx.degrees(A.s)
+    r, c = ctx.norm_vectors(dr), ctx.norm_vectors(dc)
+    Y = torch.empty((g.n_rows, f_out), device=DEV)
+    for _ in range(2):
+        ctx.gcn_layer(A.s, r, c, X, W, cid, ACT_RELU, out=Y)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(3):
+        ctx.gcn_layer(A.s, r, c, X, W, cid, ACT_RELU, out=Y)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / 3
+    assert ms / 3 < est[cid] < ms * 3, (est[cid], ms)
+    # learned mode needs its 256 bytes of workspace
+    pick = ctypes.c_int()
+    st = binding.lib().sensei_select(ctx._h, KIND_GCN, ctypes.byref(A.s), f_in, f_out, SELECT_LEARNED, ctypes.byref(pick), None, None, 0, None)
+    assert st == 1
 
 
 # ------------------------------------------------------------------- error paths
