@@ -155,3 +155,41 @@ def test_transpose_positions_rejects_a_pattern_that_is_not_the_transpose(ctx):
     A = DeviceCSR(g)
     with pytest.raises(SenseiError):
         ctx.transpose_positions(A.s, A.s)
+
+
+# ------------------------------------------------------------------ degenerate shapes
+
+@pytest.mark.parametrize("case", ["no_entries", "single_node", "width_one", "one_long_row"])
+def test_backward_degenerate_cases(ctx, case):
+    if case == "no_entries":       # rows without any stored entry: every gradient through the graph is zero
+        e = np.empty(0, dtype=np.int32)
+        g = synth.build_csr(50, 50, e, e, False, False)
+        f_in, f_out = 6, 5
+    elif case == "single_node":
+        g = synth.self_loops_only(1)
+        f_in, f_out = 3, 2
+    elif case == "width_one":
+        g = synth.erdos_renyi(81, 400, 1500)
+        f_in, f_out = 1, 1
+    else:                          # one row holding every column (spans many chunks), the others only their self edge
+        n = 3000
+        g = synth.build_csr(n, n, np.zeros(n, dtype=np.int32), np.arange(n, dtype=np.int32), False, True)
+        f_in, f_out = 20, 36
+    gt = synth.transpose(g)
+    X, W, dY = _inputs(g, f_in, f_out, 90)
+    a_l, a_r = synth.normal(91, 20, (f_out,), 0.0, 0.3), synth.normal(91, 21, (f_out,), 0.0, 0.3)
+    A, At = DeviceCSR(g), DeviceCSR(gt)
+    dr, dc = ctx.degrees(A.s)
+    r, c = ctx.norm_vectors(dr), ctx.norm_vectors(dc)
+    want_dx, want_dw = oracle.gcn_backward(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, dY)
+    for bwd in (GCN_BWD_AGG, GCN_BWD_UPD):
+        dX, dW = ctx.gcn_backward(A.s, At.s, r, c, dev(X), dev(W), dev(dY), bwd)
+        assert_close(dX, want_dx, what=f"{case} gcn dX {bwd}")
+        assert_close(dW, want_dw, what=f"{case} gcn dW {bwd}")
+    want = oracle.gat_backward(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, a_l, a_r, dY)
+    pos = ctx.transpose_positions(A.s, At.s)
+    got = ctx.gat_backward(A.s, At.s, pos, dev(X), dev(W), dev(a_l), dev(a_r), dev(dY))
+    for gpu, ref, what in zip(got, want, ("dX", "dW", "da_l", "da_r")):
+        assert_close(gpu, ref, what=f"{case} gat {what}")
+    if case == "no_entries":
+        assert float(got[1].abs().max()) == 0.0 and float(dW.abs().max()) == 0.0
