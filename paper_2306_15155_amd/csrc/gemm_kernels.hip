@@ -27,7 +27,7 @@ struct GemmArgs {
 template <int BM, int BN, int WGM, int WGN, int AVEC, int BVEC>
 __global__ __launch_bounds__(kThreads) void k_gemm(GemmArgs g) {
     constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32;
-    constexpr int APAD = 2, BPAD = 4;
+    constexpr int APAD = 36, BPAD = 36;  // row stride = 36 mod 64 words: the two k-rows an MFMA operand read touches fall on (nearly) disjoint LDS banks, and the four k-rows a stash writes are 16 banks apart
     constexpr int A_TPR = KT / AVEC;             // threads per A row
     constexpr int A_RPP = kThreads / A_TPR;      // A rows per pass
     constexpr int A_PASSES = BM / A_RPP;
