@@ -306,6 +306,27 @@ def main():
             del dYt, t_pos
         detail["gat_backward_ms"] = gat_bwd
 
+    # ---- one training iteration of the GCN stack of the workload (the layers whose input is X or the previous layer):
+    # forward with the selected compositions, backward with the associations the cost model picks; the first layer needs no dX
+    if not args.no_sweep:
+        chain = [i for i, L in enumerate(layers) if L["kind"] == "gcn" and (L["src"] == "X" or L["src"] in (-1, i - 1))]
+        chain = chain[:2] if len(chain) >= 2 and layers[chain[1]]["src"] in (-1, chain[0]) else chain[:1]
+        bwd_pick = {i: ctx.select_gcn_backward(A, layers[i]["f_in"], layers[i]["f_out"], want_dx=(i != chain[0]))[0] for i in chain}
+        dLast = torch.randn((N, layers[chain[-1]]["f_out"]), device=dev)
+
+        def train_step():
+            for i in chain:
+                run_layer(i, ids[i])
+            grad = dLast
+            for i in reversed(chain):
+                L = layers[i]
+                dX, _ = ctx.gcn_backward(A, A, r, c, src_of(i), Wd[i], grad, bwd_pick[i], Y=outs[i] if L["act"] else None, activation=L["act"],
+                                         want_dx=(i != chain[0]))
+                grad = dX
+        detail["gcn_training_iteration"] = {"layers": [tag(i) for i in chain], "ms": round(time_fn(train_step, 3), 4),
+                                            "backward": {tag(i): ("BWD_AGG", "BWD_UPD")[bwd_pick[i]] for i in chain}}
+        del dLast
+
     # ---- ceiling of the neighbour gather: the same SpMM kernel (value-less, F = 256) on a synthetic pattern whose
     # columns span only 8192 rows of the gathered matrix, so every 128-byte feature slice (1 MB) stays in one L2.
     # The rate it reaches bounds what any SpMM of this shape can consume, whatever the graph.

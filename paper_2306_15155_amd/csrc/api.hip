@@ -77,8 +77,15 @@ struct Carver {
     }
 };
 
+bool relayout_pays(const sensei_csr &A);
+
+// room for a slice-major copy of the gathered matrix of the stand-alone SpMM, where it pays
+size_t spmm_copy_bytes(const sensei_csr &A, int f) {
+    return (relayout_pays(A) && f >= 32) ? align_up((size_t)A.n_cols * pad32(f) * sizeof(float), 256) : 0;
+}
+
 size_t sparse_ws(const sensei_csr &A, int f) {
-    return plan_bytes(A.nnz) + spmm_carry_bytes(A.nnz, f) + softmax_ws_bytes(A) + 256;
+    return plan_bytes(A.nnz) + spmm_carry_bytes(A.nnz, f) + softmax_ws_bytes(A) + spmm_copy_bytes(A, f) + 256;
 }
 
 ChunkPlan make_plan(const sensei_csr &A, Carver &cv) {
@@ -93,7 +100,7 @@ bool gcn_is_agg(int id) { return id == SENSEI_GCN_DYN_AGG || id == SENSEI_GCN_DY
 
 // A slice-major copy of a user matrix the SpMM gathers from costs one pass over it (8 bytes per element); it pays
 // once every row is gathered many times.
-bool relayout_pays(const sensei_csr &A) { return A.nnz >= 16 * (int64_t)A.n_cols; }
+bool relayout_pays(const sensei_csr &A) { return A.nnz >= 16 * (int64_t)A.n_cols; }  // declared above
 
 size_t gcn_ws(const sensei_csr &A, int f_in, int f_out, int id) {
     const int fs = gcn_is_agg(id) ? pad4(f_in) : pad32(f_out);
@@ -946,15 +953,28 @@ int sensei_spmm(sensei_ctx *ctx, const sensei_csr *A, int mode, const float *r, 
     if (!workspace) return SENSEI_INVALID_ARGUMENT;
     const int f = (int)B.cols;
     const size_t cbytes = mat_bytes(C, A->n_rows, f, ldc);
-    if (overlap(C, cbytes, B.ptr, mat_bytes(B.ptr, B.rows, f, B.ld)) || overlap(C, cbytes, workspace, ws_bytes)) return SENSEI_INVALID_ARGUMENT;
+    if (overlap(C, cbytes, B.ptr, mat_bytes(B.ptr, B.rows, f, B.ld)) || overlap(C, cbytes, workspace, ws_bytes) ||
+        overlap(B.ptr, mat_bytes(B.ptr, B.rows, f, B.ld), workspace, ws_bytes))
+        return SENSEI_INVALID_ARGUMENT;
     if (ws_bytes < plan_bytes(A->nnz) + spmm_carry_bytes(A->nnz, f)) return SENSEI_WORKSPACE_TOO_SMALL;
     Carver cv(workspace, ws_bytes);
     ChunkPlan plan = make_plan(*A, cv);
     float *carry = cv.take<float>(spmm_carry_bytes(A->nnz, f) / sizeof(float));
     SENSEI_TRY(launch_chunk_rows(*A, plan, as_stream(stream)));
     const bool scaled = (mode == SENSEI_SPMM_SCALED);
-    return hip_status(spmm_any(*A, mode, scaled ? r : nullptr, scaled ? c : nullptr, B.ptr, B.ld, f, C, ldc, f, activation, plan, carry,
-                                  as_stream(stream), &ctx->timers.spmm));
+    // with room in the workspace (sensei_sparse_workspace asks for it) a matrix whose rows are gathered often is first
+    // copied slice-major, the layout the layers use for their own intermediates
+    const size_t copy_bytes = spmm_copy_bytes(*A, f);
+    const float *src = B.ptr;
+    bool sliced = false;
+    if (copy_bytes > 0 && cv.used + copy_bytes + 256 <= ws_bytes) {
+        float *T = cv.take<float>(copy_bytes / sizeof(float));
+        SENSEI_TRY(launch_to_slices(nullptr, B.ptr, B.ld, A->n_cols, f, T, as_stream(stream)));
+        src = T;
+        sliced = true;
+    }
+    return hip_status(spmm_any(*A, mode, scaled ? r : nullptr, scaled ? c : nullptr, src, B.ld, f, C, ldc, f, activation, plan, carry,
+                                  as_stream(stream), &ctx->timers.spmm, false, nullptr, sliced));
 }
 
 int sensei_gemm(sensei_ctx *ctx, sensei_mat A, sensei_mat W, float *Y, int64_t ldy, int activation, void *stream) {
