@@ -863,6 +863,13 @@ __global__ __launch_bounds__(kBlock) void k_row_sum(NnzArgs a, const float *__re
     });
 }
 
+// value of x in another lane by a data-parallel-primitive move (no LDS traffic): quad permutations and the mirror of a
+// half row of eight lanes; every lane is active where this is used
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float x) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, false));
+}
+
 struct GatBwdArgs {
     NnzArgs n;
     const float *theta, *dP;  // slice-major (tiles of 32 columns): Theta over the source nodes, dP over the destinations
@@ -875,61 +882,75 @@ struct GatBwdArgs {
 };
 
 // dalpha_ij = <dP[i,:], Theta[j,:]> for every stored entry (the general g-SDDMM of Eq. 2 with a dot product as the
-// inner operator) together with the row sums sum_j alpha_ij dalpha_ij that the softmax backward needs.  Eight lanes
-// take one neighbour: each reads 16 bytes of every 128-byte slice of Theta_j and of dP_i, eight neighbours per step.
-// NT > 0: at most NT tiles, the row of dP is held in registers; NT == 0: any width, dP re-read per neighbour (L1 hits).
-template <int NT>
-__global__ __launch_bounds__(kBlock) void k_gat_dalpha(GatBwdArgs a) {
+// inner operator) together with the row sums sum_j alpha_ij dalpha_ij that the softmax backward needs.  One launch per
+// 32-column slice: every wavefront of the GPU then gathers from the same contiguous slice of Theta (as the SpMM keeps
+// one slice per L2), eight lanes take one neighbour (16 bytes of its 128-byte line each), eight neighbours per step,
+// and the lane that owns an entry adds the slice's share to dalpha[k] - launches follow each other on the stream, so
+// no atomics.  The last launch sees the complete dot products and forms the row sums.
+__global__ __launch_bounds__(kBlock) void k_gat_dalpha(GatBwdArgs a, int tile, int first, int last) {
     const int chunk = wave_chunk();
     if (chunk >= a.n.n_chunks) return;
     const int lane = threadIdx.x & 63;
     const int g = lane >> 3, sub = lane & 7;
-    reduce_rows(a.n, chunk, lane, a.rowdot, a.carry, [&](int i, int lo, int hi) {
+    const float *theta = a.theta + (size_t)tile * a.theta_tile + sub * 4;
+    const float *dP = a.dP + (size_t)tile * a.dp_tile + sub * 4;
+    auto piece = [&](int i, int lo, int hi) {
         const float2 st = a.mz[i];
         const float m = st.x, iz = inv_z(st.y);
-        const float *dp = a.dP + (size_t)i * 32 + sub * 4;
-        float4 dpr[NT > 0 ? NT : 1];
-        if (NT > 0) {
-#pragma unroll
-            for (int t = 0; t < NT; ++t)
-                dpr[t] = t < a.n_tiles ? *reinterpret_cast<const float4 *>(dp + (size_t)t * a.dp_tile) : make_float4(0.f, 0.f, 0.f, 0.f);
-        }
+        const float4 p = *reinterpret_cast<const float4 *>(dP + (size_t)i * 32);
         float s = 0.f;
-        for (int k0 = lo; k0 < hi; k0 += 8) {
-            const int k = k0 + g;
-            const bool ok = k < hi;
-            const int j = a.n.col_idx[ok ? k : lo];
-            const float *th = a.theta + (size_t)j * 32 + sub * 4;
-            float d = 0.f;
-            if (NT > 0) {
-                float4 b[NT > 0 ? NT : 1];
+        // column indices: 64 per batch, one per lane, fetched one batch ahead and handed to the groups by cross-lane
+        // reads, so a gather never waits for its index; eight steps of eight neighbours are in flight
+        int col_next = a.n.col_idx[lo + lane < hi ? lo + lane : lo];
+        for (int k0 = lo; k0 < hi; k0 += 64) {
+            const int col = col_next;
+            const int kn = k0 + 64 + lane;
+            col_next = a.n.col_idx[kn < hi ? kn : lo];
+            float4 b[8];
 #pragma unroll
-                for (int t = 0; t < NT; ++t)
-                    if (t < a.n_tiles) b[t] = *reinterpret_cast<const float4 *>(th + (size_t)t * a.theta_tile);
-#pragma unroll
-                for (int t = 0; t < NT; ++t)
-                    if (t < a.n_tiles) {
-                        d = fmaf(b[t].x, dpr[t].x, d); d = fmaf(b[t].y, dpr[t].y, d);
-                        d = fmaf(b[t].z, dpr[t].z, d); d = fmaf(b[t].w, dpr[t].w, d);
-                    }
-            } else {
-#pragma unroll 4
-                for (int t = 0; t < a.n_tiles; ++t) {
-                    const float4 b = *reinterpret_cast<const float4 *>(th + (size_t)t * a.theta_tile);
-                    const float4 p = *reinterpret_cast<const float4 *>(dp + (size_t)t * a.dp_tile);
-                    d = fmaf(b.x, p.x, d); d = fmaf(b.y, p.y, d); d = fmaf(b.z, p.z, d); d = fmaf(b.w, p.w, d);
-                }
+            for (int u = 0; u < 8; ++u) {
+                const int j = lane_read((u * 8 + g) * 4, col);
+                b[u] = *reinterpret_cast<const float4 *>(theta + (size_t)j * 32);
             }
-            d += __shfl_xor(d, 1, 64);
-            d += __shfl_xor(d, 2, 64);
-            d += __shfl_xor(d, 4, 64);
-            if (ok && sub == 0) {
-                a.dalpha[k] = d;
-                s = fmaf(expf(a.logits[k] - m) * iz, d, s);
+            // lane (g, sub) owns entry k0 + sub * 8 + g: one coalesced 256-byte access per 64 entries
+            const int k_own = k0 + sub * 8 + g;
+            const bool own = k_own < hi;
+            float v = (own && !first) ? a.dalpha[k_own] : 0.f;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                float d = fmaf(b[u].x, p.x, fmaf(b[u].y, p.y, fmaf(b[u].z, p.z, b[u].w * p.w)));
+                d += dpp_f32<0xB1>(d);   // lane ^ 1 within each quad
+                d += dpp_f32<0x4E>(d);   // lane ^ 2 within each quad
+                d += dpp_f32<0x141>(d);  // the other quad of the eight (mirror within the half row)
+                if (sub == u) v += d;    // every lane of the group holds the sum; the owner keeps it
+            }
+            if (own) {
+                a.dalpha[k_own] = v;
+                if (last) s = fmaf(expf(a.logits[k_own] - m) * iz, v, s);
             }
         }
         return s;
-    });
+    };
+    if (last) {
+        reduce_rows(a.n, chunk, lane, a.rowdot, a.carry, piece);
+    } else {  // same walk, row sums not needed yet
+        const long long lo_ll = (long long)chunk * a.n.chunk_nnz;
+        const int lo = (int)lo_ll;
+        const int hi = (int)((lo_ll + a.n.chunk_nnz < (long long)a.n.nnz) ? lo_ll + a.n.chunk_nnz : (long long)a.n.nnz);
+        if (lo >= hi) return;
+        const int i0 = a.n.chunk_row[chunk];
+        int i = __builtin_amdgcn_readfirstlane((a.n.row_ptr[i0] > lo) ? i0 - 1 : i0);
+        int pos = lo;
+        while (pos < hi) {
+            const int re = __builtin_amdgcn_readfirstlane(a.n.row_ptr[i + 1]);
+            if (re > pos) {
+                const int seg_hi = re < hi ? re : hi;
+                (void)piece(i, pos, seg_hi);
+                pos = seg_hi;
+            }
+            i = __builtin_amdgcn_readfirstlane(i + 1);
+        }
+    }
 }
 
 struct GatDtArgs {
@@ -1257,10 +1278,8 @@ hipError_t launch_gat_dalpha(const sensei_csr &A, const float *theta, const floa
     a.dp_tile = (long long)(A.n_rows > 0 ? A.n_rows : 1) * 32;
     a.n_tiles = (f + 31) / 32;
     const dim3 grid(blocks_for(p.n_chunks, kWavesPerBlock));
-    if (a.n_tiles <= 2) hipLaunchKernelGGL((k_gat_dalpha<2>), grid, dim3(kBlock), 0, s, a);
-    else if (a.n_tiles <= 4) hipLaunchKernelGGL((k_gat_dalpha<4>), grid, dim3(kBlock), 0, s, a);
-    else if (a.n_tiles <= 8) hipLaunchKernelGGL((k_gat_dalpha<8>), grid, dim3(kBlock), 0, s, a);
-    else hipLaunchKernelGGL((k_gat_dalpha<0>), grid, dim3(kBlock), 0, s, a);
+    for (int t = 0; t < a.n_tiles; ++t)
+        hipLaunchKernelGGL(k_gat_dalpha, grid, dim3(kBlock), 0, s, a, t, t == 0 ? 1 : 0, t == a.n_tiles - 1 ? 1 : 0);
     if (p.n_chunks > 1) hipLaunchKernelGGL(k_sum_fixup, dim3(blocks_for(p.n_chunks - 1, kBlock)), dim3(kBlock), 0, s, a.n, rowdot, carry);
     return hipGetLastError();
 }
