@@ -48,7 +48,8 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="c2_rmat233k", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-sweep", action="store_true", help="skip timing every composition id")
+    ap.add_argument("--no-sweep", action="store_true", help="skip timing every composition id (and, unless --backward, the backward pass)")
+    ap.add_argument("--backward", action="store_true", help="time the backward pass even with --no-sweep")
     ap.add_argument("--no-panels", action="store_true", help="do not build the column-panel copy of the graph")
     ap.add_argument("--panels", type=int, default=0, help="force the number of column panels (0 = let the library measure)")
     ap.add_argument("--no-gather-probe", action="store_true", help="skip the L2-resident gather probe")
@@ -275,7 +276,7 @@ def main():
                                   "overhead_in_layers": round(dt / detail["layers"][tag(0)]["ms"], 2)}
 
     # ---- training: backward of the GCN layers in both associations (symmetric pattern: it is its own transpose)
-    if not args.no_sweep:
+    if not args.no_sweep or args.backward:
         bwd = {}
         for i, L in enumerate(layers):
             if L["kind"] != "gcn":
@@ -308,7 +309,7 @@ def main():
 
     # ---- one training iteration of the GCN stack of the workload (the layers whose input is X or the previous layer):
     # forward with the selected compositions, backward with the associations the cost model picks; the first layer needs no dX
-    if not args.no_sweep:
+    if not args.no_sweep or args.backward:
         chain = [i for i, L in enumerate(layers) if L["kind"] == "gcn" and (L["src"] == "X" or L["src"] in (-1, i - 1))]
         chain = chain[:2] if len(chain) >= 2 and layers[chain[1]]["src"] in (-1, chain[0]) else chain[:1]
         bwd_pick = {i: ctx.select_gcn_backward(A, layers[i]["f_in"], layers[i]["f_out"], want_dx=(i != chain[0]))[0] for i in chain}

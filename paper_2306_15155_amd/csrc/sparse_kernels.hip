@@ -550,9 +550,10 @@ __global__ void k_to_slices(const float *__restrict__ s, const float *__restrict
 // ------------------------------------------------------------- edge softmax
 
 // (m, z) pairs: z = sum of exp(e - m).  Merge keeps m the larger maximum.
-__device__ __forceinline__ void mz_add(float &m, float &z, float e) {
-    if (e > m) { z = z * expf(m - e) + 1.f; m = e; }
-    else z += expf(e - m);
+__device__ __forceinline__ void mz_add(float &m, float &z, float e) {  // e finite; branch-free: lanes of a wavefront disagree on e > m
+    const float mm = e > m ? e : m;
+    z = z * __expf(m - mm) + __expf(e - mm);  // m = -inf at the start: exp(-inf) = 0 and z = 0
+    m = mm;
 }
 __device__ __forceinline__ void mz_merge(float &m, float &z, float m2, float z2) {
     const float mm = m > m2 ? m : m2;
