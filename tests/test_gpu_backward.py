@@ -193,3 +193,46 @@ def test_backward_degenerate_cases(ctx, case):
         assert_close(gpu, ref, what=f"{case} gat {what}")
     if case == "no_entries":
         assert float(got[1].abs().max()) == 0.0 and float(dW.abs().max()) == 0.0
+
+
+def test_backward_can_be_captured_in_a_hip_graph(ctx):
+    """The backward calls only enqueue kernels (fill kernels instead of memsets, no allocation of their own, no
+    synchronisation): a captured training step replays to the same bits as the eager run, every time."""
+    g = synth.rmat(95, 4000, 90_000)
+    A = DeviceCSR(g)
+    dr, dc = ctx.degrees(A.s)
+    r, c = ctx.norm_vectors(dr), ctx.norm_vectors(dc)
+    f_in, f_out = 48, 40
+    X, W, dY = (dev(t) for t in _inputs(g, f_in, f_out, 96))
+    a_l, a_r = dev(synth.normal(96, 20, (f_out,), 0.0, 0.3)), dev(synth.normal(96, 21, (f_out,), 0.0, 0.3))
+    pos = ctx.transpose_positions(A.s, A.s)
+    Y = ctx.gcn_layer(A.s, r, c, X, W, 3, ACT_RELU)
+
+    def step():
+        out = list(ctx.gcn_backward(A.s, A.s, r, c, X, W, dY, GCN_BWD_AGG, Y=Y, activation=ACT_RELU))
+        out += list(ctx.gcn_backward(A.s, A.s, r, c, X, W, dY, GCN_BWD_UPD, Y=Y, activation=ACT_RELU))
+        out += list(ctx.gat_backward(A.s, A.s, pos, X, W, a_l, a_r, dY))
+        return out
+
+    want = [t.clone() for t in step()]  # also sizes the workspace before capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    with torch.cuda.graph(graph):
+        got = step()
+    for rep in range(3):
+        for t in got:
+            t.fill_(-7.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(got, want):
+            assert torch.equal(a, b), f"replay {rep}"
+        eager = step()  # eager work between replays
+        torch.cuda.synchronize()
+        for a, b in zip(eager, want):
+            assert torch.equal(a, b)
