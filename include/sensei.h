@@ -263,6 +263,15 @@ int sensei_gat_layer(sensei_ctx *ctx, const sensei_csr *A, sensei_mat X, sensei_
                      const float *a_r, float neg_slope, float *Y, int64_t ldy, int activation, int comp_id,
                      void *workspace, size_t ws_bytes, void *stream);
 
+/* Multi-head GAT layer, heads concatenated: W is f_in x (n_heads * d) with head h in columns [h d, (h + 1) d), a_l and
+ * a_r hold n_heads * d entries laid out the same way, Y is n_rows x (n_heads * d).  Every head is the single-head layer
+ * above on its d columns of Theta = X.W (its own logits, softmax and aggregation); Theta is formed by one GEMM for all
+ * heads.  comp_id as for sensei_gat_layer; the workspace is that of sensei_gat_workspace for f_out = n_heads * d.
+ * n_heads must divide W.cols. */
+int sensei_gat_layer_heads(sensei_ctx *ctx, const sensei_csr *A, sensei_mat X, sensei_mat W, const float *a_l, const float *a_r,
+                           int n_heads, float neg_slope, float *Y, int64_t ldy, int activation, int comp_id, void *workspace,
+                           size_t ws_bytes, void *stream);
+
 /* --------------------------------------------------------------------- selector */
 
 enum { SENSEI_SELECT_MODEL = 0, SENSEI_SELECT_TIMED = 1, SENSEI_SELECT_LEARNED = 2 };

@@ -193,6 +193,17 @@ def gat_layer(n_rows, n_cols, row_ptr, col_idx, X, W, a_l, a_r, slope=0.2, act=0
     return Y
 
 
+def gat_layer_heads(n_rows, n_cols, row_ptr, col_idx, X, W, a_l, a_r, n_heads, slope=0.2, act=0, rows=None, omp=False):
+    """Multi-head GAT with concatenated heads: head h is the single-head layer of Eq. 5 / 6 on columns
+    [h d, (h + 1) d) of W, a_l, a_r (heads share nothing but the input)."""
+    W, a_l, a_r = _f32(W), _f32(a_l), _f32(a_r)
+    assert W.shape[1] % n_heads == 0
+    d = W.shape[1] // n_heads
+    return np.concatenate([gat_layer(n_rows, n_cols, row_ptr, col_idx, X, np.ascontiguousarray(W[:, h * d:(h + 1) * d]),
+                                     a_l[h * d:(h + 1) * d], a_r[h * d:(h + 1) * d], slope, act, rows=rows, omp=omp)
+                           for h in range(n_heads)], axis=1)
+
+
 def gcn_backward(n_rows, n_cols, row_ptr, col_idx, X, W, dY, Y=None, act=0, rows=None, want_dw=True, omp=False, with_dz=False):
     """Gradient of sum(dY * Y) for the GCN layer (chain rule on Eq. 3) -> (dX, dW).
 

@@ -325,11 +325,15 @@ int run_gcn_backward(const sensei_csr &A, const sensei_csr &At, const float *r, 
     return SENSEI_OK;
 }
 
+// n_heads > 1: W holds the heads side by side (head h = columns [h d, (h + 1) d), d = f_out / n_heads), a_l / a_r likewise,
+// Y is their concatenation; Theta = X.W is formed by one GEMM for all heads, everything after it runs head by head on the
+// head's columns (its own logits, statistics and aggregation), reusing the same buffers.
 int run_gat(const sensei_csr &A, const sensei_mat &X, const sensei_mat &W, const float *a_l, const float *a_r,
-            float slope, float *Y, int64_t ldy, int act, int id, void *ws, size_t ws_bytes, hipStream_t s, Timers *tm) {
+            float slope, float *Y, int64_t ldy, int act, int id, void *ws, size_t ws_bytes, hipStream_t s, Timers *tm, int n_heads = 1) {
     KernelTimer *kt = tm ? &tm->spmm : nullptr, *gt = tm ? &tm->gemm : nullptr;
     const int f_in = (int)X.cols, f_out = (int)W.cols;
     const int fo = pad32(f_out), fi = pad4(f_in);
+    const int d = f_out / n_heads;
     Carver cv(ws, ws_bytes);
     ChunkPlan plan = make_plan(A, cv);
     float2 *stats = cv.take<float2>((size_t)A.n_rows + 1);
@@ -344,38 +348,51 @@ int run_gat(const sensei_csr &A, const sensei_mat &X, const sensei_mat &W, const
 
     SENSEI_TRY(launch_chunk_rows(A, plan, s));
     const bool fold = (id == SENSEI_GAT_RECOMP_FOLD || id == SENSEI_GAT_REUSE_FOLD);
-    const bool theta_sliced = gat_is_reuse(id);
-    if (!fold) {  // Theta = X.W, then the two projections of Theta
-        // Theta is slice-major when the SpMM gathers from it (reuse); the recompute id only projects it
-        SENSEI_TRY(launch_gemm(X.ptr, X.ld, W.ptr, W.ld, theta, fo, A.n_cols, f_in, f_out, fo, SENSEI_ACT_NONE, s, nullptr, gt, theta_sliced));
-        SENSEI_TRY(launch_gemv2(theta, fo, A.n_cols, f_out, a_l, a_r, s_l, s_r, s, theta_sliced));
-    } else {      // (X.W).a = X.(W.a)
-        SENSEI_TRY(launch_gemv2(W.ptr, W.ld, f_in, f_out, a_l, a_r, v_l, v_r, s));
-        SENSEI_TRY(launch_gemv2(X.ptr, X.ld, A.n_cols, f_in, v_l, v_r, s_l, s_r, s));
-    }
-    // One pass computes the logits and the per-row softmax statistics; the aggregation then weighs each neighbour
-    // by exp(e - max) and scales the row by 1 / sum, so the attention weights themselves are never stored.  With a
-    // panel copy the logits are written straight in panel order and the SpMM follows the panels.
-    const bool by_panel = panels_usable(A, gat_is_reuse(id) ? fo : f_in);
-    SENSEI_TRY(launch_attention_stats(A, s_l, s_r, slope, logits, by_panel ? A.panels->position : nullptr, plan, stats, carry_stats, s));
-    sensei_csr Aw = A;
-    Aw.val = logits;
-    if (gat_is_reuse(id)) {
-        if (fold) SENSEI_TRY(launch_gemm(X.ptr, X.ld, W.ptr, W.ld, theta, fo, A.n_cols, f_in, f_out, fo, SENSEI_ACT_NONE, s, nullptr, gt, true));
-        float *carry = cv.take<float>(spmm_carry_bytes(A.nnz, fo) / sizeof(float));
-        SENSEI_TRY(spmm_any(Aw, kSpmmSoftmax, nullptr, nullptr, theta, fo, fo, Y, ldy, f_out, act, plan, carry, s, kt, by_panel, stats, true));
-    } else {
-        float *carry = cv.take<float>(spmm_carry_bytes(A.nnz, fi) / sizeof(float));
-        float *U = cv.take<float>((size_t)A.n_rows * fi);
-        const float *src = X.ptr;
-        const bool sliced = relayout_pays(A);
-        if (sliced) {
+    const bool reuse = gat_is_reuse(id);
+    // Theta is slice-major when the SpMM gathers from it (reuse) and a head's columns are whole 32-column slices; the
+    // recompute id only projects it
+    const bool theta_sliced = reuse && (n_heads == 1 || d % 32 == 0);
+    if (theta) SENSEI_TRY(launch_gemm(X.ptr, X.ld, W.ptr, W.ld, theta, fo, A.n_cols, f_in, f_out, fo, SENSEI_ACT_NONE, s, nullptr, gt, theta_sliced));
+    // recompute ids gather from X: slice-major copy once for all heads when its rows are gathered often enough
+    float *carry = cv.take<float>(spmm_carry_bytes(A.nnz, reuse ? fo : fi) / sizeof(float));
+    float *U = nullptr;
+    const float *x_src = X.ptr;
+    bool x_sliced = false;
+    if (!reuse) {
+        U = cv.take<float>((size_t)A.n_rows * fi);
+        x_sliced = relayout_pays(A);
+        if (x_sliced) {
             float *T = cv.take<float>((size_t)A.n_cols * pad32(f_in));
             SENSEI_TRY(launch_to_slices(nullptr, X.ptr, X.ld, A.n_cols, f_in, T, s));
-            src = T;
+            x_src = T;
         }
-        SENSEI_TRY(spmm_any(Aw, kSpmmSoftmax, nullptr, nullptr, src, X.ld, f_in, U, fi, f_in, SENSEI_ACT_NONE, plan, carry, s, kt, by_panel, stats, sliced));
-        SENSEI_TRY(launch_gemm(U, fi, W.ptr, W.ld, Y, ldy, A.n_rows, f_in, f_out, f_out, act, s, nullptr, gt));
+    }
+    const int f_gather = reuse ? (n_heads == 1 ? fo : d) : f_in;  // width of the aggregation of one head
+    const bool by_panel = panels_usable(A, f_gather);
+    for (int h = 0; h < n_heads; ++h) {
+        const float *al = a_l + (size_t)h * d, *ar = a_r + (size_t)h * d;
+        const float *theta_h = !theta ? nullptr : theta_sliced ? theta + (size_t)h * (d / 32) * (size_t)A.n_cols * 32 : theta + (size_t)h * d;
+        if (!fold) {  // the two projections of the head's columns of Theta
+            SENSEI_TRY(launch_gemv2(theta_h, fo, A.n_cols, d, al, ar, s_l, s_r, s, theta_sliced));
+        } else {      // (X.W).a = X.(W.a)
+            SENSEI_TRY(launch_gemv2(W.ptr + (size_t)h * d, W.ld, f_in, d, al, ar, v_l, v_r, s));
+            SENSEI_TRY(launch_gemv2(X.ptr, X.ld, A.n_cols, f_in, v_l, v_r, s_l, s_r, s));
+        }
+        // One pass computes the logits and the per-row softmax statistics; the aggregation then weighs each neighbour
+        // by exp(e - max) and scales the row by 1 / sum, so the attention weights themselves are never stored.  With a
+        // panel copy the logits are written straight in panel order and the SpMM follows the panels.
+        SENSEI_TRY(launch_attention_stats(A, s_l, s_r, slope, logits, by_panel ? A.panels->position : nullptr, plan, stats, carry_stats, s));
+        sensei_csr Aw = A;
+        Aw.val = logits;
+        float *Y_h = Y + (size_t)h * d;
+        if (reuse) {
+            SENSEI_TRY(spmm_any(Aw, kSpmmSoftmax, nullptr, nullptr, theta_h, fo, f_gather, Y_h, ldy, d, act, plan, carry, s, kt, by_panel, stats,
+                                theta_sliced));
+        } else {
+            SENSEI_TRY(spmm_any(Aw, kSpmmSoftmax, nullptr, nullptr, x_src, X.ld, f_in, U, fi, f_in, SENSEI_ACT_NONE, plan, carry, s, kt, by_panel, stats,
+                                x_sliced));
+            SENSEI_TRY(launch_gemm(U, fi, W.ptr + (size_t)h * d, W.ld, Y_h, ldy, A.n_rows, f_in, d, d, act, s, nullptr, gt));
+        }
     }
     return SENSEI_OK;
 }
@@ -1143,14 +1160,15 @@ int sensei_gat_workspace(const sensei_csr *A, int f_in, int f_out, int comp_id, 
     return SENSEI_OK;
 }
 
-int sensei_gat_layer(sensei_ctx *ctx, const sensei_csr *A, sensei_mat X, sensei_mat W, const float *a_l, const float *a_r,
-                     float neg_slope, float *Y, int64_t ldy, int activation, int comp_id, void *workspace, size_t ws_bytes,
-                     void *stream) {
+int sensei_gat_layer_heads(sensei_ctx *ctx, const sensei_csr *A, sensei_mat X, sensei_mat W, const float *a_l, const float *a_r,
+                           int n_heads, float neg_slope, float *Y, int64_t ldy, int activation, int comp_id, void *workspace,
+                           size_t ws_bytes, void *stream) {
     if (comp_id < 0 || comp_id >= kNumGat) return SENSEI_INVALID_COMPOSITION;
     if (!ctx || !csr_ok(A, false) || !mat_ok(X) || !mat_ok(W)) return SENSEI_INVALID_ARGUMENT;
     if (activation != SENSEI_ACT_NONE && activation != SENSEI_ACT_RELU) return SENSEI_INVALID_ARGUMENT;
     if (A->n_rows > A->n_cols) return SENSEI_INVALID_ARGUMENT;
     if (X.rows != A->n_cols || X.cols != W.rows || X.cols <= 0 || W.cols <= 0 || ldy < W.cols) return SENSEI_INVALID_ARGUMENT;
+    if (n_heads < 1 || W.cols % n_heads != 0) return SENSEI_INVALID_ARGUMENT;
     if (X.cols > (1 << 20) || W.cols > (1 << 20)) return SENSEI_INVALID_ARGUMENT;
     if (!X.ptr && A->n_cols > 0) return SENSEI_INVALID_ARGUMENT;
     if (!W.ptr || !a_l || !a_r || (!Y && A->n_rows > 0) || !workspace) return SENSEI_INVALID_ARGUMENT;
@@ -1160,7 +1178,13 @@ int sensei_gat_layer(sensei_ctx *ctx, const sensei_csr *A, sensei_mat X, sensei_
         return SENSEI_INVALID_ARGUMENT;
     if (ws_bytes < gat_ws(*A, (int)X.cols, (int)W.cols, comp_id)) return SENSEI_WORKSPACE_TOO_SMALL;
     if (A->n_rows == 0) return SENSEI_OK;
-    return run_gat(*A, X, W, a_l, a_r, neg_slope, Y, ldy, activation, comp_id, workspace, ws_bytes, as_stream(stream), &ctx->timers);
+    return run_gat(*A, X, W, a_l, a_r, neg_slope, Y, ldy, activation, comp_id, workspace, ws_bytes, as_stream(stream), &ctx->timers, n_heads);
+}
+
+int sensei_gat_layer(sensei_ctx *ctx, const sensei_csr *A, sensei_mat X, sensei_mat W, const float *a_l, const float *a_r,
+                     float neg_slope, float *Y, int64_t ldy, int activation, int comp_id, void *workspace, size_t ws_bytes,
+                     void *stream) {
+    return sensei_gat_layer_heads(ctx, A, X, W, a_l, a_r, 1, neg_slope, Y, ldy, activation, comp_id, workspace, ws_bytes, stream);
 }
 
 int sensei_select_workspace(int kind, const sensei_csr *A, int f_in, int f_out, size_t *bytes) {

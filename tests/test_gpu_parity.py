@@ -469,3 +469,47 @@ def test_panels_min_width_and_measured_choice(ctx):
     B = synth.uniform(24, 32, (g2.n_cols, 128))
     assert_close(ctx.spmm(A2p, SPMM_PATTERN, dev(B)), oracle.spmm(g2.row_ptr, g2.col_idx, None, B), what="measured panels")
     T.close()
+
+
+# ------------------------------------------------------------------ multi-head attention
+
+@pytest.mark.parametrize("name", ["er", "rmat_hub", "hub_empty", "rect"])
+@pytest.mark.parametrize("shape", [(40, 4, 8), (24, 2, 32), (96, 3, 64), (50, 5, 9)])   # f_in, heads, width per head
+def test_multi_head_gat_is_the_single_head_layer_per_head(ctx, name, shape):
+    g = GRAPHS[name]
+    f_in, heads, d = shape
+    X, W = synth.uniform(33, 10, (g.n_cols, f_in)), synth.glorot(33, 11, f_in, heads * d)
+    a_l, a_r = synth.normal(33, 12, (heads * d,), 0.0, 0.4), synth.normal(33, 13, (heads * d,), 0.0, 0.4)
+    ref = oracle.gat_layer_heads(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, a_l, a_r, heads, 0.2, ACT_RELU)
+    A = DeviceCSR(g)
+    for cid in range(4):
+        got = ctx.gat_layer_heads(A.s, dev(X), dev(W), dev(a_l), dev(a_r), heads, cid, 0.2, ACT_RELU)
+        assert_close(got, ref, what=f"{heads} heads comp {cid}")
+    # one head of full width is the plain layer
+    one = ctx.gat_layer_heads(A.s, dev(X), dev(W), dev(a_l), dev(a_r), 1, 0, 0.2, ACT_RELU)
+    assert torch.equal(one, ctx.gat_layer(A.s, dev(X), dev(W), dev(a_l), dev(a_r), 0, 0.2, ACT_RELU))
+
+
+def test_multi_head_gat_over_column_panels_and_bad_head_counts(ctx):
+    from paper_2306_15155_amd import Panels, SenseiError, csr_struct
+    g = synth.rmat(34, 6000, 120_000)
+    A = DeviceCSR(g)
+    P = Panels(ctx, A.s, 3)
+    P_ok = binding_set_min_width(P, 32)
+    Ap = csr_struct(g.n_rows, g.n_cols, A.row_ptr, A.col_idx, None, P)
+    X, W = synth.uniform(34, 10, (g.n_cols, 72)), synth.glorot(34, 11, 72, 4 * 64)
+    a_l, a_r = synth.normal(34, 12, (256,), 0.0, 0.4), synth.normal(34, 13, (256,), 0.0, 0.4)
+    ref = oracle.gat_layer_heads(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, a_l, a_r, 4)
+    for cid in range(4):
+        assert_close(ctx.gat_layer_heads(Ap, dev(X), dev(W), dev(a_l), dev(a_r), 4, cid), ref, what=f"panels comp {cid}")
+    with pytest.raises(SenseiError):
+        ctx.gat_layer_heads(A.s, dev(X), dev(W), dev(a_l), dev(a_r), 3, 0)   # 3 does not divide 256
+    with pytest.raises(SenseiError):
+        ctx.gat_layer_heads(A.s, dev(X), dev(W), dev(a_l), dev(a_r), 0, 0)
+    assert P_ok
+    P.close()
+
+
+def binding_set_min_width(P, width):
+    from paper_2306_15155_amd import binding
+    return binding.lib().sensei_panels_set_min_width(P._h, width) == 0

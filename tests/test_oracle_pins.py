@@ -300,3 +300,22 @@ def test_embedding_size_rules(golden_dir):
     assert oracle.select_rules("gat", 256, 64) == (0,)
     assert oracle.select_rules("gat", 64, 64) == (0,)
     assert {0, 1} <= set(oracle.select_rules("gat", 64, 256))
+
+
+def test_multi_head_gat_is_head_wise_and_matches_the_dense_definition():
+    g = _rand_graph(17, 40, 120)
+    rng = np.random.default_rng(17)
+    X = rng.standard_normal((40, 6)).astype(np.float32)
+    W = rng.standard_normal((6, 12)).astype(np.float32)
+    a_l, a_r = rng.standard_normal(12).astype(np.float32), rng.standard_normal(12).astype(np.float32)
+    Y = oracle.gat_layer_heads(40, 40, g.row_ptr, g.col_idx, X, W, a_l, a_r, 3, 0.2, 1)
+    A = dense.dense_pattern(40, 40, g.row_ptr, g.col_idx)
+    for h in range(3):
+        sl = slice(4 * h, 4 * h + 4)
+        _close(Y[:, sl], dense.gat_layer_dense(A, X, W[:, sl], a_l[sl], a_r[sl], 0.2, 1))
+    _close(oracle.gat_layer_heads(40, 40, g.row_ptr, g.col_idx, X, W, a_l, a_r, 1), oracle.gat_layer(40, 40, g.row_ptr, g.col_idx, X, W, a_l, a_r))
+    # heads do not see each other: changing head 2 leaves heads 0 and 1 alone
+    W2 = W.copy(); W2[:, 8:] *= -3.0
+    Y2 = oracle.gat_layer_heads(40, 40, g.row_ptr, g.col_idx, X, W2, a_l, a_r, 3, 0.2, 1)
+    _close(Y2[:, :8], Y[:, :8])
+    assert np.max(np.abs(Y2[:, 8:] - Y[:, 8:])) > 1e-3
