@@ -312,7 +312,7 @@ def test_multi_head_gat_is_head_wise_and_matches_the_dense_definition():
     A = dense.dense_pattern(40, 40, g.row_ptr, g.col_idx)
     for h in range(3):
         sl = slice(4 * h, 4 * h + 4)
-        _close(Y[:, sl], dense.gat_layer_dense(A, X, W[:, sl], a_l[sl], a_r[sl], 0.2, 1))
+        _close(Y[:, sl], dense.gat_layer_dense(A, X, W[:, sl], a_l[sl], a_r[sl], 0.2, 1)[0])
     _close(oracle.gat_layer_heads(40, 40, g.row_ptr, g.col_idx, X, W, a_l, a_r, 1), oracle.gat_layer(40, 40, g.row_ptr, g.col_idx, X, W, a_l, a_r))
     # heads do not see each other: changing head 2 leaves heads 0 and 1 alone
     W2 = W.copy(); W2[:, 8:] *= -3.0
