@@ -193,6 +193,18 @@ def gat_layer(n_rows, n_cols, row_ptr, col_idx, X, W, a_l, a_r, slope=0.2, act=0
     return Y
 
 
+def sgc_layer(n, row_ptr, col_idx, X, W, k_hops, act=0):
+    """K-hop simplified graph convolution act(A^^k X W), A^ = D^-1/2 A~ D^-1/2 as in Eq. 3, on a square pattern:
+    k propagations (column scaling, neighbour sum of Eq. 1, row scaling) followed by the update."""
+    row_ptr, col_idx = _i32(row_ptr), _i32(col_idx)
+    dr, dc = degrees(n, n, row_ptr, col_idx)
+    r, c = inv_sqrt_deg(dr), inv_sqrt_deg(dc)
+    H = _f32(X).astype(np.float64)
+    for _ in range(k_hops):
+        H = row_broadcast(r, spmm(row_ptr, col_idx, None, row_broadcast(c, H)))
+    return activation(gemm(H, _f32(W).astype(np.float64)), act)
+
+
 def gat_layer_heads(n_rows, n_cols, row_ptr, col_idx, X, W, a_l, a_r, n_heads, slope=0.2, act=0, rows=None, omp=False):
     """Multi-head GAT with concatenated heads: head h is the single-head layer of Eq. 5 / 6 on columns
     [h d, (h + 1) d) of W, a_l, a_r (heads share nothing but the input)."""
@@ -231,7 +243,7 @@ def gcn_backward(n_rows, n_cols, row_ptr, col_idx, X, W, dY, Y=None, act=0, rows
 
 
 def gat_backward(n_rows, n_cols, row_ptr, col_idx, X, W, a_l, a_r, dY, Y=None, slope=0.2, act=0, omp=False, with_dtheta=False):
-    """Gradient of sum(dY * Y) for the GAT layer (chain rule on Eq. 5 / 6) -> (dX, dW, da_l, da_r[, dTheta])."""
+    """Gradient of sum(dY * Y) for the GAT layer (chain rule on Eq. 5 / 6) -> (dX, dW, da_l, da_r[, dTheta, ds_l, ds_r])."""
     row_ptr, col_idx, X, W, a_l, a_r, dY = _i32(row_ptr), _i32(col_idx), _f32(X), _f32(W), _f32(a_l), _f32(a_r), _f32(dY)
     F_in, F_out = W.shape
     assert X.shape == (n_cols, F_in) and dY.shape == (n_rows, F_out)
@@ -242,12 +254,14 @@ def gat_backward(n_rows, n_cols, row_ptr, col_idx, X, W, a_l, a_r, dY, Y=None, s
     dW = np.empty((F_in, F_out), dtype=np.float64)
     dal, dar = np.empty(F_out, dtype=np.float64), np.empty(F_out, dtype=np.float64)
     dTh = np.empty((n_cols, F_out), dtype=np.float64) if with_dtheta else None
+    ds = np.empty(2 * n_cols, dtype=np.float64) if with_dtheta else None
     rc = _lib(omp).orc_gat_backward(I32(n_rows), I32(n_cols), _p(row_ptr), _p(col_idx), _p(X), I64(F_in), I32(F_in), _p(W), I64(F_out),
                                    I32(F_out), _p(a_l), _p(a_r), DBL(slope), _p(Y) if act == 1 else None, I64(F_out), _p(dY),
-                                   I64(F_out), ctypes.c_int(act), _p(dX), _p(dW), _p(dal), _p(dar), None if dTh is None else _p(dTh))
+                                   I64(F_out), ctypes.c_int(act), _p(dX), _p(dW), _p(dal), _p(dar), None if dTh is None else _p(dTh),
+                                   None if ds is None else _p(ds))
     if rc != 0:
         raise RuntimeError(f"oracle gat_backward failed ({rc})")
-    return (dX, dW, dal, dar, dTh) if with_dtheta else (dX, dW, dal, dar)
+    return (dX, dW, dal, dar, dTh, ds[:n_cols], ds[n_cols:]) if with_dtheta else (dX, dW, dal, dar)
 
 
 # ------------------------------------------------------------- re-associations

@@ -475,12 +475,12 @@ int orc_gcn_backward(int32_t n_rows, int32_t n_cols, const int32_t *row_ptr, con
  *   da_l = Theta^T ds_l , da_r = Theta^T ds_r , dW = X^T dTheta , dX = dTheta W^T.
  * Square pattern only (destinations = the first n_rows sources, as in the
  * forward).  Outputs fp64: dX n_cols x F_in, dW F_in x F_out, da_l, da_r F_out; dTh_out (optional,
- * n_cols x F_out) receives dTheta. */
+ * n_cols x F_out) receives dTheta; ds_out (optional, 2 n_cols) receives ds_l then ds_r. */
 int orc_gat_backward(int32_t n_rows, int32_t n_cols, const int32_t *row_ptr, const int32_t *col_idx,
                      const float *X, int64_t ldx, int32_t F_in, const float *W, int64_t ldw, int32_t F_out,
                      const float *a_l, const float *a_r, double slope,
                      const float *Y, int64_t ldy, const float *dY, int64_t lddy, int act,
-                     double *dX, double *dW, double *da_l, double *da_r, double *dTh_out) {
+                     double *dX, double *dW, double *da_l, double *da_r, double *dTh_out, double *ds_out) {
     if (n_rows > n_cols) return 2;
     const int64_t nnz = row_ptr[n_rows];
     double *Th = (double *)malloc((size_t)n_cols * (size_t)F_out * sizeof(double) + 8);
@@ -580,6 +580,10 @@ int orc_gat_backward(int32_t n_rows, int32_t n_cols, const int32_t *row_ptr, con
             dTh[(int64_t)j * F_out + m] += dsl[j] * (double)a_l[m] + dsr[j] * (double)a_r[m];
         }
     if (dTh_out) memcpy(dTh_out, dTh, (size_t)n_cols * (size_t)F_out * sizeof(double));
+    if (ds_out) {
+        memcpy(ds_out, dsl, (size_t)n_cols * sizeof(double));
+        memcpy(ds_out + n_cols, dsr, (size_t)n_cols * sizeof(double));
+    }
     ORC_PAR
     for (int32_t f = 0; f < F_in; ++f)
         for (int32_t m = 0; m < F_out; ++m) {

@@ -208,6 +208,9 @@ def test_gat_backward_with_zero_attention_vectors_is_mean_aggregation():
     dt = 0.2 * de
     _close(dal, Th.T @ dt.sum(axis=1), 1e-11)
     _close(dar, Th.T @ dt.sum(axis=0), 1e-11)
+    ds_l, ds_r = oracle.gat_backward(15, 15, g.row_ptr, g.col_idx, X, W, z, z, dY, with_dtheta=True)[5:]
+    _close(ds_l, dt.sum(axis=1), 1e-11)                          # sixth and seventh results: gradients of s_l and s_r
+    _close(ds_r, dt.sum(axis=0), 1e-11)
 
 
 def test_backward_is_linear_in_the_upstream_gradient():

@@ -319,3 +319,37 @@ def test_multi_head_gat_is_head_wise_and_matches_the_dense_definition():
     Y2 = oracle.gat_layer_heads(40, 40, g.row_ptr, g.col_idx, X, W2, a_l, a_r, 3, 0.2, 1)
     _close(Y2[:, :8], Y[:, :8])
     assert np.max(np.abs(Y2[:, 8:] - Y[:, 8:])) > 1e-3
+
+
+# --------------------------------------------------------------- K-hop simplified graph convolution
+
+def test_sgc_is_the_matrix_power_and_one_hop_is_the_gcn_layer():
+    n = 60
+    g = _rand_graph(21, n, 200)
+    X = synth.uniform(21, 10, (n, 7))
+    W = synth.glorot(21, 11, 7, 5)
+    A = dense.dense_pattern(n, n, g.row_ptr, g.col_idx)
+    d = A.sum(axis=1)
+    dc = A.sum(axis=0)
+    Ahat = A / np.sqrt(d)[:, None] / np.sqrt(dc)[None, :]
+    XW = X.astype(np.float64) @ W.astype(np.float64)
+    for k in (1, 2, 3, 5):
+        ref = np.linalg.matrix_power(Ahat, k) @ XW
+        _close(oracle.sgc_layer(n, g.row_ptr, g.col_idx, X, W, k), ref, 1e-12)
+        _close(oracle.sgc_layer(n, g.row_ptr, g.col_idx, X, W, k, 1), np.maximum(ref, 0.0), 1e-12)
+    _close(oracle.sgc_layer(n, g.row_ptr, g.col_idx, X, W, 1, 1), oracle.gcn_layer(n, n, g.row_ptr, g.col_idx, X, W, 1), 1e-13)
+
+
+def test_sgc_on_a_regular_ring_keeps_constant_columns_and_smooths_the_rest():
+    n, kh = 48, 2
+    g = synth.ring_lattice(n, kh)
+    v = synth.uniform(22, 10, (1, 4))
+    W = synth.glorot(22, 11, 4, 3)
+    Y = oracle.sgc_layer(n, g.row_ptr, g.col_idx, np.repeat(v, n, axis=0), W, 4)
+    _close(Y, np.repeat(v.astype(np.float64) @ W.astype(np.float64), n, axis=0), 1e-13)
+    # the normalised ring operator is a circulant averaging filter: mode m is scaled by (1 + 2 sum_t cos(2 pi m t / n)) / (2 kh + 1) per hop
+    m = 3
+    x = np.cos(2 * np.pi * m * np.arange(n) / n)[:, None].astype(np.float32)
+    lam = (1 + 2 * sum(np.cos(2 * np.pi * m * t / n) for t in range(1, kh + 1))) / (2 * kh + 1)
+    Y = oracle.sgc_layer(n, g.row_ptr, g.col_idx, x, np.ones((1, 1), dtype=np.float32), 6)
+    _close(Y, lam ** 6 * x.astype(np.float64), 1e-7)
