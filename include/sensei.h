@@ -225,6 +225,16 @@ int sensei_gcn_workspace(const sensei_csr *A, int f_in, int f_out, int comp_id, 
 int sensei_gcn_layer(sensei_ctx *ctx, const sensei_csr *A, const float *r, const float *c, sensei_mat X, sensei_mat W,
                      float *Y, int64_t ldy, int activation, int comp_id, void *workspace, size_t ws_bytes, void *stream);
 
+/* K-hop simplified graph convolution (SGC, one of the GCN variants the paper names as further targets of the same
+ * re-association): Y = act( A^^k X W ) with A^ = D_r^(-1/2) A~ D_c^(-1/2) on a square pattern, k_hops >= 1.
+ *   comp_id 0: aggregate first, ((A^^k X) W): k SpMMs at width f_in, then the GEMM (the choice for f_in <= f_out);
+ *   comp_id 1: update first, (A^^k (X W)): the GEMM, then k SpMMs at width f_out (f_in >= f_out).
+ * Inner hops stay in the slice-major layout (the SpMM writes what the next SpMM gathers) with the factor r_i c_i
+ * of two adjacent scalings applied in the epilogue.  k_hops = 1 is the GCN layer. */
+int sensei_sgc_workspace(const sensei_csr *A, int f_in, int f_out, int comp_id, size_t *bytes);
+int sensei_sgc_layer(sensei_ctx *ctx, const sensei_csr *A, const float *r, const float *c, sensei_mat X, sensei_mat W, int k_hops, float *Y,
+                     int64_t ldy, int activation, int comp_id, void *workspace, size_t ws_bytes, void *stream);
+
 /* Backward of the GCN layer (the paper's evaluation trains the models: one forward and one backward per
  * iteration; the backward is the gradient of the forward by the chain rule, with the same freedom of
  * association): given dY = dL/dY it computes

@@ -160,10 +160,10 @@ bool panels_usable(const sensei_csr &A, int f) {
 // values in the order of the original pattern use the single pass.
 hipError_t spmm_any(const sensei_csr &A, int mode, const float *r, const float *c, const float *B, int64_t ldb, int f, float *C,
                     int64_t ldc, int f_store, int act, const ChunkPlan &plan, float *carry, hipStream_t s, KernelTimer *kt,
-                    bool val_in_panel_order = false, const float2 *mz = nullptr, bool b_sliced = false) {
+                    bool val_in_panel_order = false, const float2 *mz = nullptr, bool b_sliced = false, bool c_sliced = false) {
     const bool has_val = (mode == SENSEI_SPMM_WEIGHTED || mode == kSpmmSoftmax);
     if (!panels_usable(A, f) || (has_val && !val_in_panel_order))
-        return launch_spmm(A, mode, r, c, B, ldb, f, C, ldc, f_store, act, plan, carry, s, kt, false, true, mz, b_sliced);
+        return launch_spmm(A, mode, r, c, B, ldb, f, C, ldc, f_store, act, plan, carry, s, kt, false, true, mz, b_sliced, 1, c_sliced);
     const sensei_panels &P = *A.panels;
     hipEvent_t t0 = kt ? kt->next() : nullptr, t1 = t0 ? kt->next() : nullptr;
     if (t1 && hipEventRecord(t0, s) != hipSuccess) return hipErrorUnknown;
@@ -177,7 +177,7 @@ hipError_t spmm_any(const sensei_csr &A, int mode, const float *r, const float *
         pq.chunk_nnz = P.chunk_nnz;
         pq.n_chunks = P.n_chunks_q[q];
         pq.chunk_row = P.chunk_row_q[q];
-        const hipError_t e = launch_spmm(Aq, mode, r, c, B, ldb, f, C, ldc, f_store, act, pq, carry, s, nullptr, q > 0, q == P.n_panels - 1, mz, b_sliced);
+        const hipError_t e = launch_spmm(Aq, mode, r, c, B, ldb, f, C, ldc, f_store, act, pq, carry, s, nullptr, q > 0, q == P.n_panels - 1, mz, b_sliced, 1, c_sliced);
         if (e != hipSuccess) return e;
     }
     if (t1 && hipEventRecord(t1, s) != hipSuccess) return hipErrorUnknown;
@@ -236,6 +236,47 @@ int run_gcn(const sensei_csr &A, const float *r, const float *c, const sensei_ma
         } else {
             SENSEI_TRY(spmm_any(A, mode, nullptr, nullptr, Z, fs, fs, Y, ldy, f_out, act, plan, carry, s, kt, false, nullptr, true));
         }
+    }
+    return SENSEI_OK;
+}
+
+// ---- K-hop simplified graph convolution: Y = act(A^^K X W), A^ = R A~ C, square pattern
+size_t sgc_ws(const sensei_csr &A, int f_in, int f_out, int id) {
+    const int f = (id == 0) ? f_in : f_out;
+    size_t b = plan_bytes(A.nnz) + spmm_carry_bytes(A.nnz, pad32(f)) + 512;
+    b += 2 * align_up((size_t)A.n_cols * pad32(f) * sizeof(float), 256);  // the two slice-major hop buffers
+    b += align_up((size_t)A.n_rows * sizeof(float), 256);                 // r (.) c
+    if (id == 0) b += align_up((size_t)A.n_rows * pad4(f_in) * sizeof(float), 256);  // U = A^^K X
+    return b;
+}
+
+int run_sgc(const sensei_csr &A, const float *r, const float *c, const sensei_mat &X, const sensei_mat &W, int k_hops, float *Y, int64_t ldy,
+            int act, int id, void *ws, size_t ws_bytes, hipStream_t s, Timers *tm) {
+    KernelTimer *kt = tm ? &tm->spmm : nullptr, *gt = tm ? &tm->gemm : nullptr;
+    const int f_in = (int)X.cols, f_out = (int)W.cols;
+    const int f = (id == 0) ? f_in : f_out, fp = pad32(f);
+    Carver cv(ws, ws_bytes);
+    ChunkPlan plan = make_plan(A, cv);
+    float *carry = cv.take<float>(spmm_carry_bytes(A.nnz, fp) / sizeof(float));
+    float *buf[2] = {cv.take<float>((size_t)A.n_cols * fp), cv.take<float>((size_t)A.n_cols * fp)};
+    float *rc = cv.take<float>((size_t)A.n_rows);
+    SENSEI_TRY(launch_chunk_rows(A, plan, s));
+    // between two hops the row scaling of one and the column scaling of the next meet: one factor r_i c_i per node
+    SENSEI_TRY(launch_row_broadcast(r, c, 1, A.n_rows, 1, rc, 1, SENSEI_ACT_NONE, s));
+    // hop input 0, slice-major with the column scaling applied: c (x) X, or c (x) (X.W) straight from the GEMM epilogue
+    if (id == 0) SENSEI_TRY(launch_to_slices(c, X.ptr, X.ld, A.n_cols, f_in, buf[0], s));
+    else SENSEI_TRY(launch_gemm(X.ptr, X.ld, W.ptr, W.ld, buf[0], fp, A.n_cols, f_in, f_out, fp, SENSEI_ACT_NONE, s, c, gt, true));
+    for (int k = 0; k + 1 < k_hops; ++k)  // inner hops stay slice-major: the SpMM writes what the next one gathers
+        SENSEI_TRY(spmm_any(A, SENSEI_SPMM_PATTERN, rc, nullptr, buf[k & 1], fp, fp, buf[(k + 1) & 1], fp, fp, SENSEI_ACT_NONE, plan, carry, s, kt,
+                            false, nullptr, true, true));
+    const float *last = buf[(k_hops - 1) & 1];
+    if (id == 0) {
+        float *U = cv.take<float>((size_t)A.n_rows * pad4(f_in));
+        SENSEI_TRY(spmm_any(A, SENSEI_SPMM_PATTERN, r, nullptr, last, fp, f_in, U, pad4(f_in), f_in, SENSEI_ACT_NONE, plan, carry, s, kt, false,
+                            nullptr, true));
+        SENSEI_TRY(launch_gemm(U, pad4(f_in), W.ptr, W.ld, Y, ldy, A.n_rows, f_in, f_out, f_out, act, s, nullptr, gt));
+    } else {
+        SENSEI_TRY(spmm_any(A, SENSEI_SPMM_PATTERN, r, nullptr, last, fp, fp, Y, ldy, f_out, act, plan, carry, s, kt, false, nullptr, true));
     }
     return SENSEI_OK;
 }
@@ -1064,6 +1105,32 @@ int sensei_gcn_layer(sensei_ctx *ctx, const sensei_csr *A, const float *r, const
     if (ws_bytes < gcn_ws(*A, (int)X.cols, (int)W.cols, comp_id)) return SENSEI_WORKSPACE_TOO_SMALL;
     if (A->n_rows == 0) return SENSEI_OK;
     return run_gcn(*A, r, c, X, W, Y, ldy, activation, comp_id, workspace, ws_bytes, as_stream(stream), &ctx->timers);
+}
+
+int sensei_sgc_workspace(const sensei_csr *A, int f_in, int f_out, int comp_id, size_t *bytes) {
+    if (!csr_ok(A, false) || f_in <= 0 || f_out <= 0 || !bytes) return SENSEI_INVALID_ARGUMENT;
+    if (comp_id != 0 && comp_id != 1) return SENSEI_INVALID_COMPOSITION;
+    *bytes = sgc_ws(*A, f_in, f_out, comp_id);
+    return SENSEI_OK;
+}
+
+int sensei_sgc_layer(sensei_ctx *ctx, const sensei_csr *A, const float *r, const float *c, sensei_mat X, sensei_mat W, int k_hops, float *Y,
+                     int64_t ldy, int activation, int comp_id, void *workspace, size_t ws_bytes, void *stream) {
+    if (comp_id != 0 && comp_id != 1) return SENSEI_INVALID_COMPOSITION;
+    if (!ctx || !csr_ok(A, false) || !mat_ok(X) || !mat_ok(W)) return SENSEI_INVALID_ARGUMENT;
+    if (activation != SENSEI_ACT_NONE && activation != SENSEI_ACT_RELU) return SENSEI_INVALID_ARGUMENT;
+    if (A->n_rows != A->n_cols || k_hops < 1 || k_hops > 64) return SENSEI_INVALID_ARGUMENT;  // powers of the pattern need it square
+    if (X.rows != A->n_cols || X.cols != W.rows || X.cols <= 0 || W.cols <= 0 || ldy < W.cols) return SENSEI_INVALID_ARGUMENT;
+    if (X.cols > (1 << 20) || W.cols > (1 << 20)) return SENSEI_INVALID_ARGUMENT;
+    if ((!X.ptr && A->n_cols > 0) || !W.ptr || (!Y && A->n_rows > 0) || !workspace) return SENSEI_INVALID_ARGUMENT;
+    if (A->n_rows > 0 && (!r || !c)) return SENSEI_INVALID_ARGUMENT;
+    const size_t ybytes = mat_bytes(Y, A->n_rows, W.cols, ldy);
+    if (overlap(Y, ybytes, X.ptr, mat_bytes(X.ptr, X.rows, X.cols, X.ld)) || overlap(Y, ybytes, W.ptr, mat_bytes(W.ptr, W.rows, W.cols, W.ld)) ||
+        overlap(Y, ybytes, workspace, ws_bytes) || overlap(X.ptr, mat_bytes(X.ptr, X.rows, X.cols, X.ld), workspace, ws_bytes))
+        return SENSEI_INVALID_ARGUMENT;
+    if (ws_bytes < sgc_ws(*A, (int)X.cols, (int)W.cols, comp_id)) return SENSEI_WORKSPACE_TOO_SMALL;
+    if (A->n_rows == 0) return SENSEI_OK;
+    return run_sgc(*A, r, c, X, W, k_hops, Y, ldy, activation, comp_id, workspace, ws_bytes, as_stream(stream), &ctx->timers);
 }
 
 int sensei_gcn_backward_workspace(const sensei_csr *A, int f_in, int f_out, int bwd_id, size_t *bytes) {

@@ -61,9 +61,10 @@ size_t spmm_carry_bytes(int64_t nnz, int f);  // upper bound
 hipError_t launch_spmm(const sensei_csr &A, int mode, const float *r, const float *c, const float *B, int64_t ldb,
                        int f, float *C, int64_t ldc, int f_store, int act, const ChunkPlan &p, float *carry,
                        hipStream_t s, KernelTimer *timer = nullptr, bool accumulate = false, bool finalize = true,
-                       const float2 *mz = nullptr, bool b_sliced = false, int val_stride = 1);
+                       const float2 *mz = nullptr, bool b_sliced = false, int val_stride = 1, bool c_sliced = false);
 // b_sliced: B is stored slice-major in tiles of 32 floats, element (j, col) at B[(col / 32) * n_cols * 32 + j * 32 + col % 32]
 // (f padded to a multiple of 32, B 128-byte aligned); `ldb` is ignored.  val_stride: floats between consecutive values of A.val.
+// c_sliced (needs b_sliced, f a multiple of 32, f_store == f): C is written slice-major too (n_rows x f), `ldc` is ignored.
 inline size_t sliced_index(int64_t n_rows, int64_t row, int col) { return (size_t)(col >> 5) * (size_t)n_rows * 32 + (size_t)row * 32 + (col & 31); }
 // Internal SpMM mode (not part of the C ABI): A.val holds attention logits e_ij, `mz[i]` = (max_j e_ij, sum_j exp(e_ij - max));
 // the kernel weighs neighbour j of row i by exp(e_ij - max_i) and scales the finished row by 1 / sum, i.e. it aggregates

@@ -61,6 +61,8 @@ struct SpmmArgs {
     const float *val, *r, *c, *B;
     const float2 *mz;  // softmax mode: per-row (max logit, sum of exp(logit - max))
     int val_stride;    // floats from the value of one entry to the next (1, or 2 when the values sit in (value, other) pairs)
+    long long c_tile;  // floats from feature tile t of C to tile t + 1: VEC*LPG for a row-major C, n_rows * 32 for a slice-major one (ldc = 32)
+    int c_tf;          // columns per feature tile (VEC * LPG)
     float *C, *carry;
     long long ldb, ldc;
     long long tile_stride_b;  // bytes from feature tile t of B to tile t + 1: 4*VEC*LPG when rows are contiguous, a whole slice otherwise
@@ -119,6 +121,7 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
     const bool fok = f0 < a.f;
     const char *Bb = reinterpret_cast<const char *>(a.B) + (long long)tile * a.tile_stride_b;
     const unsigned f0_b = fok ? (unsigned)((lane % LPG) * VEC) * 4u : 0u;
+    float *c_tile_base = a.C + (size_t)tile * a.c_tile + (lane % LPG) * VEC;  // this lane's columns of row 0 of C
     const unsigned ldb_b32 = (unsigned)(a.ldb * 4);
     const size_t ldb_b64 = (size_t)a.ldb * 4;
 
@@ -164,7 +167,7 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
             if (cont) {
                 acc.store(a.carry + (size_t)chunk * a.f_carry + f0);
             } else {
-                float *dst = a.C + (size_t)i * a.ldc + f0;
+                float *dst = c_tile_base + (size_t)i * a.ldc;
                 const bool vec_store = a.store_vec_ok && f0 + VEC <= a.f_store;
                 if (a.accumulate) {  // later column panel: add to what the earlier panels left in C
                     if (vec_store) {
@@ -242,7 +245,7 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
                 if (cont && row == i_first) {
                     racc.store(a.carry + (size_t)chunk * a.f_carry + f0);
                 } else {
-                    float *dst = a.C + (size_t)row * a.ldc + f0;
+                    float *dst = c_tile_base + (size_t)row * a.ldc;
                     const bool vec_store = a.store_vec_ok && f0 + VEC <= a.f_store;
                     if (a.accumulate) {
                         if (vec_store) {
@@ -362,14 +365,16 @@ __global__ __launch_bounds__(kBlock) void k_spmm_fixup(SpmmArgs a) {
     const int re = a.row_ptr[i + 1];
     const int c_last = (re - 1) / a.chunk_nnz;
     const float sc = a.mz ? inv_z(a.mz[i].y) : (a.r ? a.r[i] : 1.f);
+    const int tf = a.c_tf;
     for (int f = lane; f < a.f_store; f += 64) {
-        float acc = a.C[(size_t)i * a.ldc + f];
+        float *dst = a.C + (size_t)(f / tf) * a.c_tile + (size_t)i * a.ldc + (f % tf);
+        float acc = *dst;
         for (int cc = c; cc <= c_last; ++cc) acc += a.carry[(size_t)cc * a.f_carry + f];
         if (a.finalize) {
             acc *= sc;
             if (a.act == SENSEI_ACT_RELU) acc = acc > 0.f ? acc : 0.f;
         }
-        a.C[(size_t)i * a.ldc + f] = acc;
+        *dst = acc;
     }
 }
 
@@ -1141,7 +1146,8 @@ size_t spmm_carry_bytes(int64_t nnz, int f) {
 
 hipError_t launch_spmm(const sensei_csr &A, int mode, const float *r, const float *c, const float *B, int64_t ldb,
                        int f, float *C, int64_t ldc, int f_store, int act, const ChunkPlan &p, float *carry,
-                       hipStream_t s, KernelTimer *timer, bool accumulate, bool finalize, const float2 *mz, bool b_sliced, int val_stride) {
+                       hipStream_t s, KernelTimer *timer, bool accumulate, bool finalize, const float2 *mz, bool b_sliced, int val_stride,
+                       bool c_sliced) {
     SpmmShape sh = spmm_shape(B, ldb, f);
     if (b_sliced) {  // slices of 32 floats per row: one 128-byte line per neighbour and tile
         sh.vec = 4; sh.lpg = 8; sh.n_tiles = (f + 31) / 32; sh.f_carry = sh.n_tiles * 32;
@@ -1151,6 +1157,9 @@ hipError_t launch_spmm(const sensei_csr &A, int mode, const float *r, const floa
     a.tile_stride_b = b_sliced ? (long long)(A.n_cols > 0 ? A.n_cols : 1) * 128 : (long long)sh.vec * sh.lpg * 4;
     a.mz = (mode == kSpmmSoftmax) ? mz : nullptr;
     a.val_stride = val_stride;
+    if (c_sliced) ldc = 32;  // requires b_sliced (tiles of 32 columns) and f_store == pad32(f): checked by the callers
+    a.c_tf = sh.vec * sh.lpg;
+    a.c_tile = c_sliced ? (long long)(A.n_rows > 0 ? A.n_rows : 1) * 32 : (long long)a.c_tf;
     a.row_ptr = A.row_ptr; a.col_idx = A.col_idx; a.chunk_row = p.chunk_row;
     a.val = A.val; a.r = r; a.c = c; a.B = B; a.C = C; a.carry = carry;
     a.ldb = ldb; a.ldc = ldc;

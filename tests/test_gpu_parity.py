@@ -513,3 +513,47 @@ def test_multi_head_gat_over_column_panels_and_bad_head_counts(ctx):
 def binding_set_min_width(P, width):
     from paper_2306_15155_amd import binding
     return binding.lib().sensei_panels_set_min_width(P._h, width) == 0
+
+
+# ------------------------------------------------------------------ K-hop simplified graph convolution
+
+@pytest.mark.parametrize("name", ["er", "rmat_hub", "hub_empty", "selfloops", "tiny"])
+@pytest.mark.parametrize("shape", [(40, 9), (9, 40), (64, 64), (100, 33)])
+def test_sgc_layer_matches_the_k_fold_propagation(ctx, name, shape):
+    g = GRAPHS[name]
+    A = DeviceCSR(g)
+    dr, dc = ctx.degrees(A.s)
+    r, c = ctx.norm_vectors(dr), ctx.norm_vectors(dc)
+    f_in, f_out = shape
+    X, W = synth.uniform(41, 10, (g.n_cols, f_in)), synth.glorot(41, 11, f_in, f_out)
+    for k in (1, 2, 3):
+        ref = oracle.sgc_layer(g.n_rows, g.row_ptr, g.col_idx, X, W, k, ACT_RELU)
+        for cid in (0, 1):
+            assert_close(ctx.sgc_layer(A.s, r, c, dev(X), dev(W), k, cid, ACT_RELU), ref, what=f"sgc k={k} comp {cid}")
+    one = ctx.sgc_layer(A.s, r, c, dev(X), dev(W), 1, 1, ACT_RELU)
+    assert_close(one, oracle.gcn_layer(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, ACT_RELU), what="one hop is the GCN layer")
+
+
+def test_sgc_layer_with_panels_and_argument_checks(ctx):
+    from paper_2306_15155_amd import Panels, csr_struct
+    g = synth.rmat(42, 6000, 120_000)
+    A = DeviceCSR(g)
+    P = Panels(ctx, A.s, 3)
+    assert binding_set_min_width(P, 32)
+    Ap = csr_struct(g.n_rows, g.n_cols, A.row_ptr, A.col_idx, None, P)
+    dr, dc = ctx.degrees(A.s)
+    r, c = ctx.norm_vectors(dr), ctx.norm_vectors(dc)
+    X, W = synth.uniform(42, 10, (g.n_cols, 72)), synth.glorot(42, 11, 72, 130)
+    ref = oracle.sgc_layer(g.n_rows, g.row_ptr, g.col_idx, X, W, 4)
+    for cid in (0, 1):
+        assert_close(ctx.sgc_layer(Ap, r, c, dev(X), dev(W), 4, cid), ref, what=f"panels comp {cid}")
+        assert_close(ctx.sgc_layer(A.s, r, c, dev(X), dev(W), 4, cid), ref, what=f"comp {cid}")
+    P.close()
+    with pytest.raises(SenseiError):
+        ctx.sgc_layer(A.s, r, c, dev(X), dev(W), 0, 0)       # at least one hop
+    with pytest.raises(SenseiError):
+        ctx.sgc_layer(A.s, r, c, dev(X), dev(W), 2, 2)       # two compositions
+    gr = GRAPHS["rect"]
+    Ar = DeviceCSR(gr)
+    with pytest.raises(SenseiError):                          # powers need a square pattern
+        ctx.sgc_layer(Ar.s, r, c, dev(synth.uniform(1, 1, (gr.n_cols, 8))), dev(synth.glorot(1, 2, 8, 8)), 2, 0)
