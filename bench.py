@@ -307,6 +307,16 @@ def main():
             del dYt, t_pos
         detail["gat_backward_ms"] = gat_bwd
 
+    # ---- K-hop simplified graph convolution on the shapes of the GCN layers (2 hops): both associations
+    if not args.no_sweep:
+        sgc = {}
+        for i, L in enumerate(layers):
+            if L["kind"] != "gcn":
+                continue
+            sgc[tag(i)] = {nm: round(time_fn(lambda: ctx.sgc_layer(A, r, c, src_of(i), Wd[i], 2, cid, L["act"], out=outs[i]), 2), 4)
+                           for cid, nm in ((0, "AGG"), (1, "UPD"))}
+        detail["sgc_2hop_ms"] = sgc
+
     # ---- one training iteration of the GCN stack of the workload (the layers whose input is X or the previous layer):
     # forward with the selected compositions, backward with the associations the cost model picks; the first layer needs no dX
     if not args.no_sweep or args.backward:

@@ -193,16 +193,34 @@ def gat_layer(n_rows, n_cols, row_ptr, col_idx, X, W, a_l, a_r, slope=0.2, act=0
     return Y
 
 
-def sgc_layer(n, row_ptr, col_idx, X, W, k_hops, act=0):
+def sgc_layer(n, row_ptr, col_idx, X, W, k_hops, act=0, rows=None):
     """K-hop simplified graph convolution act(A^^k X W), A^ = D^-1/2 A~ D^-1/2 as in Eq. 3, on a square pattern:
-    k propagations (column scaling, neighbour sum of Eq. 1, row scaling) followed by the update."""
+    k propagations (column scaling, neighbour sum of Eq. 1, row scaling) followed by the update.
+
+    ``rows`` selects output rows: hop by hop only the nodes those rows reach are kept (row i of a propagation needs
+    the previous values at the neighbours of i and nowhere else), which is the same sum restricted to what it reads."""
     row_ptr, col_idx = _i32(row_ptr), _i32(col_idx)
     dr, dc = degrees(n, n, row_ptr, col_idx)
     r, c = inv_sqrt_deg(dr), inv_sqrt_deg(dc)
-    H = _f32(X).astype(np.float64)
-    for _ in range(k_hops):
-        H = row_broadcast(r, spmm(row_ptr, col_idx, None, row_broadcast(c, H)))
-    return activation(gemm(H, _f32(W).astype(np.float64)), act)
+    W64 = _f32(W).astype(np.float64)
+    if rows is None:
+        H = _f32(X).astype(np.float64)
+        for _ in range(k_hops):
+            H = row_broadcast(r, spmm(row_ptr, col_idx, None, row_broadcast(c, H)))
+        return activation(gemm(H, W64), act)
+    need = [np.unique(np.asarray(rows, dtype=np.int64))]
+    for _ in range(k_hops):   # need[h + 1]: the nodes read by the rows need[h]
+        seg = [col_idx[row_ptr[i]:row_ptr[i + 1]] for i in need[-1]]
+        need.append(np.unique(np.concatenate(seg)) if seg else np.zeros(0, dtype=np.int64))
+    H = _f32(X)[need[k_hops]].astype(np.float64)
+    for h in range(k_hops - 1, -1, -1):
+        dst, src = need[h], need[h + 1]
+        seg = [np.searchsorted(src, col_idx[row_ptr[i]:row_ptr[i + 1]]) for i in dst]   # neighbours as positions in src
+        sub_ptr = np.concatenate([[0], np.cumsum([x.size for x in seg])])
+        sub_idx = np.concatenate(seg) if seg else np.zeros(0, dtype=np.int32)
+        H = row_broadcast(r[dst], spmm(sub_ptr, sub_idx, None, row_broadcast(c[src], H)))
+    pick = np.searchsorted(need[0], np.asarray(rows, dtype=np.int64))
+    return activation(gemm(H[pick], W64), act)
 
 
 def gat_layer_heads(n_rows, n_cols, row_ptr, col_idx, X, W, a_l, a_r, n_heads, slope=0.2, act=0, rows=None, omp=False):

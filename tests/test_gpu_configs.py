@@ -211,6 +211,26 @@ def test_config2_gcn_backward_full_size(ctx, reddit_like):
     assert pick == GCN_BWD_AGG and est[0] < est[1]  # f_out < f_in: aggregate the gradient at the narrow width
 
 
+def test_config2_sgc_two_hops_full_size(ctx, reddit_like):
+    """Two-hop simplified graph convolution 602 -> 256 on the Reddit-shaped graph: sampled rows against the oracle, which
+    follows the two hops back from those rows.  Rows of moderate length keep the set of nodes they reach small enough
+    for the oracle to finish in seconds; the kernels do not know which rows are sampled."""
+    g, A = reddit_like
+    f_in, f_out = 602, 256
+    X, W = synth.uniform(7, 10, (g.n_cols, f_in)), synth.glorot(7, 100, f_in, f_out)
+    deg = np.diff(g.row_ptr)
+    cand = np.flatnonzero((deg >= 30) & (deg <= 800))
+    rows = cand[np.random.default_rng(11).choice(cand.size, 6, replace=False)].astype(np.int64)
+    want = oracle.sgc_layer(g.n_rows, g.row_ptr, g.col_idx, X, W, 2, ACT_RELU, rows=rows)
+    r, c, _, _ = _norm(ctx, A)
+    sel = torch.from_numpy(rows).to(DEV)
+    Xd, Wd = dev(X), dev(W)
+    for cid in (0, 1):
+        Y = ctx.sgc_layer(A.s, r, c, Xd, Wd, 2, cid, ACT_RELU)
+        assert_close(Y[sel], want, what=f"sgc comp {cid}")
+        del Y
+
+
 def test_config4_gat_backward_full_size(ctx, reddit_like):
     """Training step of the GAT layer 602 -> 64 on the Reddit-shaped graph: every gradient against the oracle.
 

@@ -338,6 +338,9 @@ def test_sgc_is_the_matrix_power_and_one_hop_is_the_gcn_layer():
         _close(oracle.sgc_layer(n, g.row_ptr, g.col_idx, X, W, k), ref, 1e-12)
         _close(oracle.sgc_layer(n, g.row_ptr, g.col_idx, X, W, k, 1), np.maximum(ref, 0.0), 1e-12)
     _close(oracle.sgc_layer(n, g.row_ptr, g.col_idx, X, W, 1, 1), oracle.gcn_layer(n, n, g.row_ptr, g.col_idx, X, W, 1), 1e-13)
+    rows = np.array([7, 0, 59, 7, 31])   # selected rows (unsorted, one repeated) against the dense power as well
+    for k in (1, 3):
+        _close(oracle.sgc_layer(n, g.row_ptr, g.col_idx, X, W, k, 0, rows=rows), (np.linalg.matrix_power(Ahat, k) @ XW)[rows], 1e-12)
 
 
 def test_sgc_on_a_regular_ring_keeps_constant_columns_and_smooths_the_rest():
