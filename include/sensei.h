@@ -235,6 +235,16 @@ int sensei_sgc_workspace(const sensei_csr *A, int f_in, int f_out, int comp_id, 
 int sensei_sgc_layer(sensei_ctx *ctx, const sensei_csr *A, const float *r, const float *c, sensei_mat X, sensei_mat W, int k_hops, float *Y,
                      int64_t ldy, int activation, int comp_id, void *workspace, size_t ws_bytes, void *stream);
 
+/* Topology-adaptive graph convolution (TAGCN, the other K-hop variant the paper names): Y = act( sum_{k=0..k_hops} A^^k X W_k ),
+ * W = [W_0; W_1; ...; W_k_hops] stacked by hop, (k_hops + 1) * f_in rows by f_out columns; square pattern, k_hops >= 1.
+ *   comp_id 0: aggregate first: the hops H_k = A^ H_(k-1) at width f_in, then one GEMM over all hops, [H_0 .. H_K] W;
+ *   comp_id 1: update first, Horner form at width f_out: T_K = X W_K, T_k = X W_k + A^ T_(k+1), Y = act(T_0).
+ * Both do k_hops SpMMs and (k_hops + 1) n f_in f_out multiply-adds of GEMM work; they differ in the SpMM width, as in
+ * the GCN layer. */
+int sensei_tagcn_workspace(const sensei_csr *A, int f_in, int f_out, int k_hops, int comp_id, size_t *bytes);
+int sensei_tagcn_layer(sensei_ctx *ctx, const sensei_csr *A, const float *r, const float *c, sensei_mat X, sensei_mat W, int k_hops, float *Y,
+                       int64_t ldy, int activation, int comp_id, void *workspace, size_t ws_bytes, void *stream);
+
 /* Backward of the GCN layer (the paper's evaluation trains the models: one forward and one backward per
  * iteration; the backward is the gradient of the forward by the chain rule, with the same freedom of
  * association): given dY = dL/dY it computes

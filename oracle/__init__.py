@@ -223,6 +223,23 @@ def sgc_layer(n, row_ptr, col_idx, X, W, k_hops, act=0, rows=None):
     return activation(gemm(H[pick], W64), act)
 
 
+def tagcn_layer(n, row_ptr, col_idx, X, W, k_hops, act=0):
+    """TAGCN layer act(sum_{k=0..K} A^^k X W_k) with A^ the normalised operator of Eq. 3 on a square pattern and W the
+    K + 1 weight blocks stacked by rows: the sum written out term by term, each hop one more propagation of the last."""
+    row_ptr, col_idx = _i32(row_ptr), _i32(col_idx)
+    dr, dc = degrees(n, n, row_ptr, col_idx)
+    r, c = inv_sqrt_deg(dr), inv_sqrt_deg(dc)
+    H = _f32(X).astype(np.float64)
+    W64 = _f32(W).astype(np.float64)
+    f_in = H.shape[1]
+    assert W64.shape[0] == (k_hops + 1) * f_in
+    Y = gemm(H, W64[:f_in])
+    for k in range(1, k_hops + 1):
+        H = row_broadcast(r, spmm(row_ptr, col_idx, None, row_broadcast(c, H)))
+        Y = Y + gemm(H, W64[k * f_in:(k + 1) * f_in])
+    return activation(Y, act)
+
+
 def gat_layer_heads(n_rows, n_cols, row_ptr, col_idx, X, W, a_l, a_r, n_heads, slope=0.2, act=0, rows=None, omp=False):
     """Multi-head GAT with concatenated heads: head h is the single-head layer of Eq. 5 / 6 on columns
     [h d, (h + 1) d) of W, a_l, a_r (heads share nothing but the input)."""

@@ -281,6 +281,62 @@ int run_sgc(const sensei_csr &A, const float *r, const float *c, const sensei_ma
     return SENSEI_OK;
 }
 
+// ---- TAGCN: Y = act(sum_{k=0..K} A^^k X W_k), W = [W_0; ...; W_K] stacked by hop
+size_t tagcn_ws(const sensei_csr &A, int f_in, int f_out, int k_hops, int id) {
+    const int f = (id == 0) ? f_in : f_out, fp = pad32(f);
+    size_t b = plan_bytes(A.nnz) + spmm_carry_bytes(A.nnz, fp) + 512;
+    b += align_up((size_t)A.n_rows * sizeof(float), 256);  // r (.) c, or nothing to merge for id 1 (kept for one layout)
+    if (id == 0) {
+        b += align_up((size_t)(k_hops + 1) * A.n_cols * fp * sizeof(float), 256);           // c (x) H_0 .. c (x) H_K, slice-major, side by side
+        b += align_up((size_t)A.n_rows * sizeof(float), 256);                               // 1 / c
+        b += align_up((size_t)(k_hops + 1) * fp * pad4(f_out) * sizeof(float), 256);        // W with each hop's block padded to the slices
+    } else {
+        b += 2 * align_up((size_t)A.n_cols * fp * sizeof(float), 256);                      // T and the aggregated term
+    }
+    return b;
+}
+
+int run_tagcn(const sensei_csr &A, const float *r, const float *c, const sensei_mat &X, const sensei_mat &W, int k_hops, float *Y, int64_t ldy,
+              int act, int id, void *ws, size_t ws_bytes, hipStream_t s, Timers *tm) {
+    KernelTimer *kt = tm ? &tm->spmm : nullptr, *gt = tm ? &tm->gemm : nullptr;
+    const int f_in = (int)X.cols, f_out = (int)W.cols;
+    const int f = (id == 0) ? f_in : f_out, fp = pad32(f);
+    const int64_t n = A.n_rows;
+    Carver cv(ws, ws_bytes);
+    ChunkPlan plan = make_plan(A, cv);
+    float *carry = cv.take<float>(spmm_carry_bytes(A.nnz, fp) / sizeof(float));
+    float *rc = cv.take<float>((size_t)n);
+    SENSEI_TRY(launch_chunk_rows(A, plan, s));
+    if (id == 0) {
+        // hops at width f_in, kept as G_k = c (x) H_k (what the next SpMM gathers); the one GEMM over all hops undoes the
+        // scaling per row: sum_k H_k W_k = diag(1/c) [G_0 .. G_K] [W_0; ..; W_K]
+        const size_t hop = (size_t)n * fp;
+        float *G = cv.take<float>((size_t)(k_hops + 1) * hop);
+        float *inv_c = cv.take<float>((size_t)n);
+        const int ldws = pad4(f_out);
+        float *Wst = cv.take<float>((size_t)(k_hops + 1) * fp * ldws);
+        SENSEI_TRY(launch_row_broadcast(r, c, 1, n, 1, rc, 1, SENSEI_ACT_NONE, s));
+        SENSEI_TRY(launch_reciprocal(c, n, inv_c, s));
+        SENSEI_TRY(launch_stack_weights(W.ptr, W.ld, k_hops + 1, f_in, f_out, Wst, ldws, s));
+        SENSEI_TRY(launch_to_slices(c, X.ptr, X.ld, n, f_in, G, s));
+        for (int k = 1; k <= k_hops; ++k)
+            SENSEI_TRY(spmm_any(A, SENSEI_SPMM_PATTERN, rc, nullptr, G + (k - 1) * hop, fp, fp, G + k * hop, fp, fp, SENSEI_ACT_NONE, plan, carry, s, kt,
+                                false, nullptr, true, true));
+        SENSEI_TRY(launch_gemm(G, 32, Wst, ldws, Y, ldy, n, (k_hops + 1) * fp, f_out, f_out, act, s, inv_c, gt, false, true));
+        return SENSEI_OK;
+    }
+    // Horner form at width f_out: T_K = X W_K, T_k = X W_k + A^ T_{k+1}; T is kept as c (x) T_k, slice-major
+    float *T = cv.take<float>((size_t)n * fp), *P = cv.take<float>((size_t)n * fp);
+    auto w_block = [&](int k) { return W.ptr + (size_t)k * f_in * W.ld; };
+    SENSEI_TRY(launch_gemm(X.ptr, X.ld, w_block(k_hops), W.ld, T, fp, n, f_in, f_out, fp, SENSEI_ACT_NONE, s, c, gt, true));
+    for (int k = k_hops - 1; k >= 0; --k) {
+        SENSEI_TRY(spmm_any(A, SENSEI_SPMM_PATTERN, r, nullptr, T, fp, fp, P, fp, fp, SENSEI_ACT_NONE, plan, carry, s, kt, false, nullptr, true, true));
+        if (k > 0) SENSEI_TRY(launch_gemm(X.ptr, X.ld, w_block(k), W.ld, T, fp, n, f_in, f_out, fp, SENSEI_ACT_NONE, s, c, gt, true, false, P));
+        else SENSEI_TRY(launch_gemm(X.ptr, X.ld, w_block(0), W.ld, Y, ldy, n, f_in, f_out, f_out, act, s, nullptr, gt, false, false, P));
+    }
+    return SENSEI_OK;
+}
+
 // ---- backward of the GCN layer
 size_t gcn_bwd_ws(const sensei_csr &A, int f_in, int f_out, int id) {
     const int64_t nnz = A.nnz;
@@ -1131,6 +1187,33 @@ int sensei_sgc_layer(sensei_ctx *ctx, const sensei_csr *A, const float *r, const
     if (ws_bytes < sgc_ws(*A, (int)X.cols, (int)W.cols, comp_id)) return SENSEI_WORKSPACE_TOO_SMALL;
     if (A->n_rows == 0) return SENSEI_OK;
     return run_sgc(*A, r, c, X, W, k_hops, Y, ldy, activation, comp_id, workspace, ws_bytes, as_stream(stream), &ctx->timers);
+}
+
+int sensei_tagcn_workspace(const sensei_csr *A, int f_in, int f_out, int k_hops, int comp_id, size_t *bytes) {
+    if (!csr_ok(A, false) || f_in <= 0 || f_out <= 0 || k_hops < 1 || k_hops > 64 || !bytes) return SENSEI_INVALID_ARGUMENT;
+    if (comp_id != 0 && comp_id != 1) return SENSEI_INVALID_COMPOSITION;
+    *bytes = tagcn_ws(*A, f_in, f_out, k_hops, comp_id);
+    return SENSEI_OK;
+}
+
+int sensei_tagcn_layer(sensei_ctx *ctx, const sensei_csr *A, const float *r, const float *c, sensei_mat X, sensei_mat W, int k_hops, float *Y,
+                       int64_t ldy, int activation, int comp_id, void *workspace, size_t ws_bytes, void *stream) {
+    if (comp_id != 0 && comp_id != 1) return SENSEI_INVALID_COMPOSITION;
+    if (!ctx || !csr_ok(A, false) || !mat_ok(X) || !mat_ok(W)) return SENSEI_INVALID_ARGUMENT;
+    if (activation != SENSEI_ACT_NONE && activation != SENSEI_ACT_RELU) return SENSEI_INVALID_ARGUMENT;
+    if (A->n_rows != A->n_cols || k_hops < 1 || k_hops > 64) return SENSEI_INVALID_ARGUMENT;
+    if (X.rows != A->n_cols || X.cols <= 0 || W.cols <= 0 || W.rows != (int64_t)(k_hops + 1) * X.cols || ldy < W.cols) return SENSEI_INVALID_ARGUMENT;
+    if (X.cols > (1 << 20) || W.cols > (1 << 20) || (int64_t)(k_hops + 1) * pad32((int)X.cols) > (1 << 24)) return SENSEI_INVALID_ARGUMENT;
+    if ((!X.ptr && A->n_cols > 0) || !W.ptr || (!Y && A->n_rows > 0) || !workspace) return SENSEI_INVALID_ARGUMENT;
+    if (A->n_rows > 0 && (!r || !c)) return SENSEI_INVALID_ARGUMENT;
+    const size_t ybytes = mat_bytes(Y, A->n_rows, W.cols, ldy);
+    if (overlap(Y, ybytes, X.ptr, mat_bytes(X.ptr, X.rows, X.cols, X.ld)) || overlap(Y, ybytes, W.ptr, mat_bytes(W.ptr, W.rows, W.cols, W.ld)) ||
+        overlap(Y, ybytes, workspace, ws_bytes) || overlap(X.ptr, mat_bytes(X.ptr, X.rows, X.cols, X.ld), workspace, ws_bytes) ||
+        overlap(W.ptr, mat_bytes(W.ptr, W.rows, W.cols, W.ld), workspace, ws_bytes))
+        return SENSEI_INVALID_ARGUMENT;
+    if (ws_bytes < tagcn_ws(*A, (int)X.cols, (int)W.cols, k_hops, comp_id)) return SENSEI_WORKSPACE_TOO_SMALL;
+    if (A->n_rows == 0) return SENSEI_OK;
+    return run_tagcn(*A, r, c, X, W, k_hops, Y, ldy, activation, comp_id, workspace, ws_bytes, as_stream(stream), &ctx->timers);
 }
 
 int sensei_gcn_backward_workspace(const sensei_csr *A, int f_in, int f_out, int bwd_id, size_t *bytes) {

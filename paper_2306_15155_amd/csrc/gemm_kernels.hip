@@ -18,6 +18,8 @@ struct GemmArgs {
     long long lda, ldw, ldy, n;
     int k, m, m_store, act, n_bn;
     int y_sliced;  // Y stored slice-major in tiles of 32 columns: (row, col) at Y[(col / 32) * n * 32 + row * 32 + col % 32]
+    long long a_slice;   // floats from columns 32 s .. 32 s + 31 of A to the next 32: 32 for a row-major A, n * 32 (with lda = 32) for a slice-major one
+    const float *add;    // optional n x pad32(m) slice-major matrix added to the product before scaling and activation
 };
 
 // Block tile BM x BN, 4 wavefronts laid out WGM x WGN, each computing TM x TN tiles of 32 x 32
@@ -62,7 +64,7 @@ __global__ __launch_bounds__(kThreads) void k_gemm(GemmArgs g) {
             const long long row = m0 + p * A_RPP + a_row;
             const int kk = k0 + a_kk;
             if (row < g.n && kk < g.k) {
-                const float *src = g.A + row * g.lda + kk;
+                const float *src = g.A + row * g.lda + (long long)(kk >> 5) * g.a_slice + (kk & 31);
                 if (AVEC == 4) { float4 v = *reinterpret_cast<const float4 *>(src); ra[p][0] = v.x; ra[p][1 % AVEC] = v.y; ra[p][2 % AVEC] = v.z; ra[p][3 % AVEC] = v.w; }
                 else if (AVEC == 2) { float2 v = *reinterpret_cast<const float2 *>(src); ra[p][0] = v.x; ra[p][1 % AVEC] = v.y; }
                 else ra[p][0] = *src;
@@ -140,6 +142,7 @@ __global__ __launch_bounds__(kThreads) void k_gemm(GemmArgs g) {
                 const long long row = m0 + (wm * TM + i) * 32 + 8 * (r / 4) + 4 * kh + (r % 4);
                 if (row < g.n) {
                     float y = acc[i][j][r];
+                    if (g.add) y += g.add[(long long)(col >> 5) * g.n * 32 + row * 32 + (col & 31)];
                     if (g.row_scale) y *= g.row_scale[row];
                     if (g.act == SENSEI_ACT_RELU) y = y > 0.f ? y : 0.f;
                     g.Y[row * y_ld + y_col] = y;
@@ -361,8 +364,10 @@ __global__ __launch_bounds__(kThreads) void k_gemv2(const float *__restrict__ A,
 }  // namespace
 
 hipError_t launch_gemm(const float *A, int64_t lda, const float *W, int64_t ldw, float *Y, int64_t ldy, int64_t n,
-                       int k, int m, int m_store, int act, hipStream_t s, const float *row_scale, KernelTimer *timer, bool y_sliced) {
+                       int k, int m, int m_store, int act, hipStream_t s, const float *row_scale, KernelTimer *timer, bool y_sliced,
+                       bool a_sliced, const float *add_sliced) {
     if (n <= 0 || m_store <= 0) return hipSuccess;
+    if (a_sliced) lda = 32;
     hipEvent_t t0 = timer ? timer->next() : nullptr, t1 = t0 ? timer->next() : nullptr;
     if (t1 && hipEventRecord(t0, s) != hipSuccess) return hipErrorUnknown;
     auto done = [&](hipError_t e) {
@@ -373,6 +378,7 @@ hipError_t launch_gemm(const float *A, int64_t lda, const float *W, int64_t ldw,
     g.row_scale = row_scale;
     g.A = A; g.W = W; g.Y = Y; g.lda = lda; g.ldw = ldw; g.ldy = ldy; g.n = n;
     g.k = k; g.m = m; g.m_store = m_store; g.act = act; g.y_sliced = y_sliced ? 1 : 0;
+    g.a_slice = a_sliced ? n * 32 : 32; g.add = add_sliced;
     int avec = 1, bvec = 1;
     const uintptr_t aa = reinterpret_cast<uintptr_t>(A), wa = reinterpret_cast<uintptr_t>(W);
     if (k % 4 == 0 && lda % 4 == 0 && aa % 16 == 0) avec = 4;

@@ -123,6 +123,11 @@ hipError_t launch_theta_t_vec(const float *theta_sliced, int64_t n, int f, const
 // pos[k] = place of entry k of A in At (binary search in the ascending columns of At); *miss (cleared first) counts entries not found
 hipError_t launch_transpose_pos(const sensei_csr &A, const sensei_csr &At, const ChunkPlan &p, int32_t *pos, int32_t *miss, hipStream_t s);
 
+// out[i] = 1 / v[i]
+hipError_t launch_reciprocal(const float *v, int64_t n, float *out, hipStream_t s);
+// out ((hops * pad32(f_in)) x f_out, ldo): block h holds rows h*f_in .. of W followed by zero rows up to pad32(f_in)
+hipError_t launch_stack_weights(const float *W, int64_t ldw, int hops, int f_in, int f_out, float *out, int64_t ldo, hipStream_t s);
+
 // out2[0] = largest row length, out2[1] = sum of squared row lengths (device, 16 bytes)
 hipError_t launch_row_moments(const sensei_csr &A, unsigned long long *out2, hipStream_t s);
 
@@ -131,8 +136,10 @@ hipError_t launch_row_moments(const sensei_csr &A, unsigned long long *out2, hip
 // row_scale may be null (no scaling).
 hipError_t launch_gemm(const float *A, int64_t lda, const float *W, int64_t ldw, float *Y, int64_t ldy, int64_t n,
                        int k, int m, int m_store, int act, hipStream_t s, const float *row_scale = nullptr,
-                       KernelTimer *timer = nullptr, bool y_sliced = false);
-// y_sliced / a_sliced: that matrix is stored slice-major in tiles of 32 floats (see launch_spmm); its leading dimension is ignored.
+                       KernelTimer *timer = nullptr, bool y_sliced = false, bool a_sliced = false, const float *add_sliced = nullptr);
+// y_sliced / a_sliced: that matrix is stored slice-major in tiles of 32 floats (see launch_spmm); its leading dimension is ignored
+// (a slice-major A has k padded to a multiple of 32 in memory; columns k .. are not read).  add_sliced: optional n x pad32(m)
+// slice-major matrix added to the product before the row scaling and the activation.
 hipError_t launch_gemv2(const float *A, int64_t lda, int64_t n, int k, const float *v1, const float *v2, float *y1,
                         float *y2, hipStream_t s, bool a_sliced = false);
 

@@ -517,6 +517,21 @@ __global__ void k_row_broadcast(const float *__restrict__ s, const float *X, lon
     x.store(Y + i * ldy + q);
 }
 
+__global__ void k_reciprocal(const float *__restrict__ v, long long n, float *__restrict__ out) {
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) out[i] = 1.0f / v[i];
+}
+
+__global__ void k_stack_weights(const float *__restrict__ W, long long ldw, int hops, int f_in, int fp, int f_out, float *__restrict__ out,
+                                long long ldo) {
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (long long)hops * fp * f_out) return;
+    const int m = (int)(i % f_out);
+    const long long row = i / f_out;
+    const int h = (int)(row / fp), f = (int)(row % fp);
+    out[row * ldo + m] = f < f_in ? W[((long long)h * f_in + f) * ldw + m] : 0.f;
+}
+
 // Copy of X (n x f, row-major) into slice-major tiles of 32 columns, optionally scaled per row; the pad columns
 // up to the next multiple of 32 are written as zeros.  One thread per (row, 4 columns).
 __global__ void k_to_slices(const float *__restrict__ s, const float *__restrict__ X, long long ldx, long long n, int f,
@@ -1228,6 +1243,19 @@ hipError_t launch_row_broadcast(const float *s_vec, const float *X, int64_t ldx,
         hipLaunchKernelGGL((k_row_broadcast<4>), dim3(blocks_for(n * (f / 4), kBlock)), dim3(kBlock), 0, s, s_vec, X, (long long)ldx, (long long)n, f, Y, (long long)ldy, act, mask, (long long)ldm);
     else
         hipLaunchKernelGGL((k_row_broadcast<1>), dim3(blocks_for(n * f, kBlock)), dim3(kBlock), 0, s, s_vec, X, (long long)ldx, (long long)n, f, Y, (long long)ldy, act, mask, (long long)ldm);
+    return hipGetLastError();
+}
+
+hipError_t launch_reciprocal(const float *v, int64_t n, float *out, hipStream_t s) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_reciprocal, dim3(blocks_for(n, kBlock)), dim3(kBlock), 0, s, v, (long long)n, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_stack_weights(const float *W, int64_t ldw, int hops, int f_in, int f_out, float *out, int64_t ldo, hipStream_t s) {
+    const long long total = (long long)hops * pad32(f_in) * f_out;
+    if (total <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_stack_weights, dim3(blocks_for(total, kBlock)), dim3(kBlock), 0, s, W, (long long)ldw, hops, f_in, pad32(f_in), f_out, out, (long long)ldo);
     return hipGetLastError();
 }
 

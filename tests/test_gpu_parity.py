@@ -557,3 +557,46 @@ def test_sgc_layer_with_panels_and_argument_checks(ctx):
     Ar = DeviceCSR(gr)
     with pytest.raises(SenseiError):                          # powers need a square pattern
         ctx.sgc_layer(Ar.s, r, c, dev(synth.uniform(1, 1, (gr.n_cols, 8))), dev(synth.glorot(1, 2, 8, 8)), 2, 0)
+
+
+# ------------------------------------------------------------------ TAGCN
+
+@pytest.mark.parametrize("name", ["er", "rmat_hub", "hub_empty", "selfloops", "tiny"])
+@pytest.mark.parametrize("shape", [(40, 9), (9, 40), (64, 64), (100, 33), (3, 1)])
+def test_tagcn_layer_matches_the_polynomial_in_the_operator(ctx, name, shape):
+    g = GRAPHS[name]
+    A = DeviceCSR(g)
+    dr, dc = ctx.degrees(A.s)
+    r, c = ctx.norm_vectors(dr), ctx.norm_vectors(dc)
+    f_in, f_out = shape
+    X = synth.uniform(43, 10, (g.n_cols, f_in))
+    for k in (1, 2, 3):
+        W = synth.glorot(43, 11 + k, (k + 1) * f_in, f_out)
+        ref = oracle.tagcn_layer(g.n_rows, g.row_ptr, g.col_idx, X, W, k, ACT_RELU)
+        for cid in (0, 1):
+            assert_close(ctx.tagcn_layer(A.s, r, c, dev(X), dev(W), k, cid, ACT_RELU), ref, what=f"tagcn k={k} comp {cid}")
+
+
+def test_tagcn_layer_with_panels_strided_operands_and_argument_checks(ctx):
+    from paper_2306_15155_amd import Panels, csr_struct
+    g = synth.rmat(44, 6000, 120_000)
+    A = DeviceCSR(g)
+    P = Panels(ctx, A.s, 3)
+    assert binding_set_min_width(P, 32)
+    Ap = csr_struct(g.n_rows, g.n_cols, A.row_ptr, A.col_idx, None, P)
+    dr, dc = ctx.degrees(A.s)
+    r, c = ctx.norm_vectors(dr), ctx.norm_vectors(dc)
+    X, W = synth.uniform(44, 10, (g.n_cols, 72)), synth.glorot(44, 11, 4 * 72, 130)
+    ref = oracle.tagcn_layer(g.n_rows, g.row_ptr, g.col_idx, X, W, 3)
+    Xs = torch.zeros((g.n_cols, 75), device=DEV)      # odd leading dimensions: the scalar loaders
+    Xs[:, :72] = dev(X)
+    Ws = torch.zeros((4 * 72, 131), device=DEV)
+    Ws[:, :130] = dev(W)
+    for cid in (0, 1):
+        assert_close(ctx.tagcn_layer(Ap, r, c, dev(X), dev(W), 3, cid), ref, what=f"panels comp {cid}")
+        assert_close(ctx.tagcn_layer(A.s, r, c, Xs[:, :72], Ws[:, :130], 3, cid), ref, what=f"strided comp {cid}")
+    P.close()
+    with pytest.raises(SenseiError):
+        ctx.tagcn_layer(A.s, r, c, dev(X), dev(W), 2, 0)     # W holds 4 blocks, not 3
+    with pytest.raises(SenseiError):
+        ctx.tagcn_layer(A.s, r, c, dev(X), dev(W), 3, 2)

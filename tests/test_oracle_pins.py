@@ -356,3 +356,31 @@ def test_sgc_on_a_regular_ring_keeps_constant_columns_and_smooths_the_rest():
     lam = (1 + 2 * sum(np.cos(2 * np.pi * m * t / n) for t in range(1, kh + 1))) / (2 * kh + 1)
     Y = oracle.sgc_layer(n, g.row_ptr, g.col_idx, x, np.ones((1, 1), dtype=np.float32), 6)
     _close(Y, lam ** 6 * x.astype(np.float64), 1e-7)
+
+
+def test_tagcn_is_the_matrix_polynomial():
+    n, f_in, f_out = 50, 6, 4
+    g = _rand_graph(23, n, 160)
+    X = synth.uniform(23, 10, (n, f_in))
+    A = dense.dense_pattern(n, n, g.row_ptr, g.col_idx)
+    Ahat = A / np.sqrt(A.sum(axis=1))[:, None] / np.sqrt(A.sum(axis=0))[None, :]
+    X64 = X.astype(np.float64)
+    for K in (1, 2, 4):
+        W = synth.glorot(23, 11 + K, (K + 1) * f_in, f_out)
+        W64 = W.astype(np.float64)
+        ref = sum(np.linalg.matrix_power(Ahat, k) @ X64 @ W64[k * f_in:(k + 1) * f_in] for k in range(K + 1))
+        _close(oracle.tagcn_layer(n, g.row_ptr, g.col_idx, X, W, K), ref, 1e-12)
+        _close(oracle.tagcn_layer(n, g.row_ptr, g.col_idx, X, W, K, 1), np.maximum(ref, 0.0), 1e-12)
+    # only the one-hop block non-zero: the GCN layer; only the last block non-zero: the K-hop SGC layer
+    W = np.zeros((3 * f_in, f_out), dtype=np.float32)
+    W1 = synth.glorot(23, 20, f_in, f_out)
+    W[f_in:2 * f_in] = W1
+    _close(oracle.tagcn_layer(n, g.row_ptr, g.col_idx, X, W, 2, 1), oracle.gcn_layer(n, n, g.row_ptr, g.col_idx, X, W1, 1), 1e-13)
+    W[:] = 0.0
+    W[2 * f_in:] = W1
+    _close(oracle.tagcn_layer(n, g.row_ptr, g.col_idx, X, W, 2), oracle.sgc_layer(n, g.row_ptr, g.col_idx, X, W1, 2), 1e-13)
+    # self loops only: A^ = I, the layer is X (W_0 + .. + W_K)
+    gs = synth.self_loops_only(n)
+    W = synth.glorot(23, 21, 3 * f_in, f_out)
+    Wsum = W.astype(np.float64).reshape(3, f_in, f_out).sum(axis=0)
+    _close(oracle.tagcn_layer(n, gs.row_ptr, gs.col_idx, X, W, 2), X64 @ Wsum, 1e-13)
