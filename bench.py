@@ -316,6 +316,28 @@ def main():
             sgc[tag(i)] = {nm: round(time_fn(lambda: ctx.sgc_layer(A, r, c, src_of(i), Wd[i], 2, cid, L["act"], out=outs[i]), 2), 4)
                            for cid, nm in ((0, "AGG"), (1, "UPD"))}
         detail["sgc_2hop_ms"] = sgc
+        tag2 = {}
+        for i, L in enumerate(layers):
+            if L["kind"] != "gcn":
+                continue
+            W3 = torch.randn((3 * L["f_in"], L["f_out"]), device=dev) * 0.05
+            tag2[tag(i)] = {nm: round(time_fn(lambda: ctx.tagcn_layer(A, r, c, src_of(i), W3, 2, cid, L["act"], out=outs[i]), 2), 4)
+                            for cid, nm in ((0, "AGG"), (1, "UPD"))}
+            del W3
+        detail["tagcn_2hop_ms"] = tag2
+
+    # ---- GATv2 on the shapes of the GAT layers (separate W_l and W_r): reuse and recompute
+    if not args.no_sweep:
+        v2 = {}
+        for i, L in enumerate(layers):
+            if L["kind"] != "gat":
+                continue
+            Wl2 = torch.randn_like(Wd[i]) * 0.05
+            att2 = torch.randn((L["f_out"],), device=dev) * 0.1
+            v2[tag(i)] = {nm: round(time_fn(lambda: ctx.gatv2_layer(A, src_of(i), Wl2, Wd[i], att2, cid, 0.2, L["act"], out=outs[i]), 2), 4)
+                          for cid, nm in ((0, "REUSE"), (1, "RECOMP"))}
+            del Wl2, att2
+        detail["gatv2_ms"] = v2
 
     # ---- one training iteration of the GCN stack of the workload (the layers whose input is X or the previous layer):
     # forward with the selected compositions, backward with the associations the cost model picks; the first layer needs no dX

@@ -225,6 +225,17 @@ int sensei_gcn_workspace(const sensei_csr *A, int f_in, int f_out, int comp_id, 
 int sensei_gcn_layer(sensei_ctx *ctx, const sensei_csr *A, const float *r, const float *c, sensei_mat X, sensei_mat W,
                      float *Y, int64_t ldy, int activation, int comp_id, void *workspace, size_t ws_bytes, void *stream);
 
+/* GATv2 layer (the attention variant the paper's discussion names): Theta_l = X W_l over the destinations, Theta_r = X W_r
+ * over the sources, e_ij = sum_m att[m] LeakyReLU(Theta_l[i, m] + Theta_r[j, m]) on every stored entry (Eq. 2 in its general
+ * form: a vector per entry, reduced after a non-linearity), alpha = row softmax of e as in the GAT layer,
+ * Y = act( sum_j alpha_ij Theta_r[j, :] ).  W_l and W_r are f_in x f_out; passing the same matrix twice shares the weights
+ * (one GEMM on a square pattern).  att has f_out entries.  Destinations are the first n_rows sources (n_rows <= n_cols).
+ *   comp_id 0 (reuse):     aggregate Theta_r at width f_out;
+ *   comp_id 1 (recompute): aggregate X at width f_in, then one more GEMM with W_r (pays when f_in < f_out). */
+int sensei_gatv2_workspace(const sensei_csr *A, int f_in, int f_out, int comp_id, size_t *bytes);
+int sensei_gatv2_layer(sensei_ctx *ctx, const sensei_csr *A, sensei_mat X, sensei_mat W_l, sensei_mat W_r, const float *att, float neg_slope,
+                       float *Y, int64_t ldy, int activation, int comp_id, void *workspace, size_t ws_bytes, void *stream);
+
 /* K-hop simplified graph convolution (SGC, one of the GCN variants the paper names as further targets of the same
  * re-association): Y = act( A^^k X W ) with A^ = D_r^(-1/2) A~ D_c^(-1/2) on a square pattern, k_hops >= 1.
  *   comp_id 0: aggregate first, ((A^^k X) W): k SpMMs at width f_in, then the GEMM (the choice for f_in <= f_out);

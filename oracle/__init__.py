@@ -240,6 +240,28 @@ def tagcn_layer(n, row_ptr, col_idx, X, W, k_hops, act=0):
     return activation(Y, act)
 
 
+def gatv2_layer(n_rows, n_cols, row_ptr, col_idx, X, W_l, W_r, att, slope=0.2, act=0, rows=None):
+    """GATv2 layer: Theta_l = X W_l (destinations = the first n_rows sources), Theta_r = X W_r,
+    e_ij = att . LeakyReLU(Theta_l[i] + Theta_r[j]) on the stored entries (Eq. 2 with a vector per entry), alpha = row
+    softmax of e as in Eq. 5, Y = act(alpha Theta_r) as in Eq. 6.  ``rows`` selects output rows."""
+    row_ptr, col_idx = _i32(row_ptr), _i32(col_idx)
+    X32 = _f32(X)
+    Th_r = gemm(X32.astype(np.float64), _f32(W_r).astype(np.float64))
+    a = _f32(att).astype(np.float64)
+    sel = np.arange(n_rows, dtype=np.int64) if rows is None else np.asarray(rows, dtype=np.int64)
+    Th_l = gemm(X32[sel].astype(np.float64), _f32(W_l).astype(np.float64))
+    seg = [col_idx[row_ptr[i]:row_ptr[i + 1]] for i in sel]
+    sub_ptr = np.concatenate([[0], np.cumsum([x.size for x in seg])]).astype(np.int32)
+    sub_idx = (np.concatenate(seg) if seg else np.zeros(0)).astype(np.int32)
+    e = np.empty(sub_idx.size, dtype=np.float64)
+    for q in range(sel.size):
+        lo, hi = sub_ptr[q], sub_ptr[q + 1]
+        T = Th_l[q][None, :] + Th_r[sub_idx[lo:hi]]
+        e[lo:hi] = np.where(T > 0.0, T, slope * T) @ a
+    alpha = edge_softmax(sub_ptr, e)
+    return activation(spmm(sub_ptr, sub_idx, alpha, Th_r), act)
+
+
 def gat_layer_heads(n_rows, n_cols, row_ptr, col_idx, X, W, a_l, a_r, n_heads, slope=0.2, act=0, rows=None, omp=False):
     """Multi-head GAT with concatenated heads: head h is the single-head layer of Eq. 5 / 6 on columns
     [h d, (h + 1) d) of W, a_l, a_r (heads share nothing but the input)."""

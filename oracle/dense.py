@@ -48,6 +48,24 @@ def gat_layer_dense(A, X, W, a_l, a_r, slope=0.2, act=0):
     return (np.maximum(Y, 0.0) if act == 1 else Y), alpha
 
 
+def gatv2_layer_dense(A, X, W_l, W_r, att, slope=0.2, act=0):
+    """Dense GATv2: every pair (i, j) gets att . LeakyReLU(Theta_l[i] + Theta_r[j]); the pattern masks the softmax."""
+    n_rows, n_cols = A.shape
+    th_r = X.astype(np.float64) @ W_r.astype(np.float64)
+    th_l = X[:n_rows].astype(np.float64) @ W_l.astype(np.float64)
+    T = th_l[:, None, :] + th_r[None, :, :]
+    E = np.where(T > 0.0, T, slope * T) @ att.astype(np.float64)
+    alpha = np.zeros_like(E)
+    for i in range(n_rows):
+        mask = A[i] != 0.0
+        if not mask.any():
+            continue
+        ex = np.exp(E[i, mask] - E[i, mask].max())
+        alpha[i, mask] = ex / ex.sum()
+    Y = alpha @ th_r
+    return (np.maximum(Y, 0.0) if act == 1 else Y), alpha
+
+
 def spmm_dense(A_val, B):
     """Eq. 1 over every (i,j), zeros included: plain GEMM on the densified matrix."""
     n, m = A_val.shape

@@ -31,7 +31,7 @@ EXPORTS = (
     "sensei_select", "sensei_profile_enable", "sensei_profile_read", "sensei_panels_bytes", "sensei_panels_create",
     "sensei_panels_count", "sensei_panels_destroy", "sensei_panels_set_min_width", "sensei_panels_tune_bytes",
     "sensei_panels_tune", "sensei_gcn_backward_workspace", "sensei_gcn_backward", "sensei_select_gcn_backward", "sensei_transpose_positions",
-    "sensei_gat_backward_workspace", "sensei_gat_backward", "sensei_gat_layer_heads", "sensei_sgc_workspace", "sensei_sgc_layer", "sensei_tagcn_workspace", "sensei_tagcn_layer",
+    "sensei_gat_backward_workspace", "sensei_gat_backward", "sensei_gat_layer_heads", "sensei_sgc_workspace", "sensei_sgc_layer", "sensei_tagcn_workspace", "sensei_tagcn_layer", "sensei_gatv2_workspace", "sensei_gatv2_layer",
 )
 
 
@@ -97,6 +97,8 @@ def lib():
         L.sensei_sgc_layer.argtypes = [vp, P(CsrStruct), vp, vp, MatStruct, MatStruct, i32, vp, i64, i32, i32, vp, sz, vp]
         L.sensei_tagcn_workspace.argtypes = [P(CsrStruct), i32, i32, i32, i32, P(sz)]
         L.sensei_tagcn_layer.argtypes = [vp, P(CsrStruct), vp, vp, MatStruct, MatStruct, i32, vp, i64, i32, i32, vp, sz, vp]
+        L.sensei_gatv2_workspace.argtypes = [P(CsrStruct), i32, i32, i32, P(sz)]
+        L.sensei_gatv2_layer.argtypes = [vp, P(CsrStruct), MatStruct, MatStruct, MatStruct, vp, f32, vp, i64, i32, i32, vp, sz, vp]
         L.sensei_select_workspace.argtypes = [i32, P(CsrStruct), i32, i32, P(sz)]
         L.sensei_select.argtypes = [vp, i32, P(CsrStruct), i32, i32, i32, P(ctypes.c_int), P(f32), vp, sz, vp]
         L.sensei_panels_bytes.argtypes = [P(CsrStruct), i32, P(sz)]
@@ -396,6 +398,16 @@ class Context:
         self.ws.ensure(need.value)
         _check(lib().sensei_tagcn_layer(self._h, ctypes.byref(A), _ptr(r), _ptr(c), mat_struct(X), mat_struct(W), k_hops, _ptr(Y), mat_struct(Y).ld,
                                         activation, comp_id, self.ws.ptr, self.ws.nbytes, _stream()), "sensei_tagcn_layer")
+        return Y
+
+    def gatv2_layer(self, A: CsrStruct, X, W_l, W_r, att, comp_id, neg_slope=0.2, activation=ACT_NONE, out=None):
+        """GATv2 layer; pass the same tensor as W_l and W_r to share the weights; comp_id 0 reuses Theta_r, 1 recomputes."""
+        Y = torch.empty((A.n_rows, W_r.size(1)), dtype=torch.float32, device=self.device) if out is None else out
+        need = ctypes.c_size_t()
+        _check(lib().sensei_gatv2_workspace(ctypes.byref(A), X.size(1), W_r.size(1), comp_id, ctypes.byref(need)), "sensei_gatv2_workspace")
+        self.ws.ensure(need.value)
+        _check(lib().sensei_gatv2_layer(self._h, ctypes.byref(A), mat_struct(X), mat_struct(W_l), mat_struct(W_r), _ptr(att), neg_slope, _ptr(Y),
+                                        mat_struct(Y).ld, activation, comp_id, self.ws.ptr, self.ws.nbytes, _stream()), "sensei_gatv2_layer")
         return Y
 
     def gat_layer_heads(self, A: CsrStruct, X, W, a_l, a_r, n_heads, comp_id, neg_slope=0.2, activation=ACT_NONE, out=None):

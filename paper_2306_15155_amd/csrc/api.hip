@@ -494,6 +494,69 @@ int run_gat(const sensei_csr &A, const sensei_mat &X, const sensei_mat &W, const
     return SENSEI_OK;
 }
 
+// ---- GATv2: e_ij = a . LeakyReLU(W_l x_i + W_r x_j), Y = act(sum_j alpha_ij W_r x_j)
+size_t gatv2_ws(const sensei_csr &A, int f_in, int f_out, int id, bool shared) {
+    const int fo = pad32(f_out), fi = pad4(f_in);
+    size_t b = plan_bytes(A.nnz) + softmax_ws_bytes(A) + 512;
+    b += align_up((size_t)(A.nnz > 0 ? A.nnz : 1) * sizeof(float), 256);       // logits, then the attention weights in place
+    b += align_up((size_t)fo * sizeof(float), 256);                            // a, padded
+    b += align_up((size_t)A.n_cols * fo * sizeof(float), 256);                 // Theta_r (slice-major)
+    if (!shared) b += align_up((size_t)A.n_rows * fo * sizeof(float), 256);    // Theta_l (slice-major)
+    if (id == 0) {
+        b += spmm_carry_bytes(A.nnz, fo);
+    } else {
+        b += spmm_carry_bytes(A.nnz, pad32(f_in));
+        b += align_up((size_t)A.n_rows * fi * sizeof(float), 256);             // U = alpha.X
+        b += align_up((size_t)A.n_cols * pad32(f_in) * sizeof(float), 256);    // slice-major copy of X
+    }
+    return b;
+}
+
+int run_gatv2(const sensei_csr &A, const sensei_mat &X, const sensei_mat &Wl, const sensei_mat &Wr, const float *att, float slope, float *Y,
+              int64_t ldy, int act, int id, void *ws, size_t ws_bytes, hipStream_t s, Timers *tm) {
+    KernelTimer *kt = tm ? &tm->spmm : nullptr, *gt = tm ? &tm->gemm : nullptr;
+    const int f_in = (int)X.cols, f_out = (int)Wr.cols;
+    const int fo = pad32(f_out), fi = pad4(f_in);
+    const bool shared = (Wl.ptr == Wr.ptr && Wl.ld == Wr.ld);
+    Carver cv(ws, ws_bytes);
+    ChunkPlan plan = make_plan(A, cv);
+    float2 *stats = cv.take<float2>((size_t)A.n_rows + 1);
+    float2 *carry_stats = cv.take<float2>((size_t)plan.n_chunks);
+    float *logits = cv.take<float>((size_t)(A.nnz > 0 ? A.nnz : 1));
+    float *att_pad = cv.take<float>((size_t)fo);
+    float *theta_r = cv.take<float>((size_t)A.n_cols * fo);
+    // the destinations are the first n_rows sources: with one shared weight matrix their projections are rows of Theta_r,
+    // but a slice of Theta_r holds n_cols rows and a slice of Theta_l n_rows, so the slices coincide only on a square pattern
+    float *theta_l = (shared && A.n_rows == A.n_cols) ? theta_r : cv.take<float>((size_t)A.n_rows * fo);
+    SENSEI_TRY(launch_chunk_rows(A, plan, s));
+    SENSEI_TRY(launch_to_slices(nullptr, att, f_out, 1, f_out, att_pad, s));
+    SENSEI_TRY(launch_gemm(X.ptr, X.ld, Wr.ptr, Wr.ld, theta_r, fo, A.n_cols, f_in, f_out, fo, SENSEI_ACT_NONE, s, nullptr, gt, true));
+    if (theta_l != theta_r)
+        SENSEI_TRY(launch_gemm(X.ptr, X.ld, Wl.ptr, Wl.ld, theta_l, fo, A.n_rows, f_in, f_out, fo, SENSEI_ACT_NONE, s, nullptr, gt, true));
+    SENSEI_TRY(launch_score_v2(A, theta_l, theta_r, f_out, att_pad, slope, logits, plan, s));
+    SENSEI_TRY(launch_softmax(A, logits, logits, plan, stats, carry_stats, s));
+    sensei_csr Aw = A;
+    Aw.val = logits;
+    if (id == 0) {  // reuse: aggregate the projected features at width f_out
+        float *carry = cv.take<float>(spmm_carry_bytes(A.nnz, fo) / sizeof(float));
+        SENSEI_TRY(spmm_any(Aw, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, theta_r, fo, fo, Y, ldy, f_out, act, plan, carry, s, kt, false, nullptr, true));
+    } else {        // recompute: aggregate the inputs at width f_in, then project once more
+        float *carry = cv.take<float>(spmm_carry_bytes(A.nnz, pad32(f_in)) / sizeof(float));
+        float *U = cv.take<float>((size_t)A.n_rows * fi);
+        const float *x_src = X.ptr;
+        const bool x_sliced = relayout_pays(A);
+        if (x_sliced) {
+            float *T = cv.take<float>((size_t)A.n_cols * pad32(f_in));
+            SENSEI_TRY(launch_to_slices(nullptr, X.ptr, X.ld, A.n_cols, f_in, T, s));
+            x_src = T;
+        }
+        SENSEI_TRY(spmm_any(Aw, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, x_src, X.ld, f_in, U, fi, f_in, SENSEI_ACT_NONE, plan, carry, s, kt, false,
+                            nullptr, x_sliced));
+        SENSEI_TRY(launch_gemm(U, fi, Wr.ptr, Wr.ld, Y, ldy, A.n_rows, f_in, f_out, f_out, act, s, nullptr, gt));
+    }
+    return SENSEI_OK;
+}
+
 // ---- backward of the GAT layer
 size_t gat_bwd_ws(const sensei_csr &A, int f_in, int f_out) {
     const size_t nz = (size_t)(A.nnz > 0 ? A.nnz : 1), fo32 = pad32(f_out), fo4 = pad4(f_out), fi4 = pad4(f_in);
@@ -1335,6 +1398,34 @@ int sensei_gat_layer(sensei_ctx *ctx, const sensei_csr *A, sensei_mat X, sensei_
                      float neg_slope, float *Y, int64_t ldy, int activation, int comp_id, void *workspace, size_t ws_bytes,
                      void *stream) {
     return sensei_gat_layer_heads(ctx, A, X, W, a_l, a_r, 1, neg_slope, Y, ldy, activation, comp_id, workspace, ws_bytes, stream);
+}
+
+int sensei_gatv2_workspace(const sensei_csr *A, int f_in, int f_out, int comp_id, size_t *bytes) {
+    if (!csr_ok(A, false) || f_in <= 0 || f_out <= 0 || !bytes) return SENSEI_INVALID_ARGUMENT;
+    if (comp_id != 0 && comp_id != 1) return SENSEI_INVALID_COMPOSITION;
+    *bytes = gatv2_ws(*A, f_in, f_out, comp_id, false);
+    return SENSEI_OK;
+}
+
+int sensei_gatv2_layer(sensei_ctx *ctx, const sensei_csr *A, sensei_mat X, sensei_mat W_l, sensei_mat W_r, const float *att, float neg_slope,
+                       float *Y, int64_t ldy, int activation, int comp_id, void *workspace, size_t ws_bytes, void *stream) {
+    if (comp_id != 0 && comp_id != 1) return SENSEI_INVALID_COMPOSITION;
+    if (!ctx || !csr_ok(A, false) || !mat_ok(X) || !mat_ok(W_l) || !mat_ok(W_r)) return SENSEI_INVALID_ARGUMENT;
+    if (activation != SENSEI_ACT_NONE && activation != SENSEI_ACT_RELU) return SENSEI_INVALID_ARGUMENT;
+    if (A->n_rows > A->n_cols) return SENSEI_INVALID_ARGUMENT;
+    if (X.rows != A->n_cols || X.cols != W_r.rows || X.cols <= 0 || W_r.cols <= 0 || ldy < W_r.cols) return SENSEI_INVALID_ARGUMENT;
+    if (W_l.rows != W_r.rows || W_l.cols != W_r.cols) return SENSEI_INVALID_ARGUMENT;
+    if (X.cols > (1 << 20) || W_r.cols > (1 << 20)) return SENSEI_INVALID_ARGUMENT;
+    if (!X.ptr && A->n_cols > 0) return SENSEI_INVALID_ARGUMENT;
+    if (!W_l.ptr || !W_r.ptr || !att || (!Y && A->n_rows > 0) || !workspace) return SENSEI_INVALID_ARGUMENT;
+    const size_t ybytes = mat_bytes(Y, A->n_rows, W_r.cols, ldy);
+    if (overlap(Y, ybytes, X.ptr, mat_bytes(X.ptr, X.rows, X.cols, X.ld)) || overlap(Y, ybytes, W_r.ptr, mat_bytes(W_r.ptr, W_r.rows, W_r.cols, W_r.ld)) ||
+        overlap(Y, ybytes, W_l.ptr, mat_bytes(W_l.ptr, W_l.rows, W_l.cols, W_l.ld)) || overlap(Y, ybytes, workspace, ws_bytes) ||
+        overlap(X.ptr, mat_bytes(X.ptr, X.rows, X.cols, X.ld), workspace, ws_bytes))
+        return SENSEI_INVALID_ARGUMENT;
+    if (ws_bytes < gatv2_ws(*A, (int)X.cols, (int)W_r.cols, comp_id, false)) return SENSEI_WORKSPACE_TOO_SMALL;
+    if (A->n_rows == 0) return SENSEI_OK;
+    return run_gatv2(*A, X, W_l, W_r, att, neg_slope, Y, ldy, activation, comp_id, workspace, ws_bytes, as_stream(stream), &ctx->timers);
 }
 
 int sensei_select_workspace(int kind, const sensei_csr *A, int f_in, int f_out, size_t *bytes) {

@@ -114,6 +114,10 @@ hipError_t launch_gat_dalpha(const sensei_csr &A, const float *theta, const floa
 // dt[k] = alpha (dalpha - rowdot_i) LeakyReLU'(e); dt may be dalpha; adt_t[t_pos[k]] = (alpha, dt)
 hipError_t launch_gat_dt(const sensei_csr &A, const float *logits, const float *dalpha, const float *rowdot, const float2 *mz,
                          const int32_t *t_pos, float slope, float *dt, float2 *adt_t, const ChunkPlan &p, hipStream_t s);
+// logits[k] = sum_m att[m] LeakyReLU(theta_l[i, m] + theta_r[j, m]) per stored entry (i, j); both matrices slice-major
+// (n_rows x pad32(f), n_cols x pad32(f)), att padded with zeros to pad32(f)
+hipError_t launch_score_v2(const sensei_csr &A, const float *theta_l, const float *theta_r, int f, const float *att_padded, float slope,
+                           float *logits, const ChunkPlan &p, hipStream_t s);
 hipError_t launch_rank1_add(float *D, int64_t ldd, int64_t n, int f, const float *ds_l, int64_t n_l, const float *ds_r, const float *a_l,
                             const float *a_r, hipStream_t s);
 // out_l = Theta^T v_l (v_l counted for the first n_l rows), out_r = Theta^T v_r; Theta slice-major n x pad32(f); sums in fp64

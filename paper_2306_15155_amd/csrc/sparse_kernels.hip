@@ -974,6 +974,71 @@ __global__ __launch_bounds__(kBlock) void k_gat_dalpha(GatBwdArgs a, int tile, i
     }
 }
 
+struct ScoreV2Args {
+    NnzArgs n;
+    const float *theta_l, *theta_r;  // slice-major: W_l x over the destinations, W_r x over the sources
+    const float *att;                // attention vector padded with zeros to a multiple of 32
+    float *logits;                   // out, per stored entry
+    long long tl_tile, tr_tile;      // floats from one tile to the next
+    float slope;
+};
+
+// Logits of the GATv2 score, e_ij = sum_m a[m] LeakyReLU(Theta_l[i, m] + Theta_r[j, m]): the g-SDDMM of Eq. 2 with an
+// inner operator that is neither a product nor a sum alone.  Same walk as k_gat_dalpha: one launch per 32-column slice,
+// eight lanes per neighbour, the lane that owns an entry adds the slice's share to logits[k].
+__global__ __launch_bounds__(kBlock) void k_score_v2(ScoreV2Args a, int tile, int first) {
+    const int chunk = wave_chunk();
+    if (chunk >= a.n.n_chunks) return;
+    const int lane = threadIdx.x & 63;
+    const int g = lane >> 3, sub = lane & 7;
+    const float *theta_r = a.theta_r + (size_t)tile * a.tr_tile + sub * 4;
+    const float *theta_l = a.theta_l + (size_t)tile * a.tl_tile + sub * 4;
+    const float4 w = *reinterpret_cast<const float4 *>(a.att + tile * 32 + sub * 4);
+    const float slope = a.slope;
+    const long long lo_ll = (long long)chunk * a.n.chunk_nnz;
+    const int lo = (int)lo_ll;
+    const int hi = (int)((lo_ll + a.n.chunk_nnz < (long long)a.n.nnz) ? lo_ll + a.n.chunk_nnz : (long long)a.n.nnz);
+    if (lo >= hi) return;
+    const int i0 = a.n.chunk_row[chunk];
+    int i = __builtin_amdgcn_readfirstlane((a.n.row_ptr[i0] > lo) ? i0 - 1 : i0);
+    int pos = lo;
+    while (pos < hi) {
+        const int re = __builtin_amdgcn_readfirstlane(a.n.row_ptr[i + 1]);
+        if (re > pos) {
+            const int seg_hi = re < hi ? re : hi;
+            const float4 p = *reinterpret_cast<const float4 *>(theta_l + (size_t)i * 32);
+            for (int k0 = pos; k0 < seg_hi; k0 += 64) {
+                const int kl = k0 + lane;
+                const int col = a.n.col_idx[kl < seg_hi ? kl : pos];
+                float4 b[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int j = lane_read((u * 8 + g) * 4, col);
+                    b[u] = *reinterpret_cast<const float4 *>(theta_r + (size_t)j * 32);
+                }
+                const int k_own = k0 + sub * 8 + g;  // lane (g, sub) owns this entry: coalesced 256-byte accesses
+                const bool own = k_own < seg_hi;
+                float v = (own && !first) ? a.logits[k_own] : 0.f;
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const float tx = p.x + b[u].x, ty = p.y + b[u].y, tz = p.z + b[u].z, tw = p.w + b[u].w;
+                    float d = w.x * (tx > 0.f ? tx : slope * tx);
+                    d = fmaf(w.y, ty > 0.f ? ty : slope * ty, d);
+                    d = fmaf(w.z, tz > 0.f ? tz : slope * tz, d);
+                    d = fmaf(w.w, tw > 0.f ? tw : slope * tw, d);
+                    d += dpp_f32<0xB1>(d);
+                    d += dpp_f32<0x4E>(d);
+                    d += dpp_f32<0x141>(d);
+                    if (sub == u) v += d;
+                }
+                if (own) a.logits[k_own] = v;
+            }
+            pos = seg_hi;
+        }
+        i = __builtin_amdgcn_readfirstlane(i + 1);
+    }
+}
+
 struct GatDtArgs {
     NnzArgs n;
     const float *logits, *dalpha, *rowdot;
@@ -1319,6 +1384,20 @@ hipError_t launch_gat_dalpha(const sensei_csr &A, const float *theta, const floa
     for (int t = 0; t < a.n_tiles; ++t)
         hipLaunchKernelGGL(k_gat_dalpha, grid, dim3(kBlock), 0, s, a, t, t == 0 ? 1 : 0, t == a.n_tiles - 1 ? 1 : 0);
     if (p.n_chunks > 1) hipLaunchKernelGGL(k_sum_fixup, dim3(blocks_for(p.n_chunks - 1, kBlock)), dim3(kBlock), 0, s, a.n, rowdot, carry);
+    return hipGetLastError();
+}
+
+hipError_t launch_score_v2(const sensei_csr &A, const float *theta_l, const float *theta_r, int f, const float *att_padded, float slope,
+                           float *logits, const ChunkPlan &p, hipStream_t s) {
+    if (A.nnz <= 0) return hipSuccess;
+    ScoreV2Args a;
+    a.n = nnz_args(A, p);
+    a.theta_l = theta_l; a.theta_r = theta_r; a.att = att_padded; a.logits = logits; a.slope = slope;
+    a.tl_tile = (long long)(A.n_rows > 0 ? A.n_rows : 1) * 32;
+    a.tr_tile = (long long)(A.n_cols > 0 ? A.n_cols : 1) * 32;
+    const dim3 grid(blocks_for(p.n_chunks, kWavesPerBlock));
+    const int n_tiles = (f + 31) / 32;
+    for (int t = 0; t < n_tiles; ++t) hipLaunchKernelGGL(k_score_v2, grid, dim3(kBlock), 0, s, a, t, t == 0 ? 1 : 0);
     return hipGetLastError();
 }
 

@@ -231,6 +231,23 @@ def test_config2_sgc_two_hops_full_size(ctx, reddit_like):
         del Y
 
 
+def test_config4_gatv2_full_size(ctx, reddit_like):
+    """GATv2 layer 602 -> 64 on the Reddit-shaped graph: sampled rows (the longest, a shortest, 300 random) against the oracle."""
+    g, A = reddit_like
+    f_in, d = 602, 64
+    X = synth.uniform(7, 10, (g.n_cols, f_in))
+    W_l, W_r = synth.glorot(7, 120, f_in, d), synth.glorot(7, 121, f_in, d)
+    att = synth.normal(7, 220, (d,), 0.0, 0.1)
+    rows = _sample_rows(g, 12, 300)
+    want = oracle.gatv2_layer(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W_l, W_r, att, 0.2, ACT_RELU, rows=rows)
+    sel = torch.from_numpy(rows.astype(np.int64)).to(DEV)
+    Xd, Wl, Wr, ad = dev(X), dev(W_l), dev(W_r), dev(att)
+    for cid in (0, 1):
+        Y = ctx.gatv2_layer(A.s, Xd, Wl, Wr, ad, cid, 0.2, ACT_RELU)
+        assert_close(Y[sel], want, what=f"gatv2 comp {cid}")
+        del Y
+
+
 def test_config4_gat_backward_full_size(ctx, reddit_like):
     """Training step of the GAT layer 602 -> 64 on the Reddit-shaped graph: every gradient against the oracle.
 

@@ -600,3 +600,38 @@ def test_tagcn_layer_with_panels_strided_operands_and_argument_checks(ctx):
         ctx.tagcn_layer(A.s, r, c, dev(X), dev(W), 2, 0)     # W holds 4 blocks, not 3
     with pytest.raises(SenseiError):
         ctx.tagcn_layer(A.s, r, c, dev(X), dev(W), 3, 2)
+
+
+# ------------------------------------------------------------------ GATv2
+
+@pytest.mark.parametrize("name", ["er", "rmat_hub", "hub_empty", "rect", "selfloops", "tiny"])
+@pytest.mark.parametrize("shape", [(40, 8), (24, 32), (9, 64), (50, 41), (100, 130)])   # f_in, f_out
+def test_gatv2_layer_matches_the_definition(ctx, name, shape):
+    g = GRAPHS[name]
+    A = DeviceCSR(g)
+    f_in, d = shape
+    X = synth.uniform(45, 10, (g.n_cols, f_in))
+    W_l, W_r = synth.glorot(45, 11, f_in, d), synth.glorot(45, 12, f_in, d)
+    att = synth.normal(45, 13, (d,), 0.0, 0.5)
+    ref = oracle.gatv2_layer(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W_l, W_r, att, 0.2, ACT_RELU)
+    Xd, Wl, Wr, ad = dev(X), dev(W_l), dev(W_r), dev(att)
+    for cid in (0, 1):
+        assert_close(ctx.gatv2_layer(A.s, Xd, Wl, Wr, ad, cid, 0.2, ACT_RELU), ref, what=f"gatv2 comp {cid}")
+    shared = oracle.gatv2_layer(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W_r, W_r, att, 0.2, ACT_NONE)
+    for cid in (0, 1):
+        assert_close(ctx.gatv2_layer(A.s, Xd, Wr, Wr, ad, cid, 0.2, ACT_NONE), shared, what=f"shared weights comp {cid}")
+
+
+def test_gatv2_layer_larger_graph_and_argument_checks(ctx):
+    g = synth.rmat(46, 6000, 120_000)
+    A = DeviceCSR(g)
+    X = synth.uniform(46, 10, (g.n_cols, 72))
+    W_l, W_r = synth.glorot(46, 11, 72, 96), synth.glorot(46, 12, 72, 96)
+    att = synth.normal(46, 13, (96,), 0.0, 0.5)
+    ref = oracle.gatv2_layer(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W_l, W_r, att)
+    for cid in (0, 1):
+        assert_close(ctx.gatv2_layer(A.s, dev(X), dev(W_l), dev(W_r), dev(att), cid), ref, what=f"comp {cid}")
+    with pytest.raises(SenseiError):
+        ctx.gatv2_layer(A.s, dev(X), dev(W_l), dev(W_r), dev(att), 2)
+    with pytest.raises(SenseiError):
+        ctx.gatv2_layer(A.s, dev(X), dev(W_l[:, :64].copy()), dev(W_r), dev(att), 0)   # W_l and W_r differ in shape

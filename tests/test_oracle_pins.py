@@ -384,3 +384,50 @@ def test_tagcn_is_the_matrix_polynomial():
     W = synth.glorot(23, 21, 3 * f_in, f_out)
     Wsum = W.astype(np.float64).reshape(3, f_in, f_out).sum(axis=0)
     _close(oracle.tagcn_layer(n, gs.row_ptr, gs.col_idx, X, W, 2), X64 @ Wsum, 1e-13)
+
+
+# --------------------------------------------------------------- GATv2
+
+def _v2_inputs(seed, n_cols, f_in, d):
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((n_cols, f_in)).astype(np.float32)
+    W_l = (0.5 * rng.standard_normal((f_in, d))).astype(np.float32)
+    W_r = (0.5 * rng.standard_normal((f_in, d))).astype(np.float32)
+    att = rng.standard_normal(d).astype(np.float32)
+    return X, W_l, W_r, att
+
+
+@pytest.mark.parametrize("act", [0, 1])
+def test_gatv2_matches_dense_brute_force(act):
+    g = _rand_graph(24, 45, 150)
+    X, W_l, W_r, att = _v2_inputs(24, 45, 7, 5)
+    A = dense.dense_pattern(45, 45, g.row_ptr, g.col_idx)
+    _close(oracle.gatv2_layer(45, 45, g.row_ptr, g.col_idx, X, W_l, W_r, att, 0.2, act), dense.gatv2_layer_dense(A, X, W_l, W_r, att, 0.2, act)[0])
+    rows = np.array([3, 44, 0, 17])
+    _close(oracle.gatv2_layer(45, 45, g.row_ptr, g.col_idx, X, W_l, W_r, att, 0.2, act, rows=rows),
+           dense.gatv2_layer_dense(A, X, W_l, W_r, att, 0.2, act)[0][rows])
+    gr = _rect_block(25, 12, 30, 4)
+    Xr = X[:30]
+    Ar = dense.dense_pattern(12, 30, gr.row_ptr, gr.col_idx)
+    _close(oracle.gatv2_layer(12, 30, gr.row_ptr, gr.col_idx, Xr, W_l, W_r, att, 0.2, act), dense.gatv2_layer_dense(Ar, Xr, W_l, W_r, att, 0.2, act)[0])
+
+
+def test_gatv2_special_cases():
+    n = 40
+    g = _rand_graph(26, n, 130)
+    X, W_l, W_r, att = _v2_inputs(26, n, 6, 8)
+    A = dense.dense_pattern(n, n, g.row_ptr, g.col_idx)
+    Th_r = X.astype(np.float64) @ W_r.astype(np.float64)
+    # zero attention vector: all logits equal, the layer averages the projected neighbours
+    _close(oracle.gatv2_layer(n, n, g.row_ptr, g.col_idx, X, W_l, W_r, np.zeros(8, dtype=np.float32)), (A / A.sum(axis=1, keepdims=True)) @ Th_r, 1e-12)
+    # slope 1 makes the score linear: e_ij = att.Theta_l[i] + att.Theta_r[j], and the term of i cancels in the row softmax, so
+    # the weights are those of the GAT layer of Eq. 5 with W = W_r, a_r = att, slope 1 and any a_l
+    a_any = np.linspace(-1.0, 1.0, 8).astype(np.float32)
+    _close(oracle.gatv2_layer(n, n, g.row_ptr, g.col_idx, X, W_l, W_r, att, 1.0), oracle.gat_layer(n, n, g.row_ptr, g.col_idx, X, W_r, a_any, att, 1.0), 1e-11)
+    # self loops only: alpha = 1, the layer is X W_r
+    gs = synth.self_loops_only(n)
+    _close(oracle.gatv2_layer(n, n, gs.row_ptr, gs.col_idx, X, W_l, W_r, att), Th_r, 1e-13)
+    # unlike the GAT layer the ranking of the neighbours depends on the destination: with slope 0.2 some row's weights differ
+    # from the slope-1 (static) ones
+    assert np.max(np.abs(oracle.gatv2_layer(n, n, g.row_ptr, g.col_idx, X, W_l, W_r, att, 0.2) -
+                         oracle.gatv2_layer(n, n, g.row_ptr, g.col_idx, X, W_l, W_r, att, 1.0))) > 1e-3
