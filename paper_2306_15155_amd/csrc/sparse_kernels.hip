@@ -891,6 +891,111 @@ __device__ __forceinline__ float dpp_f32(float x) {
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, false));
 }
 
+// ---- per-entry reductions over one 32-column slice (the general g-SDDMM of Eq. 2: a vector per stored entry)
+//
+// acc[k] (+)= sum over the slice's 32 columns of inner(right[j, col]) for the entries k = (i, j) in [lo, hi) of one row,
+// `right` slice-major and already offset by this lane's first column (4 * (lane % 4)).  Four lanes take one neighbour:
+// lane `sub` of the four reads columns 4 sub .. 4 sub + 3 and 16 + 4 sub .. 16 + 4 sub + 3, so each of the two loads of
+// a step covers 64 contiguous bytes of 16 neighbours' lines; four steps make a batch of 64 entries.  The four partial
+// sums a lane holds after a batch (one per step) are reduced across the four lanes and scattered at the same time
+// (two exchanges: keep the half this lane will own, hand the other half to the partner), after which lane
+// (g = lane / 4, sub) owns entry k0 + 16 sub + g: the read-modify-write of acc is one coalesced 256-byte access.
+// Two batches are kept in flight: the gathers (and acc values) of the next batch are requested before the current
+// one is reduced.  own(k, v, aux) sees every finished entry once (aux = aux_arr[k] when READ_AUX).
+struct SliceBatch {
+    float4 b[8];
+    float v, aux;
+};
+
+template <bool READ_AUX, class Inner, class Own>
+__device__ __forceinline__ void slice_piece(const int32_t *__restrict__ col_idx, const float *right, float *acc, const float *aux_arr,
+                                            bool first, int lane, int lo, int hi, Inner inner, Own own) {
+    const int g = lane >> 2, sub = lane & 3;
+    const bool up = (sub & 2) != 0, odd = (sub & 1) != 0;
+    auto col_at = [&](int k0) {
+        const int kl = k0 + lane;
+        return col_idx[kl < hi ? kl : lo];
+    };
+    auto issue = [&](SliceBatch &B, int col, int k0) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int j = lane_read((u * 16 + g) * 4, col);
+            const float *src = right + (size_t)j * 32;
+            B.b[2 * u] = *reinterpret_cast<const float4 *>(src);
+            B.b[2 * u + 1] = *reinterpret_cast<const float4 *>(src + 16);
+        }
+        const int k_own = k0 + sub * 16 + g;
+        B.v = (k_own < hi && !first) ? acc[k_own] : 0.f;
+        B.aux = (READ_AUX && k_own < hi) ? aux_arr[k_own] : 0.f;
+    };
+    auto consume = [&](SliceBatch &B, int k0) {
+        float d[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) d[u] = inner(B.b[2 * u], B.b[2 * u + 1]);
+        // lanes 2, 3 of the four will own steps 2, 3: they keep d[2], d[3] and receive the partner's, and hand over d[0], d[1]
+        const float keep_a = up ? d[2] : d[0], keep_b = up ? d[3] : d[1];
+        const float send_a = up ? d[0] : d[2], send_b = up ? d[1] : d[3];
+        const float a2 = keep_a + dpp_f32<0x4E>(send_a);   // from lane ^ 2
+        const float b2 = keep_b + dpp_f32<0x4E>(send_b);
+        const float keep = odd ? b2 : a2, send = odd ? a2 : b2;
+        const float total = keep + dpp_f32<0xB1>(send);    // from lane ^ 1: the sum over the four lanes for step `sub`
+        const int k_own = k0 + sub * 16 + g;
+        if (k_own < hi) {
+            const float v = B.v + total;
+            acc[k_own] = v;
+            own(k_own, v, B.aux);
+        }
+    };
+    SliceBatch A, B;
+    const int c0 = col_at(lo);
+    int c1 = col_at(lo + 64);
+    issue(A, c0, lo);
+    for (int k0 = lo;; k0 += 128) {
+        const int c2 = col_at(k0 + 128);
+        const bool more_b = k0 + 64 < hi;
+        if (more_b) issue(B, c1, k0 + 64);
+        consume(A, k0);
+        if (!more_b) break;
+        c1 = col_at(k0 + 192);
+        const bool more_a = k0 + 128 < hi;
+        if (more_a) issue(A, c2, k0 + 128);
+        consume(B, k0 + 64);
+        if (!more_a) break;
+    }
+}
+
+// Rows of one chunk for a walk that needs no row sums: piece(i, lo, hi) for every row piece.  The row pointers of
+// the next 64 rows are fetched at once and handed out by lane reads, so a new row costs no memory round trip.
+template <class Piece>
+__device__ __forceinline__ void walk_row_pieces(const NnzArgs &a, int chunk, int lane, Piece piece) {
+    const long long lo_ll = (long long)chunk * a.chunk_nnz;
+    const int lo = (int)lo_ll;
+    const int hi = (int)((lo_ll + a.chunk_nnz < (long long)a.nnz) ? lo_ll + a.chunk_nnz : (long long)a.nnz);
+    if (lo >= hi) return;
+    const int i0 = a.chunk_row[chunk];
+    int i = __builtin_amdgcn_readfirstlane((a.row_ptr[i0] > lo) ? i0 - 1 : i0);
+    int base = i;
+    auto fetch_ends = [&]() {
+        const int q = base + 1 + lane;
+        return a.row_ptr[q < a.n_rows ? q : a.n_rows];
+    };
+    int ends = fetch_ends();
+    int pos = lo;
+    while (pos < hi) {
+        if (i - base == 64) {
+            base = i;
+            ends = fetch_ends();
+        }
+        const int re = __builtin_amdgcn_readlane(ends, __builtin_amdgcn_readfirstlane(i - base));
+        if (re > pos) {
+            const int seg_hi = re < hi ? re : hi;
+            piece(i, pos, seg_hi);
+            pos = seg_hi;
+        }
+        i = __builtin_amdgcn_readfirstlane(i + 1);
+    }
+}
+
 struct GatBwdArgs {
     NnzArgs n;
     const float *theta, *dP;  // slice-major (tiles of 32 columns): Theta over the source nodes, dP over the destinations
@@ -902,76 +1007,37 @@ struct GatBwdArgs {
     int n_tiles;
 };
 
-// dalpha_ij = <dP[i,:], Theta[j,:]> for every stored entry (the general g-SDDMM of Eq. 2 with a dot product as the
-// inner operator) together with the row sums sum_j alpha_ij dalpha_ij that the softmax backward needs.  One launch per
-// 32-column slice: every wavefront of the GPU then gathers from the same contiguous slice of Theta (as the SpMM keeps
-// one slice per L2), eight lanes take one neighbour (16 bytes of its 128-byte line each), eight neighbours per step,
-// and the lane that owns an entry adds the slice's share to dalpha[k] - launches follow each other on the stream, so
-// no atomics.  The last launch sees the complete dot products and forms the row sums.
-__global__ __launch_bounds__(kBlock) void k_gat_dalpha(GatBwdArgs a, int tile, int first, int last) {
+// dalpha_ij = <dP[i,:], Theta[j,:]> for every stored entry (Eq. 2 with a dot product as the inner operator) together
+// with the row sums sum_j alpha_ij dalpha_ij that the softmax backward needs.  One launch per 32-column slice: every
+// wavefront of the GPU then gathers from the same contiguous slice of Theta (as the SpMM keeps one slice per L2), and
+// the lane that owns an entry adds the slice's share to dalpha[k] - launches follow each other on the stream, so no
+// atomics.  The last launch sees the complete dot products and forms the row sums.
+template <bool LAST>
+__global__ __launch_bounds__(kBlock) void k_gat_dalpha(GatBwdArgs a, int tile, int first) {
     const int chunk = wave_chunk();
     if (chunk >= a.n.n_chunks) return;
     const int lane = threadIdx.x & 63;
-    const int g = lane >> 3, sub = lane & 7;
+    const int sub = lane & 3;
     const float *theta = a.theta + (size_t)tile * a.theta_tile + sub * 4;
     const float *dP = a.dP + (size_t)tile * a.dp_tile + sub * 4;
     auto piece = [&](int i, int lo, int hi) {
-        const float2 st = a.mz[i];
-        const float m = st.x, iz = inv_z(st.y);
         const float4 p = *reinterpret_cast<const float4 *>(dP + (size_t)i * 32);
-        float s = 0.f;
-        // column indices: 64 per batch, one per lane, fetched one batch ahead and handed to the groups by cross-lane
-        // reads, so a gather never waits for its index; eight steps of eight neighbours are in flight
-        int col_next = a.n.col_idx[lo + lane < hi ? lo + lane : lo];
-        for (int k0 = lo; k0 < hi; k0 += 64) {
-            const int col = col_next;
-            const int kn = k0 + 64 + lane;
-            col_next = a.n.col_idx[kn < hi ? kn : lo];
-            float4 b[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int j = lane_read((u * 8 + g) * 4, col);
-                b[u] = *reinterpret_cast<const float4 *>(theta + (size_t)j * 32);
-            }
-            // lane (g, sub) owns entry k0 + sub * 8 + g: one coalesced 256-byte access per 64 entries
-            const int k_own = k0 + sub * 8 + g;
-            const bool own = k_own < hi;
-            float v = (own && !first) ? a.dalpha[k_own] : 0.f;
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                float d = fmaf(b[u].x, p.x, fmaf(b[u].y, p.y, fmaf(b[u].z, p.z, b[u].w * p.w)));
-                d += dpp_f32<0xB1>(d);   // lane ^ 1 within each quad
-                d += dpp_f32<0x4E>(d);   // lane ^ 2 within each quad
-                d += dpp_f32<0x141>(d);  // the other quad of the eight (mirror within the half row)
-                if (sub == u) v += d;    // every lane of the group holds the sum; the owner keeps it
-            }
-            if (own) {
-                a.dalpha[k_own] = v;
-                if (last) s = fmaf(expf(a.logits[k_own] - m) * iz, v, s);
-            }
+        const float4 q = *reinterpret_cast<const float4 *>(dP + (size_t)i * 32 + 16);
+        float m = 0.f, iz = 0.f, s = 0.f;
+        if (LAST) {
+            const float2 st = a.mz[i];
+            m = st.x;
+            iz = inv_z(st.y);
         }
+        slice_piece<LAST>(a.n.col_idx, theta, a.dalpha, a.logits, first != 0, lane, lo, hi,
+                          [&](const float4 &b, const float4 &c) {
+                              return fmaf(b.x, p.x, fmaf(b.y, p.y, fmaf(b.z, p.z, fmaf(b.w, p.w, fmaf(c.x, q.x, fmaf(c.y, q.y, fmaf(c.z, q.z, c.w * q.w)))))));
+                          },
+                          [&](int, float v, float e) { if (LAST) s = fmaf(expf(e - m) * iz, v, s); });
         return s;
     };
-    if (last) {
-        reduce_rows(a.n, chunk, lane, a.rowdot, a.carry, piece);
-    } else {  // same walk, row sums not needed yet
-        const long long lo_ll = (long long)chunk * a.n.chunk_nnz;
-        const int lo = (int)lo_ll;
-        const int hi = (int)((lo_ll + a.n.chunk_nnz < (long long)a.n.nnz) ? lo_ll + a.n.chunk_nnz : (long long)a.n.nnz);
-        if (lo >= hi) return;
-        const int i0 = a.n.chunk_row[chunk];
-        int i = __builtin_amdgcn_readfirstlane((a.n.row_ptr[i0] > lo) ? i0 - 1 : i0);
-        int pos = lo;
-        while (pos < hi) {
-            const int re = __builtin_amdgcn_readfirstlane(a.n.row_ptr[i + 1]);
-            if (re > pos) {
-                const int seg_hi = re < hi ? re : hi;
-                (void)piece(i, pos, seg_hi);
-                pos = seg_hi;
-            }
-            i = __builtin_amdgcn_readfirstlane(i + 1);
-        }
-    }
+    if (LAST) reduce_rows(a.n, chunk, lane, a.rowdot, a.carry, piece);
+    else walk_row_pieces(a.n, chunk, lane, [&](int i, int lo, int hi) { (void)piece(i, lo, hi); });
 }
 
 struct ScoreV2Args {
@@ -983,60 +1049,32 @@ struct ScoreV2Args {
     float slope;
 };
 
-// Logits of the GATv2 score, e_ij = sum_m a[m] LeakyReLU(Theta_l[i, m] + Theta_r[j, m]): the g-SDDMM of Eq. 2 with an
-// inner operator that is neither a product nor a sum alone.  Same walk as k_gat_dalpha: one launch per 32-column slice,
-// eight lanes per neighbour, the lane that owns an entry adds the slice's share to logits[k].
+// Logits of the GATv2 score, e_ij = sum_m a[m] LeakyReLU(Theta_l[i, m] + Theta_r[j, m]): Eq. 2 with an inner operator
+// that is neither a product nor a sum alone.  Same walk as k_gat_dalpha, one launch per 32-column slice.
 __global__ __launch_bounds__(kBlock) void k_score_v2(ScoreV2Args a, int tile, int first) {
     const int chunk = wave_chunk();
     if (chunk >= a.n.n_chunks) return;
     const int lane = threadIdx.x & 63;
-    const int g = lane >> 3, sub = lane & 7;
+    const int sub = lane & 3;
     const float *theta_r = a.theta_r + (size_t)tile * a.tr_tile + sub * 4;
     const float *theta_l = a.theta_l + (size_t)tile * a.tl_tile + sub * 4;
     const float4 w = *reinterpret_cast<const float4 *>(a.att + tile * 32 + sub * 4);
+    const float4 w2 = *reinterpret_cast<const float4 *>(a.att + tile * 32 + 16 + sub * 4);
     const float slope = a.slope;
-    const long long lo_ll = (long long)chunk * a.n.chunk_nnz;
-    const int lo = (int)lo_ll;
-    const int hi = (int)((lo_ll + a.n.chunk_nnz < (long long)a.n.nnz) ? lo_ll + a.n.chunk_nnz : (long long)a.n.nnz);
-    if (lo >= hi) return;
-    const int i0 = a.n.chunk_row[chunk];
-    int i = __builtin_amdgcn_readfirstlane((a.n.row_ptr[i0] > lo) ? i0 - 1 : i0);
-    int pos = lo;
-    while (pos < hi) {
-        const int re = __builtin_amdgcn_readfirstlane(a.n.row_ptr[i + 1]);
-        if (re > pos) {
-            const int seg_hi = re < hi ? re : hi;
-            const float4 p = *reinterpret_cast<const float4 *>(theta_l + (size_t)i * 32);
-            for (int k0 = pos; k0 < seg_hi; k0 += 64) {
-                const int kl = k0 + lane;
-                const int col = a.n.col_idx[kl < seg_hi ? kl : pos];
-                float4 b[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const int j = lane_read((u * 8 + g) * 4, col);
-                    b[u] = *reinterpret_cast<const float4 *>(theta_r + (size_t)j * 32);
-                }
-                const int k_own = k0 + sub * 8 + g;  // lane (g, sub) owns this entry: coalesced 256-byte accesses
-                const bool own = k_own < seg_hi;
-                float v = (own && !first) ? a.logits[k_own] : 0.f;
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const float tx = p.x + b[u].x, ty = p.y + b[u].y, tz = p.z + b[u].z, tw = p.w + b[u].w;
-                    float d = w.x * (tx > 0.f ? tx : slope * tx);
-                    d = fmaf(w.y, ty > 0.f ? ty : slope * ty, d);
-                    d = fmaf(w.z, tz > 0.f ? tz : slope * tz, d);
-                    d = fmaf(w.w, tw > 0.f ? tw : slope * tw, d);
-                    d += dpp_f32<0xB1>(d);
-                    d += dpp_f32<0x4E>(d);
-                    d += dpp_f32<0x141>(d);
-                    if (sub == u) v += d;
-                }
-                if (own) a.logits[k_own] = v;
-            }
-            pos = seg_hi;
-        }
-        i = __builtin_amdgcn_readfirstlane(i + 1);
-    }
+    auto term = [&](float wt, float x, float y) {
+        const float t = x + y;
+        return wt * (t > 0.f ? t : slope * t);
+    };
+    walk_row_pieces(a.n, chunk, lane, [&](int i, int lo, int hi) {
+        const float4 p = *reinterpret_cast<const float4 *>(theta_l + (size_t)i * 32);
+        const float4 q = *reinterpret_cast<const float4 *>(theta_l + (size_t)i * 32 + 16);
+        slice_piece<false>(a.n.col_idx, theta_r, a.logits, nullptr, first != 0, lane, lo, hi,
+                           [&](const float4 &b, const float4 &c) {
+                               return ((term(w.x, p.x, b.x) + term(w.y, p.y, b.y)) + (term(w.z, p.z, b.z) + term(w.w, p.w, b.w))) +
+                                      ((term(w2.x, q.x, c.x) + term(w2.y, q.y, c.y)) + (term(w2.z, q.z, c.z) + term(w2.w, q.w, c.w)));
+                           },
+                           [](int, float, float) {});
+    });
 }
 
 struct GatDtArgs {
@@ -1381,8 +1419,10 @@ hipError_t launch_gat_dalpha(const sensei_csr &A, const float *theta, const floa
     a.dp_tile = (long long)(A.n_rows > 0 ? A.n_rows : 1) * 32;
     a.n_tiles = (f + 31) / 32;
     const dim3 grid(blocks_for(p.n_chunks, kWavesPerBlock));
-    for (int t = 0; t < a.n_tiles; ++t)
-        hipLaunchKernelGGL(k_gat_dalpha, grid, dim3(kBlock), 0, s, a, t, t == 0 ? 1 : 0, t == a.n_tiles - 1 ? 1 : 0);
+    for (int t = 0; t < a.n_tiles; ++t) {
+        if (t == a.n_tiles - 1) hipLaunchKernelGGL(k_gat_dalpha<true>, grid, dim3(kBlock), 0, s, a, t, t == 0 ? 1 : 0);
+        else hipLaunchKernelGGL(k_gat_dalpha<false>, grid, dim3(kBlock), 0, s, a, t, t == 0 ? 1 : 0);
+    }
     if (p.n_chunks > 1) hipLaunchKernelGGL(k_sum_fixup, dim3(blocks_for(p.n_chunks - 1, kBlock)), dim3(kBlock), 0, s, a.n, rowdot, carry);
     return hipGetLastError();
 }
