@@ -52,6 +52,7 @@ def parse_args():
     ap.add_argument("--backward", action="store_true", help="time the backward pass even with --no-sweep")
     ap.add_argument("--no-panels", action="store_true", help="do not build the column-panel copy of the graph")
     ap.add_argument("--panels", type=int, default=0, help="force the number of column panels (0 = let the library measure)")
+    ap.add_argument("--tiles", type=float, default=0.125, help="dense-tile split of the hub region: least density of a kept tile (0 = off)")
     ap.add_argument("--no-gather-probe", action="store_true", help="skip the L2-resident gather probe")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run four 1 GiB device-to-device copies (a kernel of known traffic, for scaling rocprofv3 --pmc byte counters)")
@@ -118,6 +119,14 @@ def main():
         torch.cuda.synchronize()
         panels_ms = (time.perf_counter() - tp) * 1e3  # includes the timed trials when the count is measured
         A = csr_struct(N, N, row_ptr, col_idx, None, panels)
+    tiles, tiles_ms = None, 0.0
+    if args.tiles > 0:
+        from paper_2306_15155_amd import Tiles
+        tp = time.perf_counter()
+        tiles = Tiles(ctx, A, args.tiles, 256)
+        torch.cuda.synchronize()
+        tiles_ms = (time.perf_counter() - tp) * 1e3
+        A = csr_struct(N, N, row_ptr, col_idx, None, panels, tiles)
     Apre = csr_struct(N, N, row_ptr, col_idx, ntil, panels)
 
     # ---- composition choice per layer (cost model: host arithmetic only)
@@ -203,7 +212,9 @@ def main():
             for line in open(prof):
                 if line.startswith("traffic_bytes_per_launch %s:" % tag(k)):
                     traffic = float(line.split(":")[1])
-        roofline = {"kernel": "k_spmm (%s, F=%d, %s)" % (tag(k), f_sp, name_of(k)), "bound": "hbm",
+        split = tiles is not None and tiles.n_tiles > 0 and f_sp >= 128
+        what = "SpMM call = k_spmm on the sparse remainder + k_dense_tiles on the hub tiles" if split else "k_spmm"
+        roofline = {"kernel": "%s (%s, F=%d, %s)" % (what, tag(k), f_sp, name_of(k)), "bound": "hbm",
                     "achieved": round(algo_bytes / t_s / 1e9, 1), "peak": 8000.0, "unit": "GB/s",
                     "frac": round(algo_bytes / t_s / 1e9 / 8000.0, 4), "traffic": traffic,
                     "avg_launch_ms": round(spmm_mean[k], 4), "algorithmic_bytes": algo_bytes,
@@ -244,6 +255,8 @@ def main():
               "gemm": gemm_info, "setup_ms": round(setup_ms, 4), "column_panels": None if panels is None else panels.count,
               "column_panels_min_width": None if panels is None else panels.min_width,
               "column_panels_setup_ms": round(panels_ms, 3),
+              "dense_tiles": None if tiles is None else {"min_density": args.tiles, "tiles": tiles.n_tiles, "nnz_dense": tiles.nnz_dense,
+                                                         "nnz_sparse": tiles.nnz_sparse, "setup_ms": round(tiles_ms, 3)},
               "column_panels_trial_ms": None if panels is None or panels.tune_ms is None else [round(x, 3) for x in panels.tune_ms], "select_model_ms": round(select_model_ms, 4),
               "graph": {"nodes": N, "nnz": nnz, "max_degree": int(np.diff(g.row_ptr).max()), "generate_s": round(gen_s, 2)}}
     if not args.no_sweep:
@@ -313,17 +326,20 @@ def main():
         for i, L in enumerate(layers):
             if L["kind"] != "gcn":
                 continue
-            sgc[tag(i)] = {nm: round(time_fn(lambda: ctx.sgc_layer(A, r, c, src_of(i), Wd[i], 2, cid, L["act"], out=outs[i]), 2), 4)
+            tmp_out = torch.empty_like(outs[i])   # the outputs of the timed step stay as they are for the parity check below
+            sgc[tag(i)] = {nm: round(time_fn(lambda: ctx.sgc_layer(A, r, c, src_of(i), Wd[i], 2, cid, L["act"], out=tmp_out), 2), 4)
                            for cid, nm in ((0, "AGG"), (1, "UPD"))}
+            del tmp_out
         detail["sgc_2hop_ms"] = sgc
         tag2 = {}
         for i, L in enumerate(layers):
             if L["kind"] != "gcn":
                 continue
             W3 = torch.randn((3 * L["f_in"], L["f_out"]), device=dev) * 0.05
-            tag2[tag(i)] = {nm: round(time_fn(lambda: ctx.tagcn_layer(A, r, c, src_of(i), W3, 2, cid, L["act"], out=outs[i]), 2), 4)
+            tmp_out = torch.empty_like(outs[i])
+            tag2[tag(i)] = {nm: round(time_fn(lambda: ctx.tagcn_layer(A, r, c, src_of(i), W3, 2, cid, L["act"], out=tmp_out), 2), 4)
                             for cid, nm in ((0, "AGG"), (1, "UPD"))}
-            del W3
+            del W3, tmp_out
         detail["tagcn_2hop_ms"] = tag2
 
     # ---- GATv2 on the shapes of the GAT layers (separate W_l and W_r): reuse and recompute
@@ -334,9 +350,10 @@ def main():
                 continue
             Wl2 = torch.randn_like(Wd[i]) * 0.05
             att2 = torch.randn((L["f_out"],), device=dev) * 0.1
-            v2[tag(i)] = {nm: round(time_fn(lambda: ctx.gatv2_layer(A, src_of(i), Wl2, Wd[i], att2, cid, 0.2, L["act"], out=outs[i]), 2), 4)
+            tmp_out = torch.empty_like(outs[i])
+            v2[tag(i)] = {nm: round(time_fn(lambda: ctx.gatv2_layer(A, src_of(i), Wl2, Wd[i], att2, cid, 0.2, L["act"], out=tmp_out), 2), 4)
                           for cid, nm in ((0, "REUSE"), (1, "RECOMP"))}
-            del Wl2, att2
+            del Wl2, att2, tmp_out
         detail["gatv2_ms"] = v2
 
     # ---- one training iteration of the GCN stack of the workload (the layers whose input is X or the previous layer):
@@ -402,6 +419,8 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
+        step()  # the outputs checked below are those of the timed configuration, whatever ran in between
+        torch.cuda.synchronize()
         budget_rows = 72_000 if N > 50_000 else N * len(layers)
         n_s = min(N, max(500, budget_rows // len(layers)))
         if args.workload == "c3_rmat2450k":

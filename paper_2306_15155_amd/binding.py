@@ -31,7 +31,8 @@ EXPORTS = (
     "sensei_select", "sensei_profile_enable", "sensei_profile_read", "sensei_panels_bytes", "sensei_panels_create",
     "sensei_panels_count", "sensei_panels_destroy", "sensei_panels_set_min_width", "sensei_panels_tune_bytes",
     "sensei_panels_tune", "sensei_gcn_backward_workspace", "sensei_gcn_backward", "sensei_select_gcn_backward", "sensei_transpose_positions",
-    "sensei_gat_backward_workspace", "sensei_gat_backward", "sensei_gat_layer_heads", "sensei_sgc_workspace", "sensei_sgc_layer", "sensei_tagcn_workspace", "sensei_tagcn_layer", "sensei_gatv2_workspace", "sensei_gatv2_layer",
+    "sensei_gat_backward_workspace", "sensei_gat_backward", "sensei_gat_layer_heads", "sensei_sgc_workspace", "sensei_sgc_layer", "sensei_tagcn_workspace", "sensei_tagcn_layer", "sensei_gatv2_workspace", "sensei_gatv2_layer", "sensei_tiles_bytes", "sensei_tiles_create", "sensei_tiles_info",
+           "sensei_tiles_set_min_width", "sensei_tiles_destroy",
 )
 
 
@@ -43,7 +44,8 @@ class SenseiError(RuntimeError):
 
 class CsrStruct(ctypes.Structure):
     _fields_ = [("n_rows", ctypes.c_int32), ("n_cols", ctypes.c_int32), ("nnz", ctypes.c_int64),
-                ("row_ptr", ctypes.c_void_p), ("col_idx", ctypes.c_void_p), ("val", ctypes.c_void_p), ("panels", ctypes.c_void_p)]
+                ("row_ptr", ctypes.c_void_p), ("col_idx", ctypes.c_void_p), ("val", ctypes.c_void_p), ("panels", ctypes.c_void_p),
+                ("tiles", ctypes.c_void_p)]
 
 
 class MatStruct(ctypes.Structure):
@@ -99,6 +101,11 @@ def lib():
         L.sensei_tagcn_layer.argtypes = [vp, P(CsrStruct), vp, vp, MatStruct, MatStruct, i32, vp, i64, i32, i32, vp, sz, vp]
         L.sensei_gatv2_workspace.argtypes = [P(CsrStruct), i32, i32, i32, P(sz)]
         L.sensei_gatv2_layer.argtypes = [vp, P(CsrStruct), MatStruct, MatStruct, MatStruct, vp, f32, vp, i64, i32, i32, vp, sz, vp]
+        L.sensei_tiles_bytes.argtypes = [P(CsrStruct), f32, i32, P(sz)]
+        L.sensei_tiles_create.argtypes = [vp, P(CsrStruct), f32, i32, vp, sz, vp, P(vp)]
+        L.sensei_tiles_info.argtypes = [vp, P(i32), P(i64), P(i64)]
+        L.sensei_tiles_set_min_width.argtypes = [vp, i32]
+        L.sensei_tiles_destroy.argtypes = [vp]
         L.sensei_select_workspace.argtypes = [i32, P(CsrStruct), i32, i32, P(sz)]
         L.sensei_select.argtypes = [vp, i32, P(CsrStruct), i32, i32, i32, P(ctypes.c_int), P(f32), vp, sz, vp]
         L.sensei_panels_bytes.argtypes = [P(CsrStruct), i32, P(sz)]
@@ -142,11 +149,12 @@ def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
-def csr_struct(n_rows, n_cols, row_ptr, col_idx, val=None, panels=None) -> CsrStruct:
+def csr_struct(n_rows, n_cols, row_ptr, col_idx, val=None, panels=None, tiles=None) -> CsrStruct:
     assert row_ptr.dtype == torch.int32 and col_idx.dtype == torch.int32
     assert val is None or val.dtype == torch.float32
     return CsrStruct(n_rows, n_cols, int(col_idx.numel()), row_ptr.data_ptr(), col_idx.data_ptr() if col_idx.numel() else None,
-                     None if val is None else val.data_ptr(), None if panels is None else panels.handle)
+                     None if val is None else val.data_ptr(), None if panels is None else panels.handle,
+                     None if tiles is None else tiles.handle)
 
 
 class Panels:
@@ -192,6 +200,38 @@ class Panels:
     def close(self):
         if self._h:
             lib().sensei_panels_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Tiles:
+    """Dense-tile split of a pattern (sensei_tiles_create); owns the device buffer it lives in."""
+
+    def __init__(self, ctx: "Context", A: CsrStruct, min_density: float = 0.125, max_width: int = 1024, min_width: int = 128):
+        need = ctypes.c_size_t()
+        _check(lib().sensei_tiles_bytes(ctypes.byref(A), min_density, max_width, ctypes.byref(need)), "sensei_tiles_bytes")
+        self.buf = torch.empty(need.value + 256, dtype=torch.uint8, device=ctx.device)
+        p = (self.buf.data_ptr() + 255) // 256 * 256
+        self._h = ctypes.c_void_p()
+        _check(lib().sensei_tiles_create(ctx._h, ctypes.byref(A), min_density, max_width, ctypes.c_void_p(p), need.value, _stream(),
+                                         ctypes.byref(self._h)), "sensei_tiles_create")
+        kept, dense, sparse = ctypes.c_int(), ctypes.c_int64(), ctypes.c_int64()
+        _check(lib().sensei_tiles_info(self._h, ctypes.byref(kept), ctypes.byref(dense), ctypes.byref(sparse)), "sensei_tiles_info")
+        self.n_tiles, self.nnz_dense, self.nnz_sparse = kept.value, dense.value, sparse.value
+        _check(lib().sensei_tiles_set_min_width(self._h, min_width), "sensei_tiles_set_min_width")
+
+    @property
+    def handle(self):
+        return self._h.value
+
+    def close(self):
+        if self._h:
+            lib().sensei_tiles_destroy(self._h)
             self._h = ctypes.c_void_p()
 
     def __del__(self):

@@ -1,5 +1,6 @@
 // C ABI of libsensei_hip: argument checks, workspace layout, the composition
 // executors for the GCN and GAT layer, and the composition selector.
+#include <algorithm>
 #include <cmath>
 #include <new>
 
@@ -33,6 +34,22 @@ struct sensei_panels {
     int32_t off_q[SENSEI_MAX_PANELS + 1];      // first entry of each panel in the copy
     int n_chunks_q[SENSEI_MAX_PANELS];
     int min_width = 128;                       // narrowest SpMM (floats per gathered row) that goes panel by panel
+};
+
+// Dense-tile split of a pattern: bit masks of the kept 128 x 128 tiles (in degree-rank order), the CSR of everything else.
+struct sensei_tiles {
+    int32_t n_rows, n_cols;
+    int64_t nnz;
+    const int32_t *src_row_ptr, *src_col_idx;  // the pattern it was built from
+    sensei::TileSplit T;
+    int64_t nnz_rem;                           // entries left in the sparse remainder
+    const int32_t *row_ptr_rem, *col_rem;
+    const int32_t *pos;                        // nnz + 1: place of each original entry in the remainder (see launch_tile_split)
+    sensei::ChunkPlan plan_rem;
+    float *Bh;                                 // room for the gathered matrix in rank order, max_width columns
+    int max_width;
+    int min_width = 128;                       // narrowest SpMM that takes the split (narrower ones lose more in the half-empty
+                                               // 128-column tiles of the dense kernel than the smaller remainder gains)
 };
 
 namespace {
@@ -155,13 +172,46 @@ bool panels_usable(const sensei_csr &A, int f) {
            p->n_rows == A.n_rows && p->n_cols == A.n_cols;
 }
 
+// The dense-tile split serves the value-less SpMM on a slice-major operand (what the layers use on graphs whose rows are
+// gathered often); everything else takes the ordinary paths.
+struct AttnVectors {  // what the softmax mode of the dense tiles needs besides the row statistics
+    const float *s_l, *s_r;
+    float slope;
+};
+
+bool tiles_usable(const sensei_csr &A, int mode, int f, bool b_sliced, bool attn = false) {
+    const sensei_tiles *D = A.tiles;
+    const bool mode_ok = (mode == SENSEI_SPMM_PATTERN) || (mode == kSpmmSoftmax && attn);
+    if (!D || !mode_ok || !b_sliced || pad32(f) > D->max_width || f < D->min_width || D->T.n_slots <= 0) return false;
+    return D->n_rows == A.n_rows && D->n_cols == A.n_cols && D->nnz == A.nnz && D->src_row_ptr == A.row_ptr && D->src_col_idx == A.col_idx;
+}
+
 // SpMM over the whole pattern, or panel after panel when the matrix carries a usable panel copy.  Values
 // (WEIGHTED, kSpmmSoftmax) can only follow the panels if they are stored in panel order (val_in_panel_order);
 // values in the order of the original pattern use the single pass.
 hipError_t spmm_any(const sensei_csr &A, int mode, const float *r, const float *c, const float *B, int64_t ldb, int f, float *C,
                     int64_t ldc, int f_store, int act, const ChunkPlan &plan, float *carry, hipStream_t s, KernelTimer *kt,
-                    bool val_in_panel_order = false, const float2 *mz = nullptr, bool b_sliced = false, bool c_sliced = false) {
+                    bool val_in_panel_order = false, const float2 *mz = nullptr, bool b_sliced = false, bool c_sliced = false,
+                    const AttnVectors *attn = nullptr) {
+    // attn: softmax mode on a pattern with a dense-tile split; A.val then holds the logits of the remainder, in its order
     const bool has_val = (mode == SENSEI_SPMM_WEIGHTED || mode == kSpmmSoftmax);
+    if (tiles_usable(A, mode, f, b_sliced, attn != nullptr)) {
+        // hub region on the matrix cores, the rest as a sparse pass that adds to it and applies the scaling and activation
+        const sensei_tiles &D = *A.tiles;
+        hipEvent_t t0 = kt ? kt->next() : nullptr, t1 = t0 ? kt->next() : nullptr;
+        if (t1 && hipEventRecord(t0, s) != hipSuccess) return hipErrorUnknown;
+        hipError_t e = launch_zero_matrix(C, A.n_rows, f_store, ldc, c_sliced, s);
+        if (e == hipSuccess)
+            e = launch_dense_tiles(D.T, B, A.n_cols, pad32(f), D.Bh, C, ldc, f_store, c_sliced, A.n_rows, s, attn ? attn->s_l : nullptr,
+                                   attn ? attn->s_r : nullptr, attn ? mz : nullptr, attn ? attn->slope : 0.f);
+        if (e != hipSuccess) return e;
+        sensei_csr Ar = A;
+        Ar.nnz = D.nnz_rem; Ar.row_ptr = D.row_ptr_rem; Ar.col_idx = D.col_rem; Ar.panels = nullptr; Ar.tiles = nullptr;
+        e = launch_spmm(Ar, mode, r, c, B, ldb, f, C, ldc, f_store, act, D.plan_rem, carry, s, nullptr, true, true, mz, b_sliced, 1, c_sliced);
+        if (e != hipSuccess) return e;
+        if (t1 && hipEventRecord(t1, s) != hipSuccess) return hipErrorUnknown;
+        return hipSuccess;
+    }
     if (!panels_usable(A, f) || (has_val && !val_in_panel_order))
         return launch_spmm(A, mode, r, c, B, ldb, f, C, ldc, f_store, act, plan, carry, s, kt, false, true, mz, b_sliced, 1, c_sliced);
     const sensei_panels &P = *A.panels;
@@ -465,7 +515,9 @@ int run_gat(const sensei_csr &A, const sensei_mat &X, const sensei_mat &W, const
         }
     }
     const int f_gather = reuse ? (n_heads == 1 ? fo : d) : f_in;  // width of the aggregation of one head
-    const bool by_panel = panels_usable(A, f_gather);
+    // dense-tile split: the tiles form their weights from s_l, s_r themselves, only the remainder's logits are stored
+    const bool by_tiles = reuse && theta_sliced && n_heads == 1 && tiles_usable(A, kSpmmSoftmax, f_gather, true, true);
+    const bool by_panel = !by_tiles && panels_usable(A, f_gather);
     for (int h = 0; h < n_heads; ++h) {
         const float *al = a_l + (size_t)h * d, *ar = a_r + (size_t)h * d;
         const float *theta_h = !theta ? nullptr : theta_sliced ? theta + (size_t)h * (d / 32) * (size_t)A.n_cols * 32 : theta + (size_t)h * d;
@@ -478,13 +530,15 @@ int run_gat(const sensei_csr &A, const sensei_mat &X, const sensei_mat &W, const
         // One pass computes the logits and the per-row softmax statistics; the aggregation then weighs each neighbour
         // by exp(e - max) and scales the row by 1 / sum, so the attention weights themselves are never stored.  With a
         // panel copy the logits are written straight in panel order and the SpMM follows the panels.
-        SENSEI_TRY(launch_attention_stats(A, s_l, s_r, slope, logits, by_panel ? A.panels->position : nullptr, plan, stats, carry_stats, s));
+        SENSEI_TRY(launch_attention_stats(A, s_l, s_r, slope, logits, by_panel ? A.panels->position : nullptr, plan, stats, carry_stats, s,
+                                          by_tiles ? A.tiles->pos : nullptr));
+        const AttnVectors attn = {s_l, s_r, slope};
         sensei_csr Aw = A;
         Aw.val = logits;
         float *Y_h = Y + (size_t)h * d;
         if (reuse) {
             SENSEI_TRY(spmm_any(Aw, kSpmmSoftmax, nullptr, nullptr, theta_h, fo, f_gather, Y_h, ldy, d, act, plan, carry, s, kt, by_panel, stats,
-                                theta_sliced));
+                                theta_sliced, false, by_tiles ? &attn : nullptr));
         } else {
             SENSEI_TRY(spmm_any(Aw, kSpmmSoftmax, nullptr, nullptr, x_src, X.ld, f_in, U, fi, f_in, SENSEI_ACT_NONE, plan, carry, s, kt, by_panel, stats,
                                 x_sliced));
@@ -1074,6 +1128,191 @@ int sensei_panels_tune(sensei_ctx *ctx, const sensei_csr *A, void *scratch, size
 }
 
 int sensei_panels_count(const sensei_panels *panels) { return panels ? panels->n_panels : 0; }
+
+// ---- dense tiles
+namespace {
+constexpr int kTileRanksMax = 65536;  // ranks per side that are examined for dense tiles
+
+struct TilesLayout {
+    int h_r, h_c, nt_r, nt_c, n_tiles, max_slots, min_count;
+    size_t rank_r, rank_c, order_r, order_c, hist, sel_scan, slot_of, slot_ct, rt_ptr, scan_small, plan, bits, pos, scan_large, col_rem,
+        row_ptr_rem, plan_rem, bh, seg_first, rt_seg, seg_rt, rank_vec, part, total;
+    int max_seg;
+};
+
+TilesLayout tiles_layout(const sensei_csr &A, float min_density, int max_width) {
+    TilesLayout L;
+    L.h_r = A.n_rows < kTileRanksMax ? A.n_rows : kTileRanksMax;
+    L.h_c = A.n_cols < kTileRanksMax ? A.n_cols : kTileRanksMax;
+    L.nt_r = (L.h_r + 127) / 128;
+    L.nt_c = (L.h_c + 127) / 128;
+    L.n_tiles = L.nt_r * L.nt_c;
+    L.min_count = (int)(min_density * 128.f * 128.f);
+    if (L.min_count < 1) L.min_count = 1;
+    const int64_t by_count = A.nnz / L.min_count;
+    L.max_slots = (int)(by_count < L.n_tiles ? by_count : L.n_tiles);
+    size_t off = 0;
+    auto put = [&](size_t bytes) { const size_t at = off; off += align_up(bytes > 0 ? bytes : 4, 256); return at; };
+    L.rank_r = put((size_t)A.n_rows * 4);
+    L.rank_c = put((size_t)A.n_cols * 4);
+    L.order_r = put((size_t)L.nt_r * 128 * 4);
+    L.order_c = put((size_t)L.nt_c * 128 * 4);
+    L.hist = put((size_t)L.n_tiles * 4);
+    L.sel_scan = put(((size_t)L.n_tiles + 1) * 4);
+    L.slot_of = put((size_t)L.n_tiles * 4);
+    L.slot_ct = put((size_t)L.n_tiles * 4);
+    L.rt_ptr = put(((size_t)L.nt_r + 1) * 4);
+    L.scan_small = put(scan_temp_bytes(L.n_tiles + 1));
+    L.plan = put(plan_bytes(A.nnz));
+    L.bits = put((size_t)L.max_slots * 128 * 4 * 4);
+    L.pos = put(((size_t)A.nnz + 1) * 4);
+    L.scan_large = put(scan_large_temp_bytes((long long)A.nnz + 1));
+    L.col_rem = put((size_t)A.nnz * 4);
+    L.row_ptr_rem = put(((size_t)A.n_rows + 1) * 4);
+    L.plan_rem = put(plan_bytes(A.nnz) + 4096);
+    L.bh = put((size_t)L.nt_c * 128 * max_width * 4);
+    L.max_seg = L.max_slots / kTilesPerSegment + L.nt_r + 1;
+    L.seg_first = put(((size_t)L.max_seg + 1) * 4);
+    L.rt_seg = put(((size_t)L.nt_r + 1) * 4);
+    L.seg_rt = put(((size_t)L.max_seg + 1) * 4);
+    L.rank_vec = put(((size_t)2 * L.nt_r + L.nt_c) * 128 * 4);
+    L.part = put((size_t)L.max_seg * 128 * max_width * 4);
+    L.total = off;
+    return L;
+}
+
+// nodes in descending order of degree (ties: lower id first): rank of every node (INT_MAX beyond the first h) and the
+// node at every rank (-1 in the padding up to whole tiles)
+void rank_by_degree(const std::vector<int32_t> &deg, int h, int n_ranks, std::vector<int32_t> *rank, std::vector<int32_t> *order) {
+    const int n = (int)deg.size();
+    std::vector<int32_t> idx(n);
+    for (int i = 0; i < n; ++i) idx[i] = i;
+    std::stable_sort(idx.begin(), idx.end(), [&](int32_t a, int32_t b) { return deg[a] > deg[b]; });
+    rank->assign(n, 0x7fffffff);
+    order->assign(n_ranks, -1);
+    for (int q = 0; q < h; ++q) { (*rank)[idx[q]] = q; (*order)[q] = idx[q]; }
+}
+}  // namespace
+
+int sensei_tiles_bytes(const sensei_csr *A, float min_density, int max_width, size_t *device_bytes) {
+    if (!csr_ok(A, false) || !device_bytes || !(min_density > 0.f) || min_density > 1.f || max_width < 32 || max_width % 32 != 0 || max_width > 4096)
+        return SENSEI_INVALID_ARGUMENT;
+    *device_bytes = tiles_layout(*A, min_density, max_width).total;
+    return SENSEI_OK;
+}
+
+int sensei_tiles_create(sensei_ctx *ctx, const sensei_csr *A, float min_density, int max_width, void *device_buf, size_t bytes, void *stream,
+                        sensei_tiles **out) {
+    if (!ctx || !csr_ok(A, false) || !out || !device_buf || !(min_density > 0.f) || min_density > 1.f || max_width < 32 || max_width % 32 != 0 ||
+        max_width > 4096)
+        return SENSEI_INVALID_ARGUMENT;
+    if (reinterpret_cast<uintptr_t>(device_buf) % 256 != 0) return SENSEI_INVALID_ARGUMENT;
+    const TilesLayout L = tiles_layout(*A, min_density, max_width);
+    if (bytes < L.total) return SENSEI_WORKSPACE_TOO_SMALL;
+    hipStream_t s = as_stream(stream);
+    char *base = static_cast<char *>(device_buf);
+    auto at = [&](size_t off) { return reinterpret_cast<int32_t *>(base + off); };
+    sensei_tiles *D = new (std::nothrow) sensei_tiles;
+    if (!D) return SENSEI_HIP_ERROR;
+    auto fail = [&](int status) { delete D; return status; };
+    D->n_rows = A->n_rows; D->n_cols = A->n_cols; D->nnz = A->nnz;
+    D->src_row_ptr = A->row_ptr; D->src_col_idx = A->col_idx;
+    D->max_width = max_width;
+    D->Bh = reinterpret_cast<float *>(base + L.bh);
+    D->T.nt_r = L.nt_r; D->T.nt_c = L.nt_c; D->T.n_slots = 0; D->T.n_seg = 0;
+    D->T.seg_first = nullptr; D->T.rt_seg = nullptr; D->T.seg_rt = nullptr; D->T.part = nullptr; D->T.rank_vec = nullptr;
+    D->T.order_r = at(L.order_r); D->T.order_c = at(L.order_c); D->T.rt_ptr = at(L.rt_ptr); D->T.slot_ct = at(L.slot_ct);
+    D->T.bits = reinterpret_cast<unsigned *>(base + L.bits);
+    D->nnz_rem = A->nnz; D->row_ptr_rem = at(L.row_ptr_rem); D->col_rem = at(L.col_rem); D->pos = at(L.pos);
+    if (A->n_rows == 0 || A->n_cols == 0 || A->nnz == 0) { *out = D; return SENSEI_OK; }  // nothing to split: never used
+
+    // degrees on the device (the pos area is free until the split), ranking on the host: n log n on a few 10^5..10^6 integers
+    int32_t *deg_r_d = at(L.pos), *deg_c_d = at(L.col_rem);
+    if (launch_degrees(*A, deg_r_d, deg_c_d, s) != hipSuccess) return fail(SENSEI_HIP_ERROR);
+    std::vector<int32_t> deg_r(A->n_rows), deg_c(A->n_cols), rank, order;
+    if (hipMemcpyAsync(deg_r.data(), deg_r_d, (size_t)A->n_rows * 4, hipMemcpyDeviceToHost, s) != hipSuccess ||
+        hipMemcpyAsync(deg_c.data(), deg_c_d, (size_t)A->n_cols * 4, hipMemcpyDeviceToHost, s) != hipSuccess || hipStreamSynchronize(s) != hipSuccess)
+        return fail(SENSEI_HIP_ERROR);
+    rank_by_degree(deg_r, L.h_r, L.nt_r * 128, &rank, &order);
+    if (hipMemcpyAsync(at(L.rank_r), rank.data(), rank.size() * 4, hipMemcpyHostToDevice, s) != hipSuccess ||
+        hipMemcpyAsync(at(L.order_r), order.data(), order.size() * 4, hipMemcpyHostToDevice, s) != hipSuccess || hipStreamSynchronize(s) != hipSuccess)
+        return fail(SENSEI_HIP_ERROR);
+    rank_by_degree(deg_c, L.h_c, L.nt_c * 128, &rank, &order);
+    if (hipMemcpyAsync(at(L.rank_c), rank.data(), rank.size() * 4, hipMemcpyHostToDevice, s) != hipSuccess ||
+        hipMemcpyAsync(at(L.order_c), order.data(), order.size() * 4, hipMemcpyHostToDevice, s) != hipSuccess || hipStreamSynchronize(s) != hipSuccess)
+        return fail(SENSEI_HIP_ERROR);
+
+    ChunkPlan plan;
+    plan.chunk_nnz = choose_chunk_nnz(A->nnz);
+    plan.n_chunks = (int)((A->nnz + plan.chunk_nnz - 1) / plan.chunk_nnz);
+    plan.chunk_row = at(L.plan);
+    if (launch_chunk_rows(*A, plan, s) != hipSuccess) return fail(SENSEI_HIP_ERROR);
+    if (launch_tile_select(*A, plan, at(L.rank_r), at(L.rank_c), L.h_r, L.h_c, L.nt_r, L.nt_c, L.min_count, at(L.hist), at(L.sel_scan), at(L.slot_of),
+                           at(L.slot_ct), at(L.rt_ptr), at(L.scan_small), s) != hipSuccess)
+        return fail(SENSEI_HIP_ERROR);
+    int32_t n_slots = 0;
+    if (hipMemcpyAsync(&n_slots, at(L.sel_scan) + L.n_tiles, 4, hipMemcpyDeviceToHost, s) != hipSuccess || hipStreamSynchronize(s) != hipSuccess)
+        return fail(SENSEI_HIP_ERROR);
+    if (n_slots < 0 || n_slots > L.max_slots) return fail(SENSEI_HIP_ERROR);
+    D->T.n_slots = n_slots;
+    if (n_slots == 0) { *out = D; return SENSEI_OK; }  // no tile is dense enough: the pattern stays as it is
+    {   // segments of the rows of tiles: the longest rows would otherwise keep one workgroup busy for hundreds of tiles
+        std::vector<int32_t> rt_ptr(L.nt_r + 1), seg_first, rt_seg(L.nt_r + 1), seg_rt;
+        if (hipMemcpyAsync(rt_ptr.data(), at(L.rt_ptr), rt_ptr.size() * 4, hipMemcpyDeviceToHost, s) != hipSuccess || hipStreamSynchronize(s) != hipSuccess)
+            return fail(SENSEI_HIP_ERROR);
+        for (int rt = 0; rt < L.nt_r; ++rt) {
+            rt_seg[rt] = (int32_t)seg_first.size();
+            for (int q = rt_ptr[rt]; q < rt_ptr[rt + 1]; q += kTilesPerSegment) { seg_first.push_back(q); seg_rt.push_back(rt); }
+        }
+        rt_seg[L.nt_r] = (int32_t)seg_first.size();
+        seg_first.push_back(rt_ptr[L.nt_r]);
+        seg_rt.push_back(0);
+        D->T.n_seg = rt_seg[L.nt_r];
+        if (D->T.n_seg > L.max_seg) return fail(SENSEI_HIP_ERROR);
+        if (hipMemcpyAsync(at(L.seg_first), seg_first.data(), seg_first.size() * 4, hipMemcpyHostToDevice, s) != hipSuccess ||
+            hipMemcpyAsync(at(L.rt_seg), rt_seg.data(), rt_seg.size() * 4, hipMemcpyHostToDevice, s) != hipSuccess ||
+            hipMemcpyAsync(at(L.seg_rt), seg_rt.data(), seg_rt.size() * 4, hipMemcpyHostToDevice, s) != hipSuccess || hipStreamSynchronize(s) != hipSuccess)
+            return fail(SENSEI_HIP_ERROR);
+        D->T.seg_first = at(L.seg_first); D->T.rt_seg = at(L.rt_seg); D->T.seg_rt = at(L.seg_rt);
+        D->T.rank_vec = reinterpret_cast<float *>(base + L.rank_vec);
+        D->T.part = reinterpret_cast<float *>(base + L.part);
+    }
+    if (launch_tile_split(*A, plan, at(L.rank_r), at(L.rank_c), L.h_r, L.h_c, L.nt_c, at(L.slot_of), n_slots, reinterpret_cast<unsigned *>(base + L.bits),
+                          at(L.pos), at(L.scan_large), at(L.col_rem), at(L.row_ptr_rem), s) != hipSuccess)
+        return fail(SENSEI_HIP_ERROR);
+    int32_t nnz_rem = 0;
+    if (hipMemcpyAsync(&nnz_rem, at(L.pos) + A->nnz, 4, hipMemcpyDeviceToHost, s) != hipSuccess || hipStreamSynchronize(s) != hipSuccess)
+        return fail(SENSEI_HIP_ERROR);
+    if (nnz_rem < 0 || nnz_rem > A->nnz) return fail(SENSEI_HIP_ERROR);
+    D->nnz_rem = nnz_rem;
+    sensei_csr Ar = *A;
+    Ar.nnz = nnz_rem; Ar.row_ptr = D->row_ptr_rem; Ar.col_idx = D->col_rem;
+    D->plan_rem.chunk_nnz = choose_chunk_nnz(nnz_rem);
+    D->plan_rem.n_chunks = nnz_rem <= 0 ? 1 : (int)(((int64_t)nnz_rem + D->plan_rem.chunk_nnz - 1) / D->plan_rem.chunk_nnz);
+    D->plan_rem.chunk_row = at(L.plan_rem);
+    if (launch_chunk_rows(Ar, D->plan_rem, s) != hipSuccess || hipStreamSynchronize(s) != hipSuccess) return fail(SENSEI_HIP_ERROR);
+    *out = D;
+    return SENSEI_OK;
+}
+
+int sensei_tiles_info(const sensei_tiles *tiles, int *n_tiles_kept, int64_t *nnz_dense, int64_t *nnz_sparse) {
+    if (!tiles) return SENSEI_INVALID_ARGUMENT;
+    if (n_tiles_kept) *n_tiles_kept = tiles->T.n_slots;
+    if (nnz_dense) *nnz_dense = tiles->nnz - tiles->nnz_rem;
+    if (nnz_sparse) *nnz_sparse = tiles->nnz_rem;
+    return SENSEI_OK;
+}
+
+int sensei_tiles_set_min_width(sensei_tiles *tiles, int min_width) {
+    if (!tiles || min_width < 1) return SENSEI_INVALID_ARGUMENT;
+    tiles->min_width = min_width;
+    return SENSEI_OK;
+}
+
+int sensei_tiles_destroy(sensei_tiles *tiles) {
+    delete tiles;
+    return SENSEI_OK;
+}
 
 int sensei_panels_destroy(sensei_panels *panels) {
     delete panels;

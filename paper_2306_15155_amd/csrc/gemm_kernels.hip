@@ -166,6 +166,193 @@ hipError_t gemm_launch_vec(const GemmArgs &g, int avec, int bvec, hipStream_t s)
     return hipGetLastError();
 }
 
+// ---- dense tiles of the hub region: C[order_r[rank], :] = sum over the kept 128 x 128 tiles of the rank's row of tiles of
+// (tile bits) . Bh[tile columns, :].  A tile's 0/1 entries are expanded from its bit mask while they are staged into LDS,
+// the right-hand operand is the copy of the gathered matrix in rank order (rows contiguous), so both loaders are as
+// regular as in the plain GEMM and the multiply runs on the fp32 matrix cores.  The rows of tiles of the largest hubs
+// keep hundreds of tiles, the others a few: the kept tiles of a row are therefore cut into segments of at most
+// kTilesPerSegment, one workgroup per (segment, 128 output columns) with a k loop of 16 ranks per step; a segment leaves
+// its 128 x f partial product in `part`, and k_tiles_reduce adds the segments of a row in order (no atomics) into C.
+struct DenseTilesArgs {
+    const unsigned *bits;                  // n_slots x 128 rows x 4 words
+    const int32_t *seg_first, *slot_ct;    // first slot of each segment (n_seg + 1 entries); column tile of a slot
+    const float *Bh;                       // (column tiles x 128) x f, row-major: row q = gathered row of the node at column rank q
+    float *part;                           // n_seg x 128 x f
+    long long ldbh;
+    int f, n_bn;
+    // attention mode: entry (i, j) of a tile weighs exp(LeakyReLU(s_l[i] + s_r[j]) - max_i), as the softmax mode of the SpMM does
+    const int32_t *seg_rt;                 // row of tiles of each segment
+    const float *sl_rank, *m_rank, *sr_rank;  // s_l and the row maximum by row rank, s_r by column rank
+    float slope;
+};
+
+template <bool ATTN>
+__global__ __launch_bounds__(kThreads) void k_dense_tiles(DenseTilesArgs g) {
+    constexpr int BM = 128, BN = 128, WGN = 2, TM = 2, TN = 2;
+    constexpr int APAD = 36, BPAD = 36;
+    __shared__ float As[KT][BM + APAD];
+    __shared__ __attribute__((aligned(16))) float Bs[KT][BN + BPAD];
+    const int seg = blockIdx.x / g.n_bn;
+    const int n0 = (blockIdx.x % g.n_bn) * BN;
+    const int s0 = g.seg_first[seg], s1 = g.seg_first[seg + 1];
+    if (s0 >= s1) return;
+    const int t = threadIdx.x;
+    const int wave = t >> 6, lane = t & 63;
+    const int wm = wave / WGN, wn = wave % WGN;
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    unsigned ra[2];   // four bits each: entries (row, k .. k + 3) of the tile
+    float4 rb[2];
+    const int a_row = t >> 2, a_kk = (t & 3) * 4;     // 64 rows per pass, 4 threads per row
+    const int b_row = t >> 5, b_nn = (t & 31) * 4;    // 8 k-rows per pass, 32 threads per row
+    const bool col_ok = n0 + b_nn < g.f;
+    float sl_t[2] = {0.f, 0.f}, m_t[2] = {0.f, 0.f};
+    float4 sr4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (ATTN) {
+        const int rt = g.seg_rt[seg];
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            sl_t[p] = g.sl_rank[rt * 128 + p * 64 + a_row];
+            m_t[p] = g.m_rank[rt * 128 + p * 64 + a_row];
+        }
+    }
+
+    auto fetch = [&](int slot, int ct, int k0) {
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            const int row = p * 64 + a_row, kk = k0 + a_kk;
+            ra[p] = (g.bits[((size_t)slot * 128 + row) * 4 + (kk >> 5)] >> (kk & 31)) & 15u;
+        }
+        if (ATTN) sr4 = *reinterpret_cast<const float4 *>(g.sr_rank + (size_t)ct * 128 + k0 + a_kk);
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            const int kr = p * 8 + b_row;
+            rb[p] = col_ok ? *reinterpret_cast<const float4 *>(g.Bh + ((size_t)ct * 128 + k0 + kr) * g.ldbh + n0 + b_nn) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int p = 0; p < 2; ++p)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float w = 1.f;
+                if (ATTN) {
+                    const float srv = e == 0 ? sr4.x : e == 1 ? sr4.y : e == 2 ? sr4.z : sr4.w;
+                    float tt = sl_t[p] + srv;
+                    tt = tt > 0.f ? tt : g.slope * tt;
+                    w = __expf(tt - m_t[p]);
+                }
+                As[a_kk + e][p * 64 + a_row] = ((ra[p] >> e) & 1u) ? w : 0.f;
+            }
+#pragma unroll
+        for (int p = 0; p < 2; ++p) *reinterpret_cast<float4 *>(&Bs[p * 8 + b_row][b_nn]) = rb[p];
+    };
+
+    const int n_steps = (s1 - s0) * (128 / KT);
+    int ct_next = g.slot_ct[s0];
+    fetch(s0, ct_next, 0);
+    for (int step = 0; step < n_steps; ++step) {
+        stash();
+        __syncthreads();
+        if (step + 1 < n_steps) {
+            const int nslot = s0 + (step + 1) / (128 / KT);
+            if ((step + 1) % (128 / KT) == 0) ct_next = g.slot_ct[nslot];
+            fetch(nslot, ct_next, ((step + 1) % (128 / KT)) * KT);
+        }
+        const int kh = lane >> 5, ll = lane & 31;
+#pragma unroll
+        for (int kk = 0; kk < KT; kk += 2) {
+            float av[TM], bv[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) av[i] = As[kk + kh][(wm * TM + i) * 32 + ll];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) bv[j] = Bs[kk + kh][(wn * TN + j) * 32 + ll];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+
+    const int kh = lane >> 5, ll = lane & 31;
+    float *out = g.part + (size_t)seg * 128 * g.f;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = (wm * TM + i) * 32 + 8 * (r / 4) + 4 * kh + (r % 4);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int col = n0 + (wn * TN + j) * 32 + ll;
+                if (col < g.f) out[(size_t)row * g.f + col] = acc[i][j][r];
+            }
+        }
+}
+
+// C[order_r[rank], :] = sum of the partial products of the segments of the rank's row of tiles, in segment order
+__global__ void k_tiles_reduce(const float *__restrict__ part, const int32_t *__restrict__ rt_seg, const int32_t *__restrict__ order_r, int nt_r,
+                               int f, int f_store, float *__restrict__ C, long long ldc, long long c_tile) {
+    const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const int f4 = f / 4;
+    if (t >= (long long)nt_r * 128 * f4) return;
+    const int col = (int)(t % f4) * 4;
+    const int rank = (int)(t / f4);
+    const int rt = rank >> 7, row = rank & 127;
+    const int g0 = rt_seg[rt], g1 = rt_seg[rt + 1];
+    if (g0 >= g1) return;  // no kept tile in this row of tiles: its rows of C keep the zeros they were given
+    const int node = order_r[rank];
+    if (node < 0) return;
+    float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int sg = g0; sg < g1; ++sg) {
+        const float4 v = *reinterpret_cast<const float4 *>(part + ((size_t)sg * 128 + row) * f + col);
+        sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+    }
+    float *dst = C + (long long)(col >> 5) * c_tile + (long long)node * ldc + (col & 31);
+    const float vals[4] = {sum.x, sum.y, sum.z, sum.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        if (col + e < f_store) dst[e] = vals[e];
+}
+
+// the attention vectors in rank order (zeros where a rank has no node)
+__global__ void k_gather_ranked_vecs(const float *__restrict__ s_l, const float *__restrict__ s_r, const float2 *__restrict__ mz,
+                                     const int32_t *__restrict__ order_r, int n_r, const int32_t *__restrict__ order_c, int n_c,
+                                     float *__restrict__ sl_rank, float *__restrict__ m_rank, float *__restrict__ sr_rank) {
+    const int q = blockIdx.x * blockDim.x + threadIdx.x;
+    if (q < n_r) {
+        const int i = order_r[q];
+        sl_rank[q] = i >= 0 ? s_l[i] : 0.f;
+        m_rank[q] = i >= 0 ? mz[i].x : 0.f;
+    }
+    if (q < n_c) {
+        const int j = order_c[q];
+        sr_rank[q] = j >= 0 ? s_r[j] : 0.f;
+    }
+}
+
+// Bh[q, 0:f) = row order_c[q] of the slice-major matrix B (zeros where the rank has no node)
+__global__ void k_gather_ranked_rows(const float *__restrict__ B, long long n_cols, int f, const int32_t *__restrict__ order_c, long long n_ranks,
+                                     float *__restrict__ Bh) {
+    const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const int f4 = f / 4;
+    if (t >= n_ranks * f4) return;
+    const long long q = t / f4;
+    const int col = (int)(t % f4) * 4;
+    const int j = order_c[q];
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (j >= 0) v = *reinterpret_cast<const float4 *>(B + (long long)(col >> 5) * n_cols * 32 + (long long)j * 32 + (col & 31));
+    *reinterpret_cast<float4 *>(Bh + q * f + col) = v;
+}
+
 // ---- C[M x N] = A^T . B with A stored [K x M] and B stored [K x N] (both row-major), K very long: the weight
 // gradient dW = X^T . G of a layer, reduced over all nodes.  The K range is cut into `splits` slabs, one
 // workgroup per (output tile, slab); slab s writes its partial tile to part[s] and k_sum_splits adds the slabs
@@ -404,6 +591,32 @@ hipError_t launch_gemm(const float *A, int64_t lda, const float *W, int64_t ldw,
     }
     g.n_bn = (m_store + 63) / 64;
     return done(gemm_launch_vec<64, 64, 2, 2>(g, avec, bvec, s));
+}
+
+hipError_t launch_dense_tiles(const TileSplit &T, const float *B_sliced, int64_t n_cols, int f, float *Bh, float *C, int64_t ldc, int f_store,
+                              bool c_sliced, int64_t n_rows, hipStream_t s, const float *s_l, const float *s_r, const float2 *mz, float slope) {
+    if (T.n_slots <= 0 || f <= 0) return hipSuccess;
+    const long long n_ranks = (long long)T.nt_c * 128;
+    hipLaunchKernelGGL(k_gather_ranked_rows, dim3((unsigned)((n_ranks * (f / 4) + 255) / 256)), dim3(256), 0, s, B_sliced, (long long)n_cols, f,
+                       T.order_c, n_ranks, Bh);
+    DenseTilesArgs g;
+    g.bits = T.bits; g.seg_first = T.seg_first; g.slot_ct = T.slot_ct;
+    g.Bh = Bh; g.ldbh = f; g.part = T.part;
+    g.f = f; g.n_bn = (f + 127) / 128;
+    g.seg_rt = T.seg_rt; g.sl_rank = nullptr; g.m_rank = nullptr; g.sr_rank = nullptr; g.slope = slope;
+    if (s_l) {
+        const int n_r = T.nt_r * 128, n_c = T.nt_c * 128;
+        g.sl_rank = T.rank_vec; g.m_rank = T.rank_vec + n_r; g.sr_rank = T.rank_vec + 2 * n_r;
+        hipLaunchKernelGGL(k_gather_ranked_vecs, dim3((unsigned)(((n_r > n_c ? n_r : n_c) + 255) / 256)), dim3(256), 0, s, s_l, s_r, mz, T.order_r, n_r,
+                           T.order_c, n_c, T.rank_vec, T.rank_vec + n_r, T.rank_vec + 2 * n_r);
+        hipLaunchKernelGGL(k_dense_tiles<true>, dim3((unsigned)(T.n_seg * g.n_bn)), dim3(kThreads), 0, s, g);
+    } else {
+        hipLaunchKernelGGL(k_dense_tiles<false>, dim3((unsigned)(T.n_seg * g.n_bn)), dim3(kThreads), 0, s, g);
+    }
+    const long long threads = (long long)T.nt_r * 128 * (f / 4);
+    hipLaunchKernelGGL(k_tiles_reduce, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, (const float *)T.part, T.rt_seg, T.order_r, T.nt_r, f,
+                       f_store, C, c_sliced ? 32LL : (long long)ldc, c_sliced ? (long long)n_rows * 32 : 32LL);
+    return hipGetLastError();
 }
 
 hipError_t launch_gemv2(const float *A, int64_t lda, int64_t n, int k, const float *v1, const float *v2, float *y1,

@@ -101,8 +101,11 @@ hipError_t launch_softmax(const sensei_csr &A, const float *e, float *alpha, con
                           hipStream_t s);
 // Logits e_ij = LeakyReLU(s_l[i] + s_r[j]) of every stored entry, written to logits[k] (or logits[dst_index[k]]), and the
 // statistics stats[i] = (row max, sum of exp(e - max)) that kSpmmSoftmax needs.
+// dst_scan (optional, nnz + 1, instead of dst_index): entry k is stored at logits[dst_scan[k]] only if dst_scan[k + 1] differs
+// from dst_scan[k] (the remainder of a dense-tile split); the statistics always cover every entry.
 hipError_t launch_attention_stats(const sensei_csr &A, const float *s_l, const float *s_r, float slope, float *logits,
-                                  const int32_t *dst_index, const ChunkPlan &p, float2 *stats, float2 *carry_stats, hipStream_t s);
+                                  const int32_t *dst_index, const ChunkPlan &p, float2 *stats, float2 *carry_stats, hipStream_t s,
+                                  const int32_t *dst_scan = nullptr);
 size_t softmax_ws_bytes(const sensei_csr &A);
 
 // ---- backward of the attention layer
@@ -134,6 +137,39 @@ hipError_t launch_stack_weights(const float *W, int64_t ldw, int hops, int f_in,
 
 // out2[0] = largest row length, out2[1] = sum of squared row lengths (device, 16 bytes)
 hipError_t launch_row_moments(const sensei_csr &A, unsigned long long *out2, hipStream_t s);
+
+// ---- dense tiles of the hub region (nodes ranked by degree; tiles of 128 x 128 ranks kept as bit masks)
+struct TileSplit {
+    int nt_r, nt_c;                    // tiles per side of the tiled region
+    int n_slots;                       // kept tiles
+    const int32_t *order_r, *order_c;  // device, nt * 128: node at rank, -1 beyond the last node
+    const int32_t *rt_ptr, *slot_ct;   // device: first slot of each row of tiles (nt_r + 1), column tile of each slot
+    const unsigned *bits;              // device: n_slots x 128 x 4 words
+    int n_seg;                         // segments of at most kTilesPerSegment consecutive slots of one row of tiles
+    const int32_t *seg_first, *rt_seg; // device: first slot of each segment (n_seg + 1); first segment of each row of tiles (nt_r + 1)
+    const int32_t *seg_rt;             // device: row of tiles of each segment
+    float *part;                       // device: n_seg x 128 x (widest operand) partial products
+    float *rank_vec;                   // device: 2 * nt_r * 128 + nt_c * 128 floats for the attention vectors in rank order
+};
+constexpr int kTilesPerSegment = 8;
+size_t scan_large_temp_bytes(long long n);
+hipError_t launch_exclusive_scan_large(int32_t *data, long long n, int32_t *temp, hipStream_t s);
+// histogram of the entries per tile, choice of the tiles with at least min_count entries, slot tables; sel_scan: n_tiles + 1 ints
+// (its last element is the number of kept tiles), scan_temp: scan_temp_bytes(n_tiles + 1)
+hipError_t launch_tile_select(const sensei_csr &A, const ChunkPlan &p, const int32_t *rank_r, const int32_t *rank_c, int h_r, int h_c,
+                              int nt_r, int nt_c, int min_count, int32_t *hist, int32_t *sel_scan, int32_t *slot_of, int32_t *slot_ct,
+                              int32_t *rt_ptr, int32_t *scan_temp, hipStream_t s);
+// bit masks of the kept tiles and the CSR of everything else; pos: nnz + 1 ints (on return entry k of A sits at place pos[k] of
+// the remainder iff pos[k + 1] != pos[k]; pos[nnz] = size of the remainder), scan_temp: scan_large_temp_bytes(nnz + 1)
+hipError_t launch_tile_split(const sensei_csr &A, const ChunkPlan &p, const int32_t *rank_r, const int32_t *rank_c, int h_r, int h_c, int nt_c,
+                             const int32_t *slot_of, int n_slots, unsigned *bits, int32_t *pos, int32_t *scan_temp, int32_t *col_rem,
+                             int32_t *row_ptr_rem, hipStream_t s);
+hipError_t launch_zero_matrix(float *C, int64_t n, int f, int64_t ldc, bool sliced, hipStream_t s);
+// C rows of the ranked nodes = (kept tiles) . B, raw sums; B slice-major with f (a multiple of 32) columns; Bh: nt_c * 128 * f floats
+// With s_l, s_r, mz (attention mode) entry (i, j) of a tile weighs exp(LeakyReLU(s_l[i] + s_r[j]) - mz[i].x) instead of 1.
+hipError_t launch_dense_tiles(const TileSplit &T, const float *B_sliced, int64_t n_cols, int f, float *Bh, float *C, int64_t ldc, int f_store,
+                              bool c_sliced, int64_t n_rows, hipStream_t s, const float *s_l = nullptr, const float *s_r = nullptr,
+                              const float2 *mz = nullptr, float slope = 0.f);
 
 // ---- dense
 // Y[0:n, 0:m_store) = act(row_scale[i] * (A[n x k] . W[k x m])); columns m..m_store are written as act(0);

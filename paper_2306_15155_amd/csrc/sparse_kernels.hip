@@ -590,7 +590,17 @@ struct SoftmaxArgs {
     float *alpha;
     float *logits;             // where the statistics pass parks the logits it computed from s_l, s_r
     const int32_t *dst_index;  // optional: the logit of entry k goes to logits[dst_index[k]] (column-panel order)
+    const int32_t *dst_scan;   // optional: entry k goes to logits[dst_scan[k]] if dst_scan[k + 1] != dst_scan[k], nowhere otherwise
 };
+
+__device__ __forceinline__ void keep_logit(const SoftmaxArgs &a, int k, float e) {
+    if (a.dst_scan) {
+        const int p = a.dst_scan[k];
+        if (a.dst_scan[k + 1] != p) a.logits[p] = e;
+    } else {
+        a.logits[a.dst_index ? a.dst_index[k] : k] = e;
+    }
+}
 
 // Row statistics with the same chunk ownership as SpMM: lanes stride over the non-zeros of the
 // current row piece, then a wavefront reduction closes the piece.
@@ -623,7 +633,7 @@ __global__ __launch_bounds__(kBlock) void k_softmax_stats(SoftmaxArgs a) {
             for (int k = rs; k < rend; ++k) {
                 float e;
                 if (FROM_E) e = a.e[k];
-                else { e = leaky(sl + a.s_r[a.n.col_idx[k]], a.slope); a.logits[a.dst_index ? a.dst_index[k] : k] = e; }  // kept for the second pass
+                else { e = leaky(sl + a.s_r[a.n.col_idx[k]], a.slope); keep_logit(a, k, e); }  // kept for the second pass
                 mz_add(rm, rz, e);
             }
             if (cont && row == i_first) a.carry[chunk] = make_float2(rm, rz);
@@ -655,7 +665,7 @@ __global__ __launch_bounds__(kBlock) void k_softmax_stats(SoftmaxArgs a) {
         for (int k = pos + lane; k < seg_hi; k += 64) {
             float e;
             if (FROM_E) e = a.e[k];
-            else { e = leaky(sl + a.s_r[a.n.col_idx[k]], a.slope); a.logits[a.dst_index ? a.dst_index[k] : k] = e; }  // kept for the second pass
+            else { e = leaky(sl + a.s_r[a.n.col_idx[k]], a.slope); keep_logit(a, k, e); }  // kept for the second pass
             mz_add(m, z, e);
         }
         pos = seg_hi;
@@ -803,6 +813,94 @@ __global__ __launch_bounds__(kBlock) void k_panel_scatter(NnzArgs a, int n_panel
                    col_out[d] = col;
                    perm_out[k] = d;
                });
+}
+
+// ------------------------------------------------------- dense tiles of the hub region (set-up kernels)
+//
+// Nodes are ranked by degree (rank 0 = the longest row / the most referenced column).  In rank order the pattern of a
+// skewed graph is nearly dense at the top left; tiles of 128 x 128 ranks that hold enough entries are stored as bit
+// masks and multiplied on the matrix cores, the entries outside such tiles stay in a (smaller) CSR remainder.
+struct TileMapArgs {
+    NnzArgs n;
+    const int32_t *rank_r, *rank_c;  // rank of every row / column node; ranks >= h_r / h_c lie outside the tiled region
+    int h_r, h_c, nt_c;
+};
+
+__device__ __forceinline__ int tile_of(const TileMapArgs &a, int rr, int col) {
+    if (rr >= a.h_r) return -1;
+    const int rc = a.rank_c[col];
+    if (rc >= a.h_c) return -1;
+    return (rr >> 7) * a.nt_c + (rc >> 7);
+}
+
+__global__ __launch_bounds__(kBlock) void k_tile_hist(TileMapArgs a, int32_t *__restrict__ hist) {
+    const int chunk = wave_chunk();
+    if (chunk >= a.n.n_chunks) return;
+    walk_chunk(a.n, chunk, threadIdx.x & 63, [&](int i) { return a.rank_r[i]; },
+               [&](int k, int rr) {
+                   const int t = tile_of(a, rr, a.n.col_idx[k]);
+                   if (t >= 0) atomicAdd(&hist[t], 1);
+               });
+}
+
+// sel[t] = 1 where tile t holds at least min_count entries (sel[n_tiles] = 0, the slot that receives the total of the scan)
+__global__ void k_tile_flags(const int32_t *__restrict__ hist, int n_tiles, int min_count, int32_t *__restrict__ sel) {
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t <= n_tiles) sel[t] = (t < n_tiles && hist[t] >= min_count) ? 1 : 0;
+}
+
+// after the exclusive scan of sel: slot numbers of the kept tiles (row-major, so the slots of one row of tiles are
+// consecutive), the column tile of every slot, the first slot of every row of tiles
+__global__ void k_tile_slots(const int32_t *__restrict__ hist, const int32_t *__restrict__ sel_scan, int n_tiles, int nt_r, int nt_c,
+                             int min_count, int32_t *__restrict__ slot_of, int32_t *__restrict__ slot_ct, int32_t *__restrict__ rt_ptr) {
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < n_tiles) {
+        const bool kept = hist[t] >= min_count;
+        slot_of[t] = kept ? sel_scan[t] : -1;
+        if (kept) slot_ct[sel_scan[t]] = t % nt_c;
+    }
+    if (t <= nt_r) rt_ptr[t] = sel_scan[(long long)t * nt_c < n_tiles ? t * nt_c : n_tiles];
+}
+
+// bit (row, column) of its tile for every entry inside a kept tile; flag[k] = 1 for the entries that stay sparse
+__global__ __launch_bounds__(kBlock) void k_tile_mark(TileMapArgs a, const int32_t *__restrict__ slot_of, unsigned *__restrict__ bits,
+                                                       int32_t *__restrict__ flag) {
+    const int chunk = wave_chunk();
+    if (chunk >= a.n.n_chunks) return;
+    walk_chunk(a.n, chunk, threadIdx.x & 63, [&](int i) { return a.rank_r[i]; },
+               [&](int k, int rr) {
+                   const int col = a.n.col_idx[k];
+                   const int t = tile_of(a, rr, col);
+                   const int slot = t >= 0 ? slot_of[t] : -1;
+                   if (slot >= 0) {
+                       const int rc = a.rank_c[col];
+                       atomicOr(&bits[((size_t)slot * 128 + (rr & 127)) * 4 + ((rc & 127) >> 5)], 1u << (rc & 31));
+                   }
+                   flag[k] = slot >= 0 ? 0 : 1;
+               });
+}
+
+// pos = exclusive scan of flag over nnz + 1 slots: entry k stays sparse iff pos[k + 1] != pos[k], at place pos[k]
+__global__ __launch_bounds__(kBlock) void k_rem_scatter(NnzArgs a, const int32_t *__restrict__ pos, int32_t *__restrict__ col_rem) {
+    const long long k = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= a.nnz) return;
+    const int p = pos[k];
+    if (pos[k + 1] != p) col_rem[p] = a.col_idx[k];
+}
+
+__global__ void k_rem_rowptr(const int32_t *__restrict__ row_ptr, int n_rows, const int32_t *__restrict__ pos, int32_t *__restrict__ row_ptr_rem) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i <= n_rows) row_ptr_rem[i] = pos[row_ptr[i]];
+}
+
+__global__ void k_zero_f32(float *__restrict__ p, long long n4) {  // n4 groups of four floats, 16-byte aligned
+    const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < n4) reinterpret_cast<float4 *>(p)[t] = make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
+__global__ void k_zero_rows(float *__restrict__ C, long long n, int f, long long ldc) {
+    const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < n * f) C[(t / f) * ldc + (t % f)] = 0.f;
 }
 
 inline unsigned blocks_for(long long n, int per_block) { return (unsigned)((n + per_block - 1) / per_block); }
@@ -1381,7 +1479,7 @@ hipError_t launch_softmax(const sensei_csr &A, const float *e, float *alpha, con
     SoftmaxArgs a;
     a.n = nnz_args(A, p);
     a.e = e; a.s_l = nullptr; a.s_r = nullptr; a.slope = 0.f; a.stats = stats; a.carry = carry_stats; a.alpha = alpha;
-    a.logits = nullptr; a.dst_index = nullptr;
+    a.logits = nullptr; a.dst_index = nullptr; a.dst_scan = nullptr;
     dim3 g1(blocks_for(p.n_chunks, kWavesPerBlock));
     hipLaunchKernelGGL((k_softmax_stats<true>), g1, dim3(kBlock), 0, s, a);
     if (p.n_chunks > 1) hipLaunchKernelGGL(k_softmax_fixup, dim3(blocks_for(p.n_chunks - 1, kBlock)), dim3(kBlock), 0, s, a);
@@ -1390,11 +1488,12 @@ hipError_t launch_softmax(const sensei_csr &A, const float *e, float *alpha, con
 }
 
 hipError_t launch_attention_stats(const sensei_csr &A, const float *s_l, const float *s_r, float slope, float *logits,
-                                  const int32_t *dst_index, const ChunkPlan &p, float2 *stats, float2 *carry_stats, hipStream_t s) {
+                                  const int32_t *dst_index, const ChunkPlan &p, float2 *stats, float2 *carry_stats, hipStream_t s,
+                                  const int32_t *dst_scan) {
     SoftmaxArgs a;
     a.n = nnz_args(A, p);
     a.e = nullptr; a.s_l = s_l; a.s_r = s_r; a.slope = slope; a.stats = stats; a.carry = carry_stats; a.alpha = nullptr;
-    a.logits = logits; a.dst_index = dst_index;
+    a.logits = logits; a.dst_index = dst_index; a.dst_scan = dst_scan;
     hipLaunchKernelGGL((k_softmax_stats<false>), dim3(blocks_for(p.n_chunks, kWavesPerBlock)), dim3(kBlock), 0, s, a);
     if (p.n_chunks > 1) hipLaunchKernelGGL(k_softmax_fixup, dim3(blocks_for(p.n_chunks - 1, kBlock)), dim3(kBlock), 0, s, a);
     return hipGetLastError();
@@ -1518,6 +1617,83 @@ hipError_t launch_panel_build(const sensei_csr &A, const ChunkPlan &plan, int n_
     if (A.nnz > 0)
         hipLaunchKernelGGL(k_panel_scatter, dim3(blocks_for(plan.n_chunks, kWavesPerBlock)), dim3(kBlock), 0, s, nnz_args(A, plan), n_panels,
                            width, pp, (const int32_t *)off, col_out, perm_out);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------ dense tiles (host side)
+
+// exclusive scan of up to 2^31 ints: the block totals are scanned by the same three kernels instead of one thread
+size_t scan_large_temp_bytes(long long n) {
+    const long long nb = (n + kScanPerBlock - 1) / kScanPerBlock;
+    return align_up((size_t)(nb + 1) * sizeof(int32_t), 256) + scan_temp_bytes((int)(nb + 1));
+}
+
+hipError_t launch_exclusive_scan_large(int32_t *data, long long n, int32_t *temp, hipStream_t s) {
+    if (n <= 0) return hipSuccess;
+    const unsigned nb = blocks_for(n, kScanPerBlock);
+    int32_t *sums = temp;
+    int32_t *temp2 = temp + align_up((size_t)(nb + 1) * sizeof(int32_t), 256) / sizeof(int32_t);
+    hipLaunchKernelGGL(k_scan_local, dim3(nb), dim3(256), 0, s, data, (int)n, sums);
+    const hipError_t e = launch_exclusive_scan(sums, (int)nb, temp2, s);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_scan_add, dim3(nb), dim3(256), 0, s, data, (int)n, (const int32_t *)sums);
+    return hipGetLastError();
+}
+
+static TileMapArgs tile_map_args(const sensei_csr &A, const ChunkPlan &p, const int32_t *rank_r, const int32_t *rank_c, int h_r, int h_c, int nt_c) {
+    TileMapArgs a;
+    a.n = nnz_args(A, p);
+    a.rank_r = rank_r; a.rank_c = rank_c; a.h_r = h_r; a.h_c = h_c; a.nt_c = nt_c;
+    return a;
+}
+
+hipError_t launch_tile_select(const sensei_csr &A, const ChunkPlan &p, const int32_t *rank_r, const int32_t *rank_c, int h_r, int h_c,
+                              int nt_r, int nt_c, int min_count, int32_t *hist, int32_t *sel_scan, int32_t *slot_of, int32_t *slot_ct,
+                              int32_t *rt_ptr, int32_t *scan_temp, hipStream_t s) {
+    const int n_tiles = nt_r * nt_c;
+    hipLaunchKernelGGL(k_fill_i32, dim3(blocks_for(n_tiles, kBlock)), dim3(kBlock), 0, s, hist, (long long)n_tiles, 0);
+    if (A.nnz > 0)
+        hipLaunchKernelGGL(k_tile_hist, dim3(blocks_for(p.n_chunks, kWavesPerBlock)), dim3(kBlock), 0, s,
+                           tile_map_args(A, p, rank_r, rank_c, h_r, h_c, nt_c), hist);
+    hipLaunchKernelGGL(k_tile_flags, dim3(blocks_for(n_tiles + 1, kBlock)), dim3(kBlock), 0, s, (const int32_t *)hist, n_tiles, min_count, sel_scan);
+    const hipError_t e = launch_exclusive_scan(sel_scan, n_tiles + 1, scan_temp, s);
+    if (e != hipSuccess) return e;
+    const int span = n_tiles > nt_r + 1 ? n_tiles : nt_r + 1;
+    hipLaunchKernelGGL(k_tile_slots, dim3(blocks_for(span, kBlock)), dim3(kBlock), 0, s, (const int32_t *)hist, (const int32_t *)sel_scan, n_tiles,
+                       nt_r, nt_c, min_count, slot_of, slot_ct, rt_ptr);
+    return hipGetLastError();
+}
+
+hipError_t launch_tile_split(const sensei_csr &A, const ChunkPlan &p, const int32_t *rank_r, const int32_t *rank_c, int h_r, int h_c, int nt_c,
+                             const int32_t *slot_of, int n_slots, unsigned *bits, int32_t *pos, int32_t *scan_temp, int32_t *col_rem,
+                             int32_t *row_ptr_rem, hipStream_t s) {
+    if (n_slots > 0) hipLaunchKernelGGL(k_fill_i32, dim3(blocks_for((long long)n_slots * 512, kBlock)), dim3(kBlock), 0, s,
+                                        reinterpret_cast<int32_t *>(bits), (long long)n_slots * 512, 0);
+    hipLaunchKernelGGL(k_fill_i32, dim3(1), dim3(64), 0, s, pos + A.nnz, 1LL, 0);
+    if (A.nnz > 0)
+        hipLaunchKernelGGL(k_tile_mark, dim3(blocks_for(p.n_chunks, kWavesPerBlock)), dim3(kBlock), 0, s,
+                           tile_map_args(A, p, rank_r, rank_c, h_r, h_c, nt_c), slot_of, bits, pos);
+    const hipError_t e = launch_exclusive_scan_large(pos, (long long)A.nnz + 1, scan_temp, s);
+    if (e != hipSuccess) return e;
+    if (A.nnz > 0) hipLaunchKernelGGL(k_rem_scatter, dim3(blocks_for(A.nnz, kBlock)), dim3(kBlock), 0, s, nnz_args(A, p), (const int32_t *)pos, col_rem);
+    hipLaunchKernelGGL(k_rem_rowptr, dim3(blocks_for((long long)A.n_rows + 1, kBlock)), dim3(kBlock), 0, s, A.row_ptr, A.n_rows, (const int32_t *)pos,
+                       row_ptr_rem);
+    return hipGetLastError();
+}
+
+// C (n x f, row-major with ldc, or slice-major when `sliced`) = 0
+hipError_t launch_zero_matrix(float *C, int64_t n, int f, int64_t ldc, bool sliced, hipStream_t s) {
+    if (n <= 0 || f <= 0) return hipSuccess;
+    if (sliced || ldc == f) {
+        const long long total = (long long)n * (sliced ? pad32(f) : f);
+        if (total % 4 == 0 && reinterpret_cast<uintptr_t>(C) % 16 == 0) {
+            hipLaunchKernelGGL(k_zero_f32, dim3(blocks_for(total / 4, kBlock)), dim3(kBlock), 0, s, C, total / 4);
+            return hipGetLastError();
+        }
+        hipLaunchKernelGGL(k_zero_rows, dim3(blocks_for(total, kBlock)), dim3(kBlock), 0, s, C, total, 1, 1LL);
+        return hipGetLastError();
+    }
+    hipLaunchKernelGGL(k_zero_rows, dim3(blocks_for((long long)n * f, kBlock)), dim3(kBlock), 0, s, C, (long long)n, f, (long long)ldc);
     return hipGetLastError();
 }
 

@@ -635,3 +635,63 @@ def test_gatv2_layer_larger_graph_and_argument_checks(ctx):
         ctx.gatv2_layer(A.s, dev(X), dev(W_l), dev(W_r), dev(att), 2)
     with pytest.raises(SenseiError):
         ctx.gatv2_layer(A.s, dev(X), dev(W_l[:, :64].copy()), dev(W_r), dev(att), 0)   # W_l and W_r differ in shape
+
+
+# ------------------------------------------------------------------ dense tiles of the hub region
+
+@pytest.mark.parametrize("density", [0.02, 0.125, 0.5])
+def test_dense_tile_split_gives_the_same_spmm_and_layers(ctx, density):
+    from paper_2306_15155_amd import Tiles, csr_struct
+    g = synth.rmat(47, 6000, 160_000)
+    A = DeviceCSR(g)
+    T = Tiles(ctx, A.s, density, 256, min_width=32)
+    assert T.nnz_dense + T.nnz_sparse == g.row_ptr[-1]
+    if density <= 0.125:
+        assert T.n_tiles > 0 and T.nnz_dense > 0
+    At = csr_struct(g.n_rows, g.n_cols, A.row_ptr, A.col_idx, None, None, T)
+    for f in (32, 41, 64, 100, 256):
+        B = synth.uniform(f, 31, (g.n_cols, f))
+        assert_close(ctx.spmm(At, SPMM_PATTERN, dev(B)), oracle.spmm(g.row_ptr, g.col_idx, None, B), what=f"pattern f={f}")
+    dr, dc = ctx.degrees(A.s)
+    r, c = ctx.norm_vectors(dr), ctx.norm_vectors(dc)
+    X, W = synth.uniform(47, 10, (g.n_cols, 100)), synth.glorot(47, 11, 100, 41)
+    ref = oracle.gcn_layer(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, ACT_RELU)
+    for cid in range(4):
+        assert_close(ctx.gcn_layer(At, r, c, dev(X), dev(W), cid, ACT_RELU), ref, what=f"gcn comp {cid}")
+    ref2 = oracle.sgc_layer(g.n_rows, g.row_ptr, g.col_idx, X, W, 3, ACT_RELU)
+    for cid in (0, 1):
+        assert_close(ctx.sgc_layer(At, r, c, dev(X), dev(W), 3, cid, ACT_RELU), ref2, what=f"sgc comp {cid}")
+    # attention: the tiles form their weights from s_l, s_r and the row maxima, the remainder from its stored logits
+    for f_out in (41, 160):
+        Wg = synth.glorot(47, 12, 100, f_out)
+        a_l, a_r = synth.normal(47, 13, (f_out,), 0.0, 0.4), synth.normal(47, 14, (f_out,), 0.0, 0.4)
+        refg = oracle.gat_layer(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, Wg, a_l, a_r, 0.2, ACT_RELU)
+        for cid in range(4):
+            assert_close(ctx.gat_layer(At, dev(X), dev(Wg), dev(a_l), dev(a_r), cid, 0.2, ACT_RELU), refg, what=f"gat {f_out} comp {cid}")
+    # a wider operand than the split was made for, and weighted modes, fall back to the ordinary path
+    B = synth.uniform(48, 31, (g.n_cols, 300))
+    assert_close(ctx.spmm(At, SPMM_PATTERN, dev(B)), oracle.spmm(g.row_ptr, g.col_idx, None, B), what="too wide")
+    T.close()
+
+
+def test_dense_tile_split_edge_cases(ctx):
+    from paper_2306_15155_amd import Tiles, csr_struct
+    # rectangular block, a graph with a hub and empty rows, a graph too small for a full tile, self loops only
+    for name in ("rect", "hub_empty", "tiny", "selfloops", "er"):
+        g = GRAPHS[name]
+        A = DeviceCSR(g)
+        T = Tiles(ctx, A.s, 0.001, 128, min_width=32)
+        assert T.nnz_dense + T.nnz_sparse == g.row_ptr[-1]
+        At = csr_struct(g.n_rows, g.n_cols, A.row_ptr, A.col_idx, None, None, T)
+        for f in (32, 47, 128):
+            B = synth.uniform(f, 33, (g.n_cols, f))
+            assert_close(ctx.spmm(At, SPMM_PATTERN, dev(B)), oracle.spmm(g.row_ptr, g.col_idx, None, B), what=f"{name} f={f}")
+        X, Wg = synth.uniform(49, 10, (g.n_cols, 20)), synth.glorot(49, 11, 20, 40)
+        a_l, a_r = synth.normal(49, 13, (40,), 0.0, 0.4), synth.normal(49, 14, (40,), 0.0, 0.4)
+        refg = oracle.gat_layer(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, Wg, a_l, a_r)
+        assert_close(ctx.gat_layer(At, dev(X), dev(Wg), dev(a_l), dev(a_r), 0), refg, what=f"{name} gat")
+        T.close()
+    with pytest.raises(SenseiError):
+        Tiles(ctx, DeviceCSR(GRAPHS["er"]).s, 0.0, 128)
+    with pytest.raises(SenseiError):
+        Tiles(ctx, DeviceCSR(GRAPHS["er"]).s, 0.1, 100)
