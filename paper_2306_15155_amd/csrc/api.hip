@@ -44,7 +44,7 @@ struct sensei_tiles {
     sensei::TileSplit T;
     int64_t nnz_rem;                           // entries left in the sparse remainder
     const int32_t *row_ptr_rem, *col_rem;
-    const int32_t *pos;                        // nnz + 1: place of each original entry in the remainder (see launch_tile_split)
+    const int32_t *dst_rem;                    // nnz: place of each original entry in the remainder, -1 for the entries inside tiles
     sensei::ChunkPlan plan_rem;
     float *Bh;                                 // room for the gathered matrix in rank order, max_width columns
     int max_width;
@@ -530,8 +530,8 @@ int run_gat(const sensei_csr &A, const sensei_mat &X, const sensei_mat &W, const
         // One pass computes the logits and the per-row softmax statistics; the aggregation then weighs each neighbour
         // by exp(e - max) and scales the row by 1 / sum, so the attention weights themselves are never stored.  With a
         // panel copy the logits are written straight in panel order and the SpMM follows the panels.
-        SENSEI_TRY(launch_attention_stats(A, s_l, s_r, slope, logits, by_panel ? A.panels->position : nullptr, plan, stats, carry_stats, s,
-                                          by_tiles ? A.tiles->pos : nullptr));
+        SENSEI_TRY(launch_attention_stats(A, s_l, s_r, slope, logits, by_tiles ? A.tiles->dst_rem : by_panel ? A.panels->position : nullptr, plan,
+                                          stats, carry_stats, s));
         const AttnVectors attn = {s_l, s_r, slope};
         sensei_csr Aw = A;
         Aw.val = logits;
@@ -1136,7 +1136,7 @@ constexpr int kTileRanksMax = 65536;  // ranks per side that are examined for de
 struct TilesLayout {
     int h_r, h_c, nt_r, nt_c, n_tiles, max_slots, min_count;
     size_t rank_r, rank_c, order_r, order_c, hist, sel_scan, slot_of, slot_ct, rt_ptr, scan_small, plan, bits, pos, scan_large, col_rem,
-        row_ptr_rem, plan_rem, bh, seg_first, rt_seg, seg_rt, rank_vec, part, total;
+        dst_rem, row_ptr_rem, plan_rem, bh, seg_first, rt_seg, seg_rt, rank_vec, part, total;
     int max_seg;
 };
 
@@ -1168,6 +1168,7 @@ TilesLayout tiles_layout(const sensei_csr &A, float min_density, int max_width) 
     L.pos = put(((size_t)A.nnz + 1) * 4);
     L.scan_large = put(scan_large_temp_bytes((long long)A.nnz + 1));
     L.col_rem = put((size_t)A.nnz * 4);
+    L.dst_rem = put((size_t)A.nnz * 4);
     L.row_ptr_rem = put(((size_t)A.n_rows + 1) * 4);
     L.plan_rem = put(plan_bytes(A.nnz) + 4096);
     L.bh = put((size_t)L.nt_c * 128 * max_width * 4);
@@ -1182,15 +1183,24 @@ TilesLayout tiles_layout(const sensei_csr &A, float min_density, int max_width) 
 }
 
 // nodes in descending order of degree (ties: lower id first): rank of every node (INT_MAX beyond the first h) and the
-// node at every rank (-1 in the padding up to whole tiles)
-void rank_by_degree(const std::vector<int32_t> &deg, int h, int n_ranks, std::vector<int32_t> *rank, std::vector<int32_t> *order) {
+// node at every rank (-1 in the padding up to whole tiles).  Only the first h places are needed: selection, then a sort
+// of those.  Returns the number of entries in the 128 highest-degree rows (or columns), an upper bound for any one tile.
+int64_t rank_by_degree(const std::vector<int32_t> &deg, int h, int n_ranks, std::vector<int32_t> *rank, std::vector<int32_t> *order) {
     const int n = (int)deg.size();
     std::vector<int32_t> idx(n);
     for (int i = 0; i < n; ++i) idx[i] = i;
-    std::stable_sort(idx.begin(), idx.end(), [&](int32_t a, int32_t b) { return deg[a] > deg[b]; });
+    auto before = [&](int32_t a, int32_t b) { return deg[a] != deg[b] ? deg[a] > deg[b] : a < b; };
+    if (h < n) std::nth_element(idx.begin(), idx.begin() + h, idx.end(), before);
+    std::sort(idx.begin(), idx.begin() + h, before);
     rank->assign(n, 0x7fffffff);
     order->assign(n_ranks, -1);
-    for (int q = 0; q < h; ++q) { (*rank)[idx[q]] = q; (*order)[q] = idx[q]; }
+    int64_t top = 0;
+    for (int q = 0; q < h; ++q) {
+        (*rank)[idx[q]] = q;
+        (*order)[q] = idx[q];
+        if (q < 128) top += deg[idx[q]];
+    }
+    return top;
 }
 }  // namespace
 
@@ -1223,7 +1233,7 @@ int sensei_tiles_create(sensei_ctx *ctx, const sensei_csr *A, float min_density,
     D->T.seg_first = nullptr; D->T.rt_seg = nullptr; D->T.seg_rt = nullptr; D->T.part = nullptr; D->T.rank_vec = nullptr;
     D->T.order_r = at(L.order_r); D->T.order_c = at(L.order_c); D->T.rt_ptr = at(L.rt_ptr); D->T.slot_ct = at(L.slot_ct);
     D->T.bits = reinterpret_cast<unsigned *>(base + L.bits);
-    D->nnz_rem = A->nnz; D->row_ptr_rem = at(L.row_ptr_rem); D->col_rem = at(L.col_rem); D->pos = at(L.pos);
+    D->nnz_rem = A->nnz; D->row_ptr_rem = at(L.row_ptr_rem); D->col_rem = at(L.col_rem); D->dst_rem = at(L.dst_rem);
     if (A->n_rows == 0 || A->n_cols == 0 || A->nnz == 0) { *out = D; return SENSEI_OK; }  // nothing to split: never used
 
     // degrees on the device (the pos area is free until the split), ranking on the host: n log n on a few 10^5..10^6 integers
@@ -1233,11 +1243,13 @@ int sensei_tiles_create(sensei_ctx *ctx, const sensei_csr *A, float min_density,
     if (hipMemcpyAsync(deg_r.data(), deg_r_d, (size_t)A->n_rows * 4, hipMemcpyDeviceToHost, s) != hipSuccess ||
         hipMemcpyAsync(deg_c.data(), deg_c_d, (size_t)A->n_cols * 4, hipMemcpyDeviceToHost, s) != hipSuccess || hipStreamSynchronize(s) != hipSuccess)
         return fail(SENSEI_HIP_ERROR);
-    rank_by_degree(deg_r, L.h_r, L.nt_r * 128, &rank, &order);
+    const int64_t top_r = rank_by_degree(deg_r, L.h_r, L.nt_r * 128, &rank, &order);
+    if (top_r < L.min_count) { *out = D; return SENSEI_OK; }  // not even the 128 longest rows together fill one tile to the threshold
     if (hipMemcpyAsync(at(L.rank_r), rank.data(), rank.size() * 4, hipMemcpyHostToDevice, s) != hipSuccess ||
         hipMemcpyAsync(at(L.order_r), order.data(), order.size() * 4, hipMemcpyHostToDevice, s) != hipSuccess || hipStreamSynchronize(s) != hipSuccess)
         return fail(SENSEI_HIP_ERROR);
-    rank_by_degree(deg_c, L.h_c, L.nt_c * 128, &rank, &order);
+    const int64_t top_c = rank_by_degree(deg_c, L.h_c, L.nt_c * 128, &rank, &order);
+    if (top_c < L.min_count) { *out = D; return SENSEI_OK; }
     if (hipMemcpyAsync(at(L.rank_c), rank.data(), rank.size() * 4, hipMemcpyHostToDevice, s) != hipSuccess ||
         hipMemcpyAsync(at(L.order_c), order.data(), order.size() * 4, hipMemcpyHostToDevice, s) != hipSuccess || hipStreamSynchronize(s) != hipSuccess)
         return fail(SENSEI_HIP_ERROR);
@@ -1278,7 +1290,7 @@ int sensei_tiles_create(sensei_ctx *ctx, const sensei_csr *A, float min_density,
         D->T.part = reinterpret_cast<float *>(base + L.part);
     }
     if (launch_tile_split(*A, plan, at(L.rank_r), at(L.rank_c), L.h_r, L.h_c, L.nt_c, at(L.slot_of), n_slots, reinterpret_cast<unsigned *>(base + L.bits),
-                          at(L.pos), at(L.scan_large), at(L.col_rem), at(L.row_ptr_rem), s) != hipSuccess)
+                          at(L.pos), at(L.scan_large), at(L.col_rem), at(L.dst_rem), at(L.row_ptr_rem), s) != hipSuccess)
         return fail(SENSEI_HIP_ERROR);
     int32_t nnz_rem = 0;
     if (hipMemcpyAsync(&nnz_rem, at(L.pos) + A->nnz, 4, hipMemcpyDeviceToHost, s) != hipSuccess || hipStreamSynchronize(s) != hipSuccess)

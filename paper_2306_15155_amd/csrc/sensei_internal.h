@@ -101,11 +101,9 @@ hipError_t launch_softmax(const sensei_csr &A, const float *e, float *alpha, con
                           hipStream_t s);
 // Logits e_ij = LeakyReLU(s_l[i] + s_r[j]) of every stored entry, written to logits[k] (or logits[dst_index[k]]), and the
 // statistics stats[i] = (row max, sum of exp(e - max)) that kSpmmSoftmax needs.
-// dst_scan (optional, nnz + 1, instead of dst_index): entry k is stored at logits[dst_scan[k]] only if dst_scan[k + 1] differs
-// from dst_scan[k] (the remainder of a dense-tile split); the statistics always cover every entry.
+// A negative dst_index[k] keeps entry k out of `logits` (it lies in a dense tile); the statistics always cover every entry.
 hipError_t launch_attention_stats(const sensei_csr &A, const float *s_l, const float *s_r, float slope, float *logits,
-                                  const int32_t *dst_index, const ChunkPlan &p, float2 *stats, float2 *carry_stats, hipStream_t s,
-                                  const int32_t *dst_scan = nullptr);
+                                  const int32_t *dst_index, const ChunkPlan &p, float2 *stats, float2 *carry_stats, hipStream_t s);
 size_t softmax_ws_bytes(const sensei_csr &A);
 
 // ---- backward of the attention layer
@@ -159,11 +157,11 @@ hipError_t launch_exclusive_scan_large(int32_t *data, long long n, int32_t *temp
 hipError_t launch_tile_select(const sensei_csr &A, const ChunkPlan &p, const int32_t *rank_r, const int32_t *rank_c, int h_r, int h_c,
                               int nt_r, int nt_c, int min_count, int32_t *hist, int32_t *sel_scan, int32_t *slot_of, int32_t *slot_ct,
                               int32_t *rt_ptr, int32_t *scan_temp, hipStream_t s);
-// bit masks of the kept tiles and the CSR of everything else; pos: nnz + 1 ints (on return entry k of A sits at place pos[k] of
-// the remainder iff pos[k + 1] != pos[k]; pos[nnz] = size of the remainder), scan_temp: scan_large_temp_bytes(nnz + 1)
+// bit masks of the kept tiles and the CSR of everything else; pos: nnz + 1 ints of scratch (pos[nnz] = size of the remainder on
+// return), scan_temp: scan_large_temp_bytes(nnz + 1); dst_rem[k] = place of entry k of A in the remainder, -1 if it lies in a tile
 hipError_t launch_tile_split(const sensei_csr &A, const ChunkPlan &p, const int32_t *rank_r, const int32_t *rank_c, int h_r, int h_c, int nt_c,
                              const int32_t *slot_of, int n_slots, unsigned *bits, int32_t *pos, int32_t *scan_temp, int32_t *col_rem,
-                             int32_t *row_ptr_rem, hipStream_t s);
+                             int32_t *dst_rem, int32_t *row_ptr_rem, hipStream_t s);
 hipError_t launch_zero_matrix(float *C, int64_t n, int f, int64_t ldc, bool sliced, hipStream_t s);
 // C rows of the ranked nodes = (kept tiles) . B, raw sums; B slice-major with f (a multiple of 32) columns; Bh: nt_c * 128 * f floats
 // With s_l, s_r, mz (attention mode) entry (i, j) of a tile weighs exp(LeakyReLU(s_l[i] + s_r[j]) - mz[i].x) instead of 1.

@@ -589,16 +589,15 @@ struct SoftmaxArgs {
     float2 *stats, *carry;
     float *alpha;
     float *logits;             // where the statistics pass parks the logits it computed from s_l, s_r
-    const int32_t *dst_index;  // optional: the logit of entry k goes to logits[dst_index[k]] (column-panel order)
-    const int32_t *dst_scan;   // optional: entry k goes to logits[dst_scan[k]] if dst_scan[k + 1] != dst_scan[k], nowhere otherwise
+    const int32_t *dst_index;  // optional: the logit of entry k goes to logits[dst_index[k]] (panel or remainder order), nowhere if negative
 };
 
 __device__ __forceinline__ void keep_logit(const SoftmaxArgs &a, int k, float e) {
-    if (a.dst_scan) {
-        const int p = a.dst_scan[k];
-        if (a.dst_scan[k + 1] != p) a.logits[p] = e;
+    if (a.dst_index) {
+        const int d = a.dst_index[k];
+        if (d >= 0) a.logits[d] = e;  // negative: the entry is not stored (it lies in a dense tile)
     } else {
-        a.logits[a.dst_index ? a.dst_index[k] : k] = e;
+        a.logits[k] = e;
     }
 }
 
@@ -881,11 +880,14 @@ __global__ __launch_bounds__(kBlock) void k_tile_mark(TileMapArgs a, const int32
 }
 
 // pos = exclusive scan of flag over nnz + 1 slots: entry k stays sparse iff pos[k + 1] != pos[k], at place pos[k]
-__global__ __launch_bounds__(kBlock) void k_rem_scatter(NnzArgs a, const int32_t *__restrict__ pos, int32_t *__restrict__ col_rem) {
+__global__ __launch_bounds__(kBlock) void k_rem_scatter(NnzArgs a, const int32_t *__restrict__ pos, int32_t *__restrict__ col_rem,
+                                                         int32_t *__restrict__ dst_rem) {
     const long long k = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (k >= a.nnz) return;
     const int p = pos[k];
-    if (pos[k + 1] != p) col_rem[p] = a.col_idx[k];
+    const bool stays = pos[k + 1] != p;
+    if (stays) col_rem[p] = a.col_idx[k];
+    dst_rem[k] = stays ? p : -1;
 }
 
 __global__ void k_rem_rowptr(const int32_t *__restrict__ row_ptr, int n_rows, const int32_t *__restrict__ pos, int32_t *__restrict__ row_ptr_rem) {
@@ -1479,7 +1481,7 @@ hipError_t launch_softmax(const sensei_csr &A, const float *e, float *alpha, con
     SoftmaxArgs a;
     a.n = nnz_args(A, p);
     a.e = e; a.s_l = nullptr; a.s_r = nullptr; a.slope = 0.f; a.stats = stats; a.carry = carry_stats; a.alpha = alpha;
-    a.logits = nullptr; a.dst_index = nullptr; a.dst_scan = nullptr;
+    a.logits = nullptr; a.dst_index = nullptr;
     dim3 g1(blocks_for(p.n_chunks, kWavesPerBlock));
     hipLaunchKernelGGL((k_softmax_stats<true>), g1, dim3(kBlock), 0, s, a);
     if (p.n_chunks > 1) hipLaunchKernelGGL(k_softmax_fixup, dim3(blocks_for(p.n_chunks - 1, kBlock)), dim3(kBlock), 0, s, a);
@@ -1488,12 +1490,11 @@ hipError_t launch_softmax(const sensei_csr &A, const float *e, float *alpha, con
 }
 
 hipError_t launch_attention_stats(const sensei_csr &A, const float *s_l, const float *s_r, float slope, float *logits,
-                                  const int32_t *dst_index, const ChunkPlan &p, float2 *stats, float2 *carry_stats, hipStream_t s,
-                                  const int32_t *dst_scan) {
+                                  const int32_t *dst_index, const ChunkPlan &p, float2 *stats, float2 *carry_stats, hipStream_t s) {
     SoftmaxArgs a;
     a.n = nnz_args(A, p);
     a.e = nullptr; a.s_l = s_l; a.s_r = s_r; a.slope = slope; a.stats = stats; a.carry = carry_stats; a.alpha = nullptr;
-    a.logits = logits; a.dst_index = dst_index; a.dst_scan = dst_scan;
+    a.logits = logits; a.dst_index = dst_index;
     hipLaunchKernelGGL((k_softmax_stats<false>), dim3(blocks_for(p.n_chunks, kWavesPerBlock)), dim3(kBlock), 0, s, a);
     if (p.n_chunks > 1) hipLaunchKernelGGL(k_softmax_fixup, dim3(blocks_for(p.n_chunks - 1, kBlock)), dim3(kBlock), 0, s, a);
     return hipGetLastError();
@@ -1666,7 +1667,7 @@ hipError_t launch_tile_select(const sensei_csr &A, const ChunkPlan &p, const int
 
 hipError_t launch_tile_split(const sensei_csr &A, const ChunkPlan &p, const int32_t *rank_r, const int32_t *rank_c, int h_r, int h_c, int nt_c,
                              const int32_t *slot_of, int n_slots, unsigned *bits, int32_t *pos, int32_t *scan_temp, int32_t *col_rem,
-                             int32_t *row_ptr_rem, hipStream_t s) {
+                             int32_t *dst_rem, int32_t *row_ptr_rem, hipStream_t s) {
     if (n_slots > 0) hipLaunchKernelGGL(k_fill_i32, dim3(blocks_for((long long)n_slots * 512, kBlock)), dim3(kBlock), 0, s,
                                         reinterpret_cast<int32_t *>(bits), (long long)n_slots * 512, 0);
     hipLaunchKernelGGL(k_fill_i32, dim3(1), dim3(64), 0, s, pos + A.nnz, 1LL, 0);
@@ -1675,7 +1676,7 @@ hipError_t launch_tile_split(const sensei_csr &A, const ChunkPlan &p, const int3
                            tile_map_args(A, p, rank_r, rank_c, h_r, h_c, nt_c), slot_of, bits, pos);
     const hipError_t e = launch_exclusive_scan_large(pos, (long long)A.nnz + 1, scan_temp, s);
     if (e != hipSuccess) return e;
-    if (A.nnz > 0) hipLaunchKernelGGL(k_rem_scatter, dim3(blocks_for(A.nnz, kBlock)), dim3(kBlock), 0, s, nnz_args(A, p), (const int32_t *)pos, col_rem);
+    if (A.nnz > 0) hipLaunchKernelGGL(k_rem_scatter, dim3(blocks_for(A.nnz, kBlock)), dim3(kBlock), 0, s, nnz_args(A, p), (const int32_t *)pos, col_rem, dst_rem);
     hipLaunchKernelGGL(k_rem_rowptr, dim3(blocks_for((long long)A.n_rows + 1, kBlock)), dim3(kBlock), 0, s, A.row_ptr, A.n_rows, (const int32_t *)pos,
                        row_ptr_rem);
     return hipGetLastError();
