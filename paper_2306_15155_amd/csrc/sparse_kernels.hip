@@ -660,12 +660,34 @@ __global__ __launch_bounds__(kBlock) void k_softmax_stats(SoftmaxArgs a) {
         const int seg_hi = re < hi ? re : hi;
         float sl = 0.f;
         if (!FROM_E) sl = a.s_l[i];
+        if (FROM_E) {
 #pragma unroll 4
-        for (int k = pos + lane; k < seg_hi; k += 64) {
-            float e;
-            if (FROM_E) e = a.e[k];
-            else { e = leaky(sl + a.s_r[a.n.col_idx[k]], a.slope); keep_logit(a, k, e); }  // kept for the second pass
-            mz_add(m, z, e);
+            for (int k = pos + lane; k < seg_hi; k += 64) mz_add(m, z, a.e[k]);
+        } else {
+            // four batches of 64 entries per trip, all loads of a trip requested before the first store: a store may alias
+            // anything as far as the compiler knows, so a plain loop would wait for one gather chain per 64 entries
+            constexpr int UB = 4;
+            for (int k0 = pos + lane; k0 < seg_hi; k0 += 64 * UB) {
+                int col[UB], dst[UB];
+                float sr[UB];
+#pragma unroll
+                for (int u = 0; u < UB; ++u) {
+                    const int k = k0 + 64 * u;
+                    const int kc = k < seg_hi ? k : pos;
+                    col[u] = a.n.col_idx[kc];
+                    dst[u] = a.dst_index ? a.dst_index[kc] : kc;
+                }
+#pragma unroll
+                for (int u = 0; u < UB; ++u) sr[u] = a.s_r[col[u]];
+#pragma unroll
+                for (int u = 0; u < UB; ++u) {
+                    if (k0 + 64 * u < seg_hi) {
+                        const float e = leaky(sl + sr[u], a.slope);
+                        if (dst[u] >= 0) a.logits[dst[u]] = e;  // kept for the second pass (negative: the entry lies in a dense tile)
+                        mz_add(m, z, e);
+                    }
+                }
+            }
         }
         pos = seg_hi;
     }
