@@ -475,6 +475,62 @@ __device__ __forceinline__ void walk_chunk(const NnzArgs &a, int chunk, int lane
     }
 }
 
+// The same walk with the work on a non-zero cut in two: `load(k, row_data)` only reads and returns what it read,
+// `apply(k, row_data, loaded)` computes and stores.  The reads of kWalkBatch non-zeros per lane are requested before the
+// first store of a trip: a store may alias anything as far as the compiler can tell, so a plain loop waits for one
+// memory round trip per non-zero and lane (measured: 12 % off the softmax backward pass of the attention layer).
+constexpr int kWalkBatch = 4;
+template <class PerRow, class Load, class Apply>
+__device__ __forceinline__ void walk_chunk2(const NnzArgs &a, int chunk, int lane, PerRow per_row, Load load, Apply apply) {
+    const long long lo_ll = (long long)chunk * a.chunk_nnz;
+    const int lo = (int)lo_ll;
+    const int hi = (int)((lo_ll + a.chunk_nnz < (long long)a.nnz) ? lo_ll + a.chunk_nnz : (long long)a.nnz);
+    if (lo >= hi) return;
+    const int i0 = a.chunk_row[chunk], i1 = a.chunk_row[chunk + 1];
+    const int i_first = (a.row_ptr[i0] > lo) ? i0 - 1 : i0;
+    if ((long long)(i1 - i_first) * kShortRowElem > (long long)(hi - lo)) {
+        for (int ib = i_first; ib < i1; ib += 64) {
+            const int row = ib + lane;
+            if (row < i1) {
+                int rs = a.row_ptr[row], re = a.row_ptr[row + 1];
+                rs = rs > lo ? rs : lo;
+                re = re < hi ? re : hi;
+                if (rs < re) {
+                    const auto rd = per_row(row);
+                    for (int k0 = rs; k0 < re; k0 += kWalkBatch) {
+                        decltype(load(k0, rd)) got[kWalkBatch];
+#pragma unroll
+                        for (int u = 0; u < kWalkBatch; ++u) got[u] = load(k0 + u < re ? k0 + u : rs, rd);
+#pragma unroll
+                        for (int u = 0; u < kWalkBatch; ++u)
+                            if (k0 + u < re) apply(k0 + u, rd, got[u]);
+                    }
+                }
+            }
+        }
+        return;
+    }
+    int i = __builtin_amdgcn_readfirstlane(i_first);
+    int pos = lo;
+    while (pos < hi) {
+        const int re = __builtin_amdgcn_readfirstlane(a.row_ptr[i + 1]);
+        if (re > pos) {
+            const int seg_hi = re < hi ? re : hi;
+            const auto rd = per_row(i);
+            for (int k0 = pos + lane; k0 < seg_hi; k0 += 64 * kWalkBatch) {
+                decltype(load(k0, rd)) got[kWalkBatch];
+#pragma unroll
+                for (int u = 0; u < kWalkBatch; ++u) got[u] = load(k0 + 64 * u < seg_hi ? k0 + 64 * u : pos, rd);
+#pragma unroll
+                for (int u = 0; u < kWalkBatch; ++u)
+                    if (k0 + 64 * u < seg_hi) apply(k0 + 64 * u, rd, got[u]);
+            }
+            pos = seg_hi;
+        }
+        i = __builtin_amdgcn_readfirstlane(i + 1);
+    }
+}
+
 __device__ __forceinline__ int wave_chunk() {
     return blockIdx.x * kWavesPerBlock + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 }
@@ -1216,16 +1272,16 @@ __global__ __launch_bounds__(kBlock) void k_gat_dt(GatDtArgs a) {
     const int chunk = wave_chunk();
     if (chunk >= a.n.n_chunks) return;
     struct RowData { float m, iz, dot; };
-    walk_chunk(a.n, chunk, threadIdx.x & 63,
-               [&](int i) { const float2 st = a.mz[i]; return RowData{st.x, inv_z(st.y), a.rowdot[i]}; },
-               [&](int k, const RowData &rd) {
-                   const float e = a.logits[k];
-                   const float al = expf(e - rd.m) * rd.iz;
-                   const float dt = al * (a.dalpha[k] - rd.dot) * (e > 0.f ? 1.f : a.slope);
-                   const int p = a.t_pos[k];
-                   a.dt[k] = dt;
-                   a.adt_t[p] = make_float2(al, dt);
-               });
+    struct Got { float e, da; int p; };
+    walk_chunk2(a.n, chunk, threadIdx.x & 63,
+                [&](int i) { const float2 st = a.mz[i]; return RowData{st.x, inv_z(st.y), a.rowdot[i]}; },
+                [&](int k, const RowData &) { return Got{a.logits[k], a.dalpha[k], a.t_pos[k]}; },
+                [&](int k, const RowData &rd, const Got &g) {
+                    const float al = expf(g.e - rd.m) * rd.iz;
+                    const float dt = al * (g.da - rd.dot) * (g.e > 0.f ? 1.f : a.slope);
+                    a.dt[k] = dt;
+                    a.adt_t[g.p] = make_float2(al, dt);
+                });
 }
 
 // dTheta[j, :] += ds_l[j] a_l + ds_r[j] a_r (ds_l counts only for j < n_l)
