@@ -52,7 +52,8 @@ def parse_args():
     ap.add_argument("--backward", action="store_true", help="time the backward pass even with --no-sweep")
     ap.add_argument("--no-panels", action="store_true", help="do not build the column-panel copy of the graph")
     ap.add_argument("--panels", type=int, default=0, help="force the number of column panels (0 = let the library measure)")
-    ap.add_argument("--tiles", type=float, default=0.125, help="dense-tile split of the hub region: least density of a kept tile (0 = off)")
+    ap.add_argument("--tiles", type=float, default=0.09, help="dense-tile split of the hub region: least density of a kept tile (0 = off)")
+    ap.add_argument("--tiles-min-width", type=int, default=64, help="narrowest SpMM (columns) that uses the dense-tile split")
     ap.add_argument("--no-gather-probe", action="store_true", help="skip the L2-resident gather probe")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run four 1 GiB device-to-device copies (a kernel of known traffic, for scaling rocprofv3 --pmc byte counters)")
@@ -123,7 +124,7 @@ def main():
     if args.tiles > 0:
         from paper_2306_15155_amd import Tiles
         tp = time.perf_counter()
-        tiles = Tiles(ctx, A, args.tiles, 256)
+        tiles = Tiles(ctx, A, args.tiles, 256, args.tiles_min_width)
         torch.cuda.synchronize()
         tiles_ms = (time.perf_counter() - tp) * 1e3
         A = csr_struct(N, N, row_ptr, col_idx, None, panels, tiles)
@@ -212,7 +213,7 @@ def main():
             for line in open(prof):
                 if line.startswith("traffic_bytes_per_launch %s:" % tag(k)):
                     traffic = float(line.split(":")[1])
-        split = tiles is not None and tiles.n_tiles > 0 and f_sp >= 128
+        split = tiles is not None and tiles.n_tiles > 0 and f_sp >= args.tiles_min_width
         what = "SpMM call = k_spmm on the sparse remainder + k_dense_tiles on the hub tiles" if split else "k_spmm"
         roofline = {"kernel": "%s (%s, F=%d, %s)" % (what, tag(k), f_sp, name_of(k)), "bound": "hbm",
                     "achieved": round(algo_bytes / t_s / 1e9, 1), "peak": 8000.0, "unit": "GB/s",

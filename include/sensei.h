@@ -242,19 +242,20 @@ int sensei_gatv2_layer(sensei_ctx *ctx, const sensei_csr *A, sensei_mat X, sense
  * On a skewed graph the rows and columns of the highest degree meet in a region that is nearly full: with the nodes in
  * order of descending degree, tiles of 128 x 128 ranks (among the first 65,536 ranks of either side) that hold at least
  * min_density * 16384 entries are kept as bit masks and multiplied on the matrix cores (sparse unweighted . dense
- * evaluated as a block-sparse GEMM), the entries outside such tiles stay in a CSR remainder whose SpMM adds to the
- * result.  A value-less SpMM on an internal slice-major operand of at most max_width columns (a multiple of 32; what
+ * evaluated as a block-sparse GEMM) on a stream of the object's own, while the caller's stream runs the SpMM over the
+ * CSR remainder of the entries outside such tiles; a last pass on the caller's stream joins the two sums and applies the
+ * row scaling and the activation (the fork and join are event dependencies between the two streams, so the call stays
+ * asynchronous and can be captured into a graph).  A value-less SpMM on an internal slice-major operand of at most max_width columns (a multiple of 32; what
  * the GCN, SGC and TAGCN layers run on graphs whose rows are gathered often) uses the split when `tiles` is set in the
  * sensei_csr; every other call ignores it.  Results differ from the unsplit path only in the order of summation.
  *   sensei_tiles_bytes   device bytes sensei_tiles_create needs (an upper bound taken before the tiles are counted);
  *   sensei_tiles_create  builds the split in device_buf (256-byte aligned, caller-owned, must outlive the object);
  *                        ranks the nodes on the host, so it synchronises the stream several times: a set-up call;
  *   sensei_tiles_info    kept tiles, entries inside them, entries in the remainder;
- *   sensei_tiles_set_min_width  narrowest SpMM (columns) that takes the split; 128 unless set (measured on a 233,000-node
- *                        power-law graph: 7 % faster at 256 columns, 13 % slower at 64);
+ *   sensei_tiles_set_min_width  narrowest SpMM (columns) that takes the split; 64 unless set;
  *   sensei_tiles_destroy frees the host object only.
- * The object keeps a buffer for the operand in rank order: calls that use one object at the same time on different
- * streams race on it. */
+ * The object keeps buffers for the operand in rank order and for the tiles' product, and its stream: calls that use one
+ * object at the same time on different streams race on them. */
 int sensei_tiles_bytes(const sensei_csr *A, float min_density, int max_width, size_t *device_bytes);
 int sensei_tiles_create(sensei_ctx *ctx, const sensei_csr *A, float min_density, int max_width, void *device_buf, size_t bytes, void *stream,
                         sensei_tiles **out);

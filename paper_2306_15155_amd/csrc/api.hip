@@ -48,8 +48,9 @@ struct sensei_tiles {
     sensei::ChunkPlan plan_rem;
     float *Bh;                                 // room for the gathered matrix in rank order, max_width columns
     int max_width;
-    int min_width = 128;                       // narrowest SpMM that takes the split (narrower ones lose more in the half-empty
-                                               // 128-column tiles of the dense kernel than the smaller remainder gains)
+    hipStream_t side = nullptr;                // the tiles are multiplied on this stream while the caller's runs the sparse remainder
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    int min_width = 64;                        // narrowest SpMM that takes the split
 };
 
 namespace {
@@ -196,18 +197,26 @@ hipError_t spmm_any(const sensei_csr &A, int mode, const float *r, const float *
     // attn: softmax mode on a pattern with a dense-tile split; A.val then holds the logits of the remainder, in its order
     const bool has_val = (mode == SENSEI_SPMM_WEIGHTED || mode == kSpmmSoftmax);
     if (tiles_usable(A, mode, f, b_sliced, attn != nullptr)) {
-        // hub region on the matrix cores, the rest as a sparse pass that adds to it and applies the scaling and activation
+        // The hub tiles go to the matrix cores on the side stream while this stream runs the sparse remainder (one is bound
+        // by the MFMA pipes, the other by the memory fabric); a last pass joins the two raw sums and applies scale and activation.
         const sensei_tiles &D = *A.tiles;
         hipEvent_t t0 = kt ? kt->next() : nullptr, t1 = t0 ? kt->next() : nullptr;
         if (t1 && hipEventRecord(t0, s) != hipSuccess) return hipErrorUnknown;
-        hipError_t e = launch_zero_matrix(C, A.n_rows, f_store, ldc, c_sliced, s);
+        hipError_t e = hipEventRecord(D.ev_fork, s);
+        if (e == hipSuccess) e = hipStreamWaitEvent(D.side, D.ev_fork, 0);
         if (e == hipSuccess)
-            e = launch_dense_tiles(D.T, B, A.n_cols, pad32(f), D.Bh, C, ldc, f_store, c_sliced, A.n_rows, s, attn ? attn->s_l : nullptr,
-                                   attn ? attn->s_r : nullptr, attn ? mz : nullptr, attn ? attn->slope : 0.f);
+            e = launch_dense_tiles(D.T, B, A.n_cols, pad32(f), D.Bh, D.side, attn ? attn->s_l : nullptr, attn ? attn->s_r : nullptr,
+                                   attn ? mz : nullptr, attn ? attn->slope : 0.f);
+        if (e == hipSuccess) e = hipEventRecord(D.ev_join, D.side);
         if (e != hipSuccess) return e;
         sensei_csr Ar = A;
         Ar.nnz = D.nnz_rem; Ar.row_ptr = D.row_ptr_rem; Ar.col_idx = D.col_rem; Ar.panels = nullptr; Ar.tiles = nullptr;
-        e = launch_spmm(Ar, mode, r, c, B, ldb, f, C, ldc, f_store, act, D.plan_rem, carry, s, nullptr, true, true, mz, b_sliced, 1, c_sliced);
+        e = launch_spmm(Ar, mode, nullptr, c, B, ldb, f, C, ldc, f_store, SENSEI_ACT_NONE, D.plan_rem, carry, s, nullptr, false, false, mz, b_sliced, 1,
+                        c_sliced);
+        if (e == hipSuccess) e = hipStreamWaitEvent(s, D.ev_join, 0);
+        if (e == hipSuccess)
+            e = launch_tiles_combine(D.T, C, A.n_rows, f_store, ldc, c_sliced, pad32(f), mode == kSpmmSoftmax ? nullptr : r,
+                                     mode == kSpmmSoftmax ? mz : nullptr, act, s);
         if (e != hipSuccess) return e;
         if (t1 && hipEventRecord(t1, s) != hipSuccess) return hipErrorUnknown;
         return hipSuccess;
@@ -1136,7 +1145,7 @@ constexpr int kTileRanksMax = 65536;  // ranks per side that are examined for de
 struct TilesLayout {
     int h_r, h_c, nt_r, nt_c, n_tiles, max_slots, min_count;
     size_t rank_r, rank_c, order_r, order_c, hist, sel_scan, slot_of, slot_ct, rt_ptr, scan_small, plan, bits, pos, scan_large, col_rem,
-        dst_rem, row_ptr_rem, plan_rem, bh, seg_first, rt_seg, seg_rt, rank_vec, part, total;
+        dst_rem, row_ptr_rem, plan_rem, bh, seg_first, rt_seg, seg_rt, rank_vec, part, dh, total;
     int max_seg;
 };
 
@@ -1178,6 +1187,7 @@ TilesLayout tiles_layout(const sensei_csr &A, float min_density, int max_width) 
     L.seg_rt = put(((size_t)L.max_seg + 1) * 4);
     L.rank_vec = put(((size_t)2 * L.nt_r + L.nt_c) * 128 * 4);
     L.part = put((size_t)L.max_seg * 128 * max_width * 4);
+    L.dh = put((size_t)L.nt_r * 128 * max_width * 4);
     L.total = off;
     return L;
 }
@@ -1224,13 +1234,14 @@ int sensei_tiles_create(sensei_ctx *ctx, const sensei_csr *A, float min_density,
     auto at = [&](size_t off) { return reinterpret_cast<int32_t *>(base + off); };
     sensei_tiles *D = new (std::nothrow) sensei_tiles;
     if (!D) return SENSEI_HIP_ERROR;
-    auto fail = [&](int status) { delete D; return status; };
+    auto fail = [&](int status) { sensei_tiles_destroy(D); return status; };
     D->n_rows = A->n_rows; D->n_cols = A->n_cols; D->nnz = A->nnz;
     D->src_row_ptr = A->row_ptr; D->src_col_idx = A->col_idx;
     D->max_width = max_width;
     D->Bh = reinterpret_cast<float *>(base + L.bh);
     D->T.nt_r = L.nt_r; D->T.nt_c = L.nt_c; D->T.n_slots = 0; D->T.n_seg = 0;
     D->T.seg_first = nullptr; D->T.rt_seg = nullptr; D->T.seg_rt = nullptr; D->T.part = nullptr; D->T.rank_vec = nullptr;
+    D->T.dh = nullptr; D->T.rank_r = nullptr;
     D->T.order_r = at(L.order_r); D->T.order_c = at(L.order_c); D->T.rt_ptr = at(L.rt_ptr); D->T.slot_ct = at(L.slot_ct);
     D->T.bits = reinterpret_cast<unsigned *>(base + L.bits);
     D->nnz_rem = A->nnz; D->row_ptr_rem = at(L.row_ptr_rem); D->col_rem = at(L.col_rem); D->dst_rem = at(L.dst_rem);
@@ -1287,6 +1298,11 @@ int sensei_tiles_create(sensei_ctx *ctx, const sensei_csr *A, float min_density,
             return fail(SENSEI_HIP_ERROR);
         D->T.seg_first = at(L.seg_first); D->T.rt_seg = at(L.rt_seg); D->T.seg_rt = at(L.seg_rt);
         D->T.rank_vec = reinterpret_cast<float *>(base + L.rank_vec);
+        D->T.dh = reinterpret_cast<float *>(base + L.dh);
+        D->T.rank_r = at(L.rank_r);
+        if (hipStreamCreateWithFlags(&D->side, hipStreamNonBlocking) != hipSuccess || hipEventCreateWithFlags(&D->ev_fork, hipEventDisableTiming) != hipSuccess ||
+            hipEventCreateWithFlags(&D->ev_join, hipEventDisableTiming) != hipSuccess)
+            return fail(SENSEI_HIP_ERROR);
         D->T.part = reinterpret_cast<float *>(base + L.part);
     }
     if (launch_tile_split(*A, plan, at(L.rank_r), at(L.rank_c), L.h_r, L.h_c, L.nt_c, at(L.slot_of), n_slots, reinterpret_cast<unsigned *>(base + L.bits),
@@ -1322,6 +1338,11 @@ int sensei_tiles_set_min_width(sensei_tiles *tiles, int min_width) {
 }
 
 int sensei_tiles_destroy(sensei_tiles *tiles) {
+    if (tiles) {
+        if (tiles->ev_fork) (void)hipEventDestroy(tiles->ev_fork);
+        if (tiles->ev_join) (void)hipEventDestroy(tiles->ev_join);
+        if (tiles->side) (void)hipStreamDestroy(tiles->side);
+    }
     delete tiles;
     return SENSEI_OK;
 }

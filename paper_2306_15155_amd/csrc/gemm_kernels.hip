@@ -172,7 +172,7 @@ hipError_t gemm_launch_vec(const GemmArgs &g, int avec, int bvec, hipStream_t s)
 // regular as in the plain GEMM and the multiply runs on the fp32 matrix cores.  The rows of tiles of the largest hubs
 // keep hundreds of tiles, the others a few: the kept tiles of a row are therefore cut into segments of at most
 // kTilesPerSegment, one workgroup per (segment, 128 output columns) with a k loop of 16 ranks per step; a segment leaves
-// its 128 x f partial product in `part`, and k_tiles_reduce adds the segments of a row in order (no atomics) into C.
+// its 128 x f partial product in `part`, and k_tiles_reduce adds the segments of a row in order (no atomics).
 struct DenseTilesArgs {
     const unsigned *bits;                  // n_slots x 128 rows x 4 words
     const int32_t *seg_first, *slot_ct;    // first slot of each segment (n_seg + 1 entries); column tile of a slot
@@ -298,9 +298,9 @@ __global__ __launch_bounds__(kThreads) void k_dense_tiles(DenseTilesArgs g) {
         }
 }
 
-// C[order_r[rank], :] = sum of the partial products of the segments of the rank's row of tiles, in segment order
-__global__ void k_tiles_reduce(const float *__restrict__ part, const int32_t *__restrict__ rt_seg, const int32_t *__restrict__ order_r, int nt_r,
-                               int f, int f_store, float *__restrict__ C, long long ldc, long long c_tile) {
+// Dh[rank, :] = sum of the partial products of the segments of the rank's row of tiles, in segment order (zeros for a row of
+// tiles that kept none)
+__global__ void k_tiles_reduce(const float *__restrict__ part, const int32_t *__restrict__ rt_seg, int nt_r, int f, float *__restrict__ Dh) {
     const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     const int f4 = f / 4;
     if (t >= (long long)nt_r * 128 * f4) return;
@@ -308,19 +308,38 @@ __global__ void k_tiles_reduce(const float *__restrict__ part, const int32_t *__
     const int rank = (int)(t / f4);
     const int rt = rank >> 7, row = rank & 127;
     const int g0 = rt_seg[rt], g1 = rt_seg[rt + 1];
-    if (g0 >= g1) return;  // no kept tile in this row of tiles: its rows of C keep the zeros they were given
-    const int node = order_r[rank];
-    if (node < 0) return;
     float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int sg = g0; sg < g1; ++sg) {
         const float4 v = *reinterpret_cast<const float4 *>(part + ((size_t)sg * 128 + row) * f + col);
         sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
     }
-    float *dst = C + (long long)(col >> 5) * c_tile + (long long)node * ldc + (col & 31);
-    const float vals[4] = {sum.x, sum.y, sum.z, sum.w};
+    *reinterpret_cast<float4 *>(Dh + (size_t)rank * f + col) = sum;
+}
+
+// C[i, :] = act(scale_i * (C[i, :] + Dh[rank of i, :])): joins the raw sums of the sparse remainder with those of the tiles
+// and applies what the SpMM epilogue would have applied (scale_i = r[i], or 1 / z_i in attention mode)
+__global__ void k_tiles_combine(float *__restrict__ C, long long n_rows, int f_store, long long ldc, long long c_tile, const float *__restrict__ Dh,
+                                int f, const int32_t *__restrict__ rank_r, int n_ranks, const float *__restrict__ r, const float2 *__restrict__ mz,
+                                int act) {
+    const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const int f4 = (f_store + 3) / 4;
+    if (t >= n_rows * f4) return;
+    const long long i = t / f4;
+    const int col = (int)(t % f4) * 4;
+    const int rank = rank_r[i];
+    float sc = 1.f;
+    if (mz) { const float z = mz[i].y; sc = z > 0.f ? 1.f / z : 0.f; }
+    else if (r) sc = r[i];
+    float *dst = C + (long long)(col >> 5) * c_tile + i * ldc + (col & 31);
+    const float *add = (rank < n_ranks) ? Dh + (size_t)rank * f + col : nullptr;
 #pragma unroll
-    for (int e = 0; e < 4; ++e)
-        if (col + e < f_store) dst[e] = vals[e];
+    for (int e = 0; e < 4; ++e) {
+        if (col + e < f_store) {
+            float y = (dst[e] + (add ? add[e] : 0.f)) * sc;
+            if (act == SENSEI_ACT_RELU) y = y > 0.f ? y : 0.f;
+            dst[e] = y;
+        }
+    }
 }
 
 // the attention vectors in rank order (zeros where a rank has no node)
@@ -593,8 +612,8 @@ hipError_t launch_gemm(const float *A, int64_t lda, const float *W, int64_t ldw,
     return done(gemm_launch_vec<64, 64, 2, 2>(g, avec, bvec, s));
 }
 
-hipError_t launch_dense_tiles(const TileSplit &T, const float *B_sliced, int64_t n_cols, int f, float *Bh, float *C, int64_t ldc, int f_store,
-                              bool c_sliced, int64_t n_rows, hipStream_t s, const float *s_l, const float *s_r, const float2 *mz, float slope) {
+hipError_t launch_dense_tiles(const TileSplit &T, const float *B_sliced, int64_t n_cols, int f, float *Bh, hipStream_t s, const float *s_l,
+                              const float *s_r, const float2 *mz, float slope) {
     if (T.n_slots <= 0 || f <= 0) return hipSuccess;
     const long long n_ranks = (long long)T.nt_c * 128;
     hipLaunchKernelGGL(k_gather_ranked_rows, dim3((unsigned)((n_ranks * (f / 4) + 255) / 256)), dim3(256), 0, s, B_sliced, (long long)n_cols, f,
@@ -614,8 +633,17 @@ hipError_t launch_dense_tiles(const TileSplit &T, const float *B_sliced, int64_t
         hipLaunchKernelGGL(k_dense_tiles<false>, dim3((unsigned)(T.n_seg * g.n_bn)), dim3(kThreads), 0, s, g);
     }
     const long long threads = (long long)T.nt_r * 128 * (f / 4);
-    hipLaunchKernelGGL(k_tiles_reduce, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, (const float *)T.part, T.rt_seg, T.order_r, T.nt_r, f,
-                       f_store, C, c_sliced ? 32LL : (long long)ldc, c_sliced ? (long long)n_rows * 32 : 32LL);
+    hipLaunchKernelGGL(k_tiles_reduce, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, (const float *)T.part, T.rt_seg, T.nt_r, f, T.dh);
+    return hipGetLastError();
+}
+
+hipError_t launch_tiles_combine(const TileSplit &T, float *C, int64_t n_rows, int f_store, int64_t ldc, bool c_sliced, int f, const float *r,
+                                const float2 *mz, int act, hipStream_t s) {
+    if (n_rows <= 0 || f_store <= 0) return hipSuccess;
+    const long long threads = (long long)n_rows * ((f_store + 3) / 4);
+    hipLaunchKernelGGL(k_tiles_combine, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, C, (long long)n_rows, f_store,
+                       c_sliced ? 32LL : (long long)ldc, c_sliced ? (long long)n_rows * 32 : 32LL, (const float *)T.dh, f, T.rank_r, T.nt_r * 128, r, mz,
+                       act);
     return hipGetLastError();
 }
 

@@ -148,6 +148,8 @@ struct TileSplit {
     const int32_t *seg_rt;             // device: row of tiles of each segment
     float *part;                       // device: n_seg x 128 x (widest operand) partial products
     float *rank_vec;                   // device: 2 * nt_r * 128 + nt_c * 128 floats for the attention vectors in rank order
+    float *dh;                         // device: nt_r * 128 x (widest operand): the tiles' product, by row rank
+    const int32_t *rank_r;             // device: rank of every row node (INT_MAX outside the tiled region)
 };
 constexpr int kTilesPerSegment = 8;
 size_t scan_large_temp_bytes(long long n);
@@ -163,11 +165,14 @@ hipError_t launch_tile_split(const sensei_csr &A, const ChunkPlan &p, const int3
                              const int32_t *slot_of, int n_slots, unsigned *bits, int32_t *pos, int32_t *scan_temp, int32_t *col_rem,
                              int32_t *dst_rem, int32_t *row_ptr_rem, hipStream_t s);
 hipError_t launch_zero_matrix(float *C, int64_t n, int f, int64_t ldc, bool sliced, hipStream_t s);
-// C rows of the ranked nodes = (kept tiles) . B, raw sums; B slice-major with f (a multiple of 32) columns; Bh: nt_c * 128 * f floats
-// With s_l, s_r, mz (attention mode) entry (i, j) of a tile weighs exp(LeakyReLU(s_l[i] + s_r[j]) - mz[i].x) instead of 1.
-hipError_t launch_dense_tiles(const TileSplit &T, const float *B_sliced, int64_t n_cols, int f, float *Bh, float *C, int64_t ldc, int f_store,
-                              bool c_sliced, int64_t n_rows, hipStream_t s, const float *s_l = nullptr, const float *s_r = nullptr,
-                              const float2 *mz = nullptr, float slope = 0.f);
+// T.dh[rank, 0:f) = (kept tiles of the rank's row of tiles) . B, raw sums; B slice-major with f (a multiple of 32) columns;
+// Bh: nt_c * 128 * f floats.  With s_l, s_r, mz (attention mode) entry (i, j) of a tile weighs
+// exp(LeakyReLU(s_l[i] + s_r[j]) - mz[i].x) instead of 1.
+hipError_t launch_dense_tiles(const TileSplit &T, const float *B_sliced, int64_t n_cols, int f, float *Bh, hipStream_t s,
+                              const float *s_l = nullptr, const float *s_r = nullptr, const float2 *mz = nullptr, float slope = 0.f);
+// C = act(scale (C + T.dh[rank of the row])) over all rows; scale_i = 1 / mz[i].y if mz, else r[i] if r, else 1
+hipError_t launch_tiles_combine(const TileSplit &T, float *C, int64_t n_rows, int f_store, int64_t ldc, bool c_sliced, int f, const float *r,
+                                const float2 *mz, int act, hipStream_t s);
 
 // ---- dense
 // Y[0:n, 0:m_store) = act(row_scale[i] * (A[n x k] . W[k x m])); columns m..m_store are written as act(0);
