@@ -741,3 +741,40 @@ def test_dense_tile_split_under_graph_capture(ctx):
         torch.cuda.synchronize()
         assert torch.equal(Y, want)
     T.close()
+
+
+def _tile_split_reference(g, min_density, max_ranks=65536):
+    """The selection rule of the dense-tile split written out with numpy: rank rows and columns by descending degree (ties: lower
+    id first), histogram the entries of the first max_ranks x max_ranks ranks per 128 x 128 tile, keep the tiles with at least
+    int(min_density * 16384) entries -> (kept tiles, entries inside them)."""
+    deg_r = np.diff(g.row_ptr).astype(np.int64)
+    deg_c = np.bincount(g.col_idx, minlength=g.n_cols).astype(np.int64)
+
+    def ranks(deg, h):
+        order = np.lexsort((np.arange(deg.size), -deg))[:h]
+        rank = np.full(deg.size, np.iinfo(np.int32).max, dtype=np.int64)
+        rank[order] = np.arange(order.size)
+        return rank
+
+    h_r, h_c = min(g.n_rows, max_ranks), min(g.n_cols, max_ranks)
+    rank_r, rank_c = ranks(deg_r, h_r), ranks(deg_c, h_c)
+    rr = np.repeat(rank_r, deg_r)
+    rc = rank_c[g.col_idx]
+    inside = (rr < h_r) & (rc < h_c)
+    nt_c = (h_c + 127) // 128
+    hist = np.bincount((rr[inside] // 128) * nt_c + rc[inside] // 128)
+    min_count = max(1, int(np.float32(min_density) * np.float32(128.0) * np.float32(128.0)))
+    kept = hist >= min_count
+    return int(kept.sum()), int(hist[kept].sum())
+
+
+@pytest.mark.parametrize("density", [0.02, 0.09, 0.3])
+def test_dense_tile_selection_is_the_stated_rule(ctx, density):
+    """Integer work of the set-up, bit exact: the number of kept tiles and of entries inside them equal the rule's."""
+    from paper_2306_15155_amd import Tiles
+    for g in (synth.rmat(51, 9000, 400_000), GRAPHS["rect"], GRAPHS["hub_empty"]):
+        A = DeviceCSR(g)
+        T = Tiles(ctx, A.s, density, 64)
+        want_tiles, want_dense = _tile_split_reference(g, density)
+        assert (T.n_tiles, T.nnz_dense, T.nnz_sparse) == (want_tiles, want_dense, int(g.row_ptr[-1]) - want_dense)
+        T.close()
