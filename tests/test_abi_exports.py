@@ -68,3 +68,38 @@ def test_host_only_queries_and_argument_checks_need_no_gpu():
     assert L.sensei_degrees(None, C.byref(A), None, None, None) == 1
     assert L.sensei_profile_enable(None, 1) == 1
     assert L.sensei_destroy(None) == 0
+
+
+def test_variant_layer_and_tile_queries_need_no_gpu():
+    """Workspace and size queries of the variant layers and of the dense-tile split: host arithmetic and argument checks."""
+    import ctypes as C
+    from paper_2306_15155_amd import binding
+    L = binding.lib()
+    A = binding.CsrStruct(1000, 1000, 50_000, 0x1000, 0x2000, None)
+    n = C.c_size_t()
+    for cid in (0, 1):
+        assert L.sensei_sgc_workspace(C.byref(A), 64, 32, cid, C.byref(n)) == 0 and n.value > 0
+        assert L.sensei_tagcn_workspace(C.byref(A), 64, 32, 3, cid, C.byref(n)) == 0 and n.value > 0
+        assert L.sensei_gatv2_workspace(C.byref(A), 64, 32, cid, C.byref(n)) == 0 and n.value > 0
+    assert L.sensei_sgc_workspace(C.byref(A), 64, 32, 2, C.byref(n)) == 2
+    assert L.sensei_tagcn_workspace(C.byref(A), 64, 32, 0, 0, C.byref(n)) == 1      # at least one hop
+    assert L.sensei_tagcn_workspace(C.byref(A), 64, 32, 3, 5, C.byref(n)) == 2
+    assert L.sensei_gatv2_workspace(C.byref(A), 0, 32, 0, C.byref(n)) == 1
+    # more hops need more room only where the hops are kept side by side (aggregate first)
+    L.sensei_tagcn_workspace(C.byref(A), 64, 32, 2, 0, C.byref(n)); two = n.value
+    L.sensei_tagcn_workspace(C.byref(A), 64, 32, 4, 0, C.byref(n)); four = n.value
+    assert four > two
+    L.sensei_tagcn_workspace(C.byref(A), 64, 32, 2, 1, C.byref(n)); two = n.value
+    L.sensei_tagcn_workspace(C.byref(A), 64, 32, 4, 1, C.byref(n)); four = n.value
+    assert four == two
+    assert L.sensei_tiles_bytes(C.byref(A), 0.09, 256, C.byref(n)) == 0 and n.value > 0 and n.value % 256 == 0
+    small = n.value
+    assert L.sensei_tiles_bytes(C.byref(A), 0.09, 512, C.byref(n)) == 0 and n.value > small   # wider operands, larger buffers
+    assert L.sensei_tiles_bytes(C.byref(A), 0.0, 256, C.byref(n)) == 1
+    assert L.sensei_tiles_bytes(C.byref(A), 1.5, 256, C.byref(n)) == 1
+    assert L.sensei_tiles_bytes(C.byref(A), 0.09, 100, C.byref(n)) == 1                       # a multiple of 32
+    assert L.sensei_tiles_info(None, None, None, None) == 1
+    assert L.sensei_tiles_set_min_width(None, 64) == 1
+    assert L.sensei_tiles_destroy(None) == 0
+    out = C.c_void_p()
+    assert L.sensei_tiles_create(None, C.byref(A), 0.09, 256, None, 0, None, C.byref(out)) == 1
