@@ -1390,9 +1390,11 @@ NnzArgs nnz_args(const sensei_csr &A, const ChunkPlan &p) {
 
 // ----------------------------------------------------------------- host side
 
+// Non-zeros per chunk (= per wavefront).  Large graphs: 512 - with 2048 the same kernels left the GPU short of
+// wavefronts: the attention statistics pass took 0.92 ms instead of 0.59 on 115 M non-zeros, an SpMM 64 columns wide
+// 1.46 ms instead of 1.34, one 256 wide 4.70 against 4.72 (1024: 4.66; 256: 4.92), the whole three-layer step 13.9 ms
+// instead of 13.3 (sweep of 128 .. 2048); only SpMMs 512 or more columns wide lose 1-2 %.
 int choose_chunk_nnz(int64_t nnz) {
-    if (nnz >= (1LL << 24)) return 2048;
-    if (nnz >= (1LL << 21)) return 1024;
     if (nnz >= (1LL << 19)) return 512;
     if (nnz >= (1LL << 18)) return 256;
     if (nnz >= (1LL << 17)) return 128;
