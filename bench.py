@@ -52,7 +52,7 @@ def parse_args():
     ap.add_argument("--backward", action="store_true", help="time the backward pass even with --no-sweep")
     ap.add_argument("--no-panels", action="store_true", help="do not build the column-panel copy of the graph")
     ap.add_argument("--panels", type=int, default=0, help="force the number of column panels (0 = let the library measure)")
-    ap.add_argument("--tiles", type=float, default=0.09, help="dense-tile split of the hub region: least density of a kept tile (0 = off)")
+    ap.add_argument("--tiles", type=float, default=0.07, help="dense-tile split of the hub region: least density of a kept tile (0 = off)")
     ap.add_argument("--tiles-min-width", type=int, default=64, help="narrowest SpMM (columns) that uses the dense-tile split")
     ap.add_argument("--no-gather-probe", action="store_true", help="skip the L2-resident gather probe")
     ap.add_argument("--copy-probe", action="store_true",

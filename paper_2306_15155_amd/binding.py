@@ -212,7 +212,7 @@ class Panels:
 class Tiles:
     """Dense-tile split of a pattern (sensei_tiles_create); owns the device buffer it lives in."""
 
-    def __init__(self, ctx: "Context", A: CsrStruct, min_density: float = 0.09, max_width: int = 1024, min_width: int = 64):
+    def __init__(self, ctx: "Context", A: CsrStruct, min_density: float = 0.07, max_width: int = 1024, min_width: int = 64):
         need = ctypes.c_size_t()
         _check(lib().sensei_tiles_bytes(ctypes.byref(A), min_density, max_width, ctypes.byref(need)), "sensei_tiles_bytes")
         self.buf = torch.empty(need.value + 256, dtype=torch.uint8, device=ctx.device)

@@ -186,9 +186,10 @@ struct DenseTilesArgs {
     float slope;
 };
 
-template <bool ATTN>
+template <bool ATTN, int BN>  // BN: output columns per workgroup, 128, or 64 for operands no wider than that
 __global__ __launch_bounds__(kThreads) void k_dense_tiles(DenseTilesArgs g) {
-    constexpr int BM = 128, BN = 128, WGN = 2, TM = 2, TN = 2;
+    constexpr int BM = 128, WGN = 2, TM = 2, TN = BN / 64;
+    constexpr int B_TPR = BN / 4, B_RPP = kThreads / B_TPR, B_PASSES = KT / B_RPP;  // threads per k-row, k-rows per pass
     constexpr int APAD = 36, BPAD = 36;
     __shared__ float As[KT][BM + APAD];
     __shared__ __attribute__((aligned(16))) float Bs[KT][BN + BPAD];
@@ -209,9 +210,9 @@ __global__ __launch_bounds__(kThreads) void k_dense_tiles(DenseTilesArgs g) {
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     unsigned ra[2];   // four bits each: entries (row, k .. k + 3) of the tile
-    float4 rb[2];
+    float4 rb[B_PASSES];
     const int a_row = t >> 2, a_kk = (t & 3) * 4;     // 64 rows per pass, 4 threads per row
-    const int b_row = t >> 5, b_nn = (t & 31) * 4;    // 8 k-rows per pass, 32 threads per row
+    const int b_row = t / B_TPR, b_nn = (t % B_TPR) * 4;
     const bool col_ok = n0 + b_nn < g.f;
     float sl_t[2] = {0.f, 0.f}, m_t[2] = {0.f, 0.f};
     float4 sr4 = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -232,8 +233,8 @@ __global__ __launch_bounds__(kThreads) void k_dense_tiles(DenseTilesArgs g) {
         }
         if (ATTN) sr4 = *reinterpret_cast<const float4 *>(g.sr_rank + (size_t)ct * 128 + k0 + a_kk);
 #pragma unroll
-        for (int p = 0; p < 2; ++p) {
-            const int kr = p * 8 + b_row;
+        for (int p = 0; p < B_PASSES; ++p) {
+            const int kr = p * B_RPP + b_row;
             rb[p] = col_ok ? *reinterpret_cast<const float4 *>(g.Bh + ((size_t)ct * 128 + k0 + kr) * g.ldbh + n0 + b_nn) : make_float4(0.f, 0.f, 0.f, 0.f);
         }
     };
@@ -252,7 +253,7 @@ __global__ __launch_bounds__(kThreads) void k_dense_tiles(DenseTilesArgs g) {
                 As[a_kk + e][p * 64 + a_row] = ((ra[p] >> e) & 1u) ? w : 0.f;
             }
 #pragma unroll
-        for (int p = 0; p < 2; ++p) *reinterpret_cast<float4 *>(&Bs[p * 8 + b_row][b_nn]) = rb[p];
+        for (int p = 0; p < B_PASSES; ++p) *reinterpret_cast<float4 *>(&Bs[p * B_RPP + b_row][b_nn]) = rb[p];
     };
 
     const int n_steps = (s1 - s0) * (128 / KT);
@@ -621,16 +622,19 @@ hipError_t launch_dense_tiles(const TileSplit &T, const float *B_sliced, int64_t
     DenseTilesArgs g;
     g.bits = T.bits; g.seg_first = T.seg_first; g.slot_ct = T.slot_ct;
     g.Bh = Bh; g.ldbh = f; g.part = T.part;
-    g.f = f; g.n_bn = (f + 127) / 128;
+    const bool narrow = f <= 64;
+    g.f = f; g.n_bn = narrow ? 1 : (f + 127) / 128;
     g.seg_rt = T.seg_rt; g.sl_rank = nullptr; g.m_rank = nullptr; g.sr_rank = nullptr; g.slope = slope;
     if (s_l) {
         const int n_r = T.nt_r * 128, n_c = T.nt_c * 128;
         g.sl_rank = T.rank_vec; g.m_rank = T.rank_vec + n_r; g.sr_rank = T.rank_vec + 2 * n_r;
         hipLaunchKernelGGL(k_gather_ranked_vecs, dim3((unsigned)(((n_r > n_c ? n_r : n_c) + 255) / 256)), dim3(256), 0, s, s_l, s_r, mz, T.order_r, n_r,
                            T.order_c, n_c, T.rank_vec, T.rank_vec + n_r, T.rank_vec + 2 * n_r);
-        hipLaunchKernelGGL(k_dense_tiles<true>, dim3((unsigned)(T.n_seg * g.n_bn)), dim3(kThreads), 0, s, g);
+        if (narrow) hipLaunchKernelGGL((k_dense_tiles<true, 64>), dim3((unsigned)T.n_seg), dim3(kThreads), 0, s, g);
+        else hipLaunchKernelGGL((k_dense_tiles<true, 128>), dim3((unsigned)(T.n_seg * g.n_bn)), dim3(kThreads), 0, s, g);
     } else {
-        hipLaunchKernelGGL(k_dense_tiles<false>, dim3((unsigned)(T.n_seg * g.n_bn)), dim3(kThreads), 0, s, g);
+        if (narrow) hipLaunchKernelGGL((k_dense_tiles<false, 64>), dim3((unsigned)T.n_seg), dim3(kThreads), 0, s, g);
+        else hipLaunchKernelGGL((k_dense_tiles<false, 128>), dim3((unsigned)(T.n_seg * g.n_bn)), dim3(kThreads), 0, s, g);
     }
     const long long threads = (long long)T.nt_r * 128 * (f / 4);
     hipLaunchKernelGGL(k_tiles_reduce, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, (const float *)T.part, T.rt_seg, T.nt_r, f, T.dh);
