@@ -83,6 +83,28 @@ def test_gcn_backward_with_saved_aggregate_and_strided_operands(ctx):
     assert_close(dW, want_dw, what="dW strided")
 
 
+def test_gcn_backward_on_a_dense_tile_split(ctx):
+    """The transposed aggregation of the backward pass is a value-less SpMM too: with a tile split attached to the (here
+    symmetric) pattern it takes the split path, and the gradients still match the chain rule."""
+    from paper_2306_15155_amd import Tiles, csr_struct
+    g = synth.rmat(48, 5000, 150_000)
+    f_in, f_out = 72, 96
+    X, W, dY = _inputs(g, f_in, f_out, 61)
+    Y = oracle.gcn_layer(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, 1).astype(np.float32)
+    want_dx, want_dw = oracle.gcn_backward(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, dY, Y=Y, act=ACT_RELU)
+    A = DeviceCSR(g)
+    T = Tiles(ctx, A.s, 0.05, 128, min_width=32)
+    assert T.n_tiles > 0
+    At = csr_struct(g.n_rows, g.n_cols, A.row_ptr, A.col_idx, None, None, T)
+    dr, dc = ctx.degrees(A.s)
+    r, c = ctx.norm_vectors(dr), ctx.norm_vectors(dc)
+    for bwd in (GCN_BWD_AGG, GCN_BWD_UPD):
+        dX, dW = ctx.gcn_backward(At, At, r, c, dev(X), dev(W), dev(dY), bwd, Y=dev(Y), activation=ACT_RELU)
+        assert_close(dX, want_dx, what=f"dX bwd {bwd}")
+        assert_close(dW, want_dw, what=f"dW bwd {bwd}")
+    T.close()
+
+
 def test_gcn_backward_argument_checks(ctx):
     import ctypes
     from paper_2306_15155_amd import binding
