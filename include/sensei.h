@@ -158,10 +158,13 @@ int sensei_panels_tune(sensei_ctx *ctx, const sensei_csr *A, void *scratch, size
  * forward call).  At: the transposed pattern (A itself when symmetric); t_pos: nnz int32 (device), the place of
  * each stored entry of A in At, from sensei_transpose_positions.  n_rows <= n_cols as in the forward.
  *   sensei_transpose_positions: fills t_pos; synchronises `stream`; INVALID_ARGUMENT if At is not the transpose
- *   of A (an entry of A has no counterpart).  Columns must be ascending within each row of At. */
+ *   of A (an entry of A has no counterpart).  Columns must be ascending within each row of At.
+ *   Dense-tile splits (sensei_tiles_create, below) are used where attached: one on A serves the dalpha products of the
+ *   entries inside its tiles (from F_out = 128), one on At the product alpha^T.dP.  The workspace query takes both patterns
+ *   as the layer call will get them (At may be NULL there if it carries no split). */
 int sensei_transpose_positions(sensei_ctx *ctx, const sensei_csr *A, const sensei_csr *At, int32_t *t_pos, void *workspace,
                                size_t ws_bytes, void *stream);
-int sensei_gat_backward_workspace(const sensei_csr *A, int f_in, int f_out, size_t *bytes);
+int sensei_gat_backward_workspace(const sensei_csr *A, const sensei_csr *At, int f_in, int f_out, size_t *bytes);
 int sensei_gat_backward(sensei_ctx *ctx, const sensei_csr *A, const sensei_csr *At, const int32_t *t_pos, sensei_mat X, sensei_mat W,
                         const float *a_l, const float *a_r, float neg_slope, const float *Y, int64_t ldy, sensei_mat dY, int activation,
                         float *dX, int64_t lddx, float *dW, int64_t lddw, float *da_l, float *da_r, void *workspace, size_t ws_bytes,

@@ -89,7 +89,7 @@ def lib():
                                           vp, i64, vp, i64, i32, vp, sz, vp]
         L.sensei_select_gcn_backward.argtypes = [vp, P(CsrStruct), i32, i32, i32, i32, P(ctypes.c_int), P(f32)]
         L.sensei_transpose_positions.argtypes = [vp, P(CsrStruct), P(CsrStruct), vp, vp, sz, vp]
-        L.sensei_gat_backward_workspace.argtypes = [P(CsrStruct), i32, i32, P(sz)]
+        L.sensei_gat_backward_workspace.argtypes = [P(CsrStruct), P(CsrStruct), i32, i32, P(sz)]
         L.sensei_gat_backward.argtypes = [vp, P(CsrStruct), P(CsrStruct), vp, MatStruct, MatStruct, vp, vp, f32, vp, i64, MatStruct, i32,
                                           vp, i64, vp, i64, vp, vp, vp, sz, vp]
         L.sensei_gat_workspace.argtypes = [P(CsrStruct), i32, i32, i32, P(sz)]
@@ -397,7 +397,7 @@ class Context:
         dal = torch.empty(f_out, dtype=torch.float32, device=self.device)
         dar = torch.empty(f_out, dtype=torch.float32, device=self.device)
         need = ctypes.c_size_t()
-        _check(lib().sensei_gat_backward_workspace(ctypes.byref(A), f_in, f_out, ctypes.byref(need)), "sensei_gat_backward_workspace")
+        _check(lib().sensei_gat_backward_workspace(ctypes.byref(A), ctypes.byref(At), f_in, f_out, ctypes.byref(need)), "sensei_gat_backward_workspace")
         self.ws.ensure(need.value)
         _check(lib().sensei_gat_backward(self._h, ctypes.byref(A), ctypes.byref(At), _ptr(t_pos), mat_struct(X), mat_struct(W), _ptr(a_l),
                                          _ptr(a_r), neg_slope, _ptr(Y), mat_struct(Y).ld if Y is not None else 0, mat_struct(dY), activation,

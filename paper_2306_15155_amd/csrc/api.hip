@@ -621,7 +621,25 @@ int run_gatv2(const sensei_csr &A, const sensei_mat &X, const sensei_mat &Wl, co
 }
 
 // ---- backward of the GAT layer
-size_t gat_bwd_ws(const sensei_csr &A, int f_in, int f_out) {
+// The per-entry dot products of the attention backward can use the dense-tile split of A: same pattern, wide enough, and
+// every tile cell addressable by the (negative) codes in dst_rem.  Below 128 columns the extra pass that merges the two
+// sources costs more than the matrix cores save.
+constexpr int kDalphaTilesMinWidth = 128;
+bool tiles_serve_dalpha(const sensei_csr &A, int f_out) {
+    const sensei_tiles *D = A.tiles;
+    if (!D || D->T.n_slots <= 0 || D->T.n_slots > kMaxCellSlots || f_out < kDalphaTilesMinWidth) return false;
+    return D->n_rows == A.n_rows && D->n_cols == A.n_cols && D->nnz == A.nnz && D->src_row_ptr == A.row_ptr && D->src_col_idx == A.col_idx;
+}
+
+// alpha^T . dP of the attention backward can use a dense-tile split of the transposed pattern: the coefficients of the entries inside
+// kept tiles are formed on the fly from s_l, s_r and the row statistics, the others are copied into the order of the remainder.
+bool tiles_serve_transposed(const sensei_csr &At, int f_out) {
+    const sensei_tiles *D = At.tiles;
+    if (!D || D->T.n_slots <= 0 || pad32(f_out) > D->max_width || f_out < D->min_width) return false;
+    return D->n_rows == At.n_rows && D->n_cols == At.n_cols && D->nnz == At.nnz && D->src_row_ptr == At.row_ptr && D->src_col_idx == At.col_idx;
+}
+
+size_t gat_bwd_ws(const sensei_csr &A, const sensei_csr *At, int f_in, int f_out) {
     const size_t nz = (size_t)(A.nnz > 0 ? A.nnz : 1), fo32 = pad32(f_out), fo4 = pad4(f_out), fi4 = pad4(f_in);
     const int t = choose_chunk_nnz(A.nnz);
     const size_t n_chunks = A.nnz <= 0 ? 1 : (size_t)((A.nnz + t - 1) / t);
@@ -637,6 +655,13 @@ size_t gat_bwd_ws(const sensei_csr &A, int f_in, int f_out) {
     b += spmm_carry_bytes(A.nnz, (int)fo32);
     b += align_up(fo4 * fi4 * sizeof(float), 256);                   // W^T
     b += gemm_tn_bytes(A.n_cols, f_in, f_out) + theta_t_vec_bytes(A.n_cols, f_out);
+    if (tiles_serve_dalpha(A, f_out)) {  // dense-tile split: the tiles' dot products, the two operands in rank order, the remainder's dalpha
+        const sensei_tiles &D = *A.tiles;
+        b += align_up((size_t)D.T.n_slots * 128 * 128 * sizeof(float), 256);
+        b += align_up((size_t)D.T.nt_r * 128 * fo32 * sizeof(float), 256) + align_up((size_t)D.T.nt_c * 128 * fo32 * sizeof(float), 256);
+        b += align_up((size_t)(D.nnz_rem > 0 ? D.nnz_rem : 1) * sizeof(float), 256);
+    }
+    if (At && tiles_serve_transposed(*At, f_out)) b += align_up((size_t)(At->tiles->nnz_rem > 0 ? At->tiles->nnz_rem : 1) * sizeof(float), 256);
     return b;
 }
 
@@ -676,16 +701,62 @@ int run_gat_backward(const sensei_csr &A, const sensei_csr &At, const int32_t *t
     // dP = dY (.) [Y > 0], slice-major
     SENSEI_TRY(launch_to_slices(nullptr, dY.ptr, dY.ld, A.n_rows, f_out, T, s, act == SENSEI_ACT_RELU ? Y : nullptr, ldy));
     // per stored entry: dalpha, then softmax and LeakyReLU backward; alpha and dt also in transposed order
-    SENSEI_TRY(launch_gat_dalpha(A, theta, T, f_out, logits, stats, dt, rowdot, plan, sum_carry, s));
+    // With a tile split on the transposed pattern, the tiles' share of alpha^T . dP needs only s_l, s_r, the row statistics and dP, all
+    // known by now: it runs on that split's own stream beside the per-entry work below and is joined where dTheta is put together.
+    const bool split_t = tiles_serve_transposed(At, f_out);
+    auto fork_transposed_tiles = [&]() -> hipError_t {
+        const sensei_tiles &D = *At.tiles;
+        hipError_t e = hipEventRecord(D.ev_fork, s);
+        if (e == hipSuccess) e = hipStreamWaitEvent(D.side, D.ev_fork, 0);
+        if (e == hipSuccess) e = launch_dense_tiles(D.T, T, At.n_cols, fo32, D.Bh, D.side, s_l, s_r, stats, slope, true);
+        if (e == hipSuccess) e = hipEventRecord(D.ev_join, D.side);
+        return e;
+    };
+    if (tiles_serve_dalpha(A, f_out)) {
+        // entries inside kept tiles: one 128 x 128 x F product per tile on the matrix cores, on the split's own stream; the rest: the
+        // slice-by-slice kernel over the remainder on this stream; then one pass puts both in the order of the pattern and forms the
+        // row sums
+        const sensei_tiles &D = *A.tiles;
+        float *Dt = cv.take<float>((size_t)D.T.n_slots * 128 * 128);
+        float *Lh = cv.take<float>((size_t)D.T.nt_r * 128 * fo32);
+        float *Rh = cv.take<float>((size_t)D.T.nt_c * 128 * fo32);
+        float *dalpha_rem = cv.take<float>((size_t)(D.nnz_rem > 0 ? D.nnz_rem : 1));
+        SENSEI_TRY(hipEventRecord(D.ev_fork, s));
+        SENSEI_TRY(hipStreamWaitEvent(D.side, D.ev_fork, 0));
+        SENSEI_TRY(launch_tiles_sddmm(D.T, T, A.n_rows, theta, A.n_cols, fo32, Lh, Rh, Dt, D.side));
+        SENSEI_TRY(hipEventRecord(D.ev_join, D.side));
+        sensei_csr Ar = A;
+        Ar.nnz = D.nnz_rem; Ar.row_ptr = D.row_ptr_rem; Ar.col_idx = D.col_rem; Ar.panels = nullptr; Ar.tiles = nullptr;
+        SENSEI_TRY(launch_gat_dalpha(Ar, theta, T, f_out, nullptr, nullptr, dalpha_rem, nullptr, D.plan_rem, sum_carry, s));
+        SENSEI_TRY(hipStreamWaitEvent(s, D.ev_join, 0));
+        if (split_t) SENSEI_TRY(fork_transposed_tiles());  // the side stream goes on while this one merges
+        SENSEI_TRY(launch_gat_dalpha_merge(A, D.dst_rem, dalpha_rem, Dt, logits, stats, dt, rowdot, plan, sum_carry, s));
+    } else {
+        if (split_t) SENSEI_TRY(fork_transposed_tiles());
+        SENSEI_TRY(launch_gat_dalpha(A, theta, T, f_out, logits, stats, dt, rowdot, plan, sum_carry, s));
+    }
     SENSEI_TRY(launch_gat_dt(A, logits, dt, rowdot, stats, t_pos, slope, dt, adt_t, plan, s));
     SENSEI_TRY(launch_row_sum(A, dt, 1, ds_l, plan, sum_carry, s));
     SENSEI_TRY(launch_row_sum(At, reinterpret_cast<const float *>(adt_t) + 1, 2, ds_r, plan_t, sum_carry, s));
     // dTheta = alpha^T.dP + ds_l a_l^T + ds_r a_r^T
-    sensei_csr Aw = At;
-    Aw.val = reinterpret_cast<const float *>(adt_t);
-    Aw.panels = nullptr;  // the values follow the order of At itself
-    SENSEI_TRY(launch_spmm(Aw, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, T, fo32, f_out, dTheta, fo4, f_out, SENSEI_ACT_NONE, plan_t, carry, s, nullptr,
-                           false, true, nullptr, true, 2));
+    if (split_t) {
+        // the remainder of the transposed pattern with its coefficients copied into its own order; the tiles' share was started above
+        const sensei_tiles &D = *At.tiles;
+        float *alpha_rem = cv.take<float>((size_t)(D.nnz_rem > 0 ? D.nnz_rem : 1));
+        SENSEI_TRY(launch_compact_values(At.nnz, D.dst_rem, reinterpret_cast<const float *>(adt_t), 2, alpha_rem, s));
+        sensei_csr Ar = At;
+        Ar.nnz = D.nnz_rem; Ar.row_ptr = D.row_ptr_rem; Ar.col_idx = D.col_rem; Ar.val = alpha_rem; Ar.panels = nullptr; Ar.tiles = nullptr;
+        SENSEI_TRY(launch_spmm(Ar, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, T, fo32, f_out, dTheta, fo4, f_out, SENSEI_ACT_NONE, D.plan_rem, carry, s,
+                               nullptr, false, false, nullptr, true, 1));
+        SENSEI_TRY(hipStreamWaitEvent(s, D.ev_join, 0));
+        SENSEI_TRY(launch_tiles_combine(D.T, dTheta, At.n_rows, f_out, fo4, false, fo32, nullptr, nullptr, SENSEI_ACT_NONE, s));
+    } else {
+        sensei_csr Aw = At;
+        Aw.val = reinterpret_cast<const float *>(adt_t);
+        Aw.panels = nullptr;  // the values follow the order of At itself
+        SENSEI_TRY(launch_spmm(Aw, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, T, fo32, f_out, dTheta, fo4, f_out, SENSEI_ACT_NONE, plan_t, carry, s, nullptr,
+                               false, true, nullptr, true, 2));
+    }
     SENSEI_TRY(launch_rank1_add(dTheta, fo4, A.n_cols, f_out, ds_l, A.n_rows, ds_r, a_l, a_r, s));
     SENSEI_TRY(launch_theta_t_vec(theta, A.n_cols, f_out, ds_l, A.n_rows, ds_r, da_l, da_r, part_a, s));
     SENSEI_TRY(launch_gemm_tn(X.ptr, X.ld, dTheta, fo4, A.n_cols, f_in, f_out, dW, lddw, part, s));
@@ -1144,7 +1215,7 @@ constexpr int kTileRanksMax = 65536;  // ranks per side that are examined for de
 
 struct TilesLayout {
     int h_r, h_c, nt_r, nt_c, n_tiles, max_slots, min_count;
-    size_t rank_r, rank_c, order_r, order_c, hist, sel_scan, slot_of, slot_ct, rt_ptr, scan_small, plan, bits, pos, scan_large, col_rem,
+    size_t rank_r, rank_c, order_r, order_c, hist, sel_scan, slot_of, slot_ct, slot_rt, rt_ptr, scan_small, plan, bits, pos, scan_large, col_rem,
         dst_rem, row_ptr_rem, plan_rem, bh, seg_first, rt_seg, seg_rt, rank_vec, part, dh, total;
     int max_seg;
 };
@@ -1170,6 +1241,7 @@ TilesLayout tiles_layout(const sensei_csr &A, float min_density, int max_width) 
     L.sel_scan = put(((size_t)L.n_tiles + 1) * 4);
     L.slot_of = put((size_t)L.n_tiles * 4);
     L.slot_ct = put((size_t)L.n_tiles * 4);
+    L.slot_rt = put((size_t)L.n_tiles * 4);
     L.rt_ptr = put(((size_t)L.nt_r + 1) * 4);
     L.scan_small = put(scan_temp_bytes(L.n_tiles + 1));
     L.plan = put(plan_bytes(A.nnz));
@@ -1185,7 +1257,7 @@ TilesLayout tiles_layout(const sensei_csr &A, float min_density, int max_width) 
     L.seg_first = put(((size_t)L.max_seg + 1) * 4);
     L.rt_seg = put(((size_t)L.nt_r + 1) * 4);
     L.seg_rt = put(((size_t)L.max_seg + 1) * 4);
-    L.rank_vec = put(((size_t)2 * L.nt_r + L.nt_c) * 128 * 4);
+    L.rank_vec = put((size_t)2 * (L.nt_r + L.nt_c) * 128 * 4);
     L.part = put((size_t)L.max_seg * 128 * max_width * 4);
     L.dh = put((size_t)L.nt_r * 128 * max_width * 4);
     L.total = off;
@@ -1242,7 +1314,7 @@ int sensei_tiles_create(sensei_ctx *ctx, const sensei_csr *A, float min_density,
     D->T.nt_r = L.nt_r; D->T.nt_c = L.nt_c; D->T.n_slots = 0; D->T.n_seg = 0;
     D->T.seg_first = nullptr; D->T.rt_seg = nullptr; D->T.seg_rt = nullptr; D->T.part = nullptr; D->T.rank_vec = nullptr;
     D->T.dh = nullptr; D->T.rank_r = nullptr;
-    D->T.order_r = at(L.order_r); D->T.order_c = at(L.order_c); D->T.rt_ptr = at(L.rt_ptr); D->T.slot_ct = at(L.slot_ct);
+    D->T.order_r = at(L.order_r); D->T.order_c = at(L.order_c); D->T.rt_ptr = at(L.rt_ptr); D->T.slot_ct = at(L.slot_ct); D->T.slot_rt = at(L.slot_rt);
     D->T.bits = reinterpret_cast<unsigned *>(base + L.bits);
     D->nnz_rem = A->nnz; D->row_ptr_rem = at(L.row_ptr_rem); D->col_rem = at(L.col_rem); D->dst_rem = at(L.dst_rem);
     if (A->n_rows == 0 || A->n_cols == 0 || A->nnz == 0) { *out = D; return SENSEI_OK; }  // nothing to split: never used
@@ -1271,7 +1343,7 @@ int sensei_tiles_create(sensei_ctx *ctx, const sensei_csr *A, float min_density,
     plan.chunk_row = at(L.plan);
     if (launch_chunk_rows(*A, plan, s) != hipSuccess) return fail(SENSEI_HIP_ERROR);
     if (launch_tile_select(*A, plan, at(L.rank_r), at(L.rank_c), L.h_r, L.h_c, L.nt_r, L.nt_c, L.min_count, at(L.hist), at(L.sel_scan), at(L.slot_of),
-                           at(L.slot_ct), at(L.rt_ptr), at(L.scan_small), s) != hipSuccess)
+                           at(L.slot_ct), at(L.slot_rt), at(L.rt_ptr), at(L.scan_small), s) != hipSuccess)
         return fail(SENSEI_HIP_ERROR);
     int32_t n_slots = 0;
     if (hipMemcpyAsync(&n_slots, at(L.sel_scan) + L.n_tiles, 4, hipMemcpyDeviceToHost, s) != hipSuccess || hipStreamSynchronize(s) != hipSuccess)
@@ -1604,9 +1676,9 @@ int sensei_transpose_positions(sensei_ctx *ctx, const sensei_csr *A, const sense
     return miss_host == 0 ? SENSEI_OK : SENSEI_INVALID_ARGUMENT;
 }
 
-int sensei_gat_backward_workspace(const sensei_csr *A, int f_in, int f_out, size_t *bytes) {
-    if (!csr_ok(A, false) || f_in <= 0 || f_out <= 0 || !bytes) return SENSEI_INVALID_ARGUMENT;
-    *bytes = gat_bwd_ws(*A, f_in, f_out);
+int sensei_gat_backward_workspace(const sensei_csr *A, const sensei_csr *At, int f_in, int f_out, size_t *bytes) {
+    if (!csr_ok(A, false) || (At && !csr_ok(At, false)) || f_in <= 0 || f_out <= 0 || !bytes) return SENSEI_INVALID_ARGUMENT;
+    *bytes = gat_bwd_ws(*A, At, f_in, f_out);
     return SENSEI_OK;
 }
 
@@ -1633,7 +1705,7 @@ int sensei_gat_backward(sensei_ctx *ctx, const sensei_csr *A, const sensei_csr *
     if (dX && (overlap(dX, dxb, workspace, ws_bytes) || overlap(dX, dxb, X.ptr, xb) || overlap(dX, dxb, W.ptr, wb) ||
                overlap(dX, dxb, dY.ptr, dyb) || overlap(dX, dxb, dW, dwb)))
         return SENSEI_INVALID_ARGUMENT;
-    if (ws_bytes < gat_bwd_ws(*A, (int)X.cols, (int)W.cols)) return SENSEI_WORKSPACE_TOO_SMALL;
+    if (ws_bytes < gat_bwd_ws(*A, At, (int)X.cols, (int)W.cols)) return SENSEI_WORKSPACE_TOO_SMALL;
     return run_gat_backward(*A, *At, t_pos, X, W, a_l, a_r, neg_slope, Y, ldy, dY, activation, dX, lddx, dW, lddw, da_l, da_r, workspace,
                             ws_bytes, as_stream(stream));
 }

@@ -180,14 +180,19 @@ struct DenseTilesArgs {
     float *part;                           // n_seg x 128 x f
     long long ldbh;
     int f, n_bn;
-    // attention mode: entry (i, j) of a tile weighs exp(LeakyReLU(s_l[i] + s_r[j]) - max_i), as the softmax mode of the SpMM does
+    // attention modes: entry (i, j) of a tile weighs exp(LeakyReLU(u[i] + v[j]) - shift), as the softmax mode of the SpMM does.
+    // kTilesAttn: u = s_l, v = s_r, shift = the maximum of row i (tiles of the pattern itself).  kTilesAttnT: the tiles are those of
+    // the transposed pattern, so the softmax row is the tile's column: u = s_r, v = s_l, shift = the maximum of column j.
     const int32_t *seg_rt;                 // row of tiles of each segment
-    const float *sl_rank, *m_rank, *sr_rank;  // s_l and the row maximum by row rank, s_r by column rank
+    const float *sl_rank, *m_rank, *sr_rank;  // u and (kTilesAttn) the shift by row rank; v by column rank
+    const float *mc_rank;                  // kTilesAttnT: the shift by column rank
     float slope;
 };
+constexpr int kTilesPlain = 0, kTilesAttn = 1, kTilesAttnT = 2;
 
-template <bool ATTN, int BN>  // BN: output columns per workgroup, 128, or 64 for operands no wider than that
+template <int MODE, int BN>  // BN: output columns per workgroup, 128, or 64 for operands no wider than that
 __global__ __launch_bounds__(kThreads) void k_dense_tiles(DenseTilesArgs g) {
+    constexpr bool ATTN = MODE != kTilesPlain;
     constexpr int BM = 128, WGN = 2, TM = 2, TN = BN / 64;
     constexpr int B_TPR = BN / 4, B_RPP = kThreads / B_TPR, B_PASSES = KT / B_RPP;  // threads per k-row, k-rows per pass
     constexpr int APAD = 36, BPAD = 36;
@@ -215,13 +220,13 @@ __global__ __launch_bounds__(kThreads) void k_dense_tiles(DenseTilesArgs g) {
     const int b_row = t / B_TPR, b_nn = (t % B_TPR) * 4;
     const bool col_ok = n0 + b_nn < g.f;
     float sl_t[2] = {0.f, 0.f}, m_t[2] = {0.f, 0.f};
-    float4 sr4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    float4 sr4 = make_float4(0.f, 0.f, 0.f, 0.f), mc4 = make_float4(0.f, 0.f, 0.f, 0.f);
     if (ATTN) {
         const int rt = g.seg_rt[seg];
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
             sl_t[p] = g.sl_rank[rt * 128 + p * 64 + a_row];
-            m_t[p] = g.m_rank[rt * 128 + p * 64 + a_row];
+            if (MODE == kTilesAttn) m_t[p] = g.m_rank[rt * 128 + p * 64 + a_row];
         }
     }
 
@@ -232,6 +237,7 @@ __global__ __launch_bounds__(kThreads) void k_dense_tiles(DenseTilesArgs g) {
             ra[p] = (g.bits[((size_t)slot * 128 + row) * 4 + (kk >> 5)] >> (kk & 31)) & 15u;
         }
         if (ATTN) sr4 = *reinterpret_cast<const float4 *>(g.sr_rank + (size_t)ct * 128 + k0 + a_kk);
+        if (MODE == kTilesAttnT) mc4 = *reinterpret_cast<const float4 *>(g.mc_rank + (size_t)ct * 128 + k0 + a_kk);
 #pragma unroll
         for (int p = 0; p < B_PASSES; ++p) {
             const int kr = p * B_RPP + b_row;
@@ -248,7 +254,8 @@ __global__ __launch_bounds__(kThreads) void k_dense_tiles(DenseTilesArgs g) {
                     const float srv = e == 0 ? sr4.x : e == 1 ? sr4.y : e == 2 ? sr4.z : sr4.w;
                     float tt = sl_t[p] + srv;
                     tt = tt > 0.f ? tt : g.slope * tt;
-                    w = __expf(tt - m_t[p]);
+                    const float shift = MODE == kTilesAttn ? m_t[p] : e == 0 ? mc4.x : e == 1 ? mc4.y : e == 2 ? mc4.z : mc4.w;
+                    w = __expf(tt - shift);
                 }
                 As[a_kk + e][p * 64 + a_row] = ((ra[p] >> e) & 1u) ? w : 0.f;
             }
@@ -343,6 +350,85 @@ __global__ void k_tiles_combine(float *__restrict__ C, long long n_rows, int f_s
     }
 }
 
+// Dt[slot] = Lh[rows of the slot's row tile] . Rh[rows of its column tile]^T, 128 x 128 per kept tile: the per-entry dot product
+// <dP_i, Theta_j> of the attention backward for all entries of a tile at once, on the matrix cores (the cells outside the tile's
+// bit mask are computed too and never read).  Both operands are rows with k contiguous, so both go through the transposing
+// stash the GEMM uses for its left operand.
+__global__ __launch_bounds__(kThreads) void k_tiles_sddmm(const float *__restrict__ Lh, const float *__restrict__ Rh, int f,
+                                                           const int32_t *__restrict__ slot_rt, const int32_t *__restrict__ slot_ct,
+                                                           float *__restrict__ Dt) {
+    constexpr int BM = 128, BN = 128, WGN = 2, TM = 2, TN = 2, PAD = 36;
+    __shared__ float As[KT][BM + PAD];
+    __shared__ float Bs[KT][BN + PAD];
+    const int slot = blockIdx.x;
+    const int t = threadIdx.x;
+    const int wave = t >> 6, lane = t & 63;
+    const int wm = wave / WGN, wn = wave % WGN;
+    const float *Lt = Lh + (size_t)slot_rt[slot] * 128 * f;
+    const float *Rt = Rh + (size_t)slot_ct[slot] * 128 * f;
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    float4 ra[2], rb[2];
+    const int a_row = t >> 2, a_kk = (t & 3) * 4;  // 64 rows per pass, 4 threads (16 k) per row
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            ra[p] = *reinterpret_cast<const float4 *>(Lt + (size_t)(p * 64 + a_row) * f + k0 + a_kk);
+            rb[p] = *reinterpret_cast<const float4 *>(Rt + (size_t)(p * 64 + a_row) * f + k0 + a_kk);
+        }
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            const float va[4] = {ra[p].x, ra[p].y, ra[p].z, ra[p].w}, vb[4] = {rb[p].x, rb[p].y, rb[p].z, rb[p].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                As[a_kk + e][p * 64 + a_row] = va[e];
+                Bs[a_kk + e][p * 64 + a_row] = vb[e];
+            }
+        }
+    };
+    const int n_kt = f / KT;  // f is a multiple of 32
+    fetch(0);
+    for (int kt = 0; kt < n_kt; ++kt) {
+        stash();
+        __syncthreads();
+        if (kt + 1 < n_kt) fetch((kt + 1) * KT);
+        const int kh = lane >> 5, ll = lane & 31;
+#pragma unroll
+        for (int kk = 0; kk < KT; kk += 2) {
+            float av[TM], bv[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) av[i] = As[kk + kh][(wm * TM + i) * 32 + ll];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) bv[j] = Bs[kk + kh][(wn * TN + j) * 32 + ll];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+    const int kh = lane >> 5, ll = lane & 31;
+    float *out = Dt + (size_t)slot * 128 * 128;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = (wm * TM + i) * 32 + 8 * (r / 4) + 4 * kh + (r % 4);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) out[(size_t)row * 128 + (wn * TN + j) * 32 + ll] = acc[i][j][r];
+        }
+}
+
 // the attention vectors in rank order (zeros where a rank has no node)
 __global__ void k_gather_ranked_vecs(const float *__restrict__ s_l, const float *__restrict__ s_r, const float2 *__restrict__ mz,
                                      const int32_t *__restrict__ order_r, int n_r, const int32_t *__restrict__ order_c, int n_c,
@@ -359,9 +445,25 @@ __global__ void k_gather_ranked_vecs(const float *__restrict__ s_l, const float 
     }
 }
 
-// Bh[q, 0:f) = row order_c[q] of the slice-major matrix B (zeros where the rank has no node)
+// the same for the tiles of the transposed pattern: its rows are the sources (s_r), its columns the destinations (s_l and their maxima)
+__global__ void k_gather_ranked_vecs_t(const float *__restrict__ s_l, const float *__restrict__ s_r, const float2 *__restrict__ mz,
+                                       const int32_t *__restrict__ order_r, int n_r, const int32_t *__restrict__ order_c, int n_c,
+                                       float *__restrict__ sr_rank, float *__restrict__ sl_rank, float *__restrict__ m_rank) {
+    const int q = blockIdx.x * blockDim.x + threadIdx.x;
+    if (q < n_r) {
+        const int j = order_r[q];
+        sr_rank[q] = j >= 0 ? s_r[j] : 0.f;
+    }
+    if (q < n_c) {
+        const int i = order_c[q];
+        sl_rank[q] = i >= 0 ? s_l[i] : 0.f;
+        m_rank[q] = i >= 0 ? mz[i].x : 0.f;
+    }
+}
+
+// Bh[q, 0:f) = row order_c[q] of the slice-major matrix B (zeros where the rank has no node), times 1 / mz[node].y if mz is given
 __global__ void k_gather_ranked_rows(const float *__restrict__ B, long long n_cols, int f, const int32_t *__restrict__ order_c, long long n_ranks,
-                                     float *__restrict__ Bh) {
+                                     float *__restrict__ Bh, const float2 *__restrict__ mz) {
     const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     const int f4 = f / 4;
     if (t >= n_ranks * f4) return;
@@ -370,6 +472,10 @@ __global__ void k_gather_ranked_rows(const float *__restrict__ B, long long n_co
     const int j = order_c[q];
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
     if (j >= 0) v = *reinterpret_cast<const float4 *>(B + (long long)(col >> 5) * n_cols * 32 + (long long)j * 32 + (col & 31));
+    if (mz && j >= 0) {
+        const float z = mz[j].y, iz = z > 0.f ? 1.f / z : 0.f;
+        v.x *= iz; v.y *= iz; v.z *= iz; v.w *= iz;
+    }
     *reinterpret_cast<float4 *>(Bh + q * f + col) = v;
 }
 
@@ -614,30 +720,50 @@ hipError_t launch_gemm(const float *A, int64_t lda, const float *W, int64_t ldw,
 }
 
 hipError_t launch_dense_tiles(const TileSplit &T, const float *B_sliced, int64_t n_cols, int f, float *Bh, hipStream_t s, const float *s_l,
-                              const float *s_r, const float2 *mz, float slope) {
+                              const float *s_r, const float2 *mz, float slope, bool transposed) {
     if (T.n_slots <= 0 || f <= 0) return hipSuccess;
     const long long n_ranks = (long long)T.nt_c * 128;
     hipLaunchKernelGGL(k_gather_ranked_rows, dim3((unsigned)((n_ranks * (f / 4) + 255) / 256)), dim3(256), 0, s, B_sliced, (long long)n_cols, f,
-                       T.order_c, n_ranks, Bh);
+                       T.order_c, n_ranks, Bh, transposed ? mz : (const float2 *)nullptr);
     DenseTilesArgs g;
     g.bits = T.bits; g.seg_first = T.seg_first; g.slot_ct = T.slot_ct;
     g.Bh = Bh; g.ldbh = f; g.part = T.part;
     const bool narrow = f <= 64;
     g.f = f; g.n_bn = narrow ? 1 : (f + 127) / 128;
-    g.seg_rt = T.seg_rt; g.sl_rank = nullptr; g.m_rank = nullptr; g.sr_rank = nullptr; g.slope = slope;
+    g.seg_rt = T.seg_rt; g.sl_rank = nullptr; g.m_rank = nullptr; g.sr_rank = nullptr; g.mc_rank = nullptr; g.slope = slope;
+    const dim3 grid((unsigned)(narrow ? T.n_seg : T.n_seg * g.n_bn));
     if (s_l) {
         const int n_r = T.nt_r * 128, n_c = T.nt_c * 128;
-        g.sl_rank = T.rank_vec; g.m_rank = T.rank_vec + n_r; g.sr_rank = T.rank_vec + 2 * n_r;
-        hipLaunchKernelGGL(k_gather_ranked_vecs, dim3((unsigned)(((n_r > n_c ? n_r : n_c) + 255) / 256)), dim3(256), 0, s, s_l, s_r, mz, T.order_r, n_r,
-                           T.order_c, n_c, T.rank_vec, T.rank_vec + n_r, T.rank_vec + 2 * n_r);
-        if (narrow) hipLaunchKernelGGL((k_dense_tiles<true, 64>), dim3((unsigned)T.n_seg), dim3(kThreads), 0, s, g);
-        else hipLaunchKernelGGL((k_dense_tiles<true, 128>), dim3((unsigned)(T.n_seg * g.n_bn)), dim3(kThreads), 0, s, g);
+        const dim3 vgrid((unsigned)(((n_r > n_c ? n_r : n_c) + 255) / 256));
+        if (transposed) {
+            g.sl_rank = T.rank_vec; g.sr_rank = T.rank_vec + n_r; g.mc_rank = T.rank_vec + n_r + n_c;
+            hipLaunchKernelGGL(k_gather_ranked_vecs_t, vgrid, dim3(256), 0, s, s_l, s_r, mz, T.order_r, n_r, T.order_c, n_c, T.rank_vec,
+                               T.rank_vec + n_r, T.rank_vec + n_r + n_c);
+            if (narrow) hipLaunchKernelGGL((k_dense_tiles<kTilesAttnT, 64>), grid, dim3(kThreads), 0, s, g);
+            else hipLaunchKernelGGL((k_dense_tiles<kTilesAttnT, 128>), grid, dim3(kThreads), 0, s, g);
+        } else {
+            g.sl_rank = T.rank_vec; g.m_rank = T.rank_vec + n_r; g.sr_rank = T.rank_vec + 2 * n_r;
+            hipLaunchKernelGGL(k_gather_ranked_vecs, vgrid, dim3(256), 0, s, s_l, s_r, mz, T.order_r, n_r, T.order_c, n_c, T.rank_vec,
+                               T.rank_vec + n_r, T.rank_vec + 2 * n_r);
+            if (narrow) hipLaunchKernelGGL((k_dense_tiles<kTilesAttn, 64>), grid, dim3(kThreads), 0, s, g);
+            else hipLaunchKernelGGL((k_dense_tiles<kTilesAttn, 128>), grid, dim3(kThreads), 0, s, g);
+        }
     } else {
-        if (narrow) hipLaunchKernelGGL((k_dense_tiles<false, 64>), dim3((unsigned)T.n_seg), dim3(kThreads), 0, s, g);
-        else hipLaunchKernelGGL((k_dense_tiles<false, 128>), dim3((unsigned)(T.n_seg * g.n_bn)), dim3(kThreads), 0, s, g);
+        if (narrow) hipLaunchKernelGGL((k_dense_tiles<kTilesPlain, 64>), grid, dim3(kThreads), 0, s, g);
+        else hipLaunchKernelGGL((k_dense_tiles<kTilesPlain, 128>), grid, dim3(kThreads), 0, s, g);
     }
     const long long threads = (long long)T.nt_r * 128 * (f / 4);
     hipLaunchKernelGGL(k_tiles_reduce, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, (const float *)T.part, T.rt_seg, T.nt_r, f, T.dh);
+    return hipGetLastError();
+}
+
+hipError_t launch_tiles_sddmm(const TileSplit &T, const float *L_sliced, int64_t n_rows, const float *R_sliced, int64_t n_cols, int f, float *Lh,
+                              float *Rh, float *Dt, hipStream_t s) {
+    if (T.n_slots <= 0 || f <= 0) return hipSuccess;
+    const long long nr = (long long)T.nt_r * 128, nc = (long long)T.nt_c * 128;
+    hipLaunchKernelGGL(k_gather_ranked_rows, dim3((unsigned)((nr * (f / 4) + 255) / 256)), dim3(256), 0, s, L_sliced, (long long)n_rows, f, T.order_r, nr, Lh, (const float2 *)nullptr);
+    hipLaunchKernelGGL(k_gather_ranked_rows, dim3((unsigned)((nc * (f / 4) + 255) / 256)), dim3(256), 0, s, R_sliced, (long long)n_cols, f, T.order_c, nc, Rh, (const float2 *)nullptr);
+    hipLaunchKernelGGL(k_tiles_sddmm, dim3((unsigned)T.n_slots), dim3(kThreads), 0, s, (const float *)Lh, (const float *)Rh, f, T.slot_rt, T.slot_ct, Dt);
     return hipGetLastError();
 }
 

@@ -109,9 +109,12 @@ size_t softmax_ws_bytes(const sensei_csr &A);
 // ---- backward of the attention layer
 // out[i] = sum of val[k * stride] over the entries k of row i; carry: n_chunks floats
 hipError_t launch_row_sum(const sensei_csr &A, const float *val, int stride, float *out, const ChunkPlan &p, float *carry, hipStream_t s);
-// dalpha[k] = <dP[i,:], Theta[j,:]> per stored entry, rowdot[i] = sum_j alpha_ij dalpha_ij; theta, dP slice-major
+// dalpha[k] = <dP[i,:], Theta[j,:]> per stored entry, rowdot[i] = sum_j alpha_ij dalpha_ij (skipped when rowdot is null); theta, dP slice-major
 hipError_t launch_gat_dalpha(const sensei_csr &A, const float *theta, const float *dP, int f, const float *logits, const float2 *mz,
                              float *dalpha, float *rowdot, const ChunkPlan &p, float *carry, hipStream_t s);
+// dense-tile split: dalpha[k] from the remainder's values (where[k] >= 0) or the cells of the tiles' product Dt (where[k] < 0), and rowdot
+hipError_t launch_gat_dalpha_merge(const sensei_csr &A, const int32_t *where, const float *dalpha_rem, const float *Dt, const float *logits,
+                                   const float2 *mz, float *dalpha, float *rowdot, const ChunkPlan &p, float *carry, hipStream_t s);
 // dt[k] = alpha (dalpha - rowdot_i) LeakyReLU'(e); dt may be dalpha; adt_t[t_pos[k]] = (alpha, dt)
 hipError_t launch_gat_dt(const sensei_csr &A, const float *logits, const float *dalpha, const float *rowdot, const float2 *mz,
                          const int32_t *t_pos, float slope, float *dt, float2 *adt_t, const ChunkPlan &p, hipStream_t s);
@@ -142,34 +145,47 @@ struct TileSplit {
     int n_slots;                       // kept tiles
     const int32_t *order_r, *order_c;  // device, nt * 128: node at rank, -1 beyond the last node
     const int32_t *rt_ptr, *slot_ct;   // device: first slot of each row of tiles (nt_r + 1), column tile of each slot
+    const int32_t *slot_rt;            // device: row of tiles of each slot
     const unsigned *bits;              // device: n_slots x 128 x 4 words
     int n_seg;                         // segments of at most kTilesPerSegment consecutive slots of one row of tiles
     const int32_t *seg_first, *rt_seg; // device: first slot of each segment (n_seg + 1); first segment of each row of tiles (nt_r + 1)
     const int32_t *seg_rt;             // device: row of tiles of each segment
     float *part;                       // device: n_seg x 128 x (widest operand) partial products
-    float *rank_vec;                   // device: 2 * nt_r * 128 + nt_c * 128 floats for the attention vectors in rank order
+    float *rank_vec;                   // device: 2 * (nt_r + nt_c) * 128 floats for the attention vectors in rank order
     float *dh;                         // device: nt_r * 128 x (widest operand): the tiles' product, by row rank
     const int32_t *rank_r;             // device: rank of every row node (INT_MAX outside the tiled region)
 };
 constexpr int kTilesPerSegment = 8;
+constexpr int kMaxCellSlots = 131071;  // slots whose cells (slot * 16384 + ...) + 1 still fit a positive int32
 size_t scan_large_temp_bytes(long long n);
 hipError_t launch_exclusive_scan_large(int32_t *data, long long n, int32_t *temp, hipStream_t s);
 // histogram of the entries per tile, choice of the tiles with at least min_count entries, slot tables; sel_scan: n_tiles + 1 ints
 // (its last element is the number of kept tiles), scan_temp: scan_temp_bytes(n_tiles + 1)
 hipError_t launch_tile_select(const sensei_csr &A, const ChunkPlan &p, const int32_t *rank_r, const int32_t *rank_c, int h_r, int h_c,
                               int nt_r, int nt_c, int min_count, int32_t *hist, int32_t *sel_scan, int32_t *slot_of, int32_t *slot_ct,
-                              int32_t *rt_ptr, int32_t *scan_temp, hipStream_t s);
+                              int32_t *slot_rt, int32_t *rt_ptr, int32_t *scan_temp, hipStream_t s);
 // bit masks of the kept tiles and the CSR of everything else; pos: nnz + 1 ints of scratch (pos[nnz] = size of the remainder on
-// return), scan_temp: scan_large_temp_bytes(nnz + 1); dst_rem[k] = place of entry k of A in the remainder, -1 if it lies in a tile
+// return), scan_temp: scan_large_temp_bytes(nnz + 1); dst_rem[k] = place of entry k of A in the remainder, or, negative,
+// -(cell + 1) with cell = (slot * 128 + row in tile) * 128 + column in tile for an entry inside a kept tile (-1 beyond kMaxCellSlots)
 hipError_t launch_tile_split(const sensei_csr &A, const ChunkPlan &p, const int32_t *rank_r, const int32_t *rank_c, int h_r, int h_c, int nt_c,
                              const int32_t *slot_of, int n_slots, unsigned *bits, int32_t *pos, int32_t *scan_temp, int32_t *col_rem,
                              int32_t *dst_rem, int32_t *row_ptr_rem, hipStream_t s);
 hipError_t launch_zero_matrix(float *C, int64_t n, int f, int64_t ldc, bool sliced, hipStream_t s);
+// out[dst_rem[k]] = src[k * stride] for the entries k of the pattern that stay in the sparse remainder (dst_rem[k] >= 0)
+hipError_t launch_compact_values(int64_t nnz, const int32_t *dst_rem, const float *src, int stride, float *out, hipStream_t s);
 // T.dh[rank, 0:f) = (kept tiles of the rank's row of tiles) . B, raw sums; B slice-major with f (a multiple of 32) columns;
 // Bh: nt_c * 128 * f floats.  With s_l, s_r, mz (attention mode) entry (i, j) of a tile weighs
-// exp(LeakyReLU(s_l[i] + s_r[j]) - mz[i].x) instead of 1.
+// exp(LeakyReLU(s_l[i] + s_r[j]) - mz[i].x) instead of 1.  `transposed` (attention mode only): T holds the tiles of the transposed
+// pattern, so its rows are the sources and its columns the destinations: entry (j, i) weighs
+// exp(LeakyReLU(s_l[i] + s_r[j]) - mz[i].x) / mz[i].y, the complete coefficient alpha_ij (the division is applied to the rows of B).
 hipError_t launch_dense_tiles(const TileSplit &T, const float *B_sliced, int64_t n_cols, int f, float *Bh, hipStream_t s,
-                              const float *s_l = nullptr, const float *s_r = nullptr, const float2 *mz = nullptr, float slope = 0.f);
+                              const float *s_l = nullptr, const float *s_r = nullptr, const float2 *mz = nullptr, float slope = 0.f,
+                              bool transposed = false);
+// Dt[(slot * 128 + i) * 128 + j] = <L[row at rank rt*128+i, 0:f), R[column node at rank ct*128+j, 0:f)> for every kept tile (all
+// of its 16384 cells, whether the pattern has them or not; ranks beyond the last node give 0); L and R slice-major with f (a
+// multiple of 32) columns; Lh: nt_r * 128 * f floats, Rh: nt_c * 128 * f floats of scratch.
+hipError_t launch_tiles_sddmm(const TileSplit &T, const float *L_sliced, int64_t n_rows, const float *R_sliced, int64_t n_cols, int f, float *Lh,
+                              float *Rh, float *Dt, hipStream_t s);
 // C = act(scale (C + T.dh[rank of the row])) over all rows; scale_i = 1 / mz[i].y if mz, else r[i] if r, else 1
 hipError_t launch_tiles_combine(const TileSplit &T, float *C, int64_t n_rows, int f_store, int64_t ldc, bool c_sliced, int f, const float *r,
                                 const float2 *mz, int act, hipStream_t s);

@@ -929,19 +929,25 @@ __global__ void k_tile_flags(const int32_t *__restrict__ hist, int n_tiles, int 
 // after the exclusive scan of sel: slot numbers of the kept tiles (row-major, so the slots of one row of tiles are
 // consecutive), the column tile of every slot, the first slot of every row of tiles
 __global__ void k_tile_slots(const int32_t *__restrict__ hist, const int32_t *__restrict__ sel_scan, int n_tiles, int nt_r, int nt_c,
-                             int min_count, int32_t *__restrict__ slot_of, int32_t *__restrict__ slot_ct, int32_t *__restrict__ rt_ptr) {
+                             int min_count, int32_t *__restrict__ slot_of, int32_t *__restrict__ slot_ct, int32_t *__restrict__ slot_rt,
+                             int32_t *__restrict__ rt_ptr) {
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
     if (t < n_tiles) {
         const bool kept = hist[t] >= min_count;
         slot_of[t] = kept ? sel_scan[t] : -1;
-        if (kept) slot_ct[sel_scan[t]] = t % nt_c;
+        if (kept) {
+            slot_ct[sel_scan[t]] = t % nt_c;
+            slot_rt[sel_scan[t]] = t / nt_c;
+        }
     }
     if (t <= nt_r) rt_ptr[t] = sel_scan[(long long)t * nt_c < n_tiles ? t * nt_c : n_tiles];
 }
 
-// bit (row, column) of its tile for every entry inside a kept tile; flag[k] = 1 for the entries that stay sparse
+// bit (row, column) of its tile for every entry inside a kept tile; flag[k] = 1 for the entries that stay sparse;
+// where[k] = -(cell + 1) for an entry inside a kept tile, cell = (slot * 128 + row in tile) * 128 + column in tile (-1 when that
+// does not fit 31 bits; the entries that stay sparse get their place in the remainder later)
 __global__ __launch_bounds__(kBlock) void k_tile_mark(TileMapArgs a, const int32_t *__restrict__ slot_of, unsigned *__restrict__ bits,
-                                                       int32_t *__restrict__ flag) {
+                                                       int32_t *__restrict__ flag, int32_t *__restrict__ where) {
     const int chunk = wave_chunk();
     if (chunk >= a.n.n_chunks) return;
     walk_chunk(a.n, chunk, threadIdx.x & 63, [&](int i) { return a.rank_r[i]; },
@@ -952,6 +958,7 @@ __global__ __launch_bounds__(kBlock) void k_tile_mark(TileMapArgs a, const int32
                    if (slot >= 0) {
                        const int rc = a.rank_c[col];
                        atomicOr(&bits[((size_t)slot * 128 + (rr & 127)) * 4 + ((rc & 127) >> 5)], 1u << (rc & 31));
+                       where[k] = slot < kMaxCellSlots ? -(((slot * 128 + (rr & 127)) * 128 + (rc & 127)) + 1) : -1;
                    }
                    flag[k] = slot >= 0 ? 0 : 1;
                });
@@ -963,9 +970,19 @@ __global__ __launch_bounds__(kBlock) void k_rem_scatter(NnzArgs a, const int32_t
     const long long k = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (k >= a.nnz) return;
     const int p = pos[k];
-    const bool stays = pos[k + 1] != p;
-    if (stays) col_rem[p] = a.col_idx[k];
-    dst_rem[k] = stays ? p : -1;
+    if (pos[k + 1] != p) {  // stays sparse; the others keep the (negative) cell code k_tile_mark gave them
+        col_rem[p] = a.col_idx[k];
+        dst_rem[k] = p;
+    }
+}
+
+// values of the entries that stay sparse, moved from the order of the pattern to the order of the remainder
+__global__ __launch_bounds__(kBlock) void k_compact_values(long long nnz, const int32_t *__restrict__ dst_rem, const float *__restrict__ src, int stride,
+                                                            float *__restrict__ out) {
+    const long long k = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= nnz) return;
+    const int d = dst_rem[k];
+    if (d >= 0) out[d] = src[k * stride];
 }
 
 __global__ void k_rem_rowptr(const int32_t *__restrict__ row_ptr, int n_rows, const int32_t *__restrict__ pos, int32_t *__restrict__ row_ptr_rem) {
@@ -1216,6 +1233,43 @@ __global__ __launch_bounds__(kBlock) void k_gat_dalpha(GatBwdArgs a, int tile, i
     };
     if (LAST) reduce_rows(a.n, chunk, lane, a.rowdot, a.carry, piece);
     else walk_row_pieces(a.n, chunk, lane, [&](int i, int lo, int hi) { (void)piece(i, lo, hi); });
+}
+
+// dalpha of every stored entry from its two sources when the pattern carries a dense-tile split: where[k] >= 0 is the place of
+// entry k in the remainder (dalpha_rem), a negative value -(cell + 1) the cell of the dense product Dt that holds it.  Writes
+// dalpha in the order of the pattern and forms the row sums sum_j alpha_ij dalpha_ij.
+__global__ __launch_bounds__(kBlock) void k_gat_dalpha_merge(NnzArgs a, const int32_t *__restrict__ where, const float *__restrict__ dalpha_rem,
+                                                              const float *__restrict__ Dt, const float *__restrict__ logits,
+                                                              const float2 *__restrict__ mz, float *__restrict__ dalpha,
+                                                              float *__restrict__ rowdot, float *__restrict__ carry) {
+    const int chunk = wave_chunk();
+    if (chunk >= a.n_chunks) return;
+    const int lane = threadIdx.x & 63;
+    reduce_rows(a, chunk, lane, rowdot, carry, [&](int i, int lo, int hi) {
+        const float2 st = mz[i];
+        const float m = st.x, iz = inv_z(st.y);
+        float s = 0.f;
+        for (int k0 = lo + lane; k0 < hi; k0 += 64 * 4) {
+            int w[4];
+            float e[4], v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int k = k0 + 64 * u < hi ? k0 + 64 * u : lo;
+                w[u] = where[k];
+                e[u] = logits[k];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u] = w[u] >= 0 ? dalpha_rem[w[u]] : Dt[-(long long)w[u] - 1];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (k0 + 64 * u < hi) {
+                    dalpha[k0 + 64 * u] = v[u];
+                    s = fmaf(expf(e[u] - m) * iz, v[u], s);
+                }
+            }
+        }
+        return s;
+    });
 }
 
 struct ScoreV2Args {
@@ -1599,11 +1653,21 @@ hipError_t launch_gat_dalpha(const sensei_csr &A, const float *theta, const floa
     a.dp_tile = (long long)(A.n_rows > 0 ? A.n_rows : 1) * 32;
     a.n_tiles = (f + 31) / 32;
     const dim3 grid(blocks_for(p.n_chunks, kWavesPerBlock));
+    if (A.nnz <= 0 && !rowdot) return hipSuccess;
     for (int t = 0; t < a.n_tiles; ++t) {
-        if (t == a.n_tiles - 1) hipLaunchKernelGGL(k_gat_dalpha<true>, grid, dim3(kBlock), 0, s, a, t, t == 0 ? 1 : 0);
+        if (t == a.n_tiles - 1 && rowdot) hipLaunchKernelGGL(k_gat_dalpha<true>, grid, dim3(kBlock), 0, s, a, t, t == 0 ? 1 : 0);
         else hipLaunchKernelGGL(k_gat_dalpha<false>, grid, dim3(kBlock), 0, s, a, t, t == 0 ? 1 : 0);
     }
-    if (p.n_chunks > 1) hipLaunchKernelGGL(k_sum_fixup, dim3(blocks_for(p.n_chunks - 1, kBlock)), dim3(kBlock), 0, s, a.n, rowdot, carry);
+    if (rowdot && p.n_chunks > 1) hipLaunchKernelGGL(k_sum_fixup, dim3(blocks_for(p.n_chunks - 1, kBlock)), dim3(kBlock), 0, s, a.n, rowdot, carry);
+    return hipGetLastError();
+}
+
+hipError_t launch_gat_dalpha_merge(const sensei_csr &A, const int32_t *where, const float *dalpha_rem, const float *Dt, const float *logits,
+                                   const float2 *mz, float *dalpha, float *rowdot, const ChunkPlan &p, float *carry, hipStream_t s) {
+    const NnzArgs n = nnz_args(A, p);
+    hipLaunchKernelGGL(k_gat_dalpha_merge, dim3(blocks_for(p.n_chunks, kWavesPerBlock)), dim3(kBlock), 0, s, n, where, dalpha_rem, Dt, logits, mz, dalpha,
+                       rowdot, carry);
+    if (p.n_chunks > 1) hipLaunchKernelGGL(k_sum_fixup, dim3(blocks_for(p.n_chunks - 1, kBlock)), dim3(kBlock), 0, s, n, rowdot, carry);
     return hipGetLastError();
 }
 
@@ -1730,7 +1794,7 @@ static TileMapArgs tile_map_args(const sensei_csr &A, const ChunkPlan &p, const 
 
 hipError_t launch_tile_select(const sensei_csr &A, const ChunkPlan &p, const int32_t *rank_r, const int32_t *rank_c, int h_r, int h_c,
                               int nt_r, int nt_c, int min_count, int32_t *hist, int32_t *sel_scan, int32_t *slot_of, int32_t *slot_ct,
-                              int32_t *rt_ptr, int32_t *scan_temp, hipStream_t s) {
+                              int32_t *slot_rt, int32_t *rt_ptr, int32_t *scan_temp, hipStream_t s) {
     const int n_tiles = nt_r * nt_c;
     hipLaunchKernelGGL(k_fill_i32, dim3(blocks_for(n_tiles, kBlock)), dim3(kBlock), 0, s, hist, (long long)n_tiles, 0);
     if (A.nnz > 0)
@@ -1741,7 +1805,7 @@ hipError_t launch_tile_select(const sensei_csr &A, const ChunkPlan &p, const int
     if (e != hipSuccess) return e;
     const int span = n_tiles > nt_r + 1 ? n_tiles : nt_r + 1;
     hipLaunchKernelGGL(k_tile_slots, dim3(blocks_for(span, kBlock)), dim3(kBlock), 0, s, (const int32_t *)hist, (const int32_t *)sel_scan, n_tiles,
-                       nt_r, nt_c, min_count, slot_of, slot_ct, rt_ptr);
+                       nt_r, nt_c, min_count, slot_of, slot_ct, slot_rt, rt_ptr);
     return hipGetLastError();
 }
 
@@ -1753,12 +1817,18 @@ hipError_t launch_tile_split(const sensei_csr &A, const ChunkPlan &p, const int3
     hipLaunchKernelGGL(k_fill_i32, dim3(1), dim3(64), 0, s, pos + A.nnz, 1LL, 0);
     if (A.nnz > 0)
         hipLaunchKernelGGL(k_tile_mark, dim3(blocks_for(p.n_chunks, kWavesPerBlock)), dim3(kBlock), 0, s,
-                           tile_map_args(A, p, rank_r, rank_c, h_r, h_c, nt_c), slot_of, bits, pos);
+                           tile_map_args(A, p, rank_r, rank_c, h_r, h_c, nt_c), slot_of, bits, pos, dst_rem);
     const hipError_t e = launch_exclusive_scan_large(pos, (long long)A.nnz + 1, scan_temp, s);
     if (e != hipSuccess) return e;
     if (A.nnz > 0) hipLaunchKernelGGL(k_rem_scatter, dim3(blocks_for(A.nnz, kBlock)), dim3(kBlock), 0, s, nnz_args(A, p), (const int32_t *)pos, col_rem, dst_rem);
     hipLaunchKernelGGL(k_rem_rowptr, dim3(blocks_for((long long)A.n_rows + 1, kBlock)), dim3(kBlock), 0, s, A.row_ptr, A.n_rows, (const int32_t *)pos,
                        row_ptr_rem);
+    return hipGetLastError();
+}
+
+hipError_t launch_compact_values(int64_t nnz, const int32_t *dst_rem, const float *src, int stride, float *out, hipStream_t s) {
+    if (nnz <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_compact_values, dim3(blocks_for(nnz, kBlock)), dim3(kBlock), 0, s, (long long)nnz, dst_rem, src, stride, out);
     return hipGetLastError();
 }
 

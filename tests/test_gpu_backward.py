@@ -171,6 +171,57 @@ def test_gat_backward_other_slope_and_weight_gradient_only(ctx):
     assert_close(dar, want[3], what="da_r")
 
 
+@pytest.mark.parametrize("widths", [(72, 96), (40, 130), (48, 24)])
+def test_gat_backward_on_a_dense_tile_split(ctx, widths):
+    """With a tile split attached to the pattern, the per-entry products <dP_i, Theta_j> of the entries inside kept tiles come
+    from one dense product per tile and the others from the remainder; the gradients still match the chain rule.  The last
+    width is below the split's minimum and takes the plain path."""
+    from paper_2306_15155_amd import Tiles, csr_struct
+    g = synth.rmat(74, 5000, 150_000)
+    f_in, f_out = widths
+    X, W, dY = _inputs(g, f_in, f_out, 75)
+    a_l, a_r = synth.normal(75, 20, (f_out,), 0.0, 0.3), synth.normal(75, 21, (f_out,), 0.0, 0.3)
+    Y = oracle.gat_layer(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, a_l, a_r, 0.2, 1).astype(np.float32)
+    want = oracle.gat_backward(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, a_l, a_r, dY, Y=Y, slope=0.2, act=ACT_RELU)
+    A = DeviceCSR(g)
+    T = Tiles(ctx, A.s, 0.05, 128, min_width=32)
+    assert T.n_tiles > 0 and T.nnz_sparse > 0
+    Ah = csr_struct(g.n_rows, g.n_cols, A.row_ptr, A.col_idx, None, None, T)
+    pos = ctx.transpose_positions(A.s, A.s)  # symmetric pattern: its own transpose
+    # split on the pattern only, on the transposed pattern only (alpha^T . dP takes it), on both; the last one twice, so that
+    # the second call meets the workspace the first one left behind
+    for how, first, second in (("A", Ah, A.s), ("At", A.s, Ah), ("both", Ah, Ah), ("both again", Ah, Ah)):
+        got = ctx.gat_backward(first, second, pos, dev(X), dev(W), dev(a_l), dev(a_r), dev(dY), Y=dev(Y), activation=ACT_RELU)
+        for gpu, ref, what in zip(got, want, ("dX", "dW", "da_l", "da_r")):
+            assert_close(gpu, ref, what=f"{what}, split on {how}")
+    T.close()
+
+
+def test_gat_backward_with_a_split_of_a_rectangular_transposed_pattern(ctx):
+    """Fewer destinations than sources: the transposed pattern is a matrix of its own with its own tile split, whose rows are
+    the sources and whose columns are the destinations."""
+    from paper_2306_15155_amd import Tiles, csr_struct
+    full = synth.rmat(76, 4500, 200_000)
+    rp = full.row_ptr[:3001].copy()  # the first 3000 destinations of a power-law graph, all 4500 sources
+    g = synth.CSR(3000, full.n_cols, rp, full.col_idx[:rp[-1]].copy())
+    gt = synth.transpose(g)
+    f_in, f_out = 56, 160
+    X, W, dY = _inputs(g, f_in, f_out, 77)
+    a_l, a_r = synth.normal(77, 20, (f_out,), 0.0, 0.3), synth.normal(77, 21, (f_out,), 0.0, 0.3)
+    want = oracle.gat_backward(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, a_l, a_r, dY, slope=0.2)
+    A, At = DeviceCSR(g), DeviceCSR(gt)
+    T, Tt = Tiles(ctx, A.s, 0.05, 192, min_width=32), Tiles(ctx, At.s, 0.05, 192, min_width=32)
+    assert T.n_tiles > 0 and Tt.n_tiles > 0
+    Ah = csr_struct(g.n_rows, g.n_cols, A.row_ptr, A.col_idx, None, None, T)
+    Ath = csr_struct(gt.n_rows, gt.n_cols, At.row_ptr, At.col_idx, None, None, Tt)
+    pos = ctx.transpose_positions(A.s, At.s)
+    got = ctx.gat_backward(Ah, Ath, pos, dev(X), dev(W), dev(a_l), dev(a_r), dev(dY))
+    for gpu, ref, what in zip(got, want, ("dX", "dW", "da_l", "da_r")):
+        assert_close(gpu, ref, what=what)
+    T.close()
+    Tt.close()
+
+
 def test_transpose_positions_rejects_a_pattern_that_is_not_the_transpose(ctx):
     from paper_2306_15155_amd import SenseiError
     g = hub_and_empty_graph(74, 500, 3000, 200, 5)   # not symmetric

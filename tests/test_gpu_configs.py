@@ -300,11 +300,17 @@ def test_config4_gat_backward_full_size(ctx, reddit_like):
     dY = synth.normal(7, 510, (g.n_rows, f_out), 0.0, 1.0)
     want = oracle.gat_backward(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, a_l, a_r, dY, omp=True, with_dtheta=True)
     pos = ctx.transpose_positions(A.s, A.s)
-    got = ctx.gat_backward(A.s, A.s, pos, dev(X), dev(W), dev(a_l), dev(a_r), dev(dY))
-    assert_close(got[0], want[0], what="dX")
+    from paper_2306_15155_amd import Tiles, csr_struct
+    T = Tiles(ctx, A.s, 0.07, 256)
+    assert T.n_tiles > 0
+    A_split = csr_struct(g.n_rows, g.n_cols, A.row_ptr, A.col_idx, None, None, T)
     # dW[f, m] = sum_j X[j, f] dTheta[j, m]: root-sum-square of those terms
     rss = np.sqrt((X.astype(np.float64) ** 2).T @ (want[4] ** 2))
-    assert_close_reduced(got[1], want[1], rss, what="dW")
-    # da[m] = sum_j ds[j] Theta[j, m]: sums over all nodes as well, and each ds[j] is itself a sum of fp32 terms
-    assert_close_reduced(got[2], want[2], np.sqrt((want[5] ** 2) @ (Th ** 2)), what="da_l")
-    assert_close_reduced(got[3], want[3], np.sqrt((want[6] ** 2) @ (Th ** 2)), what="da_r")
+    for how, pattern in (("plain", A.s), ("dense-tile split", A_split)):
+        got = ctx.gat_backward(pattern, A.s, pos, dev(X), dev(W), dev(a_l), dev(a_r), dev(dY))
+        assert_close(got[0], want[0], what=f"dX, {how}")
+        assert_close_reduced(got[1], want[1], rss, what=f"dW, {how}")
+        # da[m] = sum_j ds[j] Theta[j, m]: sums over all nodes as well, and each ds[j] is itself a sum of fp32 terms
+        assert_close_reduced(got[2], want[2], np.sqrt((want[5] ** 2) @ (Th ** 2)), what=f"da_l, {how}")
+        assert_close_reduced(got[3], want[3], np.sqrt((want[6] ** 2) @ (Th ** 2)), what=f"da_r, {how}")
+    T.close()
