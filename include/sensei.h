@@ -248,12 +248,13 @@ int sensei_gatv2_layer(sensei_ctx *ctx, const sensei_csr *A, sensei_mat X, sense
  * evaluated as a block-sparse GEMM) on a stream of the object's own, while the caller's stream runs the SpMM over the
  * CSR remainder of the entries outside such tiles; a last pass on the caller's stream joins the two sums and applies the
  * row scaling and the activation (the fork and join are event dependencies between the two streams, so the call stays
- * asynchronous and can be captured into a graph).  Two kinds of SpMM use the split when `tiles` is set in the
- * sensei_csr: the value-less one on an internal slice-major operand of at most max_width columns (a multiple of 32;
- * what the GCN, SGC and TAGCN layers and the GCN backward run on graphs whose rows are gathered often), and the
- * attention aggregation of the single-head GAT layer in its reuse compositions, where the tiles form the softmax
- * weights from the attention projections themselves.  Every other call ignores it.  Results differ from the unsplit
- * path only in the order of summation.  min_density: 0 < min_density <= 1; 0.05 .. 0.09 measured best on a
+ * asynchronous and can be captured into a graph).  These steps use the split when `tiles` is set in the sensei_csr:
+ * the value-less SpMM on an internal slice-major operand of at most max_width columns (a multiple of 32; what the
+ * GCN, SGC and TAGCN layers and the GCN backward run on graphs whose rows are gathered often); the attention
+ * aggregation of the GAT layer in its reuse compositions (every head whose width is a whole number of 32-column
+ * slices), where the tiles form the softmax weights from the attention projections themselves; and two steps of the
+ * GAT backward (see there).  Every other call ignores it.  Results differ from the unsplit path only in the order of
+ * summation.  min_density: 0 < min_density <= 1; 0.05 .. 0.09 measured best on a
  * 233,000-node power-law graph (0.07: 64 % of the entries in 22,334 tiles, step time 16.9 -> 12.9 ms).
  *   sensei_tiles_bytes   device bytes sensei_tiles_create needs (an upper bound taken before the tiles are counted);
  *   sensei_tiles_create  builds the split in device_buf (256-byte aligned, caller-owned, must outlive the object);

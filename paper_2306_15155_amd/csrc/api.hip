@@ -525,7 +525,7 @@ int run_gat(const sensei_csr &A, const sensei_mat &X, const sensei_mat &W, const
     }
     const int f_gather = reuse ? (n_heads == 1 ? fo : d) : f_in;  // width of the aggregation of one head
     // dense-tile split: the tiles form their weights from s_l, s_r themselves, only the remainder's logits are stored
-    const bool by_tiles = reuse && theta_sliced && n_heads == 1 && tiles_usable(A, kSpmmSoftmax, f_gather, true, true);
+    const bool by_tiles = reuse && theta_sliced && tiles_usable(A, kSpmmSoftmax, f_gather, true, true);
     const bool by_panel = !by_tiles && panels_usable(A, f_gather);
     for (int h = 0; h < n_heads; ++h) {
         const float *al = a_l + (size_t)h * d, *ar = a_r + (size_t)h * d;

@@ -490,6 +490,25 @@ def test_multi_head_gat_is_the_single_head_layer_per_head(ctx, name, shape):
     assert torch.equal(one, ctx.gat_layer(A.s, dev(X), dev(W), dev(a_l), dev(a_r), 0, 0.2, ACT_RELU))
 
 
+@pytest.mark.parametrize("heads,d", [(2, 64), (4, 32), (3, 40)])
+def test_multi_head_gat_on_a_dense_tile_split(ctx, heads, d):
+    """Every head of a reuse composition aggregates its own 32-column slices of Theta, tiles and remainder alike; a head width
+    that is not a whole number of slices (40) keeps Theta row-major and takes the plain path."""
+    from paper_2306_15155_amd import Tiles, csr_struct
+    g = synth.rmat(35, 5000, 150_000)
+    A = DeviceCSR(g)
+    T = Tiles(ctx, A.s, 0.05, 128, min_width=32)
+    assert T.n_tiles > 0
+    Ah = csr_struct(g.n_rows, g.n_cols, A.row_ptr, A.col_idx, None, None, T)
+    X, W = synth.uniform(35, 10, (g.n_cols, 56)), synth.glorot(35, 11, 56, heads * d)
+    a_l, a_r = synth.normal(35, 12, (heads * d,), 0.0, 0.4), synth.normal(35, 13, (heads * d,), 0.0, 0.4)
+    ref = oracle.gat_layer_heads(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, a_l, a_r, heads, 0.2, ACT_RELU)
+    for cid in range(4):
+        got = ctx.gat_layer_heads(Ah, dev(X), dev(W), dev(a_l), dev(a_r), heads, cid, 0.2, ACT_RELU)
+        assert_close(got, ref, what=f"{heads} heads of {d}, comp {cid}")
+    T.close()
+
+
 def test_multi_head_gat_over_column_panels_and_bad_head_counts(ctx):
     from paper_2306_15155_amd import Panels, SenseiError, csr_struct
     g = synth.rmat(34, 6000, 120_000)
