@@ -268,17 +268,27 @@ def test_backward_degenerate_cases(ctx, case):
         assert float(got[1].abs().max()) == 0.0 and float(dW.abs().max()) == 0.0
 
 
-def test_backward_can_be_captured_in_a_hip_graph(ctx):
+@pytest.mark.parametrize("split", [False, True])
+def test_backward_can_be_captured_in_a_hip_graph(ctx, split):
     """The backward calls only enqueue kernels (fill kernels instead of memsets, no allocation of their own, no
-    synchronisation): a captured training step replays to the same bits as the eager run, every time."""
+    synchronisation): a captured training step replays to the same bits as the eager run, every time.  With a dense-tile
+    split on the pattern the calls fork to the split's stream and join it again by events, which the capture records as
+    dependencies of the graph."""
+    from paper_2306_15155_amd import Tiles, csr_struct
     g = synth.rmat(95, 4000, 90_000)
     A = DeviceCSR(g)
-    dr, dc = ctx.degrees(A.s)
+    plain = A.s
+    dr, dc = ctx.degrees(plain)
     r, c = ctx.norm_vectors(dr), ctx.norm_vectors(dc)
-    f_in, f_out = 48, 40
+    f_in, f_out = (48, 40) if not split else (48, 136)
+    T = None
+    if split:
+        T = Tiles(ctx, plain, 0.05, 160, min_width=32)
+        assert T.n_tiles > 0
+        A = type("Split", (), {"s": csr_struct(g.n_rows, g.n_cols, A.row_ptr, A.col_idx, None, None, T), "keep": A})()
     X, W, dY = (dev(t) for t in _inputs(g, f_in, f_out, 96))
     a_l, a_r = dev(synth.normal(96, 20, (f_out,), 0.0, 0.3)), dev(synth.normal(96, 21, (f_out,), 0.0, 0.3))
-    pos = ctx.transpose_positions(A.s, A.s)
+    pos = ctx.transpose_positions(plain, plain)
     Y = ctx.gcn_layer(A.s, r, c, X, W, 3, ACT_RELU)
 
     def step():
@@ -309,3 +319,6 @@ def test_backward_can_be_captured_in_a_hip_graph(ctx):
         torch.cuda.synchronize()
         for a, b in zip(eager, want):
             assert torch.equal(a, b)
+    if T is not None:
+        del graph
+        T.close()
