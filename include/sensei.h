@@ -251,8 +251,9 @@ int sensei_gatv2_layer(sensei_ctx *ctx, const sensei_csr *A, sensei_mat X, sense
  * asynchronous and can be captured into a graph).  These steps use the split when `tiles` is set in the sensei_csr:
  * the value-less SpMM on an internal slice-major operand of at most max_width columns (a multiple of 32; what the
  * GCN, SGC and TAGCN layers and the GCN backward run on graphs whose rows are gathered often); the attention
- * aggregation of the GAT layer in its reuse compositions (every head whose width is a whole number of 32-column
- * slices), where the tiles form the softmax weights from the attention projections themselves; and two steps of the
+ * aggregation of the GAT layer (reuse compositions: every head whose width is a whole number of 32-column slices;
+ * recompute compositions: when the layer gathers from its slice-major copy of X), where the tiles form the softmax
+ * weights from the attention projections themselves; and two steps of the
  * GAT backward (see there).  Every other call ignores it.  Results differ from the unsplit path only in the order of
  * summation.  min_density: 0 < min_density <= 1; 0.05 .. 0.09 measured best on a
  * 233,000-node power-law graph (0.07: 64 % of the entries in 22,334 tiles, step time 16.9 -> 12.9 ms).

@@ -524,8 +524,9 @@ int run_gat(const sensei_csr &A, const sensei_mat &X, const sensei_mat &W, const
         }
     }
     const int f_gather = reuse ? (n_heads == 1 ? fo : d) : f_in;  // width of the aggregation of one head
-    // dense-tile split: the tiles form their weights from s_l, s_r themselves, only the remainder's logits are stored
-    const bool by_tiles = reuse && theta_sliced && tiles_usable(A, kSpmmSoftmax, f_gather, true, true);
+    // dense-tile split (the gathered operand, Theta or X, must be slice-major): the tiles form their weights from s_l, s_r
+    // themselves, only the remainder's logits are stored
+    const bool by_tiles = (reuse ? theta_sliced : x_sliced) && tiles_usable(A, kSpmmSoftmax, f_gather, true, true);
     const bool by_panel = !by_tiles && panels_usable(A, f_gather);
     for (int h = 0; h < n_heads; ++h) {
         const float *al = a_l + (size_t)h * d, *ar = a_r + (size_t)h * d;
@@ -550,7 +551,7 @@ int run_gat(const sensei_csr &A, const sensei_mat &X, const sensei_mat &W, const
                                 theta_sliced, false, by_tiles ? &attn : nullptr));
         } else {
             SENSEI_TRY(spmm_any(Aw, kSpmmSoftmax, nullptr, nullptr, x_src, X.ld, f_in, U, fi, f_in, SENSEI_ACT_NONE, plan, carry, s, kt, by_panel, stats,
-                                x_sliced));
+                                x_sliced, false, by_tiles ? &attn : nullptr));
             SENSEI_TRY(launch_gemm(U, fi, W.ptr + (size_t)h * d, W.ld, Y_h, ldy, A.n_rows, f_in, d, d, act, s, nullptr, gt));
         }
     }
