@@ -540,8 +540,23 @@ int run_gat(const sensei_csr &A, const sensei_mat &X, const sensei_mat &W, const
         // One pass computes the logits and the per-row softmax statistics; the aggregation then weighs each neighbour
         // by exp(e - max) and scales the row by 1 / sum, so the attention weights themselves are never stored.  With a
         // panel copy the logits are written straight in panel order and the SpMM follows the panels.
-        SENSEI_TRY(launch_attention_stats(A, s_l, s_r, slope, logits, by_tiles ? A.tiles->dst_rem : by_panel ? A.panels->position : nullptr, plan,
-                                          stats, carry_stats, s));
+        if (by_tiles) {
+            // the entries inside kept tiles: (max, sum) per row and segment of tiles from the bit masks and the two vectors in rank
+            // order, on the split's stream; the remainder: the ordinary pass over its CSR, which leaves its logits in its own order;
+            // then the pairs of every row are merged
+            const sensei_tiles &D = *A.tiles;
+            SENSEI_TRY(hipEventRecord(D.ev_fork, s));
+            SENSEI_TRY(hipStreamWaitEvent(D.side, D.ev_fork, 0));
+            SENSEI_TRY(launch_tile_stats(D.T, s_l, s_r, slope, D.side));
+            SENSEI_TRY(hipEventRecord(D.ev_join, D.side));
+            sensei_csr Ar = A;
+            Ar.nnz = D.nnz_rem; Ar.row_ptr = D.row_ptr_rem; Ar.col_idx = D.col_rem; Ar.panels = nullptr; Ar.tiles = nullptr;
+            SENSEI_TRY(launch_attention_stats(Ar, s_l, s_r, slope, logits, nullptr, D.plan_rem, stats, carry_stats, s));
+            SENSEI_TRY(hipStreamWaitEvent(s, D.ev_join, 0));
+            SENSEI_TRY(launch_tile_stats_merge(D.T, stats, A.n_rows, s));
+        } else {
+            SENSEI_TRY(launch_attention_stats(A, s_l, s_r, slope, logits, by_panel ? A.panels->position : nullptr, plan, stats, carry_stats, s));
+        }
         const AttnVectors attn = {s_l, s_r, slope};
         sensei_csr Aw = A;
         Aw.val = logits;
@@ -1217,7 +1232,7 @@ constexpr int kTileRanksMax = 65536;  // ranks per side that are examined for de
 struct TilesLayout {
     int h_r, h_c, nt_r, nt_c, n_tiles, max_slots, min_count;
     size_t rank_r, rank_c, order_r, order_c, hist, sel_scan, slot_of, slot_ct, slot_rt, rt_ptr, scan_small, plan, bits, pos, scan_large, col_rem,
-        dst_rem, row_ptr_rem, plan_rem, bh, seg_first, rt_seg, seg_rt, rank_vec, part, dh, total;
+        dst_rem, row_ptr_rem, plan_rem, bh, seg_first, rt_seg, seg_rt, seg_stats, rank_vec, part, dh, total;
     int max_seg;
 };
 
@@ -1258,6 +1273,7 @@ TilesLayout tiles_layout(const sensei_csr &A, float min_density, int max_width) 
     L.seg_first = put(((size_t)L.max_seg + 1) * 4);
     L.rt_seg = put(((size_t)L.nt_r + 1) * 4);
     L.seg_rt = put(((size_t)L.max_seg + 1) * 4);
+    L.seg_stats = put((size_t)L.max_seg * 128 * 8);
     L.rank_vec = put((size_t)2 * (L.nt_r + L.nt_c) * 128 * 4);
     L.part = put((size_t)L.max_seg * 128 * max_width * 4);
     L.dh = put((size_t)L.nt_r * 128 * max_width * 4);
@@ -1313,7 +1329,7 @@ int sensei_tiles_create(sensei_ctx *ctx, const sensei_csr *A, float min_density,
     D->max_width = max_width;
     D->Bh = reinterpret_cast<float *>(base + L.bh);
     D->T.nt_r = L.nt_r; D->T.nt_c = L.nt_c; D->T.n_slots = 0; D->T.n_seg = 0;
-    D->T.seg_first = nullptr; D->T.rt_seg = nullptr; D->T.seg_rt = nullptr; D->T.part = nullptr; D->T.rank_vec = nullptr;
+    D->T.seg_first = nullptr; D->T.rt_seg = nullptr; D->T.seg_rt = nullptr; D->T.part = nullptr; D->T.rank_vec = nullptr; D->T.seg_stats = nullptr;
     D->T.dh = nullptr; D->T.rank_r = nullptr;
     D->T.order_r = at(L.order_r); D->T.order_c = at(L.order_c); D->T.rt_ptr = at(L.rt_ptr); D->T.slot_ct = at(L.slot_ct); D->T.slot_rt = at(L.slot_rt);
     D->T.bits = reinterpret_cast<unsigned *>(base + L.bits);
@@ -1371,6 +1387,7 @@ int sensei_tiles_create(sensei_ctx *ctx, const sensei_csr *A, float min_density,
             return fail(SENSEI_HIP_ERROR);
         D->T.seg_first = at(L.seg_first); D->T.rt_seg = at(L.rt_seg); D->T.seg_rt = at(L.seg_rt);
         D->T.rank_vec = reinterpret_cast<float *>(base + L.rank_vec);
+        D->T.seg_stats = reinterpret_cast<float2 *>(base + L.seg_stats);
         D->T.dh = reinterpret_cast<float *>(base + L.dh);
         D->T.rank_r = at(L.rank_r);
         if (hipStreamCreateWithFlags(&D->side, hipStreamNonBlocking) != hipSuccess || hipEventCreateWithFlags(&D->ev_fork, hipEventDisableTiming) != hipSuccess ||
@@ -1388,7 +1405,9 @@ int sensei_tiles_create(sensei_ctx *ctx, const sensei_csr *A, float min_density,
     D->nnz_rem = nnz_rem;
     sensei_csr Ar = *A;
     Ar.nnz = nnz_rem; Ar.row_ptr = D->row_ptr_rem; Ar.col_idx = D->col_rem;
-    D->plan_rem.chunk_nnz = choose_chunk_nnz(nnz_rem);
+    // the chunk length of the whole pattern: the remainder then never has more chunks than the pattern, and the per-chunk carry
+    // buffers that callers size for the pattern hold the remainder's too
+    D->plan_rem.chunk_nnz = choose_chunk_nnz(A->nnz);
     D->plan_rem.n_chunks = nnz_rem <= 0 ? 1 : (int)(((int64_t)nnz_rem + D->plan_rem.chunk_nnz - 1) / D->plan_rem.chunk_nnz);
     D->plan_rem.chunk_row = at(L.plan_rem);
     if (launch_chunk_rows(Ar, D->plan_rem, s) != hipSuccess || hipStreamSynchronize(s) != hipSuccess) return fail(SENSEI_HIP_ERROR);

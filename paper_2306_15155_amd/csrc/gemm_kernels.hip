@@ -437,12 +437,87 @@ __global__ void k_gather_ranked_vecs(const float *__restrict__ s_l, const float 
     if (q < n_r) {
         const int i = order_r[q];
         sl_rank[q] = i >= 0 ? s_l[i] : 0.f;
-        m_rank[q] = i >= 0 ? mz[i].x : 0.f;
+        if (mz) m_rank[q] = i >= 0 ? mz[i].x : 0.f;
     }
     if (q < n_c) {
         const int j = order_c[q];
         sr_rank[q] = j >= 0 ? s_r[j] : 0.f;
     }
+}
+
+// (max, sum of exp) of the attention logits over the entries of one segment of tiles, per row of its row of tiles: two threads per
+// row, each walks the set bits of its half of the row's mask in every tile of the segment; the column vector of the tile sits in LDS.
+// A tile is first searched for its maximum, then summed against the running maximum, so a row costs one rescale per tile.
+__global__ __launch_bounds__(256) void k_tile_stats(const unsigned *__restrict__ bits, const int32_t *__restrict__ seg_first,
+                                                    const int32_t *__restrict__ slot_ct, const int32_t *__restrict__ seg_rt,
+                                                    const float *__restrict__ sl_rank, const float *__restrict__ sr_rank, float slope,
+                                                    float2 *__restrict__ seg_stats) {
+    __shared__ float sr_s[128];
+    const int seg = blockIdx.x;
+    const int s0 = seg_first[seg], s1 = seg_first[seg + 1];
+    const int t = threadIdx.x, row = t >> 1, half = t & 1;
+    const float sl = sl_rank[(size_t)seg_rt[seg] * 128 + row];
+    float m = -INFINITY, z = 0.f;
+    for (int slot = s0; slot < s1; ++slot) {
+        __syncthreads();  // the previous tile's column vector is no longer read
+        if (t < 128) sr_s[t] = sr_rank[(size_t)slot_ct[slot] * 128 + t];
+        __syncthreads();
+        const uint2 w = *reinterpret_cast<const uint2 *>(bits + ((size_t)slot * 128 + row) * 4 + half * 2);
+        const float *sr = sr_s + half * 64;
+        float tm = -INFINITY;
+        for (unsigned b = w.x; b; b &= b - 1) {
+            float e = sl + sr[__ffs(b) - 1];
+            e = e > 0.f ? e : slope * e;
+            tm = e > tm ? e : tm;
+        }
+        for (unsigned b = w.y; b; b &= b - 1) {
+            float e = sl + sr[32 + __ffs(b) - 1];
+            e = e > 0.f ? e : slope * e;
+            tm = e > tm ? e : tm;
+        }
+        if (tm == -INFINITY) continue;  // no entry of this row in this half of the tile
+        const float mm = m > tm ? m : tm;
+        z *= __expf(m - mm);            // m = -inf at the start: exp(-inf) = 0 and z = 0
+        m = mm;
+        for (unsigned b = w.x; b; b &= b - 1) {
+            float e = sl + sr[__ffs(b) - 1];
+            e = e > 0.f ? e : slope * e;
+            z += __expf(e - m);
+        }
+        for (unsigned b = w.y; b; b &= b - 1) {
+            float e = sl + sr[32 + __ffs(b) - 1];
+            e = e > 0.f ? e : slope * e;
+            z += __expf(e - m);
+        }
+    }
+    // the two halves of the row sit in neighbouring lanes
+    const float m2 = __shfl_xor(m, 1, 64), z2 = __shfl_xor(z, 1, 64);
+    const float mm = m > m2 ? m : m2;
+    if (half == 0) {
+        float2 out = make_float2(-INFINITY, 0.f);
+        if (mm != -INFINITY) out = make_float2(mm, z * __expf(m - mm) + z2 * __expf(m2 - mm));
+        seg_stats[(size_t)seg * 128 + row] = out;
+    }
+}
+
+// stats[i] (the pair over the remainder's entries of row i) merged with the pairs of the segments of the row's row of tiles, in
+// segment order
+__global__ void k_tile_stats_merge(float2 *__restrict__ stats, long long n_rows, const int32_t *__restrict__ rank_r, int n_ranks,
+                                   const int32_t *__restrict__ rt_seg, const float2 *__restrict__ seg_stats) {
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_rows) return;
+    const int rank = rank_r[i];
+    if (rank >= n_ranks) return;
+    float2 a = stats[i];
+    const int rt = rank >> 7, lr = rank & 127;
+    for (int seg = rt_seg[rt]; seg < rt_seg[rt + 1]; ++seg) {
+        const float2 b = seg_stats[(size_t)seg * 128 + lr];
+        const float mm = a.x > b.x ? a.x : b.x;
+        if (mm == -INFINITY) continue;
+        a.y = a.y * expf(a.x - mm) + b.y * expf(b.x - mm);
+        a.x = mm;
+    }
+    stats[i] = a;
 }
 
 // the same for the tiles of the transposed pattern: its rows are the sources (s_r), its columns the destinations (s_l and their maxima)
@@ -754,6 +829,23 @@ hipError_t launch_dense_tiles(const TileSplit &T, const float *B_sliced, int64_t
     }
     const long long threads = (long long)T.nt_r * 128 * (f / 4);
     hipLaunchKernelGGL(k_tiles_reduce, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, (const float *)T.part, T.rt_seg, T.nt_r, f, T.dh);
+    return hipGetLastError();
+}
+
+hipError_t launch_tile_stats(const TileSplit &T, const float *s_l, const float *s_r, float slope, hipStream_t s) {
+    if (T.n_slots <= 0 || T.n_seg <= 0) return hipSuccess;
+    const int n_r = T.nt_r * 128, n_c = T.nt_c * 128;
+    hipLaunchKernelGGL(k_gather_ranked_vecs, dim3((unsigned)(((n_r > n_c ? n_r : n_c) + 255) / 256)), dim3(256), 0, s, s_l, s_r, (const float2 *)nullptr,
+                       T.order_r, n_r, T.order_c, n_c, T.rank_vec, T.rank_vec + n_r, T.rank_vec + 2 * n_r);
+    hipLaunchKernelGGL(k_tile_stats, dim3((unsigned)T.n_seg), dim3(256), 0, s, T.bits, T.seg_first, T.slot_ct, T.seg_rt, (const float *)T.rank_vec,
+                       (const float *)(T.rank_vec + 2 * n_r), slope, T.seg_stats);
+    return hipGetLastError();
+}
+
+hipError_t launch_tile_stats_merge(const TileSplit &T, float2 *stats, int64_t n_rows, hipStream_t s) {
+    if (T.n_slots <= 0 || T.n_seg <= 0 || n_rows <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_tile_stats_merge, dim3((unsigned)((n_rows + 255) / 256)), dim3(256), 0, s, stats, (long long)n_rows, T.rank_r, T.nt_r * 128,
+                       T.rt_seg, (const float2 *)T.seg_stats);
     return hipGetLastError();
 }
 

@@ -152,6 +152,7 @@ struct TileSplit {
     const int32_t *seg_rt;             // device: row of tiles of each segment
     float *part;                       // device: n_seg x 128 x (widest operand) partial products
     float *rank_vec;                   // device: 2 * (nt_r + nt_c) * 128 floats for the attention vectors in rank order
+    float2 *seg_stats;                 // device: n_seg x 128 (max, sum of exp) pairs of the attention logits inside the tiles
     float *dh;                         // device: nt_r * 128 x (widest operand): the tiles' product, by row rank
     const int32_t *rank_r;             // device: rank of every row node (INT_MAX outside the tiled region)
 };
@@ -181,6 +182,11 @@ hipError_t launch_compact_values(int64_t nnz, const int32_t *dst_rem, const floa
 hipError_t launch_dense_tiles(const TileSplit &T, const float *B_sliced, int64_t n_cols, int f, float *Bh, hipStream_t s,
                               const float *s_l = nullptr, const float *s_r = nullptr, const float2 *mz = nullptr, float slope = 0.f,
                               bool transposed = false);
+// Softmax statistics of the attention logits e_ij = LeakyReLU(s_l[i] + s_r[j]) over the entries inside kept tiles: T.seg_stats[seg][row]
+// = (max, sum of exp(e - max)) per segment and row of its row of tiles.  launch_tile_stats_merge folds them into stats[i] (which holds
+// the pair over the remainder's entries of row i on entry, over all stored entries on return).
+hipError_t launch_tile_stats(const TileSplit &T, const float *s_l, const float *s_r, float slope, hipStream_t s);
+hipError_t launch_tile_stats_merge(const TileSplit &T, float2 *stats, int64_t n_rows, hipStream_t s);
 // Dt[(slot * 128 + i) * 128 + j] = <L[row at rank rt*128+i, 0:f), R[column node at rank ct*128+j, 0:f)> for every kept tile (all
 // of its 16384 cells, whether the pattern has them or not; ranks beyond the last node give 0); L and R slice-major with f (a
 // multiple of 32) columns; Lh: nt_r * 128 * f floats, Rh: nt_c * 128 * f floats of scratch.
