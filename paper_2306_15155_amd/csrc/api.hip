@@ -178,6 +178,7 @@ bool panels_usable(const sensei_csr &A, int f) {
 struct AttnVectors {  // what the softmax mode of the dense tiles needs besides the row statistics
     const float *s_l, *s_r;
     float slope;
+    bool gathered;  // the operand already sits in the split's buffer in rank order (the caller ran launch_tiles_gather)
 };
 
 bool tiles_usable(const sensei_csr &A, int mode, int f, bool b_sliced, bool attn = false) {
@@ -206,7 +207,7 @@ hipError_t spmm_any(const sensei_csr &A, int mode, const float *r, const float *
         if (e == hipSuccess) e = hipStreamWaitEvent(D.side, D.ev_fork, 0);
         if (e == hipSuccess)
             e = launch_dense_tiles(D.T, B, A.n_cols, pad32(f), D.Bh, D.side, attn ? attn->s_l : nullptr, attn ? attn->s_r : nullptr,
-                                   attn ? mz : nullptr, attn ? attn->slope : 0.f);
+                                   attn ? mz : nullptr, attn ? attn->slope : 0.f, false, attn && attn->gathered);
         if (e == hipSuccess) e = hipEventRecord(D.ev_join, D.side);
         if (e != hipSuccess) return e;
         sensei_csr Ar = A;
@@ -548,6 +549,8 @@ int run_gat(const sensei_csr &A, const sensei_mat &X, const sensei_mat &W, const
             SENSEI_TRY(hipEventRecord(D.ev_fork, s));
             SENSEI_TRY(hipStreamWaitEvent(D.side, D.ev_fork, 0));
             SENSEI_TRY(launch_tile_stats(D.T, s_l, s_r, slope, D.side));
+            // the rows the tiles will multiply, in rank order: known since the GEMM, so gathered here, beside the remainder's pass
+            SENSEI_TRY(launch_tiles_gather(D.T, reuse ? theta_h : x_src, A.n_cols, pad32(f_gather), D.Bh, D.side));
             SENSEI_TRY(hipEventRecord(D.ev_join, D.side));
             sensei_csr Ar = A;
             Ar.nnz = D.nnz_rem; Ar.row_ptr = D.row_ptr_rem; Ar.col_idx = D.col_rem; Ar.panels = nullptr; Ar.tiles = nullptr;
@@ -557,7 +560,7 @@ int run_gat(const sensei_csr &A, const sensei_mat &X, const sensei_mat &W, const
         } else {
             SENSEI_TRY(launch_attention_stats(A, s_l, s_r, slope, logits, by_panel ? A.panels->position : nullptr, plan, stats, carry_stats, s));
         }
-        const AttnVectors attn = {s_l, s_r, slope};
+        const AttnVectors attn = {s_l, s_r, slope, by_tiles};
         sensei_csr Aw = A;
         Aw.val = logits;
         float *Y_h = Y + (size_t)h * d;

@@ -794,12 +794,21 @@ hipError_t launch_gemm(const float *A, int64_t lda, const float *W, int64_t ldw,
     return done(gemm_launch_vec<64, 64, 2, 2>(g, avec, bvec, s));
 }
 
-hipError_t launch_dense_tiles(const TileSplit &T, const float *B_sliced, int64_t n_cols, int f, float *Bh, hipStream_t s, const float *s_l,
-                              const float *s_r, const float2 *mz, float slope, bool transposed) {
+hipError_t launch_tiles_gather(const TileSplit &T, const float *B_sliced, int64_t n_cols, int f, float *Bh, hipStream_t s) {
     if (T.n_slots <= 0 || f <= 0) return hipSuccess;
     const long long n_ranks = (long long)T.nt_c * 128;
     hipLaunchKernelGGL(k_gather_ranked_rows, dim3((unsigned)((n_ranks * (f / 4) + 255) / 256)), dim3(256), 0, s, B_sliced, (long long)n_cols, f,
-                       T.order_c, n_ranks, Bh, transposed ? mz : (const float2 *)nullptr);
+                       T.order_c, n_ranks, Bh, (const float2 *)nullptr);
+    return hipGetLastError();
+}
+
+hipError_t launch_dense_tiles(const TileSplit &T, const float *B_sliced, int64_t n_cols, int f, float *Bh, hipStream_t s, const float *s_l,
+                              const float *s_r, const float2 *mz, float slope, bool transposed, bool gathered) {
+    if (T.n_slots <= 0 || f <= 0) return hipSuccess;
+    const long long n_ranks = (long long)T.nt_c * 128;
+    if (!gathered)
+        hipLaunchKernelGGL(k_gather_ranked_rows, dim3((unsigned)((n_ranks * (f / 4) + 255) / 256)), dim3(256), 0, s, B_sliced, (long long)n_cols, f,
+                           T.order_c, n_ranks, Bh, transposed ? mz : (const float2 *)nullptr);
     DenseTilesArgs g;
     g.bits = T.bits; g.seg_first = T.seg_first; g.slot_ct = T.slot_ct;
     g.Bh = Bh; g.ldbh = f; g.part = T.part;

@@ -181,7 +181,10 @@ hipError_t launch_compact_values(int64_t nnz, const int32_t *dst_rem, const floa
 // exp(LeakyReLU(s_l[i] + s_r[j]) - mz[i].x) / mz[i].y, the complete coefficient alpha_ij (the division is applied to the rows of B).
 hipError_t launch_dense_tiles(const TileSplit &T, const float *B_sliced, int64_t n_cols, int f, float *Bh, hipStream_t s,
                               const float *s_l = nullptr, const float *s_r = nullptr, const float2 *mz = nullptr, float slope = 0.f,
-                              bool transposed = false);
+                              bool transposed = false, bool gathered = false);
+// the first step of launch_dense_tiles on its own: Bh = rows of B in rank order.  A caller that has other work to wait for can run it
+// early and pass gathered = true afterwards (not for the transposed mode, whose rows are scaled while they are gathered).
+hipError_t launch_tiles_gather(const TileSplit &T, const float *B_sliced, int64_t n_cols, int f, float *Bh, hipStream_t s);
 // Softmax statistics of the attention logits e_ij = LeakyReLU(s_l[i] + s_r[j]) over the entries inside kept tiles: T.seg_stats[seg][row]
 // = (max, sum of exp(e - max)) per segment and row of its row of tiles.  launch_tile_stats_merge folds them into stats[i] (which holds
 // the pair over the remainder's entries of row i on entry, over all stored entries on return).
