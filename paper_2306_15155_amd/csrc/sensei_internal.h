@@ -156,7 +156,7 @@ struct TileSplit {
     float *dh;                         // device: nt_r * 128 x (widest operand): the tiles' product, by row rank
     const int32_t *rank_r;             // device: rank of every row node (INT_MAX outside the tiled region)
 };
-constexpr int kTilesPerSegment = 8;
+constexpr int kTilesPerSegment = 16;
 constexpr int kMaxCellSlots = 131071;  // slots whose cells (slot * 16384 + ...) + 1 still fit a positive int32
 size_t scan_large_temp_bytes(long long n);
 hipError_t launch_exclusive_scan_large(int32_t *data, long long n, int32_t *temp, hipStream_t s);
