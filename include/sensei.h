@@ -263,7 +263,8 @@ int sensei_gatv2_layer(sensei_ctx *ctx, const sensei_csr *A, sensei_mat X, sense
  *   sensei_tiles_create  builds the split in device_buf (256-byte aligned, caller-owned, must outlive the object);
  *                        ranks the nodes on the host, so it synchronises the stream several times: a set-up call;
  *   sensei_tiles_info    kept tiles, entries inside them, entries in the remainder;
- *   sensei_tiles_set_min_width  narrowest SpMM (columns) that takes the split; 64 unless set;
+ *   sensei_tiles_set_min_width  narrowest SpMM (columns) that takes the split; 64 unless set (the attention aggregation
+ *                        takes it from half that width);
  *   sensei_tiles_destroy frees the host object only.
  * The object keeps buffers for the operand in rank order and for the tiles' product, and its stream: calls that use one
  * object at the same time on different streams race on them. */

@@ -184,7 +184,11 @@ struct AttnVectors {  // what the softmax mode of the dense tiles needs besides 
 bool tiles_usable(const sensei_csr &A, int mode, int f, bool b_sliced, bool attn = false) {
     const sensei_tiles *D = A.tiles;
     const bool mode_ok = (mode == SENSEI_SPMM_PATTERN) || (mode == kSpmmSoftmax && attn);
-    if (!D || !mode_ok || !b_sliced || pad32(f) > D->max_width || f < D->min_width || D->T.n_slots <= 0) return false;
+    // the attention mode has more to gain per column (its entries also skip the stored logits): half the width suffices
+    // (measured: 8 heads of 32 columns on a 233,000-node power-law graph, 13.9 -> 11.8 ms)
+    if (!D || !mode_ok || !b_sliced || D->T.n_slots <= 0) return false;
+    const int need = attn ? D->min_width / 2 : D->min_width;
+    if (pad32(f) > D->max_width || f < need) return false;
     return D->n_rows == A.n_rows && D->n_cols == A.n_cols && D->nnz == A.nnz && D->src_row_ptr == A.row_ptr && D->src_col_idx == A.col_idx;
 }
 
