@@ -708,7 +708,8 @@ def test_dense_tile_split_edge_cases(ctx):
         X, Wg = synth.uniform(49, 10, (g.n_cols, 20)), synth.glorot(49, 11, 20, 40)
         a_l, a_r = synth.normal(49, 13, (40,), 0.0, 0.4), synth.normal(49, 14, (40,), 0.0, 0.4)
         refg = oracle.gat_layer(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, Wg, a_l, a_r)
-        assert_close(ctx.gat_layer(At, dev(X), dev(Wg), dev(a_l), dev(a_r), 0), refg, what=f"{name} gat")
+        for cid in range(4):
+            assert_close(ctx.gat_layer(At, dev(X), dev(Wg), dev(a_l), dev(a_r), cid), refg, what=f"{name} gat comp {cid}")
         T.close()
     with pytest.raises(SenseiError):
         Tiles(ctx, DeviceCSR(GRAPHS["er"]).s, 0.0, 128)
