@@ -103,3 +103,28 @@ def test_variant_layer_and_tile_queries_need_no_gpu():
     assert L.sensei_tiles_destroy(None) == 0
     out = C.c_void_p()
     assert L.sensei_tiles_create(None, C.byref(A), 0.09, 256, None, 0, None, C.byref(out)) == 1
+
+
+def test_gat_backward_workspace_query_takes_both_patterns():
+    """The query sees the pattern and its transpose as the layer call will (either may carry a dense-tile split); the transpose may
+    be left out when it carries none.  Host arithmetic only."""
+    import ctypes as C
+    from paper_2306_15155_amd import binding
+    L = binding.lib()
+    A = binding.CsrStruct(1000, 1200, 50_000, 0x1000, 0x2000, None)
+    At = binding.CsrStruct(1200, 1000, 50_000, 0x3000, 0x4000, None)
+    n = C.c_size_t()
+    assert L.sensei_gat_backward_workspace(C.byref(A), C.byref(At), 64, 32, C.byref(n)) == 0 and n.value > 0
+    both = n.value
+    assert L.sensei_gat_backward_workspace(C.byref(A), None, 64, 32, C.byref(n)) == 0 and n.value == both   # no split on either
+    assert L.sensei_gat_backward_workspace(C.byref(A), C.byref(At), 64, 128, C.byref(n)) == 0 and n.value > both
+    assert L.sensei_gat_backward_workspace(None, C.byref(At), 64, 32, C.byref(n)) == 1
+    assert L.sensei_gat_backward_workspace(C.byref(A), C.byref(At), 0, 32, C.byref(n)) == 1
+    assert L.sensei_gat_backward_workspace(C.byref(A), C.byref(At), 64, 32, None) == 1
+
+
+def test_bench_refuses_more_than_one_gpu_before_touching_one():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2 and "one GPU only" in r.stderr and r.stdout.strip() == ""
