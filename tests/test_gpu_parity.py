@@ -693,6 +693,29 @@ def test_dense_tile_split_gives_the_same_spmm_and_layers(ctx, density):
     T.close()
 
 
+def test_dense_tile_split_attention_with_large_logits(ctx):
+    """Logits of magnitude 10^2: every exponential of the split path (tile statistics, their merge with the remainder's, the weights
+    the tile kernel forms) is taken relative to a maximum, so nothing overflows and rows whose largest logit sits in a tile, in the
+    remainder, or in both agree with the oracle."""
+    from paper_2306_15155_amd import Tiles, csr_struct
+    g = synth.rmat(51, 5000, 150_000)
+    A = DeviceCSR(g)
+    T = Tiles(ctx, A.s, 0.05, 128, min_width=32)
+    assert T.n_tiles > 0 and T.nnz_sparse > 0
+    At = csr_struct(g.n_rows, g.n_cols, A.row_ptr, A.col_idx, None, None, T)
+    f_in, f_out = 24, 64
+    X, W = synth.uniform(51, 10, (g.n_cols, f_in)), synth.glorot(51, 11, f_in, f_out)
+    a_l, a_r = synth.normal(51, 13, (f_out,), 0.0, 12.0), synth.normal(51, 14, (f_out,), 0.0, 12.0)
+    Th = X.astype(np.float64) @ W.astype(np.float64)
+    assert np.abs(Th @ a_r.astype(np.float64)).max() > 60.0   # the logits really are large
+    ref = oracle.gat_layer(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, a_l, a_r, 0.2, ACT_NONE)
+    for cid in range(4):
+        got = ctx.gat_layer(At, dev(X), dev(W), dev(a_l), dev(a_r), cid, 0.2, ACT_NONE)
+        assert torch.isfinite(got).all()
+        assert_close(got, ref, what=f"large logits, comp {cid}")
+    T.close()
+
+
 def test_dense_tile_split_edge_cases(ctx):
     from paper_2306_15155_amd import Tiles, csr_struct
     # rectangular block, a graph with a hub and empty rows, a graph too small for a full tile, self loops only
