@@ -197,6 +197,36 @@ def test_gat_backward_on_a_dense_tile_split(ctx, widths):
     T.close()
 
 
+def test_gat_backward_on_a_dense_tile_split_with_large_logits(ctx):
+    """Logits of a few tens: the coefficients the transposed tile kernel forms are exp(e - max of the column's softmax row) / sum,
+    never larger than one, whichever side of the split holds the row's maximum.  Gradients grow with the attention vectors, and at
+    this magnitude fp32 itself leaves about 1e-4 (dX) and 3e-4 (dW) of scaled error against the fp64 oracle with or without a split,
+    so the split path is held to the error of the plain path on the same inputs (and both to 5e-4)."""
+    from paper_2306_15155_amd import Tiles, csr_struct
+    g = synth.rmat(78, 5000, 150_000)
+    f_in, f_out = 32, 128
+    X, W, dY = _inputs(g, f_in, f_out, 79)
+    a_l, a_r = synth.normal(79, 20, (f_out,), 0.0, 3.0), synth.normal(79, 21, (f_out,), 0.0, 3.0)
+    Th = X.astype(np.float64) @ W.astype(np.float64)
+    assert np.abs(Th @ a_r.astype(np.float64)).max() > 20.0
+    want = oracle.gat_backward(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, a_l, a_r, dY, slope=0.2)
+    A = DeviceCSR(g)
+    T = Tiles(ctx, A.s, 0.05, 128, min_width=32)
+    assert T.n_tiles > 0 and T.nnz_sparse > 0
+    Ah = csr_struct(g.n_rows, g.n_cols, A.row_ptr, A.col_idx, None, None, T)
+    pos = ctx.transpose_positions(A.s, A.s)
+
+    def scaled_errors(first, second):
+        got = ctx.gat_backward(first, second, pos, dev(X), dev(W), dev(a_l), dev(a_r), dev(dY))
+        assert all(torch.isfinite(t).all() for t in got)
+        return [float(np.max(np.abs(t.cpu().numpy().astype(np.float64) - ref) / (1.0 + np.abs(ref)))) for t, ref in zip(got, want)]
+
+    plain, split = scaled_errors(A.s, A.s), scaled_errors(Ah, Ah)
+    for what, e_plain, e_split in zip(("dX", "dW", "da_l", "da_r"), plain, split):
+        assert e_split <= max(1e-4, 1.5 * e_plain) and e_split <= 5e-4, f"{what}: split {e_split:.2e}, plain {e_plain:.2e}"
+    T.close()
+
+
 def test_gat_backward_with_a_split_of_a_rectangular_transposed_pattern(ctx):
     """Fewer destinations than sources: the transposed pattern is a matrix of its own with its own tile split, whose rows are
     the sources and whose columns are the destinations."""
