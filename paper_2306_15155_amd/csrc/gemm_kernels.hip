@@ -328,7 +328,7 @@ __global__ void k_tiles_reduce(const float *__restrict__ part, const int32_t *__
 // and applies what the SpMM epilogue would have applied (scale_i = r[i], or 1 / z_i in attention mode)
 __global__ void k_tiles_combine(float *__restrict__ C, long long n_rows, int f_store, long long ldc, long long c_tile, const float *__restrict__ Dh,
                                 int f, const int32_t *__restrict__ rank_r, int n_ranks, const float *__restrict__ r, const float2 *__restrict__ mz,
-                                int act) {
+                                int act, int vec4) {
     const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     const int f4 = (f_store + 3) / 4;
     if (t >= n_rows * f4) return;
@@ -340,6 +340,19 @@ __global__ void k_tiles_combine(float *__restrict__ C, long long n_rows, int f_s
     else if (r) sc = r[i];
     float *dst = C + (long long)(col >> 5) * c_tile + i * ldc + (col & 31);
     const float *add = (rank < n_ranks) ? Dh + (size_t)rank * f + col : nullptr;
+    if (vec4 && col + 3 < f_store) {  // 16-byte accesses when the caller found every row start aligned
+        float4 y = *reinterpret_cast<const float4 *>(dst);
+        if (add) {
+            const float4 a4 = *reinterpret_cast<const float4 *>(add);
+            y.x += a4.x; y.y += a4.y; y.z += a4.z; y.w += a4.w;
+        }
+        y.x *= sc; y.y *= sc; y.z *= sc; y.w *= sc;
+        if (act == SENSEI_ACT_RELU) {
+            y.x = y.x > 0.f ? y.x : 0.f; y.y = y.y > 0.f ? y.y : 0.f; y.z = y.z > 0.f ? y.z : 0.f; y.w = y.w > 0.f ? y.w : 0.f;
+        }
+        *reinterpret_cast<float4 *>(dst) = y;
+        return;
+    }
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
         if (col + e < f_store) {
@@ -872,9 +885,10 @@ hipError_t launch_tiles_combine(const TileSplit &T, float *C, int64_t n_rows, in
                                 const float2 *mz, int act, hipStream_t s) {
     if (n_rows <= 0 || f_store <= 0) return hipSuccess;
     const long long threads = (long long)n_rows * ((f_store + 3) / 4);
+    const int vec4 = (reinterpret_cast<uintptr_t>(C) % 16 == 0 && (c_sliced || ldc % 4 == 0)) ? 1 : 0;  // T.dh rows are f floats, f a multiple of 32
     hipLaunchKernelGGL(k_tiles_combine, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, C, (long long)n_rows, f_store,
                        c_sliced ? 32LL : (long long)ldc, c_sliced ? (long long)n_rows * 32 : 32LL, (const float *)T.dh, f, T.rank_r, T.nt_r * 128, r, mz,
-                       act);
+                       act, vec4);
     return hipGetLastError();
 }
 
