@@ -366,15 +366,34 @@ __global__ __launch_bounds__(kBlock) void k_spmm_fixup(SpmmArgs a) {
     const int c_last = (re - 1) / a.chunk_nnz;
     const float sc = a.mz ? inv_z(a.mz[i].y) : (a.r ? a.r[i] : 1.f);
     const int tf = a.c_tf;
-    for (int f = lane; f < a.f_store; f += 64) {
-        float *dst = a.C + (size_t)(f / tf) * a.c_tile + (size_t)i * a.ldc + (f % tf);
-        float acc = *dst;
-        for (int cc = c; cc <= c_last; ++cc) acc += a.carry[(size_t)cc * a.f_carry + f];
-        if (a.finalize) {
-            acc *= sc;
-            if (a.act == SENSEI_ACT_RELU) acc = acc > 0.f ? acc : 0.f;
+    // four columns per lane at a time: a hub row spans a hundred chunks, and one chain of dependent adds per column would
+    // leave the wavefront waiting for one load after the other; every column still adds its slots in chunk order
+    for (int f0 = lane; f0 < a.f_store; f0 += 4 * 64) {
+        float acc[4];
+        float *dst[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int f = f0 + 64 * q;
+            dst[q] = a.C + (size_t)(f / tf) * a.c_tile + (size_t)i * a.ldc + (f % tf);
+            acc[q] = f < a.f_store ? *dst[q] : 0.f;
         }
-        *dst = acc;
+#pragma unroll 4
+        for (int cc = c; cc <= c_last; ++cc) {
+            const float *slot = a.carry + (size_t)cc * a.f_carry + f0;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (f0 + 64 * q < a.f_store) acc[q] += slot[64 * q];
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (f0 + 64 * q >= a.f_store) continue;
+            float y = acc[q];
+            if (a.finalize) {
+                y *= sc;
+                if (a.act == SENSEI_ACT_RELU) y = y > 0.f ? y : 0.f;
+            }
+            *dst[q] = y;
+        }
     }
 }
 
