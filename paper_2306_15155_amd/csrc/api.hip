@@ -216,12 +216,13 @@ hipError_t spmm_any(const sensei_csr &A, int mode, const float *r, const float *
         if (e != hipSuccess) return e;
         sensei_csr Ar = A;
         Ar.nnz = D.nnz_rem; Ar.row_ptr = D.row_ptr_rem; Ar.col_idx = D.col_rem; Ar.panels = nullptr; Ar.tiles = nullptr;
+        // the SpMM leaves its carry slots to the combine pass, which visits every row anyway
         e = launch_spmm(Ar, mode, nullptr, c, B, ldb, f, C, ldc, f_store, SENSEI_ACT_NONE, D.plan_rem, carry, s, nullptr, false, false, mz, b_sliced, 1,
-                        c_sliced);
+                        c_sliced, true);
         if (e == hipSuccess) e = hipStreamWaitEvent(s, D.ev_join, 0);
         if (e == hipSuccess)
             e = launch_tiles_combine(D.T, C, A.n_rows, f_store, ldc, c_sliced, pad32(f), mode == kSpmmSoftmax ? nullptr : r,
-                                     mode == kSpmmSoftmax ? mz : nullptr, act, s);
+                                     mode == kSpmmSoftmax ? mz : nullptr, act, s, D.row_ptr_rem, D.plan_rem.chunk_nnz, carry, pad32(f));
         if (e != hipSuccess) return e;
         if (t1 && hipEventRecord(t1, s) != hipSuccess) return hipErrorUnknown;
         return hipSuccess;
@@ -770,9 +771,10 @@ int run_gat_backward(const sensei_csr &A, const sensei_csr &At, const int32_t *t
         sensei_csr Ar = At;
         Ar.nnz = D.nnz_rem; Ar.row_ptr = D.row_ptr_rem; Ar.col_idx = D.col_rem; Ar.val = alpha_rem; Ar.panels = nullptr; Ar.tiles = nullptr;
         SENSEI_TRY(launch_spmm(Ar, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, T, fo32, f_out, dTheta, fo4, f_out, SENSEI_ACT_NONE, D.plan_rem, carry, s,
-                               nullptr, false, false, nullptr, true, 1));
+                               nullptr, false, false, nullptr, true, 1, false, true));
         SENSEI_TRY(hipStreamWaitEvent(s, D.ev_join, 0));
-        SENSEI_TRY(launch_tiles_combine(D.T, dTheta, At.n_rows, f_out, fo4, false, fo32, nullptr, nullptr, SENSEI_ACT_NONE, s));
+        SENSEI_TRY(launch_tiles_combine(D.T, dTheta, At.n_rows, f_out, fo4, false, fo32, nullptr, nullptr, SENSEI_ACT_NONE, s, D.row_ptr_rem,
+                                        D.plan_rem.chunk_nnz, carry, fo32));
     } else {
         sensei_csr Aw = At;
         Aw.val = reinterpret_cast<const float *>(adt_t);

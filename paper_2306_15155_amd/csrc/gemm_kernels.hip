@@ -328,7 +328,7 @@ __global__ void k_tiles_reduce(const float *__restrict__ part, const int32_t *__
 // and applies what the SpMM epilogue would have applied (scale_i = r[i], or 1 / z_i in attention mode)
 __global__ void k_tiles_combine(float *__restrict__ C, long long n_rows, int f_store, long long ldc, long long c_tile, const float *__restrict__ Dh,
                                 int f, const int32_t *__restrict__ rank_r, int n_ranks, const float *__restrict__ r, const float2 *__restrict__ mz,
-                                int act, int vec4) {
+                                int act, int vec4, const int32_t *__restrict__ row_ptr, int chunk_nnz, const float *__restrict__ carry, int f_carry) {
     const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     const int f4 = (f_store + 3) / 4;
     if (t >= n_rows * f4) return;
@@ -340,8 +340,23 @@ __global__ void k_tiles_combine(float *__restrict__ C, long long n_rows, int f_s
     else if (r) sc = r[i];
     float *dst = C + (long long)(col >> 5) * c_tile + i * ldc + (col & 31);
     const float *add = (rank < n_ranks) ? Dh + (size_t)rank * f + col : nullptr;
+    // the SpMM's own fix-up, when the caller left it to this pass: a row that spans chunk boundaries has its later pieces in the
+    // carry slots of the chunks it continues into, c * chunk_nnz strictly inside the row; they are added in chunk order
+    long long c_first = 1, c_last = 0;
+    if (row_ptr) {
+        const long long rs = row_ptr[i], re = row_ptr[i + 1];
+        if (re > rs) {
+            c_first = rs / chunk_nnz + 1;
+            c_last = (re - 1) / chunk_nnz;
+        }
+    }
     if (vec4 && col + 3 < f_store) {  // 16-byte accesses when the caller found every row start aligned
         float4 y = *reinterpret_cast<const float4 *>(dst);
+#pragma unroll 4
+        for (long long c = c_first; c <= c_last; ++c) {
+            const float4 p = *reinterpret_cast<const float4 *>(carry + (size_t)c * f_carry + col);
+            y.x += p.x; y.y += p.y; y.z += p.z; y.w += p.w;
+        }
         if (add) {
             const float4 a4 = *reinterpret_cast<const float4 *>(add);
             y.x += a4.x; y.y += a4.y; y.z += a4.z; y.w += a4.w;
@@ -356,7 +371,9 @@ __global__ void k_tiles_combine(float *__restrict__ C, long long n_rows, int f_s
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
         if (col + e < f_store) {
-            float y = (dst[e] + (add ? add[e] : 0.f)) * sc;
+            float y = dst[e];
+            for (long long c = c_first; c <= c_last; ++c) y += carry[(size_t)c * f_carry + col + e];
+            y = (y + (add ? add[e] : 0.f)) * sc;
             if (act == SENSEI_ACT_RELU) y = y > 0.f ? y : 0.f;
             dst[e] = y;
         }
@@ -882,13 +899,16 @@ hipError_t launch_tiles_sddmm(const TileSplit &T, const float *L_sliced, int64_t
 }
 
 hipError_t launch_tiles_combine(const TileSplit &T, float *C, int64_t n_rows, int f_store, int64_t ldc, bool c_sliced, int f, const float *r,
-                                const float2 *mz, int act, hipStream_t s) {
+                                const float2 *mz, int act, hipStream_t s, const int32_t *row_ptr_rem, int chunk_nnz, const float *carry, int f_carry) {
     if (n_rows <= 0 || f_store <= 0) return hipSuccess;
     const long long threads = (long long)n_rows * ((f_store + 3) / 4);
-    const int vec4 = (reinterpret_cast<uintptr_t>(C) % 16 == 0 && (c_sliced || ldc % 4 == 0)) ? 1 : 0;  // T.dh rows are f floats, f a multiple of 32
+    // T.dh rows are f floats, f a multiple of 32; carry slots are f_carry floats apart
+    const int vec4 = (reinterpret_cast<uintptr_t>(C) % 16 == 0 && (c_sliced || ldc % 4 == 0) &&
+                      (!carry || (f_carry % 4 == 0 && reinterpret_cast<uintptr_t>(carry) % 16 == 0))) ? 1 : 0;
+    if (!carry || chunk_nnz <= 0) row_ptr_rem = nullptr;
     hipLaunchKernelGGL(k_tiles_combine, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, C, (long long)n_rows, f_store,
                        c_sliced ? 32LL : (long long)ldc, c_sliced ? (long long)n_rows * 32 : 32LL, (const float *)T.dh, f, T.rank_r, T.nt_r * 128, r, mz,
-                       act, vec4);
+                       act, vec4, row_ptr_rem, chunk_nnz, carry, f_carry);
     return hipGetLastError();
 }
 

@@ -61,10 +61,12 @@ size_t spmm_carry_bytes(int64_t nnz, int f);  // upper bound
 hipError_t launch_spmm(const sensei_csr &A, int mode, const float *r, const float *c, const float *B, int64_t ldb,
                        int f, float *C, int64_t ldc, int f_store, int act, const ChunkPlan &p, float *carry,
                        hipStream_t s, KernelTimer *timer = nullptr, bool accumulate = false, bool finalize = true,
-                       const float2 *mz = nullptr, bool b_sliced = false, int val_stride = 1, bool c_sliced = false);
+                       const float2 *mz = nullptr, bool b_sliced = false, int val_stride = 1, bool c_sliced = false, bool defer_fixup = false);
 // b_sliced: B is stored slice-major in tiles of 32 floats, element (j, col) at B[(col / 32) * n_cols * 32 + j * 32 + col % 32]
 // (f padded to a multiple of 32, B 128-byte aligned); `ldb` is ignored.  val_stride: floats between consecutive values of A.val.
 // c_sliced (needs b_sliced, f a multiple of 32, f_store == f): C is written slice-major too (n_rows x f), `ldc` is ignored.
+// defer_fixup (with finalize = false and a slice-major B): the pass that adds the carry slots of rows spanning chunk boundaries is
+// left to the caller (launch_tiles_combine does it); the slots are pad32(f) floats apart.
 inline size_t sliced_index(int64_t n_rows, int64_t row, int col) { return (size_t)(col >> 5) * (size_t)n_rows * 32 + (size_t)row * 32 + (col & 31); }
 // Internal SpMM mode (not part of the C ABI): A.val holds attention logits e_ij, `mz[i]` = (max_j e_ij, sum_j exp(e_ij - max));
 // the kernel weighs neighbour j of row i by exp(e_ij - max_i) and scales the finished row by 1 / sum, i.e. it aggregates
@@ -197,7 +199,10 @@ hipError_t launch_tiles_sddmm(const TileSplit &T, const float *L_sliced, int64_t
                               float *Rh, float *Dt, hipStream_t s);
 // C = act(scale (C + T.dh[rank of the row])) over all rows; scale_i = 1 / mz[i].y if mz, else r[i] if r, else 1
 hipError_t launch_tiles_combine(const TileSplit &T, float *C, int64_t n_rows, int f_store, int64_t ldc, bool c_sliced, int f, const float *r,
-                                const float2 *mz, int act, hipStream_t s);
+                                const float2 *mz, int act, hipStream_t s, const int32_t *row_ptr_rem = nullptr, int chunk_nnz = 0,
+                                const float *carry = nullptr, int f_carry = 0);
+// row_ptr_rem, chunk_nnz, carry, f_carry: when the SpMM over the remainder ran with defer_fixup, this pass also adds the carry slots
+// (f_carry floats each) of the rows that span chunk boundaries, in chunk order, before anything else.
 
 // ---- dense
 // Y[0:n, 0:m_store) = act(row_scale[i] * (A[n x k] . W[k x m])); columns m..m_store are written as act(0);

@@ -1518,7 +1518,7 @@ size_t spmm_carry_bytes(int64_t nnz, int f) {
 hipError_t launch_spmm(const sensei_csr &A, int mode, const float *r, const float *c, const float *B, int64_t ldb,
                        int f, float *C, int64_t ldc, int f_store, int act, const ChunkPlan &p, float *carry,
                        hipStream_t s, KernelTimer *timer, bool accumulate, bool finalize, const float2 *mz, bool b_sliced, int val_stride,
-                       bool c_sliced) {
+                       bool c_sliced, bool defer_fixup) {
     SpmmShape sh = spmm_shape(B, ldb, f);
     if (b_sliced) {  // slices of 32 floats per row: one 128-byte line per neighbour and tile
         sh.vec = 4; sh.lpg = 8; sh.n_tiles = (f + 31) / 32; sh.f_carry = sh.n_tiles * 32;
@@ -1561,7 +1561,7 @@ hipError_t launch_spmm(const sensei_csr &A, int mode, const float *r, const floa
     }
     if (err != hipSuccess) return err;
     if (t1 && hipEventRecord(t1, s) != hipSuccess) return hipErrorUnknown;
-    if (p.n_chunks > 1) {
+    if (p.n_chunks > 1 && !(defer_fixup && b_sliced && !finalize)) {
         dim3 fg(blocks_for(p.n_chunks - 1, kWavesPerBlock));
         hipLaunchKernelGGL(k_spmm_fixup, fg, dim3(kBlock), 0, s, a);
         err = hipGetLastError();
