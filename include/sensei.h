@@ -181,6 +181,10 @@ int sensei_degrees(sensei_ctx *ctx, const sensei_csr *A, int32_t *deg_row, int32
  * form of D~^(-1/2) (Eq. 3).  deg, out: device, n entries. */
 int sensei_norm_vectors(sensei_ctx *ctx, const int32_t *deg, int64_t n, float *out, void *stream);
 
+/* Stored entries per chunk (= per 64-lane wavefront) that every sparse kernel uses on a pattern of `nnz` entries: 64, 128, 256
+ * or 512, growing with nnz (small graphs are latency bound and get more, shorter wavefronts).  Host arithmetic; 0 if nnz < 0. */
+int sensei_chunk_nnz(int64_t nnz);
+
 /* Upper bound, in bytes, on the workspace any sparse primitive below needs for this matrix at
  * feature width `f` (host pointers). */
 int sensei_sparse_workspace(const sensei_csr *A, int f, size_t *bytes);

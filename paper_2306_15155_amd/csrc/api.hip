@@ -1464,6 +1464,8 @@ int sensei_norm_vectors(sensei_ctx *ctx, const int32_t *deg, int64_t n, float *o
     return hip_status(launch_norm_vectors(deg, n, out, as_stream(stream)));
 }
 
+int sensei_chunk_nnz(int64_t nnz) { return nnz < 0 ? 0 : choose_chunk_nnz(nnz); }
+
 int sensei_sparse_workspace(const sensei_csr *A, int f, size_t *bytes) {
     if (!csr_ok(A, false) || f < 0 || !bytes) return SENSEI_INVALID_ARGUMENT;
     *bytes = sparse_ws(*A, pad32(f));

@@ -118,17 +118,97 @@ def test_config4_gat_increasing_sizes(ctx, reddit_like):
         assert_close(Y[sel], ref, what=f"GAT 64->256 comp {cid}")
 
 
-@pytest.mark.parametrize("h", [32, 128])
+@pytest.mark.parametrize("h", [32, 128, 512, 1024])
 def test_config3_embedding_sweep(ctx, products_like, h):
+    """Both layers of the sweep (100 -> h with ReLU, h -> h) in all six compositions at every hidden size of the workload.  From
+    h = 512 on the full oracle is out of reach on the host: the row-sampled oracle evaluates the longest row, a shortest one and
+    1,000 random rows exactly.  At h = 1024 the dense operands hold 2.5e9 elements (more than 2^31) and the h x h update dominates."""
     g = products_like
     A = DeviceCSR(g)
     N = g.n_rows
     r, c, Apre, _ = _norm(ctx, A)
     rows = _sample_rows(g, 3)
+    assert rows.size >= 1000 and int(np.diff(g.row_ptr).argmax()) in rows
     X = synth.normal(7, 30, (N, 100))
-    _check_gcn_all_ids(ctx, g, A, Apre, r, c, X, synth.glorot(7, 31, 100, h), ACT_RELU, rows, f"C3 100->{h}")
+    Y = _check_gcn_all_ids(ctx, g, A, Apre, r, c, X, synth.glorot(7, 31, 100, h), ACT_RELU, rows, f"C3 100->{h}")
+    del Y, X
+    torch.cuda.empty_cache()
     H = synth.uniform(7, 33, (N, h), 0.0, 1.0)  # seeded stand-in for the hidden activations
-    _check_gcn_all_ids(ctx, g, A, Apre, r, c, H, synth.glorot(7, 32, h, h), ACT_NONE, rows, f"C3 {h}->{h}")
+    if h == 1024:
+        assert H.size > (1 << 31)
+    Y = _check_gcn_all_ids(ctx, g, A, Apre, r, c, H, synth.glorot(7, 32, h, h), ACT_NONE, rows, f"C3 {h}->{h}")
+    del Y, H
+    ctx.ws.buf = torch.empty(0, dtype=torch.uint8, device=DEV)   # give the workspace of the widest layers back
+    torch.cuda.empty_cache()
+
+
+@pytest.fixture(scope="module")
+def road_like():
+    """Road-network shape (the sparsest graph of the paper's table: a few links per node, no hubs): a 4,100 x 4,100 grid with
+    53 % of its links kept, 16.8 M nodes (more than 2^24: the slice-major gathers take their 64-bit address path), 3.1 stored
+    entries per row."""
+    return synth.thinned_grid(5, 4100, 0.53)
+
+
+def test_road_shaped_graph_gcn_all_compositions(ctx, road_like):
+    g = road_like
+    N = g.n_rows
+    assert N > (1 << 24) and g.nnz < 4 * N
+    A = DeviceCSR(g)
+    r, c, Apre, (dr, dc) = _norm(ctx, A)
+    want_r, want_c = oracle.degrees(N, N, g.row_ptr, g.col_idx)
+    assert dr.cpu().numpy().tobytes() == want_r.tobytes() and dc.cpu().numpy().tobytes() == want_c.tobytes()
+    rows = np.unique(np.concatenate([_sample_rows(g, 21), [N - 1, N - 2, (1 << 24) + 1]])).astype(np.int32)   # rows whose neighbours lie past 2^24
+    X = synth.normal(5, 10, (N, 32))
+    _check_gcn_all_ids(ctx, g, A, Apre, r, c, X, synth.glorot(5, 11, 32, 64), ACT_RELU, rows, "road 32->64")
+    _check_gcn_all_ids(ctx, g, A, Apre, r, c, X, synth.glorot(5, 12, 32, 8), ACT_NONE, rows, "road 32->8")
+    ctx.ws.buf = torch.empty(0, dtype=torch.uint8, device=DEV)
+    torch.cuda.empty_cache()
+
+
+def test_road_shaped_graph_gat_all_compositions(ctx, road_like):
+    g = road_like
+    N = g.n_rows
+    A = DeviceCSR(g)
+    rows = np.unique(np.concatenate([_sample_rows(g, 22, 600), [N - 1, (1 << 24) + 1]])).astype(np.int32)
+    sel = torch.from_numpy(rows.astype(np.int64)).to(DEV)
+    X = synth.normal(5, 10, (N, 32))
+    Xd = dev(X)
+    for f_out in (64, 8):
+        W = synth.glorot(5, 13, 32, f_out)
+        a_l, a_r = synth.normal(5, 14, (f_out,), 0.0, 0.1), synth.normal(5, 15, (f_out,), 0.0, 0.1)
+        ref = oracle.gat_layer(N, N, g.row_ptr, g.col_idx, X, W, a_l, a_r, 0.2, ACT_RELU, rows=rows, omp=True)
+        for cid in range(4):
+            Y = ctx.gat_layer(A.s, Xd, dev(W), dev(a_l), dev(a_r), cid, 0.2, ACT_RELU)
+            assert_close(Y[sel], ref, what=f"road GAT 32->{f_out} comp {cid}")
+            del Y
+    ctx.ws.buf = torch.empty(0, dtype=torch.uint8, device=DEV)
+    torch.cuda.empty_cache()
+
+
+def test_very_dense_uniform_graph_all_compositions(ctx):
+    """The densest shape of the paper's table: 98,000 nodes, 1e8 stored entries spread uniformly (mean degree 1,021, no hubs, so
+    no dense-tile region either): GCN in all six compositions in both size orders, GAT in all four."""
+    g = synth.erdos_renyi(3, 98_000, 50_000_000)
+    N = g.n_rows
+    assert g.nnz > 99_000_000
+    A = DeviceCSR(g)
+    r, c, Apre, _ = _norm(ctx, A)
+    rows = _sample_rows(g, 23, 600)
+    X = synth.uniform(3, 10, (N, 256))
+    _check_gcn_all_ids(ctx, g, A, Apre, r, c, X, synth.glorot(3, 11, 256, 64), ACT_RELU, rows, "dense 256->64")
+    X64 = np.ascontiguousarray(X[:, :64])
+    _check_gcn_all_ids(ctx, g, A, Apre, r, c, X64, synth.glorot(3, 12, 64, 256), ACT_NONE, rows, "dense 64->256")
+    W = synth.glorot(3, 13, 64, 256)
+    a_l, a_r = synth.normal(3, 14, (256,), 0.0, 0.1), synth.normal(3, 15, (256,), 0.0, 0.1)
+    ref = oracle.gat_layer(N, N, g.row_ptr, g.col_idx, X64, W, a_l, a_r, 0.2, ACT_RELU, rows=rows, omp=True)
+    sel = torch.from_numpy(rows.astype(np.int64)).to(DEV)
+    for cid in range(4):
+        Y = ctx.gat_layer(A.s, dev(X64), dev(W), dev(a_l), dev(a_r), cid, 0.2, ACT_RELU)
+        assert_close(Y[sel], ref, what=f"dense GAT 64->256 comp {cid}")
+        del Y
+    ctx.ws.buf = torch.empty(0, dtype=torch.uint8, device=DEV)
+    torch.cuda.empty_cache()
 
 
 def test_config5_sampled_minibatch(ctx, products_like):
