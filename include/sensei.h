@@ -39,7 +39,8 @@ typedef enum {
     SENSEI_INVALID_COMPOSITION = 2,
     SENSEI_WORKSPACE_TOO_SMALL = 3,
     SENSEI_HIP_ERROR = 4,          /* a HIP runtime call or a launch failed */
-    SENSEI_UNSUPPORTED = 5
+    SENSEI_UNSUPPORTED = 5,
+    SENSEI_SCRATCH_TOO_SMALL = 6   /* sensei_spmm_static: the input needs more than SENSEI_STATIC_SCRATCH_BYTES */
 } sensei_status;
 
 typedef struct sensei_ctx sensei_ctx; /* opaque: device id and cost-model calibration only */
@@ -203,6 +204,20 @@ int sensei_row_broadcast(sensei_ctx *ctx, const float *s, sensei_mat X, float *Y
  * SENSEI_SPMM_SCALED only (NULL otherwise); A->val by SENSEI_SPMM_WEIGHTED only. */
 int sensei_spmm(sensei_ctx *ctx, const sensei_csr *A, int mode, const float *r, const float *c, sensei_mat B,
                 float *C, int64_t ldc, int activation, void *workspace, size_t ws_bytes, void *stream);
+
+/* sensei_spmm for callers that cannot allocate device memory or hand over a workspace: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same result and same kernels as sensei_spmm without the
+ * workspace pair: the chunk plan and the carry slots live in a static device array of SENSEI_STATIC_SCRATCH_BYTES that each
+ * GPU the library runs on holds until the process ends (its address is resolved by sensei_create).  The call allocates
+ * nothing, creates no events and uses no second stream; A->panels and A->tiles are ignored and B is gathered as it is
+ * (row-major).  Inputs that need more scratch (about 4 bytes per 512 stored entries for the plan plus
+ * ceil(nnz / chunk) * (pad32(B.cols) + 256) * 4 bytes of carry slots, chunk = 64..512 entries by nnz) are rejected with
+ * SENSEI_SCRATCH_TOO_SMALL and launch nothing.  Every call on a GPU shares that GPU's array: calls that overlap in time on
+ * one GPU (different streams, or graphs replayed concurrently) race on it; calls in stream order are safe.  `stream` must
+ * belong to the context's device. */
+#define SENSEI_STATIC_SCRATCH_BYTES (32u << 20)
+int sensei_spmm_static(sensei_ctx *ctx, const sensei_csr *A, int mode, const float *r, const float *c, sensei_mat B, float *C,
+                       int64_t ldc, int activation, void *stream);
 
 /* Dense update Y = act(A . W) on the fp32 matrix cores (background: dense primitives).
  * A: n x k, W: k x m, Y: n x m with leading dimension ldy. */

@@ -26,7 +26,7 @@ GAT_NAMES = ("REUSE", "RECOMP", "RECOMP_FOLD", "REUSE_FOLD")
 EXPORTS = (
     "sensei_create", "sensei_destroy", "sensei_calibrate", "sensei_num_compositions", "sensei_composition_name",
     "sensei_status_string", "sensei_degrees", "sensei_norm_vectors", "sensei_sparse_workspace", "sensei_chunk_nnz", "sensei_gcn_precompute",
-    "sensei_row_broadcast", "sensei_spmm", "sensei_gemm", "sensei_gemv2", "sensei_sddmm_score", "sensei_edge_softmax",
+    "sensei_row_broadcast", "sensei_spmm", "sensei_spmm_static", "sensei_gemm", "sensei_gemv2", "sensei_sddmm_score", "sensei_edge_softmax",
     "sensei_gcn_workspace", "sensei_gcn_layer", "sensei_gat_workspace", "sensei_gat_layer", "sensei_select_workspace",
     "sensei_select", "sensei_profile_enable", "sensei_profile_read", "sensei_panels_bytes", "sensei_panels_create",
     "sensei_panels_count", "sensei_panels_destroy", "sensei_panels_set_min_width", "sensei_panels_tune_bytes",
@@ -79,6 +79,7 @@ def lib():
         L.sensei_gcn_precompute.argtypes = [vp, P(CsrStruct), vp, vp, vp, vp, sz, vp]
         L.sensei_row_broadcast.argtypes = [vp, vp, MatStruct, vp, i64, vp]
         L.sensei_spmm.argtypes = [vp, P(CsrStruct), i32, vp, vp, MatStruct, vp, i64, i32, vp, sz, vp]
+        L.sensei_spmm_static.argtypes = [vp, P(CsrStruct), i32, vp, vp, MatStruct, vp, i64, i32, vp]
         L.sensei_gemm.argtypes = [vp, MatStruct, MatStruct, vp, i64, i32, vp]
         L.sensei_gemv2.argtypes = [vp, MatStruct, vp, vp, vp, vp, vp]
         L.sensei_sddmm_score.argtypes = [vp, P(CsrStruct), vp, vp, f32, vp, vp, sz, vp]
@@ -327,6 +328,12 @@ class Context:
         _check(lib().sensei_spmm(self._h, ctypes.byref(A), mode, _ptr(r), _ptr(c), mat_struct(B), _ptr(C), mat_struct(C).ld,
                                  activation, self.ws.ptr, self.ws.nbytes, _stream()), "sensei_spmm")
         return C
+
+    def spmm_static(self, A: CsrStruct, mode, B, out, r=None, c=None, activation=ACT_NONE):
+        """sensei_spmm_static: the caller passes the output; nothing is allocated on either side of the boundary."""
+        _check(lib().sensei_spmm_static(self._h, ctypes.byref(A), mode, _ptr(r), _ptr(c), mat_struct(B), _ptr(out), mat_struct(out).ld,
+                                        activation, _stream()), "sensei_spmm_static")
+        return out
 
     def gemm(self, A, W, activation=ACT_NONE, out=None):
         Y = torch.empty((A.size(0), W.size(1)), dtype=torch.float32, device=self.device) if out is None else out

@@ -19,7 +19,13 @@ struct sensei_ctx {
     double gemm_flops;     // achieved fp32 MFMA rate on large tiles
     double l2_slice_bytes; // feature-slice footprint at which 88 % of the gathers are served by the L2s
     Timers timers;         // optional per-launch timing of the SpMM and GEMM kernels
+    void *scratch;         // device address of the static scratch array on this context's GPU (sensei_spmm_static)
 };
+
+// Scratch memory of sensei_spmm_static (chunk plan + carry slots): a file-scope device array, so every GPU the library is
+// loaded on holds its own copy at its own address until the process ends.  In host code the name is only a stand-in for the
+// symbol: the device address comes from hipGetSymbolAddress (sensei_create, once per device) and is what the kernels get.
+static __device__ __align__(256) unsigned char scratch[SENSEI_STATIC_SCRATCH_BYTES];
 
 // Column-panel copy of a pattern (host descriptor; the arrays live in the caller's device buffer).
 struct sensei_panels {
@@ -58,6 +64,9 @@ namespace {
 const char *kGcnNames[] = {"DYN_AGG", "DYN_UPD", "DYNF_AGG", "DYNF_UPD", "PRE_AGG", "PRE_UPD"};
 const char *kGatNames[] = {"REUSE", "RECOMP", "RECOMP_FOLD", "REUSE_FOLD"};
 constexpr int kNumGcn = 6, kNumGat = 4;
+
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices] = {};  // device address of `scratch` per GPU, resolved by the first sensei_create on that GPU
 
 inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
 inline int hip_status(hipError_t e) { return e == hipSuccess ? SENSEI_OK : SENSEI_HIP_ERROR; }
@@ -984,6 +993,28 @@ int sensei_create(sensei_ctx **out, int device) {
     c->gather_far_bps = 6.5e12;
     c->gemm_flops = 100.0e12;
     c->l2_slice_bytes = 29.8e6;
+    // address of this GPU's copy of the static scratch array: resolved once per device, with that device current
+    c->scratch = device < kMaxDevices ? g_scratch_ptr[device] : nullptr;
+    hipError_t e = hipSuccess;
+    if (!c->scratch) {
+        int prev = 0;
+        e = hipGetDevice(&prev);
+        if (e == hipSuccess) e = hipSetDevice(device);
+        if (e == hipSuccess) {
+            void *ptr = nullptr;
+            e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+            const hipError_t e2 = hipSetDevice(prev);
+            if (e == hipSuccess) e = e2;
+            if (e == hipSuccess) {
+                c->scratch = ptr;
+                if (device < kMaxDevices) g_scratch_ptr[device] = ptr;
+            }
+        }
+    }
+    if (e != hipSuccess || !c->scratch) {
+        delete c;
+        return SENSEI_HIP_ERROR;
+    }
     *out = c;
     return SENSEI_OK;
 }
@@ -1035,6 +1066,7 @@ const char *sensei_status_string(int status) {
         case SENSEI_WORKSPACE_TOO_SMALL: return "workspace too small";
         case SENSEI_HIP_ERROR: return "HIP error";
         case SENSEI_UNSUPPORTED: return "unsupported";
+        case SENSEI_SCRATCH_TOO_SMALL: return "input exceeds the static scratch buffer";
         default: return "unknown status";
     }
 }
@@ -1527,6 +1559,31 @@ int sensei_spmm(sensei_ctx *ctx, const sensei_csr *A, int mode, const float *r, 
     }
     return hip_status(spmm_any(*A, mode, scaled ? r : nullptr, scaled ? c : nullptr, src, B.ld, f, C, ldc, f, activation, plan, carry,
                                   as_stream(stream), &ctx->timers.spmm, false, nullptr, sliced));
+}
+
+int sensei_spmm_static(sensei_ctx *ctx, const sensei_csr *A, int mode, const float *r, const float *c, sensei_mat B, float *C,
+                       int64_t ldc, int activation, void *stream) {
+    if (mode < SENSEI_SPMM_PATTERN || mode > SENSEI_SPMM_SCALED) return SENSEI_INVALID_ARGUMENT;
+    if (!ctx || !ctx->scratch || !csr_ok(A, mode == SENSEI_SPMM_WEIGHTED) || !mat_ok(B)) return SENSEI_INVALID_ARGUMENT;
+    if (activation != SENSEI_ACT_NONE && activation != SENSEI_ACT_RELU) return SENSEI_INVALID_ARGUMENT;
+    if (B.rows != A->n_cols || ldc < B.cols || B.cols > (1 << 20)) return SENSEI_INVALID_ARGUMENT;
+    if (mode == SENSEI_SPMM_SCALED && ((A->n_rows > 0 && !r) || (A->n_cols > 0 && !c))) return SENSEI_INVALID_ARGUMENT;
+    if (A->n_rows > 0 && B.cols > 0 && !C) return SENSEI_INVALID_ARGUMENT;
+    if (A->n_rows == 0 || B.cols == 0) return SENSEI_OK;
+    const int f = (int)B.cols;
+    if (overlap(C, mat_bytes(C, A->n_rows, f, ldc), B.ptr, mat_bytes(B.ptr, B.rows, f, B.ld))) return SENSEI_INVALID_ARGUMENT;
+    // chunk plan + one carry slot per chunk: everything the kernels need beyond inputs and outputs
+    if (plan_bytes(A->nnz) + spmm_carry_bytes(A->nnz, f) > (size_t)SENSEI_STATIC_SCRATCH_BYTES) return SENSEI_SCRATCH_TOO_SMALL;
+    // Nothing in the array has to start at zero: the plan kernel writes every chunk_row entry, and a carry slot is read by
+    // the fix-up pass only for chunks in which a row continues, each of which wrote its slot in this very call.
+    Carver cv(ctx->scratch, SENSEI_STATIC_SCRATCH_BYTES);
+    ChunkPlan plan = make_plan(*A, cv);
+    float *carry = cv.take<float>(spmm_carry_bytes(A->nnz, f) / sizeof(float));
+    SENSEI_TRY(launch_chunk_rows(*A, plan, as_stream(stream)));
+    const bool scaled = (mode == SENSEI_SPMM_SCALED);
+    // the plain single-pass kernel on the caller's row-major operand: no side stream, no events, no copies
+    return hip_status(launch_spmm(*A, mode, scaled ? r : nullptr, scaled ? c : nullptr, B.ptr, B.ld, f, C, ldc, f, activation, plan, carry,
+                                  as_stream(stream)));
 }
 
 int sensei_gemm(sensei_ctx *ctx, sensei_mat A, sensei_mat W, float *Y, int64_t ldy, int activation, void *stream) {
