@@ -41,6 +41,285 @@ WORKLOADS = {
 }
 
 
+def _source_sha16():
+    """Hash of the kernel sources: a counter summary under profiles/ is only quoted while it was taken from these very sources."""
+    import hashlib
+    h = hashlib.sha256()
+    src = os.path.join(ROOT, "paper_2306_15155_amd", "csrc")
+    for name in sorted(os.listdir(src)):
+        if name.endswith((".hip", ".h")):
+            h.update(open(os.path.join(src, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def _profile_value(path, key):
+    """'<key>: <number>' from a profile summary, or None when the file is missing or was taken from other kernel sources."""
+    if not os.path.exists(path):
+        return None
+    sha, val = None, None
+    for line in open(path):
+        if line.startswith("source_sha16:"):
+            sha = line.split(":")[1].strip()
+        if line.startswith(key + ":"):
+            val = float(line.split(":")[1])
+    return val if sha == _source_sha16() else None
+
+
+def _hip_runtime():
+    """The HIP runtime already mapped into this process (ctypes handle), for counting the kernel nodes of a captured stream."""
+    import ctypes
+    for line in open("/proc/self/maps"):
+        if "libamdhip64" in line:
+            return ctypes.CDLL(line.split()[-1])
+    return None
+
+
+def _kernel_count(torch, fn):
+    """Number of kernel launches of fn(): captured on a side stream into a HIP graph that is never launched, nodes counted."""
+    import ctypes
+    hip = _hip_runtime()
+    if hip is None:
+        return None
+    fn()                                 # allocations and workspace growth happen outside the capture
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph, n = ctypes.c_void_p(), ctypes.c_size_t(0)
+    with torch.cuda.stream(side):
+        st = ctypes.c_void_p(side.cuda_stream)
+        if hip.hipStreamBeginCapture(st, 2) != 0:   # relaxed mode
+            return None
+        try:
+            fn()
+        finally:
+            rc = hip.hipStreamEndCapture(st, ctypes.byref(graph))
+    if rc != 0 or not graph:
+        return None
+    rc = hip.hipGraphGetNodes(graph, None, ctypes.byref(n))
+    hip.hipGraphDestroy(graph)
+    torch.cuda.synchronize()
+    return int(n.value) if rc == 0 else None
+
+
+def _time_fn(torch, fn, iters=3):
+    fn()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(iters):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / iters
+
+
+def _graph_replay_ms(torch, fn, iters=50):
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        fn()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        fn()
+    return _time_fn(torch, graph.replay, iters)
+
+
+def _spmm_shape_of(kind, cid, f_in, f_out):
+    """(columns the SpMM of this composition gathers, bytes per stored entry it reads, scaling vectors read inside it)."""
+    if kind == "gcn":
+        return (f_in if cid in (0, 2, 4) else f_out), (8 if cid >= 4 else 4), cid in (2, 3)
+    return (f_out if cid in (0, 3) else f_in), 8, False
+
+
+def _layer_report(torch, np, ctx, kind, A, Apre, N, nnz, r, c, Xd, Wd, att, f_in, f_out, act, out, iters=2):
+    """Every composition id of one layer timed; the selector's pick with its regret (against the ids its rules allow and against
+    all ids); SpMM and GEMM launches of the picked id timed by the library's HIP events, with the roofline each is held to."""
+    from paper_2306_15155_amd import GAT_NAMES, GCN_NAMES, KIND_GAT, KIND_GCN, SELECT_MODEL
+    names = GCN_NAMES if kind == "gcn" else GAT_NAMES
+    k = KIND_GCN if kind == "gcn" else KIND_GAT
+
+    def run(cid):
+        if kind == "gcn":
+            ctx.gcn_layer(Apre if cid >= 4 else A, r, c, Xd, Wd, cid, act, out=out)
+        else:
+            ctx.gat_layer(A, Xd, Wd, att[0], att[1], cid, 0.2, act, out=out)
+
+    pick, est = ctx.select(k, A, f_in, f_out, SELECT_MODEL)
+    ms = {names[cid]: round(_time_fn(torch, lambda: run(cid), iters), 4) for cid in range(len(names))}
+    allowed = [names[cid] for cid, t in enumerate(est) if t >= 0]
+    ctx.profile_enable(True)
+    for _ in range(3):
+        run(pick)
+    torch.cuda.synchronize()
+    sp, ge = ctx.profile_read(0), ctx.profile_read(1)
+    ctx.profile_enable(False)
+    rep = {"picked": names[pick], "ms": ms, "regret_vs_allowed": round(ms[names[pick]] / min(ms[n] for n in allowed) - 1.0, 4),
+           "regret_vs_all_ids": round(ms[names[pick]] / min(ms.values()) - 1.0, 4)}
+    if sp:
+        f_sp, per_nnz, scaled = _spmm_shape_of(kind, pick, f_in, f_out)
+        t = float(np.mean(sp[len(sp) // 3:])) * 1e-3
+        idx = nnz * per_nnz + 4 * (N + 1) + (8 * N if scaled else 0)
+        b_min, b_max = idx + 8 * f_sp * N, idx + 4 * f_sp * nnz + 4 * f_sp * N
+        rep["spmm"] = {"f": f_sp, "ms": round(t * 1e3, 4), "B_min_GBps": round(b_min / t / 1e9, 1), "B_max_GBps": round(b_max / t / 1e9, 1),
+                       "frac_of_hbm_peak_on_B_min": round(b_min / t / 8e12, 4)}
+    if ge:
+        per = len(ge) // 3
+        t = float(np.max([np.mean(ge[j::per][1:]) for j in range(per)])) * 1e-3      # the longest GEMM launch of the layer
+        flops = 2.0 * N * f_in * f_out
+        by = 4.0 * (N * f_in + f_in * f_out + N * f_out)
+        bound = "mfma" if flops / by > 157.3e12 / 8e12 else "hbm"
+        rep["gemm"] = {"ms": round(t * 1e3, 4), "tflops": round(flops / t / 1e12, 1), "flop_per_byte": round(flops / by, 1), "bound": bound,
+                       "frac": round(flops / t / 157.3e12 if bound == "mfma" else by / t / 8e12, 3)}
+    run(pick)  # the picked composition's output stays in `out`
+    return rep
+
+
+def run_extras(args, torch, np, synth, oracle):
+    """What the default run reports beside the headline workload, each under its own key of `detail`."""
+    from paper_2306_15155_amd import Context, Panels, csr_struct
+    dev = "cuda:0"
+    out = {}
+    ctx = Context(0)
+
+    def upload(g):
+        row_ptr, col_idx = torch.from_numpy(g.row_ptr).to(dev), torch.from_numpy(g.col_idx).to(dev)
+        A = csr_struct(g.n_rows, g.n_cols, row_ptr, col_idx)
+        dr, dc = ctx.degrees(A)
+        r, c = ctx.norm_vectors(dr), ctx.norm_vectors(dc)
+        ntil = ctx.gcn_precompute(A, r, c)
+        return dict(row_ptr=row_ptr, col_idx=col_idx, r=r, c=c, ntil=ntil)
+
+    def patterns(g, d, with_panels):
+        panels = Panels(ctx, csr_struct(g.n_rows, g.n_cols, d["row_ptr"], d["col_idx"]), 0, tune=True) if with_panels else None
+        d["panels"] = panels
+        return (csr_struct(g.n_rows, g.n_cols, d["row_ptr"], d["col_idx"], None, panels),
+                csr_struct(g.n_rows, g.n_cols, d["row_ptr"], d["col_idx"], d["ntil"], panels))
+
+    def release():
+        ctx.ws.buf = torch.empty(0, dtype=torch.uint8, device=dev)
+        torch.cuda.empty_cache()
+
+    # ---- hidden-size sweep on the 2.45 M-node graph (both layers, all six ids per size), then the sampled mini-batch drawn from it
+    t0 = time.time()
+    g = synth.rmat(7, 2_450_000, 84_000_000)
+    N, nnz = g.n_rows, g.nnz
+    X = synth.normal(7, 10, (N, 100))
+    d = upload(g)
+    A, Apre = patterns(g, d, True)
+    Xd = torch.from_numpy(X).to(dev)
+    rows = np.sort(np.unique(np.concatenate([[int(np.diff(g.row_ptr).argmax()), int(np.diff(g.row_ptr).argmin())],
+                                            synth.distinct_nodes(7, 50, N, 1000)]))).astype(np.int32)
+    sel = torch.from_numpy(rows.astype(np.int64)).to(dev)
+    sweep = {"graph": {"nodes": N, "nnz": nnz, "max_degree": int(np.diff(g.row_ptr).max())}, "column_panels": d["panels"].count, "sizes": {}}
+    for i, h in enumerate((32, 128, 512, 1024)):
+        W1, W2 = synth.glorot(7, 100 + 2 * i, 100, h), synth.glorot(7, 101 + 2 * i, h, h)
+        H1, H2 = torch.empty((N, h), device=dev), torch.empty((N, h), device=dev)
+        l1 = _layer_report(torch, np, ctx, "gcn", A, Apre, N, nnz, d["r"], d["c"], Xd, torch.from_numpy(W1).to(dev), None, 100, h, 1, H1)
+        ref = oracle.gcn_layer(N, N, g.row_ptr, g.col_idx, X, W1, 1, rows=rows, omp=True)
+        got = H1[sel].cpu().numpy()
+        l1["sampled_parity_max_scaled_err"] = float(np.max(np.abs(got - ref) / (1.0 + np.abs(ref))))
+        l2 = _layer_report(torch, np, ctx, "gcn", A, Apre, N, nnz, d["r"], d["c"], H1, torch.from_numpy(W2).to(dev), None, h, h, 0, H2)
+        sweep["sizes"][str(h)] = {"gcn_100_%d" % h: l1, "gcn_%d_%d" % (h, h): l2, "ms_per_layer_picked": round((l1["ms"][l1["picked"]] + l2["ms"][l2["picked"]]) / 2, 4)}
+        del H1, H2
+        release()
+    sweep["parity_sample"] = "%d output rows of every 100->h layer (the longest row, a shortest one, 1,000 random) against the fp64 oracle" % rows.size
+    sweep["seconds"] = round(time.time() - t0, 1)
+    out["c3_rmat2450k_sweep"] = sweep
+    del Xd, A, Apre
+    # mini-batch: 1,024 seeds, fan-outs 10 then 25; the wide block runs first
+    t0 = time.time()
+    seeds = synth.distinct_nodes(7, 40, N, 1024)
+    b2, ids1 = synth.sample_block(7, 41, g, seeds, 10)
+    b1, ids0 = synth.sample_block(7, 42, g, ids1, 25)
+    X0 = synth.normal_rows(7, 43, ids0, 100)
+    W1, W2 = synth.glorot(7, 44, 100, 256), synth.glorot(7, 45, 256, 47)
+    d1, d2 = upload(b1), upload(b2)
+    (A1, A1p), (A2, A2p) = patterns(b1, d1, False), patterns(b2, d2, False)
+    X0d, W1d, W2d = torch.from_numpy(X0).to(dev), torch.from_numpy(W1).to(dev), torch.from_numpy(W2).to(dev)
+    H1, Y = torch.empty((b1.n_rows, 256), device=dev), torch.empty((b2.n_rows, 47), device=dev)
+    from paper_2306_15155_amd import GCN_NAMES, KIND_GCN, SELECT_MODEL
+    p1, p2 = ctx.select(KIND_GCN, A1, 100, 256, SELECT_MODEL)[0], ctx.select(KIND_GCN, A2, 256, 47, SELECT_MODEL)[0]
+
+    def l1(cid):
+        ctx.gcn_layer(A1p if cid >= 4 else A1, d1["r"], d1["c"], X0d, W1d, cid, 1, out=H1)
+
+    def l2(cid):
+        ctx.gcn_layer(A2p if cid >= 4 else A2, d2["r"], d2["c"], H1, W2d, cid, 0, out=Y)
+
+    def chain():
+        l1(p1)
+        l2(p2)
+
+    mb = {"blocks": {"wide": [b1.n_rows, b1.n_cols, b1.nnz], "narrow": [b2.n_rows, b2.n_cols, b2.nnz]},
+          "picked": [GCN_NAMES[p1], GCN_NAMES[p2]],
+          "eager_us_per_layer": round(_time_fn(torch, chain, 50) * 500.0, 2),
+          "graph_replay_us_per_layer": round(_graph_replay_ms(torch, chain) * 500.0, 2),
+          "per_id": {GCN_NAMES[cid]: {"wide_us": round(_time_fn(torch, lambda: l1(cid), 20) * 1e3, 2), "narrow_us": round(_time_fn(torch, lambda: l2(cid), 20) * 1e3, 2),
+                                      "kernels_wide": _kernel_count(torch, lambda: l1(cid)), "kernels_narrow": _kernel_count(torch, lambda: l2(cid))}
+                     for cid in range(6)}}
+    chain()
+    H1_ref = oracle.gcn_layer(b1.n_rows, b1.n_cols, b1.row_ptr, b1.col_idx, X0, W1, 1)
+    Y_ref = oracle.gcn_layer(b2.n_rows, b2.n_cols, b2.row_ptr, b2.col_idx, H1_ref.astype(np.float32), W2, 0)
+    mb["parity_max_scaled_err"] = float(np.max(np.abs(Y.cpu().numpy() - Y_ref) / (1.0 + np.abs(Y_ref))))
+    mb["note"] = "latency bound: a fraction of roofline is not meaningful at this size"
+    mb["seconds"] = round(time.time() - t0, 1)
+    out["c5_minibatch"] = mb
+    del g, d, d1, d2, X0d, H1, Y
+    release()
+
+    # ---- the 10,000-node graph: latency bound as well
+    t0 = time.time()
+    g = synth.erdos_renyi(1, 10_000, 50_000)
+    X, W = synth.uniform(1, 10, (10_000, 64)), synth.glorot(1, 11, 64, 32)
+    d = upload(g)
+    A, Apre = patterns(g, d, False)
+    Xd, Wd, Y = torch.from_numpy(X).to(dev), torch.from_numpy(W).to(dev), torch.empty((10_000, 32), device=dev)
+
+    def one(cid):
+        ctx.gcn_layer(Apre if cid >= 4 else A, d["r"], d["c"], Xd, Wd, cid, 1, out=Y)
+
+    pick = ctx.select(KIND_GCN, A, 64, 32, SELECT_MODEL)[0]
+    c1 = {"picked": GCN_NAMES[pick],
+          "per_id": {GCN_NAMES[cid]: {"eager_us": round(_time_fn(torch, lambda: one(cid), 50) * 1e3, 2),
+                                      "graph_replay_us": round(_graph_replay_ms(torch, lambda: one(cid)) * 1e3, 2),
+                                      "kernels": _kernel_count(torch, lambda: one(cid))} for cid in range(6)}}
+    one(pick)
+    ref = oracle.gcn_layer(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, 1)
+    c1["parity_max_scaled_err"] = float(np.max(np.abs(Y.cpu().numpy() - ref) / (1.0 + np.abs(ref))))
+    c1["note"] = "latency bound (working set about 4 MB): a fraction of roofline is not meaningful at this size"
+    c1["seconds"] = round(time.time() - t0, 1)
+    out["c1_er10k"] = c1
+    del g, d, Xd, Wd, Y
+    release()
+
+    # ---- the two extremes of the paper's graph table: road-network shape and very dense
+    for name, make, f_x, shapes in (("road12m", lambda: synth.thinned_grid(5, 3464, 0.53), 128, ((128, 32), (32, 128))),
+                                    ("dense98k", lambda: synth.erdos_renyi(3, 98_000, 50_000_000), 256, ((256, 64), (64, 256)))):
+        t0 = time.time()
+        g = make()
+        N, nnz = g.n_rows, g.nnz
+        X = synth.normal(5, 10, (N, f_x)) if name == "road12m" else synth.uniform(3, 10, (N, f_x))
+        d = upload(g)
+        A, Apre = patterns(g, d, True)
+        Xd = torch.from_numpy(X).to(dev)
+        rep = {"graph": {"nodes": N, "nnz": nnz, "max_degree": int(np.diff(g.row_ptr).max())}, "column_panels": d["panels"].count, "layers": {}}
+        for j, (f_in, f_out) in enumerate(shapes):
+            Xin = Xd[:, :f_in].contiguous()
+            Wd = torch.from_numpy(synth.glorot(5, 100 + j, f_in, f_out)).to(dev)
+            Y = torch.empty((N, f_out), device=dev)
+            rep["layers"]["gcn_%d_%d" % (f_in, f_out)] = _layer_report(torch, np, ctx, "gcn", A, Apre, N, nnz, d["r"], d["c"], Xin, Wd, None, f_in, f_out, 1, Y)
+            att = (torch.from_numpy(synth.normal(5, 200 + j, (f_out,), 0.0, 0.1)).to(dev), torch.from_numpy(synth.normal(5, 300 + j, (f_out,), 0.0, 0.1)).to(dev))
+            rep["layers"]["gat_%d_%d" % (f_in, f_out)] = _layer_report(torch, np, ctx, "gat", A, Apre, N, nnz, d["r"], d["c"], Xin, Wd, att, f_in, f_out, 1, Y)
+            del Xin, Wd, Y
+        rep["seconds"] = round(time.time() - t0, 1)
+        out[name] = rep
+        del g, d, A, Apre, Xd
+        release()
+    torch.cuda.synchronize()
+    ctx.close()
+    return out
+
+
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -59,18 +338,16 @@ def parse_args():
     ap.add_argument("--tiles-max-width", type=int, default=0,
                     help="widest SpMM operand (columns, rounded up to 32) the dense-tile split is built for; 0 = the widest layer dimension, at most 1024")
     ap.add_argument("--no-gather-probe", action="store_true", help="skip the L2-resident gather probe")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip what the default run adds under detail beside the headline workload: the hidden-size sweep on the 2.45 M-node "
+                         "graph, the sampled mini-batch, the 10,000-node graph, the road-shaped and the very dense graph")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run four 1 GiB device-to-device copies (a kernel of known traffic, for scaling rocprofv3 --pmc byte counters)")
     return ap.parse_args()
 
 
-def main():
-    args = parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only; pass --gpus 1 (there is no multi-GPU path to measure)",
-              file=sys.stderr)
-        sys.exit(2)
-
+def headline(args):
+    """The timed workload: returns the JSON line as a dict (every device tensor it used is released on return)."""
     import numpy as np
     import torch
 
@@ -215,12 +492,9 @@ def main():
         algo_bytes = idx_bytes + 4 * f_sp * N + 4 * f_sp * N + (8 * N if scaled else 0)
         gather_bytes = idx_bytes + 4 * f_sp * nnz + 4 * f_sp * N
         t_s = spmm_mean[k] * 1e-3
-        traffic = None
-        prof = os.path.join(ROOT, "profiles", "k_spmm_%s_pmc.txt" % args.workload)
-        if os.path.exists(prof):
-            for line in open(prof):
-                if line.startswith("traffic_bytes_per_launch %s:" % tag(k)):
-                    traffic = float(line.split(":")[1])
+        # HBM-side bytes of one call from the rocprofv3 counter summary of this workload; null when the summary was not taken
+        # from the kernel sources this run was built from
+        traffic = _profile_value(os.path.join(ROOT, "profiles", "k_spmm_%s_pmc.txt" % args.workload), "traffic_bytes_per_launch %s" % tag(k))
         split = tiles_attached and tiles.n_tiles > 0 and f_sp >= args.tiles_min_width
         what = "SpMM call = k_spmm on the sparse remainder + k_dense_tiles on the hub tiles" if split else "k_spmm"
         roofline = {"kernel": "%s (%s, F=%d, %s)" % (what, tag(k), f_sp, name_of(k)), "bound": "hbm",
@@ -269,16 +543,18 @@ def main():
               "column_panels_trial_ms": None if panels is None or panels.tune_ms is None else [round(x, 3) for x in panels.tune_ms], "select_model_ms": round(select_model_ms, 4),
               "graph": {"nodes": N, "nnz": nnz, "max_degree": int(np.diff(g.row_ptr).max()), "generate_s": round(gen_s, 2)}}
     if not args.no_sweep:
-        sweep, regret = {}, {}
+        sweep, regret, regret_all = {}, {}, {}
         for i, L in enumerate(layers):
             n_ids = 6 if L["kind"] == "gcn" else 4
             sweep[tag(i)] = {name_of(i, cid): round(time_fn(lambda: run_layer(i, cid), 2), 4) for cid in range(n_ids)}
             allowed = [cid for cid, t in enumerate(ctx.select(KIND_GCN if L["kind"] == "gcn" else KIND_GAT, A, L["f_in"], L["f_out"],
                                                               SELECT_MODEL)[1]) if t >= 0]
             regret[tag(i)] = round(sweep[tag(i)][name_of(i)] / min(sweep[tag(i)][name_of(i, cid)] for cid in allowed) - 1.0, 4)
+            regret_all[tag(i)] = round(sweep[tag(i)][name_of(i)] / min(sweep[tag(i)].values()) - 1.0, 4)
             run_layer(i, ids[i])  # leave the selected composition's output in place for later layers
         detail["all_compositions_ms"] = sweep
-        detail["selector_regret"] = regret
+        detail["selector_regret"] = regret                      # against the fastest id the embedding-size rules allow
+        detail["selector_regret_vs_all_ids"] = regret_all       # against the fastest of all callable ids
         # the same question to the learned per-primitive models (gradient-boosted trees fitted to MI355X timings)
         learned = {}
         for i, L in enumerate(layers):
@@ -410,6 +686,29 @@ def main():
             roofline["gather_frac_of_l2_resident_rate"] = round(roofline["gather_GBps_no_reuse"] / p_rate, 3)
         del p_rp, p_ci, p_B, p_C, cols
 
+    # ---- SDDMM instances and the edge softmax as stand-alone calls on this graph: time by events, algorithmic bytes
+    # (4 B column index + 4 B written per stored entry, the row pointers, the two node vectors), fraction of the HBM peak.
+    # Each stored entry gathers one 4-byte scalar of a node vector that does not fit the 32 KB vector caches, i.e. one
+    # 128-byte line from the L2: nnz * 128 B over the 64 B/clk/CU fill path of 256 CUs is the floor quoted beside it.
+    if nnz >= (1 << 22):
+        s_l = torch.rand(N, device=dev) - 0.5
+        s_r = torch.rand(N, device=dev) - 0.5
+        e_buf = torch.rand(nnz, device=dev) - 0.5
+        a_buf = torch.empty(nnz, device=dev)
+        ctx.ws.ensure(ctx.sparse_workspace(A, 1))
+        fill_ms = nnz * 128.0 / (256 * 64 * 2.4e9) * 1e3
+        edge = []
+        for kname, fn, by in (("k_sddmm_norm (Eq. 4)", lambda: ctx.gcn_precompute(A, r, c), 8.0 * nnz + 4.0 * (N + 1) + 8.0 * N),
+                              ("k_score (Eq. 2, k = 1)", lambda: ctx.sddmm_score(A, s_l, s_r), 8.0 * nnz + 4.0 * (N + 1) + 8.0 * N),
+                              ("edge softmax: k_softmax_stats + k_softmax_fixup + k_softmax_alpha", lambda: ctx.edge_softmax(A, e_buf, out=a_buf),
+                               12.0 * nnz + 8.0 * (N + 1) + 8.0 * N)):
+            t = time_fn(fn, 5)
+            edge.append({"kernel": kname, "bound": "hbm", "avg_call_ms": round(t, 4), "algorithmic_bytes": int(by), "achieved": round(by / t / 1e6, 1),
+                         "peak": 8000.0, "unit": "GB/s", "frac": round(by / t / 1e6 / 8000.0, 4),
+                         "line_fill_floor_ms": round(fill_ms, 4) if "softmax" not in kname else None})
+        detail["edge_kernels"] = edge
+        del s_l, s_r, e_buf, a_buf
+
     # ---- launch-bound workloads: the same step captured once in a HIP graph and replayed
     if N <= 50_000:
         graph = torch.cuda.CUDAGraph()
@@ -472,8 +771,29 @@ def main():
                                 "grid": "square grid, links kept with probability %s, + self loops" % wl.get("keep")}[wl["graph"]],
                       "nodes": N, "nnz": nnz, "layers": desc, "compositions": [name_of(i) for i in range(len(layers))]},
            "roofline": roofline, "cpu_baseline": cpu, "detail": detail}
-    print(json.dumps(out))
+    torch.cuda.synchronize()
     ctx.close()
+    return out
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; pass --gpus 1 (there is no multi-GPU path to measure)",
+              file=sys.stderr)
+        sys.exit(2)
+    out = headline(args)
+    if not args.no_extras:
+        import numpy as np
+        import torch
+
+        import oracle
+        import synth
+        torch.cuda.empty_cache()
+        t0 = time.time()
+        out["detail"]["other_workloads"] = run_extras(args, torch, np, synth, oracle)
+        out["detail"]["other_workloads"]["seconds"] = round(time.time() - t0, 1)
+    print(json.dumps(out))
 
 
 if __name__ == "__main__":

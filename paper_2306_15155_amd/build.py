@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB_PATH = os.path.join(HERE, "libsensei_hip.so")
 OBJ_DIR = os.path.join(ROOT, "_build")
-SOURCES = ["sparse_kernels.hip", "panel_kernels.hip", "gemm_kernels.hip", "api.hip"]
+SOURCES = ["sparse_kernels.hip", "gemm_kernels.hip", "api.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Wno-unused-command-line-argument",
          "-I" + os.path.join(ROOT, "include"), "-I" + os.path.join(HERE, "csrc"),
          # packed fp32 instructions are kept out of the generated code
