@@ -352,7 +352,7 @@ def headline(args):
     import torch
 
     import synth
-    from paper_2306_15155_amd import (GAT_NAMES, GCN_NAMES, KIND_GAT, KIND_GCN, SELECT_LEARNED, SELECT_MODEL, SELECT_TIMED, Context, Panels,
+    from paper_2306_15155_amd import (GAT_NAMES, GCN_NAMES, KIND_GAT, KIND_GCN, SELECT_AUTO, SELECT_LEARNED, SELECT_MODEL, SELECT_TIMED, Context, Panels,
                                       csr_struct)
 
     wl = WORKLOADS[args.workload]
@@ -572,6 +572,18 @@ def headline(args):
         dt = (time.perf_counter() - ts) * 1e3
         detail["select_timed"] = {"layer": tag(0), "pick": name_of(0, idt), "overhead_ms": round(dt, 3),
                                   "overhead_in_layers": round(dt / detail["layers"][tag(0)]["ms"], 2)}
+        # rules + model, with a timed trial only among candidates the model cannot separate (within 15 % of its cheapest)
+        auto = {}
+        for i, L in enumerate(layers):
+            ts = time.perf_counter()
+            ida, _ = ctx.select(KIND_GCN if L["kind"] == "gcn" else KIND_GAT, A, L["f_in"], L["f_out"], SELECT_AUTO)
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - ts) * 1e3
+            allowed_ms = [sweep[tag(i)][name_of(i, cid)] for cid, t in enumerate(ctx.select(KIND_GCN if L["kind"] == "gcn" else KIND_GAT, A, L["f_in"], L["f_out"],
+                                                                                             SELECT_MODEL)[1]) if t >= 0]
+            auto[tag(i)] = {"pick": name_of(i, ida), "regret": round(sweep[tag(i)][name_of(i, ida)] / min(allowed_ms) - 1.0, 4),
+                            "overhead_ms": round(dt, 3), "overhead_in_layers": round(dt / detail["layers"][tag(i)]["ms"], 2)}
+        detail["select_auto"] = auto
 
     # ---- training: backward of the GCN layers in both associations (symmetric pattern: it is its own transpose)
     if not args.no_sweep or args.backward:

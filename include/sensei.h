@@ -363,7 +363,7 @@ int sensei_gat_layer_heads(sensei_ctx *ctx, const sensei_csr *A, sensei_mat X, s
 
 /* --------------------------------------------------------------------- selector */
 
-enum { SENSEI_SELECT_MODEL = 0, SENSEI_SELECT_TIMED = 1, SENSEI_SELECT_LEARNED = 2 };
+enum { SENSEI_SELECT_MODEL = 0, SENSEI_SELECT_TIMED = 1, SENSEI_SELECT_LEARNED = 2, SENSEI_SELECT_AUTO = 3 };
 
 /* Bytes sensei_select needs in timed mode (it runs every candidate once on scratch operands); learned mode needs
  * 256 bytes. */
@@ -375,12 +375,17 @@ int sensei_select_workspace(int kind, const sensei_csr *A, int f_in, int f_out, 
  *   mode MODEL: cost(id) = sum of the predicted times of its primitives from the graph features
  *               (rows, columns, non-zeros, density) and the sizes; smallest cost wins, ties to
  *               the lowest id.  Host arithmetic only, nothing is launched, workspace unused.
- *   mode TIMED: every remaining candidate is run once after one warm-up on scratch operands in
- *               `workspace` and the fastest is kept (the "run all once, keep the best" strategy);
- *               synchronises `stream`.
+ *   mode TIMED: every remaining candidate is run once on scratch operands in `workspace` and the fastest is kept (the
+ *               "run all once, keep the best" strategy); a candidate that takes under 2 ms is run a second time and the second
+ *               figure kept, so that no candidate is judged on a cold first run where that could decide; synchronises `stream`.
+ *   mode AUTO:  MODEL first; if more than one candidate lies within 15 % of the cheapest prediction and `workspace` holds
+ *               sensei_select_workspace bytes, those candidates alone go through the TIMED trial (others cannot win; their
+ *               est_ms stays the prediction).  With one clear candidate, or without the workspace, it is MODEL.
  *   mode LEARNED: as MODEL, but the SpMM and GEMM times come from gradient-boosted regression trees fitted to
  *               timings of these primitives on MI355X over a grid of synthetic graphs (the learned per-primitive
- *               cost models of Section 3.5; tables generated by paper_2306_15155_amd/costmodel/train.py).  The graph
+ *               cost models of Section 3.5; tables generated by paper_2306_15155_amd/costmodel/train.py).
+ *   In MODEL, LEARNED and AUTO the value-less and attention SpMMs are priced on the path they will take: a dense-tile split
+ *   attached to A (made for this very pattern) takes its share of the gathers off those calls.  The graph
  *               feature extractor adds two measures of skew read from row_ptr by one small kernel (largest row,
  *               second moment of the row lengths): needs 256 bytes of `workspace`, synchronises `stream`.
  * comp_id_out: host int.  est_ms (host, nullable): sensei_num_compositions(kind) floats,

@@ -19,7 +19,7 @@ ACT_NONE, ACT_RELU = 0, 1
 KIND_GCN, KIND_GAT = 0, 1
 SPMM_PATTERN, SPMM_WEIGHTED, SPMM_SCALED = 0, 1, 2
 GCN_BWD_AGG, GCN_BWD_UPD = 0, 1
-SELECT_MODEL, SELECT_TIMED, SELECT_LEARNED = 0, 1, 2
+SELECT_MODEL, SELECT_TIMED, SELECT_LEARNED, SELECT_AUTO = 0, 1, 2, 3
 GCN_NAMES = ("DYN_AGG", "DYN_UPD", "DYNF_AGG", "DYNF_UPD", "PRE_AGG", "PRE_UPD")
 GAT_NAMES = ("REUSE", "RECOMP", "RECOMP_FOLD", "REUSE_FOLD")
 
@@ -480,7 +480,7 @@ class Context:
         if mode == SELECT_LEARNED:
             self.ws.ensure(256)
             ws_ptr, ws_bytes = self.ws.ptr, self.ws.nbytes
-        if mode == SELECT_TIMED:
+        if mode in (SELECT_TIMED, SELECT_AUTO):
             need = ctypes.c_size_t()
             _check(lib().sensei_select_workspace(kind, ctypes.byref(A), f_in, f_out, ctypes.byref(need)), "sensei_select_workspace")
             self.ws.ensure(need.value)

@@ -325,6 +325,33 @@ def test_selector_rules_and_modes(ctx):
                 assert est[cid] == min(t for t in est if t >= 0)
 
 
+def test_auto_selector_times_only_what_the_model_cannot_separate(ctx):
+    """AUTO is MODEL where one candidate is clearly cheapest, and a timed trial among the candidates within 15 % of the cheapest
+    prediction otherwise: the ids it tried carry measured times, the others keep their predictions and cannot win; without a
+    workspace it is MODEL."""
+    import ctypes
+    from paper_2306_15155_amd import SELECT_AUTO, binding
+    g = GRAPHS["rmat_hub"]
+    A = DeviceCSR(g)
+    for kind, f_in, f_out in ((KIND_GCN, 256, 32), (KIND_GCN, 64, 64), (KIND_GAT, 32, 256), (KIND_GAT, 256, 32)):
+        kind_name = "gcn" if kind == KIND_GCN else "gat"
+        allowed = set(oracle.select_rules(kind_name, f_in, f_out))
+        pick_m, est_m = ctx.select(kind, A.s, f_in, f_out, SELECT_MODEL)
+        pick_a, est_a = ctx.select(kind, A.s, f_in, f_out, SELECT_AUTO)
+        close = {i for i in allowed if est_m[i] <= min(est_m[j] for j in allowed) * 1.15}
+        assert pick_a in close and {i for i, t in enumerate(est_a) if t >= 0} == allowed
+        for i in allowed - close:
+            assert est_a[i] == est_m[i]                      # not tried: the prediction stands
+        if len(close) == 1:
+            assert pick_a == pick_m and est_a == est_m       # nothing to settle: nothing was run
+        else:
+            assert est_a[pick_a] == min(est_a[i] for i in close)
+        # without a workspace: the model's pick
+        pick = ctypes.c_int(-1)
+        st = binding.lib().sensei_select(ctx._h, kind, ctypes.byref(A.s), f_in, f_out, SELECT_AUTO, ctypes.byref(pick), None, None, 0, None)
+        assert st == 0 and pick.value == pick_m
+
+
 def test_learned_selector_reads_the_graph_and_predicts_the_layer_time(ctx):
     """The learned mode extracts its skew features on the GPU (bit-exact integers) and its additive prediction lands
     within a factor of three of the measured layer time on a graph that is not in its training grid."""
