@@ -352,6 +352,15 @@ int sensei_gat_layer(sensei_ctx *ctx, const sensei_csr *A, sensei_mat X, sensei_
                      const float *a_r, float neg_slope, float *Y, int64_t ldy, int activation, int comp_id,
                      void *workspace, size_t ws_bytes, void *stream);
 
+/* Which form the attention part (scores, softmax, aggregation) of sensei_gat_layer / sensei_gat_layer_heads takes for this
+ * input (host arithmetic on the sizes and on what A carries; -1 on invalid arguments):
+ *   TWO_PASS  one pass forms the logits and the row statistics (max, sum of exp), the aggregation applies exp(e - max) / sum;
+ *   ONE_WALK  score, running-maximum softmax and weighted sum in a single walk of each row, nothing stored per entry: taken where
+ *             the aggregation is 32 columns wide at most and rows average 16 entries or more, or 64 columns and 128 entries;
+ *   TILES     the dense-tile split attached to A serves statistics and aggregation; PANELS: two passes over the column panels. */
+enum { SENSEI_GAT_PATH_TWO_PASS = 0, SENSEI_GAT_PATH_ONE_WALK = 1, SENSEI_GAT_PATH_TILES = 2, SENSEI_GAT_PATH_PANELS = 3 };
+int sensei_gat_attention_path(const sensei_csr *A, int f_in, int f_out, int n_heads, int comp_id);
+
 /* Multi-head GAT layer, heads concatenated: W is f_in x (n_heads * d) with head h in columns [h d, (h + 1) d), a_l and
  * a_r hold n_heads * d entries laid out the same way, Y is n_rows x (n_heads * d).  Every head is the single-head layer
  * above on its d columns of Theta = X.W (its own logits, softmax and aggregation); Theta is formed by one GEMM for all

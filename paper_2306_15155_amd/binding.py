@@ -27,7 +27,7 @@ EXPORTS = (
     "sensei_create", "sensei_destroy", "sensei_calibrate", "sensei_num_compositions", "sensei_composition_name",
     "sensei_status_string", "sensei_degrees", "sensei_norm_vectors", "sensei_sparse_workspace", "sensei_chunk_nnz", "sensei_gcn_precompute",
     "sensei_row_broadcast", "sensei_spmm", "sensei_spmm_static", "sensei_gemm", "sensei_gemv2", "sensei_sddmm_score", "sensei_edge_softmax",
-    "sensei_gcn_workspace", "sensei_gcn_layer", "sensei_gat_workspace", "sensei_gat_layer", "sensei_select_workspace",
+    "sensei_gcn_workspace", "sensei_gcn_layer", "sensei_gat_workspace", "sensei_gat_attention_path", "sensei_gat_layer", "sensei_select_workspace",
     "sensei_select", "sensei_profile_enable", "sensei_profile_read", "sensei_panels_bytes", "sensei_panels_create",
     "sensei_panels_count", "sensei_panels_destroy", "sensei_panels_set_min_width", "sensei_panels_tune_bytes",
     "sensei_panels_tune", "sensei_gcn_backward_workspace", "sensei_gcn_backward", "sensei_select_gcn_backward", "sensei_transpose_positions",
@@ -95,6 +95,7 @@ def lib():
         L.sensei_gat_backward.argtypes = [vp, P(CsrStruct), P(CsrStruct), vp, MatStruct, MatStruct, vp, vp, f32, vp, i64, MatStruct, i32,
                                           vp, i64, vp, i64, vp, vp, vp, sz, vp]
         L.sensei_gat_workspace.argtypes = [P(CsrStruct), i32, i32, i32, P(sz)]
+        L.sensei_gat_attention_path.argtypes = [P(CsrStruct), i32, i32, i32, i32]
         L.sensei_gat_layer.argtypes = [vp, P(CsrStruct), MatStruct, MatStruct, vp, vp, f32, vp, i64, i32, i32, vp, sz, vp]
         L.sensei_gat_layer_heads.argtypes = [vp, P(CsrStruct), MatStruct, MatStruct, vp, vp, i32, f32, vp, i64, i32, i32, vp, sz, vp]
         L.sensei_sgc_workspace.argtypes = [P(CsrStruct), i32, i32, i32, P(sz)]
@@ -136,6 +137,13 @@ def composition_name(kind: int, comp_id: int) -> str:
 
 def chunk_nnz(nnz: int) -> int:
     return lib().sensei_chunk_nnz(nnz)
+
+
+GAT_PATH_TWO_PASS, GAT_PATH_ONE_WALK, GAT_PATH_TILES, GAT_PATH_PANELS = 0, 1, 2, 3
+
+
+def gat_attention_path(A: "CsrStruct", f_in: int, f_out: int, comp_id: int, n_heads: int = 1) -> int:
+    return lib().sensei_gat_attention_path(ctypes.byref(A), f_in, f_out, n_heads, comp_id)
 
 
 def num_compositions(kind: int) -> int:

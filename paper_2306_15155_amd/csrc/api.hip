@@ -2,6 +2,7 @@
 // executors for the GCN and GAT layer, and the composition selector.
 #include <algorithm>
 #include <cmath>
+#include <cstdlib>
 #include <new>
 
 #include "sensei_internal.h"
@@ -499,6 +500,25 @@ int run_gcn_backward(const sensei_csr &A, const sensei_csr &At, const float *r, 
 // n_heads > 1: W holds the heads side by side (head h = columns [h d, (h + 1) d), d = f_out / n_heads), a_l / a_r likewise,
 // Y is their concatenation; Theta = X.W is formed by one GEMM for all heads, everything after it runs head by head on the
 // head's columns (its own logits, statistics and aggregation), reusing the same buffers.
+// How the attention part of a GAT layer call runs (sensei_gat_attention_path reports it):
+//   tiles: statistics and aggregation split into dense tiles and remainder; panels: two passes, the logits stored in panel order;
+//   one walk: score, running-maximum softmax and weighted sum fused in the aggregation kernel (no stored logits, no statistics
+//   pass) - where the aggregation is one 32-column slice wide and rows average at least 16 entries, or two slices and 128
+//   entries (measured, 32 / 64 columns, layer time against the two-pass form: 233,000-node power-law graph -19 % / -7 %,
+//   98,000 nodes with 1,021 entries per row -26 % / -17 %, 2.45 M nodes with 52 per row -12 % / +6 %, road-shaped graph with 3
+//   per row +6 % / +13 %: each further slice repeats the score work, and short rows pay the per-row merge);
+//   two passes otherwise.
+enum { kAttnTwoPass = SENSEI_GAT_PATH_TWO_PASS, kAttnOneWalk = SENSEI_GAT_PATH_ONE_WALK, kAttnTiles = SENSEI_GAT_PATH_TILES,
+       kAttnPanels = SENSEI_GAT_PATH_PANELS };
+int attention_path(const sensei_csr &A, int f_gather, bool operand_sliced) {
+    if (operand_sliced && tiles_usable(A, kSpmmSoftmax, f_gather, true, true)) return kAttnTiles;
+    if (panels_usable(A, f_gather)) return kAttnPanels;
+    const double mean_row = A.n_rows > 0 ? (double)A.nnz / A.n_rows : 0.0;
+    const int slices = pad32(f_gather) / 32;
+    if ((slices == 1 && mean_row >= 16.0) || (slices == 2 && mean_row >= 128.0)) return kAttnOneWalk;
+    return kAttnTwoPass;
+}
+
 int run_gat(const sensei_csr &A, const sensei_mat &X, const sensei_mat &W, const float *a_l, const float *a_r,
             float slope, float *Y, int64_t ldy, int act, int id, void *ws, size_t ws_bytes, hipStream_t s, Timers *tm, int n_heads = 1) {
     KernelTimer *kt = tm ? &tm->spmm : nullptr, *gt = tm ? &tm->gemm : nullptr;
@@ -541,8 +561,8 @@ int run_gat(const sensei_csr &A, const sensei_mat &X, const sensei_mat &W, const
     const int f_gather = reuse ? (n_heads == 1 ? fo : d) : f_in;  // width of the aggregation of one head
     // dense-tile split (the gathered operand, Theta or X, must be slice-major): the tiles form their weights from s_l, s_r
     // themselves, only the remainder's logits are stored
-    const bool by_tiles = (reuse ? theta_sliced : x_sliced) && tiles_usable(A, kSpmmSoftmax, f_gather, true, true);
-    const bool by_panel = !by_tiles && panels_usable(A, f_gather);
+    const int path = attention_path(A, f_gather, reuse ? theta_sliced : x_sliced);
+    const bool by_tiles = path == kAttnTiles, by_panel = path == kAttnPanels, fused = path == kAttnOneWalk;
     for (int h = 0; h < n_heads; ++h) {
         const float *al = a_l + (size_t)h * d, *ar = a_r + (size_t)h * d;
         const float *theta_h = !theta ? nullptr : theta_sliced ? theta + (size_t)h * (d / 32) * (size_t)A.n_cols * 32 : theta + (size_t)h * d;
@@ -571,14 +591,28 @@ int run_gat(const sensei_csr &A, const sensei_mat &X, const sensei_mat &W, const
             SENSEI_TRY(launch_attention_stats(Ar, s_l, s_r, slope, logits, nullptr, D.plan_rem, stats, carry_stats, s));
             SENSEI_TRY(hipStreamWaitEvent(s, D.ev_join, 0));
             SENSEI_TRY(launch_tile_stats_merge(D.T, stats, A.n_rows, s));
-        } else {
+        } else if (!fused) {
             SENSEI_TRY(launch_attention_stats(A, s_l, s_r, slope, logits, by_panel ? A.panels->position : nullptr, plan, stats, carry_stats, s));
         }
         const AttnVectors attn = {s_l, s_r, slope, by_tiles};
         sensei_csr Aw = A;
         Aw.val = logits;
         float *Y_h = Y + (size_t)h * d;
-        if (reuse) {
+        if (fused) {
+            const AttnFusedArgs fa = {s_l, s_r, slope, stats, carry_stats};
+            hipEvent_t t0 = kt ? kt->next() : nullptr, t1 = t0 ? kt->next() : nullptr;   // the whole call, fix-up included
+            if (t1) SENSEI_TRY(hipEventRecord(t0, s));
+            if (reuse) {
+                SENSEI_TRY(launch_spmm(A, kSpmmAttnFused, nullptr, nullptr, theta_h, fo, f_gather, Y_h, ldy, d, act, plan, carry, s, nullptr, false, true,
+                                       nullptr, theta_sliced, 1, false, false, &fa));
+                if (t1) SENSEI_TRY(hipEventRecord(t1, s));
+            } else {
+                SENSEI_TRY(launch_spmm(A, kSpmmAttnFused, nullptr, nullptr, x_src, X.ld, f_in, U, fi, f_in, SENSEI_ACT_NONE, plan, carry, s, nullptr, false,
+                                       true, nullptr, x_sliced, 1, false, false, &fa));
+                if (t1) SENSEI_TRY(hipEventRecord(t1, s));
+                SENSEI_TRY(launch_gemm(U, fi, W.ptr + (size_t)h * d, W.ld, Y_h, ldy, A.n_rows, f_in, d, d, act, s, nullptr, gt));
+            }
+        } else if (reuse) {
             SENSEI_TRY(spmm_any(Aw, kSpmmSoftmax, nullptr, nullptr, theta_h, fo, f_gather, Y_h, ldy, d, act, plan, carry, s, kt, by_panel, stats,
                                 theta_sliced, false, by_tiles ? &attn : nullptr));
         } else {
@@ -925,8 +959,11 @@ double gcn_cost(const sensei_ctx &c, const Features &g, int f_in, int f_out, int
 double gat_cost(const sensei_ctx &c, const Features &g, int f_in, int f_out, int id) {
     const bool fold = (id == SENSEI_GAT_RECOMP_FOLD || id == SENSEI_GAT_REUSE_FOLD);
     double t = c.launch_us * 1e-6;
-    // attention: one pass over the pattern for the logits and the row statistics (the normalisation is part of the SpMM)
-    t += 2.0 * c.launch_us * 1e-6 + (g.nnz * 8.0 + g.n_rows * 16.0) / c.stream_bps;
+    // attention: one pass over the pattern for the logits and the row statistics (the normalisation is part of the SpMM),
+    // unless the aggregation is narrow enough, and the rows long enough, to run as one walk
+    const double f_agg = gat_is_reuse(id) ? f_out : f_in, mean_row = g.n_rows > 0 ? g.nnz / g.n_rows : 0.0;
+    const bool one_walk = g.tile_share <= 0.0 && ((f_agg <= 32 && mean_row >= 16.0) || (f_agg <= 64 && mean_row >= 128.0));
+    if (!one_walk) t += 2.0 * c.launch_us * 1e-6 + (g.nnz * 8.0 + g.n_rows * 16.0) / c.stream_bps;
     if (fold) t += t_stream(c, 4.0 * f_in * f_out) + t_stream(c, 4.0 * g.n_cols * f_in);
     else t += t_gemm(c, g.n_cols, f_in, f_out, g.learned) + t_stream(c, 4.0 * g.n_cols * f_out);
     if (gat_is_reuse(id)) {
@@ -1818,6 +1855,14 @@ int sensei_gat_backward(sensei_ctx *ctx, const sensei_csr *A, const sensei_csr *
     if (ws_bytes < gat_bwd_ws(*A, At, (int)X.cols, (int)W.cols)) return SENSEI_WORKSPACE_TOO_SMALL;
     return run_gat_backward(*A, *At, t_pos, X, W, a_l, a_r, neg_slope, Y, ldy, dY, activation, dX, lddx, dW, lddw, da_l, da_r, workspace,
                             ws_bytes, as_stream(stream));
+}
+
+int sensei_gat_attention_path(const sensei_csr *A, int f_in, int f_out, int n_heads, int comp_id) {
+    if (!csr_ok(A, false) || f_in <= 0 || f_out <= 0 || n_heads < 1 || f_out % n_heads != 0 || comp_id < 0 || comp_id >= kNumGat) return -1;
+    const bool reuse = gat_is_reuse(comp_id);
+    const int d = f_out / n_heads;
+    const bool sliced = reuse ? (n_heads == 1 || d % 32 == 0) : relayout_pays(*A);
+    return attention_path(*A, reuse ? (n_heads == 1 ? pad32(f_out) : d) : f_in, sliced);
 }
 
 int sensei_gat_workspace(const sensei_csr *A, int f_in, int f_out, int comp_id, size_t *bytes) {

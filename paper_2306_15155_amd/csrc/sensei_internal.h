@@ -48,6 +48,7 @@ struct Timers {
 
 // ---- SpMM
 
+struct AttnFusedArgs;
 struct SpmmShape {
     int vec;      // floats per lane load: 4, 2 or 1
     int lpg;      // lanes per neighbour group: 8, 16, 32 or 64
@@ -61,7 +62,8 @@ size_t spmm_carry_bytes(int64_t nnz, int f);  // upper bound
 hipError_t launch_spmm(const sensei_csr &A, int mode, const float *r, const float *c, const float *B, int64_t ldb,
                        int f, float *C, int64_t ldc, int f_store, int act, const ChunkPlan &p, float *carry,
                        hipStream_t s, KernelTimer *timer = nullptr, bool accumulate = false, bool finalize = true,
-                       const float2 *mz = nullptr, bool b_sliced = false, int val_stride = 1, bool c_sliced = false, bool defer_fixup = false);
+                       const float2 *mz = nullptr, bool b_sliced = false, int val_stride = 1, bool c_sliced = false, bool defer_fixup = false,
+                       const struct AttnFusedArgs *fused = nullptr);
 // b_sliced: B is stored slice-major in tiles of 32 floats, element (j, col) at B[(col / 32) * n_cols * 32 + j * 32 + col % 32]
 // (f padded to a multiple of 32, B 128-byte aligned); `ldb` is ignored.  val_stride: floats between consecutive values of A.val.
 // c_sliced (needs b_sliced, f a multiple of 32, f_store == f): C is written slice-major too (n_rows x f), `ldc` is ignored.
@@ -72,6 +74,16 @@ inline size_t sliced_index(int64_t n_rows, int64_t row, int col) { return (size_
 // the kernel weighs neighbour j of row i by exp(e_ij - max_i) and scales the finished row by 1 / sum, i.e. it aggregates
 // with the softmax weights of Eq. 6 without storing them.
 constexpr int kSpmmSoftmax = 3;
+// Internal SpMM mode: the attention aggregation of Eq. 5-6 in one walk, nothing stored per entry.  The weight of entry (i, j) is the
+// softmax over row i of LeakyReLU(s_l[i] + s_r[j]), formed with a running maximum while the neighbours are gathered.  row_mz
+// (n_rows + 1 pairs) and chunk_mz (one pair per chunk) are scratch for the rows that span chunks.  Single pass only (no column
+// panels, no deferred fix-up); A.val is not read.
+constexpr int kSpmmAttnFused = 4;
+struct AttnFusedArgs {
+    const float *s_l, *s_r;
+    float slope;
+    float2 *row_mz, *chunk_mz;
+};
 
 // ---- column panels: a copy of the pattern with the columns of each panel contiguous
 #define SENSEI_MAX_PANELS SENSEI_PANELS_MAX

@@ -70,6 +70,10 @@ struct SpmmArgs {
     int f, f_store, f_carry, n_tiles, act, store_vec_ok;
     int tiles_live, n_groups;  // feature tiles worked on at the same time; chunk groups (blocks per tile)
     int accumulate, finalize;  // column panels: add to what C holds; apply row scale and activation (last panel only)
+    // fused attention mode: the two score vectors, the LeakyReLU slope, and where the (max, sum) pairs of row pieces go
+    const float *s_l, *s_r;
+    float slope;
+    float2 *mz_out, *carry_mz;  // per row: pair of a first piece whose row goes on in the next chunk; per chunk: pair of its continued row
 };
 
 // value of `x` held by the lane whose number is byte_lane / 4 (all lanes must be active)
@@ -102,6 +106,11 @@ __device__ __forceinline__ float inv_z(float z) { return z > 0.f ? 1.f / z : 0.f
 // memory channels whatever the row pitch).
 // MODE kSpmmSoftmax: `val` holds attention logits; the weight of an entry is exp(logit - m_i) and the row is
 // scaled by 1/z_i when it is complete, so the normalised attention weights are never stored (Eq. 6).
+// MODE kSpmmAttnFused: score, softmax and weighted sum in one walk (Eq. 5-6 with nothing stored per entry): the logit
+// LeakyReLU(s_l[i] + s_r[j]) is formed from the two score vectors as the neighbour is gathered, every lane keeps a running
+// maximum m, the sum z of exp(logit - m) and its partial row relative to m, rescaling both when the maximum grows; the
+// lanes' (m, z, row) triples are merged when the row (piece) ends.  A piece of a row that spans chunks leaves its pair
+// beside its partial row (mz_out / carry_mz) and k_spmm_fixup_attn merges the pieces in chunk order.
 template <int VEC, int LPG, int MODE, bool OFF32>
 __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
     constexpr int G = 64 / LPG;
@@ -142,14 +151,28 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
     bool cont = (a.nnz > 0) && (a.row_ptr[i0] > lo);
     int i = uni(cont ? i0 - 1 : i0);
     int re = uni((i < a.n_rows) ? a.row_ptr[i + 1] : 0x7fffffff);
-    float m_row = 0.f;  // softmax mode: max logit of row i
+    float m_row = 0.f;  // softmax mode: max logit of row i; fused attention mode: s_l of row i
     if (MODE == kSpmmSoftmax) m_row = uni_f((i < a.n_rows) ? a.mz[i].x : 0.f);
+    if (MODE == kSpmmAttnFused) m_row = uni_f((i < a.n_rows) ? a.s_l[i] : 0.f);
+    float m_run = -INFINITY, z_run = 0.f;  // fused attention mode: this lane's running maximum and sum of exp(logit - maximum)
 
     Vec<VEC> acc;
 #pragma unroll
     for (int e = 0; e < VEC; ++e) acc.v[e] = 0.f;
 
     auto accumulate = [&](const Vec<VEC> &b, float ww) {
+        if (MODE == kSpmmAttnFused) {  // ww = s_r of the neighbour
+            const float t = m_row + ww;
+            const float lg = t > 0.f ? t : a.slope * t;
+            const float mn = lg > m_run ? lg : m_run;
+            const float keep = __expf(m_run - mn);  // 0 on the first neighbour (m_run = -inf), 1 while the maximum stands
+            const float p = __expf(lg - mn);
+            z_run = fmaf(z_run, keep, p);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc.v[e] = fmaf(acc.v[e], keep, p * b.v[e]);
+            m_run = mn;
+            return;
+        }
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
             if (MODE == SENSEI_SPMM_PATTERN) acc.v[e] += b.v[e];
@@ -158,10 +181,29 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
     };
 
     auto finish_row = [&](bool complete) {
+        float m_all = 0.f;
+        if (MODE == kSpmmAttnFused) {  // bring every group's partial row to the common maximum of the row piece
+            m_all = m_run;
+#pragma unroll
+            for (int off = LPG; off < 64; off <<= 1) {
+                const float o = __shfl_xor(m_all, off, 64);
+                m_all = o > m_all ? o : m_all;
+            }
+            const float sc = m_run > -INFINITY ? __expf(m_run - m_all) : 0.f;  // a group that saw no neighbour holds zeros
+            z_run *= sc;
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc.v[e] *= sc;
+#pragma unroll
+            for (int off = LPG; off < 64; off <<= 1) z_run += __shfl_xor(z_run, off, 64);
+        }
 #pragma unroll
         for (int off = LPG; off < 64; off <<= 1) {
 #pragma unroll
             for (int e = 0; e < VEC; ++e) acc.v[e] += __shfl_xor(acc.v[e], off, 64);
+        }
+        if (MODE == kSpmmAttnFused && lane == 0 && tile == 0) {  // every feature tile of the chunk forms the same pair: one writes it
+            if (cont) a.carry_mz[chunk] = make_float2(m_all, z_run);
+            else if (!complete) a.mz_out[i] = make_float2(m_all, z_run);
         }
         if (g == 0 && fok) {
             if (cont) {
@@ -180,7 +222,7 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
                     }
                 }
                 if (complete && a.finalize) {
-                    const float sc = (MODE == kSpmmSoftmax) ? inv_z(a.mz[i].y) : (a.r ? a.r[i] : 1.f);
+                    const float sc = (MODE == kSpmmAttnFused) ? inv_z(z_run) : (MODE == kSpmmSoftmax) ? inv_z(a.mz[i].y) : (a.r ? a.r[i] : 1.f);
 #pragma unroll
                     for (int e = 0; e < VEC; ++e) {
                         float y = acc.v[e] * sc;
@@ -198,6 +240,8 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
         }
 #pragma unroll
         for (int e = 0; e < VEC; ++e) acc.v[e] = 0.f;
+        m_run = -INFINITY;
+        z_run = 0.f;
     };
 
     // Many short rows in this chunk: walking them one after another would leave most neighbour groups
@@ -220,6 +264,8 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
             Vec<VEC> racc;
 #pragma unroll
             for (int e = 0; e < VEC; ++e) racc.v[e] = 0.f;
+            float rm = -INFINITY, rz = 0.f;  // fused attention mode: running maximum and sum of the group's row
+            const float sl_g = (MODE == kSpmmAttnFused && rok) ? a.s_l[row] : 0.f;
             for (int k = rs; k < rend; k += U) {
                 Vec<VEC> b[U];
                 float ww[U];
@@ -232,14 +278,39 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
                     if (MODE == SENSEI_SPMM_WEIGHTED) wq = a.val[(size_t)kq * a.val_stride];
                     if (MODE == SENSEI_SPMM_SCALED) wq = a.c[j];
                     if (MODE == kSpmmSoftmax) wq = __expf(a.val[(size_t)kq * a.val_stride] - mz_g.x);
-                    ww[q] = valid ? wq : 0.f;
+                    if (MODE == kSpmmAttnFused) {
+                        const float t = sl_g + a.s_r[j];
+                        wq = valid ? (t > 0.f ? t : a.slope * t) : -INFINITY;  // the logit; an entry past the end weighs exp(-inf) = 0
+                        ww[q] = wq;
+                    } else {
+                        ww[q] = valid ? wq : 0.f;
+                    }
                     b[q] = gather(j);
+                }
+                if (MODE == kSpmmAttnFused) {  // one rescale for the four neighbours of the step
+                    float mn = rm;
+#pragma unroll
+                    for (int q = 0; q < U; ++q) mn = ww[q] > mn ? ww[q] : mn;
+                    const float keep = __expf(rm - mn);
+                    rz *= keep;
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) racc.v[e] *= keep;
+#pragma unroll
+                    for (int q = 0; q < U; ++q) {
+                        ww[q] = __expf(ww[q] - mn);
+                        rz += ww[q];
+                    }
+                    rm = mn;
                 }
 #pragma unroll
                 for (int q = 0; q < U; ++q) {
 #pragma unroll
                     for (int e = 0; e < VEC; ++e) racc.v[e] = fmaf(ww[q], b[q].v[e], racc.v[e]);
                 }
+            }
+            if (MODE == kSpmmAttnFused && rok && tile == 0 && (lane % LPG) == 0) {
+                if (cont && row == i_first) a.carry_mz[chunk] = make_float2(rm, rz);
+                else if (row_end > hi) a.mz_out[row] = make_float2(rm, rz);
             }
             if (rok && fok) {
                 if (cont && row == i_first) {
@@ -258,7 +329,7 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
                         }
                     }
                     if (row_end <= hi && a.finalize) {
-                        const float sc = (MODE == kSpmmSoftmax) ? inv_z(mz_g.y) : (a.r ? a.r[row] : 1.f);
+                        const float sc = (MODE == kSpmmAttnFused) ? inv_z(rz) : (MODE == kSpmmSoftmax) ? inv_z(mz_g.y) : (a.r ? a.r[row] : 1.f);
 #pragma unroll
                         for (int e = 0; e < VEC; ++e) {
                             float y = racc.v[e] * sc;
@@ -287,6 +358,7 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
             col = a.col_idx[k];
             if (MODE == SENSEI_SPMM_WEIGHTED || MODE == kSpmmSoftmax) w = a.val[(size_t)k * a.val_stride];
             if (MODE == SENSEI_SPMM_SCALED) w = a.c[col];
+            if (MODE == kSpmmAttnFused) w = a.s_r[col];
         }
         const int bhi = (base + 64 < hi) ? base + 64 : hi;
         while (pos < bhi) {
@@ -296,6 +368,7 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
                 i = uni(i + 1);
                 re = uni(a.row_ptr[i + 1]);
                 if (MODE == kSpmmSoftmax) m_row = uni_f(a.mz[i].x);
+                if (MODE == kSpmmAttnFused) m_row = uni_f(a.s_l[i]);
             }
             const int seg_hi = uni(re < bhi ? re : bhi);
             const int u0 = uni(pos - base), n = uni(seg_hi - pos);
@@ -397,12 +470,46 @@ __global__ __launch_bounds__(kBlock) void k_spmm_fixup(SpmmArgs a) {
     }
 }
 
+// The same for the fused attention mode: the pieces of a row come with their (maximum, sum) pairs and are merged like the
+// lanes of a wavefront are - everything rescaled to the larger maximum - in chunk order; then 1 / sum and the activation.
+__global__ __launch_bounds__(kBlock) void k_spmm_fixup_attn(SpmmArgs a) {
+    const int c = 1 + blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+    if (c >= a.n_chunks) return;
+    const int lane = threadIdx.x & 63;
+    const long long lo = (long long)c * a.chunk_nnz;
+    const int i0 = a.chunk_row[c];
+    if ((long long)a.row_ptr[i0] <= lo) return;
+    const int i = i0 - 1;
+    const long long rs = a.row_ptr[i];
+    if (rs < lo - a.chunk_nnz) return;
+    const int re = a.row_ptr[i + 1];
+    const int c_last = (re - 1) / a.chunk_nnz;
+    const int tf = a.c_tf;
+    const float2 first = a.mz_out[i];
+    for (int f = lane; f < a.f_store; f += 64) {
+        float *dst = a.C + (size_t)(f / tf) * a.c_tile + (size_t)i * a.ldc + (f % tf);
+        float m = first.x, z = first.y, acc = *dst;
+        for (int cc = c; cc <= c_last; ++cc) {
+            const float2 p = a.carry_mz[cc];
+            const float mn = p.x > m ? p.x : m;
+            const float k0 = __expf(m - mn), k1 = __expf(p.x - mn);
+            acc = acc * k0 + a.carry[(size_t)cc * a.f_carry + f] * k1;
+            z = z * k0 + p.y * k1;
+            m = mn;
+        }
+        float y = acc * inv_z(z);
+        if (a.act == SENSEI_ACT_RELU) y = y > 0.f ? y : 0.f;
+        *dst = y;
+    }
+}
+
 template <int VEC, int LPG, bool OFF32>
 hipError_t spmm_dispatch_mode(const SpmmArgs &a, int mode, dim3 grid, hipStream_t s) {
     switch (mode) {
         case SENSEI_SPMM_PATTERN: hipLaunchKernelGGL((k_spmm<VEC, LPG, SENSEI_SPMM_PATTERN, OFF32>), grid, dim3(kBlock), 0, s, a); break;
         case SENSEI_SPMM_WEIGHTED: hipLaunchKernelGGL((k_spmm<VEC, LPG, SENSEI_SPMM_WEIGHTED, OFF32>), grid, dim3(kBlock), 0, s, a); break;
         case kSpmmSoftmax: hipLaunchKernelGGL((k_spmm<VEC, LPG, kSpmmSoftmax, OFF32>), grid, dim3(kBlock), 0, s, a); break;
+        case kSpmmAttnFused: hipLaunchKernelGGL((k_spmm<VEC, LPG, kSpmmAttnFused, OFF32>), grid, dim3(kBlock), 0, s, a); break;
         default: hipLaunchKernelGGL((k_spmm<VEC, LPG, SENSEI_SPMM_SCALED, OFF32>), grid, dim3(kBlock), 0, s, a); break;
     }
     return hipGetLastError();
@@ -1518,7 +1625,7 @@ size_t spmm_carry_bytes(int64_t nnz, int f) {
 hipError_t launch_spmm(const sensei_csr &A, int mode, const float *r, const float *c, const float *B, int64_t ldb,
                        int f, float *C, int64_t ldc, int f_store, int act, const ChunkPlan &p, float *carry,
                        hipStream_t s, KernelTimer *timer, bool accumulate, bool finalize, const float2 *mz, bool b_sliced, int val_stride,
-                       bool c_sliced, bool defer_fixup) {
+                       bool c_sliced, bool defer_fixup, const AttnFusedArgs *fused) {
     SpmmShape sh = spmm_shape(B, ldb, f);
     if (b_sliced) {  // slices of 32 floats per row: one 128-byte line per neighbour and tile
         sh.vec = 4; sh.lpg = 8; sh.n_tiles = (f + 31) / 32; sh.f_carry = sh.n_tiles * 32;
@@ -1538,6 +1645,11 @@ hipError_t launch_spmm(const sensei_csr &A, int mode, const float *r, const floa
     a.f = f; a.f_store = f_store; a.f_carry = sh.f_carry; a.n_tiles = sh.n_tiles; a.act = act;
     a.store_vec_ok = (ldc % sh.vec == 0) && (reinterpret_cast<uintptr_t>(C) % (4 * sh.vec) == 0);
     a.accumulate = accumulate ? 1 : 0; a.finalize = finalize ? 1 : 0;
+    a.s_l = nullptr; a.s_r = nullptr; a.slope = 0.f; a.mz_out = nullptr; a.carry_mz = nullptr;
+    if (mode == kSpmmAttnFused) {
+        if (!fused || accumulate || !finalize || defer_fixup) return hipErrorInvalidValue;
+        a.s_l = fused->s_l; a.s_r = fused->s_r; a.slope = fused->slope; a.mz_out = fused->row_mz; a.carry_mz = fused->chunk_mz;
+    }
     const unsigned groups = blocks_for(p.n_chunks, kWavesPerBlock);
     // Feature tiles worked on at the same time (consecutive XCDs take consecutive tiles of the live set): all eight
     // while a 128-byte slice of the gathered matrix is small, four beyond that (measured on the 233 k-node R-MAT graph
@@ -1563,7 +1675,8 @@ hipError_t launch_spmm(const sensei_csr &A, int mode, const float *r, const floa
     if (t1 && hipEventRecord(t1, s) != hipSuccess) return hipErrorUnknown;
     if (p.n_chunks > 1 && !(defer_fixup && b_sliced && !finalize)) {
         dim3 fg(blocks_for(p.n_chunks - 1, kWavesPerBlock));
-        hipLaunchKernelGGL(k_spmm_fixup, fg, dim3(kBlock), 0, s, a);
+        if (mode == kSpmmAttnFused) hipLaunchKernelGGL(k_spmm_fixup_attn, fg, dim3(kBlock), 0, s, a);
+        else hipLaunchKernelGGL(k_spmm_fixup, fg, dim3(kBlock), 0, s, a);
         err = hipGetLastError();
     }
     return err;

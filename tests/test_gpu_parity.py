@@ -218,6 +218,38 @@ def test_gat_layer_all_compositions(ctx, name, f_in, f_out):
     _gat_case(ctx, g, f_in, f_out, ACT_NONE, 5, scale=1.0)
 
 
+@pytest.mark.parametrize("f_out,n,pairs,hub", [(8, 9000, 200_000, 7000), (32, 9000, 200_000, 7000), (41, 3000, 500_000, 2500), (64, 3000, 500_000, 2500)])
+def test_gat_one_walk_aggregation_with_large_logits_and_rows_over_many_chunks(ctx, f_out, n, pairs, hub):
+    """Narrow aggregations on graphs with rows long enough run score, running-maximum softmax and weighted sum in one walk (no
+    stored logits, no statistics pass); the library's own query says which form a call takes.  Logits of a few tens (attention
+    vectors ~ N(0, 3^2)) make the running maximum move and would overflow an unshifted exp; the hub row spans several chunks
+    (its pieces are merged by their (maximum, sum) pairs); empty rows give zeros."""
+    from paper_2306_15155_amd import binding
+    g = hub_and_empty_graph(31, n, pairs, hub, 25)
+    assert int(np.diff(g.row_ptr).max()) > 4 * binding.chunk_nnz(g.nnz)
+    f_in = 48
+    X, W = synth.uniform(31, 10, (g.n_cols, f_in)), synth.glorot(31, 11, f_in, f_out)
+    a_l, a_r = synth.normal(31, 12, (f_out,), 0.0, 3.0), synth.normal(31, 13, (f_out,), 0.0, 3.0)
+    Th = X.astype(np.float64) @ W.astype(np.float64)
+    assert np.abs(Th @ a_r.astype(np.float64)).max() > 10.0
+    A = DeviceCSR(g)
+    assert binding.gat_attention_path(A.s, f_in, f_out, 0) == binding.GAT_PATH_ONE_WALK
+    assert binding.gat_attention_path(A.s, f_out, 96, 2) == binding.GAT_PATH_ONE_WALK
+    assert binding.gat_attention_path(A.s, f_in, 96, 0) == binding.GAT_PATH_TWO_PASS       # three slices: too wide
+    ref = oracle.gat_layer(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, a_l, a_r, 0.2, ACT_RELU)
+    for cid in (0, 3):   # the reuse compositions aggregate at f_out columns
+        Y = ctx.gat_layer(A.s, dev(X), dev(W), dev(a_l), dev(a_r), cid, 0.2, ACT_RELU)
+        assert_close(Y, ref, what=f"one-walk GAT, {f_out} columns, comp {cid}")
+    # the recompute compositions aggregate X: narrow input, wide output
+    W2 = synth.glorot(31, 14, f_out, 96)
+    X2 = synth.uniform(31, 15, (g.n_cols, f_out))
+    b_l, b_r = synth.normal(31, 16, (96,), 0.0, 1.0), synth.normal(31, 17, (96,), 0.0, 1.0)
+    ref2 = oracle.gat_layer(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X2, W2, b_l, b_r, 0.2, ACT_NONE)
+    for cid in (1, 2):
+        Y = ctx.gat_layer(A.s, dev(X2), dev(W2), dev(b_l), dev(b_r), cid, 0.2, ACT_NONE)
+        assert_close(Y, ref2, what=f"one-walk GAT on X, {f_out} columns, comp {cid}")
+
+
 @pytest.mark.parametrize("n,draws,chunk", [(3000, 40_000, 64), (8000, 110_000, 128), (15000, 230_000, 256), (40000, 700_000, 512)])
 def test_graphs_in_each_chunk_length_range(ctx, n, draws, chunk):
     """One graph per chunk length the library uses (64, 128, 256, 512 entries per wavefront); the length is asserted through
