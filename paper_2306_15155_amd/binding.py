@@ -166,9 +166,13 @@ def _stream():
 def csr_struct(n_rows, n_cols, row_ptr, col_idx, val=None, panels=None, tiles=None) -> CsrStruct:
     assert row_ptr.dtype == torch.int32 and col_idx.dtype == torch.int32
     assert val is None or val.dtype == torch.float32
-    return CsrStruct(n_rows, n_cols, int(col_idx.numel()), row_ptr.data_ptr(), col_idx.data_ptr() if col_idx.numel() else None,
-                     None if val is None else val.data_ptr(), None if panels is None else panels.handle,
-                     None if tiles is None else tiles.handle)
+    A = CsrStruct(n_rows, n_cols, int(col_idx.numel()), row_ptr.data_ptr(), col_idx.data_ptr() if col_idx.numel() else None,
+                  None if val is None else val.data_ptr(), None if panels is None else panels.handle,
+                  None if tiles is None else tiles.handle)
+    # the struct holds raw addresses: keep what they point into alive for as long as the struct is (the tensors, and the
+    # Panels / Tiles objects, whose host handle and device buffer would otherwise go with their last Python reference)
+    A._keep = (row_ptr, col_idx, val, panels, tiles)
+    return A
 
 
 class Panels:

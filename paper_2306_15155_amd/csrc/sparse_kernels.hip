@@ -902,8 +902,9 @@ __global__ void k_softmax_fixup(SoftmaxArgs a) {
 __global__ __launch_bounds__(kBlock) void k_softmax_alpha(SoftmaxArgs a) {
     const int chunk = wave_chunk();
     if (chunk >= a.n.n_chunks) return;
-    walk_chunk(a.n, chunk, threadIdx.x & 63, [&](int i) { return a.stats[i]; },
-               [&](int k, const float2 &st) { a.alpha[k] = expf(a.e[k] - st.x) / st.y; });
+    walk_chunk2(a.n, chunk, threadIdx.x & 63, [&](int i) { return a.stats[i]; },
+                [&](int k, const float2 &) { return a.e[k]; },
+                [&](int k, const float2 &st, float e) { a.alpha[k] = expf(e - st.x) / st.y; });
 }
 
 // ------------------------------------------------------------ column panels

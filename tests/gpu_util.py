@@ -39,20 +39,27 @@ def assert_close(gpu, ref, tol=TOL, what=""):
     return worst
 
 
-def assert_close_reduced(gpu, ref, terms_rss, tol=TOL, what=""):
+def assert_close_reduced(gpu, ref, terms_rss, tol=TOL, what="", max_share=0.01):
     """For a gradient that is a sum over all nodes (dW = X^T G): |gpu - ref| <= tol (1 + |ref|) + 2^-16 rss, where rss is the
     root-sum-square of the terms of that sum.  The terms are products with G (or dTheta), itself an fp32 sum over up to 1e5
     neighbours and so carrying a relative rounding error of the order of sqrt(degree) 2^-24 per node; these errors are
     independent across nodes, so what reaches the sum scales with the root-sum-square of its terms, not with its value, and
-    entries that cancel to nearly zero cannot be held to tol (1 + |ref|)."""
+    entries that cancel to nearly zero cannot be held to tol (1 + |ref|).  The second term is an allowance for those entries
+    only: at most `max_share` of the elements may need it (the others meet the plain bound), and the share is returned."""
     got = gpu.detach().cpu().numpy().astype(np.float64)
     ref = np.asarray(ref, dtype=np.float64)
     assert got.shape == ref.shape, (what, got.shape, ref.shape)
     assert np.all(np.isfinite(got)), what
-    bound = tol * (1.0 + np.abs(ref)) + 2.0 ** -16 * np.asarray(terms_rss, dtype=np.float64)
-    worst = float(np.max(np.abs(got - ref) / bound))
+    err = np.abs(got - ref)
+    plain = tol * (1.0 + np.abs(ref))
+    bound = plain + 2.0 ** -16 * np.asarray(terms_rss, dtype=np.float64)
+    worst = float(np.max(err / bound))
+    share = float(np.mean(err > plain))
+    print(f"{what}: worst {worst:.3f} of the bound; {share:.4%} of {err.size} elements are beyond the plain bound "
+          f"(largest plain-scaled error {float(np.max(err / (1.0 + np.abs(ref)))):.2e})")
     assert worst <= 1.0, f"{what}: error reaches {worst:.3f} of its bound"
-    return worst
+    assert share <= max_share, f"{what}: {share:.4%} of the elements need the allowance for cancelled sums (ceiling {max_share:.2%})"
+    return worst, share
 
 
 def hub_and_empty_graph(seed, n, pairs, hub_deg, n_empty):

@@ -277,16 +277,14 @@ def test_config2_gcn_backward_full_size(ctx, reddit_like):
     X, W = synth.uniform(7, 10, (g.n_cols, f_in)), synth.glorot(7, 100, f_in, f_out)
     dY = synth.normal(7, 500, (g.n_rows, f_out), 0.0, 1.0)
     rows = _sample_rows(g, 9, 500)
-    want_dx, want_dw, dz = oracle.gcn_backward(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, dY, rows=rows, want_dw=True, omp=True,
-                                               with_dz=True)
-    rss = np.sqrt((X.astype(np.float64) ** 2).T @ (dz ** 2))  # of the terms X[j, f] dZ[j, m] of dW
+    want_dx, want_dw = oracle.gcn_backward(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, dY, rows=rows, want_dw=True, omp=True)
     r, c, _, _ = _norm(ctx, A)
     sel = torch.from_numpy(rows.astype(np.int64)).to(DEV)
     Xd, Wd, dYd = dev(X), dev(W), dev(dY)
     for bwd in (GCN_BWD_AGG, GCN_BWD_UPD):
         dX, dW = ctx.gcn_backward(A.s, A.s, r, c, Xd, Wd, dYd, bwd)  # the pattern is symmetric: it is its own transpose
         assert_close(dX[sel], want_dx, what=f"dX bwd {bwd}")
-        assert_close_reduced(dW, want_dw, rss, what=f"dW bwd {bwd}")
+        assert_close(dW, want_dw, what=f"dW bwd {bwd}")   # the whole weight gradient inside the fp32 bar (measured: 2e-5 at most)
     pick, est = ctx.select_gcn_backward(A.s, f_in, f_out)
     assert pick == GCN_BWD_AGG and est[0] < est[1]  # f_out < f_in: aggregate the gradient at the narrow width
 
@@ -389,8 +387,10 @@ def test_config4_gat_backward_full_size(ctx, reddit_like):
     for how, pattern in (("plain", A.s), ("dense-tile split", A_split)):
         got = ctx.gat_backward(pattern, A.s, pos, dev(X), dev(W), dev(a_l), dev(a_r), dev(dY))
         assert_close(got[0], want[0], what=f"dX, {how}")
-        assert_close_reduced(got[1], want[1], rss, what=f"dW, {how}")
-        # da[m] = sum_j ds[j] Theta[j, m]: sums over all nodes as well, and each ds[j] is itself a sum of fp32 terms
-        assert_close_reduced(got[2], want[2], np.sqrt((want[5] ** 2) @ (Th ** 2)), what=f"da_l, {how}")
-        assert_close_reduced(got[3], want[3], np.sqrt((want[6] ** 2) @ (Th ** 2)), what=f"da_r, {how}")
+        # dW[f, m] sums 233,000 products with dTheta, whose rows are fp32 sums over up to 1e5 neighbours: entries that cancel to
+        # nearly zero may use the allowance for cancelled sums (see assert_close_reduced), at most 0.05 % of the elements
+        # (measured: 2 of 38,528, at 1.9e-4); everything else, and da_l, da_r entirely, meets the plain bar
+        assert_close_reduced(got[1], want[1], rss, what=f"dW, {how}", max_share=0.0005)
+        assert_close(got[2], want[2], what=f"da_l, {how}")
+        assert_close(got[3], want[3], what=f"da_r, {how}")
     T.close()
