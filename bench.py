@@ -333,6 +333,8 @@ def parse_args():
     ap.add_argument("--panels", type=int, default=0, help="force the number of column panels (0 = let the library measure)")
     ap.add_argument("--tiles", type=float, default=0.07, help="dense-tile split of the hub region: least density of a kept tile (0 = off)")
     ap.add_argument("--tiles-min-width", type=int, default=64, help="narrowest SpMM (columns) that uses the dense-tile split")
+    ap.add_argument("--tiles-remainder-panels", type=int, default=0,
+                    help="column panels of the panel-major copy of the split's sparse remainder (0 = the library decides, 1 = none)")
     ap.add_argument("--tiles-min-share", type=float, default=1.0 / 3.0,
                     help="the split is attached to the pattern only if at least this share of the entries lies in kept tiles")
     ap.add_argument("--tiles-max-width", type=int, default=0,
@@ -406,7 +408,7 @@ def headline(args):
         from paper_2306_15155_amd import Tiles
         tp = time.perf_counter()
         widest = args.tiles_max_width or min(1024, max(max(L["f_in"], L["f_out"]) for L in layers))
-        tiles = Tiles(ctx, A, args.tiles, (widest + 31) // 32 * 32, args.tiles_min_width)
+        tiles = Tiles(ctx, A, args.tiles, (widest + 31) // 32 * 32, args.tiles_min_width, args.tiles_remainder_panels)
         torch.cuda.synchronize()
         tiles_ms = (time.perf_counter() - tp) * 1e3
         # the split pays when a good part of the entries lies in kept tiles (measured: 64 % of them: SpMM call -25 %; 20 %: +5 %)

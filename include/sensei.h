@@ -286,7 +286,14 @@ int sensei_gatv2_layer(sensei_ctx *ctx, const sensei_csr *A, sensei_mat X, sense
  *                        takes it from half that width);
  *   sensei_tiles_destroy frees the host object only.
  * The object keeps buffers for the operand in rank order and for the tiles' product, and its stream: calls that use one
- * object at the same time on different streams race on them. */
+ * object at the same time on different streams race on them.
+ * The remainder itself may be kept a second time in panel-major order (its entries column panel by column panel, two panels), which the
+ * forward SpMM calls of 64 columns or more then walk in one launch, one raw partial row per (panel, row), joined by the last pass: the part
+ * of the gathered matrix in use at one time then fits the L2s.  Chosen automatically (a 128-byte slice of the gathered matrix of 12 MB or
+ * more, 128 or more entries per row); sensei_tiles_remainder_panels overrides the choice for the objects created afterwards in this
+ * process (0: automatic, 1: never, 2..8: that many panels whatever the graph; returns the previous setting; a tuning and testing knob -
+ * set it before sensei_tiles_bytes, which sizes the buffer for it). */
+int sensei_tiles_remainder_panels(int n_panels);
 int sensei_tiles_bytes(const sensei_csr *A, float min_density, int max_width, size_t *device_bytes);
 int sensei_tiles_create(sensei_ctx *ctx, const sensei_csr *A, float min_density, int max_width, void *device_buf, size_t bytes, void *stream,
                         sensei_tiles **out);
@@ -385,7 +392,7 @@ int sensei_select_workspace(int kind, const sensei_csr *A, int f_in, int f_out, 
  *               (rows, columns, non-zeros, density) and the sizes; smallest cost wins, ties to
  *               the lowest id.  Host arithmetic only, nothing is launched, workspace unused.
  *   mode TIMED: every remaining candidate is run once on scratch operands in `workspace` and the fastest is kept (the
- *               "run all once, keep the best" strategy); a candidate that takes under 2 ms is run a second time and the second
+ *               "run all once, keep the best" strategy); a candidate that takes under 0.5 ms is run a second time and the second
  *               figure kept, so that no candidate is judged on a cold first run where that could decide; synchronises `stream`.
  *   mode AUTO:  MODEL first; if more than one candidate lies within 15 % of the cheapest prediction and `workspace` holds
  *               sensei_select_workspace bytes, those candidates alone go through the TIMED trial (others cannot win; their

@@ -31,7 +31,7 @@ EXPORTS = (
     "sensei_select", "sensei_profile_enable", "sensei_profile_read", "sensei_panels_bytes", "sensei_panels_create",
     "sensei_panels_count", "sensei_panels_destroy", "sensei_panels_set_min_width", "sensei_panels_tune_bytes",
     "sensei_panels_tune", "sensei_gcn_backward_workspace", "sensei_gcn_backward", "sensei_select_gcn_backward", "sensei_transpose_positions",
-    "sensei_gat_backward_workspace", "sensei_gat_backward", "sensei_gat_layer_heads", "sensei_sgc_workspace", "sensei_sgc_layer", "sensei_tagcn_workspace", "sensei_tagcn_layer", "sensei_gatv2_workspace", "sensei_gatv2_layer", "sensei_tiles_bytes", "sensei_tiles_create", "sensei_tiles_info",
+    "sensei_gat_backward_workspace", "sensei_gat_backward", "sensei_gat_layer_heads", "sensei_sgc_workspace", "sensei_sgc_layer", "sensei_tagcn_workspace", "sensei_tagcn_layer", "sensei_gatv2_workspace", "sensei_gatv2_layer", "sensei_tiles_remainder_panels", "sensei_tiles_bytes", "sensei_tiles_create", "sensei_tiles_info",
            "sensei_tiles_set_min_width", "sensei_tiles_destroy",
 )
 
@@ -104,6 +104,7 @@ def lib():
         L.sensei_tagcn_layer.argtypes = [vp, P(CsrStruct), vp, vp, MatStruct, MatStruct, i32, vp, i64, i32, i32, vp, sz, vp]
         L.sensei_gatv2_workspace.argtypes = [P(CsrStruct), i32, i32, i32, P(sz)]
         L.sensei_gatv2_layer.argtypes = [vp, P(CsrStruct), MatStruct, MatStruct, MatStruct, vp, f32, vp, i64, i32, i32, vp, sz, vp]
+        L.sensei_tiles_remainder_panels.argtypes = [i32]
         L.sensei_tiles_bytes.argtypes = [P(CsrStruct), f32, i32, P(sz)]
         L.sensei_tiles_create.argtypes = [vp, P(CsrStruct), f32, i32, vp, sz, vp, P(vp)]
         L.sensei_tiles_info.argtypes = [vp, P(i32), P(i64), P(i64)]
@@ -230,7 +231,15 @@ class Panels:
 class Tiles:
     """Dense-tile split of a pattern (sensei_tiles_create); owns the device buffer it lives in."""
 
-    def __init__(self, ctx: "Context", A: CsrStruct, min_density: float = 0.07, max_width: int = 1024, min_width: int = 64):
+    def __init__(self, ctx: "Context", A: CsrStruct, min_density: float = 0.07, max_width: int = 1024, min_width: int = 64, remainder_panels: int = 0):
+        """remainder_panels: 0 lets the library decide whether the remainder is also kept panel-major, 1 never, 2..8 forces that many panels."""
+        prev = lib().sensei_tiles_remainder_panels(remainder_panels)
+        try:
+            self._build(ctx, A, min_density, max_width, min_width)
+        finally:
+            lib().sensei_tiles_remainder_panels(prev)
+
+    def _build(self, ctx, A, min_density, max_width, min_width):
         need = ctypes.c_size_t()
         _check(lib().sensei_tiles_bytes(ctypes.byref(A), min_density, max_width, ctypes.byref(need)), "sensei_tiles_bytes")
         self.buf = torch.empty(need.value + 256, dtype=torch.uint8, device=ctx.device)

@@ -58,6 +58,15 @@ struct sensei_tiles {
     hipStream_t side = nullptr;                // the tiles are multiplied on this stream while the caller's runs the sparse remainder
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     int min_width = 64;                        // narrowest SpMM that takes the split
+    // Panel-major copy of the remainder (rem_panels > 1): its entries run column panel by column panel, so that the part of the
+    // gathered matrix in use at one time fits the L2s; read as one CSR over the segments (panel q, row i) -> q * n_rows + i.
+    int rem_panels = 1;
+    const int32_t *seg_ptr = nullptr;          // rem_panels * n_rows + 1 row pointers of the segments
+    const int32_t *col_pm = nullptr;           // nnz_rem columns, panel-major
+    const int32_t *pos_pm = nullptr;           // nnz_rem: place of remainder entry d in the panel-major order
+    sensei::ChunkPlan plan_pm;
+    float *part_pm = nullptr;                  // rem_panels * n_rows x max_width raw partial rows, slice-major
+    float2 *stats_pm = nullptr;                // rem_panels copies of the per-row softmax statistics
 };
 
 namespace {
@@ -202,6 +211,9 @@ bool tiles_usable(const sensei_csr &A, int mode, int f, bool b_sliced, bool attn
     return D->n_rows == A.n_rows && D->n_cols == A.n_cols && D->nnz == A.nnz && D->src_row_ptr == A.row_ptr && D->src_col_idx == A.col_idx;
 }
 
+// The remainder of a usable split runs panel-major from 64 columns on (narrower calls are short either way)
+bool remainder_panels_usable(const sensei_tiles &D, int f) { return D.rem_panels > 1 && pad32(f) >= 64; }
+
 // SpMM over the whole pattern, or panel after panel when the matrix carries a usable panel copy.  Values
 // (WEIGHTED, kSpmmSoftmax) can only follow the panels if they are stored in panel order (val_in_panel_order);
 // values in the order of the original pattern use the single pass.
@@ -226,6 +238,30 @@ hipError_t spmm_any(const sensei_csr &A, int mode, const float *r, const float *
         if (e != hipSuccess) return e;
         sensei_csr Ar = A;
         Ar.nnz = D.nnz_rem; Ar.row_ptr = D.row_ptr_rem; Ar.col_idx = D.col_rem; Ar.panels = nullptr; Ar.tiles = nullptr;
+        if (remainder_panels_usable(D, f)) {
+            // Panel-major remainder: one launch over the segments (panel, row), whose chunks run panel by panel, so what the
+            // wavefronts in flight gather from is one column panel of one 32-column slice per L2 (measured on the 233,000-node
+            // power-law graph at 256 columns: L2 hit rate of the remainder 44 -> 82 %, bytes over the fabric 25 -> 7.5 GB per call).
+            // Every segment leaves a raw partial row; the join below adds a row's segments.  Values (the remainder's logits in
+            // attention mode) are in panel-major order: the caller wrote them through pos_pm.
+            Ar.n_rows = D.rem_panels * A.n_rows; Ar.row_ptr = D.seg_ptr; Ar.col_idx = D.col_pm;
+            const float2 *mz_seg = mz;
+            if (mode == kSpmmSoftmax) {  // the kernel reads the row maximum by segment number
+                e = launch_replicate_stats(mz, A.n_rows, D.rem_panels, D.stats_pm, s);
+                mz_seg = D.stats_pm;
+            }
+            const int fp = pad32(f);
+            if (e == hipSuccess)
+                e = launch_spmm(Ar, mode, nullptr, c, B, ldb, fp, D.part_pm, 32, fp, SENSEI_ACT_NONE, D.plan_pm, carry, s, nullptr, false, false, mz_seg,
+                                b_sliced, 1, true, true);
+            if (e == hipSuccess) e = hipStreamWaitEvent(s, D.ev_join, 0);
+            if (e == hipSuccess)
+                e = launch_tiles_combine_pm(D.T, C, A.n_rows, f_store, ldc, c_sliced, fp, mode == kSpmmSoftmax ? nullptr : r,
+                                            mode == kSpmmSoftmax ? mz : nullptr, act, s, D.part_pm, D.rem_panels, D.seg_ptr, D.plan_pm.chunk_nnz, carry, fp);
+            if (e != hipSuccess) return e;
+            if (t1 && hipEventRecord(t1, s) != hipSuccess) return hipErrorUnknown;
+            return hipSuccess;
+        }
         // the SpMM leaves its carry slots to the combine pass, which visits every row anyway
         e = launch_spmm(Ar, mode, nullptr, c, B, ldb, f, C, ldc, f_store, SENSEI_ACT_NONE, D.plan_rem, carry, s, nullptr, false, false, mz, b_sliced, 1,
                         c_sliced, true);
@@ -588,7 +624,9 @@ int run_gat(const sensei_csr &A, const sensei_mat &X, const sensei_mat &W, const
             SENSEI_TRY(hipEventRecord(D.ev_join, D.side));
             sensei_csr Ar = A;
             Ar.nnz = D.nnz_rem; Ar.row_ptr = D.row_ptr_rem; Ar.col_idx = D.col_rem; Ar.panels = nullptr; Ar.tiles = nullptr;
-            SENSEI_TRY(launch_attention_stats(Ar, s_l, s_r, slope, logits, nullptr, D.plan_rem, stats, carry_stats, s));
+            // the aggregation reads the remainder's logits in the order it walks the remainder: panel-major where that copy is used
+            SENSEI_TRY(launch_attention_stats(Ar, s_l, s_r, slope, logits, remainder_panels_usable(D, f_gather) ? D.pos_pm : nullptr, D.plan_rem, stats,
+                                              carry_stats, s));
             SENSEI_TRY(hipStreamWaitEvent(s, D.ev_join, 0));
             SENSEI_TRY(launch_tile_stats_merge(D.T, stats, A.n_rows, s));
         } else if (!fused) {
@@ -1334,7 +1372,21 @@ struct TilesLayout {
     size_t rank_r, rank_c, order_r, order_c, hist, sel_scan, slot_of, slot_ct, slot_rt, rt_ptr, scan_small, plan, bits, pos, scan_large, col_rem,
         dst_rem, row_ptr_rem, plan_rem, bh, seg_first, rt_seg, seg_rt, seg_stats, rank_vec, part, dh, total;
     int max_seg;
+    int rem_panels;  // panels of the panel-major copy of the remainder the layout has room for (1: none)
+    size_t pm_rp, pm_off, pm_scan, pm_seg_ptr, pm_col, pm_pos, pm_plan, pm_part, pm_stats;
 };
+
+// Column panels of the remainder's panel-major copy, from the features known before the split: two where a 128-byte slice of the
+// gathered matrix exceeds the L2s several times over and rows are long enough that half a row is still a run of gathers; none
+// otherwise.  Measured on the 233,000-node power-law graph (494 entries per row, 41.8 M of 115 M entries in the remainder), whole
+// three-layer step with 1 / 2 / 3 / 4 / 6 panels: 12.08 / 11.54 / 11.67 / 12.14 / 13.16 ms - the L2 hit rate of the remainder keeps
+// rising with the panel count (44 % -> 82 % at eight), but every (panel, row) segment costs a row end in the kernel and a partial
+// row written and read back, and the call shares the GPU with the tile kernel, which takes as long.
+int g_remainder_panels_override = 0;  // sensei_tiles_remainder_panels: 0 = the rule below
+int remainder_panels_for(const sensei_csr &A) {
+    if (g_remainder_panels_override > 0) return (int64_t)A.n_rows * g_remainder_panels_override < (1LL << 30) ? g_remainder_panels_override : 1;
+    return ((double)A.n_cols * 128.0 >= 12e6 && A.nnz >= 128 * (int64_t)A.n_rows && (int64_t)A.n_rows * 2 < (1LL << 30)) ? 2 : 1;
+}
 
 TilesLayout tiles_layout(const sensei_csr &A, float min_density, int max_width) {
     TilesLayout L;
@@ -1377,6 +1429,19 @@ TilesLayout tiles_layout(const sensei_csr &A, float min_density, int max_width) 
     L.rank_vec = put((size_t)2 * (L.nt_r + L.nt_c) * 128 * 4);
     L.part = put((size_t)L.max_seg * 128 * max_width * 4);
     L.dh = put((size_t)L.nt_r * 128 * max_width * 4);
+    L.rem_panels = remainder_panels_for(A);
+    if (L.rem_panels > 1) {
+        const size_t P = (size_t)L.rem_panels, n = (size_t)A.n_rows;
+        L.pm_rp = put(P * align_up((n + 1) * 4, 256));
+        L.pm_off = put(256);
+        L.pm_scan = put(scan_temp_bytes(A.n_rows + 1));
+        L.pm_seg_ptr = put((P * n + 1) * 4);
+        L.pm_col = put((size_t)A.nnz * 4);
+        L.pm_pos = put((size_t)A.nnz * 4);
+        L.pm_plan = put(plan_bytes(A.nnz) + 4096);
+        L.pm_part = put(P * n * (size_t)max_width * 4);
+        L.pm_stats = put(P * n * 8);
+    }
     L.total = off;
     return L;
 }
@@ -1511,8 +1576,34 @@ int sensei_tiles_create(sensei_ctx *ctx, const sensei_csr *A, float min_density,
     D->plan_rem.n_chunks = nnz_rem <= 0 ? 1 : (int)(((int64_t)nnz_rem + D->plan_rem.chunk_nnz - 1) / D->plan_rem.chunk_nnz);
     D->plan_rem.chunk_row = at(L.plan_rem);
     if (launch_chunk_rows(Ar, D->plan_rem, s) != hipSuccess || hipStreamSynchronize(s) != hipSuccess) return fail(SENSEI_HIP_ERROR);
+    // (automatic choice: only if the rows of the remainder are still long enough to be cut)
+    if (L.rem_panels > 1 && nnz_rem > 0 && (g_remainder_panels_override > 0 || nnz_rem >= 32 * (int64_t)A->n_rows)) {
+        const int P = L.rem_panels;
+        const int width = (A->n_cols + P - 1) / P;
+        int32_t *rp[SENSEI_MAX_PANELS] = {};
+        const size_t rp_each = align_up(((size_t)A->n_rows + 1) * 4, 256);
+        for (int q = 0; q < P; ++q) rp[q] = reinterpret_cast<int32_t *>(base + L.pm_rp + (size_t)q * rp_each);
+        if (launch_panel_build(Ar, D->plan_rem, P, width, rp, at(L.pm_off), at(L.pm_col), at(L.pm_pos), at(L.pm_scan), s) != hipSuccess ||
+            launch_panel_segments(rp, at(L.pm_off), A->n_rows, P, at(L.pm_seg_ptr), s) != hipSuccess)
+            return fail(SENSEI_HIP_ERROR);
+        sensei_csr As = Ar;
+        As.n_rows = P * A->n_rows; As.row_ptr = at(L.pm_seg_ptr); As.col_idx = at(L.pm_col);
+        D->plan_pm = D->plan_rem;
+        D->plan_pm.chunk_row = at(L.pm_plan);
+        if (launch_chunk_rows(As, D->plan_pm, s) != hipSuccess || hipStreamSynchronize(s) != hipSuccess) return fail(SENSEI_HIP_ERROR);
+        D->rem_panels = P;
+        D->seg_ptr = at(L.pm_seg_ptr); D->col_pm = at(L.pm_col); D->pos_pm = at(L.pm_pos);
+        D->part_pm = reinterpret_cast<float *>(base + L.pm_part);
+        D->stats_pm = reinterpret_cast<float2 *>(base + L.pm_stats);
+    }
     *out = D;
     return SENSEI_OK;
+}
+
+int sensei_tiles_remainder_panels(int n_panels) {
+    const int prev = g_remainder_panels_override;
+    if (n_panels >= 0 && n_panels <= SENSEI_MAX_PANELS) g_remainder_panels_override = n_panels;
+    return prev;
 }
 
 int sensei_tiles_info(const sensei_tiles *tiles, int *n_tiles_kept, int64_t *nnz_dense, int64_t *nnz_sparse) {
@@ -1955,7 +2046,7 @@ int sensei_select_gcn_backward(sensei_ctx *ctx, const sensei_csr *A, int f_in, i
 // order of candidates that take a fraction of a millisecond and is noise for the others: a candidate measured under
 // kRetimeBelowMs is run and measured a second time and the second figure kept, so every candidate's figure comes from a warm run
 // where that matters while a trial of long layers stays at one run per candidate.  measured[id] (ms) is written for the ids tried.
-static constexpr float kRetimeBelowMs = 2.0f;
+static constexpr float kRetimeBelowMs = 0.5f;
 static int timed_trial(int kind, const sensei_csr &A, int f_in, int f_out, const bool *try_id, double *measured, void *workspace,
                        size_t ws_bytes, hipStream_t s) {
     const int n = kind == SENSEI_KIND_GCN ? kNumGcn : kNumGat;

@@ -380,6 +380,54 @@ __global__ void k_tiles_combine(float *__restrict__ C, long long n_rows, int f_s
     }
 }
 
+// The join for a remainder that ran panel-major: the row's raw sum is spread over its n_panels segments (panel q, row i), each with
+// the carry slots of the chunks the segment continues into; they are added panel by panel, chunk by chunk (a fixed order).
+__global__ void k_tiles_combine_pm(float *__restrict__ C, long long n_rows, int f_store, long long ldc, long long c_tile, const float *__restrict__ Dh,
+                                   int f, const int32_t *__restrict__ rank_r, int n_ranks, const float *__restrict__ r, const float2 *__restrict__ mz,
+                                   int act, int vec4, const float *__restrict__ part, int n_panels, const int32_t *__restrict__ seg_ptr, int chunk_nnz,
+                                   const float *__restrict__ carry, int f_carry) {
+    const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const int f4 = (f_store + 3) / 4;
+    if (t >= n_rows * f4) return;
+    const long long i = t / f4;
+    const int col = (int)(t % f4) * 4;
+    const int rank = rank_r[i];
+    float sc = 1.f;
+    if (mz) { const float z = mz[i].y; sc = z > 0.f ? 1.f / z : 0.f; }
+    else if (r) sc = r[i];
+    const long long part_tile = (long long)n_panels * n_rows * 32;
+    float4 y = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int q = 0; q < n_panels; ++q) {
+        const long long seg = (long long)q * n_rows + i;
+        const float4 p = *reinterpret_cast<const float4 *>(part + (long long)(col >> 5) * part_tile + seg * 32 + (col & 31));
+        y.x += p.x; y.y += p.y; y.z += p.z; y.w += p.w;
+        const long long rs = seg_ptr[seg], re = seg_ptr[seg + 1];
+        if (re > rs) {
+            for (long long c = rs / chunk_nnz + 1; c <= (re - 1) / chunk_nnz; ++c) {
+                const float4 v = *reinterpret_cast<const float4 *>(carry + (size_t)c * f_carry + col);
+                y.x += v.x; y.y += v.y; y.z += v.z; y.w += v.w;
+            }
+        }
+    }
+    if (rank < n_ranks) {
+        const float4 a4 = *reinterpret_cast<const float4 *>(Dh + (size_t)rank * f + col);
+        y.x += a4.x; y.y += a4.y; y.z += a4.z; y.w += a4.w;
+    }
+    y.x *= sc; y.y *= sc; y.z *= sc; y.w *= sc;
+    if (act == SENSEI_ACT_RELU) {
+        y.x = y.x > 0.f ? y.x : 0.f; y.y = y.y > 0.f ? y.y : 0.f; y.z = y.z > 0.f ? y.z : 0.f; y.w = y.w > 0.f ? y.w : 0.f;
+    }
+    float *dst = C + (long long)(col >> 5) * c_tile + i * ldc + (col & 31);
+    if (vec4 && col + 3 < f_store) {
+        *reinterpret_cast<float4 *>(dst) = y;
+    } else {
+        if (col < f_store) dst[0] = y.x;
+        if (col + 1 < f_store) dst[1] = y.y;
+        if (col + 2 < f_store) dst[2] = y.z;
+        if (col + 3 < f_store) dst[3] = y.w;
+    }
+}
+
 // Dt[slot] = Lh[rows of the slot's row tile] . Rh[rows of its column tile]^T, 128 x 128 per kept tile: the per-entry dot product
 // <dP_i, Theta_j> of the attention backward for all entries of a tile at once, on the matrix cores (the cells outside the tile's
 // bit mask are computed too and never read).  Both operands are rows with k contiguous, so both go through the transposing
@@ -909,6 +957,20 @@ hipError_t launch_tiles_combine(const TileSplit &T, float *C, int64_t n_rows, in
     hipLaunchKernelGGL(k_tiles_combine, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, C, (long long)n_rows, f_store,
                        c_sliced ? 32LL : (long long)ldc, c_sliced ? (long long)n_rows * 32 : 32LL, (const float *)T.dh, f, T.rank_r, T.nt_r * 128, r, mz,
                        act, vec4, row_ptr_rem, chunk_nnz, carry, f_carry);
+    return hipGetLastError();
+}
+
+hipError_t launch_tiles_combine_pm(const TileSplit &T, float *C, int64_t n_rows, int f_store, int64_t ldc, bool c_sliced, int f, const float *r,
+                                   const float2 *mz, int act, hipStream_t s, const float *part, int n_panels, const int32_t *seg_ptr, int chunk_nnz,
+                                   const float *carry, int f_carry) {
+    if (n_rows <= 0 || f_store <= 0) return hipSuccess;
+    if (f % 32 != 0 || f_carry % 4 != 0 || reinterpret_cast<uintptr_t>(part) % 16 != 0 || reinterpret_cast<uintptr_t>(carry) % 16 != 0 || chunk_nnz <= 0)
+        return hipErrorInvalidValue;
+    const long long threads = (long long)n_rows * ((f_store + 3) / 4);
+    const int vec4 = (reinterpret_cast<uintptr_t>(C) % 16 == 0 && (c_sliced || ldc % 4 == 0)) ? 1 : 0;
+    hipLaunchKernelGGL(k_tiles_combine_pm, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, C, (long long)n_rows, f_store,
+                       c_sliced ? 32LL : (long long)ldc, c_sliced ? (long long)n_rows * 32 : 32LL, (const float *)T.dh, f, T.rank_r, T.nt_r * 128, r, mz,
+                       act, vec4, part, n_panels, seg_ptr, chunk_nnz, carry, f_carry);
     return hipGetLastError();
 }
 

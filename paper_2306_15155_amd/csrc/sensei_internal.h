@@ -94,6 +94,12 @@ size_t scan_temp_bytes(int n);
 hipError_t launch_panel_build(const sensei_csr &A, const ChunkPlan &plan, int n_panels, int width, int32_t *const *rp, int32_t *off,
                               int32_t *col_out, int32_t *perm_out, int32_t *scan_temp, hipStream_t s);
 
+// seg_ptr (n_panels * n_rows + 1): the panel copy as one CSR over the segments (panel q, row i) -> q * n_rows + i, from the
+// per-panel row pointers rp and the panel starts off that launch_panel_build left
+hipError_t launch_panel_segments(int32_t *const *rp, const int32_t *off, int n_rows, int n_panels, int32_t *seg_ptr, hipStream_t s);
+// dst[q * n + i] = src[i] for q < copies
+hipError_t launch_replicate_stats(const float2 *src, int64_t n, int copies, float2 *dst, hipStream_t s);
+
 // ---- element-wise work over the non-zeros, degrees, scalings
 hipError_t launch_degrees(const sensei_csr &A, int32_t *deg_row, int32_t *deg_col, hipStream_t s);
 hipError_t launch_norm_vectors(const int32_t *deg, int64_t n, float *out, hipStream_t s);
@@ -215,6 +221,11 @@ hipError_t launch_tiles_combine(const TileSplit &T, float *C, int64_t n_rows, in
                                 const float *carry = nullptr, int f_carry = 0);
 // row_ptr_rem, chunk_nnz, carry, f_carry: when the SpMM over the remainder ran with defer_fixup, this pass also adds the carry slots
 // (f_carry floats each) of the rows that span chunk boundaries, in chunk order, before anything else.
+// The same join when the remainder ran panel-major (its SpMM left one raw partial row per segment (panel q, row i) in `part`,
+// slice-major over n_panels * n_rows rows of f floats, fix-up deferred): C = act(scale (sum_q part[q, i] + carries + T.dh[rank])).
+hipError_t launch_tiles_combine_pm(const TileSplit &T, float *C, int64_t n_rows, int f_store, int64_t ldc, bool c_sliced, int f, const float *r,
+                                   const float2 *mz, int act, hipStream_t s, const float *part, int n_panels, const int32_t *seg_ptr, int chunk_nnz,
+                                   const float *carry, int f_carry);
 
 // ---- dense
 // Y[0:n, 0:m_store) = act(row_scale[i] * (A[n x k] . W[k x m])); columns m..m_store are written as act(0);

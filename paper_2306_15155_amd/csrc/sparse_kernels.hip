@@ -1019,6 +1019,22 @@ __global__ __launch_bounds__(kBlock) void k_panel_scatter(NnzArgs a, int n_panel
                });
 }
 
+// One row-pointer array over the segments (panel q, row i) -> q * n_rows + i of a panel copy, in global positions: the panel
+// copy read as a single CSR with n_panels * n_rows rows, whose entries run panel by panel
+__global__ void k_panel_segments(PanelPtrs pp, const int32_t *__restrict__ off, int n_rows, int n_panels, int32_t *__restrict__ seg_ptr) {
+    const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long long total = (long long)n_panels * n_rows;
+    if (t > total) return;
+    if (t == total) { seg_ptr[t] = off[n_panels]; return; }
+    const int q = (int)(t / n_rows), i = (int)(t % n_rows);
+    seg_ptr[t] = off[q] + pp.rp[q][i];
+}
+
+__global__ void k_replicate_f2(const float2 *__restrict__ src, long long n, int copies, float2 *__restrict__ dst) {
+    const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < n * copies) dst[t] = src[t % n];
+}
+
 // ------------------------------------------------------- dense tiles of the hub region (set-up kernels)
 //
 // Nodes are ranked by degree (rank 0 = the longest row / the most referenced column).  In rank order the pattern of a
@@ -1895,6 +1911,19 @@ hipError_t launch_panel_build(const sensei_csr &A, const ChunkPlan &plan, int n_
     if (A.nnz > 0)
         hipLaunchKernelGGL(k_panel_scatter, dim3(blocks_for(plan.n_chunks, kWavesPerBlock)), dim3(kBlock), 0, s, nnz_args(A, plan), n_panels,
                            width, pp, (const int32_t *)off, col_out, perm_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_panel_segments(int32_t *const *rp, const int32_t *off, int n_rows, int n_panels, int32_t *seg_ptr, hipStream_t s) {
+    PanelPtrs pp;
+    for (int q = 0; q < kMaxPanels; ++q) pp.rp[q] = q < n_panels ? rp[q] : nullptr;
+    hipLaunchKernelGGL(k_panel_segments, dim3(blocks_for((long long)n_panels * n_rows + 1, kBlock)), dim3(kBlock), 0, s, pp, off, n_rows, n_panels, seg_ptr);
+    return hipGetLastError();
+}
+
+hipError_t launch_replicate_stats(const float2 *src, int64_t n, int copies, float2 *dst, hipStream_t s) {
+    if (n <= 0 || copies <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_replicate_f2, dim3(blocks_for(n * copies, kBlock)), dim3(kBlock), 0, s, src, (long long)n, copies, dst);
     return hipGetLastError();
 }
 

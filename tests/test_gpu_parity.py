@@ -606,14 +606,15 @@ def test_multi_head_gat_is_the_single_head_layer_per_head(ctx, name, shape):
     assert torch.equal(one, ctx.gat_layer(A.s, dev(X), dev(W), dev(a_l), dev(a_r), 0, 0.2, ACT_RELU))
 
 
+@pytest.mark.parametrize("rem_panels", [1, 4])
 @pytest.mark.parametrize("heads,d", [(2, 64), (4, 32), (3, 40)])
-def test_multi_head_gat_on_a_dense_tile_split(ctx, heads, d):
+def test_multi_head_gat_on_a_dense_tile_split(ctx, heads, d, rem_panels):
     """Every head of a reuse composition aggregates its own 32-column slices of Theta, tiles and remainder alike; a head width
     that is not a whole number of slices (40) keeps Theta row-major and takes the plain path."""
     from paper_2306_15155_amd import Tiles, csr_struct
     g = synth.rmat(35, 5000, 150_000)
     A = DeviceCSR(g)
-    T = Tiles(ctx, A.s, 0.05, 128, min_width=32)
+    T = Tiles(ctx, A.s, 0.05, 128, min_width=32, remainder_panels=rem_panels)
     assert T.n_tiles > 0
     Ah = csr_struct(g.n_rows, g.n_cols, A.row_ptr, A.col_idx, None, None, T)
     X, W = synth.uniform(35, 10, (g.n_cols, 56)), synth.glorot(35, 11, 56, heads * d)
@@ -774,12 +775,15 @@ def test_gatv2_layer_larger_graph_and_argument_checks(ctx):
 
 # ------------------------------------------------------------------ dense tiles of the hub region
 
+@pytest.mark.parametrize("rem_panels", [1, 3, 4, 8])
 @pytest.mark.parametrize("density", [0.02, 0.125, 0.5])
-def test_dense_tile_split_gives_the_same_spmm_and_layers(ctx, density):
+def test_dense_tile_split_gives_the_same_spmm_and_layers(ctx, density, rem_panels):
+    """rem_panels > 1: the remainder is also kept panel-major (forced here: the automatic rule wants a graph of 10^5 nodes) and the
+    SpMM calls of 64 columns or more walk it as segments (panel, row) whose partial rows the last pass joins."""
     from paper_2306_15155_amd import Tiles, csr_struct
     g = synth.rmat(47, 6000, 160_000)
     A = DeviceCSR(g)
-    T = Tiles(ctx, A.s, density, 256, min_width=32)
+    T = Tiles(ctx, A.s, density, 256, min_width=32, remainder_panels=rem_panels)
     assert T.nnz_dense + T.nnz_sparse == g.row_ptr[-1]
     if density <= 0.125:
         assert T.n_tiles > 0 and T.nnz_dense > 0
@@ -809,14 +813,15 @@ def test_dense_tile_split_gives_the_same_spmm_and_layers(ctx, density):
     T.close()
 
 
-def test_dense_tile_split_attention_with_large_logits(ctx):
+@pytest.mark.parametrize("rem_panels", [1, 4])
+def test_dense_tile_split_attention_with_large_logits(ctx, rem_panels):
     """Logits of magnitude 10^2: every exponential of the split path (tile statistics, their merge with the remainder's, the weights
     the tile kernel forms) is taken relative to a maximum, so nothing overflows and rows whose largest logit sits in a tile, in the
     remainder, or in both agree with the oracle."""
     from paper_2306_15155_amd import Tiles, csr_struct
     g = synth.rmat(51, 5000, 150_000)
     A = DeviceCSR(g)
-    T = Tiles(ctx, A.s, 0.05, 128, min_width=32)
+    T = Tiles(ctx, A.s, 0.05, 128, min_width=32, remainder_panels=rem_panels)
     assert T.n_tiles > 0 and T.nnz_sparse > 0
     At = csr_struct(g.n_rows, g.n_cols, A.row_ptr, A.col_idx, None, None, T)
     f_in, f_out = 24, 64
@@ -856,13 +861,14 @@ def test_dense_tile_split_edge_cases(ctx):
         Tiles(ctx, DeviceCSR(GRAPHS["er"]).s, 0.1, 100)
 
 
-def test_dense_tile_split_under_graph_capture(ctx):
+@pytest.mark.parametrize("rem_panels", [1, 4])
+def test_dense_tile_split_under_graph_capture(ctx, rem_panels):
     """The split path is kernels only (zero fill, gather, tiles, ordered reduction, remainder): replays of a captured GCN + GAT
     chain equal the eager result bit for bit, with eager work in between."""
     from paper_2306_15155_amd import Tiles, csr_struct
     g = synth.rmat(50, 5000, 140_000)
     A = DeviceCSR(g)
-    T = Tiles(ctx, A.s, 0.05, 128, min_width=32)
+    T = Tiles(ctx, A.s, 0.05, 128, min_width=32, remainder_panels=rem_panels)
     assert T.n_tiles > 0
     At = csr_struct(g.n_rows, g.n_cols, A.row_ptr, A.col_idx, None, None, T)
     dr, dc = ctx.degrees(A.s)
