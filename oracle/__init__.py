@@ -262,6 +262,28 @@ def gatv2_layer(n_rows, n_cols, row_ptr, col_idx, X, W_l, W_r, att, slope=0.2, a
     return activation(spmm(sub_ptr, sub_idx, alpha, Th_r), act)
 
 
+def dotgat_layer(n_rows, n_cols, row_ptr, col_idx, X, W_q, W_k, W_v, scale, act=0, rows=None):
+    """Key-query attention layer (the score function of GaAN-style layers, which the paper's discussion of attention variants
+    names): Q = X W_q over the destinations (= the first n_rows sources), K = X W_k and V = X W_v over the sources,
+    e_ij = scale <Q[i], K[j]> on the stored entries (Eq. 2 with a dot product), alpha = row softmax of e as in Eq. 5,
+    Y = act(alpha V) as in Eq. 6.  ``rows`` selects output rows."""
+    row_ptr, col_idx = _i32(row_ptr), _i32(col_idx)
+    X32 = _f32(X)
+    K = gemm(X32.astype(np.float64), _f32(W_k).astype(np.float64))
+    V = gemm(X32.astype(np.float64), _f32(W_v).astype(np.float64))
+    sel = np.arange(n_rows, dtype=np.int64) if rows is None else np.asarray(rows, dtype=np.int64)
+    Q = gemm(X32[sel].astype(np.float64), _f32(W_q).astype(np.float64))
+    seg = [col_idx[row_ptr[i]:row_ptr[i + 1]] for i in sel]
+    sub_ptr = np.concatenate([[0], np.cumsum([x.size for x in seg])]).astype(np.int32)
+    sub_idx = (np.concatenate(seg) if seg else np.zeros(0)).astype(np.int32)
+    e = np.empty(sub_idx.size, dtype=np.float64)
+    for q in range(sel.size):
+        lo, hi = sub_ptr[q], sub_ptr[q + 1]
+        e[lo:hi] = float(scale) * (K[sub_idx[lo:hi]] @ Q[q])
+    alpha = edge_softmax(sub_ptr, e)
+    return activation(spmm(sub_ptr, sub_idx, alpha, V), act)
+
+
 def gat_layer_heads(n_rows, n_cols, row_ptr, col_idx, X, W, a_l, a_r, n_heads, slope=0.2, act=0, rows=None, omp=False):
     """Multi-head GAT with concatenated heads: head h is the single-head layer of Eq. 5 / 6 on columns
     [h d, (h + 1) d) of W, a_l, a_r (heads share nothing but the input)."""

@@ -66,6 +66,21 @@ def gatv2_layer_dense(A, X, W_l, W_r, att, slope=0.2, act=0):
     return (np.maximum(Y, 0.0) if act == 1 else Y), alpha
 
 
+def dotgat_layer_dense(A, X, W_q, W_k, W_v, scale, act=0):
+    """Dense key-query attention: softmax over the pattern of scale * Q K^T, times V (the textbook masked attention)."""
+    n_rows, _ = A.shape
+    Xd = X.astype(np.float64)
+    E = float(scale) * ((Xd[:n_rows] @ W_q.astype(np.float64)) @ (Xd @ W_k.astype(np.float64)).T)
+    E = np.where(A != 0.0, E, -np.inf)
+    alpha = np.zeros_like(E)
+    for i in range(n_rows):
+        if np.isfinite(E[i]).any():
+            ex = np.exp(E[i] - E[i][np.isfinite(E[i])].max())
+            alpha[i] = ex / ex.sum()
+    Y = alpha @ (Xd @ W_v.astype(np.float64))
+    return (np.maximum(Y, 0.0) if act == 1 else Y), alpha
+
+
 def spmm_dense(A_val, B):
     """Eq. 1 over every (i,j), zeros included: plain GEMM on the densified matrix."""
     n, m = A_val.shape

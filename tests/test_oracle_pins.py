@@ -431,3 +431,52 @@ def test_gatv2_special_cases():
     # from the slope-1 (static) ones
     assert np.max(np.abs(oracle.gatv2_layer(n, n, g.row_ptr, g.col_idx, X, W_l, W_r, att, 0.2) -
                          oracle.gatv2_layer(n, n, g.row_ptr, g.col_idx, X, W_l, W_r, att, 1.0))) > 1e-3
+
+
+# ------------------------------------------------------------- key-query attention layer
+
+def _kq_inputs(seed, n, f_in, d_k, f_out):
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((n, f_in)).astype(np.float32)
+    W_q = (0.6 * rng.standard_normal((f_in, d_k))).astype(np.float32)
+    W_k = (0.6 * rng.standard_normal((f_in, d_k))).astype(np.float32)
+    W_v = (0.5 * rng.standard_normal((f_in, f_out))).astype(np.float32)
+    return X, W_q, W_k, W_v
+
+
+@pytest.mark.parametrize("act", [0, 1])
+def test_key_query_attention_matches_dense_masked_attention(act):
+    g = _rand_graph(31, 45, 150)
+    X, W_q, W_k, W_v = _kq_inputs(31, 45, 7, 5, 6)
+    A = dense.dense_pattern(45, 45, g.row_ptr, g.col_idx)
+    want = dense.dotgat_layer_dense(A, X, W_q, W_k, W_v, 0.4, act)[0]
+    _close(oracle.dotgat_layer(45, 45, g.row_ptr, g.col_idx, X, W_q, W_k, W_v, 0.4, act), want)
+    rows = np.array([3, 44, 0, 17])
+    _close(oracle.dotgat_layer(45, 45, g.row_ptr, g.col_idx, X, W_q, W_k, W_v, 0.4, act, rows=rows), want[rows])
+    gr = _rect_block(32, 12, 30, 4)
+    Ar = dense.dense_pattern(12, 30, gr.row_ptr, gr.col_idx)
+    _close(oracle.dotgat_layer(12, 30, gr.row_ptr, gr.col_idx, X[:30], W_q, W_k, W_v, 0.4, act), dense.dotgat_layer_dense(Ar, X[:30], W_q, W_k, W_v, 0.4, act)[0])
+
+
+def test_key_query_attention_special_cases():
+    n = 40
+    g = _rand_graph(33, n, 130)
+    X, W_q, W_k, W_v = _kq_inputs(33, n, 6, 8, 5)
+    A = dense.dense_pattern(n, n, g.row_ptr, g.col_idx)
+    V = X.astype(np.float64) @ W_v.astype(np.float64)
+    # zero queries (or zero scale): all logits equal, the layer averages the value projections of the neighbours
+    _close(oracle.dotgat_layer(n, n, g.row_ptr, g.col_idx, X, np.zeros_like(W_q), W_k, W_v, 1.0), (A / A.sum(axis=1, keepdims=True)) @ V, 1e-12)
+    _close(oracle.dotgat_layer(n, n, g.row_ptr, g.col_idx, X, W_q, W_k, W_v, 0.0), (A / A.sum(axis=1, keepdims=True)) @ V, 1e-12)
+    # self loops only: alpha = 1, the layer is X W_v
+    gs = synth.self_loops_only(n)
+    _close(oracle.dotgat_layer(n, n, gs.row_ptr, gs.col_idx, X, W_q, W_k, W_v, 0.3), V, 1e-13)
+    # queries and keys are not interchangeable: swapping them changes the weights on a non-symmetric score
+    a = oracle.dotgat_layer(n, n, g.row_ptr, g.col_idx, X, W_q, W_k, W_v, 0.5)
+    b = oracle.dotgat_layer(n, n, g.row_ptr, g.col_idx, X, W_k, W_q, W_v, 0.5)
+    assert np.max(np.abs(a - b)) > 1e-3
+    # a very large scale picks the neighbour with the largest score: the row becomes that neighbour's value projection
+    Q, K = X.astype(np.float64) @ W_q.astype(np.float64), X.astype(np.float64) @ W_k.astype(np.float64)
+    hard = oracle.dotgat_layer(n, n, g.row_ptr, g.col_idx, X, W_q, W_k, W_v, 1e4)
+    for i in (0, 7, 21):
+        cols = g.col_idx[g.row_ptr[i]:g.row_ptr[i + 1]]
+        _close(hard[i], V[cols[np.argmax(K[cols] @ Q[i])]], 1e-9)
