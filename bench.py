@@ -654,6 +654,17 @@ def headline(args):
                           for cid, nm in ((0, "REUSE"), (1, "RECOMP"))}
             del Wl2, att2, tmp_out
         detail["gatv2_ms"] = v2
+        # key-query attention (dot-product scores, 64-column queries and keys) on the same shapes: reuse and recompute
+        kq = {}
+        for i, L in enumerate(layers):
+            if L["kind"] != "gat":
+                continue
+            Wq2, Wk2 = torch.randn((L["f_in"], 64), device=dev) * 0.05, torch.randn((L["f_in"], 64), device=dev) * 0.05
+            tmp_out = torch.empty_like(outs[i])
+            kq[tag(i)] = {nm: round(time_fn(lambda: ctx.dotgat_layer(A, src_of(i), Wq2, Wk2, Wd[i], 0.125, cid, L["act"], out=tmp_out), 2), 4)
+                          for cid, nm in ((0, "REUSE"), (1, "RECOMP"))}
+            del Wq2, Wk2, tmp_out
+        detail["key_query_attention_ms"] = kq
 
     # ---- one training iteration of the GCN stack of the workload (the layers whose input is X or the previous layer):
     # forward with the selected compositions, backward with the associations the cost model picks; the first layer needs no dX

@@ -260,6 +260,17 @@ int sensei_gatv2_workspace(const sensei_csr *A, int f_in, int f_out, int comp_id
 int sensei_gatv2_layer(sensei_ctx *ctx, const sensei_csr *A, sensei_mat X, sensei_mat W_l, sensei_mat W_r, const float *att, float neg_slope,
                        float *Y, int64_t ldy, int activation, int comp_id, void *workspace, size_t ws_bytes, void *stream);
 
+/* Key-query attention layer: the score function of GaAN-style layers (named with GATv2 among the attention variants the paper's
+ * discussion lists), Eq. 2 with a dot product as the inner operator: Q = X W_q over the destinations, K = X W_k over the sources,
+ * e_ij = scale <Q[i,:], K[j,:]> on every stored entry (scale is typically 1 / sqrt(d_k)), alpha = row softmax of e as in the GAT layer,
+ * Y = act( sum_j alpha_ij (X W_v)[j,:] ).  W_q, W_k: f_in x d_k; W_v: f_in x f_out.  Destinations are the first n_rows sources
+ * (n_rows <= n_cols).  Single head; GaAN's per-head gates are not part of it.
+ *   comp_id 0 (reuse):     aggregate the value projections X W_v at width f_out;
+ *   comp_id 1 (recompute): aggregate X at width f_in, then the GEMM with W_v (pays when f_in < f_out). */
+int sensei_dotgat_workspace(const sensei_csr *A, int f_in, int d_k, int f_out, int comp_id, size_t *bytes);
+int sensei_dotgat_layer(sensei_ctx *ctx, const sensei_csr *A, sensei_mat X, sensei_mat W_q, sensei_mat W_k, sensei_mat W_v, float scale, float *Y,
+                        int64_t ldy, int activation, int comp_id, void *workspace, size_t ws_bytes, void *stream);
+
 /* Dense-tile split of a pattern (layout, not a step of the paper; Section 3.2: which primitive is cheap depends on the input).
  * On a skewed graph the rows and columns of the highest degree meet in a region that is nearly full: with the nodes in
  * order of descending degree, tiles of 128 x 128 ranks (among the first 65,536 ranks of either side) that hold at least

@@ -31,7 +31,7 @@ EXPORTS = (
     "sensei_select", "sensei_profile_enable", "sensei_profile_read", "sensei_panels_bytes", "sensei_panels_create",
     "sensei_panels_count", "sensei_panels_destroy", "sensei_panels_set_min_width", "sensei_panels_tune_bytes",
     "sensei_panels_tune", "sensei_gcn_backward_workspace", "sensei_gcn_backward", "sensei_select_gcn_backward", "sensei_transpose_positions",
-    "sensei_gat_backward_workspace", "sensei_gat_backward", "sensei_gat_layer_heads", "sensei_sgc_workspace", "sensei_sgc_layer", "sensei_tagcn_workspace", "sensei_tagcn_layer", "sensei_gatv2_workspace", "sensei_gatv2_layer", "sensei_tiles_remainder_panels", "sensei_tiles_bytes", "sensei_tiles_create", "sensei_tiles_info",
+    "sensei_gat_backward_workspace", "sensei_gat_backward", "sensei_gat_layer_heads", "sensei_sgc_workspace", "sensei_sgc_layer", "sensei_tagcn_workspace", "sensei_tagcn_layer", "sensei_gatv2_workspace", "sensei_gatv2_layer", "sensei_dotgat_workspace", "sensei_dotgat_layer", "sensei_tiles_remainder_panels", "sensei_tiles_bytes", "sensei_tiles_create", "sensei_tiles_info",
            "sensei_tiles_set_min_width", "sensei_tiles_destroy",
 )
 
@@ -104,6 +104,8 @@ def lib():
         L.sensei_tagcn_layer.argtypes = [vp, P(CsrStruct), vp, vp, MatStruct, MatStruct, i32, vp, i64, i32, i32, vp, sz, vp]
         L.sensei_gatv2_workspace.argtypes = [P(CsrStruct), i32, i32, i32, P(sz)]
         L.sensei_gatv2_layer.argtypes = [vp, P(CsrStruct), MatStruct, MatStruct, MatStruct, vp, f32, vp, i64, i32, i32, vp, sz, vp]
+        L.sensei_dotgat_workspace.argtypes = [P(CsrStruct), i32, i32, i32, i32, P(sz)]
+        L.sensei_dotgat_layer.argtypes = [vp, P(CsrStruct), MatStruct, MatStruct, MatStruct, MatStruct, f32, vp, i64, i32, i32, vp, sz, vp]
         L.sensei_tiles_remainder_panels.argtypes = [i32]
         L.sensei_tiles_bytes.argtypes = [P(CsrStruct), f32, i32, P(sz)]
         L.sensei_tiles_create.argtypes = [vp, P(CsrStruct), f32, i32, vp, sz, vp, P(vp)]
@@ -481,6 +483,16 @@ class Context:
         self.ws.ensure(need.value)
         _check(lib().sensei_gatv2_layer(self._h, ctypes.byref(A), mat_struct(X), mat_struct(W_l), mat_struct(W_r), _ptr(att), neg_slope, _ptr(Y),
                                         mat_struct(Y).ld, activation, comp_id, self.ws.ptr, self.ws.nbytes, _stream()), "sensei_gatv2_layer")
+        return Y
+
+    def dotgat_layer(self, A: CsrStruct, X, W_q, W_k, W_v, scale, comp_id, activation=ACT_NONE, out=None):
+        """Key-query attention layer: e_ij = scale <x_i W_q, x_j W_k>; comp_id 0 aggregates X W_v, 1 aggregates X and projects afterwards."""
+        Y = torch.empty((A.n_rows, W_v.size(1)), dtype=torch.float32, device=self.device) if out is None else out
+        need = ctypes.c_size_t()
+        _check(lib().sensei_dotgat_workspace(ctypes.byref(A), X.size(1), W_q.size(1), W_v.size(1), comp_id, ctypes.byref(need)), "sensei_dotgat_workspace")
+        self.ws.ensure(need.value)
+        _check(lib().sensei_dotgat_layer(self._h, ctypes.byref(A), mat_struct(X), mat_struct(W_q), mat_struct(W_k), mat_struct(W_v), scale, _ptr(Y),
+                                         mat_struct(Y).ld, activation, comp_id, self.ws.ptr, self.ws.nbytes, _stream()), "sensei_dotgat_layer")
         return Y
 
     def gat_layer_heads(self, A: CsrStruct, X, W, a_l, a_r, n_heads, comp_id, neg_slope=0.2, activation=ACT_NONE, out=None):

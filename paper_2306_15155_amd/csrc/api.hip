@@ -725,6 +725,66 @@ int run_gatv2(const sensei_csr &A, const sensei_mat &X, const sensei_mat &Wl, co
     return SENSEI_OK;
 }
 
+// ---- key-query attention (the score function of GaAN-style layers): e_ij = scale <W_q x_i, W_k x_j>, Y = act(sum_j alpha_ij W_v x_j)
+size_t dotgat_ws(const sensei_csr &A, int f_in, int d_k, int f_out, int id) {
+    const int dk = pad32(d_k), fo = pad32(f_out), fi = pad4(f_in);
+    size_t b = plan_bytes(A.nnz) + softmax_ws_bytes(A) + 512;
+    b += align_up((size_t)(A.nnz > 0 ? A.nnz : 1) * sizeof(float), 256);       // logits, then the attention weights in place
+    b += align_up((size_t)A.n_rows * dk * sizeof(float), 256);                 // queries (slice-major)
+    b += align_up((size_t)A.n_cols * dk * sizeof(float), 256);                 // keys (slice-major)
+    if (id == 0) {
+        b += align_up((size_t)A.n_cols * fo * sizeof(float), 256);             // values (slice-major)
+        b += spmm_carry_bytes(A.nnz, fo);
+    } else {
+        b += spmm_carry_bytes(A.nnz, pad32(f_in));
+        b += align_up((size_t)A.n_rows * fi * sizeof(float), 256);             // U = alpha.X
+        b += align_up((size_t)A.n_cols * pad32(f_in) * sizeof(float), 256);    // slice-major copy of X
+    }
+    return b;
+}
+
+int run_dotgat(const sensei_csr &A, const sensei_mat &X, const sensei_mat &Wq, const sensei_mat &Wk, const sensei_mat &Wv, float scale, float *Y,
+               int64_t ldy, int act, int id, void *ws, size_t ws_bytes, hipStream_t s, Timers *tm) {
+    KernelTimer *kt = tm ? &tm->spmm : nullptr, *gt = tm ? &tm->gemm : nullptr;
+    const int f_in = (int)X.cols, d_k = (int)Wq.cols, f_out = (int)Wv.cols;
+    const int dk = pad32(d_k), fo = pad32(f_out), fi = pad4(f_in);
+    Carver cv(ws, ws_bytes);
+    ChunkPlan plan = make_plan(A, cv);
+    float2 *stats = cv.take<float2>((size_t)A.n_rows + 1);
+    float2 *carry_stats = cv.take<float2>((size_t)plan.n_chunks);
+    float *logits = cv.take<float>((size_t)(A.nnz > 0 ? A.nnz : 1));
+    float *Q = cv.take<float>((size_t)A.n_rows * dk);
+    float *K = cv.take<float>((size_t)A.n_cols * dk);
+    SENSEI_TRY(launch_chunk_rows(A, plan, s));
+    // both projections slice-major with zero pad columns, the layout the per-entry dot product walks (one launch per 32-column slice)
+    SENSEI_TRY(launch_gemm(X.ptr, X.ld, Wq.ptr, Wq.ld, Q, dk, A.n_rows, f_in, d_k, dk, SENSEI_ACT_NONE, s, nullptr, gt, true));
+    SENSEI_TRY(launch_gemm(X.ptr, X.ld, Wk.ptr, Wk.ld, K, dk, A.n_cols, f_in, d_k, dk, SENSEI_ACT_NONE, s, nullptr, gt, true));
+    SENSEI_TRY(launch_gat_dalpha(A, K, Q, d_k, nullptr, nullptr, logits, nullptr, plan, nullptr, s, scale));
+    SENSEI_TRY(launch_softmax(A, logits, logits, plan, stats, carry_stats, s));
+    sensei_csr Aw = A;
+    Aw.val = logits;
+    if (id == 0) {  // reuse: aggregate the value projections at width f_out
+        float *V = cv.take<float>((size_t)A.n_cols * fo);
+        float *carry = cv.take<float>(spmm_carry_bytes(A.nnz, fo) / sizeof(float));
+        SENSEI_TRY(launch_gemm(X.ptr, X.ld, Wv.ptr, Wv.ld, V, fo, A.n_cols, f_in, f_out, fo, SENSEI_ACT_NONE, s, nullptr, gt, true));
+        SENSEI_TRY(spmm_any(Aw, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, V, fo, fo, Y, ldy, f_out, act, plan, carry, s, kt, false, nullptr, true));
+    } else {        // recompute: aggregate the inputs at width f_in, then project
+        float *carry = cv.take<float>(spmm_carry_bytes(A.nnz, pad32(f_in)) / sizeof(float));
+        float *U = cv.take<float>((size_t)A.n_rows * fi);
+        const float *x_src = X.ptr;
+        const bool x_sliced = relayout_pays(A);
+        if (x_sliced) {
+            float *T = cv.take<float>((size_t)A.n_cols * pad32(f_in));
+            SENSEI_TRY(launch_to_slices(nullptr, X.ptr, X.ld, A.n_cols, f_in, T, s));
+            x_src = T;
+        }
+        SENSEI_TRY(spmm_any(Aw, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, x_src, X.ld, f_in, U, fi, f_in, SENSEI_ACT_NONE, plan, carry, s, kt, false,
+                            nullptr, x_sliced));
+        SENSEI_TRY(launch_gemm(U, fi, Wv.ptr, Wv.ld, Y, ldy, A.n_rows, f_in, f_out, f_out, act, s, nullptr, gt));
+    }
+    return SENSEI_OK;
+}
+
 // ---- backward of the GAT layer
 // The per-entry dot products of the attention backward can use the dense-tile split of A: same pattern, wide enough, and
 // every tile cell addressable by the (negative) codes in dst_rem.  Below 128 columns the extra pass that merges the two
@@ -2016,6 +2076,32 @@ int sensei_gatv2_layer(sensei_ctx *ctx, const sensei_csr *A, sensei_mat X, sense
     if (ws_bytes < gatv2_ws(*A, (int)X.cols, (int)W_r.cols, comp_id, false)) return SENSEI_WORKSPACE_TOO_SMALL;
     if (A->n_rows == 0) return SENSEI_OK;
     return run_gatv2(*A, X, W_l, W_r, att, neg_slope, Y, ldy, activation, comp_id, workspace, ws_bytes, as_stream(stream), &ctx->timers);
+}
+
+int sensei_dotgat_workspace(const sensei_csr *A, int f_in, int d_k, int f_out, int comp_id, size_t *bytes) {
+    if (!csr_ok(A, false) || f_in <= 0 || d_k <= 0 || f_out <= 0 || !bytes) return SENSEI_INVALID_ARGUMENT;
+    if (comp_id != 0 && comp_id != 1) return SENSEI_INVALID_COMPOSITION;
+    *bytes = dotgat_ws(*A, f_in, d_k, f_out, comp_id);
+    return SENSEI_OK;
+}
+
+int sensei_dotgat_layer(sensei_ctx *ctx, const sensei_csr *A, sensei_mat X, sensei_mat W_q, sensei_mat W_k, sensei_mat W_v, float scale, float *Y,
+                        int64_t ldy, int activation, int comp_id, void *workspace, size_t ws_bytes, void *stream) {
+    if (comp_id != 0 && comp_id != 1) return SENSEI_INVALID_COMPOSITION;
+    if (!ctx || !csr_ok(A, false) || !mat_ok(X) || !mat_ok(W_q) || !mat_ok(W_k) || !mat_ok(W_v)) return SENSEI_INVALID_ARGUMENT;
+    if (activation != SENSEI_ACT_NONE && activation != SENSEI_ACT_RELU) return SENSEI_INVALID_ARGUMENT;
+    if (A->n_rows > A->n_cols || X.rows != A->n_cols || X.cols <= 0 || W_q.rows != X.cols || W_k.rows != X.cols || W_v.rows != X.cols ||
+        W_q.cols <= 0 || W_q.cols != W_k.cols || W_v.cols <= 0 || ldy < W_v.cols)
+        return SENSEI_INVALID_ARGUMENT;
+    if (X.cols > (1 << 20) || W_q.cols > (1 << 20) || W_v.cols > (1 << 20)) return SENSEI_INVALID_ARGUMENT;
+    if ((!X.ptr && A->n_cols > 0) || !W_q.ptr || !W_k.ptr || !W_v.ptr || (!Y && A->n_rows > 0) || !workspace) return SENSEI_INVALID_ARGUMENT;
+    const size_t ybytes = mat_bytes(Y, A->n_rows, W_v.cols, ldy);
+    if (overlap(Y, ybytes, X.ptr, mat_bytes(X.ptr, X.rows, X.cols, X.ld)) || overlap(Y, ybytes, workspace, ws_bytes) ||
+        overlap(X.ptr, mat_bytes(X.ptr, X.rows, X.cols, X.ld), workspace, ws_bytes))
+        return SENSEI_INVALID_ARGUMENT;
+    if (ws_bytes < dotgat_ws(*A, (int)X.cols, (int)W_q.cols, (int)W_v.cols, comp_id)) return SENSEI_WORKSPACE_TOO_SMALL;
+    if (A->n_rows == 0) return SENSEI_OK;
+    return run_dotgat(*A, X, W_q, W_k, W_v, scale, Y, ldy, activation, comp_id, workspace, ws_bytes, as_stream(stream), &ctx->timers);
 }
 
 int sensei_select_workspace(int kind, const sensei_csr *A, int f_in, int f_out, size_t *bytes) {

@@ -131,7 +131,8 @@ size_t softmax_ws_bytes(const sensei_csr &A);
 hipError_t launch_row_sum(const sensei_csr &A, const float *val, int stride, float *out, const ChunkPlan &p, float *carry, hipStream_t s);
 // dalpha[k] = <dP[i,:], Theta[j,:]> per stored entry, rowdot[i] = sum_j alpha_ij dalpha_ij (skipped when rowdot is null); theta, dP slice-major
 hipError_t launch_gat_dalpha(const sensei_csr &A, const float *theta, const float *dP, int f, const float *logits, const float2 *mz,
-                             float *dalpha, float *rowdot, const ChunkPlan &p, float *carry, hipStream_t s);
+                             float *dalpha, float *rowdot, const ChunkPlan &p, float *carry, hipStream_t s, float scale = 1.f);
+// (with rowdot null and a scale it is the key-query score of an attention layer: dalpha[k] = scale <dP[i,:], theta[j,:]>)
 // dense-tile split: dalpha[k] from the remainder's values (where[k] >= 0) or the cells of the tiles' product Dt (where[k] < 0), and rowdot
 hipError_t launch_gat_dalpha_merge(const sensei_csr &A, const int32_t *where, const float *dalpha_rem, const float *Dt, const float *logits,
                                    const float2 *mz, float *dalpha, float *rowdot, const ChunkPlan &p, float *carry, hipStream_t s);

@@ -1343,6 +1343,7 @@ struct GatBwdArgs {
     float *rowdot, *carry;    // out, per row: sum_j alpha_ij dalpha_ij (+ per-chunk carry slots)
     long long theta_tile, dp_tile;  // floats from one tile to the next
     int n_tiles;
+    float scale;  // factor on every dot product (1 in the attention backward; the 1 / sqrt(d) of a key-query score)
 };
 
 // dalpha_ij = <dP[i,:], Theta[j,:]> for every stored entry (Eq. 2 with a dot product as the inner operator) together
@@ -1359,8 +1360,10 @@ __global__ __launch_bounds__(kBlock) void k_gat_dalpha(GatBwdArgs a, int tile, i
     const float *theta = a.theta + (size_t)tile * a.theta_tile + sub * 4;
     const float *dP = a.dP + (size_t)tile * a.dp_tile + sub * 4;
     auto piece = [&](int i, int lo, int hi) {
-        const float4 p = *reinterpret_cast<const float4 *>(dP + (size_t)i * 32);
-        const float4 q = *reinterpret_cast<const float4 *>(dP + (size_t)i * 32 + 16);
+        float4 p = *reinterpret_cast<const float4 *>(dP + (size_t)i * 32);
+        float4 q = *reinterpret_cast<const float4 *>(dP + (size_t)i * 32 + 16);
+        p.x *= a.scale; p.y *= a.scale; p.z *= a.scale; p.w *= a.scale;   // exact when the factor is 1
+        q.x *= a.scale; q.y *= a.scale; q.z *= a.scale; q.w *= a.scale;
         float m = 0.f, iz = 0.f, s = 0.f;
         if (LAST) {
             const float2 st = a.mz[i];
@@ -1794,8 +1797,9 @@ hipError_t launch_row_sum(const sensei_csr &A, const float *val, int stride, flo
 }
 
 hipError_t launch_gat_dalpha(const sensei_csr &A, const float *theta, const float *dP, int f, const float *logits, const float2 *mz,
-                             float *dalpha, float *rowdot, const ChunkPlan &p, float *carry, hipStream_t s) {
+                             float *dalpha, float *rowdot, const ChunkPlan &p, float *carry, hipStream_t s, float scale) {
     GatBwdArgs a;
+    a.scale = scale;
     a.n = nnz_args(A, p);
     a.theta = theta; a.dP = dP; a.logits = logits; a.mz = mz; a.dalpha = dalpha; a.rowdot = rowdot; a.carry = carry;
     a.theta_tile = (long long)(A.n_cols > 0 ? A.n_cols : 1) * 32;

@@ -354,6 +354,22 @@ def test_config4_gatv2_full_size(ctx, reddit_like):
         del Y
 
 
+def test_config4_key_query_attention_full_size(ctx, reddit_like):
+    """Key-query attention layer 602 -> 64 (64-column queries and keys) on the Reddit-shaped graph: sampled rows against the oracle."""
+    g, A = reddit_like
+    f_in, d_k, f_out = 602, 64, 64
+    X = synth.uniform(7, 10, (g.n_cols, f_in))
+    W_q, W_k, W_v = synth.glorot(7, 130, f_in, d_k), synth.glorot(7, 131, f_in, d_k), synth.glorot(7, 132, f_in, f_out)
+    rows = _sample_rows(g, 14, 300)
+    want = oracle.dotgat_layer(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W_q, W_k, W_v, 0.125, ACT_RELU, rows=rows)
+    sel = torch.from_numpy(rows.astype(np.int64)).to(DEV)
+    Xd, Wq, Wk, Wv = dev(X), dev(W_q), dev(W_k), dev(W_v)
+    for cid in (0, 1):
+        Y = ctx.dotgat_layer(A.s, Xd, Wq, Wk, Wv, 0.125, cid, ACT_RELU)
+        assert_close(Y[sel], want, what=f"key-query attention comp {cid}")
+        del Y
+
+
 def test_config4_gat_backward_full_size(ctx, reddit_like):
     """Training step of the GAT layer 602 -> 64 on the Reddit-shaped graph: every gradient against the oracle.
 

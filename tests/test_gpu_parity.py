@@ -773,6 +773,38 @@ def test_gatv2_layer_larger_graph_and_argument_checks(ctx):
         ctx.gatv2_layer(A.s, dev(X), dev(W_l[:, :64].copy()), dev(W_r), dev(att), 0)   # W_l and W_r differ in shape
 
 
+# ------------------------------------------------------------------ key-query attention layer
+
+@pytest.mark.parametrize("name", ["er", "rmat_hub", "hub_empty", "rect", "selfloops", "tiny"])
+@pytest.mark.parametrize("shape", [(40, 8, 24), (24, 32, 32), (9, 64, 40), (50, 41, 9), (100, 130, 64)])   # f_in, d_k, f_out
+def test_key_query_attention_layer_matches_the_definition(ctx, name, shape):
+    g = GRAPHS[name]
+    A = DeviceCSR(g)
+    f_in, d_k, f_out = shape
+    X = synth.uniform(55, 10, (g.n_cols, f_in))
+    W_q, W_k, W_v = synth.glorot(55, 11, f_in, d_k), synth.glorot(55, 12, f_in, d_k), synth.glorot(55, 13, f_in, f_out)
+    scale = float(1.0 / np.sqrt(d_k))
+    ref = oracle.dotgat_layer(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W_q, W_k, W_v, scale, ACT_RELU)
+    Xd, Wq, Wk, Wv = dev(X), dev(W_q), dev(W_k), dev(W_v)
+    for cid in (0, 1):
+        assert_close(ctx.dotgat_layer(A.s, Xd, Wq, Wk, Wv, scale, cid, ACT_RELU), ref, what=f"key-query attention comp {cid}")
+
+
+def test_key_query_attention_larger_graph_large_scores_and_argument_checks(ctx):
+    g = synth.rmat(56, 6000, 120_000)
+    A = DeviceCSR(g)
+    X = synth.uniform(56, 10, (g.n_cols, 72))
+    W_q, W_k, W_v = synth.glorot(56, 11, 72, 96), synth.glorot(56, 12, 72, 96), synth.glorot(56, 13, 72, 48)
+    for scale in (0.1, 4.0):   # 4.0: scores of a few tens, nearly one-hot weights, the row maximum matters
+        ref = oracle.dotgat_layer(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W_q, W_k, W_v, scale)
+        for cid in (0, 1):
+            assert_close(ctx.dotgat_layer(A.s, dev(X), dev(W_q), dev(W_k), dev(W_v), scale, cid), ref, what=f"scale {scale} comp {cid}")
+    with pytest.raises(SenseiError):
+        ctx.dotgat_layer(A.s, dev(X), dev(W_q), dev(W_k), dev(W_v), 0.1, 2)
+    with pytest.raises(SenseiError):
+        ctx.dotgat_layer(A.s, dev(X), dev(W_q[:, :64].copy()), dev(W_k), dev(W_v), 0.1, 0)   # queries and keys of different width
+
+
 # ------------------------------------------------------------------ dense tiles of the hub region
 
 @pytest.mark.parametrize("rem_panels", [1, 3, 4, 8])
