@@ -223,6 +223,28 @@ def sgc_layer(n, row_ptr, col_idx, X, W, k_hops, act=0, rows=None):
     return activation(gemm(H[pick], W64), act)
 
 
+def sgc_backward(n, row_ptr, col_idx, X, W, k_hops, dY, Y=None, act=0, rows=None):
+    """Gradient of sum(dY * Y) for the K-hop layer Y = act(A^^k X W) (chain rule on the definition in sgc_layer) -> (dX, dW):
+    dP = dY (.) [Y > 0] (the fp32 forward output ``Y`` supplies the ReLU mask), G = (A^^T)^k dP, dW = X^T G, dX = G W^T.
+    A^^T is written out as the transposed pattern with the same entry weights r_i c_j.  ``rows`` selects rows of dX."""
+    row_ptr, col_idx = _i32(row_ptr), _i32(col_idx)
+    dr, dc = degrees(n, n, row_ptr, col_idx)
+    r, c = inv_sqrt_deg(dr), inv_sqrt_deg(dc)
+    val = sddmm_mul(row_ptr, col_idx, None, r, c)                      # A^[i, j] = r_i c_j on the pattern
+    src = np.repeat(np.arange(n, dtype=np.int32), np.diff(row_ptr))    # row of every stored entry
+    order = np.lexsort((src, col_idx))                                 # the same entries by (column, row): rows of the transpose
+    t_ptr = np.concatenate([[0], np.cumsum(np.bincount(col_idx, minlength=n))]).astype(np.int32)
+    t_idx, t_val = src[order], val[order]
+    G = _f32(dY).astype(np.float64)
+    if act == 1:
+        G = G * (_f32(Y) > 0)
+    for _ in range(k_hops):
+        G = spmm(t_ptr, t_idx, t_val, G)
+    dW = gemm(np.ascontiguousarray(_f32(X).astype(np.float64).T), G)
+    dX = gemm(G if rows is None else G[np.asarray(rows, dtype=np.int64)], np.ascontiguousarray(_f32(W).astype(np.float64).T))
+    return dX, dW
+
+
 def tagcn_layer(n, row_ptr, col_idx, X, W, k_hops, act=0):
     """TAGCN layer act(sum_{k=0..K} A^^k X W_k) with A^ the normalised operator of Eq. 3 on a square pattern and W the
     K + 1 weight blocks stacked by rows: the sum written out term by term, each hop one more propagation of the last."""

@@ -224,3 +224,50 @@ def test_backward_is_linear_in_the_upstream_gradient():
                lambda d: oracle.gat_backward(30, 30, g.row_ptr, g.col_idx, X, W, a_l, a_r, d)):
         for a, b, s in zip(fn(d1), fn(d2), fn((d1 + d2).astype(np.float32))):
             _close(np.asarray(a) + np.asarray(b), s, 1e-11)
+
+
+# ------------------------------------------------------------------ K-hop layer (SGC)
+
+@pytest.mark.parametrize("k_hops", [1, 2, 3])
+def test_sgc_backward_is_the_gradient_of_the_forward(k_hops):
+    rng = np.random.default_rng(40 + k_hops)
+    u = rng.integers(0, 12, size=26)
+    v = rng.integers(0, 12, size=26)
+    g = synth.build_csr(12, 12, u, v, False, True)      # not symmetric: the transposed operator really is another matrix
+    f_in, f_out = 4, 3
+    X, W, dY = _grid(rng, (12, f_in)), _grid(rng, (f_in, f_out)), _grid(rng, (12, f_out))
+
+    def loss():
+        return float(np.sum(dY.astype(np.float64) * oracle.sgc_layer(12, g.row_ptr, g.col_idx, X, W, k_hops, 0)))
+
+    dX, dW = oracle.sgc_backward(12, g.row_ptr, g.col_idx, X, W, k_hops, dY)
+    _close(dX, _central(loss, X, 2.0 ** -8), 1e-9)      # the layer is linear in X and in W: central differences are exact
+    _close(dW, _central(loss, W, 2.0 ** -8), 1e-9)
+    rows = np.array([7, 0, 3])
+    _close(oracle.sgc_backward(12, g.row_ptr, g.col_idx, X, W, k_hops, dY, rows=rows)[0], dX[rows], 1e-14)
+
+
+def test_sgc_backward_special_cases():
+    rng = np.random.default_rng(44)
+    g = synth.erdos_renyi(9, 20, 45)
+    X, W, dY = _grid(rng, (20, 5)), _grid(rng, (5, 6)), _grid(rng, (20, 6))
+    # one hop is the GCN layer
+    a = oracle.sgc_backward(20, g.row_ptr, g.col_idx, X, W, 1, dY)
+    b = oracle.gcn_backward(20, 20, g.row_ptr, g.col_idx, X, W, dY)
+    _close(a[0], b[0], 1e-13)
+    _close(a[1], b[1], 1e-13)
+    # dense algebra: dX = (A^^T)^k dP W^T, dW = X^T (A^^T)^k dP, with the ReLU mask of the forward output
+    A = dense.dense_pattern(20, 20, g.row_ptr, g.col_idx)
+    d = A.sum(axis=1)
+    Ahat = A / np.sqrt(np.outer(d, A.sum(axis=0)))
+    Y = oracle.sgc_layer(20, g.row_ptr, g.col_idx, X, W, 3, 1).astype(np.float32)
+    assert (Y > 0).any() and (Y == 0).any()
+    G = np.linalg.matrix_power(Ahat.T, 3) @ (dY.astype(np.float64) * (Y > 0))
+    dX, dW = oracle.sgc_backward(20, g.row_ptr, g.col_idx, X, W, 3, dY, Y=Y, act=1)
+    _close(dX, G @ W.astype(np.float64).T, 1e-12)
+    _close(dW, X.astype(np.float64).T @ G, 1e-12)
+    # self loops only: A^ = I, the layer is a GEMM whatever k
+    gs = synth.self_loops_only(20)
+    dXs, dWs = oracle.sgc_backward(20, gs.row_ptr, gs.col_idx, X, W, 4, dY)
+    _close(dXs, dY.astype(np.float64) @ W.astype(np.float64).T, 1e-13)
+    _close(dWs, X.astype(np.float64).T @ dY.astype(np.float64), 1e-13)
