@@ -354,6 +354,17 @@ int sensei_gcn_backward(sensei_ctx *ctx, const sensei_csr *A, const sensei_csr *
                         sensei_mat W, const float *Y, int64_t ldy, sensei_mat dY, int activation, const float *U_saved, int64_t ldu,
                         float *dX, int64_t lddx, float *dW, int64_t lddw, int bwd_id, void *workspace, size_t ws_bytes, void *stream);
 
+/* Backward of the K-hop layer sensei_sgc_layer, Y = act( A^^k X W ) on a square pattern: dP = dY (.) [Y > 0], G = (A^^T)^k dP,
+ * dW = X^T G, dX = G W^T (skipped when dX is NULL), with the two associations of sensei_gcn_backward applied to the k hops:
+ *     SENSEI_GCN_BWD_AGG: the k transposed hops run on dP at width f_out, then dW = X^T G and dX = G W^T;
+ *     SENSEI_GCN_BWD_UPD: dW = U^T dP with U = A^^k X recomputed (k hops at width f_in), dX = (A^^T)^k (dP W^T) at width f_in.
+ * Hops keep their intermediate results in the slice-major layout the next hop gathers from, as in the forward.  k_hops = 1 is
+ * sensei_gcn_backward without a saved U.  Arguments as there. */
+int sensei_sgc_backward_workspace(const sensei_csr *A, int f_in, int f_out, int k_hops, int bwd_id, size_t *bytes);
+int sensei_sgc_backward(sensei_ctx *ctx, const sensei_csr *A, const sensei_csr *At, const float *r, const float *c, sensei_mat X, sensei_mat W,
+                        int k_hops, const float *Y, int64_t ldy, sensei_mat dY, int activation, float *dX, int64_t lddx, float *dW, int64_t lddw,
+                        int bwd_id, void *workspace, size_t ws_bytes, void *stream);
+
 /* Which association of the GCN backward is predicted faster for this graph and these sizes (the additive
  * per-primitive cost model of sensei_select, host arithmetic only).  have_saved_u: the forward kept
  * U = D_r^(-1/2) A~ D_c^(-1/2) X; want_dx: the input gradient is needed.  est_ms: optional, 2 entries. */

@@ -31,7 +31,7 @@ EXPORTS = (
     "sensei_select", "sensei_profile_enable", "sensei_profile_read", "sensei_panels_bytes", "sensei_panels_create",
     "sensei_panels_count", "sensei_panels_destroy", "sensei_panels_set_min_width", "sensei_panels_tune_bytes",
     "sensei_panels_tune", "sensei_gcn_backward_workspace", "sensei_gcn_backward", "sensei_select_gcn_backward", "sensei_transpose_positions",
-    "sensei_gat_backward_workspace", "sensei_gat_backward", "sensei_gat_layer_heads", "sensei_sgc_workspace", "sensei_sgc_layer", "sensei_tagcn_workspace", "sensei_tagcn_layer", "sensei_gatv2_workspace", "sensei_gatv2_layer", "sensei_dotgat_workspace", "sensei_dotgat_layer", "sensei_tiles_remainder_panels", "sensei_tiles_bytes", "sensei_tiles_create", "sensei_tiles_info",
+    "sensei_gat_backward_workspace", "sensei_gat_backward", "sensei_gat_layer_heads", "sensei_sgc_workspace", "sensei_sgc_layer", "sensei_sgc_backward_workspace", "sensei_sgc_backward", "sensei_tagcn_workspace", "sensei_tagcn_layer", "sensei_gatv2_workspace", "sensei_gatv2_layer", "sensei_dotgat_workspace", "sensei_dotgat_layer", "sensei_tiles_remainder_panels", "sensei_tiles_bytes", "sensei_tiles_create", "sensei_tiles_info",
            "sensei_tiles_set_min_width", "sensei_tiles_destroy",
 )
 
@@ -100,6 +100,9 @@ def lib():
         L.sensei_gat_layer_heads.argtypes = [vp, P(CsrStruct), MatStruct, MatStruct, vp, vp, i32, f32, vp, i64, i32, i32, vp, sz, vp]
         L.sensei_sgc_workspace.argtypes = [P(CsrStruct), i32, i32, i32, P(sz)]
         L.sensei_sgc_layer.argtypes = [vp, P(CsrStruct), vp, vp, MatStruct, MatStruct, i32, vp, i64, i32, i32, vp, sz, vp]
+        L.sensei_sgc_backward_workspace.argtypes = [P(CsrStruct), i32, i32, i32, i32, P(sz)]
+        L.sensei_sgc_backward.argtypes = [vp, P(CsrStruct), P(CsrStruct), vp, vp, MatStruct, MatStruct, i32, vp, i64, MatStruct, i32, vp, i64, vp, i64,
+                                          i32, vp, sz, vp]
         L.sensei_tagcn_workspace.argtypes = [P(CsrStruct), i32, i32, i32, i32, P(sz)]
         L.sensei_tagcn_layer.argtypes = [vp, P(CsrStruct), vp, vp, MatStruct, MatStruct, i32, vp, i64, i32, i32, vp, sz, vp]
         L.sensei_gatv2_workspace.argtypes = [P(CsrStruct), i32, i32, i32, P(sz)]
@@ -464,6 +467,20 @@ class Context:
         _check(lib().sensei_sgc_layer(self._h, ctypes.byref(A), _ptr(r), _ptr(c), mat_struct(X), mat_struct(W), k_hops, _ptr(Y), mat_struct(Y).ld,
                                       activation, comp_id, self.ws.ptr, self.ws.nbytes, _stream()), "sensei_sgc_layer")
         return Y
+
+    def sgc_backward(self, A: CsrStruct, At: CsrStruct, r, c, X, W, k_hops, dY, bwd_id, Y=None, activation=ACT_NONE, want_dx=True):
+        """Backward of sgc_layer -> (dX or None, dW); ``At`` is the transposed pattern (A itself when symmetric)."""
+        f_in, f_out = W.size(0), W.size(1)
+        dX = torch.empty((A.n_cols, f_in), dtype=torch.float32, device=self.device) if want_dx else None
+        dW = torch.empty((f_in, f_out), dtype=torch.float32, device=self.device)
+        need = ctypes.c_size_t()
+        _check(lib().sensei_sgc_backward_workspace(ctypes.byref(A), f_in, f_out, k_hops, bwd_id, ctypes.byref(need)), "sensei_sgc_backward_workspace")
+        self.ws.ensure(need.value)
+        _check(lib().sensei_sgc_backward(self._h, ctypes.byref(A), ctypes.byref(At), _ptr(r), _ptr(c), mat_struct(X), mat_struct(W), k_hops, _ptr(Y),
+                                         mat_struct(Y).ld if Y is not None else 0, mat_struct(dY), activation, _ptr(dX),
+                                         mat_struct(dX).ld if dX is not None else 0, _ptr(dW), mat_struct(dW).ld, bwd_id, self.ws.ptr,
+                                         self.ws.nbytes, _stream()), "sensei_sgc_backward")
+        return dX, dW
 
     def tagcn_layer(self, A: CsrStruct, r, c, X, W, k_hops, comp_id, activation=ACT_NONE, out=None):
         """TAGCN layer act(sum_k A^^k X W_k); W stacks W_0 .. W_k_hops by rows; comp_id 0 aggregates first, 1 updates first."""

@@ -449,9 +449,13 @@ int run_tagcn(const sensei_csr &A, const float *r, const float *c, const sensei_
 }
 
 // ---- backward of the GCN layer
-size_t gcn_bwd_ws(const sensei_csr &A, int f_in, int f_out, int id) {
+size_t gcn_bwd_ws(const sensei_csr &A, int f_in, int f_out, int id, int k_hops = 1) {
     const int64_t nnz = A.nnz;
     size_t b = 2 * plan_bytes(nnz) + 256;
+    if (k_hops > 1) {  // K-hop layer: a second slice-major hop buffer per chain of hops, and the merged scaling r (.) c
+        b += align_up((size_t)A.n_rows * sizeof(float), 256);
+        b += (id == SENSEI_GCN_BWD_AGG ? 1 : 3) * align_up((size_t)A.n_cols * pad32(id == SENSEI_GCN_BWD_AGG ? f_out : f_in) * sizeof(float), 256);
+    }
     b += align_up((size_t)pad4(f_in) * pad4(f_out) * sizeof(float), 256);                             // W^T
     if (id == SENSEI_GCN_BWD_AGG) {
         b += spmm_carry_bytes(nnz, pad32(f_out));
@@ -471,24 +475,40 @@ size_t gcn_bwd_ws(const sensei_csr &A, int f_in, int f_out, int id) {
 
 int run_gcn_backward(const sensei_csr &A, const sensei_csr &At, const float *r, const float *c, const sensei_mat &X, const sensei_mat &W,
                      const float *Y, int64_t ldy, const sensei_mat &dY, int act, const float *U_saved, int64_t ldu, float *dX, int64_t lddx,
-                     float *dW, int64_t lddw, int id, void *ws, size_t ws_bytes, hipStream_t s) {
+                     float *dW, int64_t lddw, int id, void *ws, size_t ws_bytes, hipStream_t s, int k_hops = 1) {
     const int f_in = (int)X.cols, f_out = (int)W.cols;
     const float *mask = (act == SENSEI_ACT_RELU) ? Y : nullptr;
     Carver cv(ws, ws_bytes);
     ChunkPlan plan_t = make_plan(At, cv);
     SENSEI_TRY(launch_chunk_rows(At, plan_t, s));
+    // K-hop layer (square pattern): every chain of hops keeps its intermediate results slice-major, one buffer written while the
+    // other is gathered from, with the adjacent scalings of two hops merged into r (.) c, as in the forward
+    float *rc = nullptr;
+    if (k_hops > 1) {
+        rc = cv.take<float>((size_t)A.n_rows);
+        SENSEI_TRY(launch_row_broadcast(r, c, 1, A.n_rows, 1, rc, 1, SENSEI_ACT_NONE, s));
+    }
     if (id == SENSEI_GCN_BWD_AGG) {
         const int fo4 = pad4(f_out);
         float *carry = cv.take<float>(spmm_carry_bytes(At.nnz, pad32(f_out)) / sizeof(float));
         float *T = cv.take<float>((size_t)A.n_rows * pad32(f_out));
         float *G = cv.take<float>((size_t)A.n_cols * fo4);
         double *part = cv.take<double>(gemm_tn_bytes(A.n_cols, f_in, f_out) / sizeof(double));
-        // T = r (x) (dY (.) mask), slice-major when the transposed SpMM gathers each row often enough
-        const bool sliced = relayout_pays(At);
+        // T = r (x) (dY (.) mask), slice-major when the transposed SpMM gathers each row often enough (always between hops)
+        const bool sliced = relayout_pays(At) || k_hops > 1;
         if (sliced) SENSEI_TRY(launch_to_slices(r, dY.ptr, dY.ld, A.n_rows, f_out, T, s, mask, ldy));
         else SENSEI_TRY(launch_row_broadcast(r, dY.ptr, dY.ld, A.n_rows, f_out, T, fo4, SENSEI_ACT_NONE, s, mask, ldy));
+        const float *last = T;
+        if (k_hops > 1) {  // inner hops: T <- (r (.) c) (x) (A~^T T)
+            float *T2 = cv.take<float>((size_t)A.n_cols * pad32(f_out));
+            float *buf[2] = {T, T2};
+            for (int k = 0; k + 1 < k_hops; ++k)
+                SENSEI_TRY(spmm_any(At, SENSEI_SPMM_PATTERN, rc, nullptr, buf[k & 1], pad32(f_out), pad32(f_out), buf[(k + 1) & 1], pad32(f_out),
+                                    pad32(f_out), SENSEI_ACT_NONE, plan_t, carry, s, nullptr, false, nullptr, true, true));
+            last = buf[(k_hops - 1) & 1];
+        }
         // G = c (x) (A~^T T)
-        SENSEI_TRY(spmm_any(At, SENSEI_SPMM_PATTERN, c, nullptr, T, fo4, f_out, G, fo4, f_out, SENSEI_ACT_NONE, plan_t, carry, s, nullptr, false,
+        SENSEI_TRY(spmm_any(At, SENSEI_SPMM_PATTERN, c, nullptr, last, fo4, f_out, G, fo4, f_out, SENSEI_ACT_NONE, plan_t, carry, s, nullptr, false,
                             nullptr, sliced));
         SENSEI_TRY(launch_gemm_tn(X.ptr, X.ld, G, fo4, A.n_cols, f_in, f_out, dW, lddw, part, s));
         if (dX) {
@@ -509,10 +529,19 @@ int run_gcn_backward(const sensei_csr &A, const sensei_csr &At, const float *r, 
             SENSEI_TRY(launch_chunk_rows(A, plan, s));
             float *T = cv.take<float>((size_t)A.n_cols * fi32);
             float *Uw = cv.take<float>((size_t)A.n_rows * fi4);
-            const bool sliced = relayout_pays(A);
+            const bool sliced = relayout_pays(A) || k_hops > 1;
             if (sliced) SENSEI_TRY(launch_to_slices(c, X.ptr, X.ld, A.n_cols, f_in, T, s));
             else SENSEI_TRY(launch_row_broadcast(c, X.ptr, X.ld, A.n_cols, f_in, T, fi4, SENSEI_ACT_NONE, s));
-            SENSEI_TRY(spmm_any(A, SENSEI_SPMM_PATTERN, r, nullptr, T, fi4, f_in, Uw, fi4, f_in, SENSEI_ACT_NONE, plan, carry, s, nullptr, false,
+            const float *last = T;
+            if (k_hops > 1) {  // the inner hops of the forward: T <- (r (.) c) (x) (A~ T)
+                float *T2 = cv.take<float>((size_t)A.n_cols * fi32);
+                float *buf[2] = {T, T2};
+                for (int k = 0; k + 1 < k_hops; ++k)
+                    SENSEI_TRY(spmm_any(A, SENSEI_SPMM_PATTERN, rc, nullptr, buf[k & 1], fi32, fi32, buf[(k + 1) & 1], fi32, fi32, SENSEI_ACT_NONE, plan,
+                                        carry, s, nullptr, false, nullptr, true, true));
+                last = buf[(k_hops - 1) & 1];
+            }
+            SENSEI_TRY(spmm_any(A, SENSEI_SPMM_PATTERN, r, nullptr, last, fi4, f_in, Uw, fi4, f_in, SENSEI_ACT_NONE, plan, carry, s, nullptr, false,
                                 nullptr, sliced));
             U = Uw;
             ld_u = fi4;
@@ -523,10 +552,19 @@ int run_gcn_backward(const sensei_csr &A, const sensei_csr &At, const float *r, 
             float *V = cv.take<float>((size_t)A.n_rows * fi32);
             SENSEI_TRY(launch_transpose(W.ptr, W.ld, f_in, f_out, Wt, fi4, s));
             // V = r (x) (dP W^T), written slice-major by the GEMM epilogue; dX = c (x) (A~^T V)
-            const bool sliced = relayout_pays(At);
+            const bool sliced = relayout_pays(At) || k_hops > 1;
             SENSEI_TRY(launch_gemm(dP, fo4, Wt, fi4, V, sliced ? fi32 : fi4, A.n_rows, f_out, f_in, sliced ? fi32 : f_in, SENSEI_ACT_NONE, s, r,
                                    nullptr, sliced));
-            SENSEI_TRY(spmm_any(At, SENSEI_SPMM_PATTERN, c, nullptr, V, fi4, f_in, dX, lddx, f_in, SENSEI_ACT_NONE, plan_t, carry, s, nullptr, false,
+            const float *last = V;
+            if (k_hops > 1) {  // inner hops of the transposed chain
+                float *V2 = cv.take<float>((size_t)A.n_cols * fi32);
+                float *buf[2] = {V, V2};
+                for (int k = 0; k + 1 < k_hops; ++k)
+                    SENSEI_TRY(spmm_any(At, SENSEI_SPMM_PATTERN, rc, nullptr, buf[k & 1], fi32, fi32, buf[(k + 1) & 1], fi32, fi32, SENSEI_ACT_NONE, plan_t,
+                                        carry, s, nullptr, false, nullptr, true, true));
+                last = buf[(k_hops - 1) & 1];
+            }
+            SENSEI_TRY(spmm_any(At, SENSEI_SPMM_PATTERN, c, nullptr, last, fi4, f_in, dX, lddx, f_in, SENSEI_ACT_NONE, plan_t, carry, s, nullptr, false,
                                 nullptr, sliced));
         }
     }
@@ -1954,6 +1992,35 @@ int sensei_gcn_backward(sensei_ctx *ctx, const sensei_csr *A, const sensei_csr *
     if (ws_bytes < gcn_bwd_ws(*A, (int)X.cols, (int)W.cols, bwd_id)) return SENSEI_WORKSPACE_TOO_SMALL;
     return run_gcn_backward(*A, *At, r, c, X, W, Y, ldy, dY, activation, U_saved, ldu, dX, lddx, dW, lddw, bwd_id, workspace, ws_bytes,
                             as_stream(stream));
+}
+
+int sensei_sgc_backward_workspace(const sensei_csr *A, int f_in, int f_out, int k_hops, int bwd_id, size_t *bytes) {
+    if (!csr_ok(A, false) || f_in <= 0 || f_out <= 0 || k_hops < 1 || !bytes) return SENSEI_INVALID_ARGUMENT;
+    if (bwd_id != SENSEI_GCN_BWD_AGG && bwd_id != SENSEI_GCN_BWD_UPD) return SENSEI_INVALID_COMPOSITION;
+    *bytes = gcn_bwd_ws(*A, f_in, f_out, bwd_id, k_hops);
+    return SENSEI_OK;
+}
+
+int sensei_sgc_backward(sensei_ctx *ctx, const sensei_csr *A, const sensei_csr *At, const float *r, const float *c, sensei_mat X, sensei_mat W,
+                        int k_hops, const float *Y, int64_t ldy, sensei_mat dY, int activation, float *dX, int64_t lddx, float *dW, int64_t lddw,
+                        int bwd_id, void *workspace, size_t ws_bytes, void *stream) {
+    if (bwd_id != SENSEI_GCN_BWD_AGG && bwd_id != SENSEI_GCN_BWD_UPD) return SENSEI_INVALID_COMPOSITION;
+    if (!ctx || !csr_ok(A, false) || !csr_ok(At, false) || !mat_ok(X) || !mat_ok(W) || !mat_ok(dY) || k_hops < 1) return SENSEI_INVALID_ARGUMENT;
+    if (activation != SENSEI_ACT_NONE && activation != SENSEI_ACT_RELU) return SENSEI_INVALID_ARGUMENT;
+    if (A->n_rows != A->n_cols || At->n_rows != A->n_cols || At->n_cols != A->n_rows || At->nnz != A->nnz) return SENSEI_INVALID_ARGUMENT;
+    if (X.rows != A->n_cols || X.cols != W.rows || X.cols <= 0 || W.cols <= 0 || dY.rows != A->n_rows || dY.cols != W.cols) return SENSEI_INVALID_ARGUMENT;
+    if (X.cols > (1 << 20) || W.cols > (1 << 20)) return SENSEI_INVALID_ARGUMENT;
+    if ((A->n_rows > 0 && (!r || !c || !X.ptr || !dY.ptr)) || !W.ptr || !dW || lddw < W.cols || !workspace) return SENSEI_INVALID_ARGUMENT;
+    if (activation == SENSEI_ACT_RELU && (!Y || ldy < W.cols)) return SENSEI_INVALID_ARGUMENT;
+    if (dX && lddx < X.cols) return SENSEI_INVALID_ARGUMENT;
+    const size_t dwb = mat_bytes(dW, W.rows, W.cols, lddw), dxb = dX ? mat_bytes(dX, A->n_cols, X.cols, lddx) : 0;
+    if (overlap(dW, dwb, workspace, ws_bytes) || overlap(dX, dxb, workspace, ws_bytes) || overlap(dX, dxb, dW, dwb) ||
+        overlap(dX, dxb, X.ptr, mat_bytes(X.ptr, X.rows, X.cols, X.ld)) || overlap(dX, dxb, dY.ptr, mat_bytes(dY.ptr, dY.rows, dY.cols, dY.ld)))
+        return SENSEI_INVALID_ARGUMENT;
+    if (ws_bytes < gcn_bwd_ws(*A, (int)X.cols, (int)W.cols, bwd_id, k_hops)) return SENSEI_WORKSPACE_TOO_SMALL;
+    if (A->n_rows == 0) return SENSEI_OK;
+    return run_gcn_backward(*A, *At, r, c, X, W, Y, ldy, dY, activation, nullptr, 0, dX, lddx, dW, lddw, bwd_id, workspace, ws_bytes,
+                            as_stream(stream), k_hops);
 }
 
 int sensei_transpose_positions(sensei_ctx *ctx, const sensei_csr *A, const sensei_csr *At, int32_t *t_pos, void *workspace,

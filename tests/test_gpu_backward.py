@@ -130,6 +130,85 @@ def test_gcn_backward_argument_checks(ctx):
     torch.cuda.synchronize()
 
 
+# ------------------------------------------------------------------ K-hop layer
+
+SQUARE = ("er", "rmat_hub", "hub_empty", "dense_small")
+
+
+@pytest.mark.parametrize("name", SQUARE)
+@pytest.mark.parametrize("widths", [(40, 24), (24, 40), (33, 130)])
+@pytest.mark.parametrize("k_hops", [1, 2, 3])
+def test_sgc_backward_matches_chain_rule(ctx, name, widths, k_hops):
+    g = GRAPHS[name]()
+    gt = synth.transpose(g)
+    f_in, f_out = widths
+    X, W, dY = _inputs(g, f_in, f_out, 80 + f_in + k_hops)
+    for act in (ACT_NONE, ACT_RELU):
+        Y = None
+        if act == ACT_RELU:
+            Y = oracle.sgc_layer(g.n_rows, g.row_ptr, g.col_idx, X, W, k_hops, 1).astype(np.float32)
+        want_dx, want_dw = oracle.sgc_backward(g.n_rows, g.row_ptr, g.col_idx, X, W, k_hops, dY, Y=Y, act=act)
+        A, At = DeviceCSR(g), DeviceCSR(gt)
+        dr, dc = ctx.degrees(A.s)
+        r, c = ctx.norm_vectors(dr), ctx.norm_vectors(dc)
+        Yd = None if Y is None else dev(Y)
+        for bwd in (GCN_BWD_AGG, GCN_BWD_UPD):
+            dX, dW = ctx.sgc_backward(A.s, At.s, r, c, dev(X), dev(W), k_hops, dev(dY), bwd, Y=Yd, activation=act)
+            assert_close(dX, want_dx, what=f"dX k={k_hops} bwd {bwd} act {act}")
+            assert_close(dW, want_dw, what=f"dW k={k_hops} bwd {bwd} act {act}")
+    none, dW = ctx.sgc_backward(A.s, At.s, r, c, dev(X), dev(W), k_hops, dev(dY), GCN_BWD_UPD, Y=Yd, activation=ACT_RELU, want_dx=False)
+    assert none is None
+    assert_close(dW, want_dw, what="dW only")
+
+
+def test_sgc_backward_one_hop_is_the_gcn_backward_and_split_patterns_agree(ctx):
+    """One hop runs exactly the kernels of the GCN backward (bit-equal outputs); with a tile split and with column panels
+    attached to the symmetric pattern the hops take those paths and still match the chain rule."""
+    from paper_2306_15155_amd import Panels, Tiles, csr_struct
+    g = synth.rmat(49, 5000, 150_000)
+    f_in, f_out = 72, 48
+    X, W, dY = _inputs(g, f_in, f_out, 90)
+    A = DeviceCSR(g)
+    dr, dc = ctx.degrees(A.s)
+    r, c = ctx.norm_vectors(dr), ctx.norm_vectors(dc)
+    for bwd in (GCN_BWD_AGG, GCN_BWD_UPD):
+        a = ctx.gcn_backward(A.s, A.s, r, c, dev(X), dev(W), dev(dY), bwd)
+        a = [t.clone() for t in a]
+        b = ctx.sgc_backward(A.s, A.s, r, c, dev(X), dev(W), 1, dev(dY), bwd)
+        assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+    want_dx, want_dw = oracle.sgc_backward(g.n_rows, g.row_ptr, g.col_idx, X, W, 3, dY)
+    T = Tiles(ctx, A.s, 0.05, 128, min_width=32)
+    assert T.n_tiles > 0
+    P = Panels(ctx, A.s, 4)
+    for At in (csr_struct(g.n_rows, g.n_cols, A.row_ptr, A.col_idx, None, None, T), csr_struct(g.n_rows, g.n_cols, A.row_ptr, A.col_idx, None, P)):
+        for bwd in (GCN_BWD_AGG, GCN_BWD_UPD):
+            dX, dW = ctx.sgc_backward(At, At, r, c, dev(X), dev(W), 3, dev(dY), bwd)
+            assert_close(dX, want_dx, what=f"dX bwd {bwd}")
+            assert_close(dW, want_dw, what=f"dW bwd {bwd}")
+    T.close()
+    P.close()
+
+
+def test_sgc_backward_argument_checks(ctx):
+    g = synth.erdos_renyi(47, 200, 600)
+    A = DeviceCSR(g)
+    X, W, dY = (torch.zeros(s, device="cuda:0") for s in ((200, 8), (8, 4), (200, 4)))
+    r = torch.ones(200, device="cuda:0")
+    ctx.sgc_backward(A.s, A.s, r, r, X, W, 2, dY, GCN_BWD_AGG)
+    with pytest.raises(RuntimeError):
+        ctx.sgc_backward(A.s, A.s, r, r, X, W, 0, dY, GCN_BWD_AGG)      # at least one hop
+    with pytest.raises(RuntimeError):
+        ctx.sgc_backward(A.s, A.s, r, r, X, W, 2, dY, 2)                # two associations
+    with pytest.raises(RuntimeError):
+        ctx.sgc_backward(A.s, A.s, r, r, X, W, 2, dY, GCN_BWD_AGG, activation=ACT_RELU)   # ReLU without the forward output
+    gr = rect_block(44, 70, 400, 9)
+    Ar, Art = DeviceCSR(gr), DeviceCSR(synth.transpose(gr))
+    with pytest.raises(RuntimeError):                                     # hops need a square pattern
+        ctx.sgc_backward(Ar.s, Art.s, torch.ones(70, device="cuda:0"), torch.ones(400, device="cuda:0"), torch.zeros((400, 8), device="cuda:0"), W, 2,
+                         torch.zeros((70, 4), device="cuda:0"), GCN_BWD_AGG)
+    torch.cuda.synchronize()
+
+
 # ------------------------------------------------------------------ GAT
 
 @pytest.mark.parametrize("name", sorted(GRAPHS))

@@ -337,6 +337,32 @@ def test_config2_sgc_two_hops_full_size(ctx, reddit_like):
         del Y
 
 
+def test_config2_sgc_backward_two_hops_full_size(ctx, reddit_like):
+    """Backward of the two-hop layer 602 -> 256 on the Reddit-shaped graph.  The pattern is symmetric, so the transposed
+    chain (A^^T)^2 dY W^T equals the forward chain applied to dY with W^T as the update: sampled rows of dX are checked against
+    the oracle's forward walk from those rows.  The weight gradient, which needs every row, is checked by the adjoint identity
+    X^T (A^^2 dY) = (A^^2 X)^T dY: the two associations form it from opposite ends and must agree."""
+    from paper_2306_15155_amd import GCN_BWD_AGG, GCN_BWD_UPD
+    g, A = reddit_like
+    f_in, f_out = 602, 256
+    X, W = synth.uniform(7, 10, (g.n_cols, f_in)), synth.glorot(7, 100, f_in, f_out)
+    dY = synth.normal(7, 500, (g.n_rows, f_out), 0.0, 1.0)
+    deg = np.diff(g.row_ptr)
+    cand = np.flatnonzero((deg >= 30) & (deg <= 800))
+    rows = cand[np.random.default_rng(12).choice(cand.size, 6, replace=False)].astype(np.int64)
+    want_dx = oracle.sgc_layer(g.n_rows, g.row_ptr, g.col_idx, dY, np.ascontiguousarray(W.T), 2, ACT_NONE, rows=rows)
+    r, c, _, _ = _norm(ctx, A)
+    sel = torch.from_numpy(rows).to(DEV)
+    Xd, Wd, dYd = dev(X), dev(W), dev(dY)
+    dws = []
+    for bwd in (GCN_BWD_AGG, GCN_BWD_UPD):
+        dX, dW = ctx.sgc_backward(A.s, A.s, r, c, Xd, Wd, 2, dYd, bwd)
+        assert_close(dX[sel], want_dx, what=f"dX bwd {bwd}")
+        dws.append(dW.double().cpu().numpy())
+        del dX
+    assert_close(torch.from_numpy(dws[0]), dws[1], what="dW of the two associations")
+
+
 def test_config4_gatv2_full_size(ctx, reddit_like):
     """GATv2 layer 602 -> 64 on the Reddit-shaped graph: sampled rows (the longest, a shortest, 300 random) against the oracle."""
     g, A = reddit_like
