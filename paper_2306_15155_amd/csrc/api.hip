@@ -229,12 +229,20 @@ hipError_t spmm_any(const sensei_csr &A, int mode, const float *r, const float *
         const sensei_tiles &D = *A.tiles;
         hipEvent_t t0 = kt ? kt->next() : nullptr, t1 = t0 ? kt->next() : nullptr;
         if (t1 && hipEventRecord(t0, s) != hipSuccess) return hipErrorUnknown;
-        hipError_t e = hipEventRecord(D.ev_fork, s);
-        if (e == hipSuccess) e = hipStreamWaitEvent(D.side, D.ev_fork, 0);
+        // The attention tiles run on the side stream beside the sparse remainder.  The value-less tiles run before it on this
+        // stream: their kernel keeps most of a compute unit's registers, and beside it the remainder lost more time than the
+        // tiles take alone (233,000-node power-law graph, 256 columns: 3.44 ms together, 3.28 ms one after the other).
+        const bool beside = attn != nullptr;
+        hipStream_t ts = beside ? D.side : s;
+        hipError_t e = hipSuccess;
+        if (beside) {
+            e = hipEventRecord(D.ev_fork, s);
+            if (e == hipSuccess) e = hipStreamWaitEvent(D.side, D.ev_fork, 0);
+        }
         if (e == hipSuccess)
-            e = launch_dense_tiles(D.T, B, A.n_cols, pad32(f), D.Bh, D.side, attn ? attn->s_l : nullptr, attn ? attn->s_r : nullptr,
+            e = launch_dense_tiles(D.T, B, A.n_cols, pad32(f), D.Bh, ts, attn ? attn->s_l : nullptr, attn ? attn->s_r : nullptr,
                                    attn ? mz : nullptr, attn ? attn->slope : 0.f, false, attn && attn->gathered);
-        if (e == hipSuccess) e = hipEventRecord(D.ev_join, D.side);
+        if (e == hipSuccess && beside) e = hipEventRecord(D.ev_join, D.side);
         if (e != hipSuccess) return e;
         sensei_csr Ar = A;
         Ar.nnz = D.nnz_rem; Ar.row_ptr = D.row_ptr_rem; Ar.col_idx = D.col_rem; Ar.panels = nullptr; Ar.tiles = nullptr;
@@ -254,7 +262,7 @@ hipError_t spmm_any(const sensei_csr &A, int mode, const float *r, const float *
             if (e == hipSuccess)
                 e = launch_spmm(Ar, mode, nullptr, c, B, ldb, fp, D.part_pm, 32, fp, SENSEI_ACT_NONE, D.plan_pm, carry, s, nullptr, false, false, mz_seg,
                                 b_sliced, 1, true, true);
-            if (e == hipSuccess) e = hipStreamWaitEvent(s, D.ev_join, 0);
+            if (e == hipSuccess && beside) e = hipStreamWaitEvent(s, D.ev_join, 0);
             if (e == hipSuccess)
                 e = launch_tiles_combine_pm(D.T, C, A.n_rows, f_store, ldc, c_sliced, fp, mode == kSpmmSoftmax ? nullptr : r,
                                             mode == kSpmmSoftmax ? mz : nullptr, act, s, D.part_pm, D.rem_panels, D.seg_ptr, D.plan_pm.chunk_nnz, carry, fp);
@@ -265,7 +273,7 @@ hipError_t spmm_any(const sensei_csr &A, int mode, const float *r, const float *
         // the SpMM leaves its carry slots to the combine pass, which visits every row anyway
         e = launch_spmm(Ar, mode, nullptr, c, B, ldb, f, C, ldc, f_store, SENSEI_ACT_NONE, D.plan_rem, carry, s, nullptr, false, false, mz, b_sliced, 1,
                         c_sliced, true);
-        if (e == hipSuccess) e = hipStreamWaitEvent(s, D.ev_join, 0);
+        if (e == hipSuccess && beside) e = hipStreamWaitEvent(s, D.ev_join, 0);
         if (e == hipSuccess)
             e = launch_tiles_combine(D.T, C, A.n_rows, f_store, ldc, c_sliced, pad32(f), mode == kSpmmSoftmax ? nullptr : r,
                                      mode == kSpmmSoftmax ? mz : nullptr, act, s, D.row_ptr_rem, D.plan_rem.chunk_nnz, carry, pad32(f));
@@ -1518,7 +1526,7 @@ TilesLayout tiles_layout(const sensei_csr &A, float min_density, int max_width) 
     L.dst_rem = put((size_t)A.nnz * 4);
     L.row_ptr_rem = put(((size_t)A.n_rows + 1) * 4);
     L.plan_rem = put(plan_bytes(A.nnz) + 4096);
-    L.bh = put((size_t)L.nt_c * 128 * max_width * 4);
+    L.bh = put((size_t)L.nt_c * 128 * max_width * 6);   // fp32 rows (attention modes), or three bf16 pieces per element (value-less mode)
     L.max_seg = L.max_slots / kTilesPerSegment + L.nt_r + 1;
     L.seg_first = put(((size_t)L.max_seg + 1) * 4);
     L.rt_seg = put(((size_t)L.nt_r + 1) * 4);

@@ -306,6 +306,152 @@ __global__ __launch_bounds__(kThreads) void k_dense_tiles(DenseTilesArgs g) {
         }
 }
 
+// The value-less product on the bf16 matrix cores, which run 16 times the fp32 rate, without giving up fp32 accuracy: a
+// tile entry is 0 or 1, exact in bf16, and every fp32 element of the right-hand operand is cut into three bf16 pieces of
+// eight significand bits each (truncate, subtract, truncate, subtract: the pieces add up to the element exactly), so the three
+// products per piece are exact and only the fp32 accumulation of the matrix core rounds, as it does in the fp32 instruction.
+// Neither operand passes through LDS and the wavefronts never synchronise:
+//   - a lane of the 32 x 32 x 16 instruction holds eight consecutive k of one tile row, i.e. one byte of that row's 128-bit
+//     mask, which it expands in registers (to 2.0 = 0x4000, a single bit per entry; the stored result is halved);
+//   - the right-hand operand is cut into its pieces once per call, by the kernel that gathers it into rank order, and stored
+//     in the order the instruction's lanes read it: per (piece, column tile, 16 k, 32 columns) one contiguous kilobyte, lane
+//     (k half, column) holding its eight k, so an operand fetch is one 16-byte load per lane straight from global memory.
+// A wavefront owns 128 tile rows x 32 columns (four accumulators) and walks its segment's tiles with the fetches running three
+// steps of 16 k ahead; the wavefronts of a workgroup only share the segment.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ void split_bf16x3(float v, unsigned &hi, unsigned &mid, unsigned &lo) {
+    hi = __float_as_uint(v) & 0xFFFF0000u;
+    const float r1 = v - __uint_as_float(hi);          // exact: at most 16 significant bits remain
+    mid = __float_as_uint(r1) & 0xFFFF0000u;
+    lo = __float_as_uint(r1 - __uint_as_float(mid));   // exact: at most 8 significant bits, so its low half is zero
+}
+// two fp32 bit patterns whose low halves do not matter -> their high halves as a pair of bf16 (first in the low half)
+__device__ __forceinline__ unsigned pack_bf16(unsigned first, unsigned second) { return __builtin_amdgcn_perm(second, first, 0x07060302u); }
+// eight mask bits -> eight bf16 of value 0 or 2.0: bit k is copied to k and k + 15, then each pair (2d, 2d + 1) is moved onto
+// bits 14 and 30 of its word
+__device__ __forceinline__ uintx4 expand_mask_byte(unsigned byte) {
+    unsigned twice = byte | (byte << 15);
+    asm volatile("" : "+v"(twice));   // keeps the shifts below shifts: folded with the line above they become 32-bit multiplies, four times as slow
+    uintx4 a;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) a[d] = (twice << (14 - 2 * d)) & 0x40004000u;
+    return a;
+}
+
+// Bq: the gathered matrix in rank order, cut into bf16 pieces, in the lane order described above.  Element (rank q = 128 ct +
+// 16 k16 + 8 kh + e, column n = 32 nb + nl) of piece p sits at p * n_ranks * f + ((((ct * 8 + k16) * (f / 32) + nb) * 2 + kh) * 32 + nl) * 8 + e.
+// One thread: eight consecutive ranks of one column (one 16-byte store per piece).  Rows are those of the slice-major matrix B
+// (zeros where the rank has no node).
+__global__ void k_gather_ranked_split(const float *__restrict__ B, long long n_cols, int f, const int32_t *__restrict__ order_c, long long n_ranks,
+                                      unsigned short *__restrict__ Bq) {
+    const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const int nb_count = f / 32;
+    if (t >= n_ranks / 8 * f) return;
+    const int nl = (int)(t & 31);
+    const int nb = (int)((t >> 5) % nb_count);
+    const long long g8 = (t >> 5) / nb_count;
+    const long long q0 = g8 * 8;
+    unsigned pc[8][3];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const int j = order_c[q0 + e];
+        const float v = j >= 0 ? B[(long long)nb * n_cols * 32 + (long long)j * 32 + nl] : 0.f;
+        split_bf16x3(v, pc[e][0], pc[e][1], pc[e][2]);
+    }
+    const long long at = ((g8 >> 1) * nb_count + nb) * 512 + (g8 & 1) * 256 + nl * 8;   // g8 = (ct * 8 + k16) * 2 + kh
+#pragma unroll
+    for (int p = 0; p < 3; ++p) {
+        uintx4 w;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) w[d] = pack_bf16(pc[2 * d][p], pc[2 * d + 1][p]);
+        *reinterpret_cast<uintx4 *>(Bq + (long long)p * n_ranks * f + at) = w;
+    }
+}
+
+struct DenseTilesBfArgs {
+    const unsigned *bits;                  // n_slots x 128 rows x 4 words
+    const int32_t *seg_first, *slot_ct;    // first slot of each segment (n_seg + 1 entries); column tile of a slot
+    const unsigned short *Bq;              // k_gather_ranked_split's output
+    float *part;                           // n_seg x 128 x f
+    long long plane;                       // elements per piece: ranks x f
+    int f, n_bn;                           // f: multiple of 32; n_bn: workgroups (of up to four 32-column blocks) per segment
+};
+
+__global__ __launch_bounds__(kThreads) void k_dense_tiles_bf(DenseTilesBfArgs g) {
+    constexpr int PF = 3, RING = PF + 1;   // fetch distance in steps of 16 k; 8 steps per tile, so ring positions are static
+    const int seg = blockIdx.x / g.n_bn;
+    const int lane = threadIdx.x & 63;
+    const int nb = (blockIdx.x % g.n_bn) * 4 + (threadIdx.x >> 6);   // this wavefront's block of 32 columns
+    const int nb_count = g.f / 32;
+    if (nb >= nb_count) return;            // wavefronts do not synchronise: an idle one may leave
+    const int s0 = __builtin_amdgcn_readfirstlane(g.seg_first[seg]), s1 = __builtin_amdgcn_readfirstlane(g.seg_first[seg + 1]);
+    if (s0 >= s1) return;
+    const int kh = lane >> 5, ll = lane & 31;
+
+    floatx16 acc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+
+    uintx4 ring[RING][3];
+    uintx4 ab[4], ab_n[4];
+    const unsigned short *bq = g.Bq + (long long)nb * 512 + lane * 8;
+    auto fetch = [&](int ct, int k16, int pos) {
+        const unsigned short *at = bq + ((long long)ct * 8 + k16) * nb_count * 512;
+#pragma unroll
+        for (int p = 0; p < 3; ++p) ring[pos][p] = *reinterpret_cast<const uintx4 *>(at + p * g.plane);
+    };
+    auto fetch_bits = [&](int slot) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) ab_n[i] = *reinterpret_cast<const uintx4 *>(g.bits + ((size_t)slot * 128 + i * 32 + ll) * 4);
+    };
+
+    int ct = g.slot_ct[s0], ct_next = g.slot_ct[s0 + 1 < s1 ? s0 + 1 : s0];
+    fetch_bits(s0);
+    __builtin_amdgcn_sched_barrier(0);   // the fetches complete in issue order: the order here is the one the loop continues
+#pragma unroll
+    for (int k = 0; k < PF; ++k) {
+        fetch(ct, k, k);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    for (int slot = s0; slot < s1; ++slot) {
+        // the loop body has no branches, so that the fetches stay in flight across iterations: past the last tile it fetches
+        // that tile again and drops the result
+        const int slot_next = slot + 1 < s1 ? slot + 1 : slot;
+        const int ct_after = g.slot_ct[slot + 2 < s1 ? slot + 2 : s1 - 1];   // needed one tile from now: by then it has long arrived
+#pragma unroll
+        for (int i = 0; i < 4; ++i) ab[i] = ab_n[i];
+#pragma unroll
+        for (int k16 = 0; k16 < 8; ++k16) {
+            if (k16 + PF < 8) fetch(ct, k16 + PF, (k16 + PF) % RING);
+            else fetch(ct_next, k16 + PF - 8, (k16 + PF) % RING);
+            if (k16 == 4) fetch_bits(slot_next);
+            __builtin_amdgcn_sched_barrier(0);   // keeps the fetches PF steps ahead of their use: the scheduler would sink them to it
+            uintx4 av[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) av[i] = expand_mask_byte((ab[i][k16 >> 1] >> ((k16 & 1) * 16 + kh * 8)) & 0xFFu);
+#pragma unroll
+            for (int p = 2; p >= 0; --p)   // smallest pieces first
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av[i]), __builtin_bit_cast(bf16x8, ring[k16 % RING][p]),
+                                                                     acc[i], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        ct = ct_next;
+        ct_next = __builtin_amdgcn_readfirstlane(ct_after);   // placed after the last scheduling barrier: it does not wait on the fetches in flight
+    }
+
+    float *out = g.part + (size_t)seg * 128 * g.f + nb * 32 + ll;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) out[(size_t)(i * 32 + 8 * (r / 4) + 4 * kh + (r % 4)) * g.f] = 0.5f * acc[i][r];
+}
+
 // Dh[rank, :] = sum of the partial products of the segments of the rank's row of tiles, in segment order (zeros for a row of
 // tiles that kept none)
 __global__ void k_tiles_reduce(const float *__restrict__ part, const int32_t *__restrict__ rt_seg, int nt_r, int f, float *__restrict__ Dh) {
@@ -884,6 +1030,20 @@ hipError_t launch_dense_tiles(const TileSplit &T, const float *B_sliced, int64_t
                               const float *s_r, const float2 *mz, float slope, bool transposed, bool gathered) {
     if (T.n_slots <= 0 || f <= 0) return hipSuccess;
     const long long n_ranks = (long long)T.nt_c * 128;
+    if (!s_l) {  // value-less: pieces of the operand in lane order, then the bf16 tile kernel
+        unsigned short *Bq = reinterpret_cast<unsigned short *>(Bh);
+        hipLaunchKernelGGL(k_gather_ranked_split, dim3((unsigned)((n_ranks / 8 * f + 255) / 256)), dim3(256), 0, s, B_sliced, (long long)n_cols, f,
+                           T.order_c, n_ranks, Bq);
+        DenseTilesBfArgs b;
+        b.bits = T.bits; b.seg_first = T.seg_first; b.slot_ct = T.slot_ct; b.Bq = Bq; b.part = T.part;
+        b.plane = n_ranks * f; b.f = f;
+        const int nb_count = f / 32, waves = nb_count < 4 ? nb_count : 4;
+        b.n_bn = (nb_count + 3) / 4;
+        hipLaunchKernelGGL(k_dense_tiles_bf, dim3((unsigned)(T.n_seg * b.n_bn)), dim3(64 * waves), 0, s, b);
+        const long long threads = (long long)T.nt_r * 128 * (f / 4);
+        hipLaunchKernelGGL(k_tiles_reduce, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, (const float *)T.part, T.rt_seg, T.nt_r, f, T.dh);
+        return hipGetLastError();
+    }
     if (!gathered)
         hipLaunchKernelGGL(k_gather_ranked_rows, dim3((unsigned)((n_ranks * (f / 4) + 255) / 256)), dim3(256), 0, s, B_sliced, (long long)n_cols, f,
                            T.order_c, n_ranks, Bh, transposed ? mz : (const float2 *)nullptr);
@@ -910,9 +1070,6 @@ hipError_t launch_dense_tiles(const TileSplit &T, const float *B_sliced, int64_t
             if (narrow) hipLaunchKernelGGL((k_dense_tiles<kTilesAttn, 64>), grid, dim3(kThreads), 0, s, g);
             else hipLaunchKernelGGL((k_dense_tiles<kTilesAttn, 128>), grid, dim3(kThreads), 0, s, g);
         }
-    } else {
-        if (narrow) hipLaunchKernelGGL((k_dense_tiles<kTilesPlain, 64>), grid, dim3(kThreads), 0, s, g);
-        else hipLaunchKernelGGL((k_dense_tiles<kTilesPlain, 128>), grid, dim3(kThreads), 0, s, g);
     }
     const long long threads = (long long)T.nt_r * 128 * (f / 4);
     hipLaunchKernelGGL(k_tiles_reduce, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, (const float *)T.part, T.rt_seg, T.nt_r, f, T.dh);
