@@ -224,25 +224,17 @@ hipError_t spmm_any(const sensei_csr &A, int mode, const float *r, const float *
     // attn: softmax mode on a pattern with a dense-tile split; A.val then holds the logits of the remainder, in its order
     const bool has_val = (mode == SENSEI_SPMM_WEIGHTED || mode == kSpmmSoftmax);
     if (tiles_usable(A, mode, f, b_sliced, attn != nullptr)) {
-        // The hub tiles go to the matrix cores on the side stream while this stream runs the sparse remainder (one is bound
-        // by the MFMA pipes, the other by the memory fabric); a last pass joins the two raw sums and applies scale and activation.
+        // The hub tiles go to the matrix cores, the sparse remainder runs as an SpMM; a last pass joins the two raw sums and
+        // applies scale and activation.
         const sensei_tiles &D = *A.tiles;
         hipEvent_t t0 = kt ? kt->next() : nullptr, t1 = t0 ? kt->next() : nullptr;
         if (t1 && hipEventRecord(t0, s) != hipSuccess) return hipErrorUnknown;
-        // The attention tiles run on the side stream beside the sparse remainder.  The value-less tiles run before it on this
-        // stream: their kernel keeps most of a compute unit's registers, and beside it the remainder lost more time than the
-        // tiles take alone (233,000-node power-law graph, 256 columns: 3.44 ms together, 3.28 ms one after the other).
-        const bool beside = attn != nullptr;
-        hipStream_t ts = beside ? D.side : s;
-        hipError_t e = hipSuccess;
-        if (beside) {
-            e = hipEventRecord(D.ev_fork, s);
-            if (e == hipSuccess) e = hipStreamWaitEvent(D.side, D.ev_fork, 0);
-        }
-        if (e == hipSuccess)
-            e = launch_dense_tiles(D.T, B, A.n_cols, pad32(f), D.Bh, ts, attn ? attn->s_l : nullptr, attn ? attn->s_r : nullptr,
-                                   attn ? mz : nullptr, attn ? attn->slope : 0.f, false, attn && attn->gathered);
-        if (e == hipSuccess && beside) e = hipEventRecord(D.ev_join, D.side);
+        // The tiles run before the sparse remainder, on the same stream.  On a second stream beside it they gain nothing: the
+        // tile kernels keep most of a compute unit's registers, and beside them the remainder loses more time than the tiles
+        // take alone (233,000-node power-law graph, 256 columns: 3.44 ms together, 3.28 ms one after the other); the attention
+        // tiles, eight wavefronts and 36 KB of LDS a workgroup, find no room beside the remainder and run after it anyway.
+        hipError_t e = launch_dense_tiles(D.T, B, A.n_cols, pad32(f), D.Bh, s, attn ? attn->s_l : nullptr, attn ? attn->s_r : nullptr,
+                                          attn ? mz : nullptr, attn ? attn->slope : 0.f, false, attn && attn->gathered);
         if (e != hipSuccess) return e;
         sensei_csr Ar = A;
         Ar.nnz = D.nnz_rem; Ar.row_ptr = D.row_ptr_rem; Ar.col_idx = D.col_rem; Ar.panels = nullptr; Ar.tiles = nullptr;
@@ -262,7 +254,6 @@ hipError_t spmm_any(const sensei_csr &A, int mode, const float *r, const float *
             if (e == hipSuccess)
                 e = launch_spmm(Ar, mode, nullptr, c, B, ldb, fp, D.part_pm, 32, fp, SENSEI_ACT_NONE, D.plan_pm, carry, s, nullptr, false, false, mz_seg,
                                 b_sliced, 1, true, true);
-            if (e == hipSuccess && beside) e = hipStreamWaitEvent(s, D.ev_join, 0);
             if (e == hipSuccess)
                 e = launch_tiles_combine_pm(D.T, C, A.n_rows, f_store, ldc, c_sliced, fp, mode == kSpmmSoftmax ? nullptr : r,
                                             mode == kSpmmSoftmax ? mz : nullptr, act, s, D.part_pm, D.rem_panels, D.seg_ptr, D.plan_pm.chunk_nnz, carry, fp);
@@ -273,7 +264,6 @@ hipError_t spmm_any(const sensei_csr &A, int mode, const float *r, const float *
         // the SpMM leaves its carry slots to the combine pass, which visits every row anyway
         e = launch_spmm(Ar, mode, nullptr, c, B, ldb, f, C, ldc, f_store, SENSEI_ACT_NONE, D.plan_rem, carry, s, nullptr, false, false, mz, b_sliced, 1,
                         c_sliced, true);
-        if (e == hipSuccess && beside) e = hipStreamWaitEvent(s, D.ev_join, 0);
         if (e == hipSuccess)
             e = launch_tiles_combine(D.T, C, A.n_rows, f_store, ldc, c_sliced, pad32(f), mode == kSpmmSoftmax ? nullptr : r,
                                      mode == kSpmmSoftmax ? mz : nullptr, act, s, D.row_ptr_rem, D.plan_rem.chunk_nnz, carry, pad32(f));

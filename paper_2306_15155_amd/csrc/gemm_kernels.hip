@@ -167,145 +167,10 @@ hipError_t gemm_launch_vec(const GemmArgs &g, int avec, int bvec, hipStream_t s)
 }
 
 // ---- dense tiles of the hub region: C[order_r[rank], :] = sum over the kept 128 x 128 tiles of the rank's row of tiles of
-// (tile bits) . Bh[tile columns, :].  A tile's 0/1 entries are expanded from its bit mask while they are staged into LDS,
-// the right-hand operand is the copy of the gathered matrix in rank order (rows contiguous), so both loaders are as
-// regular as in the plain GEMM and the multiply runs on the fp32 matrix cores.  The rows of tiles of the largest hubs
-// keep hundreds of tiles, the others a few: the kept tiles of a row are therefore cut into segments of at most
-// kTilesPerSegment, one workgroup per (segment, 128 output columns) with a k loop of 16 ranks per step; a segment leaves
-// its 128 x f partial product in `part`, and k_tiles_reduce adds the segments of a row in order (no atomics).
-struct DenseTilesArgs {
-    const unsigned *bits;                  // n_slots x 128 rows x 4 words
-    const int32_t *seg_first, *slot_ct;    // first slot of each segment (n_seg + 1 entries); column tile of a slot
-    const float *Bh;                       // (column tiles x 128) x f, row-major: row q = gathered row of the node at column rank q
-    float *part;                           // n_seg x 128 x f
-    long long ldbh;
-    int f, n_bn;
-    // attention modes: entry (i, j) of a tile weighs exp(LeakyReLU(u[i] + v[j]) - shift), as the softmax mode of the SpMM does.
-    // kTilesAttn: u = s_l, v = s_r, shift = the maximum of row i (tiles of the pattern itself).  kTilesAttnT: the tiles are those of
-    // the transposed pattern, so the softmax row is the tile's column: u = s_r, v = s_l, shift = the maximum of column j.
-    const int32_t *seg_rt;                 // row of tiles of each segment
-    const float *sl_rank, *m_rank, *sr_rank;  // u and (kTilesAttn) the shift by row rank; v by column rank
-    const float *mc_rank;                  // kTilesAttnT: the shift by column rank
-    float slope;
-};
-constexpr int kTilesPlain = 0, kTilesAttn = 1, kTilesAttnT = 2;
-
-template <int MODE, int BN>  // BN: output columns per workgroup, 128, or 64 for operands no wider than that
-__global__ __launch_bounds__(kThreads) void k_dense_tiles(DenseTilesArgs g) {
-    constexpr bool ATTN = MODE != kTilesPlain;
-    constexpr int BM = 128, WGN = 2, TM = 2, TN = BN / 64;
-    constexpr int B_TPR = BN / 4, B_RPP = kThreads / B_TPR, B_PASSES = KT / B_RPP;  // threads per k-row, k-rows per pass
-    constexpr int APAD = 36, BPAD = 36;
-    __shared__ float As[KT][BM + APAD];
-    __shared__ __attribute__((aligned(16))) float Bs[KT][BN + BPAD];
-    const int seg = blockIdx.x / g.n_bn;
-    const int n0 = (blockIdx.x % g.n_bn) * BN;
-    const int s0 = g.seg_first[seg], s1 = g.seg_first[seg + 1];
-    if (s0 >= s1) return;
-    const int t = threadIdx.x;
-    const int wave = t >> 6, lane = t & 63;
-    const int wm = wave / WGN, wn = wave % WGN;
-
-    floatx16 acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-    unsigned ra[2];   // four bits each: entries (row, k .. k + 3) of the tile
-    float4 rb[B_PASSES];
-    const int a_row = t >> 2, a_kk = (t & 3) * 4;     // 64 rows per pass, 4 threads per row
-    const int b_row = t / B_TPR, b_nn = (t % B_TPR) * 4;
-    const bool col_ok = n0 + b_nn < g.f;
-    float sl_t[2] = {0.f, 0.f}, m_t[2] = {0.f, 0.f};
-    float4 sr4 = make_float4(0.f, 0.f, 0.f, 0.f), mc4 = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (ATTN) {
-        const int rt = g.seg_rt[seg];
-#pragma unroll
-        for (int p = 0; p < 2; ++p) {
-            sl_t[p] = g.sl_rank[rt * 128 + p * 64 + a_row];
-            if (MODE == kTilesAttn) m_t[p] = g.m_rank[rt * 128 + p * 64 + a_row];
-        }
-    }
-
-    auto fetch = [&](int slot, int ct, int k0) {
-#pragma unroll
-        for (int p = 0; p < 2; ++p) {
-            const int row = p * 64 + a_row, kk = k0 + a_kk;
-            ra[p] = (g.bits[((size_t)slot * 128 + row) * 4 + (kk >> 5)] >> (kk & 31)) & 15u;
-        }
-        if (ATTN) sr4 = *reinterpret_cast<const float4 *>(g.sr_rank + (size_t)ct * 128 + k0 + a_kk);
-        if (MODE == kTilesAttnT) mc4 = *reinterpret_cast<const float4 *>(g.mc_rank + (size_t)ct * 128 + k0 + a_kk);
-#pragma unroll
-        for (int p = 0; p < B_PASSES; ++p) {
-            const int kr = p * B_RPP + b_row;
-            rb[p] = col_ok ? *reinterpret_cast<const float4 *>(g.Bh + ((size_t)ct * 128 + k0 + kr) * g.ldbh + n0 + b_nn) : make_float4(0.f, 0.f, 0.f, 0.f);
-        }
-    };
-    auto stash = [&]() {
-#pragma unroll
-        for (int p = 0; p < 2; ++p)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                float w = 1.f;
-                if (ATTN) {
-                    const float srv = e == 0 ? sr4.x : e == 1 ? sr4.y : e == 2 ? sr4.z : sr4.w;
-                    float tt = sl_t[p] + srv;
-                    tt = tt > 0.f ? tt : g.slope * tt;
-                    const float shift = MODE == kTilesAttn ? m_t[p] : e == 0 ? mc4.x : e == 1 ? mc4.y : e == 2 ? mc4.z : mc4.w;
-                    w = __expf(tt - shift);
-                }
-                As[a_kk + e][p * 64 + a_row] = ((ra[p] >> e) & 1u) ? w : 0.f;
-            }
-#pragma unroll
-        for (int p = 0; p < B_PASSES; ++p) *reinterpret_cast<float4 *>(&Bs[p * B_RPP + b_row][b_nn]) = rb[p];
-    };
-
-    const int n_steps = (s1 - s0) * (128 / KT);
-    int ct_next = g.slot_ct[s0];
-    fetch(s0, ct_next, 0);
-    for (int step = 0; step < n_steps; ++step) {
-        stash();
-        __syncthreads();
-        if (step + 1 < n_steps) {
-            const int nslot = s0 + (step + 1) / (128 / KT);
-            if ((step + 1) % (128 / KT) == 0) ct_next = g.slot_ct[nslot];
-            fetch(nslot, ct_next, ((step + 1) % (128 / KT)) * KT);
-        }
-        const int kh = lane >> 5, ll = lane & 31;
-#pragma unroll
-        for (int kk = 0; kk < KT; kk += 2) {
-            float av[TM], bv[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) av[i] = As[kk + kh][(wm * TM + i) * 32 + ll];
-#pragma unroll
-            for (int j = 0; j < TN; ++j) bv[j] = Bs[kk + kh][(wn * TN + j) * 32 + ll];
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
-        }
-        __syncthreads();
-    }
-
-    const int kh = lane >> 5, ll = lane & 31;
-    float *out = g.part + (size_t)seg * 128 * g.f;
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int row = (wm * TM + i) * 32 + 8 * (r / 4) + 4 * kh + (r % 4);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int col = n0 + (wn * TN + j) * 32 + ll;
-                if (col < g.f) out[(size_t)row * g.f + col] = acc[i][j][r];
-            }
-        }
-}
-
+// (tile bits) . B[tile columns, :], B in rank order.  The rows of tiles of the largest hubs keep hundreds of tiles, the others a
+// few: the kept tiles of a row are therefore cut into segments of at most kTilesPerSegment, one workgroup per (segment, group
+// of 32-column blocks); a segment leaves its 128 x f partial product in `part`, and k_tiles_reduce adds the segments of a row
+// in order (no atomics).
 // The value-less product on the bf16 matrix cores, which run 16 times the fp32 rate, without giving up fp32 accuracy: a
 // tile entry is 0 or 1, exact in bf16, and every fp32 element of the right-hand operand is cut into three bf16 pieces of
 // eight significand bits each (truncate, subtract, truncate, subtract: the pieces add up to the element exactly), so the three
@@ -343,9 +208,9 @@ __device__ __forceinline__ uintx4 expand_mask_byte(unsigned byte) {
 // Bq: the gathered matrix in rank order, cut into bf16 pieces, in the lane order described above.  Element (rank q = 128 ct +
 // 16 k16 + 8 kh + e, column n = 32 nb + nl) of piece p sits at p * n_ranks * f + ((((ct * 8 + k16) * (f / 32) + nb) * 2 + kh) * 32 + nl) * 8 + e.
 // One thread: eight consecutive ranks of one column (one 16-byte store per piece).  Rows are those of the slice-major matrix B
-// (zeros where the rank has no node).
+// (zeros where the rank has no node), times 1 / mz[node].y if mz is given.
 __global__ void k_gather_ranked_split(const float *__restrict__ B, long long n_cols, int f, const int32_t *__restrict__ order_c, long long n_ranks,
-                                      unsigned short *__restrict__ Bq) {
+                                      unsigned short *__restrict__ Bq, const float2 *__restrict__ mz) {
     const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     const int nb_count = f / 32;
     if (t >= n_ranks / 8 * f) return;
@@ -357,7 +222,8 @@ __global__ void k_gather_ranked_split(const float *__restrict__ B, long long n_c
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         const int j = order_c[q0 + e];
-        const float v = j >= 0 ? B[(long long)nb * n_cols * 32 + (long long)j * 32 + nl] : 0.f;
+        float v = j >= 0 ? B[(long long)nb * n_cols * 32 + (long long)j * 32 + nl] : 0.f;
+        if (mz && j >= 0) { const float z = mz[j].y; v *= z > 0.f ? 1.f / z : 0.f; }
         split_bf16x3(v, pc[e][0], pc[e][1], pc[e][2]);
     }
     const long long at = ((g8 >> 1) * nb_count + nb) * 512 + (g8 & 1) * 256 + nl * 8;   // g8 = (ct * 8 + k16) * 2 + kh
@@ -450,6 +316,162 @@ __global__ __launch_bounds__(kThreads) void k_dense_tiles_bf(DenseTilesBfArgs g)
     for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) out[(size_t)(i * 32 + 8 * (r / 4) + 4 * kh + (r % 4)) * g.f] = 0.5f * acc[i][r];
+}
+
+// The attention modes on the bf16 matrix cores.  Entry (i, k) of a tile weighs w = exp(LeakyReLU(u[i] + v[k]) - shift), an fp32
+// number, which is cut into three bf16 pieces like the right-hand operand; of the nine piece products the six of weight
+// 2^-16 and above are formed (w1 b1, w1 b2, w2 b1, w1 b3, w2 b2, w3 b1: what is left out is below 2^-23 of a term, the rounding
+// of the fp32 instruction).  kTilesAttn: u = s_l, v = s_r, shift = the maximum of row i (tiles of the pattern itself).
+// kTilesAttnT: the tiles are those of the transposed pattern, so the softmax row is the tile's column: u = s_r, v = s_l,
+// shift = the maximum of column k.
+// The weights of one step (128 rows x 16 k) are computed once per workgroup, every thread a few of them, and shared through
+// LDS (two buffers: the weights of step s + 1 are written while step s multiplies, one barrier per step); a wavefront owns 128
+// rows x 32 columns as in the value-less kernel and fetches its right-hand pieces straight from global memory one step ahead.
+// NW wavefronts per workgroup (as many 32-column blocks, up to eight); a workgroup whose last blocks do not exist lets those
+// wavefronts repeat the last block and drop the result, so that every wavefront reaches every barrier.
+struct DenseTilesAttnArgs {
+    const unsigned *bits;
+    const int32_t *seg_first, *slot_ct, *seg_rt;
+    const unsigned short *Bq;
+    float *part;
+    long long plane;
+    int f, n_bn;
+    const float *u_rank, *m_rank;    // by row rank: u, and (kTilesAttn) the shift
+    const float *v_rank, *mc_rank;   // by column rank: v, and (kTilesAttnT) the shift
+    float slope;
+};
+constexpr int kTilesAttn = 1, kTilesAttnT = 2;
+
+template <int MODE, int NW>
+__global__ __launch_bounds__(64 * NW) void k_dense_tiles_attn_bf(DenseTilesAttnArgs g) {
+    constexpr int THREADS = 64 * NW;
+    constexpr int KP = NW >= 8 ? 4 : NW == 4 ? 8 : 16;   // consecutive k per thread and row when the weights are formed
+    constexpr int TPR = 16 / KP;                          // threads per row
+    constexpr int RPT = 128 * TPR / THREADS;              // rows per thread (2 for a single wavefront)
+    constexpr int AROW = 24;                              // bf16 per row of a piece in LDS: 16 k and 16 bytes of padding (conflict-free 16-byte reads)
+    __shared__ __attribute__((aligned(16))) unsigned short As[2][3][128][AROW];
+    const int seg = blockIdx.x / g.n_bn;
+    const int t = threadIdx.x, lane = t & 63;
+    const int nb_count = g.f / 32;
+    const int nb_want = (blockIdx.x % g.n_bn) * NW + (t >> 6);
+    const bool stores = nb_want < nb_count;
+    const int nb = stores ? nb_want : nb_count - 1;
+    const int s0 = __builtin_amdgcn_readfirstlane(g.seg_first[seg]), s1 = __builtin_amdgcn_readfirstlane(g.seg_first[seg + 1]);
+    if (s0 >= s1) return;
+    const int rt = g.seg_rt[seg];
+    const int kh = lane >> 5, ll = lane & 31;
+    const int a_row = t / TPR, a_kq = t % TPR;
+
+    floatx16 acc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+
+    float u_t[RPT], m_t[RPT];
+    uintx4 ab[RPT], ab_n[RPT];
+#pragma unroll
+    for (int rr = 0; rr < RPT; ++rr) {
+        const int row = a_row + rr * (THREADS / TPR);
+        u_t[rr] = g.u_rank[rt * 128 + row];
+        m_t[rr] = MODE == kTilesAttn ? g.m_rank[rt * 128 + row] : 0.f;
+    }
+    auto fetch_bits = [&](int slot) {
+#pragma unroll
+        for (int rr = 0; rr < RPT; ++rr)
+            ab_n[rr] = *reinterpret_cast<const uintx4 *>(g.bits + ((size_t)slot * 128 + a_row + rr * (THREADS / TPR)) * 4);
+    };
+    uintx4 ring[2][3];
+    const unsigned short *bq = g.Bq + (long long)nb * 512 + lane * 8;
+    auto fetch = [&](int ct, int k16, int pos) {
+        const unsigned short *at = bq + ((long long)ct * 8 + k16) * nb_count * 512;
+#pragma unroll
+        for (int p = 0; p < 3; ++p) ring[pos][p] = *reinterpret_cast<const uintx4 *>(at + p * g.plane);
+    };
+    float4 vv[KP / 4], mc[KP / 4];
+    auto fetch_v = [&](int ct, int k16) {
+#pragma unroll
+        for (int q = 0; q < KP / 4; ++q) {
+            vv[q] = *reinterpret_cast<const float4 *>(g.v_rank + (size_t)ct * 128 + k16 * 16 + a_kq * KP + q * 4);
+            if (MODE == kTilesAttnT) mc[q] = *reinterpret_cast<const float4 *>(g.mc_rank + (size_t)ct * 128 + k16 * 16 + a_kq * KP + q * 4);
+        }
+    };
+    // the weights of step k16 of the tile whose mask rows are `mask`, from the vectors fetch_v has brought, into buffer `buf`
+    auto weights = [&](const uintx4 (&mask)[RPT], int k16, int buf) {
+#pragma unroll
+        for (int rr = 0; rr < RPT; ++rr) {
+            const unsigned present = (mask[rr][k16 >> 1] >> ((k16 & 1) * 16 + a_kq * KP)) & ((1u << KP) - 1u);
+            unsigned pc[KP][3];
+#pragma unroll
+            for (int e = 0; e < KP; ++e) {
+                const float4 v4 = vv[e / 4];
+                const float ve = (e & 3) == 0 ? v4.x : (e & 3) == 1 ? v4.y : (e & 3) == 2 ? v4.z : v4.w;
+                float tt = u_t[rr] + ve;
+                tt = tt > 0.f ? tt : g.slope * tt;
+                float shift = m_t[rr];
+                if (MODE == kTilesAttnT) { const float4 c4 = mc[e / 4]; shift = (e & 3) == 0 ? c4.x : (e & 3) == 1 ? c4.y : (e & 3) == 2 ? c4.z : c4.w; }
+                const float w = ((present >> e) & 1u) ? __expf(tt - shift) : 0.f;
+                split_bf16x3(w, pc[e][0], pc[e][1], pc[e][2]);
+            }
+            const int row = a_row + rr * (THREADS / TPR);
+#pragma unroll
+            for (int p = 0; p < 3; ++p) {
+                unsigned short *dst = &As[buf][p][row][a_kq * KP];
+#pragma unroll
+                for (int q = 0; q < KP / 4; ++q)
+                    *reinterpret_cast<uint2 *>(dst + q * 4) = make_uint2(pack_bf16(pc[q * 4][p], pc[q * 4 + 1][p]), pack_bf16(pc[q * 4 + 2][p], pc[q * 4 + 3][p]));
+            }
+        }
+    };
+
+    int ct = g.slot_ct[s0], ct_next = g.slot_ct[s0 + 1 < s1 ? s0 + 1 : s0];
+    fetch_bits(s0);
+    fetch_v(ct, 0);
+    fetch(ct, 0, 0);
+#pragma unroll
+    for (int rr = 0; rr < RPT; ++rr) ab[rr] = ab_n[rr];
+    weights(ab, 0, 0);
+    for (int slot = s0; slot < s1; ++slot) {
+        // no branches in the body (the fetches stay in flight across iterations): past the last tile it works on that tile again
+        // and drops the result
+        const int slot_next = slot + 1 < s1 ? slot + 1 : slot;
+        const int ct_after = g.slot_ct[slot + 2 < s1 ? slot + 2 : s1 - 1];
+#pragma unroll
+        for (int k16 = 0; k16 < 8; ++k16) {
+            // what the next step needs: its right-hand pieces, and the column vectors its weights are formed from
+            if (k16 < 7) { fetch(ct, k16 + 1, (k16 + 1) & 1); fetch_v(ct, k16 + 1); }
+            else { fetch(ct_next, 0, 0); fetch_v(ct_next, 0); }
+            if (k16 == 3) fetch_bits(slot_next);
+            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();   // the weights of this step are in As[k16 & 1]; nobody reads the other buffer any more
+#pragma unroll
+            for (int pa = 2; pa >= 0; --pa) {
+                uintx4 av[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) av[i] = *reinterpret_cast<const uintx4 *>(&As[k16 & 1][pa][i * 32 + ll][kh * 8]);
+#pragma unroll
+                for (int pb = 2 - pa; pb >= 0; --pb)   // smallest products first
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av[i]), __builtin_bit_cast(bf16x8, ring[k16 & 1][pb]),
+                                                                         acc[i], 0, 0, 0);
+            }
+            if (k16 < 7) weights(ab, k16 + 1, (k16 + 1) & 1);
+            else weights(ab_n, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int rr = 0; rr < RPT; ++rr) ab[rr] = ab_n[rr];
+        ct = ct_next;
+        ct_next = __builtin_amdgcn_readfirstlane(ct_after);
+    }
+
+    if (!stores) return;
+    float *out = g.part + (size_t)seg * 128 * g.f + nb * 32 + ll;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) out[(size_t)(i * 32 + 8 * (r / 4) + 4 * kh + (r % 4)) * g.f] = acc[i][r];
 }
 
 // Dh[rank, :] = sum of the partial products of the segments of the rank's row of tiles, in segment order (zeros for a row of
@@ -1021,54 +1043,56 @@ hipError_t launch_gemm(const float *A, int64_t lda, const float *W, int64_t ldw,
 hipError_t launch_tiles_gather(const TileSplit &T, const float *B_sliced, int64_t n_cols, int f, float *Bh, hipStream_t s) {
     if (T.n_slots <= 0 || f <= 0) return hipSuccess;
     const long long n_ranks = (long long)T.nt_c * 128;
-    hipLaunchKernelGGL(k_gather_ranked_rows, dim3((unsigned)((n_ranks * (f / 4) + 255) / 256)), dim3(256), 0, s, B_sliced, (long long)n_cols, f,
-                       T.order_c, n_ranks, Bh, (const float2 *)nullptr);
+    hipLaunchKernelGGL(k_gather_ranked_split, dim3((unsigned)((n_ranks / 8 * f + 255) / 256)), dim3(256), 0, s, B_sliced, (long long)n_cols, f,
+                       T.order_c, n_ranks, reinterpret_cast<unsigned short *>(Bh), (const float2 *)nullptr);
     return hipGetLastError();
 }
 
+template <int MODE>
+static void launch_attn_tiles(const DenseTilesAttnArgs &a, int n_seg, int nb_count, hipStream_t s) {
+    DenseTilesAttnArgs g = a;
+    const int nw = nb_count >= 5 ? 8 : nb_count >= 3 ? 4 : nb_count;   // wavefronts (32-column blocks) per workgroup
+    g.n_bn = (nb_count + nw - 1) / nw;
+    const dim3 grid((unsigned)(n_seg * g.n_bn));
+    if (nw == 8) hipLaunchKernelGGL((k_dense_tiles_attn_bf<MODE, 8>), grid, dim3(512), 0, s, g);
+    else if (nw == 4) hipLaunchKernelGGL((k_dense_tiles_attn_bf<MODE, 4>), grid, dim3(256), 0, s, g);
+    else if (nw == 2) hipLaunchKernelGGL((k_dense_tiles_attn_bf<MODE, 2>), grid, dim3(128), 0, s, g);
+    else hipLaunchKernelGGL((k_dense_tiles_attn_bf<MODE, 1>), grid, dim3(64), 0, s, g);
+}
+
+// f: a multiple of 32.  Bh: room for 6 bytes per (rank, column).
 hipError_t launch_dense_tiles(const TileSplit &T, const float *B_sliced, int64_t n_cols, int f, float *Bh, hipStream_t s, const float *s_l,
                               const float *s_r, const float2 *mz, float slope, bool transposed, bool gathered) {
     if (T.n_slots <= 0 || f <= 0) return hipSuccess;
     const long long n_ranks = (long long)T.nt_c * 128;
-    if (!s_l) {  // value-less: pieces of the operand in lane order, then the bf16 tile kernel
-        unsigned short *Bq = reinterpret_cast<unsigned short *>(Bh);
+    unsigned short *Bq = reinterpret_cast<unsigned short *>(Bh);
+    const int nb_count = f / 32;
+    if (!gathered)   // pieces of the operand in lane order (the transposed attention mode folds 1 / z of the softmax row into them)
         hipLaunchKernelGGL(k_gather_ranked_split, dim3((unsigned)((n_ranks / 8 * f + 255) / 256)), dim3(256), 0, s, B_sliced, (long long)n_cols, f,
-                           T.order_c, n_ranks, Bq);
+                           T.order_c, n_ranks, Bq, (s_l && transposed) ? mz : (const float2 *)nullptr);
+    if (!s_l) {
         DenseTilesBfArgs b;
         b.bits = T.bits; b.seg_first = T.seg_first; b.slot_ct = T.slot_ct; b.Bq = Bq; b.part = T.part;
         b.plane = n_ranks * f; b.f = f;
-        const int nb_count = f / 32, waves = nb_count < 4 ? nb_count : 4;
+        const int waves = nb_count < 4 ? nb_count : 4;
         b.n_bn = (nb_count + 3) / 4;
         hipLaunchKernelGGL(k_dense_tiles_bf, dim3((unsigned)(T.n_seg * b.n_bn)), dim3(64 * waves), 0, s, b);
-        const long long threads = (long long)T.nt_r * 128 * (f / 4);
-        hipLaunchKernelGGL(k_tiles_reduce, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, (const float *)T.part, T.rt_seg, T.nt_r, f, T.dh);
-        return hipGetLastError();
-    }
-    if (!gathered)
-        hipLaunchKernelGGL(k_gather_ranked_rows, dim3((unsigned)((n_ranks * (f / 4) + 255) / 256)), dim3(256), 0, s, B_sliced, (long long)n_cols, f,
-                           T.order_c, n_ranks, Bh, transposed ? mz : (const float2 *)nullptr);
-    DenseTilesArgs g;
-    g.bits = T.bits; g.seg_first = T.seg_first; g.slot_ct = T.slot_ct;
-    g.Bh = Bh; g.ldbh = f; g.part = T.part;
-    const bool narrow = f <= 64;
-    g.f = f; g.n_bn = narrow ? 1 : (f + 127) / 128;
-    g.seg_rt = T.seg_rt; g.sl_rank = nullptr; g.m_rank = nullptr; g.sr_rank = nullptr; g.mc_rank = nullptr; g.slope = slope;
-    const dim3 grid((unsigned)(narrow ? T.n_seg : T.n_seg * g.n_bn));
-    if (s_l) {
+    } else {
+        DenseTilesAttnArgs g;
+        g.bits = T.bits; g.seg_first = T.seg_first; g.slot_ct = T.slot_ct; g.seg_rt = T.seg_rt; g.Bq = Bq; g.part = T.part;
+        g.plane = n_ranks * f; g.f = f; g.n_bn = 1; g.slope = slope;
         const int n_r = T.nt_r * 128, n_c = T.nt_c * 128;
         const dim3 vgrid((unsigned)(((n_r > n_c ? n_r : n_c) + 255) / 256));
         if (transposed) {
-            g.sl_rank = T.rank_vec; g.sr_rank = T.rank_vec + n_r; g.mc_rank = T.rank_vec + n_r + n_c;
+            g.u_rank = T.rank_vec; g.m_rank = nullptr; g.v_rank = T.rank_vec + n_r; g.mc_rank = T.rank_vec + n_r + n_c;
             hipLaunchKernelGGL(k_gather_ranked_vecs_t, vgrid, dim3(256), 0, s, s_l, s_r, mz, T.order_r, n_r, T.order_c, n_c, T.rank_vec,
                                T.rank_vec + n_r, T.rank_vec + n_r + n_c);
-            if (narrow) hipLaunchKernelGGL((k_dense_tiles<kTilesAttnT, 64>), grid, dim3(kThreads), 0, s, g);
-            else hipLaunchKernelGGL((k_dense_tiles<kTilesAttnT, 128>), grid, dim3(kThreads), 0, s, g);
+            launch_attn_tiles<kTilesAttnT>(g, T.n_seg, nb_count, s);
         } else {
-            g.sl_rank = T.rank_vec; g.m_rank = T.rank_vec + n_r; g.sr_rank = T.rank_vec + 2 * n_r;
+            g.u_rank = T.rank_vec; g.m_rank = T.rank_vec + n_r; g.v_rank = T.rank_vec + 2 * n_r; g.mc_rank = nullptr;
             hipLaunchKernelGGL(k_gather_ranked_vecs, vgrid, dim3(256), 0, s, s_l, s_r, mz, T.order_r, n_r, T.order_c, n_c, T.rank_vec,
                                T.rank_vec + n_r, T.rank_vec + 2 * n_r);
-            if (narrow) hipLaunchKernelGGL((k_dense_tiles<kTilesAttn, 64>), grid, dim3(kThreads), 0, s, g);
-            else hipLaunchKernelGGL((k_dense_tiles<kTilesAttn, 128>), grid, dim3(kThreads), 0, s, g);
+            launch_attn_tiles<kTilesAttn>(g, T.n_seg, nb_count, s);
         }
     }
     const long long threads = (long long)T.nt_r * 128 * (f / 4);
