@@ -3,6 +3,8 @@
 // two-vector GEMV for the attention projections.
 #include "sensei_internal.h"
 
+#include <type_traits>
+
 namespace sensei {
 
 namespace {
@@ -166,6 +168,203 @@ hipError_t gemm_launch_vec(const GemmArgs &g, int avec, int bvec, hipStream_t s)
     return hipGetLastError();
 }
 
+// ---- the same GEMM on the bf16 matrix cores, which run 16 times the fp32 rate, at fp32 accuracy.  Every fp32 operand element
+// is cut into three bf16 pieces of eight significand bits (truncate, subtract, truncate, subtract: the pieces add up to the
+// element exactly); of the nine piece products of a term the six of weight 2^-16 and above are formed (a1 b1, a1 b2, a2 b1, a1 b3,
+// a2 b2, a3 b1), each exact, and accumulated in fp32 by the matrix core: what is left out is below 2^-23 of the term, the
+// rounding of the fp32 instruction.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ void split_bf16x3(float v, unsigned &hi, unsigned &mid, unsigned &lo) {
+    hi = __float_as_uint(v) & 0xFFFF0000u;
+    const float r1 = v - __uint_as_float(hi);          // exact: at most 16 significant bits remain
+    mid = __float_as_uint(r1) & 0xFFFF0000u;
+    lo = __float_as_uint(r1 - __uint_as_float(mid));   // exact: at most 8 significant bits, so its low half is zero
+}
+// two fp32 bit patterns whose low halves do not matter -> their high halves as a pair of bf16 (first in the low half)
+__device__ __forceinline__ unsigned pack_bf16(unsigned first, unsigned second) { return __builtin_amdgcn_perm(second, first, 0x07060302u); }
+
+// Block tile 256 x 32 TN: four wavefronts stacked over the rows, each 64 rows x 32 TN columns (2 x TN accumulators).  The
+// 256 x 16 block of A of a step goes through LDS as fp32 (fetched with neighbouring lanes on one row, so that a row's 64 bytes
+// are one request); a lane of the 32 x 32 x 16 instruction holds eight consecutive k of one row, reads them back as two 16-byte
+// words and cuts them into pieces in registers.  The 16 x 32 TN block of W of a step is cut once per workgroup (a thread:
+// eight k of one column) and left in LDS in lane order.  Two buffers each, filled for step s + 1 while step s multiplies: one
+// barrier per step.  Rows past the end are computed from the last row and dropped.
+template <int TN, int AVEC>
+__global__ __launch_bounds__(kThreads, 2) void k_gemm_bf(GemmArgs g) {
+    constexpr int BM = 256, BN = 32 * TN;
+    constexpr int A_TPR = 16 / AVEC, A_RPP = kThreads / A_TPR, A_PASSES = BM / A_RPP;   // threads per row, rows per pass
+    constexpr int ALD = 20;   // floats per row of A in LDS: 16 k and 16 bytes of padding (conflict-free 16-byte reads of 16 rows)
+    __shared__ __attribute__((aligned(16))) float As[2][BM][ALD];
+    __shared__ __attribute__((aligned(16))) unsigned short Bs[2][3][TN][2][32][8];
+    const int t = threadIdx.x, wave = t >> 6, lane = t & 63, kh = lane >> 5, ll = lane & 31;
+    const long long m0 = (long long)(blockIdx.x / g.n_bn) * BM;
+    const int n0 = (int)(blockIdx.x % g.n_bn) * BN;
+
+    floatx16 acc[2][TN];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    const int a_row = t / A_TPR, a_kk = (t % A_TPR) * AVEC;
+    float ra[A_PASSES][AVEC];
+    // Addresses: a uniform base that moves with k, plus a 32-bit byte offset per lane and pass that never changes (the row within
+    // the block, clamped to the last row of A, and the lane's k): nothing per step is left for the vector ALU.
+    const float *a_blk = g.A + m0 * g.lda;
+    unsigned a_off[A_PASSES];
+#pragma unroll
+    for (int p = 0; p < A_PASSES; ++p) {
+        long long row = m0 + p * A_RPP + a_row;
+        if (row > g.n - 1) row = g.n - 1;
+        a_off[p] = (unsigned)(((row - m0) * g.lda + a_kk) * 4);
+    }
+    // a step whose 16 k all exist: vector fetches; the last step of a k that is no multiple of 16 (and the idle fetch past the
+    // last step): element by element from a clamped k, zeros past k
+    auto fetch_a = [&](int k0, auto whole) {
+        const char *src = reinterpret_cast<const char *>(a_blk + (long long)(k0 >> 5) * g.a_slice + (k0 & 31));
+#pragma unroll
+        for (int p = 0; p < A_PASSES; ++p) {
+            if constexpr (decltype(whole)::value) {
+                if (AVEC == 4) { const float4 v = *reinterpret_cast<const float4 *>(src + a_off[p]); ra[p][0] = v.x; ra[p][1 % AVEC] = v.y; ra[p][2 % AVEC] = v.z; ra[p][3 % AVEC] = v.w; }
+                else if (AVEC == 2) { const float2 v = *reinterpret_cast<const float2 *>(src + a_off[p]); ra[p][0] = v.x; ra[p][1 % AVEC] = v.y; }
+                else ra[p][0] = *reinterpret_cast<const float *>(src + a_off[p]);
+            } else {
+                const float *base = reinterpret_cast<const float *>(reinterpret_cast<const char *>(a_blk) + a_off[p]) - a_kk;   // the row's first element
+#pragma unroll
+                for (int e = 0; e < AVEC; ++e) {
+                    const int k = k0 + a_kk + e, kc = k < g.k ? k : g.k - 1;
+                    const float v = base[(long long)(kc >> 5) * g.a_slice + (kc & 31)];
+                    ra[p][e] = __uint_as_float(__float_as_uint(v) & (k < g.k ? ~0u : 0u));   // a mask, not a branch around the fetch
+                }
+            }
+        }
+    };
+    auto stash_a = [&](int buf) {
+#pragma unroll
+        for (int p = 0; p < A_PASSES; ++p) {
+            float *dst = &As[buf][p * A_RPP + a_row][a_kk];
+            if (AVEC == 4) *reinterpret_cast<float4 *>(dst) = make_float4(ra[p][0], ra[p][1 % AVEC], ra[p][2 % AVEC], ra[p][3 % AVEC]);
+            else if (AVEC == 2) *reinterpret_cast<float2 *>(dst) = make_float2(ra[p][0], ra[p][1 % AVEC]);
+            else *dst = ra[p][0];
+        }
+    };
+    const bool w_on = t < 2 * BN;
+    const int wcol = t % BN, wkh = (t / BN) & 1;
+    const bool wcol_ok = n0 + wcol < g.m;
+    const unsigned wmask = wcol_ok ? ~0u : 0u;   // columns past m read the last column and are cleared: a mask, not a branch around the fetch
+    const unsigned w_off = (unsigned)(((long long)wkh * 8 * g.ldw + (wcol_ok ? n0 + wcol : g.m - 1)) * 4);
+    float w_raw[8];
+    auto fetch_w = [&](int k0, auto whole) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            if constexpr (decltype(whole)::value) {
+                const char *row = reinterpret_cast<const char *>(g.W + (long long)(k0 + e) * g.ldw);   // uniform
+                w_raw[e] = __uint_as_float(__float_as_uint(*reinterpret_cast<const float *>(row + w_off)) & wmask);
+            } else {   // rows past k read the last row: their factors in A are zero
+                const int k = k0 + wkh * 8 + e;
+                const char *row = reinterpret_cast<const char *>(g.W + (long long)(k < g.k ? k : g.k - 1) * g.ldw - (long long)wkh * 8 * g.ldw);
+                w_raw[e] = __uint_as_float(__float_as_uint(*reinterpret_cast<const float *>(row + w_off)) & wmask);
+            }
+        }
+    };
+    auto stash_w = [&](int buf) {
+        unsigned pc[8][3];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) split_bf16x3(w_raw[e], pc[e][0], pc[e][1], pc[e][2]);
+        if (w_on) {
+#pragma unroll
+            for (int p = 0; p < 3; ++p) {
+                uintx4 w;
+#pragma unroll
+                for (int d = 0; d < 4; ++d) w[d] = pack_bf16(pc[2 * d][p], pc[2 * d + 1][p]);
+                *reinterpret_cast<uintx4 *>(&Bs[buf][p][wcol >> 5][wkh][wcol & 31][0]) = w;
+            }
+        }
+    };
+
+    // one step: fetch what step st + 1 needs, multiply step st out of the buffers st & 1, then fill the other buffers
+    auto step = [&](int st, auto next_whole) {
+        const int k1 = (st + 1) * 16;
+        fetch_a(k1, next_whole);   // past the last step: zeros, not used
+        fetch_w(k1, next_whole);
+        __builtin_amdgcn_sched_barrier(0);   // the fetches stay here and their use stays below the multiply: the scheduler would join them
+        __syncthreads();   // this step's blocks are in As[st & 1], Bs[st & 1]; nobody reads the other buffers any more
+        uintx4 af[2][3];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const float *src = &As[st & 1][wave * 64 + i * 32 + ll][kh * 8];
+            const float4 lo4 = *reinterpret_cast<const float4 *>(src), hi4 = *reinterpret_cast<const float4 *>(src + 4);
+            const float av[8] = {lo4.x, lo4.y, lo4.z, lo4.w, hi4.x, hi4.y, hi4.z, hi4.w};
+            unsigned pc[8][3];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) split_bf16x3(av[e], pc[e][0], pc[e][1], pc[e][2]);
+#pragma unroll
+            for (int p = 0; p < 3; ++p)
+#pragma unroll
+                for (int d = 0; d < 4; ++d) af[i][p][d] = pack_bf16(pc[2 * d][p], pc[2 * d + 1][p]);
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            uintx4 bf[3];
+#pragma unroll
+            for (int p = 0; p < 3; ++p) bf[p] = *reinterpret_cast<const uintx4 *>(&Bs[st & 1][p][j][kh][ll][0]);
+#pragma unroll
+            for (int pa = 2; pa >= 0; --pa)
+#pragma unroll
+                for (int pb = 2 - pa; pb >= 0; --pb)   // smallest products first
+#pragma unroll
+                    for (int i = 0; i < 2; ++i)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af[i][pa]), __builtin_bit_cast(bf16x8, bf[pb]),
+                                                                             acc[i][j], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        stash_a((st + 1) & 1);
+        stash_w((st + 1) & 1);
+    };
+    const int n_full = g.k / 16, n_steps = (g.k + 15) / 16;
+    if (n_full > 0) { fetch_a(0, std::true_type()); fetch_w(0, std::true_type()); }
+    else { fetch_a(0, std::false_type()); fetch_w(0, std::false_type()); }
+    stash_a(0);
+    stash_w(0);
+    int st = 0;
+    for (; st + 1 < n_full; ++st) step(st, std::true_type());
+    for (; st < n_steps; ++st) step(st, std::false_type());
+
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = n0 + j * 32 + ll;
+            if (col >= g.m_store) continue;
+            const long long y_col = g.y_sliced ? (long long)(col >> 5) * g.n * 32 + (col & 31) : (long long)col;
+            const long long y_ld = g.y_sliced ? 32 : g.ldy;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const long long row = m0 + wave * 64 + i * 32 + 8 * (r / 4) + 4 * kh + (r % 4);
+                if (row < g.n) {
+                    float y = acc[i][j][r];
+                    if (g.add) y += g.add[(long long)(col >> 5) * g.n * 32 + row * 32 + (col & 31)];
+                    if (g.row_scale) y *= g.row_scale[row];
+                    if (g.act == SENSEI_ACT_RELU) y = y > 0.f ? y : 0.f;
+                    g.Y[row * y_ld + y_col] = y;
+                }
+            }
+        }
+}
+
+template <int TN>
+hipError_t gemm_bf_launch(const GemmArgs &g, int avec, hipStream_t s) {
+    const dim3 grid((unsigned)(((g.n + 255) / 256) * g.n_bn));
+    if (avec == 4) hipLaunchKernelGGL((k_gemm_bf<TN, 4>), grid, dim3(kThreads), 0, s, g);
+    else if (avec == 2) hipLaunchKernelGGL((k_gemm_bf<TN, 2>), grid, dim3(kThreads), 0, s, g);
+    else hipLaunchKernelGGL((k_gemm_bf<TN, 1>), grid, dim3(kThreads), 0, s, g);
+    return hipGetLastError();
+}
+
 // ---- dense tiles of the hub region: C[order_r[rank], :] = sum over the kept 128 x 128 tiles of the rank's row of tiles of
 // (tile bits) . B[tile columns, :], B in rank order.  The rows of tiles of the largest hubs keep hundreds of tiles, the others a
 // few: the kept tiles of a row are therefore cut into segments of at most kTilesPerSegment, one workgroup per (segment, group
@@ -183,17 +382,6 @@ hipError_t gemm_launch_vec(const GemmArgs &g, int avec, int bvec, hipStream_t s)
 //     (k half, column) holding its eight k, so an operand fetch is one 16-byte load per lane straight from global memory.
 // A wavefront owns 128 tile rows x 32 columns (four accumulators) and walks its segment's tiles with the fetches running three
 // steps of 16 k ahead; the wavefronts of a workgroup only share the segment.
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ void split_bf16x3(float v, unsigned &hi, unsigned &mid, unsigned &lo) {
-    hi = __float_as_uint(v) & 0xFFFF0000u;
-    const float r1 = v - __uint_as_float(hi);          // exact: at most 16 significant bits remain
-    mid = __float_as_uint(r1) & 0xFFFF0000u;
-    lo = __float_as_uint(r1 - __uint_as_float(mid));   // exact: at most 8 significant bits, so its low half is zero
-}
-// two fp32 bit patterns whose low halves do not matter -> their high halves as a pair of bf16 (first in the low half)
-__device__ __forceinline__ unsigned pack_bf16(unsigned first, unsigned second) { return __builtin_amdgcn_perm(second, first, 0x07060302u); }
 // eight mask bits -> eight bf16 of value 0 or 2.0: bit k is copied to k and k + 15, then each pair (2d, 2d + 1) is moved onto
 // bits 14 and 30 of its word
 __device__ __forceinline__ uintx4 expand_mask_byte(unsigned byte) {
@@ -1018,6 +1206,20 @@ hipError_t launch_gemm(const float *A, int64_t lda, const float *W, int64_t ldw,
     if (k % 4 == 0 && lda % 4 == 0 && aa % 16 == 0) avec = 4;
     else if (k % 2 == 0 && lda % 2 == 0 && aa % 8 == 0) avec = 2;
     if (m % 4 == 0 && ldw % 4 == 0 && wa % 16 == 0) bvec = 4;
+    // Large products go to the bf16-piece kernel (256-row blocks): from one block per compute unit on
+    {
+        const int tn = m_store <= 32 ? 1 : m_store <= 64 ? 2 : 4;
+        const int n_bn = (m_store + 32 * tn - 1) / (32 * tn);
+        if (k >= 16 && ((n + 255) / 256) * n_bn >= 256 && lda < (1 << 21) && ldw < (1 << 21)) {   // leading dimensions: 32-bit byte offsets within a block
+            g.n_bn = n_bn;
+            int av = 1;
+            if (lda % 4 == 0 && aa % 16 == 0) av = 4;
+            else if (lda % 2 == 0 && aa % 8 == 0) av = 2;
+            if (tn == 1) return done(gemm_bf_launch<1>(g, av, s));
+            if (tn == 2) return done(gemm_bf_launch<2>(g, av, s));
+            return done(gemm_bf_launch<4>(g, av, s));
+        }
+    }
     // tile choice: widest column tile that the output needs; small tiles when the big ones
     // would leave most of the 256 compute units without a workgroup
     const long long big_blocks = ((n + 127) / 128) * ((m_store + 127) / 128);
