@@ -167,11 +167,21 @@ def _layer_report(torch, np, ctx, kind, A, Apre, N, nnz, r, c, Xd, Wd, att, f_in
         t = float(np.max([np.mean(ge[j::per][1:]) for j in range(per)])) * 1e-3      # the longest GEMM launch of the layer
         flops = 2.0 * N * f_in * f_out
         by = 4.0 * (N * f_in + f_in * f_out + N * f_out)
-        bound = "mfma" if flops / by > 157.3e12 / 8e12 else "hbm"
+        mult, peak, dtype = _gemm_matrix_core(N, f_in, f_out)
+        bound = "mfma" if mult * flops / by > peak / 8e12 else "hbm"
         rep["gemm"] = {"ms": round(t * 1e3, 4), "tflops": round(flops / t / 1e12, 1), "flop_per_byte": round(flops / by, 1), "bound": bound,
-                       "frac": round(flops / t / 157.3e12 if bound == "mfma" else by / t / 8e12, 3)}
+                       "matrix_core": dtype, "frac": round(mult * flops / t / peak if bound == "mfma" else by / t / 8e12, 3)}
     run(pick)  # the picked composition's output stays in `out`
     return rep
+
+
+def _gemm_matrix_core(n, k, m):
+    """(matrix-core operations per fp32 multiply-add pair, dense peak of that instruction in op/s, description) of the kernel the
+    library takes for an n x k by k x m product: the fp32 instruction, or six bf16 piece products per term for large products."""
+    from paper_2306_15155_amd import binding
+    if binding.gemm_kernel(n, k, m) == binding.GEMM_BF16_PIECES:
+        return 6.0, 2.5e15, "bf16, three exact pieces per fp32 operand, six piece products per term"
+    return 1.0, 157.3e12, "fp32"
 
 
 def run_extras(args, torch, np, synth, oracle):
@@ -506,7 +516,7 @@ def headline(args):
                     "gather_GBps_no_reuse": round(gather_bytes / t_s / 1e9, 1),
                     "measured_traffic_GBps": None if traffic is None else round(traffic / t_s / 1e9, 1)}
 
-    # ---- MFMA utilisation of the GEMM launch with the largest mean time (fp32 matrix peak 157.3 TFLOP/s)
+    # ---- MFMA utilisation of the GEMM launch with the largest mean time, against the peak of the instruction its kernel uses
     gemm_info = None
     n_gemm = [2 if (L["kind"] == "gat" and ids[i] == 1) else 1 for i, L in enumerate(layers)]
     if len(gemm_ms) == sum(n_gemm) * args.steps:
@@ -519,8 +529,11 @@ def headline(args):
             off += n_gemm[i]
         i, t = best
         flops = 2.0 * N * layers[i]["f_in"] * layers[i]["f_out"]
-        gemm_info = {"kernel": "k_gemm (%s, %dx%dx%d)" % (tag(i), N, layers[i]["f_in"], layers[i]["f_out"]), "avg_launch_ms": round(t, 4),
-                     "tflops": round(flops / t / 1e9, 1), "mfma_peak_tflops": 157.3, "mfma_utilisation": round(flops / t / 1e9 / 157.3, 3)}
+        mult, peak, dtype = _gemm_matrix_core(N, layers[i]["f_in"], layers[i]["f_out"])
+        gemm_info = {"kernel": "%s (%s, %dx%dx%d)" % ("k_gemm_bf" if mult > 1 else "k_gemm", tag(i), N, layers[i]["f_in"], layers[i]["f_out"]),
+                     "avg_launch_ms": round(t, 4), "tflops": round(flops / t / 1e9, 1), "matrix_core": dtype,
+                     "mfma_tflops": round(mult * flops / t / 1e9, 1), "mfma_peak_tflops": peak / 1e12,
+                     "mfma_utilisation": round(mult * flops / t / 1e9 / (peak / 1e12), 3)}
 
     # ---- per-layer and per-composition times (outside the timed region)
     def time_fn(fn, iters=3):

@@ -186,6 +186,13 @@ int sensei_norm_vectors(sensei_ctx *ctx, const int32_t *deg, int64_t n, float *o
  * or 512, growing with nnz (small graphs are latency bound and get more, shorter wavefronts).  Host arithmetic; 0 if nnz < 0. */
 int sensei_chunk_nnz(int64_t nnz);
 
+/* Which matrix-core kernel sensei_gemm (and the GEMM inside the layers) takes for an n x k by k x m product: the fp32 instruction,
+ * or, for large products, the bf16 instruction on three exact bf16 pieces per fp32 operand element with six piece products per
+ * term (what is left out is below 2^-23 of a term: the result is as accurate as the fp32 instruction's, at several times its
+ * rate).  Host arithmetic; for reports that price the kernel against the right matrix-core peak. */
+enum { SENSEI_GEMM_FP32 = 0, SENSEI_GEMM_BF16_PIECES = 1 };
+int sensei_gemm_kernel(int64_t n, int k, int m);
+
 /* Upper bound, in bytes, on the workspace any sparse primitive below needs for this matrix at
  * feature width `f` (host pointers). */
 int sensei_sparse_workspace(const sensei_csr *A, int f, size_t *bytes);

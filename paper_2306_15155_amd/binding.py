@@ -25,7 +25,7 @@ GAT_NAMES = ("REUSE", "RECOMP", "RECOMP_FOLD", "REUSE_FOLD")
 
 EXPORTS = (
     "sensei_create", "sensei_destroy", "sensei_calibrate", "sensei_num_compositions", "sensei_composition_name",
-    "sensei_status_string", "sensei_degrees", "sensei_norm_vectors", "sensei_sparse_workspace", "sensei_chunk_nnz", "sensei_gcn_precompute",
+    "sensei_status_string", "sensei_degrees", "sensei_norm_vectors", "sensei_sparse_workspace", "sensei_chunk_nnz", "sensei_gemm_kernel", "sensei_gcn_precompute",
     "sensei_row_broadcast", "sensei_spmm", "sensei_spmm_static", "sensei_gemm", "sensei_gemv2", "sensei_sddmm_score", "sensei_edge_softmax",
     "sensei_gcn_workspace", "sensei_gcn_layer", "sensei_gat_workspace", "sensei_gat_attention_path", "sensei_gat_layer", "sensei_select_workspace",
     "sensei_select", "sensei_profile_enable", "sensei_profile_read", "sensei_panels_bytes", "sensei_panels_create",
@@ -76,6 +76,7 @@ def lib():
         L.sensei_norm_vectors.argtypes = [vp, vp, i64, vp, vp]
         L.sensei_sparse_workspace.argtypes = [P(CsrStruct), i32, P(sz)]
         L.sensei_chunk_nnz.argtypes = [i64]
+        L.sensei_gemm_kernel.argtypes = [i64, i32, i32]
         L.sensei_gcn_precompute.argtypes = [vp, P(CsrStruct), vp, vp, vp, vp, sz, vp]
         L.sensei_row_broadcast.argtypes = [vp, vp, MatStruct, vp, i64, vp]
         L.sensei_spmm.argtypes = [vp, P(CsrStruct), i32, vp, vp, MatStruct, vp, i64, i32, vp, sz, vp]
@@ -143,6 +144,13 @@ def composition_name(kind: int, comp_id: int) -> str:
 
 def chunk_nnz(nnz: int) -> int:
     return lib().sensei_chunk_nnz(nnz)
+
+
+GEMM_FP32, GEMM_BF16_PIECES = 0, 1
+
+
+def gemm_kernel(n: int, k: int, m: int) -> int:
+    return lib().sensei_gemm_kernel(n, k, m)
 
 
 GAT_PATH_TWO_PASS, GAT_PATH_ONE_WALK, GAT_PATH_TILES, GAT_PATH_PANELS = 0, 1, 2, 3

@@ -1744,6 +1744,8 @@ int sensei_norm_vectors(sensei_ctx *ctx, const int32_t *deg, int64_t n, float *o
 
 int sensei_chunk_nnz(int64_t nnz) { return nnz < 0 ? 0 : choose_chunk_nnz(nnz); }
 
+int sensei_gemm_kernel(int64_t n, int k, int m) { return (n > 0 && k > 0 && m > 0 && gemm_uses_pieces(n, k, m)) ? SENSEI_GEMM_BF16_PIECES : SENSEI_GEMM_FP32; }
+
 int sensei_sparse_workspace(const sensei_csr *A, int f, size_t *bytes) {
     if (!csr_ok(A, false) || f < 0 || !bytes) return SENSEI_INVALID_ARGUMENT;
     *bytes = sparse_ws(*A, pad32(f));

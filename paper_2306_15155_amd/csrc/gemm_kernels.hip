@@ -1185,6 +1185,13 @@ __global__ __launch_bounds__(kThreads) void k_gemv2(const float *__restrict__ A,
 
 }  // namespace
 
+// from one 256-row block per compute unit on, and at least one whole step of 16 k
+bool gemm_uses_pieces(int64_t n, int k, int m_store) {
+    const int tn = m_store <= 32 ? 1 : m_store <= 64 ? 2 : 4;
+    const int n_bn = (m_store + 32 * tn - 1) / (32 * tn);
+    return k >= 16 && m_store > 0 && ((n + 255) / 256) * n_bn >= 256;
+}
+
 hipError_t launch_gemm(const float *A, int64_t lda, const float *W, int64_t ldw, float *Y, int64_t ldy, int64_t n,
                        int k, int m, int m_store, int act, hipStream_t s, const float *row_scale, KernelTimer *timer, bool y_sliced,
                        bool a_sliced, const float *add_sliced) {
@@ -1206,11 +1213,11 @@ hipError_t launch_gemm(const float *A, int64_t lda, const float *W, int64_t ldw,
     if (k % 4 == 0 && lda % 4 == 0 && aa % 16 == 0) avec = 4;
     else if (k % 2 == 0 && lda % 2 == 0 && aa % 8 == 0) avec = 2;
     if (m % 4 == 0 && ldw % 4 == 0 && wa % 16 == 0) bvec = 4;
-    // Large products go to the bf16-piece kernel (256-row blocks): from one block per compute unit on
+    // Large products go to the bf16-piece kernel (256-row blocks)
     {
         const int tn = m_store <= 32 ? 1 : m_store <= 64 ? 2 : 4;
         const int n_bn = (m_store + 32 * tn - 1) / (32 * tn);
-        if (k >= 16 && ((n + 255) / 256) * n_bn >= 256 && lda < (1 << 21) && ldw < (1 << 21)) {   // leading dimensions: 32-bit byte offsets within a block
+        if (gemm_uses_pieces(n, k, m_store) && lda < (1 << 21) && ldw < (1 << 21)) {   // leading dimensions: 32-bit byte offsets within a block
             g.n_bn = n_bn;
             int av = 1;
             if (lda % 4 == 0 && aa % 16 == 0) av = 4;

@@ -231,6 +231,7 @@ hipError_t launch_tiles_combine_pm(const TileSplit &T, float *C, int64_t n_rows,
 // ---- dense
 // Y[0:n, 0:m_store) = act(row_scale[i] * (A[n x k] . W[k x m])); columns m..m_store are written as act(0);
 // row_scale may be null (no scaling).
+bool gemm_uses_pieces(int64_t n, int k, int m_store);   // whether launch_gemm takes the bf16-piece kernel for this shape (ordinary leading dimensions)
 hipError_t launch_gemm(const float *A, int64_t lda, const float *W, int64_t ldw, float *Y, int64_t ldy, int64_t n,
                        int k, int m, int m_store, int act, hipStream_t s, const float *row_scale = nullptr,
                        KernelTimer *timer = nullptr, bool y_sliced = false, bool a_sliced = false, const float *add_sliced = nullptr);
