@@ -1039,14 +1039,14 @@ double t_spmm_unsplit(const sensei_ctx &c, const Features &g, double f, int flav
 
 // What the call costs on the path it will take: a pattern that carries a usable dense-tile split runs its value-less and
 // attention aggregations as tiles + remainder, which removes the tiles' share of the gathers but leaves the cold entries
-// (measured on the 233,000-node power-law graph, 64 % of the entries in tiles: 0.75 of the unsplit call at 256 columns,
-// 0.79 at 64).  Weighted and scaled SpMMs do not take the split.
+// (measured on the 233,000-node power-law graph, 64 % of the entries in tiles: 0.57 of the unsplit call at 256 columns,
+// 3.26 against 5.74 ms).  Weighted and scaled SpMMs do not take the split.
 double t_spmm(const sensei_ctx &c, const Features &g, double f, int flavour) {
     const double t = t_spmm_unsplit(c, g, f, flavour);
     const bool takes_split = (flavour == kSpmmPattern || flavour == kSpmmSoftmaxCost) && g.tile_share > 0.0;
     const double need = flavour == kSpmmSoftmaxCost ? g.tile_min_width / 2.0 : g.tile_min_width;
     if (!takes_split || f < need || std::ceil(f / 32.0) * 32.0 > g.tile_max_width) return t;
-    return t * (1.0 - 0.4 * g.tile_share);
+    return t * (1.0 - 0.65 * g.tile_share);
 }
 
 double t_spmm_unsplit(const sensei_ctx &c, const Features &g, double f, int flavour) {
