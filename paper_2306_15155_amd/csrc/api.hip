@@ -1473,15 +1473,17 @@ struct TilesLayout {
 };
 
 // Column panels of the remainder's panel-major copy, from the features known before the split: two where a 128-byte slice of the
-// gathered matrix exceeds the L2s several times over and rows are long enough that half a row is still a run of gathers; none
-// otherwise.  Measured on the 233,000-node power-law graph (494 entries per row, 41.8 M of 115 M entries in the remainder), whole
-// three-layer step with 1 / 2 / 3 / 4 / 6 panels: 12.08 / 11.54 / 11.67 / 12.14 / 13.16 ms - the L2 hit rate of the remainder keeps
-// rising with the panel count (44 % -> 82 % at eight), but every (panel, row) segment costs a row end in the kernel and a partial
-// row written and read back, and the call shares the GPU with the tile kernel, which takes as long.
+// gathered matrix exceeds the L2s several times over (12 MB) and rows are long enough that a part of a row is still a run of
+// gathers, three from 24 MB on; none otherwise.  Measured on the 233,000-node power-law graph (slice 29.8 MB, 494 entries per
+// row, 41.8 M of 115 M entries in the remainder), whole three-layer step with 2 / 3 / 4 panels: 10.00 / 9.90 / 10.59 ms - the L2
+// hit rate of the remainder keeps rising with the panel count (44 % -> 82 % at eight), but every (panel, row) segment costs a
+// row end in the kernel and a partial row written and read back.
 int g_remainder_panels_override = 0;  // sensei_tiles_remainder_panels: 0 = the rule below
 int remainder_panels_for(const sensei_csr &A) {
     if (g_remainder_panels_override > 0) return (int64_t)A.n_rows * g_remainder_panels_override < (1LL << 30) ? g_remainder_panels_override : 1;
-    return ((double)A.n_cols * 128.0 >= 12e6 && A.nnz >= 128 * (int64_t)A.n_rows && (int64_t)A.n_rows * 2 < (1LL << 30)) ? 2 : 1;
+    if ((double)A.n_cols * 128.0 < 12e6 || A.nnz < 128 * (int64_t)A.n_rows) return 1;
+    const int q = (double)A.n_cols * 128.0 >= 24e6 ? 3 : 2;
+    return (int64_t)A.n_rows * q < (1LL << 30) ? q : 1;
 }
 
 TilesLayout tiles_layout(const sensei_csr &A, float min_density, int max_width) {
