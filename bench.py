@@ -508,7 +508,7 @@ def headline(args):
         # from the kernel sources this run was built from
         traffic = _profile_value(os.path.join(ROOT, "profiles", "k_spmm_%s_pmc.txt" % args.workload), "traffic_bytes_per_launch %s" % tag(k))
         split = tiles_attached and tiles.n_tiles > 0 and f_sp >= args.tiles_min_width
-        what = "SpMM call = k_spmm on the sparse remainder + k_dense_tiles on the hub tiles" if split else "k_spmm"
+        what = "SpMM call = hub tiles on the bf16 matrix cores (k_dense_tiles_bf / k_dense_tiles_attn_bf) + k_spmm on the sparse remainder + join" if split else "k_spmm"
         roofline = {"kernel": "%s (%s, F=%d, %s)" % (what, tag(k), f_sp, name_of(k)), "bound": "hbm",
                     "achieved": round(algo_bytes / t_s / 1e9, 1), "peak": 8000.0, "unit": "GB/s",
                     "frac": round(algo_bytes / t_s / 1e9 / 8000.0, 4), "traffic": traffic,
