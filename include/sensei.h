@@ -226,7 +226,8 @@ int sensei_spmm(sensei_ctx *ctx, const sensei_csr *A, int mode, const float *r, 
 int sensei_spmm_static(sensei_ctx *ctx, const sensei_csr *A, int mode, const float *r, const float *c, sensei_mat B, float *C,
                        int64_t ldc, int activation, void *stream);
 
-/* Dense update Y = act(A . W) on the fp32 matrix cores (background: dense primitives).
+/* Dense update Y = act(A . W) on the matrix cores, fp32 in and out at fp32 accuracy (background: dense primitives; which
+ * instruction a shape takes: sensei_gemm_kernel).
  * A: n x k, W: k x m, Y: n x m with leading dimension ldy. */
 int sensei_gemm(sensei_ctx *ctx, sensei_mat A, sensei_mat W, float *Y, int64_t ldy, int activation, void *stream);
 
@@ -282,10 +283,13 @@ int sensei_dotgat_layer(sensei_ctx *ctx, const sensei_csr *A, sensei_mat X, sens
  * On a skewed graph the rows and columns of the highest degree meet in a region that is nearly full: with the nodes in
  * order of descending degree, tiles of 128 x 128 ranks (among the first 65,536 ranks of either side) that hold at least
  * min_density * 16384 entries are kept as bit masks and multiplied on the matrix cores (sparse unweighted . dense
- * evaluated as a block-sparse GEMM) on a stream of the object's own, while the caller's stream runs the SpMM over the
- * CSR remainder of the entries outside such tiles; a last pass on the caller's stream joins the two sums and applies the
- * row scaling and the activation (the fork and join are event dependencies between the two streams, so the call stays
- * asynchronous and can be captured into a graph).  These steps use the split when `tiles` is set in the sensei_csr:
+ * evaluated as a block-sparse GEMM), the SpMM runs over the CSR remainder of the entries outside such tiles, and a last
+ * pass joins the two sums and applies the row scaling and the activation.  The tiles use the bf16 matrix instruction at
+ * fp32 accuracy: a mask entry is 0 or 1, and every fp32 operand element is cut exactly into three bf16 pieces (the attention
+ * weights as well: six piece products per term, what is left out is below 2^-23 of a term).  Where a step uses the object's
+ * own stream (the GAT layer's tile statistics, the backward), the fork and join are event dependencies between the two
+ * streams, so the call stays asynchronous and can be captured into a graph.  These steps use the split when `tiles` is set
+ * in the sensei_csr:
  * the value-less SpMM on an internal slice-major operand of at most max_width columns (a multiple of 32; what the
  * GCN, SGC and TAGCN layers and the GCN backward run on graphs whose rows are gathered often); the attention
  * aggregation of the GAT layer (reuse compositions: every head whose width is a whole number of 32-column slices;
@@ -293,9 +297,9 @@ int sensei_dotgat_layer(sensei_ctx *ctx, const sensei_csr *A, sensei_mat X, sens
  * weights from the attention projections themselves; and two steps of the
  * GAT backward (see there).  Every other call ignores it.  Results differ from the unsplit path only in the order of
  * summation.  Whether the split pays depends on the graph: attach it when a good part of the entries lies in kept tiles
- * (sensei_tiles_info; measured: 64 % of the entries: SpMM call -25 %; 20 %: +5 %, so leave it off there).
+ * (sensei_tiles_info; measured: 64 % of the entries: SpMM call -44 %; 20 %: +2 %, so leave it off there).
  * min_density: 0 < min_density <= 1; 0.05 .. 0.09 measured best on a
- * 233,000-node power-law graph (0.07: 64 % of the entries in 22,334 tiles, step time 16.9 -> 12.1 ms).
+ * 233,000-node power-law graph (0.07: 64 % of the entries in 22,334 tiles, step time 16.9 -> 9.9 ms).
  *   sensei_tiles_bytes   device bytes sensei_tiles_create needs (an upper bound taken before the tiles are counted);
  *   sensei_tiles_create  builds the split in device_buf (256-byte aligned, caller-owned, must outlive the object);
  *                        ranks the nodes on the host, so it synchronises the stream several times: a set-up call;
@@ -305,10 +309,10 @@ int sensei_dotgat_layer(sensei_ctx *ctx, const sensei_csr *A, sensei_mat X, sens
  *   sensei_tiles_destroy frees the host object only.
  * The object keeps buffers for the operand in rank order and for the tiles' product, and its stream: calls that use one
  * object at the same time on different streams race on them.
- * The remainder itself may be kept a second time in panel-major order (its entries column panel by column panel, two panels), which the
+ * The remainder itself may be kept a second time in panel-major order (its entries column panel by column panel, two or three panels), which the
  * forward SpMM calls of 64 columns or more then walk in one launch, one raw partial row per (panel, row), joined by the last pass: the part
  * of the gathered matrix in use at one time then fits the L2s.  Chosen automatically (a 128-byte slice of the gathered matrix of 12 MB or
- * more, 128 or more entries per row); sensei_tiles_remainder_panels overrides the choice for the objects created afterwards in this
+ * more, 128 or more entries per row; three panels from 24 MB on); sensei_tiles_remainder_panels overrides the choice for the objects created afterwards in this
  * process (0: automatic, 1: never, 2..8: that many panels whatever the graph; returns the previous setting; a tuning and testing knob -
  * set it before sensei_tiles_bytes, which sizes the buffer for it). */
 int sensei_tiles_remainder_panels(int n_panels);

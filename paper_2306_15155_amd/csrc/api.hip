@@ -17,7 +17,7 @@ struct sensei_ctx {
     double stream_bps;     // achieved bandwidth of a streaming (read + write) kernel
     double gather_l2_bps;  // row-gather bandwidth when the gathered slice fits the L2s
     double gather_far_bps; // row-gather bandwidth when it does not (Infinity Cache / HBM)
-    double gemm_flops;     // achieved fp32 MFMA rate on large tiles
+    double gemm_flops;     // achieved rate of fp32 multiply-adds of the GEMM on large products
     double l2_slice_bytes; // feature-slice footprint at which 88 % of the gathers are served by the L2s
     Timers timers;         // optional per-launch timing of the SpMM and GEMM kernels
     void *scratch;         // device address of the static scratch array on this context's GPU (sensei_spmm_static)

@@ -1,6 +1,7 @@
-// Dense kernels for gfx950: the fp32 update GEMM on the matrix cores
-// (v_mfma_f32_32x32x2_f32) with the activation fused into the epilogue, and a
-// two-vector GEMV for the attention projections.
+// Dense kernels for gfx950: the fp32 update GEMM on the matrix cores with the activation fused into the
+// epilogue (small products: v_mfma_f32_32x32x2_f32; large ones: v_mfma_f32_32x32x16_bf16 on three exact
+// bf16 pieces per fp32 operand), the dense tiles of the hub region of a skewed graph (the same bf16
+// instruction), the weight-gradient GEMM with fp64 slabs, and a two-vector GEMV for the attention projections.
 #include "sensei_internal.h"
 
 #include <type_traits>
