@@ -1132,6 +1132,137 @@ __global__ __launch_bounds__(kThreads) void k_gemm_tn(GemmTnArgs g) {
         }
 }
 
+// The same reduction on the bf16 matrix instruction at fp32 accuracy (three exact bf16 pieces per operand element, six piece
+// products per term, as in k_gemm_bf).  Both operands arrive k-major, while a lane of the 32 x 32 x 16 instruction wants eight
+// consecutive k of one column: a thread fetches exactly that (eight rows of its column, neighbouring lanes on neighbouring columns),
+// cuts the eight values into pieces and leaves them in LDS in lane order, for both operands alike; two buffers, one barrier per step
+// of 16 k, fetches one step ahead.  The fp32 accumulators are emptied into fp64 registers after every second step.
+constexpr int kFlushStepsBf = 2;
+
+__global__ __launch_bounds__(kThreads) void k_gemm_tn_bf(GemmTnArgs g) {
+    constexpr int BM = 128, BN = 128, TM = 2, TN = 2;
+    __shared__ __attribute__((aligned(16))) unsigned short Ps[2][2][3][4][2][32][8];   // [buffer][operand][piece][32-column block][k half][column][8 k]
+    const int t = threadIdx.x;
+    const int wave = t >> 6, lane = t & 63;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int kh = lane >> 5, ll = lane & 31;
+    const int tile = (int)(blockIdx.x % g.n_tiles), split = (int)(blockIdx.x / g.n_tiles);
+    const int m0 = (tile / g.n_bn) * BM, n0 = (tile % g.n_bn) * BN;
+    const long long k_lo = (long long)split * g.k_per_split;
+    const long long k_hi = (k_lo + g.k_per_split < g.k) ? k_lo + g.k_per_split : g.k;
+
+    floatx16 acc[TM][TN];
+    double dacc[TM][TN][16];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { acc[i][j][r] = 0.f; dacc[i][j][r] = 0.0; }
+    auto flush = [&]() {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) { dacc[i][j][r] += (double)acc[i][j][r]; acc[i][j][r] = 0.f; }
+    };
+
+    // staging: thread -> (column of the 128, k half); columns past the edge read the last column and are cleared, rows past the slab
+    // read its last row and are cleared (masks, not branches around the fetches)
+    const int col = t & 127, skh = t >> 7;
+    const bool a_ok = m0 + col < g.m, b_ok = n0 + col < g.n;
+    const unsigned a_mask = a_ok ? ~0u : 0u, b_mask = b_ok ? ~0u : 0u;
+    // addresses: a uniform row pointer per k plus one 32-bit byte offset per lane (its k half and column), fixed before the loop
+    const unsigned a_off = (unsigned)(((long long)skh * 8 * g.lda + (a_ok ? m0 + col : g.m - 1)) * 4);
+    const unsigned b_off = (unsigned)(((long long)skh * 8 * g.ldb + (b_ok ? n0 + col : g.n - 1)) * 4);
+    float ra[8], rb[8];
+    auto fetch = [&](long long k0, auto whole) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            if constexpr (decltype(whole)::value) {   // all 16 rows of the step lie inside the slab
+                const char *ar = reinterpret_cast<const char *>(g.A + (k0 + e) * g.lda), *br = reinterpret_cast<const char *>(g.B + (k0 + e) * g.ldb);
+                ra[e] = __uint_as_float(__float_as_uint(*reinterpret_cast<const float *>(ar + a_off)) & a_mask);
+                rb[e] = __uint_as_float(__float_as_uint(*reinterpret_cast<const float *>(br + b_off)) & b_mask);
+            } else {
+                const long long k = k0 + skh * 8 + e;
+                const long long kc = (k < k_hi ? k : k_hi - 1) - skh * 8;
+                const unsigned live = k < k_hi ? ~0u : 0u;
+                const char *ar = reinterpret_cast<const char *>(g.A + kc * g.lda), *br = reinterpret_cast<const char *>(g.B + kc * g.ldb);
+                ra[e] = __uint_as_float(__float_as_uint(*reinterpret_cast<const float *>(ar + a_off)) & a_mask & live);
+                rb[e] = __uint_as_float(__float_as_uint(*reinterpret_cast<const float *>(br + b_off)) & b_mask);
+            }
+        }
+    };
+    auto stash_one = [&](const float (&src)[8], int buf, int operand) {
+        unsigned pc[8][3];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) split_bf16x3(src[e], pc[e][0], pc[e][1], pc[e][2]);
+#pragma unroll
+        for (int p = 0; p < 3; ++p) {
+            uintx4 w;
+#pragma unroll
+            for (int d = 0; d < 4; ++d) w[d] = pack_bf16(pc[2 * d][p], pc[2 * d + 1][p]);
+            *reinterpret_cast<uintx4 *>(&Ps[buf][operand][p][col >> 5][skh][col & 31][0]) = w;
+        }
+    };
+    auto stash = [&](int buf) {
+        stash_one(ra, buf, 0);
+        __builtin_amdgcn_sched_barrier(0);   // one operand's pieces at a time in registers
+        stash_one(rb, buf, 1);
+    };
+
+    if (k_lo < k_hi) {
+        int buf = 0, since_flush = 0;
+        auto step = [&](long long k0, auto next_whole) {
+            fetch(k0 + 16 < k_hi ? k0 + 16 : k0, next_whole);   // past the last step: this step again, not used
+            __builtin_amdgcn_sched_barrier(0);      // the fetches stay here and their use stays below the multiply
+            __syncthreads();                        // this step's pieces are in Ps[buf]; nobody reads the other buffer any more
+            // few fragments live at a time (the fp64 accumulators take half the registers): the pieces of B are read again for each
+            // piece of A they meet
+#pragma unroll
+            for (int pa = 2; pa >= 0; --pa) {
+                uintx4 af[TM];
+#pragma unroll
+                for (int i = 0; i < TM; ++i) af[i] = *reinterpret_cast<const uintx4 *>(&Ps[buf][0][pa][wm * TM + i][kh][ll][0]);
+#pragma unroll
+                for (int pb = 2 - pa; pb >= 0; --pb)   // smallest products first
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        const uintx4 bf = *reinterpret_cast<const uintx4 *>(&Ps[buf][1][pb][wn * TN + j][kh][ll][0]);
+#pragma unroll
+                        for (int i = 0; i < TM; ++i)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af[i]), __builtin_bit_cast(bf16x8, bf), acc[i][j], 0, 0, 0);
+                    }
+            }
+            if (++since_flush == kFlushStepsBf) { flush(); since_flush = 0; }
+            __builtin_amdgcn_sched_barrier(0);
+            stash(buf ^ 1);
+            buf ^= 1;
+        };
+        if (k_lo + 16 <= k_hi) fetch(k_lo, std::true_type()); else fetch(k_lo, std::false_type());
+        stash(0);
+        long long k0 = k_lo;
+        for (; k0 + 32 <= k_hi; k0 += 16) step(k0, std::true_type());   // the next step is whole
+        for (; k0 < k_hi; k0 += 16) step(k0, std::false_type());
+    }
+    flush();
+
+    double *out = g.part + (size_t)split * (size_t)g.m * (size_t)g.n;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int c = n0 + (wn * TN + j) * 32 + ll;
+            if (c >= g.n) continue;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = m0 + (wm * TM + i) * 32 + 8 * (r / 4) + 4 * kh + (r % 4);
+                if (row < g.m) out[(size_t)row * g.n + c] = dacc[i][j][r];
+            }
+        }
+}
+
 // C[i] = sum over the slabs, in slab order
 __global__ void k_sum_splits(const double *__restrict__ part, int splits, long long mn, int n, float *__restrict__ C, long long ldc) {
     const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -1404,7 +1535,9 @@ hipError_t launch_gemm_tn(const float *A, int64_t lda, const float *B, int64_t l
     const bool va = (m % 4 == 0 && lda % 4 == 0 && reinterpret_cast<uintptr_t>(A) % 16 == 0);
     const bool vb = (n % 4 == 0 && ldb % 4 == 0 && reinterpret_cast<uintptr_t>(B) % 16 == 0);
     dim3 grid((unsigned)(g.n_tiles * splits));
-    if (va && vb) hipLaunchKernelGGL((k_gemm_tn<4, 4>), grid, dim3(kThreads), 0, s, g);
+    // long reductions (the weight gradients of a layer) take the bf16-piece kernel
+    if (g.k >= 4096 && g.k_per_split >= 64) hipLaunchKernelGGL(k_gemm_tn_bf, grid, dim3(kThreads), 0, s, g);
+    else if (va && vb) hipLaunchKernelGGL((k_gemm_tn<4, 4>), grid, dim3(kThreads), 0, s, g);
     else if (va) hipLaunchKernelGGL((k_gemm_tn<4, 1>), grid, dim3(kThreads), 0, s, g);
     else if (vb) hipLaunchKernelGGL((k_gemm_tn<1, 4>), grid, dim3(kThreads), 0, s, g);
     else hipLaunchKernelGGL((k_gemm_tn<1, 1>), grid, dim3(kThreads), 0, s, g);
