@@ -36,7 +36,7 @@ def _cut16(x):
     return (x.view(np.uint32) & np.uint32(0xFFFFFF00)).view(np.float32)
 
 
-@pytest.mark.parametrize("shape", [(70_000, 602, 256), (140_000, 100, 64), (300_000, 48, 24)])
+@pytest.mark.parametrize("shape", [(70_000, 602, 256), (140_000, 100, 64), (300_000, 48, 24), (90_000, 101, 96)])   # 8-, 16-, 16- and 4-byte aligned rows
 def test_gemm_on_bf16_pieces_is_as_accurate_as_fp32(ctx, shape):
     n, k, m = shape
     assert binding.gemm_kernel(n, k, m) == binding.GEMM_BF16_PIECES
