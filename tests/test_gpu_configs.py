@@ -363,6 +363,29 @@ def test_config2_sgc_backward_two_hops_full_size(ctx, reddit_like):
     assert_close(torch.from_numpy(dws[0]), dws[1], what="dW of the two associations")
 
 
+@pytest.mark.parametrize("shape", [(40, 96), (100, 41), (33, 200)])
+def test_k_hop_layers_at_a_size_that_takes_the_large_product_gemm(ctx, shape):
+    """The K-hop layers feed the update GEMM a slice-major operand (TAGCN aggregate-first: depth (K + 1) F_in), add a slice-major
+    term in its epilogue (TAGCN update-first) and let it write slice-major (both); on small graphs those GEMMs take the fp32
+    kernel.  70,000 nodes put them on the kernel for large products; the whole output is checked against the oracle."""
+    from paper_2306_15155_amd import binding
+    g = synth.rmat(61, 70_000, 900_000)
+    f_in, f_out = shape
+    assert binding.gemm_kernel(g.n_rows, f_in, f_out) == binding.GEMM_BF16_PIECES
+    A = DeviceCSR(g)
+    dr, dc = ctx.degrees(A.s)
+    r, c = ctx.norm_vectors(dr), ctx.norm_vectors(dc)
+    X = synth.uniform(61, 10, (g.n_cols, f_in))
+    W = synth.glorot(61, 11, 3 * f_in, f_out)
+    ref = oracle.tagcn_layer(g.n_rows, g.row_ptr, g.col_idx, X, W, 2, ACT_RELU)
+    for cid in (0, 1):
+        assert_close(ctx.tagcn_layer(A.s, r, c, dev(X), dev(W), 2, cid, ACT_RELU), ref, what=f"tagcn comp {cid}")
+    Ws = synth.glorot(61, 12, f_in, f_out)
+    ref = oracle.sgc_layer(g.n_rows, g.row_ptr, g.col_idx, X, Ws, 2, ACT_RELU)
+    for cid in (0, 1):
+        assert_close(ctx.sgc_layer(A.s, r, c, dev(X), dev(Ws), 2, cid, ACT_RELU), ref, what=f"sgc comp {cid}")
+
+
 def test_config4_gatv2_full_size(ctx, reddit_like):
     """GATv2 layer 602 -> 64 on the Reddit-shaped graph: sampled rows (the longest, a shortest, 300 random) against the oracle."""
     g, A = reddit_like
