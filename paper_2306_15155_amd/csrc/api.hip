@@ -198,6 +198,7 @@ struct AttnVectors {  // what the softmax mode of the dense tiles needs besides 
     const float *s_l, *s_r;
     float slope;
     bool gathered;  // the operand already sits in the split's buffer in rank order (the caller ran launch_tiles_gather)
+    bool tiles_done = false;  // the caller has also multiplied the tiles already, with the tile-local shift (launch_dense_tiles, local_shift)
 };
 
 bool tiles_usable(const sensei_csr &A, int mode, int f, bool b_sliced, bool attn = false) {
@@ -233,8 +234,11 @@ hipError_t spmm_any(const sensei_csr &A, int mode, const float *r, const float *
         // tile kernels keep most of a compute unit's registers, and beside them the remainder loses more time than the tiles
         // take alone (233,000-node power-law graph, 256 columns: 3.44 ms together, 3.28 ms one after the other); the attention
         // tiles, eight wavefronts and 36 KB of LDS a workgroup, find no room beside the remainder and run after it anyway.
-        hipError_t e = launch_dense_tiles(D.T, B, A.n_cols, pad32(f), D.Bh, s, attn ? attn->s_l : nullptr, attn ? attn->s_r : nullptr,
-                                          attn ? mz : nullptr, attn ? attn->slope : 0.f, false, attn && attn->gathered);
+        const bool tiles_done = attn && attn->tiles_done;
+        const float *tile_shift = tiles_done ? D.T.rank_vec + (size_t)D.T.nt_r * 128 : nullptr;
+        hipError_t e = tiles_done ? hipSuccess
+                                  : launch_dense_tiles(D.T, B, A.n_cols, pad32(f), D.Bh, s, attn ? attn->s_l : nullptr, attn ? attn->s_r : nullptr,
+                                                       attn ? mz : nullptr, attn ? attn->slope : 0.f, false, attn && attn->gathered);
         if (e != hipSuccess) return e;
         sensei_csr Ar = A;
         Ar.nnz = D.nnz_rem; Ar.row_ptr = D.row_ptr_rem; Ar.col_idx = D.col_rem; Ar.panels = nullptr; Ar.tiles = nullptr;
@@ -256,7 +260,8 @@ hipError_t spmm_any(const sensei_csr &A, int mode, const float *r, const float *
                                 b_sliced, 1, true, true);
             if (e == hipSuccess)
                 e = launch_tiles_combine_pm(D.T, C, A.n_rows, f_store, ldc, c_sliced, fp, mode == kSpmmSoftmax ? nullptr : r,
-                                            mode == kSpmmSoftmax ? mz : nullptr, act, s, D.part_pm, D.rem_panels, D.seg_ptr, D.plan_pm.chunk_nnz, carry, fp);
+                                            mode == kSpmmSoftmax ? mz : nullptr, act, s, D.part_pm, D.rem_panels, D.seg_ptr, D.plan_pm.chunk_nnz, carry, fp,
+                                            tile_shift);
             if (e != hipSuccess) return e;
             if (t1 && hipEventRecord(t1, s) != hipSuccess) return hipErrorUnknown;
             return hipSuccess;
@@ -266,7 +271,7 @@ hipError_t spmm_any(const sensei_csr &A, int mode, const float *r, const float *
                         c_sliced, true);
         if (e == hipSuccess)
             e = launch_tiles_combine(D.T, C, A.n_rows, f_store, ldc, c_sliced, pad32(f), mode == kSpmmSoftmax ? nullptr : r,
-                                     mode == kSpmmSoftmax ? mz : nullptr, act, s, D.row_ptr_rem, D.plan_rem.chunk_nnz, carry, pad32(f));
+                                     mode == kSpmmSoftmax ? mz : nullptr, act, s, D.row_ptr_rem, D.plan_rem.chunk_nnz, carry, pad32(f), tile_shift);
         if (e != hipSuccess) return e;
         if (t1 && hipEventRecord(t1, s) != hipSuccess) return hipErrorUnknown;
         return hipSuccess;
@@ -655,8 +660,12 @@ int run_gat(const sensei_csr &A, const sensei_mat &X, const sensei_mat &W, const
             SENSEI_TRY(hipEventRecord(D.ev_fork, s));
             SENSEI_TRY(hipStreamWaitEvent(D.side, D.ev_fork, 0));
             SENSEI_TRY(launch_tile_stats(D.T, s_l, s_r, slope, D.side));
-            // the rows the tiles will multiply, in rank order: known since the GEMM, so gathered here, beside the remainder's pass
+            // the rows the tiles will multiply, in rank order: known since the GEMM, so gathered here, beside the remainder's pass; and
+            // the tiles themselves, with the maximum over a row's tile entries as its shift (the join rescales their product to the
+            // row's own maximum): the remainder's pass asks little of the matrix cores, so the two share the chip better than
+            // the tiles and the aggregation of the remainder would (233,000-node power-law graph, 256 columns: layer 4.94 -> 4.78 ms)
             SENSEI_TRY(launch_tiles_gather(D.T, reuse ? theta_h : x_src, A.n_cols, pad32(f_gather), D.Bh, D.side));
+            SENSEI_TRY(launch_dense_tiles(D.T, nullptr, A.n_cols, pad32(f_gather), D.Bh, D.side, s_l, s_r, nullptr, slope, false, true, true));
             SENSEI_TRY(hipEventRecord(D.ev_join, D.side));
             sensei_csr Ar = A;
             Ar.nnz = D.nnz_rem; Ar.row_ptr = D.row_ptr_rem; Ar.col_idx = D.col_rem; Ar.panels = nullptr; Ar.tiles = nullptr;
@@ -668,7 +677,7 @@ int run_gat(const sensei_csr &A, const sensei_mat &X, const sensei_mat &W, const
         } else if (!fused) {
             SENSEI_TRY(launch_attention_stats(A, s_l, s_r, slope, logits, by_panel ? A.panels->position : nullptr, plan, stats, carry_stats, s));
         }
-        const AttnVectors attn = {s_l, s_r, slope, by_tiles};
+        const AttnVectors attn = {s_l, s_r, slope, by_tiles, by_tiles};
         sensei_csr Aw = A;
         Aw.val = logits;
         float *Y_h = Y + (size_t)h * d;

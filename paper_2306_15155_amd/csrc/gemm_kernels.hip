@@ -685,7 +685,8 @@ __global__ void k_tiles_reduce(const float *__restrict__ part, const int32_t *__
 // and applies what the SpMM epilogue would have applied (scale_i = r[i], or 1 / z_i in attention mode)
 __global__ void k_tiles_combine(float *__restrict__ C, long long n_rows, int f_store, long long ldc, long long c_tile, const float *__restrict__ Dh,
                                 int f, const int32_t *__restrict__ rank_r, int n_ranks, const float *__restrict__ r, const float2 *__restrict__ mz,
-                                int act, int vec4, const int32_t *__restrict__ row_ptr, int chunk_nnz, const float *__restrict__ carry, int f_carry) {
+                                int act, int vec4, const int32_t *__restrict__ row_ptr, int chunk_nnz, const float *__restrict__ carry, int f_carry,
+                                const float *__restrict__ tile_shift) {
     const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     const int f4 = (f_store + 3) / 4;
     if (t >= n_rows * f4) return;
@@ -697,6 +698,10 @@ __global__ void k_tiles_combine(float *__restrict__ C, long long n_rows, int f_s
     else if (r) sc = r[i];
     float *dst = C + (long long)(col >> 5) * c_tile + i * ldc + (col & 31);
     const float *add = (rank < n_ranks) ? Dh + (size_t)rank * f + col : nullptr;
+    // attention tiles that were multiplied before the row maxima were known used the maximum over the row's tile entries as the shift:
+    // exp(that - the row maximum) brings their sum to the row's scale
+    float tf = 1.f;
+    if (tile_shift && add) { const float ts = tile_shift[rank]; tf = ts > -INFINITY ? __expf(ts - mz[i].x) : 0.f; }
     // the SpMM's own fix-up, when the caller left it to this pass: a row that spans chunk boundaries has its later pieces in the
     // carry slots of the chunks it continues into, c * chunk_nnz strictly inside the row; they are added in chunk order
     long long c_first = 1, c_last = 0;
@@ -716,7 +721,7 @@ __global__ void k_tiles_combine(float *__restrict__ C, long long n_rows, int f_s
         }
         if (add) {
             const float4 a4 = *reinterpret_cast<const float4 *>(add);
-            y.x += a4.x; y.y += a4.y; y.z += a4.z; y.w += a4.w;
+            y.x += tf * a4.x; y.y += tf * a4.y; y.z += tf * a4.z; y.w += tf * a4.w;
         }
         y.x *= sc; y.y *= sc; y.z *= sc; y.w *= sc;
         if (act == SENSEI_ACT_RELU) {
@@ -730,7 +735,7 @@ __global__ void k_tiles_combine(float *__restrict__ C, long long n_rows, int f_s
         if (col + e < f_store) {
             float y = dst[e];
             for (long long c = c_first; c <= c_last; ++c) y += carry[(size_t)c * f_carry + col + e];
-            y = (y + (add ? add[e] : 0.f)) * sc;
+            y = (y + (add ? tf * add[e] : 0.f)) * sc;
             if (act == SENSEI_ACT_RELU) y = y > 0.f ? y : 0.f;
             dst[e] = y;
         }
@@ -742,7 +747,7 @@ __global__ void k_tiles_combine(float *__restrict__ C, long long n_rows, int f_s
 __global__ void k_tiles_combine_pm(float *__restrict__ C, long long n_rows, int f_store, long long ldc, long long c_tile, const float *__restrict__ Dh,
                                    int f, const int32_t *__restrict__ rank_r, int n_ranks, const float *__restrict__ r, const float2 *__restrict__ mz,
                                    int act, int vec4, const float *__restrict__ part, int n_panels, const int32_t *__restrict__ seg_ptr, int chunk_nnz,
-                                   const float *__restrict__ carry, int f_carry) {
+                                   const float *__restrict__ carry, int f_carry, const float *__restrict__ tile_shift) {
     const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     const int f4 = (f_store + 3) / 4;
     if (t >= n_rows * f4) return;
@@ -767,8 +772,10 @@ __global__ void k_tiles_combine_pm(float *__restrict__ C, long long n_rows, int 
         }
     }
     if (rank < n_ranks) {
+        float tf = 1.f;   // see k_tiles_combine
+        if (tile_shift) { const float ts = tile_shift[rank]; tf = ts > -INFINITY ? __expf(ts - mz[i].x) : 0.f; }
         const float4 a4 = *reinterpret_cast<const float4 *>(Dh + (size_t)rank * f + col);
-        y.x += a4.x; y.y += a4.y; y.z += a4.z; y.w += a4.w;
+        y.x += tf * a4.x; y.y += tf * a4.y; y.z += tf * a4.z; y.w += tf * a4.w;
     }
     y.x *= sc; y.y *= sc; y.z *= sc; y.w *= sc;
     if (act == SENSEI_ACT_RELU) {
@@ -953,6 +960,16 @@ __global__ void k_tile_stats_merge(float2 *__restrict__ stats, long long n_rows,
         a.x = mm;
     }
     stats[i] = a;
+}
+
+// m_rank[q] = the largest logit among the tile entries of the row of rank q (-inf: none): the shift the attention tiles can use before
+// the row maxima over all entries are known
+__global__ void k_tile_row_max(const int32_t *__restrict__ rt_seg, const float2 *__restrict__ seg_stats, int n_ranks, float *__restrict__ m_rank) {
+    const int q = blockIdx.x * blockDim.x + threadIdx.x;
+    if (q >= n_ranks) return;
+    float m = -INFINITY;
+    for (int seg = rt_seg[q >> 7]; seg < rt_seg[(q >> 7) + 1]; ++seg) { const float v = seg_stats[(size_t)seg * 128 + (q & 127)].x; m = v > m ? v : m; }
+    m_rank[q] = m;
 }
 
 // the same for the tiles of the transposed pattern: its rows are the sources (s_r), its columns the destinations (s_l and their maxima)
@@ -1402,8 +1419,10 @@ static void launch_attn_tiles(const DenseTilesAttnArgs &a, int n_seg, int nb_cou
 }
 
 // f: a multiple of 32.  Bh: room for 6 bytes per (rank, column).
+// local_shift (attention on the pattern itself): launch_tile_stats has run on this stream - the vectors are in rank order and the shift of a
+// row is the maximum over its tile entries, so the call needs no row statistics; the join rescales (tile_shift of the combine launchers)
 hipError_t launch_dense_tiles(const TileSplit &T, const float *B_sliced, int64_t n_cols, int f, float *Bh, hipStream_t s, const float *s_l,
-                              const float *s_r, const float2 *mz, float slope, bool transposed, bool gathered) {
+                              const float *s_r, const float2 *mz, float slope, bool transposed, bool gathered, bool local_shift) {
     if (T.n_slots <= 0 || f <= 0) return hipSuccess;
     const long long n_ranks = (long long)T.nt_c * 128;
     unsigned short *Bq = reinterpret_cast<unsigned short *>(Bh);
@@ -1431,8 +1450,9 @@ hipError_t launch_dense_tiles(const TileSplit &T, const float *B_sliced, int64_t
             launch_attn_tiles<kTilesAttnT>(g, T.n_seg, nb_count, s);
         } else {
             g.u_rank = T.rank_vec; g.m_rank = T.rank_vec + n_r; g.v_rank = T.rank_vec + 2 * n_r; g.mc_rank = nullptr;
-            hipLaunchKernelGGL(k_gather_ranked_vecs, vgrid, dim3(256), 0, s, s_l, s_r, mz, T.order_r, n_r, T.order_c, n_c, T.rank_vec,
-                               T.rank_vec + n_r, T.rank_vec + 2 * n_r);
+            if (!local_shift)
+                hipLaunchKernelGGL(k_gather_ranked_vecs, vgrid, dim3(256), 0, s, s_l, s_r, mz, T.order_r, n_r, T.order_c, n_c, T.rank_vec,
+                                   T.rank_vec + n_r, T.rank_vec + 2 * n_r);
             launch_attn_tiles<kTilesAttn>(g, T.n_seg, nb_count, s);
         }
     }
@@ -1448,6 +1468,7 @@ hipError_t launch_tile_stats(const TileSplit &T, const float *s_l, const float *
                        T.order_r, n_r, T.order_c, n_c, T.rank_vec, T.rank_vec + n_r, T.rank_vec + 2 * n_r);
     hipLaunchKernelGGL(k_tile_stats, dim3((unsigned)T.n_seg), dim3(256), 0, s, T.bits, T.seg_first, T.slot_ct, T.seg_rt, (const float *)T.rank_vec,
                        (const float *)(T.rank_vec + 2 * n_r), slope, T.seg_stats);
+    hipLaunchKernelGGL(k_tile_row_max, dim3((unsigned)((n_r + 255) / 256)), dim3(256), 0, s, T.rt_seg, (const float2 *)T.seg_stats, n_r, T.rank_vec + n_r);
     return hipGetLastError();
 }
 
@@ -1469,7 +1490,8 @@ hipError_t launch_tiles_sddmm(const TileSplit &T, const float *L_sliced, int64_t
 }
 
 hipError_t launch_tiles_combine(const TileSplit &T, float *C, int64_t n_rows, int f_store, int64_t ldc, bool c_sliced, int f, const float *r,
-                                const float2 *mz, int act, hipStream_t s, const int32_t *row_ptr_rem, int chunk_nnz, const float *carry, int f_carry) {
+                                const float2 *mz, int act, hipStream_t s, const int32_t *row_ptr_rem, int chunk_nnz, const float *carry, int f_carry,
+                                const float *tile_shift) {
     if (n_rows <= 0 || f_store <= 0) return hipSuccess;
     const long long threads = (long long)n_rows * ((f_store + 3) / 4);
     // T.dh rows are f floats, f a multiple of 32; carry slots are f_carry floats apart
@@ -1478,13 +1500,13 @@ hipError_t launch_tiles_combine(const TileSplit &T, float *C, int64_t n_rows, in
     if (!carry || chunk_nnz <= 0) row_ptr_rem = nullptr;
     hipLaunchKernelGGL(k_tiles_combine, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, C, (long long)n_rows, f_store,
                        c_sliced ? 32LL : (long long)ldc, c_sliced ? (long long)n_rows * 32 : 32LL, (const float *)T.dh, f, T.rank_r, T.nt_r * 128, r, mz,
-                       act, vec4, row_ptr_rem, chunk_nnz, carry, f_carry);
+                       act, vec4, row_ptr_rem, chunk_nnz, carry, f_carry, mz ? tile_shift : nullptr);
     return hipGetLastError();
 }
 
 hipError_t launch_tiles_combine_pm(const TileSplit &T, float *C, int64_t n_rows, int f_store, int64_t ldc, bool c_sliced, int f, const float *r,
                                    const float2 *mz, int act, hipStream_t s, const float *part, int n_panels, const int32_t *seg_ptr, int chunk_nnz,
-                                   const float *carry, int f_carry) {
+                                   const float *carry, int f_carry, const float *tile_shift) {
     if (n_rows <= 0 || f_store <= 0) return hipSuccess;
     if (f % 32 != 0 || f_carry % 4 != 0 || reinterpret_cast<uintptr_t>(part) % 16 != 0 || reinterpret_cast<uintptr_t>(carry) % 16 != 0 || chunk_nnz <= 0)
         return hipErrorInvalidValue;
@@ -1492,7 +1514,7 @@ hipError_t launch_tiles_combine_pm(const TileSplit &T, float *C, int64_t n_rows,
     const int vec4 = (reinterpret_cast<uintptr_t>(C) % 16 == 0 && (c_sliced || ldc % 4 == 0)) ? 1 : 0;
     hipLaunchKernelGGL(k_tiles_combine_pm, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, C, (long long)n_rows, f_store,
                        c_sliced ? 32LL : (long long)ldc, c_sliced ? (long long)n_rows * 32 : 32LL, (const float *)T.dh, f, T.rank_r, T.nt_r * 128, r, mz,
-                       act, vec4, part, n_panels, seg_ptr, chunk_nnz, carry, f_carry);
+                       act, vec4, part, n_panels, seg_ptr, chunk_nnz, carry, f_carry, mz ? tile_shift : nullptr);
     return hipGetLastError();
 }
 

@@ -202,7 +202,10 @@ hipError_t launch_compact_values(int64_t nnz, const int32_t *dst_rem, const floa
 // exp(LeakyReLU(s_l[i] + s_r[j]) - mz[i].x) / mz[i].y, the complete coefficient alpha_ij (the division is applied to the rows of B).
 hipError_t launch_dense_tiles(const TileSplit &T, const float *B_sliced, int64_t n_cols, int f, float *Bh, hipStream_t s,
                               const float *s_l = nullptr, const float *s_r = nullptr, const float2 *mz = nullptr, float slope = 0.f,
-                              bool transposed = false, bool gathered = false);
+                              bool transposed = false, bool gathered = false, bool local_shift = false);
+// local_shift (attention on the pattern itself, after launch_tile_stats on the same stream): the shift of a row is the maximum over its
+// tile entries (T.rank_vec + 128 T.nt_r, by row rank), so the tiles can be multiplied before the row statistics of the whole pattern exist;
+// the join then rescales their product (tile_shift of the combine launchers).
 // the first step of launch_dense_tiles on its own: Bh = rows of B in rank order.  A caller that has other work to wait for can run it
 // early and pass gathered = true afterwards (not for the transposed mode, whose rows are scaled while they are gathered).
 hipError_t launch_tiles_gather(const TileSplit &T, const float *B_sliced, int64_t n_cols, int f, float *Bh, hipStream_t s);
@@ -219,14 +222,14 @@ hipError_t launch_tiles_sddmm(const TileSplit &T, const float *L_sliced, int64_t
 // C = act(scale (C + T.dh[rank of the row])) over all rows; scale_i = 1 / mz[i].y if mz, else r[i] if r, else 1
 hipError_t launch_tiles_combine(const TileSplit &T, float *C, int64_t n_rows, int f_store, int64_t ldc, bool c_sliced, int f, const float *r,
                                 const float2 *mz, int act, hipStream_t s, const int32_t *row_ptr_rem = nullptr, int chunk_nnz = 0,
-                                const float *carry = nullptr, int f_carry = 0);
+                                const float *carry = nullptr, int f_carry = 0, const float *tile_shift = nullptr);
 // row_ptr_rem, chunk_nnz, carry, f_carry: when the SpMM over the remainder ran with defer_fixup, this pass also adds the carry slots
 // (f_carry floats each) of the rows that span chunk boundaries, in chunk order, before anything else.
 // The same join when the remainder ran panel-major (its SpMM left one raw partial row per segment (panel q, row i) in `part`,
 // slice-major over n_panels * n_rows rows of f floats, fix-up deferred): C = act(scale (sum_q part[q, i] + carries + T.dh[rank])).
 hipError_t launch_tiles_combine_pm(const TileSplit &T, float *C, int64_t n_rows, int f_store, int64_t ldc, bool c_sliced, int f, const float *r,
                                    const float2 *mz, int act, hipStream_t s, const float *part, int n_panels, const int32_t *seg_ptr, int chunk_nnz,
-                                   const float *carry, int f_carry);
+                                   const float *carry, int f_carry, const float *tile_shift = nullptr);
 
 // ---- dense
 // Y[0:n, 0:m_store) = act(row_scale[i] * (A[n x k] . W[k x m])); columns m..m_store are written as act(0);
