@@ -299,7 +299,7 @@ int sensei_dotgat_layer(sensei_ctx *ctx, const sensei_csr *A, sensei_mat X, sens
  * summation.  Whether the split pays depends on the graph: attach it when a good part of the entries lies in kept tiles
  * (sensei_tiles_info; measured: 64 % of the entries: SpMM call -44 %; 20 %: +2 %, so leave it off there).
  * min_density: 0 < min_density <= 1; 0.05 .. 0.09 measured best on a
- * 233,000-node power-law graph (0.07: 64 % of the entries in 22,334 tiles, step time 16.9 -> 9.8 ms).
+ * 233,000-node power-law graph (0.07: 64 % of the entries in 22,334 tiles, step time 16.9 -> 9.65 ms).
  *   sensei_tiles_bytes   device bytes sensei_tiles_create needs (an upper bound taken before the tiles are counted);
  *   sensei_tiles_create  builds the split in device_buf (256-byte aligned, caller-owned, must outlive the object);
  *                        ranks the nodes on the host, so it synchronises the stream several times: a set-up call;
