@@ -953,14 +953,24 @@ int run_gat_backward(const sensei_csr &A, const sensei_csr &At, const int32_t *t
         // the remainder of the transposed pattern with its coefficients copied into its own order; the tiles' share was started above
         const sensei_tiles &D = *At.tiles;
         float *alpha_rem = cv.take<float>((size_t)(D.nnz_rem > 0 ? D.nnz_rem : 1));
-        SENSEI_TRY(launch_compact_values(At.nnz, D.dst_rem, reinterpret_cast<const float *>(adt_t), 2, alpha_rem, s));
+        const bool pm = remainder_panels_usable(D, f_out);   // the panel-major copy of the remainder, as in the forward aggregation
+        SENSEI_TRY(launch_compact_values(At.nnz, D.dst_rem, reinterpret_cast<const float *>(adt_t), 2, alpha_rem, s, pm ? D.pos_pm : nullptr));
         sensei_csr Ar = At;
         Ar.nnz = D.nnz_rem; Ar.row_ptr = D.row_ptr_rem; Ar.col_idx = D.col_rem; Ar.val = alpha_rem; Ar.panels = nullptr; Ar.tiles = nullptr;
-        SENSEI_TRY(launch_spmm(Ar, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, T, fo32, f_out, dTheta, fo4, f_out, SENSEI_ACT_NONE, D.plan_rem, carry, s,
-                               nullptr, false, false, nullptr, true, 1, false, true));
-        SENSEI_TRY(hipStreamWaitEvent(s, D.ev_join, 0));
-        SENSEI_TRY(launch_tiles_combine(D.T, dTheta, At.n_rows, f_out, fo4, false, fo32, nullptr, nullptr, SENSEI_ACT_NONE, s, D.row_ptr_rem,
-                                        D.plan_rem.chunk_nnz, carry, fo32));
+        if (pm) {
+            Ar.n_rows = D.rem_panels * At.n_rows; Ar.row_ptr = D.seg_ptr; Ar.col_idx = D.col_pm;
+            SENSEI_TRY(launch_spmm(Ar, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, T, fo32, fo32, D.part_pm, 32, fo32, SENSEI_ACT_NONE, D.plan_pm, carry, s,
+                                   nullptr, false, false, nullptr, true, 1, true, true));
+            SENSEI_TRY(hipStreamWaitEvent(s, D.ev_join, 0));
+            SENSEI_TRY(launch_tiles_combine_pm(D.T, dTheta, At.n_rows, f_out, fo4, false, fo32, nullptr, nullptr, SENSEI_ACT_NONE, s, D.part_pm,
+                                               D.rem_panels, D.seg_ptr, D.plan_pm.chunk_nnz, carry, fo32));
+        } else {
+            SENSEI_TRY(launch_spmm(Ar, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, T, fo32, f_out, dTheta, fo4, f_out, SENSEI_ACT_NONE, D.plan_rem, carry, s,
+                                   nullptr, false, false, nullptr, true, 1, false, true));
+            SENSEI_TRY(hipStreamWaitEvent(s, D.ev_join, 0));
+            SENSEI_TRY(launch_tiles_combine(D.T, dTheta, At.n_rows, f_out, fo4, false, fo32, nullptr, nullptr, SENSEI_ACT_NONE, s, D.row_ptr_rem,
+                                            D.plan_rem.chunk_nnz, carry, fo32));
+        }
     } else {
         sensei_csr Aw = At;
         Aw.val = reinterpret_cast<const float *>(adt_t);

@@ -194,7 +194,8 @@ hipError_t launch_tile_split(const sensei_csr &A, const ChunkPlan &p, const int3
                              int32_t *dst_rem, int32_t *row_ptr_rem, hipStream_t s);
 hipError_t launch_zero_matrix(float *C, int64_t n, int f, int64_t ldc, bool sliced, hipStream_t s);
 // out[dst_rem[k]] = src[k * stride] for the entries k of the pattern that stay in the sparse remainder (dst_rem[k] >= 0)
-hipError_t launch_compact_values(int64_t nnz, const int32_t *dst_rem, const float *src, int stride, float *out, hipStream_t s);
+hipError_t launch_compact_values(int64_t nnz, const int32_t *dst_rem, const float *src, int stride, float *out, hipStream_t s,
+                                 const int32_t *place = nullptr);
 // T.dh[rank, 0:f) = (kept tiles of the rank's row of tiles) . B, raw sums; B slice-major with f (a multiple of 32) columns;
 // Bh: nt_c * 128 * f floats.  With s_l, s_r, mz (attention mode) entry (i, j) of a tile weighs
 // exp(LeakyReLU(s_l[i] + s_r[j]) - mz[i].x) instead of 1.  `transposed` (attention mode only): T holds the tiles of the transposed

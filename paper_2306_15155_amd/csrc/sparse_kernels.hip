@@ -1119,13 +1119,14 @@ __global__ __launch_bounds__(kBlock) void k_rem_scatter(NnzArgs a, const int32_t
     }
 }
 
-// values of the entries that stay sparse, moved from the order of the pattern to the order of the remainder
+// values of the entries that stay sparse, moved from the order of the pattern to the order of the remainder (place: to the place of
+// every remainder entry in another order of the remainder, its panel-major copy)
 __global__ __launch_bounds__(kBlock) void k_compact_values(long long nnz, const int32_t *__restrict__ dst_rem, const float *__restrict__ src, int stride,
-                                                            float *__restrict__ out) {
+                                                            float *__restrict__ out, const int32_t *__restrict__ place) {
     const long long k = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (k >= nnz) return;
     const int d = dst_rem[k];
-    if (d >= 0) out[d] = src[k * stride];
+    if (d >= 0) out[place ? place[d] : d] = src[k * stride];
 }
 
 __global__ void k_rem_rowptr(const int32_t *__restrict__ row_ptr, int n_rows, const int32_t *__restrict__ pos, int32_t *__restrict__ row_ptr_rem) {
@@ -1992,9 +1993,9 @@ hipError_t launch_tile_split(const sensei_csr &A, const ChunkPlan &p, const int3
     return hipGetLastError();
 }
 
-hipError_t launch_compact_values(int64_t nnz, const int32_t *dst_rem, const float *src, int stride, float *out, hipStream_t s) {
+hipError_t launch_compact_values(int64_t nnz, const int32_t *dst_rem, const float *src, int stride, float *out, hipStream_t s, const int32_t *place) {
     if (nnz <= 0) return hipSuccess;
-    hipLaunchKernelGGL(k_compact_values, dim3(blocks_for(nnz, kBlock)), dim3(kBlock), 0, s, (long long)nnz, dst_rem, src, stride, out);
+    hipLaunchKernelGGL(k_compact_values, dim3(blocks_for(nnz, kBlock)), dim3(kBlock), 0, s, (long long)nnz, dst_rem, src, stride, out, place);
     return hipGetLastError();
 }
 
