@@ -542,6 +542,43 @@ __global__ void k_deg_col(const int32_t *__restrict__ col_idx, long long nnz, in
     if (k < nnz) atomicAdd(&deg_col[col_idx[k]], 1);  // integer atomics: the result is exact in any order
 }
 
+// The same count for patterns whose columns fit a few LDS-sized ranges: a workgroup counts the entries of one share of the
+// pattern that fall into one range of kDegRange columns in LDS and adds its non-zero counters to deg_col at the end, so the
+// global atomics number (shares x columns) instead of one per entry, and the columns that every row refers to no longer
+// serialise them.  Workgroup number -> (share, range): the ranges of one share run on one XCD at about the same time
+// (workgroups are dealt round-robin to the eight XCDs), so a share is read from memory once and from that L2 afterwards.
+constexpr int kDegRange = 32768, kDegThreads = 1024, kDegRangesMax = 16;
+
+__global__ __launch_bounds__(kDegThreads) void k_deg_col_ranges(const int32_t *__restrict__ col_idx, long long nnz, int n_cols, int n_ranges,
+                                                                long long per_share, int32_t *__restrict__ deg_col) {
+    __shared__ int32_t cnt[kDegRange];
+    const int g = blockIdx.x >> 3;
+    const int range = g % n_ranges, share = (g / n_ranges) * 8 + (blockIdx.x & 7);
+    const int lo_col = range * kDegRange;
+    for (int d = threadIdx.x; d < kDegRange; d += kDegThreads) cnt[d] = 0;
+    __syncthreads();
+    const long long k0 = share * per_share, k1 = k0 + per_share < nnz ? k0 + per_share : nnz;
+    long long k = k0 + threadIdx.x;
+    for (; k + 3 * kDegThreads < k1; k += 4 * kDegThreads) {
+        unsigned d[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) d[u] = (unsigned)(col_idx[k + u * kDegThreads] - lo_col);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (d[u] < (unsigned)kDegRange) atomicAdd(&cnt[d[u]], 1);
+    }
+    for (; k < k1; k += kDegThreads) {
+        const unsigned d = (unsigned)(col_idx[k] - lo_col);
+        if (d < (unsigned)kDegRange) atomicAdd(&cnt[d], 1);
+    }
+    __syncthreads();
+    const int width = n_cols - lo_col < kDegRange ? n_cols - lo_col : kDegRange;
+    for (int d = threadIdx.x; d < width; d += kDegThreads) {
+        const int32_t c = cnt[d];
+        if (c) atomicAdd(&deg_col[lo_col + d], c);
+    }
+}
+
 __global__ void k_norm_vec(const int32_t *__restrict__ deg, long long n, float *__restrict__ out) {
     long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (t < n) {
@@ -1706,7 +1743,16 @@ hipError_t launch_spmm(const sensei_csr &A, int mode, const float *r, const floa
 hipError_t launch_degrees(const sensei_csr &A, int32_t *deg_row, int32_t *deg_col, hipStream_t s) {
     if (A.n_rows > 0) hipLaunchKernelGGL(k_deg_row, dim3(blocks_for(A.n_rows, kBlock)), dim3(kBlock), 0, s, A.row_ptr, A.n_rows, deg_row);
     if (A.n_cols > 0) hipLaunchKernelGGL(k_fill_i32, dim3(blocks_for(A.n_cols, kBlock)), dim3(kBlock), 0, s, deg_col, (long long)A.n_cols, 0);
-    if (A.nnz > 0) hipLaunchKernelGGL(k_deg_col, dim3(blocks_for(A.nnz, kBlock)), dim3(kBlock), 0, s, A.col_idx, (long long)A.nnz, deg_col);
+    const int n_ranges = (int)((A.n_cols + kDegRange - 1) / kDegRange);
+    if (A.nnz >= (1 << 18) && n_ranges <= kDegRangesMax) {
+        int shares = 256 / n_ranges / 8 * 8;  // about one workgroup per compute unit, a multiple of eight shares
+        if (shares < 8) shares = 8;
+        const long long per_share = (A.nnz + shares - 1) / shares;
+        hipLaunchKernelGGL(k_deg_col_ranges, dim3(shares * n_ranges), dim3(kDegThreads), 0, s, A.col_idx, (long long)A.nnz, (int)A.n_cols, n_ranges,
+                           per_share, deg_col);
+    } else if (A.nnz > 0) {
+        hipLaunchKernelGGL(k_deg_col, dim3(blocks_for(A.nnz, kBlock)), dim3(kBlock), 0, s, A.col_idx, (long long)A.nnz, deg_col);
+    }
     return hipGetLastError();
 }
 

@@ -52,6 +52,25 @@ def test_degrees_bit_exact(ctx, name):
     assert dc.cpu().numpy().tobytes() == want_c.tobytes()
 
 
+@pytest.mark.parametrize("n_cols", [32_768, 32_769, 100_000, 16 * 32_768, 16 * 32_768 + 1])
+def test_column_degrees_over_ranges_of_columns(ctx, n_cols):
+    """From 2^18 entries on, patterns of up to 16 x 32,768 columns are counted range by range in LDS; wider ones and smaller ones
+    take one global atomic per entry.  Both sides of each limit, a ragged last range, one column that every row refers to."""
+    for per_row, want_ranges in ((100, True), (60, False)):
+        g = rect_block(21, 3000, n_cols, per_row)
+        u = np.repeat(np.arange(g.n_rows), np.diff(g.row_ptr))
+        v = g.col_idx.astype(np.int64)
+        extra = np.arange(g.n_rows)
+        g = synth.build_csr(g.n_rows, n_cols, np.concatenate([u, extra]), np.concatenate([v, np.full(g.n_rows, n_cols - 1)]), False, False)
+        assert (g.nnz >= (1 << 18)) == want_ranges
+        A = DeviceCSR(g)
+        dr, dc = ctx.degrees(A.s)
+        want_r, want_c = oracle.degrees(g.n_rows, g.n_cols, g.row_ptr, g.col_idx)
+        assert want_c[n_cols - 1] == g.n_rows
+        assert dr.cpu().numpy().tobytes() == want_r.tobytes()
+        assert dc.cpu().numpy().tobytes() == want_c.tobytes()
+
+
 def test_norm_vectors(ctx):
     deg = np.array([0, 1, 2, 3, 4, 7, 100, 109_603, 2_000_000], dtype=np.int32)
     got = ctx.norm_vectors(dev(deg)).cpu().numpy()
