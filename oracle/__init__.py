@@ -262,6 +262,40 @@ def tagcn_layer(n, row_ptr, col_idx, X, W, k_hops, act=0):
     return activation(Y, act)
 
 
+def tagcn_backward(n, row_ptr, col_idx, X, W, k_hops, dY, Y=None, act=0, rows=None):
+    """Gradient of sum(dY * Y) for the TAGCN layer Y = act(sum_k A^^k X W_k) (chain rule on tagcn_layer, term by term) -> (dX, dW):
+    dP = dY (.) [Y > 0] (the fp32 forward output ``Y`` supplies the ReLU mask); term k is H_k W_k with H_k = A^^k X, so
+    dW_k = H_k^T dP (stacked by rows like W) and the term's share of dX is dP W_k^T carried back through its k propagations,
+    (A^^T)^k (dP W_k^T).  A^^T is written out as the transposed pattern with the same entry weights r_i c_j.  ``rows`` selects
+    rows of dX."""
+    row_ptr, col_idx = _i32(row_ptr), _i32(col_idx)
+    dr, dc = degrees(n, n, row_ptr, col_idx)
+    r, c = inv_sqrt_deg(dr), inv_sqrt_deg(dc)
+    val = sddmm_mul(row_ptr, col_idx, None, r, c)                      # A^[i, j] = r_i c_j on the pattern
+    src = np.repeat(np.arange(n, dtype=np.int32), np.diff(row_ptr))    # row of every stored entry
+    order = np.lexsort((src, col_idx))                                 # the same entries by (column, row): rows of the transpose
+    t_ptr = np.concatenate([[0], np.cumsum(np.bincount(col_idx, minlength=n))]).astype(np.int32)
+    t_idx, t_val = src[order], val[order]
+    W64 = _f32(W).astype(np.float64)
+    H = _f32(X).astype(np.float64)
+    f_in = H.shape[1]
+    assert W64.shape[0] == (k_hops + 1) * f_in
+    dP = _f32(dY).astype(np.float64)
+    if act == 1:
+        dP = dP * (_f32(Y) > 0)
+    dW = np.zeros_like(W64)
+    dX = np.zeros_like(H)
+    for k in range(k_hops + 1):
+        if k > 0:
+            H = row_broadcast(r, spmm(row_ptr, col_idx, None, row_broadcast(c, H)))     # H_k = A^ H_(k-1)
+        dW[k * f_in:(k + 1) * f_in] = gemm(np.ascontiguousarray(H.T), dP)
+        M = gemm(dP, np.ascontiguousarray(W64[k * f_in:(k + 1) * f_in].T))
+        for _ in range(k):
+            M = spmm(t_ptr, t_idx, t_val, M)
+        dX = dX + M
+    return (dX if rows is None else dX[np.asarray(rows, dtype=np.int64)]), dW
+
+
 def gatv2_layer(n_rows, n_cols, row_ptr, col_idx, X, W_l, W_r, att, slope=0.2, act=0, rows=None):
     """GATv2 layer: Theta_l = X W_l (destinations = the first n_rows sources), Theta_r = X W_r,
     e_ij = att . LeakyReLU(Theta_l[i] + Theta_r[j]) on the stored entries (Eq. 2 with a vector per entry), alpha = row

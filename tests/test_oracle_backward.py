@@ -271,3 +271,65 @@ def test_sgc_backward_special_cases():
     dXs, dWs = oracle.sgc_backward(20, gs.row_ptr, gs.col_idx, X, W, 4, dY)
     _close(dXs, dY.astype(np.float64) @ W.astype(np.float64).T, 1e-13)
     _close(dWs, X.astype(np.float64).T @ dY.astype(np.float64), 1e-13)
+
+
+# ------------------------------------------------------------------ K-hop layer with a weight block per hop (TAGCN)
+
+@pytest.mark.parametrize("k_hops", [0, 1, 2, 3])
+def test_tagcn_backward_is_the_gradient_of_the_forward(k_hops):
+    rng = np.random.default_rng(60 + k_hops)
+    u = rng.integers(0, 12, size=26)
+    v = rng.integers(0, 12, size=26)
+    g = synth.build_csr(12, 12, u, v, False, True)      # not symmetric: the transposed operator really is another matrix
+    f_in, f_out = 4, 3
+    X, W, dY = _grid(rng, (12, f_in)), _grid(rng, ((k_hops + 1) * f_in, f_out)), _grid(rng, (12, f_out))
+
+    def loss():
+        return float(np.sum(dY.astype(np.float64) * oracle.tagcn_layer(12, g.row_ptr, g.col_idx, X, W, k_hops, 0)))
+
+    dX, dW = oracle.tagcn_backward(12, g.row_ptr, g.col_idx, X, W, k_hops, dY)
+    _close(dX, _central(loss, X, 2.0 ** -8), 1e-9)      # the layer is linear in X and in W: central differences are exact
+    _close(dW, _central(loss, W, 2.0 ** -8), 1e-9)
+    rows = np.array([7, 0, 3])
+    _close(oracle.tagcn_backward(12, g.row_ptr, g.col_idx, X, W, k_hops, dY, rows=rows)[0], dX[rows], 1e-14)
+
+
+def test_tagcn_backward_special_cases():
+    rng = np.random.default_rng(64)
+    g = synth.build_csr(20, 20, rng.integers(0, 20, size=60), rng.integers(0, 20, size=60), False, True)   # not symmetric
+    f_in, f_out, K = 5, 6, 3
+    X, dY = _grid(rng, (20, f_in)), _grid(rng, (20, f_out))
+    W = _grid(rng, ((K + 1) * f_in, f_out))
+    X64, dY64 = X.astype(np.float64), dY.astype(np.float64)
+    # no hops: a dense layer
+    dX0, dW0 = oracle.tagcn_backward(20, g.row_ptr, g.col_idx, X, W[:f_in], 0, dY)
+    _close(dX0, dY64 @ W[:f_in].astype(np.float64).T, 1e-13)
+    _close(dW0, X64.T @ dY64, 1e-13)
+    # only the last block non-zero: dX and that block's dW are those of the K-hop layer without per-hop weights
+    Wl = np.zeros_like(W)
+    Wl[K * f_in:] = W[K * f_in:]
+    dXl, dWl = oracle.tagcn_backward(20, g.row_ptr, g.col_idx, X, Wl, K, dY)
+    dXs, dWs = oracle.sgc_backward(20, g.row_ptr, g.col_idx, X, W[K * f_in:], K, dY)
+    _close(dXl, dXs, 1e-13)
+    _close(dWl[K * f_in:], dWs, 1e-13)
+    # dense algebra with the ReLU mask of the forward output: dW_k = (A^^k X)^T dP, dX = sum_k (A^^T)^k dP W_k^T
+    A = dense.dense_pattern(20, 20, g.row_ptr, g.col_idx)
+    Ahat = A / np.sqrt(np.outer(A.sum(axis=1), A.sum(axis=0)))
+    Y = oracle.tagcn_layer(20, g.row_ptr, g.col_idx, X, W, K, 1).astype(np.float32)
+    assert (Y > 0).any() and (Y == 0).any()
+    dP = dY64 * (Y > 0)
+    dX, dW = oracle.tagcn_backward(20, g.row_ptr, g.col_idx, X, W, K, dY, Y=Y, act=1)
+    want_dx = np.zeros((20, f_in))
+    for k in range(K + 1):
+        Wk = W[k * f_in:(k + 1) * f_in].astype(np.float64)
+        _close(dW[k * f_in:(k + 1) * f_in], (np.linalg.matrix_power(Ahat, k) @ X64).T @ dP, 1e-12)
+        want_dx += np.linalg.matrix_power(Ahat.T, k) @ dP @ Wk.T
+    _close(dX, want_dx, 1e-12)
+    assert np.abs(Ahat - Ahat.T).max() > 1e-3     # a transposed operand would show
+    # self loops only: A^ = I, every hop sees X itself
+    gs = synth.self_loops_only(20)
+    dXi, dWi = oracle.tagcn_backward(20, gs.row_ptr, gs.col_idx, X, W, K, dY)
+    Wsum = sum(W[k * f_in:(k + 1) * f_in].astype(np.float64) for k in range(K + 1))
+    _close(dXi, dY64 @ Wsum.T, 1e-13)
+    for k in range(K + 1):
+        _close(dWi[k * f_in:(k + 1) * f_in], X64.T @ dY64, 1e-13)
