@@ -651,7 +651,11 @@ def headline(args):
             tmp_out = torch.empty_like(outs[i])
             tag2[tag(i)] = {nm: round(time_fn(lambda: ctx.tagcn_layer(A, r, c, src_of(i), W3, 2, cid, L["act"], out=tmp_out), 2), 4)
                             for cid, nm in ((0, "AGG"), (1, "UPD"))}
-            del W3, tmp_out
+            dYt = torch.randn((N, L["f_out"]), device=dev)
+            for bid, nm in ((0, "BWD_AGG"), (1, "BWD_UPD")):
+                tag2[tag(i)][nm] = round(time_fn(lambda: ctx.tagcn_backward(A, A, r, c, src_of(i), W3, 2, dYt, bid, Y=outs[i] if L["act"] else None,
+                                                                           activation=L["act"]), 2), 4)
+            del W3, tmp_out, dYt
         detail["tagcn_2hop_ms"] = tag2
 
     # ---- GATv2 on the shapes of the GAT layers (separate W_l and W_r): reuse and recompute

@@ -376,6 +376,22 @@ int sensei_sgc_backward(sensei_ctx *ctx, const sensei_csr *A, const sensei_csr *
                         int k_hops, const float *Y, int64_t ldy, sensei_mat dY, int activation, float *dX, int64_t lddx, float *dW, int64_t lddw,
                         int bwd_id, void *workspace, size_t ws_bytes, void *stream);
 
+/* Backward of the layer sensei_tagcn_layer, Y = act( sum_{k=0..K} A^^k X W_k ) on a square pattern (the K-hop variant with a weight
+ * block per hop, among the further GNN variants the paper's discussion names; training as in its evaluation section): with
+ * dP = dY (.) [Y > 0],   dW_k = (A^^k X)^T dP = X^T (A^^T)^k dP   (stacked by rows like W)   and   dX = sum_k (A^^T)^k dP W_k^T
+ * (skipped when dX is NULL).  The two ways of writing dW_k are the two associations:
+ *     SENSEI_GCN_BWD_AGG: the gradient goes through the hops at width f_out, Q_k = A^^T Q_(k-1) from Q_0 = dP (K transposed
+ *                         aggregations), dW_k = X^T Q_k, dX = [Q_0 .. Q_K] [W_0^T; ..; W_K^T] as one product of depth (K+1) f_out;
+ *     SENSEI_GCN_BWD_UPD: the input goes forward at width f_in, H_k = A^^ H_(k-1) from H_0 = X (K aggregations), dW_k = H_k^T dP,
+ *                         and dX comes back in Horner form, R_K = dP W_K^T, R_k = dP W_k^T + A^^T R_(k+1), dX = R_0 (K transposed
+ *                         aggregations at width f_in).
+ * k_hops >= 0 (0: a dense layer).  W and dW: (k_hops + 1) f_in x f_out.  Other arguments, aliasing rules and error codes as for
+ * sensei_gcn_backward; with no rows dW is set to zero. */
+int sensei_tagcn_backward_workspace(const sensei_csr *A, int f_in, int f_out, int k_hops, int bwd_id, size_t *bytes);
+int sensei_tagcn_backward(sensei_ctx *ctx, const sensei_csr *A, const sensei_csr *At, const float *r, const float *c, sensei_mat X, sensei_mat W,
+                          int k_hops, const float *Y, int64_t ldy, sensei_mat dY, int activation, float *dX, int64_t lddx, float *dW, int64_t lddw,
+                          int bwd_id, void *workspace, size_t ws_bytes, void *stream);
+
 /* Which association of the GCN backward is predicted faster for this graph and these sizes (the additive
  * per-primitive cost model of sensei_select, host arithmetic only).  have_saved_u: the forward kept
  * U = D_r^(-1/2) A~ D_c^(-1/2) X; want_dx: the input gradient is needed.  est_ms: optional, 2 entries. */

@@ -31,7 +31,7 @@ EXPORTS = (
     "sensei_select", "sensei_profile_enable", "sensei_profile_read", "sensei_panels_bytes", "sensei_panels_create",
     "sensei_panels_count", "sensei_panels_destroy", "sensei_panels_set_min_width", "sensei_panels_tune_bytes",
     "sensei_panels_tune", "sensei_gcn_backward_workspace", "sensei_gcn_backward", "sensei_select_gcn_backward", "sensei_transpose_positions",
-    "sensei_gat_backward_workspace", "sensei_gat_backward", "sensei_gat_layer_heads", "sensei_sgc_workspace", "sensei_sgc_layer", "sensei_sgc_backward_workspace", "sensei_sgc_backward", "sensei_tagcn_workspace", "sensei_tagcn_layer", "sensei_gatv2_workspace", "sensei_gatv2_layer", "sensei_dotgat_workspace", "sensei_dotgat_layer", "sensei_tiles_remainder_panels", "sensei_tiles_bytes", "sensei_tiles_create", "sensei_tiles_info",
+    "sensei_gat_backward_workspace", "sensei_gat_backward", "sensei_gat_layer_heads", "sensei_sgc_workspace", "sensei_sgc_layer", "sensei_sgc_backward_workspace", "sensei_sgc_backward", "sensei_tagcn_workspace", "sensei_tagcn_layer", "sensei_tagcn_backward_workspace", "sensei_tagcn_backward", "sensei_gatv2_workspace", "sensei_gatv2_layer", "sensei_dotgat_workspace", "sensei_dotgat_layer", "sensei_tiles_remainder_panels", "sensei_tiles_bytes", "sensei_tiles_create", "sensei_tiles_info",
            "sensei_tiles_set_min_width", "sensei_tiles_destroy",
 )
 
@@ -105,6 +105,9 @@ def lib():
         L.sensei_sgc_backward.argtypes = [vp, P(CsrStruct), P(CsrStruct), vp, vp, MatStruct, MatStruct, i32, vp, i64, MatStruct, i32, vp, i64, vp, i64,
                                           i32, vp, sz, vp]
         L.sensei_tagcn_workspace.argtypes = [P(CsrStruct), i32, i32, i32, i32, P(sz)]
+        L.sensei_tagcn_backward_workspace.argtypes = [P(CsrStruct), i32, i32, i32, i32, P(sz)]
+        L.sensei_tagcn_backward.argtypes = [vp, P(CsrStruct), P(CsrStruct), vp, vp, MatStruct, MatStruct, i32, vp, i64, MatStruct, i32, vp, i64, vp, i64,
+                                            i32, vp, sz, vp]
         L.sensei_tagcn_layer.argtypes = [vp, P(CsrStruct), vp, vp, MatStruct, MatStruct, i32, vp, i64, i32, i32, vp, sz, vp]
         L.sensei_gatv2_workspace.argtypes = [P(CsrStruct), i32, i32, i32, P(sz)]
         L.sensei_gatv2_layer.argtypes = [vp, P(CsrStruct), MatStruct, MatStruct, MatStruct, vp, f32, vp, i64, i32, i32, vp, sz, vp]
@@ -488,6 +491,21 @@ class Context:
                                          mat_struct(Y).ld if Y is not None else 0, mat_struct(dY), activation, _ptr(dX),
                                          mat_struct(dX).ld if dX is not None else 0, _ptr(dW), mat_struct(dW).ld, bwd_id, self.ws.ptr,
                                          self.ws.nbytes, _stream()), "sensei_sgc_backward")
+        return dX, dW
+
+    def tagcn_backward(self, A: CsrStruct, At: CsrStruct, r, c, X, W, k_hops, dY, bwd_id, Y=None, activation=ACT_NONE, want_dx=True):
+        """Backward of tagcn_layer -> (dX or None, dW); W and dW stack the k_hops + 1 blocks by rows; ``At`` is the transposed pattern."""
+        f_in, f_out = X.size(1), W.size(1)
+        dX = torch.empty((A.n_cols, f_in), dtype=torch.float32, device=self.device) if want_dx else None
+        dW = torch.empty((W.size(0), f_out), dtype=torch.float32, device=self.device)
+        need = ctypes.c_size_t()
+        _check(lib().sensei_tagcn_backward_workspace(ctypes.byref(A), f_in, f_out, k_hops, bwd_id, ctypes.byref(need)),
+               "sensei_tagcn_backward_workspace")
+        self.ws.ensure(need.value)
+        _check(lib().sensei_tagcn_backward(self._h, ctypes.byref(A), ctypes.byref(At), _ptr(r), _ptr(c), mat_struct(X), mat_struct(W), k_hops, _ptr(Y),
+                                           mat_struct(Y).ld if Y is not None else 0, mat_struct(dY), activation, _ptr(dX),
+                                           mat_struct(dX).ld if dX is not None else 0, _ptr(dW), mat_struct(dW).ld, bwd_id, self.ws.ptr,
+                                           self.ws.nbytes, _stream()), "sensei_tagcn_backward")
         return dX, dW
 
     def tagcn_layer(self, A: CsrStruct, r, c, X, W, k_hops, comp_id, activation=ACT_NONE, out=None):

@@ -574,6 +574,105 @@ int run_gcn_backward(const sensei_csr &A, const sensei_csr &At, const float *r, 
     return SENSEI_OK;
 }
 
+// ---- backward of the TAGCN layer Y = act(sum_k A^^k X W_k): with dP = dY (.) [Y > 0],
+//   dW_k = (A^^k X)^T dP = X^T (A^^T)^k dP   and   dX = sum_k (A^^T)^k dP W_k^T.
+// The two forms of dW_k are the two associations: bwd_id AGG carries the gradient through the hops at width f_out (Q_k = (A^^T)^k dP,
+// K transposed propagations, dW_k = X^T Q_k, dX = [Q_0 .. Q_K] [W_0^T; ..; W_K^T] as one GEMM); bwd_id UPD carries the input forward at
+// width f_in (H_k = A^^k X, K propagations, dW_k = H_k^T dP) and dX back in Horner form, R_K = dP W_K^T, R_k = dP W_k^T + A^^T R_(k+1).
+// Between hops the operand stays slice-major with the scaling of the next gather already applied; the row-major copy of every hop's
+// result is what the weight gradient reads.
+size_t tagcn_bwd_ws(const sensei_csr &A, int f_in, int f_out, int k_hops, int id) {
+    const int fo4 = pad4(f_out), fi4 = pad4(f_in);
+    const size_t n = (size_t)A.n_rows;
+    size_t b = 2 * plan_bytes(A.nnz) + 512;
+    if (id == SENSEI_GCN_BWD_AGG) {
+        b += spmm_carry_bytes(A.nnz, pad32(f_out));
+        b += align_up(n * (size_t)(k_hops + 1) * fo4 * sizeof(float), 256);          // Q_0 .. Q_K side by side, row-major
+        b += align_up(n * pad32(f_out) * sizeof(float), 256);                        // r (x) Q_k, slice-major
+        b += align_up((size_t)(k_hops + 1) * fo4 * fi4 * sizeof(float), 256);        // W_k^T stacked
+        b += gemm_tn_bytes(A.n_rows, f_in, f_out);
+    } else {
+        b += spmm_carry_bytes(A.nnz, pad32(f_in));
+        b += align_up(n * fo4 * sizeof(float), 256);                                 // dP
+        b += align_up(n * fi4 * sizeof(float), 256);                                 // H_k, row-major
+        b += 2 * align_up(n * pad32(f_in) * sizeof(float), 256);                     // slice-major operand of a hop and its result
+        b += align_up((size_t)(k_hops + 1) * fo4 * fi4 * sizeof(float), 256);        // W_k^T, block after block
+        b += gemm_tn_bytes(A.n_rows, f_in, f_out);
+    }
+    return b;
+}
+
+int run_tagcn_backward(const sensei_csr &A, const sensei_csr &At, const float *r, const float *c, const sensei_mat &X, const sensei_mat &W,
+                       int k_hops, const float *Y, int64_t ldy, const sensei_mat &dY, int act, float *dX, int64_t lddx, float *dW, int64_t lddw,
+                       int id, void *ws, size_t ws_bytes, hipStream_t s) {
+    const int f_in = (int)X.cols, f_out = (int)W.cols;
+    const int fo4 = pad4(f_out), fi4 = pad4(f_in), fo32 = pad32(f_out), fi32 = pad32(f_in);
+    const int64_t n = A.n_rows;
+    const float *mask = (act == SENSEI_ACT_RELU) ? Y : nullptr;
+    Carver cv(ws, ws_bytes);
+    ChunkPlan plan_t = make_plan(At, cv);
+    SENSEI_TRY(launch_chunk_rows(At, plan_t, s));
+    auto w_block = [&](int k) { return W.ptr + (size_t)k * f_in * W.ld; };
+    auto dw_block = [&](int k) { return dW + (size_t)k * f_in * lddw; };
+    if (id == SENSEI_GCN_BWD_AGG) {
+        const int64_t ldq = (int64_t)(k_hops + 1) * fo4;
+        float *carry = cv.take<float>(spmm_carry_bytes(At.nnz, fo32) / sizeof(float));
+        float *Q = cv.take<float>((size_t)n * ldq);
+        float *S = cv.take<float>((size_t)n * fo32);
+        float *Wst = cv.take<float>((size_t)ldq * fi4);
+        double *part = cv.take<double>(gemm_tn_bytes(n, f_in, f_out) / sizeof(double));
+        if (fo4 != f_out) SENSEI_TRY(launch_zero_matrix(Q, n, (int)ldq, ldq, false, s));   // the pad columns enter the GEMM below
+        SENSEI_TRY(launch_row_broadcast(nullptr, dY.ptr, dY.ld, n, f_out, Q, ldq, SENSEI_ACT_NONE, s, mask, ldy));
+        for (int k = 1; k <= k_hops; ++k) {   // Q_k = c (x) (A~^T (r (x) Q_(k-1)))
+            SENSEI_TRY(launch_to_slices(r, Q + (size_t)(k - 1) * fo4, ldq, n, f_out, S, s));
+            SENSEI_TRY(spmm_any(At, SENSEI_SPMM_PATTERN, c, nullptr, S, fo32, f_out, Q + (size_t)k * fo4, ldq, f_out, SENSEI_ACT_NONE, plan_t, carry, s,
+                                nullptr, false, nullptr, true));
+        }
+        for (int k = 0; k <= k_hops; ++k)
+            SENSEI_TRY(launch_gemm_tn(X.ptr, X.ld, Q + (size_t)k * fo4, ldq, n, f_in, f_out, dw_block(k), lddw, part, s));
+        if (dX) {
+            SENSEI_TRY(launch_zero_matrix(Wst, ldq, fi4, fi4, false, s));
+            for (int k = 0; k <= k_hops; ++k) SENSEI_TRY(launch_transpose(w_block(k), W.ld, f_in, f_out, Wst + (size_t)k * fo4 * fi4, fi4, s));
+            SENSEI_TRY(launch_gemm(Q, ldq, Wst, fi4, dX, lddx, n, (int)ldq, f_in, f_in, SENSEI_ACT_NONE, s));
+        }
+        return SENSEI_OK;
+    }
+    ChunkPlan plan = make_plan(A, cv);
+    SENSEI_TRY(launch_chunk_rows(A, plan, s));
+    float *carry = cv.take<float>(spmm_carry_bytes(A.nnz, fi32) / sizeof(float));
+    float *dP = cv.take<float>((size_t)n * fo4);
+    float *H = cv.take<float>((size_t)n * fi4);
+    float *T = cv.take<float>((size_t)n * fi32), *P = cv.take<float>((size_t)n * fi32);
+    float *Wt = cv.take<float>((size_t)(k_hops + 1) * fo4 * fi4);
+    double *part = cv.take<double>(gemm_tn_bytes(n, f_in, f_out) / sizeof(double));
+    SENSEI_TRY(launch_row_broadcast(nullptr, dY.ptr, dY.ld, n, f_out, dP, fo4, SENSEI_ACT_NONE, s, mask, ldy));
+    // weight gradients, hop after hop: H_k = r (x) (A~ (c (x) H_(k-1)))
+    SENSEI_TRY(launch_gemm_tn(X.ptr, X.ld, dP, fo4, n, f_in, f_out, dw_block(0), lddw, part, s));
+    for (int k = 1; k <= k_hops; ++k) {
+        SENSEI_TRY(launch_to_slices(c, k == 1 ? X.ptr : H, k == 1 ? X.ld : fi4, n, f_in, T, s));
+        SENSEI_TRY(spmm_any(A, SENSEI_SPMM_PATTERN, r, nullptr, T, fi32, f_in, H, fi4, f_in, SENSEI_ACT_NONE, plan, carry, s, nullptr, false, nullptr,
+                            true));
+        SENSEI_TRY(launch_gemm_tn(H, fi4, dP, fo4, n, f_in, f_out, dw_block(k), lddw, part, s));
+    }
+    if (dX) {
+        for (int k = 0; k <= k_hops; ++k) SENSEI_TRY(launch_transpose(w_block(k), W.ld, f_in, f_out, Wt + (size_t)k * fo4 * fi4, fi4, s));
+        auto wt_block = [&](int k) { return Wt + (size_t)k * fo4 * fi4; };
+        if (k_hops == 0) {
+            SENSEI_TRY(launch_gemm(dP, fo4, wt_block(0), fi4, dX, lddx, n, f_out, f_in, f_in, SENSEI_ACT_NONE, s));
+        } else {
+            // T holds r (x) R_k, slice-major: what the transposed propagation gathers
+            SENSEI_TRY(launch_gemm(dP, fo4, wt_block(k_hops), fi4, T, fi32, n, f_out, f_in, fi32, SENSEI_ACT_NONE, s, r, nullptr, true));
+            for (int k = k_hops - 1; k >= 0; --k) {
+                SENSEI_TRY(spmm_any(At, SENSEI_SPMM_PATTERN, c, nullptr, T, fi32, fi32, P, fi32, fi32, SENSEI_ACT_NONE, plan_t, carry, s, nullptr, false,
+                                    nullptr, true, true));
+                if (k > 0) SENSEI_TRY(launch_gemm(dP, fo4, wt_block(k), fi4, T, fi32, n, f_out, f_in, fi32, SENSEI_ACT_NONE, s, r, nullptr, true, false, P));
+                else SENSEI_TRY(launch_gemm(dP, fo4, wt_block(0), fi4, dX, lddx, n, f_out, f_in, f_in, SENSEI_ACT_NONE, s, nullptr, nullptr, false, false, P));
+            }
+        }
+    }
+    return SENSEI_OK;
+}
+
 // n_heads > 1: W holds the heads side by side (head h = columns [h d, (h + 1) d), d = f_out / n_heads), a_l / a_r likewise,
 // Y is their concatenation; Theta = X.W is formed by one GEMM for all heads, everything after it runs head by head on the
 // head's columns (its own logits, statistics and aggregation), reusing the same buffers.
@@ -2042,6 +2141,40 @@ int sensei_sgc_backward(sensei_ctx *ctx, const sensei_csr *A, const sensei_csr *
     if (A->n_rows == 0) return SENSEI_OK;
     return run_gcn_backward(*A, *At, r, c, X, W, Y, ldy, dY, activation, nullptr, 0, dX, lddx, dW, lddw, bwd_id, workspace, ws_bytes,
                             as_stream(stream), k_hops);
+}
+
+int sensei_tagcn_backward_workspace(const sensei_csr *A, int f_in, int f_out, int k_hops, int bwd_id, size_t *bytes) {
+    if (!csr_ok(A, false) || f_in <= 0 || f_out <= 0 || k_hops < 0 || k_hops > 64 || !bytes) return SENSEI_INVALID_ARGUMENT;
+    if (bwd_id != SENSEI_GCN_BWD_AGG && bwd_id != SENSEI_GCN_BWD_UPD) return SENSEI_INVALID_COMPOSITION;
+    *bytes = tagcn_bwd_ws(*A, f_in, f_out, k_hops, bwd_id);
+    return SENSEI_OK;
+}
+
+int sensei_tagcn_backward(sensei_ctx *ctx, const sensei_csr *A, const sensei_csr *At, const float *r, const float *c, sensei_mat X, sensei_mat W,
+                          int k_hops, const float *Y, int64_t ldy, sensei_mat dY, int activation, float *dX, int64_t lddx, float *dW, int64_t lddw,
+                          int bwd_id, void *workspace, size_t ws_bytes, void *stream) {
+    if (bwd_id != SENSEI_GCN_BWD_AGG && bwd_id != SENSEI_GCN_BWD_UPD) return SENSEI_INVALID_COMPOSITION;
+    if (!ctx || !csr_ok(A, false) || !csr_ok(At, false) || !mat_ok(X) || !mat_ok(W) || !mat_ok(dY) || k_hops < 0 || k_hops > 64)
+        return SENSEI_INVALID_ARGUMENT;
+    if (activation != SENSEI_ACT_NONE && activation != SENSEI_ACT_RELU) return SENSEI_INVALID_ARGUMENT;
+    if (A->n_rows != A->n_cols || At->n_rows != A->n_cols || At->n_cols != A->n_rows || At->nnz != A->nnz) return SENSEI_INVALID_ARGUMENT;
+    if (X.rows != A->n_cols || X.cols <= 0 || W.cols <= 0 || W.rows != (int64_t)(k_hops + 1) * X.cols || dY.rows != A->n_rows || dY.cols != W.cols)
+        return SENSEI_INVALID_ARGUMENT;
+    if (X.cols > (1 << 20) || W.cols > (1 << 20) || (int64_t)(k_hops + 1) * pad4((int)W.cols) > (1 << 20)) return SENSEI_INVALID_ARGUMENT;
+    if ((A->n_rows > 0 && (!r || !c || !X.ptr || !dY.ptr)) || !W.ptr || !dW || lddw < W.cols || !workspace) return SENSEI_INVALID_ARGUMENT;
+    if (activation == SENSEI_ACT_RELU && A->n_rows > 0 && (!Y || ldy < W.cols)) return SENSEI_INVALID_ARGUMENT;
+    if (dX && lddx < X.cols) return SENSEI_INVALID_ARGUMENT;
+    const size_t dwb = mat_bytes(dW, W.rows, W.cols, lddw), dxb = dX ? mat_bytes(dX, A->n_cols, X.cols, lddx) : 0;
+    const size_t xb = mat_bytes(X.ptr, X.rows, X.cols, X.ld), wb = mat_bytes(W.ptr, W.rows, W.cols, W.ld),
+                 dyb = mat_bytes(dY.ptr, dY.rows, dY.cols, dY.ld);
+    if (overlap(dW, dwb, workspace, ws_bytes) || overlap(dW, dwb, X.ptr, xb) || overlap(dW, dwb, W.ptr, wb) || overlap(dW, dwb, dY.ptr, dyb))
+        return SENSEI_INVALID_ARGUMENT;
+    if (dX && (overlap(dX, dxb, workspace, ws_bytes) || overlap(dX, dxb, X.ptr, xb) || overlap(dX, dxb, W.ptr, wb) ||
+               overlap(dX, dxb, dY.ptr, dyb) || overlap(dX, dxb, dW, dwb)))
+        return SENSEI_INVALID_ARGUMENT;
+    if (ws_bytes < tagcn_bwd_ws(*A, (int)X.cols, (int)W.cols, k_hops, bwd_id)) return SENSEI_WORKSPACE_TOO_SMALL;
+    if (A->n_rows == 0) return launch_zero_matrix(dW, W.rows, (int)W.cols, lddw, false, as_stream(stream)) == hipSuccess ? SENSEI_OK : SENSEI_HIP_ERROR;
+    return run_tagcn_backward(*A, *At, r, c, X, W, k_hops, Y, ldy, dY, activation, dX, lddx, dW, lddw, bwd_id, workspace, ws_bytes, as_stream(stream));
 }
 
 int sensei_transpose_positions(sensei_ctx *ctx, const sensei_csr *A, const sensei_csr *At, int32_t *t_pos, void *workspace,

@@ -1176,13 +1176,18 @@ __global__ __launch_bounds__(kThreads) void k_gemm_tn_bf(GemmTnArgs g) {
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) { acc[i][j][r] = 0.f; dacc[i][j][r] = 0.0; }
+    // Every other group of steps multiplies -A and is subtracted: the instruction's sum of 16 products and the accumulator loses
+    // low bits of the smaller addends downwards whatever their sign (measured: about -2^-29 of the sum of the terms' magnitudes),
+    // which over 10^5 rows would add up to several units of fp32 rounding of the root-sum-square; in alternating groups it cancels.
+    int neg = split & 1;   // slabs with an odd number of groups leave one over: neighbouring slabs start with opposite signs
     auto flush = [&]() {
+        const double sg = neg ? -1.0 : 1.0;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) { dacc[i][j][r] += (double)acc[i][j][r]; acc[i][j][r] = 0.f; }
+                for (int r = 0; r < 16; ++r) { dacc[i][j][r] = fma(sg, (double)acc[i][j][r], dacc[i][j][r]); acc[i][j][r] = 0.f; }
     };
 
     // staging: thread -> (column of the 128, k half); columns past the edge read the last column and are cleared, rows past the slab
@@ -1215,11 +1220,12 @@ __global__ __launch_bounds__(kThreads) void k_gemm_tn_bf(GemmTnArgs g) {
         unsigned pc[8][3];
 #pragma unroll
         for (int e = 0; e < 8; ++e) split_bf16x3(src[e], pc[e][0], pc[e][1], pc[e][2]);
+        const unsigned flip = (operand == 0 && neg) ? 0x80008000u : 0u;   // the sign bits of a pair of bf16
 #pragma unroll
         for (int p = 0; p < 3; ++p) {
             uintx4 w;
 #pragma unroll
-            for (int d = 0; d < 4; ++d) w[d] = pack_bf16(pc[2 * d][p], pc[2 * d + 1][p]);
+            for (int d = 0; d < 4; ++d) w[d] = pack_bf16(pc[2 * d][p], pc[2 * d + 1][p]) ^ flip;
             *reinterpret_cast<uintx4 *>(&Ps[buf][operand][p][col >> 5][skh][col & 31][0]) = w;
         }
     };
@@ -1252,7 +1258,7 @@ __global__ __launch_bounds__(kThreads) void k_gemm_tn_bf(GemmTnArgs g) {
                             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af[i]), __builtin_bit_cast(bf16x8, bf), acc[i][j], 0, 0, 0);
                     }
             }
-            if (++since_flush == kFlushStepsBf) { flush(); since_flush = 0; }
+            if (++since_flush == kFlushStepsBf) { flush(); since_flush = 0; neg ^= 1; }   // the pieces stashed below belong to the next group
             __builtin_amdgcn_sched_barrier(0);
             stash(buf ^ 1);
             buf ^= 1;

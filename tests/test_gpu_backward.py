@@ -209,6 +209,90 @@ def test_sgc_backward_argument_checks(ctx):
     torch.cuda.synchronize()
 
 
+# ------------------------------------------------------------------ K-hop layer with a weight block per hop (TAGCN)
+
+def _tagcn_inputs(g, f_in, f_out, k_hops, seed):
+    X = synth.uniform(seed, 10, (g.n_cols, f_in))
+    W = np.concatenate([synth.glorot(seed, 20 + k, f_in, f_out) for k in range(k_hops + 1)], axis=0)
+    dY = synth.normal(seed, 12, (g.n_rows, f_out), 0.0, 1.0)
+    return X, W, dY
+
+
+@pytest.mark.parametrize("name", SQUARE)
+@pytest.mark.parametrize("widths", [(40, 24), (24, 40), (33, 130), (41, 7)])
+@pytest.mark.parametrize("k_hops", [0, 1, 2, 3])
+def test_tagcn_backward_matches_chain_rule(ctx, name, widths, k_hops):
+    g = GRAPHS[name]()
+    gt = synth.transpose(g)
+    f_in, f_out = widths
+    X, W, dY = _tagcn_inputs(g, f_in, f_out, k_hops, 120 + f_in + k_hops)
+    A, At = DeviceCSR(g), DeviceCSR(gt)
+    dr, dc = ctx.degrees(A.s)
+    r, c = ctx.norm_vectors(dr), ctx.norm_vectors(dc)
+    for act in (ACT_NONE, ACT_RELU):
+        Y = None
+        if act == ACT_RELU:
+            Y = oracle.tagcn_layer(g.n_rows, g.row_ptr, g.col_idx, X, W, k_hops, 1).astype(np.float32)
+        want_dx, want_dw = oracle.tagcn_backward(g.n_rows, g.row_ptr, g.col_idx, X, W, k_hops, dY, Y=Y, act=act)
+        Yd = None if Y is None else dev(Y)
+        for bwd in (GCN_BWD_AGG, GCN_BWD_UPD):
+            dX, dW = ctx.tagcn_backward(A.s, At.s, r, c, dev(X), dev(W), k_hops, dev(dY), bwd, Y=Yd, activation=act)
+            assert_close(dX, want_dx, what=f"dX k={k_hops} bwd {bwd} act {act}")
+            assert_close(dW, want_dw, what=f"dW k={k_hops} bwd {bwd} act {act}")
+    for bwd in (GCN_BWD_AGG, GCN_BWD_UPD):
+        none, dW = ctx.tagcn_backward(A.s, At.s, r, c, dev(X), dev(W), k_hops, dev(dY), bwd, Y=Yd, activation=ACT_RELU, want_dx=False)
+        assert none is None
+        assert_close(dW, want_dw, what=f"dW only, bwd {bwd}")
+
+
+def test_tagcn_backward_on_split_patterns_and_strided_operands(ctx):
+    """With a tile split and with column panels attached to the symmetric pattern the hops take those paths; operands and results
+    with leading dimensions larger than their widths."""
+    from paper_2306_15155_amd import Panels, Tiles, csr_struct
+    g = synth.rmat(49, 5000, 150_000)
+    f_in, f_out, K = 72, 48, 2
+    X, W, dY = _tagcn_inputs(g, f_in, f_out, K, 130)
+    A = DeviceCSR(g)
+    dr, dc = ctx.degrees(A.s)
+    r, c = ctx.norm_vectors(dr), ctx.norm_vectors(dc)
+    Y = oracle.tagcn_layer(g.n_rows, g.row_ptr, g.col_idx, X, W, K, 1).astype(np.float32)
+    want_dx, want_dw = oracle.tagcn_backward(g.n_rows, g.row_ptr, g.col_idx, X, W, K, dY, Y=Y, act=1)
+    T = Tiles(ctx, A.s, 0.05, 128, min_width=32)
+    assert T.n_tiles > 0
+    P = Panels(ctx, A.s, 4)
+    Xs = torch.zeros((g.n_cols, f_in + 5), device="cuda:0")
+    Xs[:, :f_in] = dev(X)
+    dYs = torch.zeros((g.n_rows, f_out + 3), device="cuda:0")
+    dYs[:, :f_out] = dev(dY)
+    for At in (csr_struct(g.n_rows, g.n_cols, A.row_ptr, A.col_idx, None, None, T), csr_struct(g.n_rows, g.n_cols, A.row_ptr, A.col_idx, None, P)):
+        for bwd in (GCN_BWD_AGG, GCN_BWD_UPD):
+            dX, dW = ctx.tagcn_backward(At, At, r, c, Xs[:, :f_in], dev(W), K, dYs[:, :f_out], bwd, Y=dev(Y), activation=ACT_RELU)
+            assert_close(dX, want_dx, what=f"dX bwd {bwd}")
+            assert_close(dW, want_dw, what=f"dW bwd {bwd}")
+    T.close()
+    P.close()
+
+
+def test_tagcn_backward_argument_checks(ctx):
+    g = synth.erdos_renyi(47, 200, 600)
+    A = DeviceCSR(g)
+    X, W, dY = (torch.zeros(s, device="cuda:0") for s in ((200, 8), (24, 4), (200, 4)))
+    r = torch.ones(200, device="cuda:0")
+    ctx.tagcn_backward(A.s, A.s, r, r, X, W, 2, dY, GCN_BWD_AGG)
+    with pytest.raises(RuntimeError):
+        ctx.tagcn_backward(A.s, A.s, r, r, X, W, 1, dY, GCN_BWD_AGG)     # W holds three blocks, not two
+    with pytest.raises(RuntimeError):
+        ctx.tagcn_backward(A.s, A.s, r, r, X, W, 2, dY, 2)               # two associations
+    with pytest.raises(RuntimeError):
+        ctx.tagcn_backward(A.s, A.s, r, r, X, W, 2, dY, GCN_BWD_UPD, activation=ACT_RELU)   # ReLU without the forward output
+    gr = rect_block(44, 70, 400, 9)
+    Ar, Art = DeviceCSR(gr), DeviceCSR(synth.transpose(gr))
+    with pytest.raises(RuntimeError):                                      # hops need a square pattern
+        ctx.tagcn_backward(Ar.s, Art.s, torch.ones(70, device="cuda:0"), torch.ones(400, device="cuda:0"), torch.zeros((400, 8), device="cuda:0"), W, 2,
+                           torch.zeros((70, 4), device="cuda:0"), GCN_BWD_AGG)
+    torch.cuda.synchronize()
+
+
 # ------------------------------------------------------------------ GAT
 
 @pytest.mark.parametrize("name", sorted(GRAPHS))

@@ -363,6 +363,51 @@ def test_config2_sgc_backward_two_hops_full_size(ctx, reddit_like):
     assert_close(torch.from_numpy(dws[0]), dws[1], what="dW of the two associations")
 
 
+def test_config2_tagcn_backward_two_hops_full_size(ctx, reddit_like):
+    """Backward of the TAGCN layer with two hops, 602 -> 256, on the Reddit-shaped graph, with and without a dense-tile split.  The
+    pattern is symmetric, so (A^^T)^k = A^^k: sampled rows of dX = sum_k A^^k dY W_k^T are the oracle's forward walks from those rows,
+    one per hop count.  Of the weight gradient, block 0 is X^T dY in full, and sampled columns b of every block k are
+    X^T (A^^k dY[:, b]), which needs the propagation of a few vectors only.  All of it is held to the plain bound."""
+    from paper_2306_15155_amd import GCN_BWD_AGG, GCN_BWD_UPD, Tiles, csr_struct
+    g, A = reddit_like
+    n, f_in, f_out, K = g.n_rows, 602, 256, 2
+    X = synth.uniform(7, 10, (g.n_cols, f_in))
+    W = np.concatenate([synth.glorot(7, 100 + k, f_in, f_out) for k in range(K + 1)], axis=0)
+    dY = synth.normal(7, 500, (n, f_out), 0.0, 1.0)
+    deg = np.diff(g.row_ptr)
+    cand = np.flatnonzero((deg >= 30) & (deg <= 800))
+    rows = cand[np.random.default_rng(13).choice(cand.size, 5, replace=False)].astype(np.int64)
+    want_dx = sum(oracle.sgc_layer(n, g.row_ptr, g.col_idx, dY, np.ascontiguousarray(W[k * f_in:(k + 1) * f_in].T), k, ACT_NONE, rows=rows)
+                  for k in range(K + 1))
+    cols = np.array([0, 31, 32, 97, 128, 200, 254, 255])
+    X64 = X.astype(np.float64)
+    dr_h, dc_h = oracle.degrees(n, n, g.row_ptr, g.col_idx)
+    r_h, c_h = oracle.inv_sqrt_deg(dr_h), oracle.inv_sqrt_deg(dc_h)
+    V = dY[:, cols].astype(np.float64)
+    want_dw_cols = []
+    for k in range(K + 1):
+        if k > 0:
+            V = oracle.row_broadcast(r_h, oracle.spmm(g.row_ptr, g.col_idx, None, oracle.row_broadcast(c_h, V)))
+        want_dw_cols.append(X64.T @ V)
+    want_dw0 = X64.T @ dY.astype(np.float64)
+    r, c, _, _ = _norm(ctx, A)
+    sel = torch.from_numpy(rows).to(DEV)
+    Xd, Wd, dYd = dev(X), dev(W), dev(dY)
+    T = Tiles(ctx, A.s, 0.07, 608)
+    assert T.n_tiles > 0
+    At = csr_struct(n, n, A.row_ptr, A.col_idx, None, None, T)
+    for P in (A.s, At):
+        for bwd in (GCN_BWD_AGG, GCN_BWD_UPD):
+            dX, dW = ctx.tagcn_backward(P, P, r, c, Xd, Wd, K, dYd, bwd)
+            assert_close(dX[sel], want_dx, what=f"dX bwd {bwd}")
+            dw = dW.double().cpu().numpy()
+            assert_close(torch.from_numpy(dw[:f_in]), want_dw0, what=f"dW block 0, bwd {bwd}")
+            for k in range(K + 1):
+                assert_close(torch.from_numpy(np.ascontiguousarray(dw[k * f_in:(k + 1) * f_in][:, cols])), want_dw_cols[k], what=f"dW block {k}, bwd {bwd}")
+            del dX, dW
+    T.close()
+
+
 @pytest.mark.parametrize("shape", [(40, 96), (100, 41), (33, 200)])
 def test_k_hop_layers_at_a_size_that_takes_the_large_product_gemm(ctx, shape):
     """The K-hop layers feed the update GEMM a slice-major operand (TAGCN aggregate-first: depth (K + 1) F_in), add a slice-major
@@ -454,7 +499,7 @@ def test_config4_gat_backward_full_size(ctx, reddit_like):
         assert_close(got[0], want[0], what=f"dX, {how}")
         # dW[f, m] sums 233,000 products with dTheta, whose rows are fp32 sums over up to 1e5 neighbours: entries that cancel to
         # nearly zero may use the allowance for cancelled sums (see assert_close_reduced), at most 0.05 % of the elements
-        # (measured: 2 of 38,528, at 1.9e-4); everything else, and da_l, da_r entirely, meets the plain bar
+        # (measured: 2 of 38,528, at 3.7e-4 = 6 % of their bound); everything else, and da_l, da_r entirely, meets the plain bar
         assert_close_reduced(got[1], want[1], rss, what=f"dW, {how}", max_share=0.0005)
         assert_close(got[2], want[2], what=f"da_l, {how}")
         assert_close(got[3], want[3], what=f"da_r, {how}")

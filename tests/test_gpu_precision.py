@@ -9,7 +9,7 @@ import torch
 
 import oracle
 import synth
-from paper_2306_15155_amd import ACT_NONE, SPMM_PATTERN, Context, Tiles, binding, csr_struct
+from paper_2306_15155_amd import ACT_NONE, GCN_BWD_AGG, SPMM_PATTERN, Context, Tiles, binding, csr_struct
 
 from gpu_util import DeviceCSR, dev
 
@@ -85,3 +85,24 @@ def test_value_less_tiles_on_bf16_pieces_are_as_accurate_as_fp32(ctx):
     assert np.median(err[hub]) < 3.0 * np.median(err_plain[hub]) + 1e-9
     assert np.median(err[hub]) < 0.2 * np.median((two_piece / scale)[hub]), (np.median(err[hub]), np.median((two_piece / scale)[hub]))
     T.close()
+
+
+def test_long_transposed_product_has_no_systematic_error(ctx):
+    """dW = X^T dP over 200,000 rows on the bf16 instruction.  The instruction's own summation loses low bits of its smaller addends
+    downwards whatever their sign; summed over that many rows this showed as an offset of every element by several units of fp32
+    rounding of the root-sum-square of its terms (8 units at 233,000 rows).  The kernel multiplies -A in every other group of steps and
+    subtracts, so the offset cancels: the mean error over the elements must stay within a fraction of a unit, and the spread within the
+    few units that fp32 accumulation inside a group of 32 rows and the final rounding explain."""
+    n, f_in, f_out = 200_000, 96, 64
+    g = synth.self_loops_only(n)                       # A^ = I: the layer without hops is a dense layer, dW = X^T dY
+    A = DeviceCSR(g)
+    ones = torch.ones(n, device="cuda:0")
+    X, dY = synth.uniform(13, 10, (n, f_in)), synth.normal(13, 11, (n, f_out), 0.0, 1.0)
+    W = synth.glorot(13, 12, f_in, f_out)
+    _, dW = ctx.tagcn_backward(A.s, A.s, ones, ones, dev(X), dev(W), 0, dev(dY), GCN_BWD_AGG, want_dx=False)
+    X64, d64 = X.astype(np.float64), dY.astype(np.float64)
+    ref = X64.T @ d64
+    rss = np.sqrt((X64 ** 2).T @ (d64 ** 2))
+    e = (dW.double().cpu().numpy() - ref) / rss * 2.0 ** 24
+    assert abs(e.mean()) < 0.5, e.mean()
+    assert np.sqrt((e ** 2).mean()) < 2.5 and np.abs(e).max() < 12.0, (np.sqrt((e ** 2).mean()), np.abs(e).max())
