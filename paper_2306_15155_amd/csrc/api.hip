@@ -2138,7 +2138,8 @@ int sensei_sgc_backward(sensei_ctx *ctx, const sensei_csr *A, const sensei_csr *
         overlap(dX, dxb, X.ptr, mat_bytes(X.ptr, X.rows, X.cols, X.ld)) || overlap(dX, dxb, dY.ptr, mat_bytes(dY.ptr, dY.rows, dY.cols, dY.ld)))
         return SENSEI_INVALID_ARGUMENT;
     if (ws_bytes < gcn_bwd_ws(*A, (int)X.cols, (int)W.cols, bwd_id, k_hops)) return SENSEI_WORKSPACE_TOO_SMALL;
-    if (A->n_rows == 0) return SENSEI_OK;
+    if (A->n_rows == 0)   // a sum over no nodes
+        return launch_zero_matrix(dW, W.rows, (int)W.cols, lddw, false, as_stream(stream)) == hipSuccess ? SENSEI_OK : SENSEI_HIP_ERROR;
     return run_gcn_backward(*A, *At, r, c, X, W, Y, ldy, dY, activation, nullptr, 0, dX, lddx, dW, lddw, bwd_id, workspace, ws_bytes,
                             as_stream(stream), k_hops);
 }

@@ -273,6 +273,33 @@ def test_tagcn_backward_on_split_patterns_and_strided_operands(ctx):
     P.close()
 
 
+def test_k_hop_backward_degenerate_patterns(ctx):
+    """A pattern without entries (A^ = 0: only the hop-free term of TAGCN is left, the SGC layer and its gradients vanish) and a
+    pattern without nodes (the weight gradient, a sum over no nodes, is zero)."""
+    n, f_in, f_out, K = 50, 12, 7, 2
+    none = np.empty(0, np.int32)
+    g = synth.build_csr(n, n, none, none, False, False)
+    X, W, dY = _tagcn_inputs(g, f_in, f_out, K, 140)
+    A = DeviceCSR(g)
+    ones = torch.ones(n, device="cuda:0")
+    want_dx, want_dw = oracle.tagcn_backward(n, g.row_ptr, g.col_idx, X, W, K, dY)
+    assert np.abs(want_dw[f_in:]).max() == 0.0 and np.abs(want_dw[:f_in]).max() > 0.0
+    for bwd in (GCN_BWD_AGG, GCN_BWD_UPD):
+        dX, dW = ctx.tagcn_backward(A.s, A.s, ones, ones, dev(X), dev(W), K, dev(dY), bwd)
+        assert_close(dX, want_dx, what=f"tagcn dX, bwd {bwd}")
+        assert_close(dW, want_dw, what=f"tagcn dW, bwd {bwd}")
+        dX, dW = ctx.sgc_backward(A.s, A.s, ones, ones, dev(X), dev(W[:f_in]), K, dev(dY), bwd)
+        assert float(dX.abs().max()) == 0.0 and float(dW.abs().max()) == 0.0
+    g0 = synth.build_csr(0, 0, none, none, False, False)
+    A0 = DeviceCSR(g0)
+    e = torch.empty(0, device="cuda:0")
+    for bwd in (GCN_BWD_AGG, GCN_BWD_UPD):
+        for fn, Wd in ((ctx.tagcn_backward, dev(W)), (ctx.sgc_backward, dev(W[:f_in]))):
+            dX, dW = fn(A0.s, A0.s, e, e, torch.empty((0, f_in), device="cuda:0"), Wd, K, torch.empty((0, f_out), device="cuda:0"), bwd)
+            assert dX.shape == (0, f_in) and dW.shape == Wd.shape and float(dW.abs().max()) == 0.0
+    torch.cuda.synchronize()
+
+
 def test_tagcn_backward_argument_checks(ctx):
     g = synth.erdos_renyi(47, 200, 600)
     A = DeviceCSR(g)
