@@ -318,6 +318,47 @@ def gatv2_layer(n_rows, n_cols, row_ptr, col_idx, X, W_l, W_r, att, slope=0.2, a
     return activation(spmm(sub_ptr, sub_idx, alpha, Th_r), act)
 
 
+def gatv2_backward(n_rows, n_cols, row_ptr, col_idx, X, W_l, W_r, att, dY, Y=None, slope=0.2, act=0):
+    """Gradient of sum(dY * Y) for the GATv2 layer of gatv2_layer -> (dX, dW_l, dW_r, datt): the chain rule taken backwards through
+    its steps, row by row.  dP = dY (.) [Y > 0] (the fp32 forward output ``Y`` supplies the ReLU mask).  For row i with
+    neighbours j, U = Theta_l[i] + Theta_r[j] (one vector per entry), e = LeakyReLU(U) att, alpha = softmax(e):
+      aggregation  Y_i = sum_j alpha_j Theta_r[j]:   dTheta_r[j] += alpha_j dP_i,  dalpha_j = <dP_i, Theta_r[j]>
+      softmax:     de_j = alpha_j (dalpha_j - sum_k alpha_k dalpha_k)
+      score:       datt += sum_j de_j LeakyReLU(U_j);   dU_j = de_j att (.) LeakyReLU'(U_j);   dTheta_l[i] += sum_j dU_j;
+                   dTheta_r[j] += dU_j
+    and then dW_l = X_dst^T dTheta_l, dW_r = X^T dTheta_r, dX = dTheta_r W_r^T with dTheta_l W_l^T added to the first n_rows rows."""
+    row_ptr, col_idx = _i32(row_ptr), _i32(col_idx)
+    X64 = _f32(X).astype(np.float64)
+    Wl, Wr = _f32(W_l).astype(np.float64), _f32(W_r).astype(np.float64)
+    a = _f32(att).astype(np.float64)
+    Th_l, Th_r = gemm(X64[:n_rows], Wl), gemm(X64, Wr)
+    dP = _f32(dY).astype(np.float64)
+    if act == 1:
+        dP = dP * (_f32(Y) > 0)
+    dTh_l, dTh_r = np.zeros_like(Th_l), np.zeros_like(Th_r)
+    datt = np.zeros_like(a)
+    for i in range(n_rows):
+        nb = col_idx[row_ptr[i]:row_ptr[i + 1]]
+        if nb.size == 0:
+            continue
+        U = Th_l[i][None, :] + Th_r[nb]
+        L = np.where(U > 0.0, U, slope * U)
+        e = L @ a
+        p = np.exp(e - e.max())
+        alpha = p / p.sum()
+        dalpha = Th_r[nb] @ dP[i]
+        de = alpha * (dalpha - float(alpha @ dalpha))
+        datt += de @ L
+        dU = de[:, None] * (a[None, :] * np.where(U > 0.0, 1.0, slope))
+        dTh_l[i] += dU.sum(axis=0)
+        np.add.at(dTh_r, nb, alpha[:, None] * dP[i][None, :] + dU)
+    dW_l = gemm(np.ascontiguousarray(X64[:n_rows].T), dTh_l)
+    dW_r = gemm(np.ascontiguousarray(X64.T), dTh_r)
+    dX = gemm(dTh_r, np.ascontiguousarray(Wr.T))
+    dX[:n_rows] += gemm(dTh_l, np.ascontiguousarray(Wl.T))
+    return dX, dW_l, dW_r, datt
+
+
 def dotgat_layer(n_rows, n_cols, row_ptr, col_idx, X, W_q, W_k, W_v, scale, act=0, rows=None):
     """Key-query attention layer (the score function of GaAN-style layers, which the paper's discussion of attention variants
     names): Q = X W_q over the destinations (= the first n_rows sources), K = X W_k and V = X W_v over the sources,

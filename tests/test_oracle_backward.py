@@ -333,3 +333,88 @@ def test_tagcn_backward_special_cases():
     _close(dXi, dY64 @ Wsum.T, 1e-13)
     for k in range(K + 1):
         _close(dWi[k * f_in:(k + 1) * f_in], X64.T @ dY64, 1e-13)
+
+
+# ------------------------------------------------------------------ GATv2
+
+def _gatv2_case(seed0, g, f_in, f_out, slope, h):
+    """First seed whose per-entry vectors U = Theta_l[i] + Theta_r[j] all stay clear of the LeakyReLU kink."""
+    for seed in range(seed0, seed0 + 200):
+        rng = np.random.default_rng(seed)
+        X, dY = _grid(rng, (g.n_cols, f_in)), _grid(rng, (g.n_rows, f_out))
+        W_l, W_r, att = _grid(rng, (f_in, f_out)), _grid(rng, (f_in, f_out)), _grid(rng, (f_out,))
+        Tl = X[:g.n_rows].astype(np.float64) @ W_l.astype(np.float64)
+        Tr = X.astype(np.float64) @ W_r.astype(np.float64)
+        U = np.concatenate([Tl[i][None, :] + Tr[g.col_idx[g.row_ptr[i]:g.row_ptr[i + 1]]] for i in range(g.n_rows)])
+        if np.min(np.abs(U)) > 16 * h and np.min(np.abs(att)) > 0:
+            return X, W_l, W_r, att, dY
+    raise AssertionError("no seed keeps the score vectors away from zero")
+
+
+@pytest.mark.parametrize("shape", ["square", "rect"])
+def test_gatv2_backward_is_the_gradient_of_the_forward(shape):
+    g = synth.rmat(71, 10, 22) if shape == "square" else _rect_block(72, 5, 11, 3)
+    f_in, f_out, slope, h = 3, 3, 0.2, 2.0 ** -11
+    X, W_l, W_r, att, dY = _gatv2_case(300, g, f_in, f_out, slope, h)
+
+    def loss():
+        return float(np.sum(dY.astype(np.float64) * oracle.gatv2_layer(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W_l, W_r, att, slope, 0)))
+
+    dX, dWl, dWr, da = oracle.gatv2_backward(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W_l, W_r, att, dY, slope=slope)
+    _close(dX, _richardson(loss, X, h), 1e-7)
+    _close(dWl, _richardson(loss, W_l, h), 1e-7)
+    _close(dWr, _richardson(loss, W_r, h), 1e-7)
+    _close(da, _richardson(loss, att, h), 1e-7)
+    assert min(np.max(np.abs(dWl)), np.max(np.abs(da))) > 1e-4       # the score path carries gradient
+
+
+def test_gatv2_backward_with_relu_and_other_slope():
+    g = synth.rmat(73, 12, 30)
+    f_in, f_out, slope, h = 3, 4, 0.05, 2.0 ** -11
+    X, W_l, W_r, att, dY = _gatv2_case(400, g, f_in, f_out, slope, h)
+    P = oracle.gatv2_layer(12, 12, g.row_ptr, g.col_idx, X, W_l, W_r, att, slope, 0)
+    ok = np.abs(P) > 64 * h          # outputs near the ReLU kink are left out of the loss
+    dYm = (dY * ok).astype(np.float32)
+    Y = oracle.gatv2_layer(12, 12, g.row_ptr, g.col_idx, X, W_l, W_r, att, slope, 1).astype(np.float32)
+    assert (Y > 0).any() and (Y == 0).any()
+
+    def loss():
+        return float(np.sum(dYm.astype(np.float64) * oracle.gatv2_layer(12, 12, g.row_ptr, g.col_idx, X, W_l, W_r, att, slope, 1)))
+
+    got = oracle.gatv2_backward(12, 12, g.row_ptr, g.col_idx, X, W_l, W_r, att, dYm, Y=Y, slope=slope, act=1)
+    for grad, x in zip(got, (X, W_l, W_r, att)):
+        _close(grad, _richardson(loss, x, h), 1e-7)
+
+
+def test_gatv2_backward_special_cases():
+    rng = np.random.default_rng(75)
+    g = synth.rmat(75, 16, 40)
+    f_in, f_out = 4, 3
+    X, dY = _grid(rng, (16, f_in)), _grid(rng, (16, f_out))
+    W_l, W_r, att = _grid(rng, (f_in, f_out)), _grid(rng, (f_in, f_out)), _grid(rng, (f_out,))
+    # slope 1: the score is att.Theta_l[i] + att.Theta_r[j], whose first term cancels in the softmax: the layer is the GAT layer with
+    # W = W_r and a_r = att, nothing flows through W_l, and the gradients are those of that layer (its own oracle, written in C)
+    dX, dWl, dWr, da = oracle.gatv2_backward(16, 16, g.row_ptr, g.col_idx, X, W_l, W_r, att, dY, slope=1.0)
+    a_l = _grid(rng, (f_out,))
+    wx, ww, _, war = oracle.gat_backward(16, 16, g.row_ptr, g.col_idx, X, W_r, a_l, att, dY, slope=1.0)
+    _close(dWl, np.zeros_like(dWl), 1e-12)
+    _close(dX, wx, 1e-11)
+    _close(dWr, ww, 1e-11)
+    _close(da, war, 1e-11)
+    # att = 0: every row averages its neighbours and the score path is switched off: dTheta_r = M^T dP with M the row-normalised
+    # pattern, dX = dTheta_r W_r^T, dW_r = X^T dTheta_r, dW_l = 0
+    A = dense.dense_pattern(16, 16, g.row_ptr, g.col_idx)
+    M = A / A.sum(axis=1, keepdims=True)
+    zero = np.zeros(f_out, dtype=np.float32)
+    dX0, dWl0, dWr0, da0 = oracle.gatv2_backward(16, 16, g.row_ptr, g.col_idx, X, W_l, W_r, zero, dY)
+    dTr = M.T @ dY.astype(np.float64)
+    _close(dX0, dTr @ W_r.astype(np.float64).T, 1e-12)
+    _close(dWr0, X.astype(np.float64).T @ dTr, 1e-12)
+    _close(dWl0, np.zeros_like(dWl0), 1e-12)
+    # linear in dY
+    d2 = _grid(rng, (16, f_out))
+    a = oracle.gatv2_backward(16, 16, g.row_ptr, g.col_idx, X, W_l, W_r, att, dY)
+    b = oracle.gatv2_backward(16, 16, g.row_ptr, g.col_idx, X, W_l, W_r, att, d2)
+    c = oracle.gatv2_backward(16, 16, g.row_ptr, g.col_idx, X, W_l, W_r, att, (dY + d2).astype(np.float32))
+    for x, y, z in zip(a, b, c):
+        _close(np.asarray(x) + np.asarray(y), z, 1e-11)
