@@ -669,7 +669,11 @@ def headline(args):
             tmp_out = torch.empty_like(outs[i])
             v2[tag(i)] = {nm: round(time_fn(lambda: ctx.gatv2_layer(A, src_of(i), Wl2, Wd[i], att2, cid, 0.2, L["act"], out=tmp_out), 2), 4)
                           for cid, nm in ((0, "REUSE"), (1, "RECOMP"))}
-            del Wl2, att2, tmp_out
+            t_pos = ctx.transpose_positions(A, A)
+            dYt = torch.randn((N, L["f_out"]), device=dev)
+            v2[tag(i)]["BACKWARD"] = round(time_fn(lambda: ctx.gatv2_backward(A, A, t_pos, src_of(i), Wl2, Wd[i], att2, dYt, Y=outs[i] if L["act"] else None,
+                                                                              activation=L["act"]), 2), 4)
+            del Wl2, att2, tmp_out, t_pos, dYt
         detail["gatv2_ms"] = v2
         # key-query attention (dot-product scores, 64-column queries and keys) on the same shapes: reuse and recompute
         kq = {}

@@ -171,6 +171,23 @@ int sensei_gat_backward(sensei_ctx *ctx, const sensei_csr *A, const sensei_csr *
                         float *dX, int64_t lddx, float *dW, int64_t lddw, float *da_l, float *da_r, void *workspace, size_t ws_bytes,
                         void *stream);
 
+/* Backward of the layer sensei_gatv2_layer (the GATv2 variant named with the attention variants of the paper's discussion; training as in
+ * its evaluation section).  With dP = dY (.) [Y > 0], Theta_l = X_dst W_l, Theta_r = X W_r, U_ij = Theta_l[i] + Theta_r[j],
+ * e_ij = att . LeakyReLU(U_ij) and alpha the row softmax of e (Eq. 5 with this score):
+ *   dalpha_ij = <dP_i, Theta_r[j]>,   de_ij = alpha_ij (dalpha_ij - sum_k alpha_ik dalpha_ik),
+ *   datt = sum_ij de_ij LeakyReLU(U_ij),
+ *   dTheta_l[i] = att (.) sum_j de_ij LeakyReLU'(U_ij),   dTheta_r[j] = sum_i alpha_ij dP_i + att (.) sum_i de_ij LeakyReLU'(U_ij),
+ *   dW_l = X_dst^T dTheta_l (f_in x f_out, lddwl),   dW_r = X^T dTheta_r (lddwr),   datt (f_out floats),
+ *   dX = dTheta_r W_r^T, plus dTheta_l W_l^T on the first n_rows rows (n_cols x f_in, lddx; skipped when dX is NULL).
+ * With one shared weight matrix (W_l = W_r in the forward) its gradient is dW_l + dW_r.  At, t_pos: the transposed pattern and the
+ * place of every stored entry in it (sensei_transpose_positions), as for sensei_gat_backward; the other arguments, aliasing rules and
+ * error codes as there.  Column panels and tile splits attached to the patterns are not used by this call. */
+int sensei_gatv2_backward_workspace(const sensei_csr *A, int f_in, int f_out, size_t *bytes);
+int sensei_gatv2_backward(sensei_ctx *ctx, const sensei_csr *A, const sensei_csr *At, const int32_t *t_pos, sensei_mat X, sensei_mat W_l,
+                          sensei_mat W_r, const float *att, float neg_slope, const float *Y, int64_t ldy, sensei_mat dY, int activation, float *dX,
+                          int64_t lddx, float *dW_l, int64_t lddwl, float *dW_r, int64_t lddwr, float *datt, void *workspace, size_t ws_bytes,
+                          void *stream);
+
 /* ------------------------------------------------- primitives (steps of a layer) */
 
 /* Degrees of the stored pattern, which holds the self edges (case study GCN: D~ is the degree

@@ -869,6 +869,109 @@ int run_gatv2(const sensei_csr &A, const sensei_mat &X, const sensei_mat &Wl, co
     return SENSEI_OK;
 }
 
+// ---- backward of the GATv2 layer.  With dP = dY (.) [Y > 0], U_ij = Theta_l[i] + Theta_r[j], e_ij = att . LeakyReLU(U_ij):
+//   dalpha_ij = <dP_i, Theta_r[j]>,  de_ij = alpha_ij (dalpha_ij - sum_k alpha_ik dalpha_ik)          (as in the GAT backward, no outer LeakyReLU)
+//   dTheta_l[i] = att (.) sum_j de_ij LeakyReLU'(U_ij)                                                 (row sums over the pattern)
+//   dTheta_r[j] = sum_i alpha_ij dP_i + att (.) sum_i de_ij LeakyReLU'(U_ij)                           (row sums over the transposed pattern)
+//   datt        = sum_i sum_j de_ij LeakyReLU(U_ij)
+//   dW_l = X_dst^T dTheta_l,  dW_r = X^T dTheta_r,  dX = dTheta_r W_r^T + [dTheta_l W_l^T on the first n_rows rows]
+// The three sums with a vector per entry are SpMM walks whose gathered row meets a vector of the output row (kSpmmSignSum / kSpmmLreluSum).
+size_t gatv2_bwd_ws(const sensei_csr &A, int f_in, int f_out) {
+    const size_t nz = (size_t)(A.nnz > 0 ? A.nnz : 1), fo = pad32(f_out), fo4 = pad4(f_out), fi4 = pad4(f_in);
+    const int t = choose_chunk_nnz(A.nnz);
+    const size_t n_chunks = A.nnz <= 0 ? 1 : (size_t)((A.nnz + t - 1) / t);
+    size_t b = 2 * plan_bytes(A.nnz) + softmax_ws_bytes(A) + 1024;
+    b += 2 * align_up(nz * sizeof(float), 256) + align_up(nz * sizeof(float2), 256);   // logits, dalpha / de, (alpha, de) transposed
+    b += align_up((size_t)(A.n_rows + 1) * sizeof(float), 256) + align_up(n_chunks * sizeof(float), 256);   // row dots and their carry
+    b += 2 * align_up(fo * sizeof(float), 256);                                        // att padded, a scratch vector
+    b += align_up((size_t)A.n_cols * fo * sizeof(float), 256);                         // Theta_r (slice-major)
+    b += 3 * align_up((size_t)A.n_rows * fo * sizeof(float), 256);                     // Theta_l, dP, the LeakyReLU sums (slice-major)
+    b += align_up((size_t)A.n_cols * 2 * fo4 * sizeof(float), 256);                    // [dTheta_r | dTheta_l]
+    b += align_up((size_t)A.n_cols * fo4 * sizeof(float), 256);                        // the sign sums over the transposed pattern
+    b += align_up((size_t)A.n_rows * sizeof(float), 256);                              // ones
+    b += spmm_carry_bytes(A.nnz, (int)fo);
+    b += align_up(2 * fo4 * fi4 * sizeof(float), 256);                                 // [W_r^T; W_l^T]
+    b += gemm_tn_bytes(A.n_cols, f_in, f_out) + theta_t_vec_bytes(A.n_rows, f_out);
+    return b;
+}
+
+int run_gatv2_backward(const sensei_csr &A_in, const sensei_csr &At_in, const int32_t *t_pos, const sensei_mat &X, const sensei_mat &Wl,
+                       const sensei_mat &Wr, const float *att, float slope, const float *Y, int64_t ldy, const sensei_mat &dY, int act, float *dX,
+                       int64_t lddx, float *dWl, int64_t lddwl, float *dWr, int64_t lddwr, float *datt, void *ws, size_t ws_bytes, hipStream_t s) {
+    sensei_csr A = A_in, At = At_in;   // plain walks: no column panels, no tile split
+    A.panels = nullptr; A.tiles = nullptr; At.panels = nullptr; At.tiles = nullptr;
+    const int f_in = (int)X.cols, f_out = (int)Wr.cols;
+    const int fo = pad32(f_out), fo4 = pad4(f_out), fi4 = pad4(f_in);
+    const int64_t ldd = 2 * (int64_t)fo4;
+    const size_t nz = (size_t)(A.nnz > 0 ? A.nnz : 1);
+    Carver cv(ws, ws_bytes);
+    ChunkPlan plan = make_plan(A, cv), plan_t = make_plan(At, cv);
+    float2 *stats = cv.take<float2>((size_t)A.n_rows + 1);
+    float2 *carry_stats = cv.take<float2>((size_t)plan.n_chunks);
+    float *logits = cv.take<float>(nz);
+    float *de = cv.take<float>(nz);
+    float2 *ade_t = cv.take<float2>(nz);            // (alpha, de) in the order of the transposed pattern
+    float *rowdot = cv.take<float>((size_t)A.n_rows + 1);
+    float *sum_carry = cv.take<float>((size_t)plan.n_chunks);
+    float *att_pad = cv.take<float>((size_t)fo);
+    float *vec_scratch = cv.take<float>((size_t)fo);
+    float *theta_r = cv.take<float>((size_t)A.n_cols * fo);
+    float *theta_l = cv.take<float>((size_t)A.n_rows * fo);
+    float *dPs = cv.take<float>((size_t)A.n_rows * fo);
+    float *Rs = cv.take<float>((size_t)A.n_rows * fo);
+    float *Dcat = cv.take<float>((size_t)A.n_cols * ldd);
+    float *GR = cv.take<float>((size_t)A.n_cols * fo4);
+    float *ones = cv.take<float>((size_t)A.n_rows);
+    float *carry = cv.take<float>(spmm_carry_bytes(A.nnz, fo) / sizeof(float));
+    float *Wcat = cv.take<float>((size_t)ldd * fi4);
+    double *part = cv.take<double>(gemm_tn_bytes(A.n_cols, f_in, f_out) / sizeof(double));
+    double *part_a = cv.take<double>(theta_t_vec_bytes(A.n_rows, f_out) / sizeof(double));
+    float *dThR = Dcat, *dThL = Dcat + fo4;
+
+    SENSEI_TRY(launch_chunk_rows(A, plan, s));
+    SENSEI_TRY(launch_chunk_rows(At, plan_t, s));
+    // forward quantities: both projections (slice-major), the logits and the row statistics
+    SENSEI_TRY(launch_to_slices(nullptr, att, f_out, 1, f_out, att_pad, s));
+    SENSEI_TRY(launch_gemm(X.ptr, X.ld, Wr.ptr, Wr.ld, theta_r, fo, A.n_cols, f_in, f_out, fo, SENSEI_ACT_NONE, s, nullptr, nullptr, true));
+    SENSEI_TRY(launch_gemm(X.ptr, X.ld, Wl.ptr, Wl.ld, theta_l, fo, A.n_rows, f_in, f_out, fo, SENSEI_ACT_NONE, s, nullptr, nullptr, true));
+    SENSEI_TRY(launch_score_v2(A, theta_l, theta_r, f_out, att_pad, slope, logits, plan, s));
+    SENSEI_TRY(launch_softmax(A, logits, de, plan, stats, carry_stats, s));   // the weights it writes are not kept: de is overwritten below
+    SENSEI_TRY(launch_to_slices(nullptr, dY.ptr, dY.ld, A.n_rows, f_out, dPs, s, act == SENSEI_ACT_RELU ? Y : nullptr, ldy));
+    // per stored entry: dalpha and its weighted row sums, then the softmax backward; alpha and de also in transposed order
+    SENSEI_TRY(launch_gat_dalpha(A, theta_r, dPs, f_out, logits, stats, de, rowdot, plan, sum_carry, s));
+    SENSEI_TRY(launch_gat_dt(A, logits, de, rowdot, stats, t_pos, 1.f, de, ade_t, plan, s));
+    // [dTheta_r | dTheta_l], zero where nothing is written (pad columns; the rows of dTheta_l past the destinations)
+    SENSEI_TRY(launch_zero_matrix(Dcat, A.n_cols, (int)ldd, ldd, false, s));
+    SENSEI_TRY(launch_zero_matrix(Wcat, ldd, fi4, fi4, false, s));
+    sensei_csr Aw = At;
+    Aw.val = reinterpret_cast<const float *>(ade_t);
+    SENSEI_TRY(launch_spmm(Aw, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, dPs, fo, f_out, dThR, ldd, f_out, SENSEI_ACT_NONE, plan_t, carry, s, nullptr, false,
+                           true, nullptr, true, 2));
+    SelfSumArgs self_l = {theta_l, slope}, self_r = {theta_r, slope};
+    sensei_csr Ae = A;
+    Ae.val = de;
+    SENSEI_TRY(launch_spmm(Ae, kSpmmSignSum, nullptr, nullptr, theta_r, fo, f_out, dThL, ldd, f_out, SENSEI_ACT_NONE, plan, carry, s, nullptr, false, true,
+                           nullptr, true, 1, false, false, nullptr, &self_l));
+    SENSEI_TRY(launch_spmm(Ae, kSpmmLreluSum, nullptr, nullptr, theta_r, fo, fo, Rs, fo, fo, SENSEI_ACT_NONE, plan, carry, s, nullptr, false, true, nullptr,
+                           true, 1, true, false, nullptr, &self_l));
+    Aw.val = reinterpret_cast<const float *>(ade_t) + 1;
+    SENSEI_TRY(launch_spmm(Aw, kSpmmSignSum, nullptr, nullptr, theta_l, fo, f_out, GR, fo4, f_out, SENSEI_ACT_NONE, plan_t, carry, s, nullptr, false, true,
+                           nullptr, true, 2, false, false, nullptr, &self_r));
+    SENSEI_TRY(launch_scale_cols(dThL, ldd, dThL, ldd, att, A.n_rows, f_out, false, s));
+    SENSEI_TRY(launch_scale_cols(dThR, ldd, GR, fo4, att, A.n_cols, f_out, true, s));
+    // datt: column sums of the LeakyReLU sums
+    SENSEI_TRY(launch_fill_f32(ones, A.n_rows, 1.f, s));
+    SENSEI_TRY(launch_theta_t_vec(Rs, A.n_rows, f_out, ones, A.n_rows, ones, datt, vec_scratch, part_a, s));
+    SENSEI_TRY(launch_gemm_tn(X.ptr, X.ld, dThL, ldd, A.n_rows, f_in, f_out, dWl, lddwl, part, s));
+    SENSEI_TRY(launch_gemm_tn(X.ptr, X.ld, dThR, ldd, A.n_cols, f_in, f_out, dWr, lddwr, part, s));
+    if (dX) {
+        SENSEI_TRY(launch_transpose(Wr.ptr, Wr.ld, f_in, f_out, Wcat, fi4, s));
+        SENSEI_TRY(launch_transpose(Wl.ptr, Wl.ld, f_in, f_out, Wcat + (size_t)fo4 * fi4, fi4, s));
+        SENSEI_TRY(launch_gemm(Dcat, ldd, Wcat, fi4, dX, lddx, A.n_cols, (int)ldd, f_in, f_in, SENSEI_ACT_NONE, s));
+    }
+    return SENSEI_OK;
+}
+
 // ---- key-query attention (the score function of GaAN-style layers): e_ij = scale <W_q x_i, W_k x_j>, Y = act(sum_j alpha_ij W_v x_j)
 size_t dotgat_ws(const sensei_csr &A, int f_in, int d_k, int f_out, int id) {
     const int dk = pad32(d_k), fo = pad32(f_out), fi = pad4(f_in);
@@ -2228,6 +2331,46 @@ int sensei_gat_backward(sensei_ctx *ctx, const sensei_csr *A, const sensei_csr *
     if (ws_bytes < gat_bwd_ws(*A, At, (int)X.cols, (int)W.cols)) return SENSEI_WORKSPACE_TOO_SMALL;
     return run_gat_backward(*A, *At, t_pos, X, W, a_l, a_r, neg_slope, Y, ldy, dY, activation, dX, lddx, dW, lddw, da_l, da_r, workspace,
                             ws_bytes, as_stream(stream));
+}
+
+int sensei_gatv2_backward_workspace(const sensei_csr *A, int f_in, int f_out, size_t *bytes) {
+    if (!csr_ok(A, false) || f_in <= 0 || f_out <= 0 || !bytes) return SENSEI_INVALID_ARGUMENT;
+    *bytes = gatv2_bwd_ws(*A, f_in, f_out);
+    return SENSEI_OK;
+}
+
+int sensei_gatv2_backward(sensei_ctx *ctx, const sensei_csr *A, const sensei_csr *At, const int32_t *t_pos, sensei_mat X, sensei_mat W_l,
+                          sensei_mat W_r, const float *att, float neg_slope, const float *Y, int64_t ldy, sensei_mat dY, int activation, float *dX,
+                          int64_t lddx, float *dW_l, int64_t lddwl, float *dW_r, int64_t lddwr, float *datt, void *workspace, size_t ws_bytes,
+                          void *stream) {
+    if (!ctx || !csr_ok(A, false) || !csr_ok(At, false) || !mat_ok(X) || !mat_ok(W_l) || !mat_ok(W_r) || !mat_ok(dY)) return SENSEI_INVALID_ARGUMENT;
+    if (At->n_rows != A->n_cols || At->n_cols != A->n_rows || At->nnz != A->nnz || A->n_rows > A->n_cols) return SENSEI_INVALID_ARGUMENT;
+    if (activation != SENSEI_ACT_NONE && activation != SENSEI_ACT_RELU) return SENSEI_INVALID_ARGUMENT;
+    if (X.rows != A->n_cols || X.cols != W_r.rows || X.cols != W_l.rows || W_l.cols != W_r.cols || X.cols <= 0 || W_r.cols <= 0)
+        return SENSEI_INVALID_ARGUMENT;
+    if (X.cols > (1 << 20) || W_r.cols > (1 << 19)) return SENSEI_INVALID_ARGUMENT;
+    if (dY.rows != A->n_rows || dY.cols != W_r.cols) return SENSEI_INVALID_ARGUMENT;
+    if ((!X.ptr && A->n_cols > 0) || !W_l.ptr || !W_r.ptr || (!dY.ptr && A->n_rows > 0) || !dW_l || !dW_r || !datt || !att || !workspace)
+        return SENSEI_INVALID_ARGUMENT;
+    if (!t_pos && A->nnz > 0) return SENSEI_INVALID_ARGUMENT;
+    if (lddwl < W_l.cols || lddwr < W_r.cols || (dX && lddx < X.cols)) return SENSEI_INVALID_ARGUMENT;
+    if (activation == SENSEI_ACT_RELU && ((!Y && A->n_rows > 0) || ldy < W_r.cols)) return SENSEI_INVALID_ARGUMENT;
+    const size_t xb = mat_bytes(X.ptr, X.rows, X.cols, X.ld), dyb = mat_bytes(dY.ptr, dY.rows, dY.cols, dY.ld);
+    const size_t wlb = mat_bytes(W_l.ptr, W_l.rows, W_l.cols, W_l.ld), wrb = mat_bytes(W_r.ptr, W_r.rows, W_r.cols, W_r.ld);
+    const size_t dxb = dX ? mat_bytes(dX, A->n_cols, X.cols, lddx) : 0;
+    struct Out { const void *p; size_t n; } outs[4] = {{dW_l, mat_bytes(dW_l, W_l.rows, W_l.cols, lddwl)}, {dW_r, mat_bytes(dW_r, W_r.rows, W_r.cols, lddwr)},
+                                                     {datt, (size_t)W_r.cols * sizeof(float)}, {dX, dxb}};
+    for (int a = 0; a < 4; ++a) {
+        const Out &o = outs[a];
+        if (overlap(o.p, o.n, workspace, ws_bytes) || overlap(o.p, o.n, X.ptr, xb) || overlap(o.p, o.n, W_l.ptr, wlb) || overlap(o.p, o.n, W_r.ptr, wrb) ||
+            overlap(o.p, o.n, dY.ptr, dyb) || overlap(o.p, o.n, att, (size_t)W_r.cols * sizeof(float)))
+            return SENSEI_INVALID_ARGUMENT;
+        for (int b = a + 1; b < 4; ++b)
+            if (overlap(o.p, o.n, outs[b].p, outs[b].n)) return SENSEI_INVALID_ARGUMENT;
+    }
+    if (ws_bytes < gatv2_bwd_ws(*A, (int)X.cols, (int)W_r.cols)) return SENSEI_WORKSPACE_TOO_SMALL;
+    return run_gatv2_backward(*A, *At, t_pos, X, W_l, W_r, att, neg_slope, Y, ldy, dY, activation, dX, lddx, dW_l, lddwl, dW_r, lddwr, datt, workspace,
+                              ws_bytes, as_stream(stream));
 }
 
 int sensei_gat_attention_path(const sensei_csr *A, int f_in, int f_out, int n_heads, int comp_id) {

@@ -63,7 +63,7 @@ hipError_t launch_spmm(const sensei_csr &A, int mode, const float *r, const floa
                        int f, float *C, int64_t ldc, int f_store, int act, const ChunkPlan &p, float *carry,
                        hipStream_t s, KernelTimer *timer = nullptr, bool accumulate = false, bool finalize = true,
                        const float2 *mz = nullptr, bool b_sliced = false, int val_stride = 1, bool c_sliced = false, bool defer_fixup = false,
-                       const struct AttnFusedArgs *fused = nullptr);
+                       const struct AttnFusedArgs *fused = nullptr, const struct SelfSumArgs *self = nullptr);
 // b_sliced: B is stored slice-major in tiles of 32 floats, element (j, col) at B[(col / 32) * n_cols * 32 + j * 32 + col % 32]
 // (f padded to a multiple of 32, B 128-byte aligned); `ldb` is ignored.  val_stride: floats between consecutive values of A.val.
 // c_sliced (needs b_sliced, f a multiple of 32, f_store == f): C is written slice-major too (n_rows x f), `ldc` is ignored.
@@ -83,6 +83,15 @@ struct AttnFusedArgs {
     const float *s_l, *s_r;
     float slope;
     float2 *row_mz, *chunk_mz;
+};
+// Internal SpMM modes for the backward pass of a score with a vector per entry, e_ij = att . LeakyReLU(U_ij), U_ij = self[i, :] + B[j, :]
+// (slice-major self over the rows and B over the columns): C[i, m] = sum_j val_ij LeakyReLU'(U_ij[m]) (kSpmmSignSum: 1 where
+// U > 0, else the slope) or sum_j val_ij LeakyReLU(U_ij[m]) (kSpmmLreluSum).  Single pass, slice-major B only.
+constexpr int kSpmmSignSum = 5;
+constexpr int kSpmmLreluSum = 6;
+struct SelfSumArgs {
+    const float *self_sliced;
+    float slope;
 };
 
 // ---- column panels: a copy of the pattern with the columns of each panel contiguous
@@ -146,6 +155,9 @@ hipError_t launch_score_v2(const sensei_csr &A, const float *theta_l, const floa
 hipError_t launch_rank1_add(float *D, int64_t ldd, int64_t n, int f, const float *ds_l, int64_t n_l, const float *ds_r, const float *a_l,
                             const float *a_r, hipStream_t s);
 // out_l = Theta^T v_l (v_l counted for the first n_l rows), out_r = Theta^T v_r; Theta slice-major n x pad32(f); sums in fp64
+// D[i, m] = (accumulate ? D[i, m] : 0) + v[m] G[i, m] over n rows and f columns (G may be D)
+hipError_t launch_scale_cols(float *D, int64_t ldd, const float *G, int64_t ldg, const float *v, int64_t n, int f, bool accumulate, hipStream_t s);
+hipError_t launch_fill_f32(float *p, int64_t n, float v, hipStream_t s);
 size_t theta_t_vec_bytes(int64_t n, int f);
 hipError_t launch_theta_t_vec(const float *theta_sliced, int64_t n, int f, const float *v_l, int64_t n_l, const float *v_r, float *out_l,
                               float *out_r, double *part, hipStream_t s);

@@ -74,6 +74,9 @@ struct SpmmArgs {
     const float *s_l, *s_r;
     float slope;
     float2 *mz_out, *carry_mz;  // per row: pair of a first piece whose row goes on in the next chunk; per chunk: pair of its continued row
+    // modes kSpmmSignSum / kSpmmLreluSum: a vector per row, slice-major like C (tile t of row i at self + t * self_tile + i * 32)
+    const float *self;
+    long long self_tile;
 };
 
 // value of `x` held by the lane whose number is byte_lane / 4 (all lanes must be active)
@@ -111,6 +114,9 @@ __device__ __forceinline__ float inv_z(float z) { return z > 0.f ? 1.f / z : 0.f
 // maximum m, the sum z of exp(logit - m) and its partial row relative to m, rescaling both when the maximum grows; the
 // lanes' (m, z, row) triples are merged when the row (piece) ends.  A piece of a row that spans chunks leaves its pair
 // beside its partial row (mz_out / carry_mz) and k_spmm_fixup_attn merges the pieces in chunk order.
+// MODES kSpmmSignSum, kSpmmLreluSum (slice-major operands, 32-column tiles): the gathered row meets a vector of the output row itself,
+// u = self[i, :] + B[j, :], and what is summed is val_ij LeakyReLU'(u) or val_ij LeakyReLU(u), column by column: the reductions
+// of the backward pass of a score with a vector per entry.
 template <int VEC, int LPG, int MODE, bool OFF32>
 __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
     constexpr int G = 64 / LPG;
@@ -155,6 +161,15 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
     if (MODE == kSpmmSoftmax) m_row = uni_f((i < a.n_rows) ? a.mz[i].x : 0.f);
     if (MODE == kSpmmAttnFused) m_row = uni_f((i < a.n_rows) ? a.s_l[i] : 0.f);
     float m_run = -INFINITY, z_run = 0.f;  // fused attention mode: this lane's running maximum and sum of exp(logit - maximum)
+    constexpr bool kSelfMode = (MODE == kSpmmSignSum || MODE == kSpmmLreluSum);
+    const float *self_lane = nullptr;   // this lane's columns of row 0 of the per-row vector
+    Vec<VEC> self_v;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) self_v.v[e] = 0.f;
+    if (kSelfMode) {
+        self_lane = a.self + (size_t)tile * a.self_tile + (fok ? (lane % LPG) * VEC : 0);
+        if (i < a.n_rows) self_v = Vec<VEC>::load(self_lane + (size_t)i * 32);
+    }
 
     Vec<VEC> acc;
 #pragma unroll
@@ -171,6 +186,15 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
 #pragma unroll
             for (int e = 0; e < VEC; ++e) acc.v[e] = fmaf(acc.v[e], keep, p * b.v[e]);
             m_run = mn;
+            return;
+        }
+        if (kSelfMode) {
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                const float u = self_v.v[e] + b.v[e];
+                const float d = u > 0.f ? 1.f : a.slope;
+                acc.v[e] = fmaf(ww, MODE == kSpmmSignSum ? d : d * u, acc.v[e]);
+            }
             return;
         }
 #pragma unroll
@@ -266,6 +290,10 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
             for (int e = 0; e < VEC; ++e) racc.v[e] = 0.f;
             float rm = -INFINITY, rz = 0.f;  // fused attention mode: running maximum and sum of the group's row
             const float sl_g = (MODE == kSpmmAttnFused && rok) ? a.s_l[row] : 0.f;
+            Vec<VEC> self_g;
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) self_g.v[e] = 0.f;
+            if (kSelfMode && rok) self_g = Vec<VEC>::load(self_lane + (size_t)row * 32);
             for (int k = rs; k < rend; k += U) {
                 Vec<VEC> b[U];
                 float ww[U];
@@ -275,7 +303,7 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
                     const int kq = valid ? k + q : k;
                     const int j = a.col_idx[kq];
                     float wq = 1.f;
-                    if (MODE == SENSEI_SPMM_WEIGHTED) wq = a.val[(size_t)kq * a.val_stride];
+                    if (MODE == SENSEI_SPMM_WEIGHTED || kSelfMode) wq = a.val[(size_t)kq * a.val_stride];
                     if (MODE == SENSEI_SPMM_SCALED) wq = a.c[j];
                     if (MODE == kSpmmSoftmax) wq = __expf(a.val[(size_t)kq * a.val_stride] - mz_g.x);
                     if (MODE == kSpmmAttnFused) {
@@ -305,7 +333,15 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
 #pragma unroll
                 for (int q = 0; q < U; ++q) {
 #pragma unroll
-                    for (int e = 0; e < VEC; ++e) racc.v[e] = fmaf(ww[q], b[q].v[e], racc.v[e]);
+                    for (int e = 0; e < VEC; ++e) {
+                        if (kSelfMode) {
+                            const float u = self_g.v[e] + b[q].v[e];
+                            const float d = u > 0.f ? 1.f : a.slope;
+                            racc.v[e] = fmaf(ww[q], MODE == kSpmmSignSum ? d : d * u, racc.v[e]);
+                        } else {
+                            racc.v[e] = fmaf(ww[q], b[q].v[e], racc.v[e]);
+                        }
+                    }
                 }
             }
             if (MODE == kSpmmAttnFused && rok && tile == 0 && (lane % LPG) == 0) {
@@ -356,7 +392,7 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
         float w = 0.f;
         if (k < hi) {
             col = a.col_idx[k];
-            if (MODE == SENSEI_SPMM_WEIGHTED || MODE == kSpmmSoftmax) w = a.val[(size_t)k * a.val_stride];
+            if (MODE == SENSEI_SPMM_WEIGHTED || MODE == kSpmmSoftmax || kSelfMode) w = a.val[(size_t)k * a.val_stride];
             if (MODE == SENSEI_SPMM_SCALED) w = a.c[col];
             if (MODE == kSpmmAttnFused) w = a.s_r[col];
         }
@@ -369,6 +405,7 @@ __global__ __launch_bounds__(kBlock) void k_spmm(SpmmArgs a) {
                 re = uni(a.row_ptr[i + 1]);
                 if (MODE == kSpmmSoftmax) m_row = uni_f(a.mz[i].x);
                 if (MODE == kSpmmAttnFused) m_row = uni_f(a.s_l[i]);
+                if (kSelfMode) self_v = Vec<VEC>::load(self_lane + (size_t)i * 32);
             }
             const int seg_hi = uni(re < bhi ? re : bhi);
             const int u0 = uni(pos - base), n = uni(seg_hi - pos);
@@ -510,6 +547,15 @@ hipError_t spmm_dispatch_mode(const SpmmArgs &a, int mode, dim3 grid, hipStream_
         case SENSEI_SPMM_WEIGHTED: hipLaunchKernelGGL((k_spmm<VEC, LPG, SENSEI_SPMM_WEIGHTED, OFF32>), grid, dim3(kBlock), 0, s, a); break;
         case kSpmmSoftmax: hipLaunchKernelGGL((k_spmm<VEC, LPG, kSpmmSoftmax, OFF32>), grid, dim3(kBlock), 0, s, a); break;
         case kSpmmAttnFused: hipLaunchKernelGGL((k_spmm<VEC, LPG, kSpmmAttnFused, OFF32>), grid, dim3(kBlock), 0, s, a); break;
+        case kSpmmSignSum:
+        case kSpmmLreluSum:
+            if constexpr (VEC == 4 && LPG == 8) {   // slice-major operands only
+                if (mode == kSpmmSignSum) hipLaunchKernelGGL((k_spmm<4, 8, kSpmmSignSum, OFF32>), grid, dim3(kBlock), 0, s, a);
+                else hipLaunchKernelGGL((k_spmm<4, 8, kSpmmLreluSum, OFF32>), grid, dim3(kBlock), 0, s, a);
+                break;
+            } else {
+                return hipErrorInvalidValue;
+            }
         default: hipLaunchKernelGGL((k_spmm<VEC, LPG, SENSEI_SPMM_SCALED, OFF32>), grid, dim3(kBlock), 0, s, a); break;
     }
     return hipGetLastError();
@@ -1533,6 +1579,22 @@ __global__ void k_rank1_add(float *__restrict__ D, long long ldd, long long n, i
     D[j * ldd + q] += l * a_l[q] + ds_r[j] * a_r[q];
 }
 
+// D[i, m] = (accumulate ? D[i, m] : 0) + v[m] G[i, m]: a column scaling, on its own or added to what D holds (G may be D itself)
+__global__ void k_scale_cols(float *D, long long ldd, const float *G, long long ldg, const float *__restrict__ v, long long n, int f,
+                             int accumulate) {
+    const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= n * f) return;
+    const long long i = t / f;
+    const int m = (int)(t % f);
+    const float g = v[m] * G[i * ldg + m];
+    D[i * ldd + m] = accumulate ? D[i * ldd + m] + g : g;
+}
+
+__global__ void k_fill_f32(float *p, long long n, float v) {
+    const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < n) p[t] = v;
+}
+
 // part[slab][0][q] = sum_j Theta[j, q] v_l[j], part[slab][1][q] = sum_j Theta[j, q] v_r[j] over the rows of the slab,
 // Theta slice-major, sums in fp64.  One workgroup per (tile, slab): 32 columns x 8 rows per pass.
 __global__ __launch_bounds__(256) void k_theta_t_vec(const float *__restrict__ theta, long long n, int f_pad, const float *__restrict__ v_l,
@@ -1683,7 +1745,7 @@ size_t spmm_carry_bytes(int64_t nnz, int f) {
 hipError_t launch_spmm(const sensei_csr &A, int mode, const float *r, const float *c, const float *B, int64_t ldb,
                        int f, float *C, int64_t ldc, int f_store, int act, const ChunkPlan &p, float *carry,
                        hipStream_t s, KernelTimer *timer, bool accumulate, bool finalize, const float2 *mz, bool b_sliced, int val_stride,
-                       bool c_sliced, bool defer_fixup, const AttnFusedArgs *fused) {
+                       bool c_sliced, bool defer_fixup, const AttnFusedArgs *fused, const SelfSumArgs *self) {
     SpmmShape sh = spmm_shape(B, ldb, f);
     if (b_sliced) {  // slices of 32 floats per row: one 128-byte line per neighbour and tile
         sh.vec = 4; sh.lpg = 8; sh.n_tiles = (f + 31) / 32; sh.f_carry = sh.n_tiles * 32;
@@ -1707,6 +1769,12 @@ hipError_t launch_spmm(const sensei_csr &A, int mode, const float *r, const floa
     if (mode == kSpmmAttnFused) {
         if (!fused || accumulate || !finalize || defer_fixup) return hipErrorInvalidValue;
         a.s_l = fused->s_l; a.s_r = fused->s_r; a.slope = fused->slope; a.mz_out = fused->row_mz; a.carry_mz = fused->chunk_mz;
+    }
+    a.self = nullptr; a.self_tile = 0;
+    if (mode == kSpmmSignSum || mode == kSpmmLreluSum) {
+        if (!self || !self->self_sliced || !b_sliced || !A.val) return hipErrorInvalidValue;
+        a.self = self->self_sliced; a.slope = self->slope;
+        a.self_tile = (long long)(A.n_rows > 0 ? A.n_rows : 1) * 32;
     }
     const unsigned groups = blocks_for(p.n_chunks, kWavesPerBlock);
     // Feature tiles worked on at the same time (consecutive XCDs take consecutive tiles of the live set): all eight
@@ -1901,6 +1969,19 @@ hipError_t launch_rank1_add(float *D, int64_t ldd, int64_t n, int f, const float
     if (n <= 0 || f <= 0) return hipSuccess;
     hipLaunchKernelGGL(k_rank1_add, dim3(blocks_for(n * f, kBlock)), dim3(kBlock), 0, s, D, (long long)ldd, (long long)n, f, ds_l, (long long)n_l,
                        ds_r, a_l, a_r);
+    return hipGetLastError();
+}
+
+hipError_t launch_scale_cols(float *D, int64_t ldd, const float *G, int64_t ldg, const float *v, int64_t n, int f, bool accumulate, hipStream_t s) {
+    if (n <= 0 || f <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_scale_cols, dim3(blocks_for(n * f, kBlock)), dim3(kBlock), 0, s, D, (long long)ldd, G, (long long)ldg, v, (long long)n, f,
+                       accumulate ? 1 : 0);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_f32(float *p, int64_t n, float v, hipStream_t s) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_fill_f32, dim3(blocks_for(n, kBlock)), dim3(kBlock), 0, s, p, (long long)n, v);
     return hipGetLastError();
 }
 

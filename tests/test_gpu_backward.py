@@ -545,3 +545,116 @@ def test_backward_can_be_captured_in_a_hip_graph(ctx, split):
     if T is not None:
         del graph
         T.close()
+
+
+# ------------------------------------------------------------------ GATv2
+
+def _gatv2_inputs(g, f_in, f_out, seed):
+    """The derivative of LeakyReLU jumps where a component of U_ij = Theta_l[i] + Theta_r[j] is zero, and with millions of components some
+    lie closer to zero than fp32 rounding of the projections (seen: one of 4.3 million at 1.3e-8, where the fp32 path and the fp64
+    oracle took different branches and one column of dW_l moved by 2e-4).  X and the two weight matrices therefore take multiples
+    of 1/64: products and sums of the projections are then exact in fp32 in any order, both sides see the same U, and take the
+    same branch everywhere, also where U is exactly zero."""
+    grid = lambda a: (np.round(a * 64.0) / 64.0).astype(np.float32)
+    X = grid(synth.uniform(seed, 10, (g.n_cols, f_in)))
+    W_l, W_r = grid(synth.glorot(seed, 13, f_in, f_out) * 2.0), grid(synth.glorot(seed, 11, f_in, f_out) * 2.0)
+    att = synth.normal(seed, 20, (f_out,), 0.0, 0.3)
+    dY = synth.normal(seed, 12, (g.n_rows, f_out), 0.0, 1.0)
+    return X, W_l, W_r, att, dY
+
+
+@pytest.mark.parametrize("name", sorted(GRAPHS))
+@pytest.mark.parametrize("widths", [(40, 24), (24, 40), (70, 41), (20, 64)])
+@pytest.mark.parametrize("act", [ACT_NONE, ACT_RELU])
+def test_gatv2_backward_matches_chain_rule(ctx, name, widths, act):
+    g = GRAPHS[name]()
+    gt = synth.transpose(g)
+    f_in, f_out = widths
+    X, W_l, W_r, att, dY = _gatv2_inputs(g, f_in, f_out, 170 + f_in)
+    assert np.count_nonzero(W_l) > W_l.size // 2
+    Y = None
+    if act == ACT_RELU:
+        Y = oracle.gatv2_layer(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W_l, W_r, att, 0.2, 1).astype(np.float32)
+    want = oracle.gatv2_backward(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W_l, W_r, att, dY, Y=Y, slope=0.2, act=act)
+    A, At = DeviceCSR(g), DeviceCSR(gt)
+    pos = ctx.transpose_positions(A.s, At.s)
+    got = ctx.gatv2_backward(A.s, At.s, pos, dev(X), dev(W_l), dev(W_r), dev(att), dev(dY), Y=None if Y is None else dev(Y), activation=act)
+    for gpu, ref, what in zip(got, want, ("dX", "dW_l", "dW_r", "datt")):
+        assert_close(gpu, ref, what=what)
+
+
+def test_gatv2_backward_other_slope_shared_weights_and_strides(ctx):
+    """Another slope; one weight matrix passed for both roles (its gradient is the sum of the two returned); operands and results with
+    leading dimensions larger than their widths; weight gradients only."""
+    g = synth.rmat(172, 3000, 60_000)
+    f_in, f_out = 48, 64
+    X, W, _, att, dY = _gatv2_inputs(g, f_in, f_out, 173)
+    want = oracle.gatv2_backward(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, W, att, dY, slope=0.05)
+    A = DeviceCSR(g)
+    pos = ctx.transpose_positions(A.s, A.s)  # symmetric pattern: its own transpose
+    Xs = torch.zeros((g.n_cols, f_in + 3), device="cuda:0")
+    Xs[:, :f_in] = dev(X)
+    Ws = torch.zeros((f_in, f_out + 8), device="cuda:0")
+    Ws[:, :f_out] = dev(W)
+    dYs = torch.zeros((g.n_rows, f_out + 4), device="cuda:0")
+    dYs[:, :f_out] = dev(dY)
+    dX, dWl, dWr, da = ctx.gatv2_backward(A.s, A.s, pos, Xs[:, :f_in], Ws[:, :f_out], Ws[:, :f_out], dev(att), dYs[:, :f_out], neg_slope=0.05)
+    assert_close(dX, want[0], what="dX")
+    assert_close(dWl, want[1], what="dW_l")
+    assert_close(dWr, want[2], what="dW_r")
+    assert_close(da, want[3], what="datt")
+    none, dWl2, dWr2, da2 = ctx.gatv2_backward(A.s, A.s, pos, dev(X), dev(W), dev(W), dev(att), dev(dY), neg_slope=0.05, want_dx=False)
+    assert none is None and torch.equal(dWl2, dWl) and torch.equal(dWr2, dWr) and torch.equal(da2, da)
+
+
+def test_gatv2_backward_on_a_graph_of_millions_of_entries(ctx):
+    """2 million stored entries, thousands of chunks, hub rows that span hundreds of them (their carries and fix-ups in every one
+    of the SpMM-shaped sums), ReLU mask."""
+    g = synth.rmat(176, 20_000, 2_000_000)
+    assert g.nnz > 2_000_000 and np.diff(g.row_ptr).max() > 5000
+    f_in, f_out = 32, 32
+    X, W_l, W_r, att, dY = _gatv2_inputs(g, f_in, f_out, 177)
+    Y = oracle.gatv2_layer(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W_l, W_r, att, 0.2, 1).astype(np.float32)
+    want = oracle.gatv2_backward(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W_l, W_r, att, dY, Y=Y, slope=0.2, act=1)
+    A = DeviceCSR(g)
+    pos = ctx.transpose_positions(A.s, A.s)
+    got = ctx.gatv2_backward(A.s, A.s, pos, dev(X), dev(W_l), dev(W_r), dev(att), dev(dY), Y=dev(Y), activation=ACT_RELU)
+    for gpu, ref, what in zip(got, want, ("dX", "dW_l", "dW_r", "datt")):
+        assert_close(gpu, ref, what=what)
+
+
+def test_gatv2_backward_slope_one_is_the_gat_backward(ctx):
+    """With slope 1 the score is att.Theta_l[i] + att.Theta_r[j]; the first term cancels in the softmax, so the layer is the GAT layer
+    with W = W_r and a_r = att: nothing flows through W_l, and dX, dW_r, datt are that layer's dX, dW, da_r (its own oracle)."""
+    g = synth.rmat(174, 2000, 30_000)
+    f_in, f_out = 24, 40
+    X, W_r, dY = _inputs(g, f_in, f_out, 175)
+    W_l = synth.glorot(175, 13, f_in, f_out)
+    att = synth.normal(175, 20, (f_out,), 0.0, 0.3)
+    want = oracle.gat_backward(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W_r, np.zeros(f_out, np.float32), att, dY, slope=1.0)
+    A = DeviceCSR(g)
+    pos = ctx.transpose_positions(A.s, A.s)
+    dX, dWl, dWr, da = ctx.gatv2_backward(A.s, A.s, pos, dev(X), dev(W_l), dev(W_r), dev(att), dev(dY), neg_slope=1.0)
+    assert_close(dX, want[0], what="dX")
+    assert_close(dWr, want[1], what="dW_r")
+    assert_close(da, want[3], what="datt")
+    assert_close(dWl, np.zeros((f_in, f_out)), what="dW_l")
+
+
+def test_gatv2_backward_argument_checks(ctx):
+    g = synth.erdos_renyi(47, 200, 600)
+    A = DeviceCSR(g)
+    pos = ctx.transpose_positions(A.s, A.s)
+    X, W, dY = (torch.zeros(s, device="cuda:0") for s in ((200, 8), (8, 4), (200, 4)))
+    att = torch.zeros(4, device="cuda:0")
+    ctx.gatv2_backward(A.s, A.s, pos, X, W, W, att, dY)
+    with pytest.raises(RuntimeError):
+        ctx.gatv2_backward(A.s, A.s, pos, X, W, torch.zeros((8, 5), device="cuda:0"), att, dY)      # the two projections differ in width
+    with pytest.raises(RuntimeError):
+        ctx.gatv2_backward(A.s, A.s, pos, X, W, W, att, dY, activation=ACT_RELU)                    # ReLU without the forward output
+    with pytest.raises(RuntimeError):
+        ctx.gatv2_backward(A.s, A.s, None, X, W, W, att, dY)                                         # no transposition map
+    g2 = synth.erdos_renyi(48, 100, 300)
+    with pytest.raises(RuntimeError):
+        ctx.gatv2_backward(A.s, DeviceCSR(g2).s, pos, X, W, W, att, dY)                              # transposed pattern of another shape
+    torch.cuda.synchronize()
