@@ -381,6 +381,42 @@ def dotgat_layer(n_rows, n_cols, row_ptr, col_idx, X, W_q, W_k, W_v, scale, act=
     return activation(spmm(sub_ptr, sub_idx, alpha, V), act)
 
 
+def dotgat_backward(n_rows, n_cols, row_ptr, col_idx, X, W_q, W_k, W_v, scale, dY, Y=None, act=0):
+    """Gradient of sum(dY * Y) for the key-query attention layer of dotgat_layer -> (dX, dW_q, dW_k, dW_v): the chain rule backwards
+    through its steps, row by row.  dP = dY (.) [Y > 0] (the fp32 forward output ``Y`` supplies the ReLU mask).  For row i with
+    neighbours j: e_j = scale <Q_i, K_j>, alpha = softmax(e), Y_i = sum_j alpha_j V_j, hence
+      dV_j += alpha_j dP_i,   dalpha_j = <dP_i, V_j>,   de_j = alpha_j (dalpha_j - sum_k alpha_k dalpha_k),
+      dQ_i = scale sum_j de_j K_j,   dK_j += scale de_j Q_i,
+    and dW_q = X_dst^T dQ, dW_k = X^T dK, dW_v = X^T dV, dX = dK W_k^T + dV W_v^T with dQ W_q^T added to the first n_rows rows."""
+    row_ptr, col_idx = _i32(row_ptr), _i32(col_idx)
+    X64 = _f32(X).astype(np.float64)
+    Wq, Wk, Wv = (_f32(W).astype(np.float64) for W in (W_q, W_k, W_v))
+    Q, K, V = gemm(X64[:n_rows], Wq), gemm(X64, Wk), gemm(X64, Wv)
+    dP = _f32(dY).astype(np.float64)
+    if act == 1:
+        dP = dP * (_f32(Y) > 0)
+    dQ, dK, dV = np.zeros_like(Q), np.zeros_like(K), np.zeros_like(V)
+    sc = float(scale)
+    for i in range(n_rows):
+        nb = col_idx[row_ptr[i]:row_ptr[i + 1]]
+        if nb.size == 0:
+            continue
+        e = sc * (K[nb] @ Q[i])
+        p = np.exp(e - e.max())
+        alpha = p / p.sum()
+        dalpha = V[nb] @ dP[i]
+        de = alpha * (dalpha - float(alpha @ dalpha))
+        dQ[i] = sc * (de @ K[nb])
+        np.add.at(dK, nb, sc * de[:, None] * Q[i][None, :])
+        np.add.at(dV, nb, alpha[:, None] * dP[i][None, :])
+    dW_q = gemm(np.ascontiguousarray(X64[:n_rows].T), dQ)
+    dW_k = gemm(np.ascontiguousarray(X64.T), dK)
+    dW_v = gemm(np.ascontiguousarray(X64.T), dV)
+    dX = gemm(dK, np.ascontiguousarray(Wk.T)) + gemm(dV, np.ascontiguousarray(Wv.T))
+    dX[:n_rows] += gemm(dQ, np.ascontiguousarray(Wq.T))
+    return dX, dW_q, dW_k, dW_v
+
+
 def gat_layer_heads(n_rows, n_cols, row_ptr, col_idx, X, W, a_l, a_r, n_heads, slope=0.2, act=0, rows=None, omp=False):
     """Multi-head GAT with concatenated heads: head h is the single-head layer of Eq. 5 / 6 on columns
     [h d, (h + 1) d) of W, a_l, a_r (heads share nothing but the input)."""

@@ -418,3 +418,58 @@ def test_gatv2_backward_special_cases():
     c = oracle.gatv2_backward(16, 16, g.row_ptr, g.col_idx, X, W_l, W_r, att, (dY + d2).astype(np.float32))
     for x, y, z in zip(a, b, c):
         _close(np.asarray(x) + np.asarray(y), z, 1e-11)
+
+
+# ------------------------------------------------------------------ key-query attention
+
+@pytest.mark.parametrize("shape", ["square", "rect"])
+def test_key_query_attention_backward_is_the_gradient_of_the_forward(shape):
+    rng = np.random.default_rng(81)
+    g = synth.rmat(81, 10, 22) if shape == "square" else _rect_block(82, 5, 11, 3)
+    f_in, d_k, f_out, scale, h = 3, 2, 4, 0.7, 2.0 ** -11
+    X, dY = _grid(rng, (g.n_cols, f_in)), _grid(rng, (g.n_rows, f_out))
+    W_q, W_k, W_v = _grid(rng, (f_in, d_k)), _grid(rng, (f_in, d_k)), _grid(rng, (f_in, f_out))
+    Y = oracle.dotgat_layer(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W_q, W_k, W_v, scale, 1).astype(np.float32)
+    P = oracle.dotgat_layer(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W_q, W_k, W_v, scale, 0)
+    for act in (0, 1):
+        dYm = dY if act == 0 else (dY * (np.abs(P) > 64 * h)).astype(np.float32)   # outputs near the ReLU kink stay out of the loss
+
+        def loss():
+            return float(np.sum(dYm.astype(np.float64) * oracle.dotgat_layer(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W_q, W_k, W_v, scale, act)))
+
+        got = oracle.dotgat_backward(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W_q, W_k, W_v, scale, dYm, Y=Y, act=act)
+        for grad, x in zip(got, (X, W_q, W_k, W_v)):
+            _close(grad, _richardson(loss, x, h), 1e-7)
+        assert min(np.max(np.abs(got[1])), np.max(np.abs(got[2]))) > 1e-4      # the score path carries gradient
+
+
+def test_key_query_attention_backward_special_cases():
+    rng = np.random.default_rng(83)
+    g = synth.build_csr(14, 14, rng.integers(0, 14, size=40), rng.integers(0, 14, size=40), False, True)   # not symmetric
+    f_in, d_k, f_out, scale = 4, 3, 3, 0.5
+    X, dY = _grid(rng, (14, f_in)), _grid(rng, (14, f_out))
+    W_q, W_k, W_v = _grid(rng, (f_in, d_k)), _grid(rng, (f_in, d_k)), _grid(rng, (f_in, f_out))
+    X64, d64 = X.astype(np.float64), dY.astype(np.float64)
+    Wq, Wk, Wv = W_q.astype(np.float64), W_k.astype(np.float64), W_v.astype(np.float64)
+    # the textbook gradient of dense masked attention softmax(scale Q K^T + mask) V, in matrices
+    A = dense.dense_pattern(14, 14, g.row_ptr, g.col_idx)
+    Q, K, V = X64 @ Wq, X64 @ Wk, X64 @ Wv
+    S = np.where(A > 0, scale * Q @ K.T, -np.inf)
+    Pm = np.exp(S - S.max(axis=1, keepdims=True))
+    Pm /= Pm.sum(axis=1, keepdims=True)
+    dPm = d64 @ V.T
+    dS = Pm * (dPm - np.sum(Pm * dPm, axis=1, keepdims=True))
+    dQ, dK, dV = scale * dS @ K, scale * dS.T @ Q, Pm.T @ d64
+    got = oracle.dotgat_backward(14, 14, g.row_ptr, g.col_idx, X, W_q, W_k, W_v, scale, dY)
+    _close(got[0], dQ @ Wq.T + dK @ Wk.T + dV @ Wv.T, 1e-12)
+    _close(got[1], X64.T @ dQ, 1e-12)
+    _close(got[2], X64.T @ dK, 1e-12)
+    _close(got[3], X64.T @ dV, 1e-12)
+    assert np.abs(dS - dS.T).max() > 1e-4            # swapping the roles of rows and columns would show
+    # scale 0: every row averages its neighbours, nothing flows through the queries and keys
+    M = A / A.sum(axis=1, keepdims=True)
+    z = oracle.dotgat_backward(14, 14, g.row_ptr, g.col_idx, X, W_q, W_k, W_v, 0.0, dY)
+    _close(z[1], np.zeros_like(z[1]), 1e-13)
+    _close(z[2], np.zeros_like(z[2]), 1e-13)
+    _close(z[3], X64.T @ (M.T @ d64), 1e-12)
+    _close(z[0], (M.T @ d64) @ Wv.T, 1e-12)
