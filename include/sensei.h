@@ -188,6 +188,20 @@ int sensei_gatv2_backward(sensei_ctx *ctx, const sensei_csr *A, const sensei_csr
                           int64_t lddx, float *dW_l, int64_t lddwl, float *dW_r, int64_t lddwr, float *datt, void *workspace, size_t ws_bytes,
                           void *stream);
 
+/* Backward of the layer sensei_dotgat_layer (key-query attention; training as in the paper's evaluation section).  With
+ * dP = dY (.) [Y > 0], Q = X_dst W_q, K = X W_k, V = X W_v, e_ij = scale <Q_i, K_j> and alpha the row softmax of e:
+ *   dV_j = sum_i alpha_ij dP_i,   dalpha_ij = <dP_i, V_j>,   de_ij = alpha_ij (dalpha_ij - sum_k alpha_ik dalpha_ik),
+ *   dQ_i = scale sum_j de_ij K_j,   dK_j = scale sum_i de_ij Q_i,
+ *   dW_q = X_dst^T dQ (f_in x d_k, lddwq),   dW_k = X^T dK (lddwk),   dW_v = X^T dV (f_in x f_out, lddwv),
+ *   dX = dK W_k^T + dV W_v^T, plus dQ W_q^T on the first n_rows rows (n_cols x f_in, lddx; skipped when dX is NULL).
+ * At, t_pos and the other arguments, aliasing rules and error codes as for sensei_gat_backward.  Column panels and tile splits attached
+ * to the patterns are not used by this call. */
+int sensei_dotgat_backward_workspace(const sensei_csr *A, int f_in, int d_k, int f_out, size_t *bytes);
+int sensei_dotgat_backward(sensei_ctx *ctx, const sensei_csr *A, const sensei_csr *At, const int32_t *t_pos, sensei_mat X, sensei_mat W_q,
+                           sensei_mat W_k, sensei_mat W_v, float scale, const float *Y, int64_t ldy, sensei_mat dY, int activation, float *dX,
+                           int64_t lddx, float *dW_q, int64_t lddwq, float *dW_k, int64_t lddwk, float *dW_v, int64_t lddwv, void *workspace,
+                           size_t ws_bytes, void *stream);
+
 /* ------------------------------------------------- primitives (steps of a layer) */
 
 /* Degrees of the stored pattern, which holds the self edges (case study GCN: D~ is the degree

@@ -31,7 +31,7 @@ EXPORTS = (
     "sensei_select", "sensei_profile_enable", "sensei_profile_read", "sensei_panels_bytes", "sensei_panels_create",
     "sensei_panels_count", "sensei_panels_destroy", "sensei_panels_set_min_width", "sensei_panels_tune_bytes",
     "sensei_panels_tune", "sensei_gcn_backward_workspace", "sensei_gcn_backward", "sensei_select_gcn_backward", "sensei_transpose_positions",
-    "sensei_gat_backward_workspace", "sensei_gat_backward", "sensei_gat_layer_heads", "sensei_sgc_workspace", "sensei_sgc_layer", "sensei_sgc_backward_workspace", "sensei_sgc_backward", "sensei_tagcn_workspace", "sensei_tagcn_layer", "sensei_tagcn_backward_workspace", "sensei_tagcn_backward", "sensei_gatv2_workspace", "sensei_gatv2_layer", "sensei_gatv2_backward_workspace", "sensei_gatv2_backward", "sensei_dotgat_workspace", "sensei_dotgat_layer", "sensei_tiles_remainder_panels", "sensei_tiles_bytes", "sensei_tiles_create", "sensei_tiles_info",
+    "sensei_gat_backward_workspace", "sensei_gat_backward", "sensei_gat_layer_heads", "sensei_sgc_workspace", "sensei_sgc_layer", "sensei_sgc_backward_workspace", "sensei_sgc_backward", "sensei_tagcn_workspace", "sensei_tagcn_layer", "sensei_tagcn_backward_workspace", "sensei_tagcn_backward", "sensei_gatv2_workspace", "sensei_gatv2_layer", "sensei_gatv2_backward_workspace", "sensei_gatv2_backward", "sensei_dotgat_workspace", "sensei_dotgat_layer", "sensei_dotgat_backward_workspace", "sensei_dotgat_backward", "sensei_tiles_remainder_panels", "sensei_tiles_bytes", "sensei_tiles_create", "sensei_tiles_info",
            "sensei_tiles_set_min_width", "sensei_tiles_destroy",
 )
 
@@ -98,6 +98,9 @@ def lib():
         L.sensei_gatv2_backward_workspace.argtypes = [P(CsrStruct), i32, i32, P(sz)]
         L.sensei_gatv2_backward.argtypes = [vp, P(CsrStruct), P(CsrStruct), vp, MatStruct, MatStruct, MatStruct, vp, f32, vp, i64, MatStruct, i32,
                                             vp, i64, vp, i64, vp, i64, vp, vp, sz, vp]
+        L.sensei_dotgat_backward_workspace.argtypes = [P(CsrStruct), i32, i32, i32, P(sz)]
+        L.sensei_dotgat_backward.argtypes = [vp, P(CsrStruct), P(CsrStruct), vp, MatStruct, MatStruct, MatStruct, MatStruct, f32, vp, i64, MatStruct, i32,
+                                             vp, i64, vp, i64, vp, i64, vp, i64, vp, sz, vp]
         L.sensei_gat_workspace.argtypes = [P(CsrStruct), i32, i32, i32, P(sz)]
         L.sensei_gat_attention_path.argtypes = [P(CsrStruct), i32, i32, i32, i32]
         L.sensei_gat_layer.argtypes = [vp, P(CsrStruct), MatStruct, MatStruct, vp, vp, f32, vp, i64, i32, i32, vp, sz, vp]
@@ -472,6 +475,23 @@ class Context:
                                            _ptr(dX), mat_struct(dX).ld if dX is not None else 0, _ptr(dWl), mat_struct(dWl).ld, _ptr(dWr),
                                            mat_struct(dWr).ld, _ptr(da), self.ws.ptr, self.ws.nbytes, _stream()), "sensei_gatv2_backward")
         return dX, dWl, dWr, da
+
+    def dotgat_backward(self, A: CsrStruct, At: CsrStruct, t_pos, X, W_q, W_k, W_v, scale, dY, Y=None, activation=ACT_NONE, want_dx=True):
+        """Backward of dotgat_layer -> (dX or None, dW_q, dW_k, dW_v)."""
+        f_in, d_k, f_out = W_q.size(0), W_q.size(1), W_v.size(1)
+        dX = torch.empty((A.n_cols, f_in), dtype=torch.float32, device=self.device) if want_dx else None
+        dWq = torch.empty((f_in, d_k), dtype=torch.float32, device=self.device)
+        dWk = torch.empty((f_in, d_k), dtype=torch.float32, device=self.device)
+        dWv = torch.empty((f_in, f_out), dtype=torch.float32, device=self.device)
+        need = ctypes.c_size_t()
+        _check(lib().sensei_dotgat_backward_workspace(ctypes.byref(A), f_in, d_k, f_out, ctypes.byref(need)), "sensei_dotgat_backward_workspace")
+        self.ws.ensure(need.value)
+        _check(lib().sensei_dotgat_backward(self._h, ctypes.byref(A), ctypes.byref(At), _ptr(t_pos), mat_struct(X), mat_struct(W_q), mat_struct(W_k),
+                                            mat_struct(W_v), scale, _ptr(Y), mat_struct(Y).ld if Y is not None else 0, mat_struct(dY), activation,
+                                            _ptr(dX), mat_struct(dX).ld if dX is not None else 0, _ptr(dWq), mat_struct(dWq).ld, _ptr(dWk),
+                                            mat_struct(dWk).ld, _ptr(dWv), mat_struct(dWv).ld, self.ws.ptr, self.ws.nbytes, _stream()),
+               "sensei_dotgat_backward")
+        return dX, dWq, dWk, dWv
 
     def select_gcn_backward(self, A: CsrStruct, f_in, f_out, have_saved_u=False, want_dx=True):
         pick = ctypes.c_int()

@@ -1032,6 +1032,100 @@ int run_dotgat(const sensei_csr &A, const sensei_mat &X, const sensei_mat &Wq, c
     return SENSEI_OK;
 }
 
+// ---- backward of the key-query attention layer.  With dP = dY (.) [Y > 0], e_ij = scale <Q_i, K_j>, alpha the row softmax of e:
+//   dV_j = sum_i alpha_ij dP_i,  dalpha_ij = <dP_i, V_j>,  de_ij = alpha_ij (dalpha_ij - sum_k alpha_ik dalpha_ik),
+//   dQ_i = scale sum_j de_ij K_j,  dK_j = scale sum_i de_ij Q_i,
+//   dW_q = X_dst^T dQ,  dW_k = X^T dK,  dW_v = X^T dV,  dX = dK W_k^T + dV W_v^T + [dQ W_q^T on the first n_rows rows].
+// Every step is a kernel the other layers already use: the per-entry dot products and the softmax backward of the GAT backward, weighted
+// SpMMs over the pattern (dQ) and its transpose (dK, dV).
+size_t dotgat_bwd_ws(const sensei_csr &A, int f_in, int d_k, int f_out) {
+    const size_t nz = (size_t)(A.nnz > 0 ? A.nnz : 1), dk = pad32(d_k), fo = pad32(f_out), dk4 = pad4(d_k), fo4 = pad4(f_out), fi4 = pad4(f_in);
+    const int t = choose_chunk_nnz(A.nnz);
+    const size_t n_chunks = A.nnz <= 0 ? 1 : (size_t)((A.nnz + t - 1) / t);
+    const size_t ldd = 2 * dk4 + fo4;
+    size_t b = 2 * plan_bytes(A.nnz) + softmax_ws_bytes(A) + 1024;
+    b += 2 * align_up(nz * sizeof(float), 256) + align_up(nz * sizeof(float2), 256);   // logits, dalpha / de, (alpha, de) transposed
+    b += align_up((size_t)(A.n_rows + 1) * sizeof(float), 256) + align_up(n_chunks * sizeof(float), 256);   // row dots and their carry
+    b += align_up((size_t)A.n_rows * dk * sizeof(float), 256) + align_up((size_t)A.n_cols * dk * sizeof(float), 256);   // Q, K (slice-major)
+    b += align_up((size_t)A.n_cols * fo * sizeof(float), 256) + align_up((size_t)A.n_rows * fo * sizeof(float), 256);   // V, dP (slice-major)
+    b += align_up((size_t)A.n_cols * ldd * sizeof(float), 256);                        // [dK | dV | dQ]
+    b += align_up(dk * sizeof(float), 256);                                            // the scale, once per column
+    b += spmm_carry_bytes(A.nnz, (int)(fo > dk ? fo : dk));
+    b += align_up(ldd * fi4 * sizeof(float), 256);                                     // [W_k^T; W_v^T; W_q^T]
+    b += gemm_tn_bytes(A.n_cols, f_in, f_out > d_k ? f_out : d_k);
+    return b;
+}
+
+int run_dotgat_backward(const sensei_csr &A_in, const sensei_csr &At_in, const int32_t *t_pos, const sensei_mat &X, const sensei_mat &Wq,
+                        const sensei_mat &Wk, const sensei_mat &Wv, float scale, const float *Y, int64_t ldy, const sensei_mat &dY, int act,
+                        float *dX, int64_t lddx, float *dWq, int64_t lddwq, float *dWk, int64_t lddwk, float *dWv, int64_t lddwv, void *ws,
+                        size_t ws_bytes, hipStream_t s) {
+    sensei_csr A = A_in, At = At_in;   // plain walks: no column panels, no tile split
+    A.panels = nullptr; A.tiles = nullptr; At.panels = nullptr; At.tiles = nullptr;
+    const int f_in = (int)X.cols, d_k = (int)Wq.cols, f_out = (int)Wv.cols;
+    const int dk = pad32(d_k), fo = pad32(f_out), dk4 = pad4(d_k), fo4 = pad4(f_out), fi4 = pad4(f_in);
+    const int64_t ldd = 2 * (int64_t)dk4 + fo4;
+    const size_t nz = (size_t)(A.nnz > 0 ? A.nnz : 1);
+    Carver cv(ws, ws_bytes);
+    ChunkPlan plan = make_plan(A, cv), plan_t = make_plan(At, cv);
+    float2 *stats = cv.take<float2>((size_t)A.n_rows + 1);
+    float2 *carry_stats = cv.take<float2>((size_t)plan.n_chunks);
+    float *logits = cv.take<float>(nz);
+    float *de = cv.take<float>(nz);
+    float2 *ade_t = cv.take<float2>(nz);
+    float *rowdot = cv.take<float>((size_t)A.n_rows + 1);
+    float *sum_carry = cv.take<float>((size_t)plan.n_chunks);
+    float *Q = cv.take<float>((size_t)A.n_rows * dk);
+    float *K = cv.take<float>((size_t)A.n_cols * dk);
+    float *V = cv.take<float>((size_t)A.n_cols * fo);
+    float *dPs = cv.take<float>((size_t)A.n_rows * fo);
+    float *Dcat = cv.take<float>((size_t)A.n_cols * ldd);
+    float *scale_vec = cv.take<float>((size_t)dk);
+    float *carry = cv.take<float>(spmm_carry_bytes(A.nnz, fo > dk ? fo : dk) / sizeof(float));
+    float *Wcat = cv.take<float>((size_t)ldd * fi4);
+    double *part = cv.take<double>(gemm_tn_bytes(A.n_cols, f_in, f_out > d_k ? f_out : d_k) / sizeof(double));
+    float *dK = Dcat, *dV = Dcat + dk4, *dQ = Dcat + dk4 + fo4;
+
+    SENSEI_TRY(launch_chunk_rows(A, plan, s));
+    SENSEI_TRY(launch_chunk_rows(At, plan_t, s));
+    // forward quantities
+    SENSEI_TRY(launch_gemm(X.ptr, X.ld, Wq.ptr, Wq.ld, Q, dk, A.n_rows, f_in, d_k, dk, SENSEI_ACT_NONE, s, nullptr, nullptr, true));
+    SENSEI_TRY(launch_gemm(X.ptr, X.ld, Wk.ptr, Wk.ld, K, dk, A.n_cols, f_in, d_k, dk, SENSEI_ACT_NONE, s, nullptr, nullptr, true));
+    SENSEI_TRY(launch_gemm(X.ptr, X.ld, Wv.ptr, Wv.ld, V, fo, A.n_cols, f_in, f_out, fo, SENSEI_ACT_NONE, s, nullptr, nullptr, true));
+    SENSEI_TRY(launch_gat_dalpha(A, K, Q, d_k, nullptr, nullptr, logits, nullptr, plan, nullptr, s, scale));
+    SENSEI_TRY(launch_softmax(A, logits, de, plan, stats, carry_stats, s));   // the weights it writes are not kept: de is overwritten below
+    SENSEI_TRY(launch_to_slices(nullptr, dY.ptr, dY.ld, A.n_rows, f_out, dPs, s, act == SENSEI_ACT_RELU ? Y : nullptr, ldy));
+    // per stored entry: dalpha and its weighted row sums, then the softmax backward; alpha and de also in transposed order
+    SENSEI_TRY(launch_gat_dalpha(A, V, dPs, f_out, logits, stats, de, rowdot, plan, sum_carry, s));
+    SENSEI_TRY(launch_gat_dt(A, logits, de, rowdot, stats, t_pos, 1.f, de, ade_t, plan, s));
+    SENSEI_TRY(launch_zero_matrix(Dcat, A.n_cols, (int)ldd, ldd, false, s));   // pad columns; the rows of dQ past the destinations
+    SENSEI_TRY(launch_zero_matrix(Wcat, ldd, fi4, fi4, false, s));
+    sensei_csr Aw = At;
+    Aw.val = reinterpret_cast<const float *>(ade_t);
+    SENSEI_TRY(launch_spmm(Aw, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, dPs, fo, f_out, dV, ldd, f_out, SENSEI_ACT_NONE, plan_t, carry, s, nullptr, false, true,
+                           nullptr, true, 2));
+    Aw.val = reinterpret_cast<const float *>(ade_t) + 1;
+    SENSEI_TRY(launch_spmm(Aw, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, Q, dk, d_k, dK, ldd, d_k, SENSEI_ACT_NONE, plan_t, carry, s, nullptr, false, true,
+                           nullptr, true, 2));
+    sensei_csr Ae = A;
+    Ae.val = de;
+    SENSEI_TRY(launch_spmm(Ae, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, K, dk, d_k, dQ, ldd, d_k, SENSEI_ACT_NONE, plan, carry, s, nullptr, false, true,
+                           nullptr, true, 1));
+    SENSEI_TRY(launch_fill_f32(scale_vec, d_k, scale, s));
+    SENSEI_TRY(launch_scale_cols(dK, ldd, dK, ldd, scale_vec, A.n_cols, d_k, false, s));
+    SENSEI_TRY(launch_scale_cols(dQ, ldd, dQ, ldd, scale_vec, A.n_rows, d_k, false, s));
+    SENSEI_TRY(launch_gemm_tn(X.ptr, X.ld, dK, ldd, A.n_cols, f_in, d_k, dWk, lddwk, part, s));
+    SENSEI_TRY(launch_gemm_tn(X.ptr, X.ld, dV, ldd, A.n_cols, f_in, f_out, dWv, lddwv, part, s));
+    SENSEI_TRY(launch_gemm_tn(X.ptr, X.ld, dQ, ldd, A.n_rows, f_in, d_k, dWq, lddwq, part, s));
+    if (dX) {
+        SENSEI_TRY(launch_transpose(Wk.ptr, Wk.ld, f_in, d_k, Wcat, fi4, s));
+        SENSEI_TRY(launch_transpose(Wv.ptr, Wv.ld, f_in, f_out, Wcat + (size_t)dk4 * fi4, fi4, s));
+        SENSEI_TRY(launch_transpose(Wq.ptr, Wq.ld, f_in, d_k, Wcat + (size_t)(dk4 + fo4) * fi4, fi4, s));
+        SENSEI_TRY(launch_gemm(Dcat, ldd, Wcat, fi4, dX, lddx, A.n_cols, (int)ldd, f_in, f_in, SENSEI_ACT_NONE, s));
+    }
+    return SENSEI_OK;
+}
+
 // ---- backward of the GAT layer
 // The per-entry dot products of the attention backward can use the dense-tile split of A: same pattern, wide enough, and
 // every tile cell addressable by the (negative) codes in dst_rem.  Below 128 columns the extra pass that merges the two
@@ -2467,6 +2561,48 @@ int sensei_dotgat_layer(sensei_ctx *ctx, const sensei_csr *A, sensei_mat X, sens
     if (ws_bytes < dotgat_ws(*A, (int)X.cols, (int)W_q.cols, (int)W_v.cols, comp_id)) return SENSEI_WORKSPACE_TOO_SMALL;
     if (A->n_rows == 0) return SENSEI_OK;
     return run_dotgat(*A, X, W_q, W_k, W_v, scale, Y, ldy, activation, comp_id, workspace, ws_bytes, as_stream(stream), &ctx->timers);
+}
+
+int sensei_dotgat_backward_workspace(const sensei_csr *A, int f_in, int d_k, int f_out, size_t *bytes) {
+    if (!csr_ok(A, false) || f_in <= 0 || d_k <= 0 || f_out <= 0 || !bytes) return SENSEI_INVALID_ARGUMENT;
+    *bytes = dotgat_bwd_ws(*A, f_in, d_k, f_out);
+    return SENSEI_OK;
+}
+
+int sensei_dotgat_backward(sensei_ctx *ctx, const sensei_csr *A, const sensei_csr *At, const int32_t *t_pos, sensei_mat X, sensei_mat W_q,
+                           sensei_mat W_k, sensei_mat W_v, float scale, const float *Y, int64_t ldy, sensei_mat dY, int activation, float *dX,
+                           int64_t lddx, float *dW_q, int64_t lddwq, float *dW_k, int64_t lddwk, float *dW_v, int64_t lddwv, void *workspace,
+                           size_t ws_bytes, void *stream) {
+    if (!ctx || !csr_ok(A, false) || !csr_ok(At, false) || !mat_ok(X) || !mat_ok(W_q) || !mat_ok(W_k) || !mat_ok(W_v) || !mat_ok(dY))
+        return SENSEI_INVALID_ARGUMENT;
+    if (At->n_rows != A->n_cols || At->n_cols != A->n_rows || At->nnz != A->nnz || A->n_rows > A->n_cols) return SENSEI_INVALID_ARGUMENT;
+    if (activation != SENSEI_ACT_NONE && activation != SENSEI_ACT_RELU) return SENSEI_INVALID_ARGUMENT;
+    if (X.rows != A->n_cols || X.cols <= 0 || W_q.rows != X.cols || W_k.rows != X.cols || W_v.rows != X.cols || W_q.cols <= 0 ||
+        W_q.cols != W_k.cols || W_v.cols <= 0)
+        return SENSEI_INVALID_ARGUMENT;
+    if (X.cols > (1 << 20) || W_q.cols > (1 << 18) || W_v.cols > (1 << 18)) return SENSEI_INVALID_ARGUMENT;
+    if (dY.rows != A->n_rows || dY.cols != W_v.cols) return SENSEI_INVALID_ARGUMENT;
+    if ((!X.ptr && A->n_cols > 0) || !W_q.ptr || !W_k.ptr || !W_v.ptr || (!dY.ptr && A->n_rows > 0) || !dW_q || !dW_k || !dW_v || !workspace)
+        return SENSEI_INVALID_ARGUMENT;
+    if (!t_pos && A->nnz > 0) return SENSEI_INVALID_ARGUMENT;
+    if (lddwq < W_q.cols || lddwk < W_k.cols || lddwv < W_v.cols || (dX && lddx < X.cols)) return SENSEI_INVALID_ARGUMENT;
+    if (activation == SENSEI_ACT_RELU && ((!Y && A->n_rows > 0) || ldy < W_v.cols)) return SENSEI_INVALID_ARGUMENT;
+    struct Buf { const void *p; size_t n; };
+    const Buf ins[5] = {{X.ptr, mat_bytes(X.ptr, X.rows, X.cols, X.ld)}, {dY.ptr, mat_bytes(dY.ptr, dY.rows, dY.cols, dY.ld)},
+                        {W_q.ptr, mat_bytes(W_q.ptr, W_q.rows, W_q.cols, W_q.ld)}, {W_k.ptr, mat_bytes(W_k.ptr, W_k.rows, W_k.cols, W_k.ld)},
+                        {W_v.ptr, mat_bytes(W_v.ptr, W_v.rows, W_v.cols, W_v.ld)}};
+    const Buf outs[4] = {{dW_q, mat_bytes(dW_q, W_q.rows, W_q.cols, lddwq)}, {dW_k, mat_bytes(dW_k, W_k.rows, W_k.cols, lddwk)},
+                         {dW_v, mat_bytes(dW_v, W_v.rows, W_v.cols, lddwv)}, {dX, dX ? mat_bytes(dX, A->n_cols, X.cols, lddx) : 0}};
+    for (int a = 0; a < 4; ++a) {
+        if (overlap(outs[a].p, outs[a].n, workspace, ws_bytes)) return SENSEI_INVALID_ARGUMENT;
+        for (int b = 0; b < 5; ++b)
+            if (overlap(outs[a].p, outs[a].n, ins[b].p, ins[b].n)) return SENSEI_INVALID_ARGUMENT;
+        for (int b = a + 1; b < 4; ++b)
+            if (overlap(outs[a].p, outs[a].n, outs[b].p, outs[b].n)) return SENSEI_INVALID_ARGUMENT;
+    }
+    if (ws_bytes < dotgat_bwd_ws(*A, (int)X.cols, (int)W_q.cols, (int)W_v.cols)) return SENSEI_WORKSPACE_TOO_SMALL;
+    return run_dotgat_backward(*A, *At, t_pos, X, W_q, W_k, W_v, scale, Y, ldy, dY, activation, dX, lddx, dW_q, lddwq, dW_k, lddwk, dW_v, lddwv,
+                               workspace, ws_bytes, as_stream(stream));
 }
 
 int sensei_select_workspace(int kind, const sensei_csr *A, int f_in, int f_out, size_t *bytes) {

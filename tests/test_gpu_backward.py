@@ -658,3 +658,70 @@ def test_gatv2_backward_argument_checks(ctx):
     with pytest.raises(RuntimeError):
         ctx.gatv2_backward(A.s, DeviceCSR(g2).s, pos, X, W, W, att, dY)                              # transposed pattern of another shape
     torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ key-query attention
+
+def _kq_inputs(g, f_in, d_k, f_out, seed):
+    X = synth.uniform(seed, 10, (g.n_cols, f_in))
+    W_q, W_k, W_v = synth.glorot(seed, 14, f_in, d_k), synth.glorot(seed, 15, f_in, d_k), synth.glorot(seed, 16, f_in, f_out)
+    dY = synth.normal(seed, 12, (g.n_rows, f_out), 0.0, 1.0)
+    return X, W_q, W_k, W_v, dY
+
+
+@pytest.mark.parametrize("name", sorted(GRAPHS))
+@pytest.mark.parametrize("widths", [(40, 16, 24), (24, 40, 40), (70, 33, 41), (20, 64, 7)])
+@pytest.mark.parametrize("act", [ACT_NONE, ACT_RELU])
+def test_key_query_attention_backward_matches_chain_rule(ctx, name, widths, act):
+    g = GRAPHS[name]()
+    gt = synth.transpose(g)
+    f_in, d_k, f_out = widths
+    X, W_q, W_k, W_v, dY = _kq_inputs(g, f_in, d_k, f_out, 190 + f_in)
+    scale = 1.0 / np.sqrt(d_k)
+    Y = None
+    if act == ACT_RELU:
+        Y = oracle.dotgat_layer(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W_q, W_k, W_v, scale, 1).astype(np.float32)
+    want = oracle.dotgat_backward(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W_q, W_k, W_v, scale, dY, Y=Y, act=act)
+    A, At = DeviceCSR(g), DeviceCSR(gt)
+    pos = ctx.transpose_positions(A.s, At.s)
+    got = ctx.dotgat_backward(A.s, At.s, pos, dev(X), dev(W_q), dev(W_k), dev(W_v), float(scale), dev(dY), Y=None if Y is None else dev(Y),
+                              activation=act)
+    for gpu, ref, what in zip(got, want, ("dX", "dW_q", "dW_k", "dW_v")):
+        assert_close(gpu, ref, what=what)
+
+
+def test_key_query_attention_backward_large_graph_strides_and_weight_gradients_only(ctx):
+    g = synth.rmat(192, 20_000, 2_000_000)
+    f_in, d_k, f_out = 32, 16, 48
+    X, W_q, W_k, W_v, dY = _kq_inputs(g, f_in, d_k, f_out, 193)
+    Y = oracle.dotgat_layer(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W_q, W_k, W_v, 0.25, 1).astype(np.float32)
+    want = oracle.dotgat_backward(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W_q, W_k, W_v, 0.25, dY, Y=Y, act=1)
+    A = DeviceCSR(g)
+    pos = ctx.transpose_positions(A.s, A.s)
+    Xs = torch.zeros((g.n_cols, f_in + 3), device="cuda:0")
+    Xs[:, :f_in] = dev(X)
+    dYs = torch.zeros((g.n_rows, f_out + 4), device="cuda:0")
+    dYs[:, :f_out] = dev(dY)
+    got = ctx.dotgat_backward(A.s, A.s, pos, Xs[:, :f_in], dev(W_q), dev(W_k), dev(W_v), 0.25, dYs[:, :f_out], Y=dev(Y), activation=ACT_RELU)
+    for gpu, ref, what in zip(got, want, ("dX", "dW_q", "dW_k", "dW_v")):
+        assert_close(gpu, ref, what=what)
+    none, dWq, dWk, dWv = ctx.dotgat_backward(A.s, A.s, pos, dev(X), dev(W_q), dev(W_k), dev(W_v), 0.25, dev(dY), Y=dev(Y), activation=ACT_RELU,
+                                              want_dx=False)
+    assert none is None and torch.equal(dWq, got[1]) and torch.equal(dWk, got[2]) and torch.equal(dWv, got[3])
+
+
+def test_key_query_attention_backward_argument_checks(ctx):
+    g = synth.erdos_renyi(47, 200, 600)
+    A = DeviceCSR(g)
+    pos = ctx.transpose_positions(A.s, A.s)
+    X, Wq, Wv, dY = (torch.zeros(s, device="cuda:0") for s in ((200, 8), (8, 3), (8, 4), (200, 4)))
+    ctx.dotgat_backward(A.s, A.s, pos, X, Wq, Wq, Wv, 0.5, dY)
+    with pytest.raises(RuntimeError):
+        ctx.dotgat_backward(A.s, A.s, pos, X, Wq, torch.zeros((8, 5), device="cuda:0"), Wv, 0.5, dY)      # queries and keys differ in width
+    with pytest.raises(RuntimeError):
+        ctx.dotgat_backward(A.s, A.s, pos, X, Wq, Wq, Wv, 0.5, dY, activation=ACT_RELU)                   # ReLU without the forward output
+    with pytest.raises(RuntimeError):
+        ctx.dotgat_backward(A.s, A.s, None, X, Wq, Wq, Wv, 0.5, dY)                                        # no transposition map
+    with pytest.raises(RuntimeError):
+        ctx.dotgat_backward(A.s, A.s, pos, X, Wq, Wq, Wv, 0.5, torch.zeros((200, 5), device="cuda:0"))    # dY of another width
+    torch.cuda.synchronize()
