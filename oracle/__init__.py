@@ -476,6 +476,26 @@ def gat_backward(n_rows, n_cols, row_ptr, col_idx, X, W, a_l, a_r, dY, Y=None, s
     return (dX, dW, dal, dar, dTh, ds[:n_cols], ds[n_cols:]) if with_dtheta else (dX, dW, dal, dar)
 
 
+def gat_backward_heads(n_rows, n_cols, row_ptr, col_idx, X, W, a_l, a_r, n_heads, dY, Y=None, slope=0.2, act=0, omp=False):
+    """Gradient of sum(dY * Y) for the multi-head layer of gat_layer_heads -> (dX, dW, da_l, da_r).  The heads share only the input:
+    head h is the single-head layer on columns [h d, (h + 1) d), so its gradients with respect to its own columns of W, a_l, a_r
+    are those of that layer for its columns of dY, and dX is the sum of the heads' input gradients."""
+    W, a_l, a_r, dY = _f32(W), _f32(a_l), _f32(a_r), _f32(dY)
+    assert W.shape[1] % n_heads == 0
+    d = W.shape[1] // n_heads
+    dX = np.zeros((n_cols, W.shape[0]), dtype=np.float64)
+    dW = np.empty(W.shape, dtype=np.float64)
+    dal, dar = np.empty(W.shape[1], dtype=np.float64), np.empty(W.shape[1], dtype=np.float64)
+    for h in range(n_heads):
+        c = slice(h * d, (h + 1) * d)
+        Yh = None if Y is None else np.ascontiguousarray(_f32(Y)[:, c])
+        gx, gw, gl, gr = gat_backward(n_rows, n_cols, row_ptr, col_idx, X, np.ascontiguousarray(W[:, c]), a_l[c], a_r[c],
+                                      np.ascontiguousarray(dY[:, c]), Y=Yh, slope=slope, act=act, omp=omp)
+        dX += gx
+        dW[:, c], dal[c], dar[c] = gw, gl, gr
+    return dX, dW, dal, dar
+
+
 # ------------------------------------------------------------- re-associations
 
 GCN_COMPOSITIONS = ("DYN_AGG", "DYN_UPD", "DYNF_AGG", "DYNF_UPD", "PRE_AGG", "PRE_UPD")

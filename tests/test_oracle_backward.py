@@ -473,3 +473,42 @@ def test_key_query_attention_backward_special_cases():
     _close(z[2], np.zeros_like(z[2]), 1e-13)
     _close(z[3], X64.T @ (M.T @ d64), 1e-12)
     _close(z[0], (M.T @ d64) @ Wv.T, 1e-12)
+
+
+# ------------------------------------------------------------------ multi-head GAT
+
+def test_multi_head_gat_backward_is_the_gradient_of_the_forward():
+    g = synth.rmat(91, 10, 22)
+    f_in, f_out, heads, h = 3, 4, 2, 2.0 ** -11
+    for seed in range(91, 191):   # first seed whose logits, in every head, stay clear of the LeakyReLU kink
+        rng = np.random.default_rng(seed)
+        X, W, dY = _grid(rng, (10, f_in)), _grid(rng, (f_in, f_out)), _grid(rng, (10, f_out))
+        a_l, a_r = _grid(rng, (f_out,)), _grid(rng, (f_out,))
+        Th = X.astype(np.float64) @ W.astype(np.float64)
+        d = f_out // heads
+        t = []
+        for k in range(heads):
+            sl, sr = Th[:, k * d:(k + 1) * d] @ a_l[k * d:(k + 1) * d], Th[:, k * d:(k + 1) * d] @ a_r[k * d:(k + 1) * d]
+            t += [sl[i] + sr[g.col_idx[g.row_ptr[i]:g.row_ptr[i + 1]]] for i in range(10)]
+        if np.min(np.abs(np.concatenate(t))) > 8 * h:
+            break
+    else:
+        raise AssertionError("no seed keeps the logits away from zero")
+
+    def loss():
+        return float(np.sum(dY.astype(np.float64) * oracle.gat_layer_heads(10, 10, g.row_ptr, g.col_idx, X, W, a_l, a_r, heads, 0.2, 0)))
+
+    got = oracle.gat_backward_heads(10, 10, g.row_ptr, g.col_idx, X, W, a_l, a_r, heads, dY)
+    for grad, x in zip(got, (X, W, a_l, a_r)):
+        _close(grad, _richardson(loss, x, h), 1e-7)
+    # one head is the single-head layer
+    one = oracle.gat_backward_heads(10, 10, g.row_ptr, g.col_idx, X, W, a_l, a_r, 1, dY)
+    ref = oracle.gat_backward(10, 10, g.row_ptr, g.col_idx, X, W, a_l, a_r, dY)
+    for a, b in zip(one, ref):
+        _close(a, b, 1e-14)
+    # a head's parameters do not feel the other head's output gradient
+    dY2 = dY.copy()
+    dY2[:, d:] = 0
+    part = oracle.gat_backward_heads(10, 10, g.row_ptr, g.col_idx, X, W, a_l, a_r, heads, dY2)
+    _close(part[1][:, :d], got[1][:, :d], 1e-14)
+    _close(part[1][:, d:], np.zeros((f_in, d)), 1e-14)
