@@ -171,6 +171,16 @@ int sensei_gat_backward(sensei_ctx *ctx, const sensei_csr *A, const sensei_csr *
                         float *dX, int64_t lddx, float *dW, int64_t lddw, float *da_l, float *da_r, void *workspace, size_t ws_bytes,
                         void *stream);
 
+/* Backward of the multi-head layer sensei_gat_layer_heads (heads concatenated; they share only the input): head h is the single-head
+ * layer on columns [h d, (h + 1) d) of W, a_l, a_r and Y, d = f_out / n_heads, so dW, da_l and da_r hold the heads' gradients in the
+ * same columns and dX is the sum over the heads; the products with X and W are formed once for all heads.  Arguments, aliasing rules
+ * and error codes as for sensei_gat_backward; n_heads must divide f_out. */
+int sensei_gat_backward_heads_workspace(const sensei_csr *A, const sensei_csr *At, int f_in, int f_out, int n_heads, size_t *bytes);
+int sensei_gat_backward_heads(sensei_ctx *ctx, const sensei_csr *A, const sensei_csr *At, const int32_t *t_pos, sensei_mat X, sensei_mat W,
+                              const float *a_l, const float *a_r, int n_heads, float neg_slope, const float *Y, int64_t ldy, sensei_mat dY,
+                              int activation, float *dX, int64_t lddx, float *dW, int64_t lddw, float *da_l, float *da_r, void *workspace,
+                              size_t ws_bytes, void *stream);
+
 /* Backward of the layer sensei_gatv2_layer (the GATv2 variant named with the attention variants of the paper's discussion; training as in
  * its evaluation section).  With dP = dY (.) [Y > 0], Theta_l = X_dst W_l, Theta_r = X W_r, U_ij = Theta_l[i] + Theta_r[j],
  * e_ij = att . LeakyReLU(U_ij) and alpha the row softmax of e (Eq. 5 with this score):

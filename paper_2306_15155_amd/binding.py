@@ -31,7 +31,7 @@ EXPORTS = (
     "sensei_select", "sensei_profile_enable", "sensei_profile_read", "sensei_panels_bytes", "sensei_panels_create",
     "sensei_panels_count", "sensei_panels_destroy", "sensei_panels_set_min_width", "sensei_panels_tune_bytes",
     "sensei_panels_tune", "sensei_gcn_backward_workspace", "sensei_gcn_backward", "sensei_select_gcn_backward", "sensei_transpose_positions",
-    "sensei_gat_backward_workspace", "sensei_gat_backward", "sensei_gat_layer_heads", "sensei_sgc_workspace", "sensei_sgc_layer", "sensei_sgc_backward_workspace", "sensei_sgc_backward", "sensei_tagcn_workspace", "sensei_tagcn_layer", "sensei_tagcn_backward_workspace", "sensei_tagcn_backward", "sensei_gatv2_workspace", "sensei_gatv2_layer", "sensei_gatv2_backward_workspace", "sensei_gatv2_backward", "sensei_dotgat_workspace", "sensei_dotgat_layer", "sensei_dotgat_backward_workspace", "sensei_dotgat_backward", "sensei_tiles_remainder_panels", "sensei_tiles_bytes", "sensei_tiles_create", "sensei_tiles_info",
+    "sensei_gat_backward_workspace", "sensei_gat_backward", "sensei_gat_backward_heads_workspace", "sensei_gat_backward_heads", "sensei_gat_layer_heads", "sensei_sgc_workspace", "sensei_sgc_layer", "sensei_sgc_backward_workspace", "sensei_sgc_backward", "sensei_tagcn_workspace", "sensei_tagcn_layer", "sensei_tagcn_backward_workspace", "sensei_tagcn_backward", "sensei_gatv2_workspace", "sensei_gatv2_layer", "sensei_gatv2_backward_workspace", "sensei_gatv2_backward", "sensei_dotgat_workspace", "sensei_dotgat_layer", "sensei_dotgat_backward_workspace", "sensei_dotgat_backward", "sensei_tiles_remainder_panels", "sensei_tiles_bytes", "sensei_tiles_create", "sensei_tiles_info",
            "sensei_tiles_set_min_width", "sensei_tiles_destroy",
 )
 
@@ -101,6 +101,9 @@ def lib():
         L.sensei_dotgat_backward_workspace.argtypes = [P(CsrStruct), i32, i32, i32, P(sz)]
         L.sensei_dotgat_backward.argtypes = [vp, P(CsrStruct), P(CsrStruct), vp, MatStruct, MatStruct, MatStruct, MatStruct, f32, vp, i64, MatStruct, i32,
                                              vp, i64, vp, i64, vp, i64, vp, i64, vp, sz, vp]
+        L.sensei_gat_backward_heads_workspace.argtypes = [P(CsrStruct), P(CsrStruct), i32, i32, i32, P(sz)]
+        L.sensei_gat_backward_heads.argtypes = [vp, P(CsrStruct), P(CsrStruct), vp, MatStruct, MatStruct, vp, vp, i32, f32, vp, i64, MatStruct, i32,
+                                                vp, i64, vp, i64, vp, vp, vp, sz, vp]
         L.sensei_gat_workspace.argtypes = [P(CsrStruct), i32, i32, i32, P(sz)]
         L.sensei_gat_attention_path.argtypes = [P(CsrStruct), i32, i32, i32, i32]
         L.sensei_gat_layer.argtypes = [vp, P(CsrStruct), MatStruct, MatStruct, vp, vp, f32, vp, i64, i32, i32, vp, sz, vp]
@@ -458,6 +461,24 @@ class Context:
                                          _ptr(a_r), neg_slope, _ptr(Y), mat_struct(Y).ld if Y is not None else 0, mat_struct(dY), activation,
                                          _ptr(dX), mat_struct(dX).ld if dX is not None else 0, _ptr(dW), mat_struct(dW).ld, _ptr(dal),
                                          _ptr(dar), self.ws.ptr, self.ws.nbytes, _stream()), "sensei_gat_backward")
+        return dX, dW, dal, dar
+
+    def gat_backward_heads(self, A: CsrStruct, At: CsrStruct, t_pos, X, W, a_l, a_r, n_heads, dY, Y=None, neg_slope=0.2, activation=ACT_NONE,
+                           want_dx=True):
+        """Backward of gat_layer_heads -> (dX or None, dW, da_l, da_r)."""
+        f_in, f_out = W.size(0), W.size(1)
+        dX = torch.empty((A.n_cols, f_in), dtype=torch.float32, device=self.device) if want_dx else None
+        dW = torch.empty((f_in, f_out), dtype=torch.float32, device=self.device)
+        dal = torch.empty(f_out, dtype=torch.float32, device=self.device)
+        dar = torch.empty(f_out, dtype=torch.float32, device=self.device)
+        need = ctypes.c_size_t()
+        _check(lib().sensei_gat_backward_heads_workspace(ctypes.byref(A), ctypes.byref(At), f_in, f_out, n_heads, ctypes.byref(need)),
+               "sensei_gat_backward_heads_workspace")
+        self.ws.ensure(need.value)
+        _check(lib().sensei_gat_backward_heads(self._h, ctypes.byref(A), ctypes.byref(At), _ptr(t_pos), mat_struct(X), mat_struct(W), _ptr(a_l),
+                                               _ptr(a_r), n_heads, neg_slope, _ptr(Y), mat_struct(Y).ld if Y is not None else 0, mat_struct(dY),
+                                               activation, _ptr(dX), mat_struct(dX).ld if dX is not None else 0, _ptr(dW), mat_struct(dW).ld,
+                                               _ptr(dal), _ptr(dar), self.ws.ptr, self.ws.nbytes, _stream()), "sensei_gat_backward_heads")
         return dX, dW, dal, dar
 
     def gatv2_backward(self, A: CsrStruct, At: CsrStruct, t_pos, X, W_l, W_r, att, dY, Y=None, neg_slope=0.2, activation=ACT_NONE, want_dx=True):

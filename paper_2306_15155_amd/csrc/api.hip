@@ -1173,7 +1173,10 @@ size_t gat_bwd_ws(const sensei_csr &A, const sensei_csr *At, int f_in, int f_out
 
 int run_gat_backward(const sensei_csr &A, const sensei_csr &At, const int32_t *t_pos, const sensei_mat &X, const sensei_mat &W,
                      const float *a_l, const float *a_r, float slope, const float *Y, int64_t ldy, const sensei_mat &dY, int act, float *dX,
-                     int64_t lddx, float *dW, int64_t lddw, float *da_l, float *da_r, void *ws, size_t ws_bytes, hipStream_t s) {
+                     int64_t lddx, float *dW, int64_t lddw, float *da_l, float *da_r, void *ws, size_t ws_bytes, hipStream_t s,
+                     float *dtheta_out = nullptr, int64_t ld_dtheta = 0) {
+    // dtheta_out (one head of a multi-head layer): dTheta is left there (row-major, ld_dtheta) and the products with X and W, which the
+    // caller forms once for all heads, are skipped
     const int f_in = (int)X.cols, f_out = (int)W.cols;
     const int fo32 = pad32(f_out), fo4 = pad4(f_out), fi4 = pad4(f_in);
     const size_t nz = (size_t)(A.nnz > 0 ? A.nnz : 1);
@@ -1192,7 +1195,9 @@ int run_gat_backward(const sensei_csr &A, const sensei_csr &At, const int32_t *t
     float *sum_carry = cv.take<float>((size_t)plan.n_chunks);
     float *ds_l = cv.take<float>((size_t)A.n_cols + 1);
     float *ds_r = cv.take<float>((size_t)A.n_cols + 1);
-    float *dTheta = cv.take<float>((size_t)A.n_cols * fo4);
+    float *dTheta_own = cv.take<float>((size_t)A.n_cols * fo4);
+    float *dTheta = dtheta_out ? dtheta_out : dTheta_own;
+    const int64_t ldt = dtheta_out ? ld_dtheta : fo4;
     float *carry = cv.take<float>(spmm_carry_bytes(A.nnz, fo32) / sizeof(float));
     float *Wt = cv.take<float>((size_t)fo4 * fi4);
     double *part = cv.take<double>(gemm_tn_bytes(A.n_cols, f_in, f_out) / sizeof(double));
@@ -1258,28 +1263,65 @@ int run_gat_backward(const sensei_csr &A, const sensei_csr &At, const int32_t *t
             SENSEI_TRY(launch_spmm(Ar, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, T, fo32, fo32, D.part_pm, 32, fo32, SENSEI_ACT_NONE, D.plan_pm, carry, s,
                                    nullptr, false, false, nullptr, true, 1, true, true));
             SENSEI_TRY(hipStreamWaitEvent(s, D.ev_join, 0));
-            SENSEI_TRY(launch_tiles_combine_pm(D.T, dTheta, At.n_rows, f_out, fo4, false, fo32, nullptr, nullptr, SENSEI_ACT_NONE, s, D.part_pm,
+            SENSEI_TRY(launch_tiles_combine_pm(D.T, dTheta, At.n_rows, f_out, ldt, false, fo32, nullptr, nullptr, SENSEI_ACT_NONE, s, D.part_pm,
                                                D.rem_panels, D.seg_ptr, D.plan_pm.chunk_nnz, carry, fo32));
         } else {
-            SENSEI_TRY(launch_spmm(Ar, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, T, fo32, f_out, dTheta, fo4, f_out, SENSEI_ACT_NONE, D.plan_rem, carry, s,
+            SENSEI_TRY(launch_spmm(Ar, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, T, fo32, f_out, dTheta, ldt, f_out, SENSEI_ACT_NONE, D.plan_rem, carry, s,
                                    nullptr, false, false, nullptr, true, 1, false, true));
             SENSEI_TRY(hipStreamWaitEvent(s, D.ev_join, 0));
-            SENSEI_TRY(launch_tiles_combine(D.T, dTheta, At.n_rows, f_out, fo4, false, fo32, nullptr, nullptr, SENSEI_ACT_NONE, s, D.row_ptr_rem,
+            SENSEI_TRY(launch_tiles_combine(D.T, dTheta, At.n_rows, f_out, ldt, false, fo32, nullptr, nullptr, SENSEI_ACT_NONE, s, D.row_ptr_rem,
                                             D.plan_rem.chunk_nnz, carry, fo32));
         }
     } else {
         sensei_csr Aw = At;
         Aw.val = reinterpret_cast<const float *>(adt_t);
         Aw.panels = nullptr;  // the values follow the order of At itself
-        SENSEI_TRY(launch_spmm(Aw, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, T, fo32, f_out, dTheta, fo4, f_out, SENSEI_ACT_NONE, plan_t, carry, s, nullptr,
+        SENSEI_TRY(launch_spmm(Aw, SENSEI_SPMM_WEIGHTED, nullptr, nullptr, T, fo32, f_out, dTheta, ldt, f_out, SENSEI_ACT_NONE, plan_t, carry, s, nullptr,
                                false, true, nullptr, true, 2));
     }
-    SENSEI_TRY(launch_rank1_add(dTheta, fo4, A.n_cols, f_out, ds_l, A.n_rows, ds_r, a_l, a_r, s));
+    SENSEI_TRY(launch_rank1_add(dTheta, ldt, A.n_cols, f_out, ds_l, A.n_rows, ds_r, a_l, a_r, s));
     SENSEI_TRY(launch_theta_t_vec(theta, A.n_cols, f_out, ds_l, A.n_rows, ds_r, da_l, da_r, part_a, s));
-    SENSEI_TRY(launch_gemm_tn(X.ptr, X.ld, dTheta, fo4, A.n_cols, f_in, f_out, dW, lddw, part, s));
+    if (dtheta_out) return SENSEI_OK;
+    SENSEI_TRY(launch_gemm_tn(X.ptr, X.ld, dTheta, ldt, A.n_cols, f_in, f_out, dW, lddw, part, s));
     if (dX) {
         SENSEI_TRY(launch_transpose(W.ptr, W.ld, f_in, f_out, Wt, fi4, s));
-        SENSEI_TRY(launch_gemm(dTheta, fo4, Wt, fi4, dX, lddx, A.n_cols, f_out, f_in, f_in, SENSEI_ACT_NONE, s));
+        SENSEI_TRY(launch_gemm(dTheta, ldt, Wt, fi4, dX, lddx, A.n_cols, f_out, f_in, f_in, SENSEI_ACT_NONE, s));
+    }
+    return SENSEI_OK;
+}
+
+// Multi-head layer: the heads share only the input.  Every head runs the single-head backward on its columns and leaves its dTheta
+// beside the others'; dW = X^T [dTheta_0 .. dTheta_(H-1)] and dX = [dTheta_0 ..] W^T are then one product each for all heads.
+size_t gat_bwd_heads_ws(const sensei_csr &A, const sensei_csr *At, int f_in, int f_out, int n_heads) {
+    const size_t fo4 = pad4(f_out), fi4 = pad4(f_in);
+    return gat_bwd_ws(A, At, f_in, f_out / n_heads) + align_up((size_t)A.n_cols * fo4 * sizeof(float), 256) + align_up(fo4 * fi4 * sizeof(float), 256) +
+           gemm_tn_bytes(A.n_cols, f_in, f_out) + 256;
+}
+
+int run_gat_backward_heads(const sensei_csr &A, const sensei_csr &At, const int32_t *t_pos, const sensei_mat &X, const sensei_mat &W,
+                           const float *a_l, const float *a_r, int n_heads, float slope, const float *Y, int64_t ldy, const sensei_mat &dY, int act,
+                           float *dX, int64_t lddx, float *dW, int64_t lddw, float *da_l, float *da_r, void *ws, size_t ws_bytes, hipStream_t s) {
+    const int f_in = (int)X.cols, f_out = (int)W.cols, d = f_out / n_heads;
+    const int fo4 = pad4(f_out), fi4 = pad4(f_in);
+    Carver cv(ws, ws_bytes);
+    float *dTh = cv.take<float>((size_t)A.n_cols * fo4);
+    float *Wt = cv.take<float>((size_t)fo4 * fi4);
+    double *part = cv.take<double>(gemm_tn_bytes(A.n_cols, f_in, f_out) / sizeof(double));
+    void *ws_head = cv.base + cv.used;
+    const size_t ws_head_bytes = ws_bytes - cv.used;
+    for (int h = 0; h < n_heads; ++h) {
+        sensei_mat W_h = W, dY_h = dY;
+        W_h.ptr = W.ptr + (size_t)h * d; W_h.cols = d;
+        dY_h.ptr = dY.ptr + (size_t)h * d; dY_h.cols = d;
+        const int rc = run_gat_backward(A, At, t_pos, X, W_h, a_l + (size_t)h * d, a_r + (size_t)h * d, slope, Y ? Y + (size_t)h * d : nullptr, ldy,
+                                        dY_h, act, nullptr, 0, nullptr, 0, da_l + (size_t)h * d, da_r + (size_t)h * d, ws_head, ws_head_bytes, s,
+                                        dTh + (size_t)h * d, fo4);
+        if (rc != SENSEI_OK) return rc;
+    }
+    SENSEI_TRY(launch_gemm_tn(X.ptr, X.ld, dTh, fo4, A.n_cols, f_in, f_out, dW, lddw, part, s));
+    if (dX) {
+        SENSEI_TRY(launch_transpose(W.ptr, W.ld, f_in, f_out, Wt, fi4, s));
+        SENSEI_TRY(launch_gemm(dTh, fo4, Wt, fi4, dX, lddx, A.n_cols, f_out, f_in, f_in, SENSEI_ACT_NONE, s));
     }
     return SENSEI_OK;
 }
@@ -2425,6 +2467,41 @@ int sensei_gat_backward(sensei_ctx *ctx, const sensei_csr *A, const sensei_csr *
     if (ws_bytes < gat_bwd_ws(*A, At, (int)X.cols, (int)W.cols)) return SENSEI_WORKSPACE_TOO_SMALL;
     return run_gat_backward(*A, *At, t_pos, X, W, a_l, a_r, neg_slope, Y, ldy, dY, activation, dX, lddx, dW, lddw, da_l, da_r, workspace,
                             ws_bytes, as_stream(stream));
+}
+
+int sensei_gat_backward_heads_workspace(const sensei_csr *A, const sensei_csr *At, int f_in, int f_out, int n_heads, size_t *bytes) {
+    if (!csr_ok(A, false) || (At && !csr_ok(At, false)) || f_in <= 0 || f_out <= 0 || n_heads < 1 || f_out % n_heads != 0 || !bytes)
+        return SENSEI_INVALID_ARGUMENT;
+    *bytes = gat_bwd_heads_ws(*A, At, f_in, f_out, n_heads);
+    return SENSEI_OK;
+}
+
+int sensei_gat_backward_heads(sensei_ctx *ctx, const sensei_csr *A, const sensei_csr *At, const int32_t *t_pos, sensei_mat X, sensei_mat W,
+                              const float *a_l, const float *a_r, int n_heads, float neg_slope, const float *Y, int64_t ldy, sensei_mat dY,
+                              int activation, float *dX, int64_t lddx, float *dW, int64_t lddw, float *da_l, float *da_r, void *workspace,
+                              size_t ws_bytes, void *stream) {
+    if (!ctx || !csr_ok(A, false) || !csr_ok(At, false) || !mat_ok(X) || !mat_ok(W) || !mat_ok(dY)) return SENSEI_INVALID_ARGUMENT;
+    if (At->n_rows != A->n_cols || At->n_cols != A->n_rows || At->nnz != A->nnz || A->n_rows > A->n_cols) return SENSEI_INVALID_ARGUMENT;
+    if (activation != SENSEI_ACT_NONE && activation != SENSEI_ACT_RELU) return SENSEI_INVALID_ARGUMENT;
+    if (X.rows != A->n_cols || X.cols != W.rows || X.cols <= 0 || W.cols <= 0 || n_heads < 1 || W.cols % n_heads != 0) return SENSEI_INVALID_ARGUMENT;
+    if (X.cols > (1 << 20) || W.cols > (1 << 20)) return SENSEI_INVALID_ARGUMENT;
+    if (dY.rows != A->n_rows || dY.cols != W.cols) return SENSEI_INVALID_ARGUMENT;
+    if ((!X.ptr && A->n_cols > 0) || !W.ptr || (!dY.ptr && A->n_rows > 0) || !dW || !da_l || !da_r || !a_l || !a_r || !workspace)
+        return SENSEI_INVALID_ARGUMENT;
+    if (!t_pos && A->nnz > 0) return SENSEI_INVALID_ARGUMENT;
+    if (lddw < W.cols || (dX && lddx < X.cols)) return SENSEI_INVALID_ARGUMENT;
+    if (activation == SENSEI_ACT_RELU && ((!Y && A->n_rows > 0) || ldy < W.cols)) return SENSEI_INVALID_ARGUMENT;
+    const size_t dwb = mat_bytes(dW, W.rows, W.cols, lddw), dxb = dX ? mat_bytes(dX, A->n_cols, X.cols, lddx) : 0;
+    const size_t xb = mat_bytes(X.ptr, X.rows, X.cols, X.ld), wb = mat_bytes(W.ptr, W.rows, W.cols, W.ld),
+                 dyb = mat_bytes(dY.ptr, dY.rows, dY.cols, dY.ld);
+    if (overlap(dW, dwb, workspace, ws_bytes) || overlap(dW, dwb, X.ptr, xb) || overlap(dW, dwb, W.ptr, wb) || overlap(dW, dwb, dY.ptr, dyb))
+        return SENSEI_INVALID_ARGUMENT;
+    if (dX && (overlap(dX, dxb, workspace, ws_bytes) || overlap(dX, dxb, X.ptr, xb) || overlap(dX, dxb, W.ptr, wb) ||
+               overlap(dX, dxb, dY.ptr, dyb) || overlap(dX, dxb, dW, dwb)))
+        return SENSEI_INVALID_ARGUMENT;
+    if (ws_bytes < gat_bwd_heads_ws(*A, At, (int)X.cols, (int)W.cols, n_heads)) return SENSEI_WORKSPACE_TOO_SMALL;
+    return run_gat_backward_heads(*A, *At, t_pos, X, W, a_l, a_r, n_heads, neg_slope, Y, ldy, dY, activation, dX, lddx, dW, lddw, da_l, da_r, workspace,
+                                  ws_bytes, as_stream(stream));
 }
 
 int sensei_gatv2_backward_workspace(const sensei_csr *A, int f_in, int f_out, size_t *bytes) {

@@ -547,6 +547,53 @@ def test_backward_can_be_captured_in_a_hip_graph(ctx, split):
         T.close()
 
 
+# ------------------------------------------------------------------ multi-head GAT
+
+@pytest.mark.parametrize("name", sorted(GRAPHS))
+@pytest.mark.parametrize("shape", [(40, 24, 2), (24, 40, 5), (70, 41, 1), (33, 128, 2), (20, 96, 3), (24, 15, 3), (16, 130, 2)])
+@pytest.mark.parametrize("act", [ACT_NONE, ACT_RELU])
+def test_multi_head_gat_backward_matches_chain_rule(ctx, name, shape, act):
+    g = GRAPHS[name]()
+    gt = synth.transpose(g)
+    f_in, f_out, heads = shape
+    X, W, dY = _inputs(g, f_in, f_out, 150 + f_in)
+    a_l, a_r = synth.normal(151, 20, (f_out,), 0.0, 0.3), synth.normal(151, 21, (f_out,), 0.0, 0.3)
+    Y = None
+    if act == ACT_RELU:
+        Y = oracle.gat_layer_heads(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, a_l, a_r, heads, 0.2, 1).astype(np.float32)
+    want = oracle.gat_backward_heads(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, a_l, a_r, heads, dY, Y=Y, slope=0.2, act=act)
+    A, At = DeviceCSR(g), DeviceCSR(gt)
+    pos = ctx.transpose_positions(A.s, At.s)
+    got = ctx.gat_backward_heads(A.s, At.s, pos, dev(X), dev(W), dev(a_l), dev(a_r), heads, dev(dY), Y=None if Y is None else dev(Y), activation=act)
+    for gpu, ref, what in zip(got, want, ("dX", "dW", "da_l", "da_r")):
+        assert_close(gpu, ref, what=what)
+
+
+def test_multi_head_gat_backward_one_head_and_split_patterns(ctx):
+    """One head is the single-head call (bit-equal); with a tile split attached the heads of 128 columns take the split paths."""
+    from paper_2306_15155_amd import Tiles, csr_struct
+    g = synth.rmat(152, 5000, 150_000)
+    f_in, f_out = 48, 256
+    X, W, dY = _inputs(g, f_in, f_out, 153)
+    a_l, a_r = synth.normal(153, 20, (f_out,), 0.0, 0.3), synth.normal(153, 21, (f_out,), 0.0, 0.3)
+    A = DeviceCSR(g)
+    pos = ctx.transpose_positions(A.s, A.s)
+    one = [t.clone() for t in ctx.gat_backward_heads(A.s, A.s, pos, dev(X), dev(W), dev(a_l), dev(a_r), 1, dev(dY))]
+    ref = ctx.gat_backward(A.s, A.s, pos, dev(X), dev(W), dev(a_l), dev(a_r), dev(dY))
+    assert all(torch.equal(a, b) for a, b in zip(one, ref))
+    want = oracle.gat_backward_heads(g.n_rows, g.n_cols, g.row_ptr, g.col_idx, X, W, a_l, a_r, 2, dY)
+    T = Tiles(ctx, A.s, 0.05, 128, min_width=32)
+    assert T.n_tiles > 0
+    At = csr_struct(g.n_rows, g.n_cols, A.row_ptr, A.col_idx, None, None, T)
+    none, dW, dal, dar = ctx.gat_backward_heads(At, At, pos, dev(X), dev(W), dev(a_l), dev(a_r), 2, dev(dY), want_dx=False)
+    assert none is None
+    for gpu, ref, what in zip((dW, dal, dar), want[1:], ("dW", "da_l", "da_r")):
+        assert_close(gpu, ref, what=what)
+    with pytest.raises(RuntimeError):
+        ctx.gat_backward_heads(A.s, A.s, pos, dev(X), dev(W), dev(a_l), dev(a_r), 3, dev(dY))     # 3 does not divide 256
+    T.close()
+
+
 # ------------------------------------------------------------------ GATv2
 
 def _gatv2_inputs(g, f_in, f_out, seed):
