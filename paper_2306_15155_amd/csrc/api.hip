@@ -2540,6 +2540,15 @@ int sensei_gatv2_backward(sensei_ctx *ctx, const sensei_csr *A, const sensei_csr
             if (overlap(o.p, o.n, outs[b].p, outs[b].n)) return SENSEI_INVALID_ARGUMENT;
     }
     if (ws_bytes < gatv2_bwd_ws(*A, (int)X.cols, (int)W_r.cols)) return SENSEI_WORKSPACE_TOO_SMALL;
+    if (A->n_rows == 0) {   // no output rows: nothing depends on the inputs
+        hipStream_t st = as_stream(stream);
+        if (launch_zero_matrix(dW_l, W_l.rows, (int)W_l.cols, lddwl, false, st) != hipSuccess ||
+            launch_zero_matrix(dW_r, W_r.rows, (int)W_r.cols, lddwr, false, st) != hipSuccess ||
+            launch_zero_matrix(datt, 1, (int)W_r.cols, W_r.cols, false, st) != hipSuccess ||
+            (dX && launch_zero_matrix(dX, A->n_cols, (int)X.cols, lddx, false, st) != hipSuccess))
+            return SENSEI_HIP_ERROR;
+        return SENSEI_OK;
+    }
     return run_gatv2_backward(*A, *At, t_pos, X, W_l, W_r, att, neg_slope, Y, ldy, dY, activation, dX, lddx, dW_l, lddwl, dW_r, lddwr, datt, workspace,
                               ws_bytes, as_stream(stream));
 }
@@ -2678,6 +2687,15 @@ int sensei_dotgat_backward(sensei_ctx *ctx, const sensei_csr *A, const sensei_cs
             if (overlap(outs[a].p, outs[a].n, outs[b].p, outs[b].n)) return SENSEI_INVALID_ARGUMENT;
     }
     if (ws_bytes < dotgat_bwd_ws(*A, (int)X.cols, (int)W_q.cols, (int)W_v.cols)) return SENSEI_WORKSPACE_TOO_SMALL;
+    if (A->n_rows == 0) {   // no output rows: nothing depends on the inputs
+        hipStream_t st = as_stream(stream);
+        if (launch_zero_matrix(dW_q, W_q.rows, (int)W_q.cols, lddwq, false, st) != hipSuccess ||
+            launch_zero_matrix(dW_k, W_k.rows, (int)W_k.cols, lddwk, false, st) != hipSuccess ||
+            launch_zero_matrix(dW_v, W_v.rows, (int)W_v.cols, lddwv, false, st) != hipSuccess ||
+            (dX && launch_zero_matrix(dX, A->n_cols, (int)X.cols, lddx, false, st) != hipSuccess))
+            return SENSEI_HIP_ERROR;
+        return SENSEI_OK;
+    }
     return run_dotgat_backward(*A, *At, t_pos, X, W_q, W_k, W_v, scale, Y, ldy, dY, activation, dX, lddx, dW_q, lddwq, dW_k, lddwk, dW_v, lddwv,
                                workspace, ws_bytes, as_stream(stream));
 }

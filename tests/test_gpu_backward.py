@@ -772,3 +772,18 @@ def test_key_query_attention_backward_argument_checks(ctx):
     with pytest.raises(RuntimeError):
         ctx.dotgat_backward(A.s, A.s, pos, X, Wq, Wq, Wv, 0.5, torch.zeros((200, 5), device="cuda:0"))    # dY of another width
     torch.cuda.synchronize()
+
+
+def test_attention_variant_backward_without_output_rows(ctx):
+    """A block with sources but no destinations: no output depends on anything, every gradient is zero."""
+    none = np.empty(0, np.int32)
+    g = synth.build_csr(0, 6, none, none, False, False)
+    A, At = DeviceCSR(g), DeviceCSR(synth.transpose(g))
+    X = torch.ones((6, 5), device="cuda:0")
+    W, Wq = torch.ones((5, 4), device="cuda:0"), torch.ones((5, 3), device="cuda:0")
+    att = torch.ones(4, device="cuda:0")
+    dY = torch.empty((0, 4), device="cuda:0")
+    for got in (ctx.gatv2_backward(A.s, At.s, None, X, W, W, att, dY), ctx.dotgat_backward(A.s, At.s, None, X, Wq, Wq, W, 0.5, dY)):
+        assert got[0].shape == (6, 5)
+        assert all(float(t.abs().max()) == 0.0 for t in got)
+    torch.cuda.synchronize()
