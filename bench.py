@@ -684,7 +684,11 @@ def headline(args):
             tmp_out = torch.empty_like(outs[i])
             kq[tag(i)] = {nm: round(time_fn(lambda: ctx.dotgat_layer(A, src_of(i), Wq2, Wk2, Wd[i], 0.125, cid, L["act"], out=tmp_out), 2), 4)
                           for cid, nm in ((0, "REUSE"), (1, "RECOMP"))}
-            del Wq2, Wk2, tmp_out
+            t_pos = ctx.transpose_positions(A, A)
+            dYt = torch.randn((N, L["f_out"]), device=dev)
+            kq[tag(i)]["BACKWARD"] = round(time_fn(lambda: ctx.dotgat_backward(A, A, t_pos, src_of(i), Wq2, Wk2, Wd[i], 0.125, dYt,
+                                                                               Y=outs[i] if L["act"] else None, activation=L["act"]), 2), 4)
+            del Wq2, Wk2, tmp_out, t_pos, dYt
         detail["key_query_attention_ms"] = kq
 
     # ---- one training iteration of the GCN stack of the workload (the layers whose input is X or the previous layer):
