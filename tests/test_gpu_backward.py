@@ -547,6 +547,53 @@ def test_backward_can_be_captured_in_a_hip_graph(ctx, split):
         T.close()
 
 
+def test_variant_backwards_can_be_captured_in_a_hip_graph(ctx):
+    """The same for the backward calls of the variant layers: a captured step replays to the bits of the eager run."""
+    g = synth.rmat(97, 4000, 90_000)
+    A = DeviceCSR(g)
+    dr, dc = ctx.degrees(A.s)
+    r, c = ctx.norm_vectors(dr), ctx.norm_vectors(dc)
+    f_in, f_out, K = 24, 32, 2
+    X, W, dY = (dev(t) for t in _inputs(g, f_in, f_out, 98))
+    W3 = dev(np.concatenate([synth.glorot(98, 30 + k, f_in, f_out) for k in range(K + 1)], axis=0))
+    Wq = dev(synth.glorot(98, 40, f_in, 16))
+    a_l, a_r = dev(synth.normal(98, 20, (f_out,), 0.0, 0.3)), dev(synth.normal(98, 21, (f_out,), 0.0, 0.3))
+    pos = ctx.transpose_positions(A.s, A.s)
+
+    def step():
+        out = []
+        for bwd in (GCN_BWD_AGG, GCN_BWD_UPD):
+            out += list(ctx.sgc_backward(A.s, A.s, r, c, X, W, K, dY, bwd))
+            out += list(ctx.tagcn_backward(A.s, A.s, r, c, X, W3, K, dY, bwd))
+        out += list(ctx.gat_backward_heads(A.s, A.s, pos, X, W, a_l, a_r, 4, dY))
+        out += list(ctx.gatv2_backward(A.s, A.s, pos, X, W, W, a_l, dY))
+        out += list(ctx.dotgat_backward(A.s, A.s, pos, X, Wq, Wq, W, 0.25, dY))
+        return out
+
+    want = [t.clone() for t in step()]  # also sizes the workspace before capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    with torch.cuda.graph(graph):
+        got = step()
+    for rep in range(3):
+        for t in got:
+            t.fill_(-7.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(got, want):
+            assert torch.equal(a, b), f"replay {rep}"
+        eager = step()  # eager work between replays
+        torch.cuda.synchronize()
+        for a, b in zip(eager, want):
+            assert torch.equal(a, b)
+
+
 # ------------------------------------------------------------------ multi-head GAT
 
 @pytest.mark.parametrize("name", sorted(GRAPHS))
