@@ -655,6 +655,9 @@ def headline(args):
             for bid, nm in ((0, "BWD_AGG"), (1, "BWD_UPD")):
                 tag2[tag(i)][nm] = round(time_fn(lambda: ctx.tagcn_backward(A, A, r, c, src_of(i), W3, 2, dYt, bid, Y=outs[i] if L["act"] else None,
                                                                            activation=L["act"]), 2), 4)
+            pick, _ = ctx.select_khop_backward(A, L["f_in"], L["f_out"], 2, True)
+            tag2[tag(i)]["backward_picked"] = ("BWD_AGG", "BWD_UPD")[pick]
+            tag2[tag(i)]["backward_regret"] = round(tag2[tag(i)][tag2[tag(i)]["backward_picked"]] / min(tag2[tag(i)]["BWD_AGG"], tag2[tag(i)]["BWD_UPD"]) - 1.0, 4)
             del W3, tmp_out, dYt
         detail["tagcn_2hop_ms"] = tag2
 

@@ -438,6 +438,11 @@ int sensei_tagcn_backward(sensei_ctx *ctx, const sensei_csr *A, const sensei_csr
  * U = D_r^(-1/2) A~ D_c^(-1/2) X; want_dx: the input gradient is needed.  est_ms: optional, 2 entries. */
 int sensei_select_gcn_backward(sensei_ctx *ctx, const sensei_csr *A, int f_in, int f_out, int have_saved_u, int want_dx,
                                int *bwd_id_out, float *est_ms);
+/* The same for the backward of the K-hop layers (the selection of Section 3.5 applied to their two associations): per_hop_weights = 0
+ * prices sensei_sgc_backward, 1 sensei_tagcn_backward.  Every hop adds one aggregation at the width the association carries through
+ * the hops (f_out for SENSEI_GCN_BWD_AGG; f_in, forward and - with want_dx - back again, for SENSEI_GCN_BWD_UPD). */
+int sensei_select_khop_backward(sensei_ctx *ctx, const sensei_csr *A, int f_in, int f_out, int k_hops, int per_hop_weights, int want_dx,
+                                int *bwd_id_out, float *est_ms);
 
 int sensei_gat_workspace(const sensei_csr *A, int f_in, int f_out, int comp_id, size_t *bytes);
 

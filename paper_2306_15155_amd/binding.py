@@ -30,7 +30,7 @@ EXPORTS = (
     "sensei_gcn_workspace", "sensei_gcn_layer", "sensei_gat_workspace", "sensei_gat_attention_path", "sensei_gat_layer", "sensei_select_workspace",
     "sensei_select", "sensei_profile_enable", "sensei_profile_read", "sensei_panels_bytes", "sensei_panels_create",
     "sensei_panels_count", "sensei_panels_destroy", "sensei_panels_set_min_width", "sensei_panels_tune_bytes",
-    "sensei_panels_tune", "sensei_gcn_backward_workspace", "sensei_gcn_backward", "sensei_select_gcn_backward", "sensei_transpose_positions",
+    "sensei_panels_tune", "sensei_gcn_backward_workspace", "sensei_gcn_backward", "sensei_select_gcn_backward", "sensei_select_khop_backward", "sensei_transpose_positions",
     "sensei_gat_backward_workspace", "sensei_gat_backward", "sensei_gat_backward_heads_workspace", "sensei_gat_backward_heads", "sensei_gat_layer_heads", "sensei_sgc_workspace", "sensei_sgc_layer", "sensei_sgc_backward_workspace", "sensei_sgc_backward", "sensei_tagcn_workspace", "sensei_tagcn_layer", "sensei_tagcn_backward_workspace", "sensei_tagcn_backward", "sensei_gatv2_workspace", "sensei_gatv2_layer", "sensei_gatv2_backward_workspace", "sensei_gatv2_backward", "sensei_dotgat_workspace", "sensei_dotgat_layer", "sensei_dotgat_backward_workspace", "sensei_dotgat_backward", "sensei_tiles_remainder_panels", "sensei_tiles_bytes", "sensei_tiles_create", "sensei_tiles_info",
            "sensei_tiles_set_min_width", "sensei_tiles_destroy",
 )
@@ -91,6 +91,7 @@ def lib():
         L.sensei_gcn_backward.argtypes = [vp, P(CsrStruct), P(CsrStruct), vp, vp, MatStruct, MatStruct, vp, i64, MatStruct, i32, vp, i64,
                                           vp, i64, vp, i64, i32, vp, sz, vp]
         L.sensei_select_gcn_backward.argtypes = [vp, P(CsrStruct), i32, i32, i32, i32, P(ctypes.c_int), P(f32)]
+        L.sensei_select_khop_backward.argtypes = [vp, P(CsrStruct), i32, i32, i32, i32, i32, P(ctypes.c_int), P(f32)]
         L.sensei_transpose_positions.argtypes = [vp, P(CsrStruct), P(CsrStruct), vp, vp, sz, vp]
         L.sensei_gat_backward_workspace.argtypes = [P(CsrStruct), P(CsrStruct), i32, i32, P(sz)]
         L.sensei_gat_backward.argtypes = [vp, P(CsrStruct), P(CsrStruct), vp, MatStruct, MatStruct, vp, vp, f32, vp, i64, MatStruct, i32,
@@ -513,6 +514,14 @@ class Context:
                                             mat_struct(dWk).ld, _ptr(dWv), mat_struct(dWv).ld, self.ws.ptr, self.ws.nbytes, _stream()),
                "sensei_dotgat_backward")
         return dX, dWq, dWk, dWv
+
+    def select_khop_backward(self, A: CsrStruct, f_in, f_out, k_hops, per_hop_weights, want_dx=True):
+        """Predicted faster association of sgc_backward (per_hop_weights False) or tagcn_backward (True) -> (bwd_id, [ms AGG, ms UPD])."""
+        pick = ctypes.c_int()
+        est = (ctypes.c_float * 2)()
+        _check(lib().sensei_select_khop_backward(self._h, ctypes.byref(A), f_in, f_out, k_hops, int(per_hop_weights), int(want_dx), ctypes.byref(pick),
+                                                 est), "sensei_select_khop_backward")
+        return pick.value, [float(x) for x in est]
 
     def select_gcn_backward(self, A: CsrStruct, f_in, f_out, have_saved_u=False, want_dx=True):
         pick = ctypes.c_int()

@@ -1484,6 +1484,25 @@ double gcn_bwd_cost(const sensei_ctx &c, const Features &g, int f_in, int f_out,
     return t;
 }
 
+// The K-hop layers: every hop is one more aggregation at the width its association carries through the hops; TAGCN forms one weight
+// gradient per hop and, in its update-side association, one product with W_k^T per hop.
+double khop_bwd_cost(const sensei_ctx &c, const Features &g, int f_in, int f_out, int k_hops, bool tagcn, int id, bool want_dx) {
+    Features gt = g;  // the transposed pattern
+    gt.n_rows = g.n_cols; gt.n_cols = g.n_rows;
+    const int blocks = tagcn ? k_hops + 1 : 1;
+    double t = t_stream(c, 12.0 * g.n_rows * f_out);
+    if (id == SENSEI_GCN_BWD_AGG) {
+        t += k_hops * (t_spmm(c, gt, f_out, kSpmmPattern) + (tagcn ? t_stream(c, 8.0 * g.n_rows * f_out) : 0.0));
+        t += blocks * t_gemm(c, f_in, g.n_cols, f_out, g.learned);
+        if (want_dx) t += t_gemm(c, g.n_cols, (double)blocks * f_out, f_in, g.learned);
+    } else {
+        t += k_hops * (t_stream(c, 8.0 * g.n_cols * f_in) + t_spmm(c, g, f_in, kSpmmPattern));
+        t += blocks * t_gemm(c, f_in, g.n_rows, f_out, g.learned);
+        if (want_dx) t += blocks * t_gemm(c, g.n_rows, f_out, f_in, g.learned) + k_hops * t_spmm(c, gt, f_in, kSpmmPattern);
+    }
+    return t;
+}
+
 constexpr double kAutoMargin = 0.15;  // AUTO mode: predicted costs this close to the cheapest are settled by measurement
 
 void rule_filter(int kind, int f_in, int f_out, bool *keep) {
@@ -2716,6 +2735,21 @@ int sensei_select_gcn_backward(sensei_ctx *ctx, const sensei_csr *A, int f_in, i
     double cost[2];
     for (int id = 0; id < 2; ++id) {
         cost[id] = 1e3 * gcn_bwd_cost(*ctx, g, f_in, f_out, id, have_saved_u != 0, want_dx != 0);
+        if (est_ms) est_ms[id] = (float)cost[id];
+    }
+    *bwd_id_out = cost[SENSEI_GCN_BWD_UPD] < cost[SENSEI_GCN_BWD_AGG] ? SENSEI_GCN_BWD_UPD : SENSEI_GCN_BWD_AGG;
+    return SENSEI_OK;
+}
+
+int sensei_select_khop_backward(sensei_ctx *ctx, const sensei_csr *A, int f_in, int f_out, int k_hops, int per_hop_weights, int want_dx,
+                                int *bwd_id_out, float *est_ms) {
+    if (!ctx || !csr_ok(A, false) || f_in <= 0 || f_out <= 0 || k_hops < 0 || k_hops > 64 || !bwd_id_out) return SENSEI_INVALID_ARGUMENT;
+    Features g;
+    g.n_rows = A->n_rows; g.n_cols = A->n_cols; g.nnz = (double)A->nnz;
+    g.density = (A->n_rows > 0 && A->n_cols > 0) ? g.nnz / (g.n_rows * g.n_cols) : 0.0;
+    double cost[2];
+    for (int id = 0; id < 2; ++id) {
+        cost[id] = 1e3 * khop_bwd_cost(*ctx, g, f_in, f_out, k_hops, per_hop_weights != 0, id, want_dx != 0);
         if (est_ms) est_ms[id] = (float)cost[id];
     }
     *bwd_id_out = cost[SENSEI_GCN_BWD_UPD] < cost[SENSEI_GCN_BWD_AGG] ? SENSEI_GCN_BWD_UPD : SENSEI_GCN_BWD_AGG;

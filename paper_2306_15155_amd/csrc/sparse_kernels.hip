@@ -1590,7 +1590,7 @@ __global__ void k_scale_cols(float *D, long long ldd, const float *G, long long 
     D[i * ldd + m] = accumulate ? D[i * ldd + m] + g : g;
 }
 
-__global__ void k_fill_f32(float *p, long long n, float v) {
+__global__ void k_set_f32(float *p, long long n, float v) {
     const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (t < n) p[t] = v;
 }
@@ -1981,7 +1981,7 @@ hipError_t launch_scale_cols(float *D, int64_t ldd, const float *G, int64_t ldg,
 
 hipError_t launch_fill_f32(float *p, int64_t n, float v, hipStream_t s) {
     if (n <= 0) return hipSuccess;
-    hipLaunchKernelGGL(k_fill_f32, dim3(blocks_for(n, kBlock)), dim3(kBlock), 0, s, p, (long long)n, v);
+    hipLaunchKernelGGL(k_set_f32, dim3(blocks_for(n, kBlock)), dim3(kBlock), 0, s, p, (long long)n, v);
     return hipGetLastError();
 }
 

@@ -300,6 +300,36 @@ def test_k_hop_backward_degenerate_patterns(ctx):
     torch.cuda.synchronize()
 
 
+def test_khop_backward_selection_follows_the_widths(ctx):
+    """The cost model's pick between the two associations of the K-hop backward: the hops run at the narrower width, for both layers,
+    and the pick is the association that is measured faster where the widths differ by a factor of eight."""
+    import time
+    g = synth.rmat(99, 60_000, 3_000_000)
+    A = DeviceCSR(g)
+    dr, dc = ctx.degrees(A.s)
+    r, c = ctx.norm_vectors(dr), ctx.norm_vectors(dc)
+    for f_in, f_out, want in ((128, 16, GCN_BWD_AGG), (16, 128, GCN_BWD_UPD)):
+        for tagcn in (False, True):
+            pick, est = ctx.select_khop_backward(A.s, f_in, f_out, 2, tagcn)
+            assert pick == want and len(est) == 2 and min(est) > 0, (f_in, f_out, tagcn, pick, est)
+            X = torch.rand((g.n_cols, f_in), device="cuda:0")
+            W = torch.rand(((3 if tagcn else 1) * f_in, f_out), device="cuda:0")
+            dY = torch.randn((g.n_rows, f_out), device="cuda:0")
+            fn = ctx.tagcn_backward if tagcn else ctx.sgc_backward
+            ms = []
+            for bwd in (GCN_BWD_AGG, GCN_BWD_UPD):
+                fn(A.s, A.s, r, c, X, W, 2, dY, bwd)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(3):
+                    fn(A.s, A.s, r, c, X, W, 2, dY, bwd)
+                torch.cuda.synchronize()
+                ms.append((time.perf_counter() - t0) / 3)
+            assert ms[pick] <= 1.1 * min(ms), (f_in, f_out, tagcn, pick, ms)
+    with pytest.raises(RuntimeError):
+        ctx.select_khop_backward(A.s, 16, 16, -1, True)
+
+
 def test_tagcn_backward_argument_checks(ctx):
     g = synth.erdos_renyi(47, 200, 600)
     A = DeviceCSR(g)
